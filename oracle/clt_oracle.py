@@ -1,0 +1,289 @@
+"""CPU oracle for one cross-layer-transcoder (CLT) training step.
+
+TEST INFRASTRUCTURE ONLY.  This module is the plain, slow, obviously-correct
+definition that the HIP library is checked against.  It may be imported only by
+tests, by the smoke check and by the benchmark's CPU-baseline leg; the product
+path never calls it and it shares no code with the HIP path.
+
+Everything is numpy float64.  Each function is the paper's definition written
+out, with matmul as the only library step and no blocking, fusion or
+reordering:
+
+  encoder pre-activation ........ Sec. 2.1, eq. (1)
+  JumpReLU ...................... Sec. 2.1 / Sec. 3.2 (named there; the form
+                                  z = pre * H(pre - theta), strict ">", is the
+                                  one of the JumpReLU literature the paper
+                                  follows for its training recipe)
+  cross-layer decode ............ Sec. 2.1, eq. (3); eq. (2) is its L = 1 case
+  decoder norms ................. App. B: norm of the concatenation of all
+                                  decoders that leave a source layer
+  objective ..................... App. B training objective, reconstruction and
+                                  sparsity terms (lambda_1 = 0)
+  backward ...................... chain rule through the above; the threshold
+                                  gets the rectangle-kernel straight-through
+                                  pseudo-gradient
+  Adam .......................... App. C, Table 1 (betas, learning rate); bias
+                                  correction on, eps outside the square root
+
+Storage conventions (they only transpose the paper's matrices):
+  x      [L, B, d]   MLP inputs h_l per layer and token
+  y      [L, B, d]   MLP outputs m_l (reconstruction targets)
+  W_enc  [L, d, F]   pre = x @ W_enc[l] + b_enc[l]
+  b_enc  [L, F], theta [L, F]
+  W_dec  [P, F, d]   P = L(L+1)/2 blocks, block p(l, l') maps source l to
+                     target l' >= l; source-major packing, see packed_index
+  b_dec  [L, d]
+
+Readings taken where the paper is silent are listed in the repository's design
+document; the ones that matter here: the loss sums over layers, model dims and
+features and takes the mean over the B tokens; the decoder norm is
+differentiated; dn/dW uses max(n, 1e-30) so an all-zero decoder row gives 0.
+
+Parity pins (tests/test_oracle_*.py): brute-force Python loops, closed forms,
+special cases that reduce to torch.nn.functional.linear / torch.optim.Adam,
+central finite differences, a torch-autograd re-derivation, a hand-worked
+example, and the paper's printed parameter count.  The threshold
+pseudo-gradient is a definition, not a derivative, so finite differences cannot
+pin it; it is pinned by the hand-worked example, by the autograd re-derivation
+and by the "empty window gives zero" invariant.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+F64 = np.float64
+
+
+# --------------------------------------------------------------------------
+# packed triangular decoder (eq. 3: sum over source layers l <= l')
+# --------------------------------------------------------------------------
+def num_blocks(L: int) -> int:
+    """Number of (source, target) decoder blocks with l <= l' (eq. 3)."""
+    return L * (L + 1) // 2
+
+
+def packed_index(l: int, lp: int, L: int) -> int:
+    """Block index of the decoder W_dec^{l -> l'} in source-major packing.
+
+    Source 0 owns blocks 0..L-1 (targets 0..L-1), source 1 the next L-1
+    (targets 1..L-1), and so on, so that all decoders leaving one source layer
+    are contiguous (the "concatenation" whose norm App. B uses).
+    """
+    if not (0 <= l <= lp < L):
+        raise ValueError("need 0 <= l <= l' < L")
+    return l * L - l * (l - 1) // 2 + (lp - l)
+
+
+def decoder_param_count(L: int, d: int, e: int) -> int:
+    """App. B parameter formula: (L(L-1)/2 + L) * e * d^2."""
+    return (L * (L - 1) // 2 + L) * e * d * d
+
+
+# --------------------------------------------------------------------------
+# forward
+# --------------------------------------------------------------------------
+def encoder_preact(x, W_enc, b_enc):
+    """eq. (1) before the nonlinearity: pre[l] = x[l] @ W_enc[l] + b_enc[l]."""
+    x = np.asarray(x, F64)
+    W_enc = np.asarray(W_enc, F64)
+    b_enc = np.asarray(b_enc, F64)
+    L = x.shape[0]
+    pre = np.empty((L, x.shape[1], W_enc.shape[2]), F64)
+    for l in range(L):
+        pre[l] = x[l] @ W_enc[l] + b_enc[l][None, :]
+    return pre
+
+
+def jumprelu(pre, theta, tie_break=None, band=0.0):
+    """JumpReLU: z = pre where pre > theta (strictly), else 0.
+
+    `tie_break`, if given, is a boolean array of forced decisions that is
+    honoured only where |pre - theta| < band: there both decisions are valid
+    results for an implementation whose pre-activation differs from this one by
+    rounding, and a caller may ask which of the valid results to continue with.
+    Outside the band the forced value must agree with the oracle's own.
+    """
+    pre = np.asarray(pre, F64)
+    theta = np.asarray(theta, F64)
+    active = pre > theta[:, None, :]
+    if tie_break is not None:
+        tb = np.asarray(tie_break, bool)
+        inband = np.abs(pre - theta[:, None, :]) < band
+        if np.any((tb != active) & ~inband):
+            raise ValueError("tie_break disagrees with the oracle outside the band")
+        active = np.where(inband, tb, active)
+    z = np.where(active, pre, 0.0)
+    return z, active
+
+
+def ste_window(pre, theta, eps, tie_break=None, band=0.0):
+    """Support of the rectangle kernel: |pre - theta| < eps / 2 (strict)."""
+    pre = np.asarray(pre, F64)
+    theta = np.asarray(theta, F64)
+    dist = np.abs(pre - theta[:, None, :])
+    win = dist < 0.5 * eps
+    if tie_break is not None:
+        tb = np.asarray(tie_break, bool)
+        inband = np.abs(dist - 0.5 * eps) < band
+        if np.any((tb != win) & ~inband):
+            raise ValueError("window tie_break disagrees outside the band")
+        win = np.where(inband, tb, win)
+    return win
+
+
+def decode(z, W_dec, b_dec):
+    """eq. (3): y_hat[l'] = b_dec[l'] + sum_{l <= l'} z[l] @ W_dec[p(l, l')].
+
+    Written as the explicit loop over (target, source) pairs.
+    """
+    z = np.asarray(z, F64)
+    b_dec = np.asarray(b_dec, F64)
+    L, B, _ = z.shape
+    d = b_dec.shape[1]
+    y_hat = np.empty((L, B, d), F64)
+    for lp in range(L):
+        acc = np.tile(b_dec[lp][None, :], (B, 1))
+        for l in range(lp + 1):
+            acc += z[l] @ np.asarray(W_dec[packed_index(l, lp, L)], F64)
+        y_hat[lp] = acc
+    return y_hat
+
+
+def decoder_norms(W_dec, L):
+    """App. B: n[l, f] = l2 norm of feature f's rows over all blocks l -> l'."""
+    F = W_dec.shape[1]
+    n2 = np.zeros((L, F), F64)
+    for l in range(L):
+        for lp in range(l, L):
+            Wb = np.asarray(W_dec[packed_index(l, lp, L)], F64)
+            n2[l] += np.sum(Wb * Wb, axis=1)
+    return np.sqrt(n2)
+
+
+def loss_terms(y_hat, y, z, n, lambda0, C):
+    """App. B objective, lambda_1 = 0, mean over the B tokens.
+
+    L_rec = (1/B) sum_{l', b, j} (y_hat - y)^2
+    L_sp  = (lambda0/B) sum_{l, b, f} tanh(C * z * n[l, f])
+    """
+    y = np.asarray(y, F64)
+    B = y.shape[1]
+    r = y_hat - y
+    L_rec = np.sum(r * r) / B
+    L_sp = lambda0 * np.sum(np.tanh(C * z * n[:, None, :])) / B
+    return L_rec + L_sp, L_rec, L_sp
+
+
+def forward(x, W_enc, b_enc, theta, W_dec, b_dec, tie_break=None, band=0.0):
+    """Encoder, JumpReLU, cross-layer decode.  Returns a dict of intermediates."""
+    pre = encoder_preact(x, W_enc, b_enc)
+    z, active = jumprelu(pre, theta, tie_break, band)
+    y_hat = decode(z, W_dec, b_dec)
+    return {"pre": pre, "z": z, "active": active, "y_hat": y_hat,
+            "l0_per_layer": active.sum(axis=(1, 2))}
+
+
+# --------------------------------------------------------------------------
+# backward
+# --------------------------------------------------------------------------
+def backward(x, y, theta, W_dec, fwd, lambda0, C, eps,
+             window_tie_break=None, band=0.0):
+    """Gradients of L_rec + L_sp w.r.t. the five parameter tensors.
+
+    d y_hat = 2 (y_hat - y) / B
+    dz[l]   = sum_{l' >= l} d y_hat[l'] @ W_dec[p(l,l')]^T
+              + (lambda0/B) C n sech^2(C z n)
+    dpre    = dz where active, else 0              (no pseudo-term on pre)
+    dtheta  = -(theta/eps) sum_b [ |pre-theta| < eps/2 ] dz
+    dW_dec[p(l,l')] = z[l]^T @ d y_hat[l'] + (G[l,f]/n[l,f]) W_dec[p(l,l')][f,:]
+              with G[l,f] = (lambda0/B) sum_b C z sech^2(C z n)
+    db_dec  = sum_b d y_hat,  dW_enc[l] = x[l]^T @ dpre[l],  db_enc = sum_b dpre
+    """
+    x = np.asarray(x, F64)
+    y = np.asarray(y, F64)
+    theta = np.asarray(theta, F64)
+    L, B, d = x.shape
+    z, pre, active, y_hat = fwd["z"], fwd["pre"], fwd["active"], fwd["y_hat"]
+    F = z.shape[2]
+    n = decoder_norms(W_dec, L)
+
+    d_yhat = 2.0 * (y_hat - y) / B
+    u = C * z * n[:, None, :]
+    sech2 = 1.0 / np.cosh(u) ** 2
+    g_sp = (lambda0 / B) * C * n[:, None, :] * sech2
+    G = (lambda0 / B) * np.sum(C * z * sech2, axis=1)          # [L, F]
+
+    dz = g_sp.copy()
+    for l in range(L):
+        for lp in range(l, L):
+            dz[l] += d_yhat[lp] @ np.asarray(W_dec[packed_index(l, lp, L)], F64).T
+    dpre = np.where(active, dz, 0.0)
+    win = ste_window(pre, theta, eps, window_tie_break, band)
+    dtheta = -(theta / eps) * np.sum(np.where(win, dz, 0.0), axis=1)
+    db_enc = dpre.sum(axis=1)
+
+    dW_dec = np.empty((num_blocks(L), F, d), F64)
+    n_safe = np.maximum(n, 1e-30)
+    for l in range(L):
+        for lp in range(l, L):
+            p = packed_index(l, lp, L)
+            Wb = np.asarray(W_dec[p], F64)
+            dW_dec[p] = z[l].T @ d_yhat[lp] + (G[l] / n_safe[l])[:, None] * Wb
+    db_dec = d_yhat.sum(axis=1)
+
+    dW_enc = np.empty((L, d, F), F64)
+    for l in range(L):
+        dW_enc[l] = x[l].T @ dpre[l]
+
+    return {"dW_enc": dW_enc, "db_enc": db_enc, "dtheta": dtheta,
+            "dW_dec": dW_dec, "db_dec": db_dec,
+            "d_yhat": d_yhat, "dz": dz, "dpre": dpre, "window": win,
+            "n": n, "G": G}
+
+
+# --------------------------------------------------------------------------
+# Adam (App. C Table 1: betas (0.9, 0.999), learning rate 2e-4)
+# --------------------------------------------------------------------------
+def adam_update(p, g, m, v, t, lr, beta1=0.9, beta2=0.999, eps=1e-8):
+    """One Adam step, 1-based step count t.  Returns (p, m, v) as new arrays."""
+    p = np.asarray(p, F64)
+    g = np.asarray(g, F64)
+    m = beta1 * np.asarray(m, F64) + (1.0 - beta1) * g
+    v = beta2 * np.asarray(v, F64) + (1.0 - beta2) * g * g
+    m_hat = m / (1.0 - beta1 ** t)
+    v_hat = v / (1.0 - beta2 ** t)
+    p = p - lr * m_hat / (np.sqrt(v_hat) + eps)
+    return p, m, v
+
+
+PARAM_NAMES = ("W_enc", "b_enc", "theta", "W_dec", "b_dec")
+
+
+def train_step(x, y, params, m, v, t, lr, lambda0, C, eps,
+               beta1=0.9, beta2=0.999, adam_eps=1e-8):
+    """Forward, loss, backward and Adam on all five tensors.
+
+    `params`, `m`, `v` are dicts keyed by PARAM_NAMES.  Returns
+    (new_params, new_m, new_v, info) with info holding forward values, loss
+    terms and gradients.
+    """
+    fwd = forward(x, params["W_enc"], params["b_enc"], params["theta"],
+                  params["W_dec"], params["b_dec"])
+    L = np.asarray(x).shape[0]
+    n = decoder_norms(params["W_dec"], L)
+    total, rec, sp = loss_terms(fwd["y_hat"], y, fwd["z"], n, lambda0, C)
+    grads = backward(x, y, params["theta"], params["W_dec"], fwd, lambda0, C, eps)
+    new_p, new_m, new_v = {}, {}, {}
+    for k in PARAM_NAMES:
+        new_p[k], new_m[k], new_v[k] = adam_update(
+            params[k], grads["d" + k], m[k], v[k], t, lr, beta1, beta2, adam_eps)
+    info = {"fwd": fwd, "loss": (total, rec, sp), "grads": grads}
+    return new_p, new_m, new_v, info
+
+
+# --------------------------------------------------------------------------
+# int8 activation cache (Sec. 3.1): the step consumes dequantised values
+# --------------------------------------------------------------------------
+def dequantize_rows(q, s):
+    """x[l, b, :] = q[l, b, :] * s[l, b] for symmetric int8 codes q."""
+    return np.asarray(q, F64) * np.asarray(s, F64)[:, :, None]
