@@ -1,0 +1,151 @@
+/*
+ * libclt -- one training step of a cross-layer transcoder (CLT) on one AMD
+ * MI355X (gfx950).  C ABI: plain pointers and sizes, no C++ or framework types.
+ *
+ * The model (paper Sec. 2.1): per layer l an encoder with JumpReLU,
+ *     pre[l] = x[l] W_enc[l] + b_enc[l],   z[l] = pre[l] * 1[pre[l] > theta[l]]   (eq. 1)
+ * and a cross-layer decode in which target layer l' sums the contributions of
+ * all source layers l <= l',
+ *     y_hat[l'] = sum_{l <= l'} z[l] W_dec[p(l,l')] + b_dec[l']                    (eq. 3)
+ * trained on the objective of App. B (reconstruction + lambda0 * tanh sparsity
+ * weighted by the decoder norm; the dead-feature term is not part of this
+ * library) with Adam (App. C, Table 1).
+ *
+ * Tensors (all DEVICE pointers owned by the caller, contiguous, row-major,
+ * 16-byte aligned; the library never allocates, frees or keeps them):
+ *   x      [L,B,d]  MLP inputs      storage type T (see clt_config.dtype), or int8 codes
+ *   y      [L,B,d]  MLP outputs     T, or int8 codes
+ *   W_enc  [L,d,F]  T               b_enc [L,F] float     theta [L,F] float
+ *   W_dec  [P,F,d]  T, P = L(L+1)/2 b_dec [L,d] float
+ *   z, pre [L,B,F]  T               y_hat [L,B,d] float (always fp32)
+ *   act_class [L,B,F] uint8: bit 0 = active (pre > theta), bit 1 = inside the
+ *          straight-through window |pre - theta| < ste_bandwidth/2; both decided
+ *          on the fp32 accumulator before any rounding.
+ * Packed decoder: block p(l,l') = l*L - l(l-1)/2 + (l'-l), 0 <= l <= l' < L
+ * (source-major: all decoders that leave source layer l are contiguous, which
+ * is the "concatenation" whose row norm the sparsity term uses); each block is
+ * [F,d] row-major, so one feature's decoder row is contiguous.
+ * The vectors b_enc, theta, b_dec, their gradients and all Adam moments are
+ * always float; T applies to the matrices and activations.
+ *
+ * Every function returns 0 (CLT_OK) or a negative clt_status.  Arguments are
+ * checked before any kernel is launched; after an error nothing was enqueued.
+ * All work is enqueued on the caller's HIP stream (`stream` is a hipStream_t
+ * passed as void*; NULL = the default stream) and the functions do not
+ * synchronise, except clt_loss when asked for a host copy of the loss.
+ * Calls on one handle must not overlap (they share its workspace).
+ */
+#ifndef CLT_H_
+#define CLT_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct clt_handle clt_handle;
+
+typedef enum clt_status {
+  CLT_OK = 0,
+  CLT_ERR_INVALID_ARG = -1, /* null pointer, bad enum or scalar               */
+  CLT_ERR_SHAPE = -2,       /* L,d,F,B out of the supported range              */
+  CLT_ERR_ALIGN = -3,       /* a tensor pointer is not 16-byte aligned         */
+  CLT_ERR_WORKSPACE = -4,   /* workspace missing, misaligned or too small      */
+  CLT_ERR_HIP = -5,         /* a HIP runtime call failed (see clt_last_error)  */
+  CLT_ERR_STATE = -6        /* calls out of order (loss before forward, ...)   */
+} clt_status;
+
+enum { CLT_DTYPE_F32 = 0, CLT_DTYPE_BF16 = 1 };
+enum { CLT_INPUT_NATIVE = 0, CLT_INPUT_INT8_ROWSCALE = 1 };
+enum { CLT_DECODE_AUTO = 0, CLT_DECODE_DENSE = 1, CLT_DECODE_GATHER = 2 };
+
+/* Plain data; set .size = sizeof(clt_config).  Shapes: L >= 1, B >= 1,
+ * d and F positive multiples of 8. */
+typedef struct clt_config {
+  uint32_t size;
+  int32_t L, d, F, B;
+  int32_t dtype;          /* CLT_DTYPE_F32: fp32 storage and fp32 FMA accumulate;
+                             CLT_DTYPE_BF16: bf16 storage, bf16 MFMA, fp32 accumulate */
+  int32_t input_format;   /* CLT_INPUT_INT8_ROWSCALE: x and y are int8 codes with one
+                             float scale per (layer, token) row (Sec. 3.1 cache format) */
+  int32_t master_weights; /* 1: clt_adam_step updates fp32 master copies of W_enc/W_dec  */
+  int32_t decode_mode;    /* dense GEMM decode, active-feature gather decode (Sec. 3.2),
+                             or chosen per step from the measured density               */
+  float gather_density_threshold; /* AUTO: gather when mean active fraction <= this      */
+  float C;                /* sparsity scale C of the App. B objective                     */
+  float ste_bandwidth;    /* width eps of the rectangle kernel of the threshold gradient */
+  float beta1, beta2, adam_eps; /* Adam (App. C Table 1: 0.9, 0.999)                     */
+} clt_config;
+
+/* The five learned tensors, or things shaped like them (gradients, moments). */
+typedef struct clt_tensors {
+  void* W_enc;  /* [L,d,F] */
+  float* b_enc; /* [L,F]   */
+  float* theta; /* [L,F]   */
+  void* W_dec;  /* [P,F,d] */
+  float* b_dec; /* [L,d]   */
+} clt_tensors;
+
+/* Bytes of device workspace clt_init needs for this configuration. */
+int clt_workspace_bytes(const clt_config* cfg, size_t* bytes);
+
+/* Creates a handle bound to `workspace` (device memory, 256-byte aligned, at
+ * least clt_workspace_bytes long, owned by the caller and kept alive until
+ * clt_destroy).  Fails with CLT_ERR_HIP when no HIP device is usable. */
+int clt_init(clt_handle** handle, const clt_config* cfg, void* workspace, size_t workspace_bytes);
+int clt_destroy(clt_handle* handle);
+
+/* Message of the last error on this handle (or of the last failed clt_init /
+ * clt_workspace_bytes on this thread when handle is NULL).  Never NULL. */
+const char* clt_last_error(const clt_handle* handle);
+
+/* Encoder + JumpReLU (eq. 1), decoder norms (App. B), cross-layer decode (eq. 3).
+ * x_scale: [L,B] float for int8 inputs, else NULL.  Outputs: z, act_class,
+ * y_hat are required; pre and l0_per_layer ([L] int32, active entries per
+ * layer summed over tokens) may be NULL. */
+int clt_forward(clt_handle* handle, void* stream,
+                const void* x, const float* x_scale,
+                const void* W_enc, const float* b_enc, const float* theta,
+                const void* W_dec, const float* b_dec,
+                void* z, void* pre, uint8_t* act_class, float* y_hat, int32_t* l0_per_layer);
+
+/* App. B objective with lambda_1 = 0, mean over the B tokens:
+ *   L_rec = (1/B) sum (y_hat - y)^2,  L_sp = (lambda0/B) sum tanh(C z n[l,f]).
+ * Needs the decoder norms of the preceding clt_forward on this handle.  Writes
+ * loss_dev[0..2] = {L_rec + L_sp, L_rec, L_sp} (device) and keeps d y_hat and the
+ * sparsity-gradient column sums in the workspace for clt_backward.  If
+ * loss_host is not NULL the three floats are also copied there and the stream
+ * is synchronised. */
+int clt_loss(clt_handle* handle, void* stream,
+             const void* y, const float* y_scale, const float* y_hat, const void* z,
+             float lambda0, float* loss_dev, float* loss_host);
+
+/* Gradients of the objective evaluated by the preceding clt_loss, w.r.t. the
+ * five learned tensors (grads->W_enc, W_dec in T; vectors float).  JumpReLU
+ * passes gradient to pre where active; theta gets the rectangle-kernel
+ * pseudo-gradient -(theta/eps) sum_b 1[in window] dz. */
+int clt_backward(clt_handle* handle, void* stream,
+                 const void* x, const float* x_scale, const float* theta,
+                 const void* W_dec, const void* z, const uint8_t* act_class,
+                 const clt_tensors* grads);
+
+/* One Adam step (1-based step count t, bias correction on, eps outside the
+ * square root, no weight decay) on all five tensors.  m and v hold float
+ * moments for every tensor.  master: NULL, or fp32 master copies of W_enc and
+ * W_dec (its vector members are ignored) that are updated and then rounded
+ * into params. */
+int clt_adam_step(clt_handle* handle, void* stream, int64_t t, float lr,
+                  const clt_tensors* params, const clt_tensors* grads,
+                  const clt_tensors* m, const clt_tensors* v, const clt_tensors* master);
+
+/* Device pointers into the workspace, for inspection by tests and tools:
+ * which = 0 decoder norms [L,F] float; 1 d y_hat [L,B,d] T; 2 d pre [L,B,F] T;
+ * 3 sparsity column sums G [L,F] float.  Valid after the call that writes them. */
+int clt_workspace_view(const clt_handle* handle, int which, void** ptr, size_t* bytes);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CLT_H_ */

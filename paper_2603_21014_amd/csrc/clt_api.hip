@@ -1,0 +1,347 @@
+// C ABI of libclt (include/clt.h): argument validation, workspace planning and
+// the order in which the kernels of a CLT train step are enqueued.  No
+// arithmetic of the method lives here.
+#include "../../include/clt.h"
+
+#include <math.h>
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <new>
+
+#include "common.h"
+
+using namespace clt;
+
+namespace {
+
+constexpr size_t ALIGN = 256;
+inline size_t align_up(size_t v) { return (v + ALIGN - 1) / ALIGN * ALIGN; }
+
+struct Plan {
+  size_t norms, G, d_yhat, dpre, part_cols, part_cols2, part_rec, part_sp, total;
+};
+
+thread_local char g_err[256] = "";
+
+void set_err(char* dst, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(dst, 256, fmt, ap);
+  va_end(ap);
+}
+
+}  // namespace
+
+struct clt_handle {
+  clt_config cfg;
+  Dims D;
+  bool bf16, int8;
+  size_t esz;             // bytes per element of T
+  char* ws;
+  Plan plan;
+  int stage;              // 0 = fresh, 1 = forward done, 2 = loss done
+  float lambda0;
+  char err[256];
+};
+
+namespace {
+
+int check_config(const clt_config* c, char* err) {
+  if (!c) { set_err(err, "config is NULL"); return CLT_ERR_INVALID_ARG; }
+  if (c->size != sizeof(clt_config)) {
+    set_err(err, "config.size is %u, this library expects %zu", c->size, sizeof(clt_config));
+    return CLT_ERR_INVALID_ARG;
+  }
+  if (c->L < 1 || c->L > 128 || c->B < 1 || c->d < 8 || c->F < 8 || (c->d % 8) || (c->F % 8)) {
+    set_err(err, "unsupported shape L=%d d=%d F=%d B=%d (need 1<=L<=128, B>=1, d and F positive multiples of 8)",
+            c->L, c->d, c->F, c->B);
+    return CLT_ERR_SHAPE;
+  }
+  if ((double)c->L * c->B * (double)c->F >= 9.0e18 || (size_t)c->L * c->B > (size_t)1 << 31) {
+    set_err(err, "shape too large");
+    return CLT_ERR_SHAPE;
+  }
+  if (c->dtype != CLT_DTYPE_F32 && c->dtype != CLT_DTYPE_BF16) { set_err(err, "bad dtype %d", c->dtype); return CLT_ERR_INVALID_ARG; }
+  if (c->input_format != CLT_INPUT_NATIVE && c->input_format != CLT_INPUT_INT8_ROWSCALE) {
+    set_err(err, "bad input_format %d", c->input_format);
+    return CLT_ERR_INVALID_ARG;
+  }
+  if (c->input_format == CLT_INPUT_INT8_ROWSCALE && c->dtype != CLT_DTYPE_BF16) {
+    set_err(err, "int8 inputs need dtype bf16");
+    return CLT_ERR_INVALID_ARG;
+  }
+  if (c->master_weights != 0 && c->master_weights != 1) { set_err(err, "bad master_weights"); return CLT_ERR_INVALID_ARG; }
+  if (c->decode_mode != CLT_DECODE_DENSE) {
+    set_err(err, "decode_mode %d is not available in this build (dense = %d only)", c->decode_mode, CLT_DECODE_DENSE);
+    return CLT_ERR_INVALID_ARG;
+  }
+  if (!(c->C > 0.f) || !(c->ste_bandwidth > 0.f) || !(c->beta1 >= 0.f && c->beta1 < 1.f) ||
+      !(c->beta2 >= 0.f && c->beta2 < 1.f) || !(c->adam_eps > 0.f)) {
+    set_err(err, "bad scalar: need C>0, ste_bandwidth>0, 0<=beta<1, adam_eps>0");
+    return CLT_ERR_INVALID_ARG;
+  }
+  return CLT_OK;
+}
+
+Plan make_plan(const clt_config* c) {
+  const size_t L = c->L, d = c->d, F = c->F, B = c->B;
+  const size_t esz = c->dtype == CLT_DTYPE_BF16 ? 2 : 4;
+  const size_t rbs = row_blocks(c->B);
+  const size_t wide = F > d ? F : d;
+  Plan p;
+  size_t o = 0;
+  p.norms = o;      o += align_up(L * F * 4);
+  p.G = o;          o += align_up(L * F * 4);
+  p.d_yhat = o;     o += align_up(L * B * d * esz);
+  p.dpre = o;       o += align_up(L * B * F * esz);
+  p.part_cols = o;  o += align_up(rbs * L * wide * 4);
+  p.part_cols2 = o; o += align_up(rbs * L * F * 4);
+  p.part_rec = o;   o += align_up(rbs * L * 8);
+  p.part_sp = o;    o += align_up(rbs * L * 8);
+  p.total = o;
+  return p;
+}
+
+bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
+
+#define REQ(h, ptr)                                                                   \
+  do {                                                                                \
+    if (!(ptr)) { set_err((h)->err, "%s: argument %s is NULL", __func__, #ptr); return CLT_ERR_INVALID_ARG; } \
+    if (misaligned(ptr)) { set_err((h)->err, "%s: argument %s is not 16-byte aligned", __func__, #ptr); return CLT_ERR_ALIGN; } \
+  } while (0)
+#define OPT(h, ptr)                                                                   \
+  do {                                                                                \
+    if ((ptr) && misaligned(ptr)) { set_err((h)->err, "%s: argument %s is not 16-byte aligned", __func__, #ptr); return CLT_ERR_ALIGN; } \
+  } while (0)
+#define HIPCHK(h, expr)                                                               \
+  do {                                                                                \
+    hipError_t e__ = (expr);                                                          \
+    if (e__ != hipSuccess) {                                                          \
+      set_err((h)->err, "%s: %s failed: %s", __func__, #expr, hipGetErrorString(e__)); \
+      return CLT_ERR_HIP;                                                             \
+    }                                                                                 \
+  } while (0)
+
+int check_tensors(clt_handle* h, const char* what, const clt_tensors* t, bool need_matrices_only) {
+  if (!t) { set_err(h->err, "clt tensors '%s' is NULL", what); return CLT_ERR_INVALID_ARG; }
+  const void* ptrs[5] = {t->W_enc, t->b_enc, t->theta, t->W_dec, t->b_dec};
+  const char* names[5] = {"W_enc", "b_enc", "theta", "W_dec", "b_dec"};
+  for (int i = 0; i < 5; ++i) {
+    const bool matrix = (i == 0 || i == 3);
+    if (need_matrices_only && !matrix) continue;
+    if (!ptrs[i]) { set_err(h->err, "%s.%s is NULL", what, names[i]); return CLT_ERR_INVALID_ARG; }
+    if (misaligned(ptrs[i])) { set_err(h->err, "%s.%s is not 16-byte aligned", what, names[i]); return CLT_ERR_ALIGN; }
+  }
+  return CLT_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int clt_workspace_bytes(const clt_config* cfg, size_t* bytes) {
+  if (!bytes) { set_err(g_err, "clt_workspace_bytes: bytes is NULL"); return CLT_ERR_INVALID_ARG; }
+  const int rc = check_config(cfg, g_err);
+  if (rc != CLT_OK) return rc;
+  *bytes = make_plan(cfg).total;
+  return CLT_OK;
+}
+
+int clt_init(clt_handle** handle, const clt_config* cfg, void* workspace, size_t workspace_bytes) {
+  if (!handle) { set_err(g_err, "clt_init: handle is NULL"); return CLT_ERR_INVALID_ARG; }
+  *handle = nullptr;
+  const int rc = check_config(cfg, g_err);
+  if (rc != CLT_OK) return rc;
+  const Plan plan = make_plan(cfg);
+  if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & (ALIGN - 1)) || workspace_bytes < plan.total) {
+    set_err(g_err, "clt_init: workspace must be non-NULL, 256-byte aligned and at least %zu bytes (got %zu)",
+            plan.total, workspace_bytes);
+    return CLT_ERR_WORKSPACE;
+  }
+  int ndev = 0;
+  hipError_t e = hipGetDeviceCount(&ndev);
+  if (e != hipSuccess || ndev < 1) {
+    set_err(g_err, "clt_init: no usable HIP device (%s)", e != hipSuccess ? hipGetErrorString(e) : "count 0");
+    (void)hipGetLastError();
+    return CLT_ERR_HIP;
+  }
+  if (cfg->dtype == CLT_DTYPE_BF16) {
+    e = init_gemm_bf16();
+    if (e != hipSuccess) {
+      set_err(g_err, "clt_init: cannot configure the MFMA kernels (%s); this library needs a gfx950 device",
+              hipGetErrorString(e));
+      (void)hipGetLastError();
+      return CLT_ERR_HIP;
+    }
+  }
+  clt_handle* h = new (std::nothrow) clt_handle;
+  if (!h) { set_err(g_err, "clt_init: out of host memory"); return CLT_ERR_INVALID_ARG; }
+  h->cfg = *cfg;
+  h->D = Dims{cfg->L, cfg->d, cfg->F, cfg->B};
+  h->bf16 = cfg->dtype == CLT_DTYPE_BF16;
+  h->int8 = cfg->input_format == CLT_INPUT_INT8_ROWSCALE;
+  h->esz = h->bf16 ? 2 : 4;
+  h->ws = static_cast<char*>(workspace);
+  h->plan = plan;
+  h->stage = 0;
+  h->lambda0 = 0.f;
+  h->err[0] = 0;
+  *handle = h;
+  return CLT_OK;
+}
+
+int clt_destroy(clt_handle* handle) {
+  delete handle;
+  return CLT_OK;
+}
+
+const char* clt_last_error(const clt_handle* handle) { return handle ? handle->err : g_err; }
+
+int clt_workspace_view(const clt_handle* h, int which, void** ptr, size_t* bytes) {
+  if (!h || !ptr || !bytes) return CLT_ERR_INVALID_ARG;
+  const size_t L = h->D.L, d = h->D.d, F = h->D.F, B = h->D.B;
+  switch (which) {
+    case 0: *ptr = h->ws + h->plan.norms; *bytes = L * F * 4; break;
+    case 1: *ptr = h->ws + h->plan.d_yhat; *bytes = L * B * d * h->esz; break;
+    case 2: *ptr = h->ws + h->plan.dpre; *bytes = L * B * F * h->esz; break;
+    case 3: *ptr = h->ws + h->plan.G; *bytes = L * F * 4; break;
+    default: return CLT_ERR_INVALID_ARG;
+  }
+  return CLT_OK;
+}
+
+int clt_forward(clt_handle* h, void* stream, const void* x, const float* x_scale, const void* W_enc,
+                const float* b_enc, const float* theta, const void* W_dec, const float* b_dec, void* z, void* pre,
+                uint8_t* act_class, float* y_hat, int32_t* l0_per_layer) {
+  if (!h) { set_err(g_err, "clt_forward: handle is NULL"); return CLT_ERR_INVALID_ARG; }
+  REQ(h, x); REQ(h, W_enc); REQ(h, b_enc); REQ(h, theta); REQ(h, W_dec); REQ(h, b_dec);
+  REQ(h, z); REQ(h, act_class); REQ(h, y_hat);
+  OPT(h, pre); OPT(h, l0_per_layer);
+  if (h->int8) REQ(h, x_scale);
+  else if (x_scale) { set_err(h->err, "clt_forward: x_scale given but input_format is native"); return CLT_ERR_INVALID_ARG; }
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  h->stage = 0;
+  float* norms = reinterpret_cast<float*>(h->ws + h->plan.norms);
+  if (l0_per_layer) HIPCHK(h, launch_zero_i32(s, l0_per_layer, h->D.L));
+  HIPCHK(h, launch_decoder_norms(s, h->bf16, h->D, W_dec, norms));
+  EncArgs ea{x, x_scale, W_enc, b_enc, theta, h->cfg.ste_bandwidth, z, pre, act_class, l0_per_layer};
+  DecArgs da{z, W_dec, b_dec, y_hat};
+  if (h->bf16) {
+    HIPCHK(h, launch_enc_bf16(s, h->D, ea, h->int8));
+    HIPCHK(h, launch_dec_bf16(s, h->D, da));
+  } else {
+    HIPCHK(h, launch_enc_f32(s, h->D, ea));
+    HIPCHK(h, launch_dec_f32(s, h->D, da));
+  }
+  h->stage = 1;
+  return CLT_OK;
+}
+
+int clt_loss(clt_handle* h, void* stream, const void* y, const float* y_scale, const float* y_hat, const void* z,
+             float lambda0, float* loss_dev, float* loss_host) {
+  if (!h) { set_err(g_err, "clt_loss: handle is NULL"); return CLT_ERR_INVALID_ARG; }
+  REQ(h, y); REQ(h, y_hat); REQ(h, z); REQ(h, loss_dev);
+  if (h->int8) REQ(h, y_scale);
+  else if (y_scale) { set_err(h->err, "clt_loss: y_scale given but input_format is native"); return CLT_ERR_INVALID_ARG; }
+  if (!(lambda0 >= 0.f)) { set_err(h->err, "clt_loss: lambda0 must be >= 0"); return CLT_ERR_INVALID_ARG; }
+  if (h->stage < 1) { set_err(h->err, "clt_loss: call clt_forward first (decoder norms missing)"); return CLT_ERR_STATE; }
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const Dims D = h->D;
+  const int rbs = row_blocks(D.B);
+  float* norms = reinterpret_cast<float*>(h->ws + h->plan.norms);
+  float* G = reinterpret_cast<float*>(h->ws + h->plan.G);
+  float* part = reinterpret_cast<float*>(h->ws + h->plan.part_cols);
+  double* prec = reinterpret_cast<double*>(h->ws + h->plan.part_rec);
+  double* psp = reinterpret_cast<double*>(h->ws + h->plan.part_sp);
+  void* d_yhat = h->ws + h->plan.d_yhat;
+  h->stage = 1;
+  // sparsity first: its column partials are folded into G before the same
+  // partial buffer is reused for the db_dec partials of the reconstruction pass
+  HIPCHK(h, launch_loss_sparsity(s, h->bf16, D, z, norms, h->cfg.C, psp, part));
+  HIPCHK(h, launch_col_reduce(s, part, rbs, D.L * D.F, lambda0 / (float)D.B, nullptr, 0.f, G));
+  HIPCHK(h, launch_loss_rec(s, h->bf16, h->int8, D, y_hat, y, y_scale, d_yhat, prec, part));
+  HIPCHK(h, launch_loss_final(s, prec, rbs * D.L, psp, rbs * D.L, 1.0f / (float)D.B, lambda0, loss_dev));
+  h->lambda0 = lambda0;
+  h->stage = 2;
+  if (loss_host) {
+    HIPCHK(h, hipMemcpyAsync(loss_host, loss_dev, 3 * sizeof(float), hipMemcpyDeviceToHost, s));
+    HIPCHK(h, hipStreamSynchronize(s));
+  }
+  return CLT_OK;
+}
+
+int clt_backward(clt_handle* h, void* stream, const void* x, const float* x_scale, const float* theta,
+                 const void* W_dec, const void* z, const uint8_t* act_class, const clt_tensors* grads) {
+  if (!h) { set_err(g_err, "clt_backward: handle is NULL"); return CLT_ERR_INVALID_ARG; }
+  REQ(h, x); REQ(h, theta); REQ(h, W_dec); REQ(h, z); REQ(h, act_class);
+  if (h->int8) REQ(h, x_scale);
+  else if (x_scale) { set_err(h->err, "clt_backward: x_scale given but input_format is native"); return CLT_ERR_INVALID_ARG; }
+  int rc = check_tensors(h, "grads", grads, false);
+  if (rc != CLT_OK) return rc;
+  if (h->stage < 2) { set_err(h->err, "clt_backward: call clt_forward and clt_loss first"); return CLT_ERR_STATE; }
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const Dims D = h->D;
+  const int rbs = row_blocks(D.B);
+  float* norms = reinterpret_cast<float*>(h->ws + h->plan.norms);
+  float* G = reinterpret_cast<float*>(h->ws + h->plan.G);
+  float* part = reinterpret_cast<float*>(h->ws + h->plan.part_cols);
+  float* part2 = reinterpret_cast<float*>(h->ws + h->plan.part_cols2);
+  void* d_yhat = h->ws + h->plan.d_yhat;
+  void* dpre = h->ws + h->plan.dpre;
+
+  // db_dec from the column partials that clt_loss left behind
+  HIPCHK(h, launch_col_reduce(s, part, rbs, D.L * D.d, 1.0f, nullptr, 0.f, grads->b_dec));
+  DzArgs za{d_yhat, W_dec, z, act_class, norms, h->lambda0 * h->cfg.C / (float)D.B, h->cfg.C, dpre};
+  DWdecArgs wa{z, d_yhat, W_dec, G, norms, grads->W_dec};
+  DWencArgs ea{x, dpre, grads->W_enc};
+  if (h->bf16) HIPCHK(h, launch_dz_bf16(s, D, za)); else HIPCHK(h, launch_dz_f32(s, D, za));
+  HIPCHK(h, launch_ste_reduce(s, h->bf16, D, dpre, act_class, h->int8 ? x_scale : nullptr, part, part2));
+  HIPCHK(h, launch_col_reduce(s, part, rbs, D.L * D.F, 1.0f, theta, 1.0f / h->cfg.ste_bandwidth, grads->theta));
+  HIPCHK(h, launch_col_reduce(s, part2, rbs, D.L * D.F, 1.0f, nullptr, 0.f, grads->b_enc));
+  if (h->bf16) {
+    HIPCHK(h, launch_dwenc_bf16(s, D, ea, h->int8));
+    HIPCHK(h, launch_dwdec_bf16(s, D, wa));
+  } else {
+    HIPCHK(h, launch_dwenc_f32(s, D, ea));
+    HIPCHK(h, launch_dwdec_f32(s, D, wa));
+  }
+  h->stage = 1;   // the loss by-products are consumed; a new clt_loss is needed before the next backward
+  return CLT_OK;
+}
+
+int clt_adam_step(clt_handle* h, void* stream, int64_t t, float lr, const clt_tensors* params,
+                  const clt_tensors* grads, const clt_tensors* m, const clt_tensors* v, const clt_tensors* master) {
+  if (!h) { set_err(g_err, "clt_adam_step: handle is NULL"); return CLT_ERR_INVALID_ARG; }
+  if (t < 1) { set_err(h->err, "clt_adam_step: step count t must be >= 1"); return CLT_ERR_INVALID_ARG; }
+  if (!(lr >= 0.f)) { set_err(h->err, "clt_adam_step: lr must be >= 0"); return CLT_ERR_INVALID_ARG; }
+  int rc;
+  if ((rc = check_tensors(h, "params", params, false)) != CLT_OK) return rc;
+  if ((rc = check_tensors(h, "grads", grads, false)) != CLT_OK) return rc;
+  if ((rc = check_tensors(h, "m", m, false)) != CLT_OK) return rc;
+  if ((rc = check_tensors(h, "v", v, false)) != CLT_OK) return rc;
+  if (h->cfg.master_weights) {
+    if ((rc = check_tensors(h, "master", master, true)) != CLT_OK) return rc;
+  } else if (master) {
+    set_err(h->err, "clt_adam_step: master given but config.master_weights is 0");
+    return CLT_ERR_INVALID_ARG;
+  }
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const Dims D = h->D;
+  AdamScalars a;
+  a.lr = lr; a.beta1 = h->cfg.beta1; a.beta2 = h->cfg.beta2; a.eps = h->cfg.adam_eps;
+  a.bc1 = (float)(1.0 - pow((double)h->cfg.beta1, (double)t));
+  a.bc2 = (float)(1.0 - pow((double)h->cfg.beta2, (double)t));
+  const size_t n_enc = (size_t)D.L * D.d * D.F, n_dec = (size_t)D.P() * D.F * D.d;
+  HIPCHK(h, launch_adam_matrix(s, h->bf16, n_dec, params->W_dec, grads->W_dec, (float*)m->W_dec, (float*)v->W_dec,
+                               master ? (float*)master->W_dec : nullptr, a));
+  HIPCHK(h, launch_adam_matrix(s, h->bf16, n_enc, params->W_enc, grads->W_enc, (float*)m->W_enc, (float*)v->W_enc,
+                               master ? (float*)master->W_enc : nullptr, a));
+  HIPCHK(h, launch_adam_vector(s, (size_t)D.L * D.F, params->b_enc, grads->b_enc, m->b_enc, v->b_enc, a));
+  HIPCHK(h, launch_adam_vector(s, (size_t)D.L * D.F, params->theta, grads->theta, m->theta, v->theta, a));
+  HIPCHK(h, launch_adam_vector(s, (size_t)D.L * D.d, params->b_dec, grads->b_dec, m->b_dec, v->b_dec, a));
+  return CLT_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,127 @@
+// Shared declarations of the HIP side of libclt: problem dimensions, bf16
+// helpers and the internal launch interface between the C ABI (clt_api.hip)
+// and the kernel translation units.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace clt {
+
+struct Dims {
+  int L, d, F, B;
+  __host__ __device__ int P() const { return L * (L + 1) / 2; }
+};
+
+// Packed index of decoder block (source l -> target lp), source-major (eq. 3).
+__host__ __device__ inline int packed_index(int l, int lp, int L) {
+  return l * L - (l * (l - 1)) / 2 + (lp - l);
+}
+
+typedef uint16_t bf16_t;  // raw bf16 bits
+
+__device__ __forceinline__ float bf16_to_f32(bf16_t h) { return __uint_as_float(((uint32_t)h) << 16); }
+
+// Round-to-nearest-even float -> bf16 (NaN stays NaN).
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (bf16_t)(u >> 16);
+}
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+  return (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16);
+}
+
+// Element-type traits for the two storage types.
+template <typename T> struct Elem;
+template <> struct Elem<float> {
+  static __device__ __forceinline__ float load(const float* p) { return *p; }
+  static __device__ __forceinline__ void store(float* p, float v) { *p = v; }
+  static __device__ __forceinline__ void store4(float* p, float4 v) { *reinterpret_cast<float4*>(p) = v; }
+  static __device__ __forceinline__ float4 load4(const float* p) { return *reinterpret_cast<const float4*>(p); }
+};
+template <> struct Elem<bf16_t> {
+  static __device__ __forceinline__ float load(const bf16_t* p) { return bf16_to_f32(*p); }
+  static __device__ __forceinline__ void store(bf16_t* p, float v) { *p = f32_to_bf16(v); }
+  static __device__ __forceinline__ void store4(bf16_t* p, float4 v) {
+    uint2 u;
+    u.x = pack_bf16x2(v.x, v.y);
+    u.y = pack_bf16x2(v.z, v.w);
+    *reinterpret_cast<uint2*>(p) = u;
+  }
+  static __device__ __forceinline__ float4 load4(const bf16_t* p) {
+    uint2 u = *reinterpret_cast<const uint2*>(p);
+    return make_float4(__uint_as_float(u.x << 16), __uint_as_float(u.x & 0xffff0000u),
+                       __uint_as_float(u.y << 16), __uint_as_float(u.y & 0xffff0000u));
+  }
+};
+
+// act_class bits
+constexpr uint8_t CLS_ACTIVE = 1;
+constexpr uint8_t CLS_WINDOW = 2;
+
+// ---------------------------------------------------------------------------
+// Launch interface.  `bf16` selects the storage type T of matrices/activations.
+// All functions enqueue on `s` and return the launch status.
+// ---------------------------------------------------------------------------
+struct EncArgs {       // pre = x W_enc + b_enc; JumpReLU; classes; L0 counts
+  const void* x; const float* x_scale; const void* W_enc; const float* b_enc; const float* theta;
+  float ste_eps; void* z; void* pre; uint8_t* cls; int32_t* l0;
+};
+struct DecArgs {       // y_hat[lp] = sum_{l<=lp} z[l] W_dec[p(l,lp)] + b_dec[lp]
+  const void* z; const void* W_dec; const float* b_dec; float* y_hat;
+};
+struct DzArgs {        // dz[l] = sum_{lp>=l} dyhat[lp] W_dec[p(l,lp)]^T + g_sp, kept where active|window
+  const void* d_yhat; const void* W_dec; const void* z; const uint8_t* cls; const float* norms;
+  float lam_c_over_b; float C; void* dpre;
+};
+struct DWdecArgs {     // dW_dec[p] = z[l]^T dyhat[lp] + (G/n)[l,f] W_dec[p][f,:]
+  const void* z; const void* d_yhat; const void* W_dec; const float* G; const float* norms; void* dW_dec;
+};
+struct DWencArgs {     // dW_enc[l] = x[l]^T dpre[l]
+  const void* x; const void* dpre; void* dW_enc;
+};
+
+hipError_t launch_enc_f32(hipStream_t s, Dims D, const EncArgs& a);
+hipError_t launch_dec_f32(hipStream_t s, Dims D, const DecArgs& a);
+hipError_t launch_dz_f32(hipStream_t s, Dims D, const DzArgs& a);
+hipError_t launch_dwdec_f32(hipStream_t s, Dims D, const DWdecArgs& a);
+hipError_t launch_dwenc_f32(hipStream_t s, Dims D, const DWencArgs& a);
+
+hipError_t launch_enc_bf16(hipStream_t s, Dims D, const EncArgs& a, bool int8_x);
+hipError_t launch_dec_bf16(hipStream_t s, Dims D, const DecArgs& a);
+hipError_t launch_dz_bf16(hipStream_t s, Dims D, const DzArgs& a);
+hipError_t launch_dwdec_bf16(hipStream_t s, Dims D, const DWdecArgs& a);
+hipError_t launch_dwenc_bf16(hipStream_t s, Dims D, const DWencArgs& a, bool int8_x);
+hipError_t init_gemm_bf16();   // one-time function attributes (LDS size)
+
+// Elementwise / reduction kernels (kernels_elementwise.hip)
+constexpr int LOSS_ROWS_PER_BLOCK = 32;   // token rows per block of the row-blocked reductions
+inline int row_blocks(int B) { return (B + LOSS_ROWS_PER_BLOCK - 1) / LOSS_ROWS_PER_BLOCK; }
+
+hipError_t launch_zero_i32(hipStream_t s, int32_t* p, int n);
+hipError_t launch_decoder_norms(hipStream_t s, bool bf16, Dims D, const void* W_dec, float* norms);
+// L_rec partials, d_yhat = 2 r / B, column partials for db_dec
+hipError_t launch_loss_rec(hipStream_t s, bool bf16, bool int8_y, Dims D, const float* y_hat, const void* y,
+                           const float* y_scale, void* d_yhat, double* loss_part, float* col_part);
+// L_sp partials and column partials of C z sech^2(C z n)
+hipError_t launch_loss_sparsity(hipStream_t s, bool bf16, Dims D, const void* z, const float* norms, float C,
+                                double* loss_part, float* col_part);
+// final loss: loss_dev = {rec + sp, rec, sp}
+hipError_t launch_loss_final(hipStream_t s, const double* part_rec, int n_rec, const double* part_sp, int n_sp,
+                             float inv_B, float lambda0, float* loss_dev);
+// out[c] = alpha * sum_r part[r][c] (fixed order), optionally times -(theta[c]/eps)
+hipError_t launch_col_reduce(hipStream_t s, const float* part, int nparts, int ncols, float alpha,
+                             const float* theta_or_null, float inv_eps, float* out);
+// reads dz kept where active|window: column partials for dtheta (window) and db_enc (active);
+// zeroes entries that are in the window but not active so the buffer becomes dpre
+hipError_t launch_ste_reduce(hipStream_t s, bool bf16, Dims D, void* dpre, const uint8_t* cls,
+                             const float* row_scale_or_null, float* part_theta, float* part_benc);
+
+struct AdamScalars { float lr, beta1, beta2, eps, bc1, bc2; };   // bc = 1 - beta^t
+// p, g in T (or p in T with fp32 master); m, v float
+hipError_t launch_adam_matrix(hipStream_t s, bool bf16, size_t n, void* p, const void* g, float* m, float* v,
+                              float* master_or_null, AdamScalars a);
+hipError_t launch_adam_vector(hipStream_t s, size_t n, float* p, const float* g, float* m, float* v, AdamScalars a);
+
+}  // namespace clt

@@ -1,0 +1,238 @@
+// The five contractions of a CLT train step, each described as a "policy":
+// operand addressing (which memory dimension is the contraction index K), the
+// K segments of the triangular sums, and the fused epilogue.  The same policies
+// drive the fp32 FMA kernel (gemm_f32.h) and the bf16 MFMA kernel
+// (gemm_bf16.h).
+//
+// A policy exposes
+//   A_KC / B_KC  true when the operand is contiguous along K in memory
+//                (A element (m,k) at a[m*lda + k]; otherwise at a[k*lda + m];
+//                 B element (k,n) at b[n*ldb + k] when B_KC, else b[k*ldb + n])
+//   M, N, kseg   tile-space extents and the length of one K segment
+//   ginfo(order) group visited at position `order` of the launch (longest K first)
+//   nseg(gi), a_seg(gi,s), b_seg(gi,s)   K segments of a group
+//   epi4(st, gi, row, col, v)  consumes 4 accumulators of one row, columns col..col+3
+#pragma once
+#include "common.h"
+
+namespace clt {
+
+// Maps a workgroup index to (group order, tile row, tile column).
+// Workgroups are dealt round-robin to the 8 XCDs, each with a private L2, so
+// XCD x = wg % 8 takes a contiguous eighth of every group's tile list, and the
+// list itself runs through column panels SN tiles wide: the ~32 tiles an XCD
+// has in flight then form a compact 2-D block that shares few A and B panels.
+struct TileGrid {
+  int G, mt, nt, per_xcd;
+  static constexpr int SN = 8;
+  __host__ __device__ static TileGrid make(int G, int M, int N, int TM, int TN) {
+    TileGrid t;
+    t.G = G;
+    t.mt = (M + TM - 1) / TM;
+    t.nt = (N + TN - 1) / TN;
+    t.per_xcd = (t.mt * t.nt + 7) / 8;
+    return t;
+  }
+  __host__ __device__ int num_wg() const { return G * per_xcd * 8; }
+  __device__ bool decode(int wg, int& gorder, int& tm, int& tn) const {
+    const int xcd = wg & 7, slot = wg >> 3;
+    gorder = slot / per_xcd;
+    const int t = xcd * per_xcd + (slot - gorder * per_xcd);
+    if (t >= mt * nt) return false;
+    const int full = nt / SN, rem = nt - full * SN;
+    const int tiles_full = full * mt * SN;
+    if (t < tiles_full) {
+      const int panel = t / (mt * SN), r = t - panel * mt * SN;
+      tm = r / SN;
+      tn = panel * SN + (r - tm * SN);
+    } else {
+      const int r = t - tiles_full;
+      tm = r / rem;
+      tn = full * SN + (r - tm * rem);
+    }
+    return true;
+  }
+};
+
+__device__ __forceinline__ uint32_t pack_u8x4(uint32_t a, uint32_t b, uint32_t c, uint32_t d) {
+  return a | (b << 8) | (c << 16) | (d << 24);
+}
+
+// ---------------------------------------------------------------------------
+// Encoder: pre[l] = x[l] W_enc[l] + b_enc[l]  (eq. 1), JumpReLU epilogue.
+// ---------------------------------------------------------------------------
+template <typename T, typename TA = T>
+struct EncPolicy {
+  static constexpr bool A_KC = true, B_KC = false;
+  typedef TA AType;
+  Dims D;
+  int M, N, kseg, lda, ldb;
+  const TA* x; const T* W_enc; const float* b_enc; const float* theta; const float* x_scale;
+  float half_eps; T* z; T* pre; uint8_t* cls; int32_t* l0;
+  struct GInfo { int l; };
+  struct Epi { int count; };
+  __device__ GInfo ginfo(int order) const { return {order}; }
+  __device__ int nseg(const GInfo&) const { return 1; }
+  __device__ const TA* a_seg(const GInfo& g, int) const { return x + (size_t)g.l * D.B * D.d; }
+  __device__ const T* b_seg(const GInfo& g, int) const { return W_enc + (size_t)g.l * D.d * D.F; }
+  __device__ void epi_begin(Epi& e) const { e.count = 0; }
+  __device__ void epi4(Epi& e, const GInfo& g, int row, int col, float4 v) const {
+    const size_t vo = (size_t)g.l * D.F + col;
+    const float4 b = *reinterpret_cast<const float4*>(b_enc + vo);
+    const float4 th = *reinterpret_cast<const float4*>(theta + vo);
+    if (x_scale) {   // int8 codes: the row scale multiplies the integer dot product
+      const float s = x_scale[(size_t)g.l * D.B + row];
+      v.x *= s; v.y *= s; v.z *= s; v.w *= s;
+    }
+    float p[4] = {v.x + b.x, v.y + b.y, v.z + b.z, v.w + b.w};
+    const float t[4] = {th.x, th.y, th.z, th.w};
+    float zz[4];
+    uint32_t c[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const bool act = p[i] > t[i];
+      const bool win = fabsf(p[i] - t[i]) < half_eps;
+      zz[i] = act ? p[i] : 0.0f;
+      c[i] = (act ? CLS_ACTIVE : 0) | (win ? CLS_WINDOW : 0);
+      e.count += act ? 1 : 0;
+    }
+    const size_t o = ((size_t)g.l * D.B + row) * D.F + col;
+    Elem<T>::store4(z + o, make_float4(zz[0], zz[1], zz[2], zz[3]));
+    if (pre) Elem<T>::store4(pre + o, make_float4(p[0], p[1], p[2], p[3]));
+    *reinterpret_cast<uint32_t*>(cls + o) = pack_u8x4(c[0], c[1], c[2], c[3]);
+  }
+  __device__ void epi_end(Epi& e, const GInfo& g) const {
+    if (!l0) return;
+    int c = e.count;
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) c += __shfl_xor(c, off, 64);
+    if ((threadIdx.x & 63) == 0 && c) atomicAdd(l0 + g.l, c);
+  }
+};
+
+// ---------------------------------------------------------------------------
+// Cross-layer decode (eq. 3): target lp, K runs over the sources l = 0..lp.
+// ---------------------------------------------------------------------------
+template <typename T>
+struct DecPolicy {
+  static constexpr bool A_KC = true, B_KC = false;
+  typedef T AType;
+  Dims D;
+  int M, N, kseg, lda, ldb;
+  const T* z; const T* W_dec; const float* b_dec; float* y_hat;
+  struct GInfo { int lp; };
+  struct Epi {};
+  __device__ GInfo ginfo(int order) const { return {D.L - 1 - order}; }   // longest K first
+  __device__ int nseg(const GInfo& g) const { return g.lp + 1; }
+  __device__ const T* a_seg(const GInfo&, int s) const { return z + (size_t)s * D.B * D.F; }
+  __device__ const T* b_seg(const GInfo& g, int s) const {
+    return W_dec + (size_t)packed_index(s, g.lp, D.L) * D.F * D.d;
+  }
+  __device__ void epi_begin(Epi&) const {}
+  __device__ void epi4(Epi&, const GInfo& g, int row, int col, float4 v) const {
+    const float4 b = *reinterpret_cast<const float4*>(b_dec + (size_t)g.lp * D.d + col);
+    *reinterpret_cast<float4*>(y_hat + ((size_t)g.lp * D.B + row) * D.d + col) =
+        make_float4(v.x + b.x, v.y + b.y, v.z + b.z, v.w + b.w);
+  }
+  __device__ void epi_end(Epi&, const GInfo&) const {}
+};
+
+// ---------------------------------------------------------------------------
+// dz[l] = sum_{lp>=l} dyhat[lp] W_dec[p(l,lp)]^T + sparsity gradient, kept
+// where the feature is active or inside the threshold window (0 elsewhere).
+// ---------------------------------------------------------------------------
+template <typename T>
+struct DzPolicy {
+  static constexpr bool A_KC = true, B_KC = true;
+  typedef T AType;
+  Dims D;
+  int M, N, kseg, lda, ldb;
+  const T* d_yhat; const T* W_dec; const T* z; const uint8_t* cls; const float* norms;
+  float lam_c_over_b, C; T* dpre;
+  struct GInfo { int l; };
+  struct Epi {};
+  __device__ GInfo ginfo(int order) const { return {order}; }             // K = (L-l) d, longest first
+  __device__ int nseg(const GInfo& g) const { return D.L - g.l; }
+  __device__ const T* a_seg(const GInfo& g, int s) const { return d_yhat + (size_t)(g.l + s) * D.B * D.d; }
+  __device__ const T* b_seg(const GInfo& g, int s) const {
+    return W_dec + (size_t)packed_index(g.l, g.l + s, D.L) * D.F * D.d;
+  }
+  __device__ void epi_begin(Epi&) const {}
+  __device__ void epi4(Epi&, const GInfo& g, int row, int col, float4 v) const {
+    const size_t o = ((size_t)g.l * D.B + row) * D.F + col;
+    const uint32_t c4 = *reinterpret_cast<const uint32_t*>(cls + o);
+    float4 out = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (c4) {
+      const float4 z4 = Elem<T>::load4(z + o);
+      const float4 n4 = *reinterpret_cast<const float4*>(norms + (size_t)g.l * D.F + col);
+      const float zz[4] = {z4.x, z4.y, z4.z, z4.w}, nn[4] = {n4.x, n4.y, n4.z, n4.w};
+      const float vv[4] = {v.x, v.y, v.z, v.w};
+      float r[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const float t = tanhf(C * zz[i] * nn[i]);
+        const float gsp = lam_c_over_b * nn[i] * (1.0f - t * t);
+        r[i] = ((c4 >> (8 * i)) & 3u) ? vv[i] + gsp : 0.0f;
+      }
+      out = make_float4(r[0], r[1], r[2], r[3]);
+    }
+    Elem<T>::store4(dpre + o, out);
+  }
+  __device__ void epi_end(Epi&, const GInfo&) const {}
+};
+
+// ---------------------------------------------------------------------------
+// dW_dec[p(l,lp)] = z[l]^T dyhat[lp] + (G[l,f] / n[l,f]) W_dec[p][f,:]
+// ---------------------------------------------------------------------------
+template <typename T>
+struct DWdecPolicy {
+  static constexpr bool A_KC = false, B_KC = false;
+  typedef T AType;
+  Dims D;
+  int M, N, kseg, lda, ldb;
+  const T* z; const T* d_yhat; const T* W_dec; const float* G; const float* norms; T* dW_dec;
+  struct GInfo { int p, l, lp; };
+  struct Epi {};
+  __device__ GInfo ginfo(int order) const {
+    int l = 0, r = order;
+    while (r >= D.L - l) { r -= D.L - l; ++l; }
+    return {order, l, l + r};
+  }
+  __device__ int nseg(const GInfo&) const { return 1; }
+  __device__ const T* a_seg(const GInfo& g, int) const { return z + (size_t)g.l * D.B * D.F; }
+  __device__ const T* b_seg(const GInfo& g, int) const { return d_yhat + (size_t)g.lp * D.B * D.d; }
+  __device__ void epi_begin(Epi&) const {}
+  __device__ void epi4(Epi&, const GInfo& g, int row, int col, float4 v) const {
+    const size_t nf = (size_t)g.l * D.F + row;
+    const float coef = G[nf] / fmaxf(norms[nf], 1e-30f);
+    const size_t o = ((size_t)g.p * D.F + row) * D.d + col;
+    const float4 w = Elem<T>::load4(W_dec + o);
+    Elem<T>::store4(dW_dec + o, make_float4(v.x + coef * w.x, v.y + coef * w.y, v.z + coef * w.z, v.w + coef * w.w));
+  }
+  __device__ void epi_end(Epi&, const GInfo&) const {}
+};
+
+// ---------------------------------------------------------------------------
+// dW_enc[l] = x[l]^T dpre[l]
+// ---------------------------------------------------------------------------
+template <typename T, typename TA = T>
+struct DWencPolicy {
+  static constexpr bool A_KC = false, B_KC = false;
+  typedef TA AType;
+  Dims D;
+  int M, N, kseg, lda, ldb;
+  const TA* x; const T* dpre; T* dW_enc;
+  struct GInfo { int l; };
+  struct Epi {};
+  __device__ GInfo ginfo(int order) const { return {order}; }
+  __device__ int nseg(const GInfo&) const { return 1; }
+  __device__ const TA* a_seg(const GInfo& g, int) const { return x + (size_t)g.l * D.B * D.d; }
+  __device__ const T* b_seg(const GInfo& g, int) const { return dpre + (size_t)g.l * D.B * D.F; }
+  __device__ void epi_begin(Epi&) const {}
+  __device__ void epi4(Epi&, const GInfo& g, int row, int col, float4 v) const {
+    Elem<T>::store4(dW_enc + ((size_t)g.l * D.d + row) * D.F + col, v);
+  }
+  __device__ void epi_end(Epi&, const GInfo&) const {}
+};
+
+}  // namespace clt

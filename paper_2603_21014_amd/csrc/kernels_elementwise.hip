@@ -1,0 +1,334 @@
+// HBM-bound kernels of the CLT train step: decoder norms, loss reductions with
+// their fused gradient by-products, the threshold (straight-through) column
+// reductions and Adam.  Reductions are two-stage with a fixed summation order
+// (per-block partials, then one pass over the partials), so results are
+// bitwise reproducible run to run.
+#include "common.h"
+
+namespace clt {
+namespace {
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+  return v;
+}
+__device__ __forceinline__ double wave_sum(double v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+  return v;
+}
+// sum over a 256-lane block; result valid in thread 0
+__device__ __forceinline__ double block_sum_256(double v) {
+  __shared__ double sh[4];
+  v = wave_sum(v);
+  if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = v;
+  __syncthreads();
+  return sh[0] + sh[1] + sh[2] + sh[3];
+}
+
+__global__ void zero_i32_kernel(int32_t* p, int n) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = 0;
+}
+
+// ---- decoder norms (App. B): one wavefront per (source layer, feature) -----
+// The L-l blocks that leave source l are contiguous in the source-major packing,
+// so feature f's rows are L-l runs of d contiguous elements.
+template <typename T>
+__global__ __launch_bounds__(256) void decoder_norms_kernel(Dims D, const T* __restrict__ W_dec,
+                                                            float* __restrict__ norms) {
+  const int lane = threadIdx.x & 63;
+  const long row = (long)blockIdx.x * 4 + (threadIdx.x >> 6);   // l * F + f
+  if (row >= (long)D.L * D.F) return;
+  const int l = (int)(row / D.F), f = (int)(row - (long)l * D.F);
+  const T* base = W_dec + ((size_t)packed_index(l, l, D.L) * D.F + f) * D.d;
+  float acc = 0.f;
+  for (int s = 0; s < D.L - l; ++s) {
+    const T* r = base + (size_t)s * D.F * D.d;
+    for (int j = lane * 4; j < D.d; j += 256) {
+      const float4 v = Elem<T>::load4(r + j);
+      acc += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+    }
+  }
+  acc = wave_sum(acc);
+  if (lane == 0) norms[row] = sqrtf(acc);
+}
+
+// ---- reconstruction loss: r = y_hat - y; partial sum r^2; d_yhat = 2 r / B;
+// column partial sums of d_yhat (for db_dec).  grid = (row blocks, L), each
+// thread owns 4 consecutive columns and walks the block's rows.
+template <typename T, bool INT8>
+__global__ __launch_bounds__(256) void loss_rec_kernel(Dims D, const float* __restrict__ y_hat, const void* yv,
+                                                       const float* __restrict__ y_scale, T* __restrict__ d_yhat,
+                                                       double* __restrict__ loss_part, float* __restrict__ col_part) {
+  const int rb = blockIdx.x, l = blockIdx.y;
+  const int r0 = rb * LOSS_ROWS_PER_BLOCK, r1 = min(D.B, r0 + LOSS_ROWS_PER_BLOCK);
+  const float two_over_b = 2.0f / (float)D.B;
+  double sq = 0.0;
+  for (int c = threadIdx.x * 4; c < D.d; c += 1024) {
+    float4 cs = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int r = r0; r < r1; ++r) {
+      const size_t o = ((size_t)l * D.B + r) * D.d + c;
+      const float4 yh = *reinterpret_cast<const float4*>(y_hat + o);
+      float4 y;
+      if (INT8) {
+        const uint32_t q = *reinterpret_cast<const uint32_t*>(reinterpret_cast<const int8_t*>(yv) + o);
+        const float s = y_scale[(size_t)l * D.B + r];
+        y = make_float4(s * (float)(int8_t)q, s * (float)(int8_t)(q >> 8), s * (float)(int8_t)(q >> 16),
+                        s * (float)(int8_t)(q >> 24));
+      } else {
+        y = Elem<T>::load4(reinterpret_cast<const T*>(yv) + o);
+      }
+      const float4 rr = make_float4(yh.x - y.x, yh.y - y.y, yh.z - y.z, yh.w - y.w);
+      sq += (double)(rr.x * rr.x + rr.y * rr.y) + (double)(rr.z * rr.z + rr.w * rr.w);
+      const float4 g = make_float4(two_over_b * rr.x, two_over_b * rr.y, two_over_b * rr.z, two_over_b * rr.w);
+      Elem<T>::store4(d_yhat + o, g);
+      cs.x += g.x; cs.y += g.y; cs.z += g.z; cs.w += g.w;
+    }
+    *reinterpret_cast<float4*>(col_part + ((size_t)rb * D.L + l) * D.d + c) = cs;
+  }
+  const double tot = block_sum_256(sq);
+  if (threadIdx.x == 0) loss_part[(size_t)l * gridDim.x + rb] = tot;
+}
+
+// ---- sparsity loss: partial sum tanh(C z n); column partials of C z sech^2(C z n)
+template <typename T>
+__global__ __launch_bounds__(256) void loss_sparsity_kernel(Dims D, const T* __restrict__ z,
+                                                            const float* __restrict__ norms, float C,
+                                                            double* __restrict__ loss_part,
+                                                            float* __restrict__ col_part) {
+  const int rb = blockIdx.x, l = blockIdx.y;
+  const int r0 = rb * LOSS_ROWS_PER_BLOCK, r1 = min(D.B, r0 + LOSS_ROWS_PER_BLOCK);
+  double sp = 0.0;
+  for (int c = threadIdx.x * 4; c < D.F; c += 1024) {
+    const float4 n4 = *reinterpret_cast<const float4*>(norms + (size_t)l * D.F + c);
+    const float cn[4] = {C * n4.x, C * n4.y, C * n4.z, C * n4.w};
+    float cs[4] = {0.f, 0.f, 0.f, 0.f};
+    float ts = 0.f;
+    for (int r = r0; r < r1; ++r) {
+      const float4 z4 = Elem<T>::load4(z + ((size_t)l * D.B + r) * D.F + c);
+      const float zz[4] = {z4.x, z4.y, z4.z, z4.w};
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        if (zz[i] != 0.f) {
+          const float t = tanhf(cn[i] * zz[i]);
+          ts += t;
+          cs[i] += C * zz[i] * (1.0f - t * t);
+        }
+      }
+    }
+    sp += (double)ts;
+    *reinterpret_cast<float4*>(col_part + ((size_t)rb * D.L + l) * D.F + c) = make_float4(cs[0], cs[1], cs[2], cs[3]);
+  }
+  const double tot = block_sum_256(sp);
+  if (threadIdx.x == 0) loss_part[(size_t)l * gridDim.x + rb] = tot;
+}
+
+__global__ __launch_bounds__(256) void loss_final_kernel(const double* part_rec, int n_rec, const double* part_sp,
+                                                         int n_sp, float inv_B, float lambda0, float* loss_dev) {
+  double a = 0.0, b = 0.0;
+  for (int i = threadIdx.x; i < n_rec; i += 256) a += part_rec[i];
+  for (int i = threadIdx.x; i < n_sp; i += 256) b += part_sp[i];
+  a = block_sum_256(a);
+  __syncthreads();
+  b = block_sum_256(b);
+  if (threadIdx.x == 0) {
+    const double rec = a * (double)inv_B, sp = b * (double)inv_B * (double)lambda0;
+    loss_dev[0] = (float)(rec + sp);
+    loss_dev[1] = (float)rec;
+    loss_dev[2] = (float)sp;
+  }
+}
+
+__global__ __launch_bounds__(256) void col_reduce_kernel(const float* __restrict__ part, int nparts, int ncols,
+                                                         float alpha, const float* __restrict__ theta, float inv_eps,
+                                                         float* __restrict__ out) {
+  const int c = blockIdx.x * 256 + threadIdx.x;
+  if (c >= ncols) return;
+  float s = 0.f;
+  for (int r = 0; r < nparts; ++r) s += part[(size_t)r * ncols + c];
+  s *= alpha;
+  if (theta) s *= -(theta[c] * inv_eps);
+  out[c] = s;
+}
+
+// ---- straight-through reductions over the buffer that holds dz where a feature
+// is active or in the threshold window: column partials of dz over the window
+// (-> dtheta) and over the active set (-> db_enc); entries that are in the
+// window but inactive are zeroed so the buffer becomes dpre.  With a row scale
+// (int8 inputs) dpre rows are additionally multiplied by it, because the
+// encoder-weight gradient contracts them with the integer codes.
+template <typename T>
+__global__ __launch_bounds__(256) void ste_reduce_kernel(Dims D, T* __restrict__ dpre,
+                                                         const uint8_t* __restrict__ cls,
+                                                         const float* __restrict__ row_scale,
+                                                         float* __restrict__ part_theta,
+                                                         float* __restrict__ part_benc) {
+  const int rb = blockIdx.x, l = blockIdx.y;
+  const int r0 = rb * LOSS_ROWS_PER_BLOCK, r1 = min(D.B, r0 + LOSS_ROWS_PER_BLOCK);
+  for (int c = threadIdx.x * 4; c < D.F; c += 1024) {
+    float st[4] = {0.f, 0.f, 0.f, 0.f}, sb[4] = {0.f, 0.f, 0.f, 0.f};
+    for (int r = r0; r < r1; ++r) {
+      const size_t o = ((size_t)l * D.B + r) * D.F + c;
+      const uint32_t c4 = *reinterpret_cast<const uint32_t*>(cls + o);
+      if (!c4) continue;
+      const float4 g4 = Elem<T>::load4(dpre + o);
+      float g[4] = {g4.x, g4.y, g4.z, g4.w};
+      bool rewrite = row_scale != nullptr;
+      const float s = row_scale ? row_scale[(size_t)l * D.B + r] : 1.0f;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const uint32_t ci = (c4 >> (8 * i)) & 3u;
+        if (ci & CLS_WINDOW) st[i] += g[i];
+        if (ci & CLS_ACTIVE) {
+          sb[i] += g[i];
+          g[i] *= s;
+        } else if (ci) {
+          g[i] = 0.f;
+          rewrite = true;
+        }
+      }
+      if (rewrite) Elem<T>::store4(dpre + o, make_float4(g[0], g[1], g[2], g[3]));
+    }
+    const size_t po = ((size_t)rb * D.L + l) * D.F + c;
+    *reinterpret_cast<float4*>(part_theta + po) = make_float4(st[0], st[1], st[2], st[3]);
+    *reinterpret_cast<float4*>(part_benc + po) = make_float4(sb[0], sb[1], sb[2], sb[3]);
+  }
+}
+
+// ---- Adam (App. C Table 1), 4 elements per lane --------------------------------
+template <typename T, bool MASTER>
+__global__ __launch_bounds__(256) void adam_kernel(size_t n4, T* __restrict__ p, const T* __restrict__ g,
+                                                   float* __restrict__ m, float* __restrict__ v,
+                                                   float* __restrict__ master, AdamScalars a) {
+  const float inv_bc1 = 1.0f / a.bc1, inv_bc2 = 1.0f / a.bc2;
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n4; i += (size_t)gridDim.x * 256) {
+    const size_t o = i * 4;
+    const float4 g4 = Elem<T>::load4(g + o);
+    float4 m4 = *reinterpret_cast<const float4*>(m + o);
+    float4 v4 = *reinterpret_cast<const float4*>(v + o);
+    float4 p4 = MASTER ? *reinterpret_cast<const float4*>(master + o) : Elem<T>::load4(p + o);
+    const float gg[4] = {g4.x, g4.y, g4.z, g4.w};
+    float mm[4] = {m4.x, m4.y, m4.z, m4.w}, vv[4] = {v4.x, v4.y, v4.z, v4.w}, pp[4] = {p4.x, p4.y, p4.z, p4.w};
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      mm[k] = a.beta1 * mm[k] + (1.0f - a.beta1) * gg[k];
+      vv[k] = a.beta2 * vv[k] + (1.0f - a.beta2) * gg[k] * gg[k];
+      pp[k] -= a.lr * (mm[k] * inv_bc1) / (sqrtf(vv[k] * inv_bc2) + a.eps);
+    }
+    *reinterpret_cast<float4*>(m + o) = make_float4(mm[0], mm[1], mm[2], mm[3]);
+    *reinterpret_cast<float4*>(v + o) = make_float4(vv[0], vv[1], vv[2], vv[3]);
+    const float4 pn = make_float4(pp[0], pp[1], pp[2], pp[3]);
+    if (MASTER) *reinterpret_cast<float4*>(master + o) = pn;
+    Elem<T>::store4(p + o, pn);
+  }
+}
+
+inline int grid_for(size_t n, int per_block, int cap) {
+  size_t b = (n + per_block - 1) / per_block;
+  if (b < 1) b = 1;
+  if (b > (size_t)cap) b = cap;
+  return (int)b;
+}
+
+}  // namespace
+
+hipError_t launch_zero_i32(hipStream_t s, int32_t* p, int n) {
+  hipLaunchKernelGGL(zero_i32_kernel, dim3((n + 255) / 256), dim3(256), 0, s, p, n);
+  return hipGetLastError();
+}
+
+hipError_t launch_decoder_norms(hipStream_t s, bool bf16, Dims D, const void* W_dec, float* norms) {
+  const long rows = (long)D.L * D.F;
+  const dim3 grid((unsigned)((rows + 3) / 4));
+  if (bf16)
+    hipLaunchKernelGGL((decoder_norms_kernel<bf16_t>), grid, dim3(256), 0, s, D, (const bf16_t*)W_dec, norms);
+  else
+    hipLaunchKernelGGL((decoder_norms_kernel<float>), grid, dim3(256), 0, s, D, (const float*)W_dec, norms);
+  return hipGetLastError();
+}
+
+hipError_t launch_loss_rec(hipStream_t s, bool bf16, bool int8_y, Dims D, const float* y_hat, const void* y,
+                           const float* y_scale, void* d_yhat, double* loss_part, float* col_part) {
+  const dim3 grid(row_blocks(D.B), D.L);
+  if (!bf16)
+    hipLaunchKernelGGL((loss_rec_kernel<float, false>), grid, dim3(256), 0, s, D, y_hat, y, y_scale, (float*)d_yhat,
+                       loss_part, col_part);
+  else if (int8_y)
+    hipLaunchKernelGGL((loss_rec_kernel<bf16_t, true>), grid, dim3(256), 0, s, D, y_hat, y, y_scale,
+                       (bf16_t*)d_yhat, loss_part, col_part);
+  else
+    hipLaunchKernelGGL((loss_rec_kernel<bf16_t, false>), grid, dim3(256), 0, s, D, y_hat, y, y_scale,
+                       (bf16_t*)d_yhat, loss_part, col_part);
+  return hipGetLastError();
+}
+
+hipError_t launch_loss_sparsity(hipStream_t s, bool bf16, Dims D, const void* z, const float* norms, float C,
+                                double* loss_part, float* col_part) {
+  const dim3 grid(row_blocks(D.B), D.L);
+  if (bf16)
+    hipLaunchKernelGGL((loss_sparsity_kernel<bf16_t>), grid, dim3(256), 0, s, D, (const bf16_t*)z, norms, C,
+                       loss_part, col_part);
+  else
+    hipLaunchKernelGGL((loss_sparsity_kernel<float>), grid, dim3(256), 0, s, D, (const float*)z, norms, C, loss_part,
+                       col_part);
+  return hipGetLastError();
+}
+
+hipError_t launch_loss_final(hipStream_t s, const double* part_rec, int n_rec, const double* part_sp, int n_sp,
+                             float inv_B, float lambda0, float* loss_dev) {
+  hipLaunchKernelGGL(loss_final_kernel, dim3(1), dim3(256), 0, s, part_rec, n_rec, part_sp, n_sp, inv_B, lambda0,
+                     loss_dev);
+  return hipGetLastError();
+}
+
+hipError_t launch_col_reduce(hipStream_t s, const float* part, int nparts, int ncols, float alpha,
+                             const float* theta_or_null, float inv_eps, float* out) {
+  hipLaunchKernelGGL(col_reduce_kernel, dim3((ncols + 255) / 256), dim3(256), 0, s, part, nparts, ncols, alpha,
+                     theta_or_null, inv_eps, out);
+  return hipGetLastError();
+}
+
+hipError_t launch_ste_reduce(hipStream_t s, bool bf16, Dims D, void* dpre, const uint8_t* cls,
+                             const float* row_scale_or_null, float* part_theta, float* part_benc) {
+  const dim3 grid(row_blocks(D.B), D.L);
+  if (bf16)
+    hipLaunchKernelGGL((ste_reduce_kernel<bf16_t>), grid, dim3(256), 0, s, D, (bf16_t*)dpre, cls, row_scale_or_null,
+                       part_theta, part_benc);
+  else
+    hipLaunchKernelGGL((ste_reduce_kernel<float>), grid, dim3(256), 0, s, D, (float*)dpre, cls, row_scale_or_null,
+                       part_theta, part_benc);
+  return hipGetLastError();
+}
+
+hipError_t launch_adam_matrix(hipStream_t s, bool bf16, size_t n, void* p, const void* g, float* m, float* v,
+                              float* master, AdamScalars a) {
+  const size_t n4 = n / 4;   // matrices have a multiple of 64 elements (d, F multiples of 8)
+  const dim3 grid(grid_for(n4, 256, 256 * 32));
+  if (bf16) {
+    if (master)
+      hipLaunchKernelGGL((adam_kernel<bf16_t, true>), grid, dim3(256), 0, s, n4, (bf16_t*)p, (const bf16_t*)g, m, v,
+                         master, a);
+    else
+      hipLaunchKernelGGL((adam_kernel<bf16_t, false>), grid, dim3(256), 0, s, n4, (bf16_t*)p, (const bf16_t*)g, m, v,
+                         master, a);
+  } else {
+    if (master)
+      hipLaunchKernelGGL((adam_kernel<float, true>), grid, dim3(256), 0, s, n4, (float*)p, (const float*)g, m, v,
+                         master, a);
+    else
+      hipLaunchKernelGGL((adam_kernel<float, false>), grid, dim3(256), 0, s, n4, (float*)p, (const float*)g, m, v,
+                         master, a);
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_adam_vector(hipStream_t s, size_t n, float* p, const float* g, float* m, float* v, AdamScalars a) {
+  const size_t n4 = n / 4;   // vectors have L*F or L*d elements, multiples of 8
+  hipLaunchKernelGGL((adam_kernel<float, false>), dim3(grid_for(n4, 256, 256 * 32)), dim3(256), 0, s, n4, p, g, m, v,
+                     (float*)nullptr, a);
+  return hipGetLastError();
+}
+
+}  // namespace clt

@@ -1,0 +1,146 @@
+"""GPU parity: the HIP library, called through its C ABI, against the CPU oracle
+on the same seeded inputs.  Tolerances: 1e-4 relative (per tensor, per decoder
+block) for the fp32 path, 2e-2 for the bf16 MFMA path; masks bit-exact except
+for pre-activations within 1e-3 of a decision boundary."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import clt_oracle as O
+from workloads import clt_synth as S
+
+from clt_testlib import GpuRun, OracleRun, compare_step, rel_l2, run_both, to_np
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-4, "bf16": 2e-2}
+
+
+def show(name, errs):
+    worst = sorted(errs.items(), key=lambda kv: -kv[1])[:4]
+    print(f"[{name}] worst: " + ", ".join(f"{k}={e:.2e}" for k, e in worst), flush=True)
+
+
+def test_tiny_config_fp32_full_step():
+    """BASELINE config 1: L=4, d=64, F=256, B=128, fp32, one fwd+bwd+Adam step."""
+    w = S.WORKLOADS["tiny"]
+    g, o = run_both(w)
+    assert 0.2 < g.active.mean() < 0.8
+    assert g.window.sum() > 100
+    show("tiny f32", compare_step(w, g, o, TOL["f32"]))
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("L,d,F,B", [
+    (3, 40, 72, 77),        # nothing is a multiple of any tile size
+    (2, 264, 520, 300),     # 256-tiles plus ragged tails in every dimension
+    (1, 64, 128, 1),        # single layer, single token
+    (5, 128, 256, 130),
+])
+def test_ragged_shapes_full_step(dtype, L, d, F, B):
+    w = S.scaled(S.WORKLOADS["tiny"], dtype=dtype, L=L, d=d, F=F, B=B, seed=7 + L + d)
+    g, o = run_both(w)
+    show(f"{dtype} L{L} d{d} F{F} B{B}", compare_step(w, g, o, TOL[dtype]))
+
+
+def test_bf16_several_tiles_and_segments():
+    """Spans 2x3 output tiles of 256x256 per group and up to 4 K segments."""
+    w = S.scaled(S.WORKLOADS["gpt2"], L=4, d=512, F=768, B=512, k_active=16)
+    g, o = run_both(w)
+    show("bf16 multi-tile", compare_step(w, g, o, TOL["bf16"]))
+
+
+def test_bf16_outlier_inputs_llama_shaped_slice():
+    """Config 3's input recipe (log-normal norms, outlier dims) at a slice of its shape."""
+    w = S.scaled(S.WORKLOADS["llama1b"], L=3, d=2048, F=512, B=256)
+    g, o = run_both(w)
+    show("bf16 llama slice", compare_step(w, g, o, TOL["bf16"]))
+
+
+def test_master_weights_bf16():
+    w = S.scaled(S.WORKLOADS["gemma2b"], L=2, d=64, F=256, B=96)
+    g, o = run_both(w)
+    show("bf16 master", compare_step(w, g, o, TOL["bf16"]))
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_infinite_threshold_gives_bias_only(dtype):
+    w = S.scaled(S.WORKLOADS["tiny"], dtype=dtype)
+    theta = torch.full((w.L, w.F), float("inf"))
+    params = S.make_params(w)
+    params["b_dec"] = torch.randn((w.L, w.d), generator=torch.Generator().manual_seed(3))
+    x, y = S.make_inputs(w)
+    g = GpuRun(w, params, x, y, theta=theta)
+    assert not g.active.any() and not g.z.any() and g.l0.sum() == 0
+    for lp in range(w.L):
+        assert (g.y_hat[lp] == params["b_dec"][lp].numpy()[None, :]).all()
+    want = np.sum((params["b_dec"].numpy()[:, None, :].astype(np.float64) - to_np(y)) ** 2) / w.B
+    assert abs(g.loss[1] - want) / want < 1e-5 and g.loss[2] == 0.0
+    assert not g.grads["W_enc"].any() and not g.grads["theta"].any()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_zero_decoder_rows_do_not_produce_nan(dtype):
+    w = S.scaled(S.WORKLOADS["tiny"], dtype=dtype, L=2, B=64)
+    params = S.make_params(w)
+    params["W_dec"][:, 5, :] = 0.0
+    x, y = S.make_inputs(w)
+    g = GpuRun(w, params, x, y)
+    o = OracleRun(w, params, x, y, gpu_active=g.active, gpu_window=g.window)
+    assert np.isfinite(g.grads["W_dec"]).all()
+    show(f"zero rows {dtype}", compare_step(w, g, o, TOL[dtype]))
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_adam_later_step_with_given_moments(dtype):
+    """Adam at t = 7 from non-zero moments: m, v and the update against the oracle."""
+    w = S.scaled(S.WORKLOADS["tiny"], dtype=dtype, L=2, B=64, master_weights=(dtype == "bf16"))
+    params = S.make_params(w)
+    gen = torch.Generator().manual_seed(11)
+    m = {k: 1e-3 * torch.randn(p.shape, generator=gen) for k, p in params.items()}
+    v = {k: 1e-6 * torch.rand(p.shape, generator=gen) for k, p in params.items()}
+    x, y = S.make_inputs(w)
+    g = GpuRun(w, params, x, y, t=7, m=m, v=v)
+    o = OracleRun(w, params, x, y, t=7, m=m, v=v, gpu_active=g.active, gpu_window=g.window)
+    tol = TOL[dtype]
+    for k in O.PARAM_NAMES:
+        assert rel_l2(g.new_m[k], o.new_m[k]) <= tol, k
+        assert rel_l2(g.new_v[k], o.new_v[k]) <= tol, k
+        got = g.new_master[k] if (w.master_weights and k in ("W_enc", "W_dec")) else g.new_params[k]
+        assert rel_l2(got - o.params[k], o.new_params[k] - o.params[k]) <= tol, k
+
+
+def test_rerun_is_bitwise_deterministic():
+    w = S.scaled(S.WORKLOADS["gpt2"], L=3, d=256, F=512, B=300)
+    params = S.make_params(w)
+    x, y = S.make_inputs(w)
+    a = GpuRun(w, params, x, y)
+    b = GpuRun(w, params, x, y)
+    assert a.loss == b.loss
+    for k in O.PARAM_NAMES:
+        assert (a.grads[k] == b.grads[k]).all(), k
+        assert (a.new_params[k] == b.new_params[k]).all(), k
+
+
+def test_call_order_and_argument_errors():
+    from paper_2603_21014_amd import binding as K
+    step = K.CLTStep(2, 64, 128, 32, dtype="f32")
+    w = S.scaled(S.WORKLOADS["tiny"], L=2, d=64, F=128, B=32)
+    params = {k: p.cuda() for k, p in S.make_params(w).items()}
+    x, y = (t.cuda() for t in S.make_inputs(w))
+    with pytest.raises(K.CLTError) as e:
+        step.loss(y, 1.0)
+    assert e.value.code == -6
+    step.forward(x, params)
+    with pytest.raises(K.CLTError) as e:
+        step.backward(x, params)
+    assert e.value.code == -6
+    with pytest.raises(ValueError):
+        step.forward(x[:, :16], params)                 # wrong shape is caught before the ABI
+    with pytest.raises(K.CLTError) as e:                # misaligned pointer is caught by the ABI
+        K._check(K._lib.clt_forward(step.H.h, None, x.data_ptr() + 4, None, params["W_enc"].data_ptr(),
+                                    params["b_enc"].data_ptr(), params["theta"].data_ptr(),
+                                    params["W_dec"].data_ptr(), params["b_dec"].data_ptr(), step.z.data_ptr(),
+                                    None, step.act_class.data_ptr(), step.y_hat.data_ptr(), None), step.H.h)
+    assert e.value.code == -3
+    torch.cuda.synchronize()
