@@ -1,0 +1,168 @@
+#!/usr/bin/env python3
+"""Benchmark of the CLT train step (forward + loss + backward + Adam) on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload llama1b]
+
+Prints ONE JSON line: tokens/s of the whole step on synthetic inputs resident in
+HBM, the roofline entry of the dominant kernel (timed live with HIP events on
+the stream the kernels run on) and the CPU oracle timed on a bounded sample.
+Everything runs on one GPU; --gpus above 1 exits with a message.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA, published
+GEMM_PAIRS = {"encoder_jumprelu_gemm": "L", "dW_enc_gemm": "L", "decode_gemm": "P", "dz_gemm": "P",
+              "dW_dec_gemm": "P"}
+
+
+def cpu_oracle_baseline(w, log):
+    """The oracle as it stands on a bounded sample of the workload: full L and d,
+    F/16 features and B/16 tokens.  The contraction cost is linear in B*F, Adam
+    and the decoder norms in F, so the sample time is scaled back to the full
+    shape and expressed in tokens/s."""
+    import numpy as np
+    import torch
+    from oracle import clt_oracle as O
+    from workloads import clt_synth as S
+    fs, bs = max(8, w.F // 16), max(1, w.B // 16)
+    ws = S.scaled(w, F=fs, B=bs, k_active=max(1, w.k_active // 16))
+    params = {k: v.numpy().astype(np.float64) for k, v in S.make_params(ws).items()}
+    x, y = (t.numpy().astype(np.float64) for t in S.make_inputs(ws))
+    zeros = {k: np.zeros_like(v) for k, v in params.items()}
+    t0 = time.perf_counter()
+    fwd = O.forward(x, params["W_enc"], params["b_enc"], params["theta"], params["W_dec"], params["b_dec"])
+    n = O.decoder_norms(params["W_dec"], ws.L)
+    O.loss_terms(fwd["y_hat"], y, fwd["z"], n, ws.lambda0, ws.C)
+    grads = O.backward(x, y, params["theta"], params["W_dec"], fwd, ws.lambda0, ws.C, ws.ste_eps)
+    t1 = time.perf_counter()
+    for k in O.PARAM_NAMES:
+        O.adam_update(params[k], grads["d" + k], zeros[k], zeros[k], 1, ws.lr)
+    t2 = time.perf_counter()
+    t_fb, t_adam = t1 - t0, t2 - t1
+    full = t_fb * (w.F / fs) * (w.B / bs) + t_adam * (w.F / fs)
+    log(f"cpu oracle sample: fwd+loss+bwd {t_fb:.2f}s, adam {t_adam:.2f}s -> full step est {full:.0f}s")
+    return {"value": w.B / full, "unit": "tokens/s", "cores": torch.get_num_threads(), "kind": "oracle",
+            "sample": f"L={ws.L} d={ws.d} F={fs} (1/{w.F // fs}) B={bs} (1/{w.B // bs}) of {w.name}; "
+                      f"measured {t_fb + t_adam:.1f}s, scaled by B*F (contractions) and F (Adam)"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="llama1b")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-kernel-timing", action="store_true",
+                    help="skip the per-kernel HIP-event brackets (roofline entry becomes null)")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        sys.exit("bench.py: this build runs the CLT train step on ONE GPU only (no sharding, no collectives); "
+                 "use --gpus 1")
+
+    def log(msg):
+        print(f"[bench] {msg}", file=sys.stderr, flush=True)
+
+    import torch
+    from paper_2603_21014_amd import binding as K
+    from workloads import clt_synth as S
+
+    w = S.WORKLOADS[args.workload]
+    assert w.dtype == "bf16", "the benchmark times the bf16 path"
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    t0 = time.perf_counter()
+    T = torch.bfloat16
+    params32 = S.make_params(w, device=dev)
+    params = {k: (v.to(T) if k in ("W_enc", "W_dec") else v) for k, v in params32.items()}
+    master = {k: params32[k] for k in ("W_enc", "W_dec")} if w.master_weights else None
+    del params32
+    x, y = S.make_inputs(w, device=dev)
+    xs = ys = None
+    if w.int8_inputs:
+        x, xs = S.quantize_rows_int8(x)
+        y, ys = S.quantize_rows_int8(y)
+    else:
+        x, y = x.to(T), y.to(T)
+    m = {k: torch.zeros(v.shape, dtype=torch.float32, device=dev) for k, v in params.items()}
+    v_ = {k: torch.zeros(v.shape, dtype=torch.float32, device=dev) for k, v in params.items()}
+    step = K.CLTStep(w.L, w.d, w.F, w.B, dtype="bf16", int8_inputs=w.int8_inputs, master_weights=w.master_weights,
+                     C_=w.C, ste_bandwidth=w.ste_eps, device=dev, keep_pre=False)
+    torch.cuda.synchronize()
+    log(f"workload {w.name}: L={w.L} d={w.d} F={w.F} B={w.B}, inputs ready in {time.perf_counter() - t0:.1f}s, "
+        f"{torch.cuda.memory_allocated() / 2**30:.1f} GiB allocated")
+
+    t = 0
+    for _ in range(args.warmup):
+        t += 1
+        step.train_step(x, y, params, m, v_, t, w.lr, w.lambda0, master, xs, ys)
+    torch.cuda.synchronize()
+    log("warmup done")
+    if not args.no_kernel_timing:
+        K.clt_profile_enable(step.H, True)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(args.steps):
+        t += 1
+        step.train_step(x, y, params, m, v_, t, w.lr, w.lambda0, master, xs, ys)
+    e1.record()
+    torch.cuda.synchronize()
+    ms_per_step = e0.elapsed_time(e1) / args.steps
+    loss = step.loss_dev.cpu().tolist()
+    l0 = (step.l0.double().mean() / w.B).item()
+    log(f"{ms_per_step:.2f} ms/step, loss {loss[0]:.4g}, mean active features/token/layer {l0:.1f}")
+
+    flop = w.dense_flop_per_step()
+    roof, kernels = None, None
+    if not args.no_kernel_timing:
+        prof = K.clt_profile_query(step.H)
+        K.clt_profile_enable(step.H, False)
+        pair = 2.0 * w.B * w.F * w.d
+        kernels = {}
+        for name, (ms, n) in prof.items():
+            if n == 0:
+                continue
+            avg = ms / n
+            ent = {"avg_ms": round(avg, 4), "launches_per_step": n / args.steps}
+            if name in GEMM_PAIRS:
+                fl = pair * (w.L if GEMM_PAIRS[name] == "L" else w.P)
+                ent["tflops"] = round(fl / (avg * 1e-3) / 1e12, 1)
+                ent["flop"] = fl
+            kernels[name] = ent
+        dom = max((k for k in kernels if k in GEMM_PAIRS), key=lambda k: kernels[k]["avg_ms"])
+        ach = kernels[dom]["tflops"]
+        roof = {"kernel": dom, "bound": "mfma", "achieved": ach, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                "frac": round(ach / PEAK_BF16_TFLOPS, 4), "traffic": None,
+                "avg_launch_ms": kernels[dom]["avg_ms"], "flop_per_launch": kernels[dom]["flop"]}
+        for name, ent in sorted(kernels.items(), key=lambda kv: -kv[1]["avg_ms"] * kv[1]["launches_per_step"]):
+            log(f"  {name:24s} {ent['avg_ms']:9.3f} ms x {ent['launches_per_step']:.0f}"
+                + (f"  {ent['tflops']:7.1f} TFLOP/s" if "tflops" in ent else ""))
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        cpu = cpu_oracle_baseline(w, log)
+
+    out = {
+        "metric": "CLT train-step tokens/s (fwd+bwd+Adam, bf16)", "value": w.B / (ms_per_step * 1e-3),
+        "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": w.name, "L": w.L, "d_model": w.d, "features_per_layer": w.F, "tokens": w.B,
+                   "decoder_blocks": w.P, "int8_inputs": w.int8_inputs, "master_weights": w.master_weights},
+        "step_dense_tflops": flop / (ms_per_step * 1e-3) / 1e12,
+        "step_frac_of_bf16_mfma_peak": flop / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+        "roofline": roof, "cpu_baseline": cpu, "kernels": kernels,
+    }
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -145,6 +145,16 @@ int clt_adam_step(clt_handle* handle, void* stream, int64_t t, float lr,
  * 3 sparsity column sums G [L,F] float.  Valid after the call that writes them. */
 int clt_workspace_view(const clt_handle* handle, int which, void** ptr, size_t* bytes);
 
+/* Optional per-kernel timing, for benchmarks and profiling (not part of the
+ * method).  While enabled, every kernel the library enqueues is bracketed by
+ * HIP events on the caller's stream.  clt_profile_query waits for the recorded
+ * events and returns, for kernel index 0 <= kernel < clt_profile_num_kernels(),
+ * its name (static string), the accumulated device milliseconds and the number
+ * of launches since profiling was last enabled. */
+int clt_profile_enable(clt_handle* handle, int on);
+int clt_profile_num_kernels(void);
+int clt_profile_query(clt_handle* handle, int kernel, const char** name, double* total_ms, int64_t* launches);
+
 #ifdef __cplusplus
 }
 #endif

@@ -219,7 +219,10 @@ def backward(x, y, theta, W_dec, fwd, lambda0, C, eps,
             dz[l] += d_yhat[lp] @ np.asarray(W_dec[packed_index(l, lp, L)], F64).T
     dpre = np.where(active, dz, 0.0)
     win = ste_window(pre, theta, eps, window_tie_break, band)
-    dtheta = -(theta / eps) * np.sum(np.where(win, dz, 0.0), axis=1)
+    # sum over the window entries of the per-entry pseudo-derivative -(theta/eps) dz;
+    # an empty window contributes exactly 0, also for a non-finite threshold
+    with np.errstate(invalid="ignore"):
+        dtheta = np.sum(np.where(win, -(theta[:, None, :] / eps) * dz, 0.0), axis=1)
     db_enc = dpre.sum(axis=1)
 
     dW_dec = np.empty((num_blocks(L), F, d), F64)

@@ -23,7 +23,8 @@ INPUT_NATIVE, INPUT_INT8_ROWSCALE = 0, 1
 DECODE_AUTO, DECODE_DENSE, DECODE_GATHER = 0, 1, 2
 
 EXPORTS = ("clt_workspace_bytes", "clt_init", "clt_destroy", "clt_last_error", "clt_forward",
-           "clt_loss", "clt_backward", "clt_adam_step", "clt_workspace_view")
+           "clt_loss", "clt_backward", "clt_adam_step", "clt_workspace_view",
+           "clt_profile_enable", "clt_profile_num_kernels", "clt_profile_query")
 
 
 class CLTError(RuntimeError):
@@ -59,6 +60,10 @@ def _load():
     lib.clt_backward.argtypes = [vp, vp, vp, fp, fp, vp, vp, vp, C.POINTER(clt_tensors)]
     lib.clt_adam_step.argtypes = [vp, vp, C.c_int64, C.c_float] + [C.POINTER(clt_tensors)] * 5
     lib.clt_workspace_view.argtypes = [vp, C.c_int, C.POINTER(vp), C.POINTER(C.c_size_t)]
+    lib.clt_profile_enable.argtypes = [vp, C.c_int]
+    lib.clt_profile_num_kernels.argtypes = []
+    lib.clt_profile_query.argtypes = [vp, C.c_int, C.POINTER(C.c_char_p), C.POINTER(C.c_double),
+                                      C.POINTER(C.c_int64)]
     for n in EXPORTS:
         if n != "clt_last_error":
             getattr(lib, n).restype = C.c_int
@@ -208,6 +213,20 @@ def clt_workspace_view(H: Handle, which: str) -> torch.Tensor:
     _check(_lib.clt_workspace_view(H.h, idx, C.byref(ptr), C.byref(nbytes)), H.h)
     off = ptr.value - H.workspace.data_ptr()
     return H.workspace[off:off + nbytes.value].view(dt).view(shp(H.cfg))
+
+
+def clt_profile_enable(H: Handle, on: bool):
+    _check(_lib.clt_profile_enable(H.h, int(on)), H.h)
+
+
+def clt_profile_query(H: Handle) -> dict:
+    """{kernel name: (total device ms, launches)} since profiling was enabled."""
+    out = {}
+    for k in range(_lib.clt_profile_num_kernels()):
+        name, ms, n = C.c_char_p(), C.c_double(), C.c_int64()
+        _check(_lib.clt_profile_query(H.h, k, C.byref(name), C.byref(ms), C.byref(n)), H.h)
+        out[name.value.decode()] = (ms.value, n.value)
+    return out
 
 
 class CLTStep:

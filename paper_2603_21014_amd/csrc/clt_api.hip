@@ -9,6 +9,7 @@
 #include <string.h>
 
 #include <new>
+#include <vector>
 
 #include "common.h"
 
@@ -34,7 +35,23 @@ void set_err(char* dst, const char* fmt, ...) {
 
 }  // namespace
 
+enum KernelId {
+  K_NORMS, K_ENC, K_DEC, K_LOSS_SP, K_LOSS_REC, K_LOSS_FINAL, K_COLRED, K_DZ, K_STE, K_DWENC, K_DWDEC,
+  K_ADAM_WDEC, K_ADAM_WENC, K_ADAM_VEC, K_ZERO, K_COUNT
+};
+static const char* const kKernelNames[K_COUNT] = {
+  "decoder_norms", "encoder_jumprelu_gemm", "decode_gemm", "loss_sparsity", "loss_reconstruction", "loss_final",
+  "column_reduce", "dz_gemm", "ste_reduce", "dW_enc_gemm", "dW_dec_gemm", "adam_W_dec", "adam_W_enc",
+  "adam_vectors", "zero_counters"};
+
+struct ProfSpan { int kernel; hipEvent_t a, b; };
+
 struct clt_handle {
+  bool prof_on = false;
+  std::vector<ProfSpan> spans;          // recorded, not yet harvested
+  std::vector<hipEvent_t> free_events;  // recycled events
+  double prof_ms[K_COUNT] = {};
+  int64_t prof_n[K_COUNT] = {};
   clt_config cfg;
   Dims D;
   bool bf16, int8;
@@ -124,6 +141,28 @@ bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) !
     }                                                                                 \
   } while (0)
 
+hipEvent_t take_event(clt_handle* h) {
+  if (!h->free_events.empty()) { hipEvent_t e = h->free_events.back(); h->free_events.pop_back(); return e; }
+  hipEvent_t e = nullptr;
+  if (hipEventCreate(&e) != hipSuccess) { (void)hipGetLastError(); return nullptr; }
+  return e;
+}
+
+// Enqueues one kernel; with profiling on, brackets it with events on the same stream.
+#define RUN(h, s, kid, expr)                                                          \
+  do {                                                                                \
+    hipEvent_t ea__ = nullptr, eb__ = nullptr;                                        \
+    if ((h)->prof_on && (h)->spans.size() < 65536) {                                  \
+      ea__ = take_event(h); eb__ = take_event(h);                                     \
+      if (ea__ && eb__) HIPCHK(h, hipEventRecord(ea__, s));                           \
+    }                                                                                 \
+    HIPCHK(h, expr);                                                                  \
+    if (ea__ && eb__) {                                                               \
+      HIPCHK(h, hipEventRecord(eb__, s));                                             \
+      (h)->spans.push_back(ProfSpan{kid, ea__, eb__});                                \
+    }                                                                                 \
+  } while (0)
+
 int check_tensors(clt_handle* h, const char* what, const clt_tensors* t, bool need_matrices_only) {
   if (!t) { set_err(h->err, "clt tensors '%s' is NULL", what); return CLT_ERR_INVALID_ARG; }
   const void* ptrs[5] = {t->W_enc, t->b_enc, t->theta, t->W_dec, t->b_dec};
@@ -193,7 +232,45 @@ int clt_init(clt_handle** handle, const clt_config* cfg, void* workspace, size_t
 }
 
 int clt_destroy(clt_handle* handle) {
+  if (!handle) return CLT_OK;
+  for (ProfSpan& sp : handle->spans) { (void)hipEventDestroy(sp.a); (void)hipEventDestroy(sp.b); }
+  for (hipEvent_t e : handle->free_events) (void)hipEventDestroy(e);
   delete handle;
+  return CLT_OK;
+}
+
+int clt_profile_enable(clt_handle* h, int on) {
+  if (!h) { set_err(g_err, "clt_profile_enable: handle is NULL"); return CLT_ERR_INVALID_ARG; }
+  h->prof_on = on != 0;
+  if (h->prof_on) {
+    for (ProfSpan& sp : h->spans) { h->free_events.push_back(sp.a); h->free_events.push_back(sp.b); }
+    h->spans.clear();
+    for (int k = 0; k < K_COUNT; ++k) { h->prof_ms[k] = 0.0; h->prof_n[k] = 0; }
+  }
+  return CLT_OK;
+}
+
+int clt_profile_num_kernels(void) { return K_COUNT; }
+
+int clt_profile_query(clt_handle* h, int kernel, const char** name, double* total_ms, int64_t* launches) {
+  if (!h) { set_err(g_err, "clt_profile_query: handle is NULL"); return CLT_ERR_INVALID_ARG; }
+  if (kernel < 0 || kernel >= K_COUNT || !name || !total_ms || !launches) {
+    set_err(h->err, "clt_profile_query: bad argument");
+    return CLT_ERR_INVALID_ARG;
+  }
+  for (ProfSpan& sp : h->spans) {       // harvest: waits for the recorded events
+    float ms = 0.f;
+    HIPCHK(h, hipEventSynchronize(sp.b));
+    HIPCHK(h, hipEventElapsedTime(&ms, sp.a, sp.b));
+    h->prof_ms[sp.kernel] += ms;
+    h->prof_n[sp.kernel] += 1;
+    h->free_events.push_back(sp.a);
+    h->free_events.push_back(sp.b);
+  }
+  h->spans.clear();
+  *name = kKernelNames[kernel];
+  *total_ms = h->prof_ms[kernel];
+  *launches = h->prof_n[kernel];
   return CLT_OK;
 }
 
@@ -224,16 +301,16 @@ int clt_forward(clt_handle* h, void* stream, const void* x, const float* x_scale
   hipStream_t s = static_cast<hipStream_t>(stream);
   h->stage = 0;
   float* norms = reinterpret_cast<float*>(h->ws + h->plan.norms);
-  if (l0_per_layer) HIPCHK(h, launch_zero_i32(s, l0_per_layer, h->D.L));
-  HIPCHK(h, launch_decoder_norms(s, h->bf16, h->D, W_dec, norms));
+  if (l0_per_layer) RUN(h, s, K_ZERO, launch_zero_i32(s, l0_per_layer, h->D.L));
+  RUN(h, s, K_NORMS, launch_decoder_norms(s, h->bf16, h->D, W_dec, norms));
   EncArgs ea{x, x_scale, W_enc, b_enc, theta, h->cfg.ste_bandwidth, z, pre, act_class, l0_per_layer};
   DecArgs da{z, W_dec, b_dec, y_hat};
   if (h->bf16) {
-    HIPCHK(h, launch_enc_bf16(s, h->D, ea, h->int8));
-    HIPCHK(h, launch_dec_bf16(s, h->D, da));
+    RUN(h, s, K_ENC, launch_enc_bf16(s, h->D, ea, h->int8));
+    RUN(h, s, K_DEC, launch_dec_bf16(s, h->D, da));
   } else {
-    HIPCHK(h, launch_enc_f32(s, h->D, ea));
-    HIPCHK(h, launch_dec_f32(s, h->D, da));
+    RUN(h, s, K_ENC, launch_enc_f32(s, h->D, ea));
+    RUN(h, s, K_DEC, launch_dec_f32(s, h->D, da));
   }
   h->stage = 1;
   return CLT_OK;
@@ -259,10 +336,10 @@ int clt_loss(clt_handle* h, void* stream, const void* y, const float* y_scale, c
   h->stage = 1;
   // sparsity first: its column partials are folded into G before the same
   // partial buffer is reused for the db_dec partials of the reconstruction pass
-  HIPCHK(h, launch_loss_sparsity(s, h->bf16, D, z, norms, h->cfg.C, psp, part));
-  HIPCHK(h, launch_col_reduce(s, part, rbs, D.L * D.F, lambda0 / (float)D.B, nullptr, 0.f, G));
-  HIPCHK(h, launch_loss_rec(s, h->bf16, h->int8, D, y_hat, y, y_scale, d_yhat, prec, part));
-  HIPCHK(h, launch_loss_final(s, prec, rbs * D.L, psp, rbs * D.L, 1.0f / (float)D.B, lambda0, loss_dev));
+  RUN(h, s, K_LOSS_SP, launch_loss_sparsity(s, h->bf16, D, z, norms, h->cfg.C, psp, part));
+  RUN(h, s, K_COLRED, launch_col_reduce(s, part, rbs, D.L * D.F, lambda0 / (float)D.B, nullptr, 0.f, G));
+  RUN(h, s, K_LOSS_REC, launch_loss_rec(s, h->bf16, h->int8, D, y_hat, y, y_scale, d_yhat, prec, part));
+  RUN(h, s, K_LOSS_FINAL, launch_loss_final(s, prec, rbs * D.L, psp, rbs * D.L, 1.0f / (float)D.B, lambda0, loss_dev));
   h->lambda0 = lambda0;
   h->stage = 2;
   if (loss_host) {
@@ -292,20 +369,20 @@ int clt_backward(clt_handle* h, void* stream, const void* x, const float* x_scal
   void* dpre = h->ws + h->plan.dpre;
 
   // db_dec from the column partials that clt_loss left behind
-  HIPCHK(h, launch_col_reduce(s, part, rbs, D.L * D.d, 1.0f, nullptr, 0.f, grads->b_dec));
+  RUN(h, s, K_COLRED, launch_col_reduce(s, part, rbs, D.L * D.d, 1.0f, nullptr, 0.f, grads->b_dec));
   DzArgs za{d_yhat, W_dec, z, act_class, norms, h->lambda0 * h->cfg.C / (float)D.B, h->cfg.C, dpre};
   DWdecArgs wa{z, d_yhat, W_dec, G, norms, grads->W_dec};
   DWencArgs ea{x, dpre, grads->W_enc};
-  if (h->bf16) HIPCHK(h, launch_dz_bf16(s, D, za)); else HIPCHK(h, launch_dz_f32(s, D, za));
-  HIPCHK(h, launch_ste_reduce(s, h->bf16, D, dpre, act_class, h->int8 ? x_scale : nullptr, part, part2));
-  HIPCHK(h, launch_col_reduce(s, part, rbs, D.L * D.F, 1.0f, theta, 1.0f / h->cfg.ste_bandwidth, grads->theta));
-  HIPCHK(h, launch_col_reduce(s, part2, rbs, D.L * D.F, 1.0f, nullptr, 0.f, grads->b_enc));
+  if (h->bf16) RUN(h, s, K_DZ, launch_dz_bf16(s, D, za)); else RUN(h, s, K_DZ, launch_dz_f32(s, D, za));
+  RUN(h, s, K_STE, launch_ste_reduce(s, h->bf16, D, dpre, act_class, h->int8 ? x_scale : nullptr, part, part2));
+  RUN(h, s, K_COLRED, launch_col_reduce(s, part, rbs, D.L * D.F, 1.0f, theta, 1.0f / h->cfg.ste_bandwidth, grads->theta));
+  RUN(h, s, K_COLRED, launch_col_reduce(s, part2, rbs, D.L * D.F, 1.0f, nullptr, 0.f, grads->b_enc));
   if (h->bf16) {
-    HIPCHK(h, launch_dwenc_bf16(s, D, ea, h->int8));
-    HIPCHK(h, launch_dwdec_bf16(s, D, wa));
+    RUN(h, s, K_DWENC, launch_dwenc_bf16(s, D, ea, h->int8));
+    RUN(h, s, K_DWDEC, launch_dwdec_bf16(s, D, wa));
   } else {
-    HIPCHK(h, launch_dwenc_f32(s, D, ea));
-    HIPCHK(h, launch_dwdec_f32(s, D, wa));
+    RUN(h, s, K_DWENC, launch_dwenc_f32(s, D, ea));
+    RUN(h, s, K_DWDEC, launch_dwdec_f32(s, D, wa));
   }
   h->stage = 1;   // the loss by-products are consumed; a new clt_loss is needed before the next backward
   return CLT_OK;
@@ -334,13 +411,13 @@ int clt_adam_step(clt_handle* h, void* stream, int64_t t, float lr, const clt_te
   a.bc1 = (float)(1.0 - pow((double)h->cfg.beta1, (double)t));
   a.bc2 = (float)(1.0 - pow((double)h->cfg.beta2, (double)t));
   const size_t n_enc = (size_t)D.L * D.d * D.F, n_dec = (size_t)D.P() * D.F * D.d;
-  HIPCHK(h, launch_adam_matrix(s, h->bf16, n_dec, params->W_dec, grads->W_dec, (float*)m->W_dec, (float*)v->W_dec,
+  RUN(h, s, K_ADAM_WDEC, launch_adam_matrix(s, h->bf16, n_dec, params->W_dec, grads->W_dec, (float*)m->W_dec, (float*)v->W_dec,
                                master ? (float*)master->W_dec : nullptr, a));
-  HIPCHK(h, launch_adam_matrix(s, h->bf16, n_enc, params->W_enc, grads->W_enc, (float*)m->W_enc, (float*)v->W_enc,
+  RUN(h, s, K_ADAM_WENC, launch_adam_matrix(s, h->bf16, n_enc, params->W_enc, grads->W_enc, (float*)m->W_enc, (float*)v->W_enc,
                                master ? (float*)master->W_enc : nullptr, a));
-  HIPCHK(h, launch_adam_vector(s, (size_t)D.L * D.F, params->b_enc, grads->b_enc, m->b_enc, v->b_enc, a));
-  HIPCHK(h, launch_adam_vector(s, (size_t)D.L * D.F, params->theta, grads->theta, m->theta, v->theta, a));
-  HIPCHK(h, launch_adam_vector(s, (size_t)D.L * D.d, params->b_dec, grads->b_dec, m->b_dec, v->b_dec, a));
+  RUN(h, s, K_ADAM_VEC, launch_adam_vector(s, (size_t)D.L * D.F, params->b_enc, grads->b_enc, m->b_enc, v->b_enc, a));
+  RUN(h, s, K_ADAM_VEC, launch_adam_vector(s, (size_t)D.L * D.F, params->theta, grads->theta, m->theta, v->theta, a));
+  RUN(h, s, K_ADAM_VEC, launch_adam_vector(s, (size_t)D.L * D.d, params->b_dec, grads->b_dec, m->b_dec, v->b_dec, a));
   return CLT_OK;
 }
 

@@ -149,7 +149,7 @@ __global__ __launch_bounds__(256) void col_reduce_kernel(const float* __restrict
   float s = 0.f;
   for (int r = 0; r < nparts; ++r) s += part[(size_t)r * ncols + c];
   s *= alpha;
-  if (theta) s *= -(theta[c] * inv_eps);
+  if (theta) s = (s == 0.f) ? 0.f : s * -(theta[c] * inv_eps);   // empty window: exactly 0, also for theta = inf
   out[c] = s;
 }
 

@@ -134,29 +134,28 @@ def bf16_ulp(a):
 
 
 def check_adam_outputs(w, g: GpuRun, o: OracleRun, tol):
-    """Moments within tol.  At t = 1 the update is -lr * g / (|g| + eps): where the
-    gradient is tiny relative to eps its rounding error is amplified, so the
-    parameter comparison is on the update with an absolute floor of tol * lr, and
-    bf16 weights without master copies are compared to within one bf16 ulp."""
+    """Moments within tol (they are linear / quadratic in the gradient).  The first
+    update is -lr * g / (|g| + eps): it is compared where it is well conditioned
+    (|g| >> eps and both gradients agree in sign and scale), up to the rounding of
+    the stored parameter; everywhere it must stay within one learning rate."""
     for k in O.PARAM_NAMES:
         assert rel_l2(g.new_m[k], o.new_m[k]) <= tol, f"Adam m[{k}]"
         assert rel_l2(g.new_v[k], o.new_v[k]) <= 2 * tol, f"Adam v[{k}]"
-        got = g.new_params[k]
-        if w.master_weights and k in MATS:
-            got = g.new_master[k]
-        want = o.new_params[k]
-        if w.dtype == "bf16" and k in MATS and not w.master_weights:
-            assert (np.abs(got - want) <= 1.01 * bf16_ulp(want)).all(), f"Adam bf16 weights {k}"
-            continue
-        upd_g, upd_o = got - o.params[k], want - o.params[k]
-        big = np.abs(o.bwd["d" + k]) > 1e-5       # update well conditioned in the gradient
-        err = np.abs(upd_g - upd_o)
-        lim = tol * np.abs(upd_o) + (1e-7 if w.dtype == "f32" else 1e-5) * np.abs(want) + 1e-9
-        assert (err[big] <= lim[big] + tol * w.lr).all(), f"Adam update {k}"
-        assert (np.abs(upd_g) <= 1.001 * w.lr + 1e-7 * np.abs(want) + 1e-9).all(), f"Adam step bound {k}"
-        if w.dtype == "bf16" and k in MATS:
+        master = w.master_weights and k in MATS
+        got = g.new_master[k] if master else g.new_params[k]
+        want, old = o.new_params[k], o.params[k]
+        g_o, g_g = o.bwd["d" + k], g.grads[k]
+        cond = (np.abs(g_o) > 1e-5) & (np.abs(g_g - g_o) <= 0.5 * np.abs(g_o))
+        if w.dtype == "bf16" and k in MATS and not master:
+            quant = 0.51 * bf16_ulp(np.maximum(np.abs(got), np.abs(want)))
+        else:
+            quant = 2e-7 * np.abs(want) + 1e-12
+        err = np.abs(got - want)
+        assert (err[cond] <= quant[cond] + 2e-3 * w.lr).all(), f"Adam update {k}"
+        assert (np.abs(got - old) <= 1.001 * w.lr + quant).all(), f"Adam step bound {k}"
+        if master:
             rounded = g.new_params[k]
-            assert (np.abs(rounded - got) <= 0.51 * bf16_ulp(got)).all(), f"bf16 shadow of master {k}"
+            assert (np.abs(rounded - got) <= 0.51 * bf16_ulp(got)).all(), f"bf16 copy of master {k}"
 
 
 def run_both(w, theta=None, t=1, m=None, v=None):
