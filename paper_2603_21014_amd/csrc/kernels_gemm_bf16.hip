@@ -27,6 +27,9 @@ namespace {
 
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float f32x16_t __attribute__((ext_vector_type(16)));
+// native 16-byte register vector (HIP's uint4 is a class type; selects on it go through memory)
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int TM = 256, TN = 256, TK = 64;
 constexpr int STAGE_ELEMS = 2 * 256 * TK;            // A tile + B tile, bf16 elements
@@ -37,24 +40,24 @@ __device__ __forceinline__ int lds_off(int row, int c) {
   return row * TK + (((c ^ row ^ (row >> 3)) & 7) << 3);
 }
 
-__device__ __forceinline__ uint4 ld16(const void* p) { return *reinterpret_cast<const uint4*>(p); }
+__device__ __forceinline__ u32x4 ld16(const void* p) { return *reinterpret_cast<const u32x4*>(p); }
 
 // int8 codes -> bf16 (exact: |q| <= 127 fits the 8-bit significand)
 __device__ __forceinline__ uint32_t i8x2_to_bf16x2(int lo, int hi) {
   return (__float_as_uint((float)lo) >> 16) | (__float_as_uint((float)hi) & 0xffff0000u);
 }
-__device__ __forceinline__ uint4 i8x8_to_bf16x8(uint2 q) {
-  uint4 r;
-  r.x = i8x2_to_bf16x2((int)(int8_t)(q.x), (int)(int8_t)(q.x >> 8));
-  r.y = i8x2_to_bf16x2((int)(int8_t)(q.x >> 16), (int)(int8_t)(q.x >> 24));
-  r.z = i8x2_to_bf16x2((int)(int8_t)(q.y), (int)(int8_t)(q.y >> 8));
-  r.w = i8x2_to_bf16x2((int)(int8_t)(q.y >> 16), (int)(int8_t)(q.y >> 24));
+__device__ __forceinline__ u32x4 i8x8_to_bf16x8(u32x2 q) {
+  u32x4 r;
+  r[0] = i8x2_to_bf16x2((int)(int8_t)(q[0]), (int)(int8_t)(q[0] >> 8));
+  r[1] = i8x2_to_bf16x2((int)(int8_t)(q[0] >> 16), (int)(int8_t)(q[0] >> 24));
+  r[2] = i8x2_to_bf16x2((int)(int8_t)(q[1]), (int)(int8_t)(q[1] >> 8));
+  r[3] = i8x2_to_bf16x2((int)(int8_t)(q[1] >> 16), (int)(int8_t)(q[1] >> 24));
   return r;
 }
-template <typename TE> __device__ __forceinline__ uint4 load8(const TE* p);
-template <> __device__ __forceinline__ uint4 load8<bf16_t>(const bf16_t* p) { return ld16(p); }
-template <> __device__ __forceinline__ uint4 load8<int8_t>(const int8_t* p) {
-  return i8x8_to_bf16x8(*reinterpret_cast<const uint2*>(p));
+template <typename TE> __device__ __forceinline__ u32x4 load8(const TE* p);
+template <> __device__ __forceinline__ u32x4 load8<bf16_t>(const bf16_t* p) { return ld16(p); }
+template <> __device__ __forceinline__ u32x4 load8<int8_t>(const int8_t* p) {
+  return i8x8_to_bf16x8(*reinterpret_cast<const u32x2*>(p));
 }
 
 // Fetch one 256(rows) x 64(k) operand tile into 8 x 16-byte registers per lane.
@@ -62,9 +65,9 @@ template <> __device__ __forceinline__ uint4 load8<int8_t>(const int8_t* p) {
 // 8(k) x 8(rows) block kb = t/32, nb = t%32.  Out-of-range chunks read as zero
 // (the address is redirected to the tensor base, which is always readable).
 template <bool KC, typename TE>
-__device__ __forceinline__ void gload(uint4 (&r)[8], const TE* base, int ld, int r0, int R, int k0, int kseg,
+__device__ __forceinline__ void gload(u32x4 (&r)[8], const TE* base, int ld, int r0, int R, int k0, int kseg,
                                       int t) {
-  const uint4 zero = make_uint4(0, 0, 0, 0);
+  const u32x4 zero = {0u, 0u, 0u, 0u};
   if (KC) {
     const int kk = k0 + ((t & 7) << 3);
     const bool kok = kk < kseg;
@@ -72,7 +75,7 @@ __device__ __forceinline__ void gload(uint4 (&r)[8], const TE* base, int ld, int
     for (int i = 0; i < 8; ++i) {
       const int row = r0 + (t >> 3) + 32 * i;
       const bool ok = kok && row < R;
-      const uint4 v = load8<TE>(base + (ok ? (size_t)row * ld + kk : (size_t)0));
+      const u32x4 v = load8<TE>(base + (ok ? (size_t)row * ld + kk : (size_t)0));
       r[i] = ok ? v : zero;
     }
   } else {
@@ -83,36 +86,32 @@ __device__ __forceinline__ void gload(uint4 (&r)[8], const TE* base, int ld, int
     for (int j = 0; j < 8; ++j) {
       const int k = kb + j;
       const bool ok = cok && k < kseg;
-      const uint4 v = load8<TE>(base + (ok ? (size_t)k * ld + col : (size_t)0));
+      const u32x4 v = load8<TE>(base + (ok ? (size_t)k * ld + col : (size_t)0));
       r[j] = ok ? v : zero;
     }
   }
 }
 
 template <bool KC>
-__device__ __forceinline__ void sstore(bf16_t* lds, const uint4 (&r)[8], int t) {
+__device__ __forceinline__ void sstore(bf16_t* lds, const u32x4 (&r)[8], int t) {
   if (KC) {
     const int c = t & 7;
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       const int row = (t >> 3) + 32 * i;
-      *reinterpret_cast<uint4*>(lds + lds_off(row, c)) = r[i];
+      *reinterpret_cast<u32x4*>(lds + lds_off(row, c)) = r[i];
     }
   } else {
     const int nb = t & 31, kb = t >> 5;
-    const uint32_t in[8][4] = {{r[0].x, r[0].y, r[0].z, r[0].w}, {r[1].x, r[1].y, r[1].z, r[1].w},
-                               {r[2].x, r[2].y, r[2].z, r[2].w}, {r[3].x, r[3].y, r[3].z, r[3].w},
-                               {r[4].x, r[4].y, r[4].z, r[4].w}, {r[5].x, r[5].y, r[5].z, r[5].w},
-                               {r[6].x, r[6].y, r[6].z, r[6].w}, {r[7].x, r[7].y, r[7].z, r[7].w}};
 #pragma unroll
     for (int n = 0; n < 8; ++n) {
-      uint32_t o[4];
+      u32x4 o;
 #pragma unroll
       for (int w = 0; w < 4; ++w) {
-        const uint32_t lo = in[2 * w][n >> 1], hi = in[2 * w + 1][n >> 1];
+        const uint32_t lo = r[2 * w][n >> 1], hi = r[2 * w + 1][n >> 1];
         o[w] = (n & 1) ? __builtin_amdgcn_perm(hi, lo, 0x07060302u) : __builtin_amdgcn_perm(hi, lo, 0x05040100u);
       }
-      *reinterpret_cast<uint4*>(lds + lds_off(8 * nb + n, kb)) = make_uint4(o[0], o[1], o[2], o[3]);
+      *reinterpret_cast<u32x4*>(lds + lds_off(8 * nb + n, kb)) = o;
     }
   }
 }
@@ -133,7 +132,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(P p, TileGrid tg) {
   int ld_seg = 0, ld_k0 = 0;
   const TA* Aseg = p.a_seg(gi, 0);
   const bf16_t* Bseg = p.b_seg(gi, 0);
-  uint4 ra[8], rb[8];
+  u32x4 ra[8], rb[8];
 
   auto fetch = [&]() {
     gload<P::A_KC, TA>(ra, Aseg, p.lda, m0, M, ld_k0, kseg, t);
@@ -162,7 +161,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(P p, TileGrid tg) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  uint4 fa[2][4], fb[2][4];
+  u32x4 fa[2][4], fb[2][4];
   const int frow = lane & 31, fch = lane >> 5;
   auto frags = [&](int st, int kk, int buf) {
     const bf16_t* a = smem + st * STAGE_ELEMS;
