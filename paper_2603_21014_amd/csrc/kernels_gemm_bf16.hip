@@ -1,8 +1,8 @@
 // bf16 MFMA path of the five CLT contractions on gfx950 (CDNA4).
 //
-// One workgroup = 4 wavefronts (one per SIMD) computes a 256x256 output tile;
-// each wavefront owns a 128x128 quadrant as 4x4 v_mfma_f32_32x32x16_bf16
-// accumulators (256 accumulator registers per lane).  K advances in steps of
+// One workgroup = 8 wavefronts (two per SIMD) computes a 256x256 output tile;
+// each wavefront owns a 128x64 block as 4x2 v_mfma_f32_32x32x16_bf16
+// accumulators (128 accumulator registers per lane).  K advances in steps of
 // 64 through two LDS stages (2 x 64 KB): while the MFMAs of step t run from one
 // stage, the tile of step t+1 goes registers -> LDS into the other stage and
 // the tile of step t+2 is fetched from HBM into registers.
@@ -60,83 +60,109 @@ template <> __device__ __forceinline__ u32x4 load8<int8_t>(const int8_t* p) {
   return i8x8_to_bf16x8(*reinterpret_cast<const u32x2*>(p));
 }
 
-// Fetch one 256(rows) x 64(k) operand tile into 8 x 16-byte registers per lane.
-// KC: lane t takes chunk c = t%8 of rows t/8 + 32 i.  Otherwise lane t takes the
-// 8(k) x 8(rows) block kb = t/32, nb = t%32.  Out-of-range chunks read as zero
-// (the address is redirected to the tensor base, which is always readable).
+// ---------------------------------------------------------------------------
+// Staging of one 256(rows) x 64(k) operand tile by 256 lanes (lt = 0..255),
+// 8 x 16 bytes per lane.
+//   K-contiguous operand: lane takes 16-byte chunk c = lt%8 of rows lt/8 + 32 i.
+//   K-strided operand:    lane takes the 8(k) x 8(rows) block kb = lt/32, nb = lt%32
+//                         and transposes it in registers before the LDS write.
+// Addresses are a wave-uniform base (tile origin, advanced along K by the
+// caller) plus one 32-bit per-lane byte offset that never changes, so a load
+// needs a single address register.  The EDGE variants predicate every chunk
+// and redirect out-of-range ones to the tensor base (always readable); they
+// return zeros there.
+// ---------------------------------------------------------------------------
 template <bool KC, typename TE>
-__device__ __forceinline__ void gload(u32x4 (&r)[8], const TE* base, int ld, int r0, int R, int k0, int kseg,
-                                      int t) {
-  const u32x4 zero = {0u, 0u, 0u, 0u};
-  if (KC) {
-    const int kk = k0 + ((t & 7) << 3);
-    const bool kok = kk < kseg;
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const int row = r0 + (t >> 3) + 32 * i;
-      const bool ok = kok && row < R;
-      const u32x4 v = load8<TE>(base + (ok ? (size_t)row * ld + kk : (size_t)0));
-      r[i] = ok ? v : zero;
-    }
-  } else {
-    const int col = r0 + ((t & 31) << 3);
-    const bool cok = col < R;
-    const int kb = k0 + ((t >> 5) << 3);
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      const int k = kb + j;
-      const bool ok = cok && k < kseg;
-      const u32x4 v = load8<TE>(base + (ok ? (size_t)k * ld + col : (size_t)0));
-      r[j] = ok ? v : zero;
+struct Stager {
+  uint32_t voff;       // per-lane byte offset inside the tile
+  uint32_t step;       // byte distance between the lane's consecutive chunks (uniform)
+  int r_lane, k_lane;  // EDGE only: first row / k index of this lane inside the tile
+
+  __device__ __forceinline__ void init(int lt, int ld) {
+    if (KC) {
+      r_lane = lt >> 3; k_lane = (lt & 7) << 3;
+      voff = (uint32_t)(((size_t)r_lane * ld + k_lane) * sizeof(TE));
+      step = (uint32_t)(32u * ld * sizeof(TE));
+    } else {
+      r_lane = (lt & 31) << 3; k_lane = (lt >> 5) << 3;
+      voff = (uint32_t)(((size_t)k_lane * ld + r_lane) * sizeof(TE));
+      step = (uint32_t)(ld * sizeof(TE));
     }
   }
-}
-
-template <bool KC>
-__device__ __forceinline__ void sstore(bf16_t* lds, const u32x4 (&r)[8], int t) {
-  if (KC) {
-    const int c = t & 7;
+  // tile_base = operand + tile origin (row r0, k index k0), uniform
+  template <bool EDGE>
+  __device__ __forceinline__ void load(u32x4 (&r)[8], const TE* seg_base, const TE* tile_base, int rows_left,
+                                       int k_left) const {
+    const char* b = reinterpret_cast<const char*>(tile_base);
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-      const int row = (t >> 3) + 32 * i;
-      *reinterpret_cast<u32x4*>(lds + lds_off(row, c)) = r[i];
-    }
-  } else {
-    const int nb = t & 31, kb = t >> 5;
-#pragma unroll
-    for (int n = 0; n < 8; ++n) {
-      u32x4 o;
-#pragma unroll
-      for (int w = 0; w < 4; ++w) {
-        const uint32_t lo = r[2 * w][n >> 1], hi = r[2 * w + 1][n >> 1];
-        o[w] = (n & 1) ? __builtin_amdgcn_perm(hi, lo, 0x07060302u) : __builtin_amdgcn_perm(hi, lo, 0x05040100u);
+      const char* bi = b + (size_t)i * step;            // uniform
+      if (!EDGE) {
+        r[i] = load8<TE>(reinterpret_cast<const TE*>(bi + voff));
+      } else {
+        const bool ok = KC ? (r_lane + 32 * i < rows_left && k_lane < k_left)
+                           : (r_lane < rows_left && k_lane + i < k_left);
+        const TE* ptr = ok ? reinterpret_cast<const TE*>(bi + voff) : seg_base;
+        const u32x4 v = load8<TE>(ptr);
+        const u32x4 zero = {0u, 0u, 0u, 0u};
+        r[i] = ok ? v : zero;
       }
-      *reinterpret_cast<u32x4*>(lds + lds_off(8 * nb + n, kb)) = o;
     }
   }
-}
+  __device__ __forceinline__ void store(bf16_t* lds, const u32x4 (&r)[8], int lt) const {
+    if (KC) {
+      const int c = lt & 7;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const int row = (lt >> 3) + 32 * i;
+        *reinterpret_cast<u32x4*>(lds + lds_off(row, c)) = r[i];
+      }
+    } else {
+      const int nb = lt & 31, kb = lt >> 5;
+#pragma unroll
+      for (int n = 0; n < 8; ++n) {
+        u32x4 o;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+          const uint32_t lo = r[2 * w][n >> 1], hi = r[2 * w + 1][n >> 1];
+          o[w] = (n & 1) ? __builtin_amdgcn_perm(hi, lo, 0x07060302u) : __builtin_amdgcn_perm(hi, lo, 0x05040100u);
+        }
+        *reinterpret_cast<u32x4*>(lds + lds_off(8 * nb + n, kb)) = o;
+      }
+    }
+  }
+};
 
-template <class P>
-__global__ __launch_bounds__(256) void gemm_bf16_kernel(P p, TileGrid tg) {
-  extern __shared__ __align__(16) bf16_t smem[];
-  int gorder, tm, tn;
-  if (!tg.decode(blockIdx.x, gorder, tm, tn)) return;
-  const typename P::GInfo gi = p.ginfo(gorder);
+constexpr int NTHREADS = 512;   // 8 wavefronts: two per SIMD, so one's memory phase hides under the other's MFMAs
+
+// K loop of one output tile.  EDGE = false assumes the tile lies fully inside the
+// matrices and kseg is a multiple of 64 (no predication at all).
+template <class P, bool EDGE>
+__device__ __forceinline__ void main_loop(const P& p, const typename P::GInfo& gi, int m0, int n0, bf16_t* smem,
+                                          f32x16_t (&acc)[4][2]) {
   typedef typename P::AType TA;
-
-  const int t = threadIdx.x, lane = t & 63, w = t >> 6, wm = w >> 1, wn = w & 1;
-  const int m0 = tm * TM, n0 = tn * TN;
-  const int M = p.M, N = p.N, kseg = p.kseg, nseg = p.nseg(gi);
+  const int t = threadIdx.x, lane = t & 63, w = t >> 6, wm = w >> 2, wn = w & 3;
+  const int lt = t & 255;
+  const bool loads_a = __builtin_amdgcn_readfirstlane(w) < 4;   // waves 0-3 stage A, waves 4-7 stage B
+  const int kseg = p.kseg, nseg = p.nseg(gi);
   const int nk = nseg * ((kseg + TK - 1) / TK);
 
+  Stager<P::A_KC, TA> sa;
+  Stager<P::B_KC, bf16_t> sb;
+  sa.init(lt, p.lda);
+  sb.init(lt, p.ldb);
+  // uniform cursors: current segment bases, k offset inside the segment
   int ld_seg = 0, ld_k0 = 0;
   const TA* Aseg = p.a_seg(gi, 0);
   const bf16_t* Bseg = p.b_seg(gi, 0);
-  u32x4 ra[8], rb[8];
+  const size_t a_row0 = P::A_KC ? (size_t)m0 * p.lda : (size_t)m0;   // tile origin at k = 0
+  const size_t b_row0 = P::B_KC ? (size_t)n0 * p.ldb : (size_t)n0;
+  const size_t a_kstep = P::A_KC ? 1 : (size_t)p.lda, b_kstep = P::B_KC ? 1 : (size_t)p.ldb;
+  u32x4 rg[8];
 
   auto fetch = [&]() {
-    gload<P::A_KC, TA>(ra, Aseg, p.lda, m0, M, ld_k0, kseg, t);
-    gload<P::B_KC, bf16_t>(rb, Bseg, p.ldb, n0, N, ld_k0, kseg, t);
+    if (loads_a) sa.template load<EDGE>(rg, Aseg, Aseg + a_row0 + ld_k0 * a_kstep, p.M - m0, kseg - ld_k0);
+    else sb.template load<EDGE>(rg, Bseg, Bseg + b_row0 + ld_k0 * b_kstep, p.N - n0, kseg - ld_k0);
     ld_k0 += TK;
     if (ld_k0 >= kseg) {
       ld_k0 = 0;
@@ -149,19 +175,11 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(P p, TileGrid tg) {
   };
   auto stage = [&](int st) {
     bf16_t* base = smem + st * STAGE_ELEMS;
-    sstore<P::A_KC>(base, ra, t);
-    sstore<P::B_KC>(base + 256 * TK, rb, t);
+    if (loads_a) sa.store(base, rg, lt);
+    else sb.store(base + 256 * TK, rg, lt);
   };
 
-  f32x16_t acc[4][4];
-#pragma unroll
-  for (int i = 0; i < 4; ++i)
-#pragma unroll
-    for (int j = 0; j < 4; ++j)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-
-  u32x4 fa[2][4], fb[2][4];
+  u32x4 fa[2][4], fb[2][2];
   const int frow = lane & 31, fch = lane >> 5;
   auto frags = [&](int st, int kk, int buf) {
     const bf16_t* a = smem + st * STAGE_ELEMS;
@@ -169,13 +187,13 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(P p, TileGrid tg) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) fa[buf][i] = ld16(a + lds_off(wm * 128 + i * 32 + frow, 2 * kk + fch));
 #pragma unroll
-    for (int j = 0; j < 4; ++j) fb[buf][j] = ld16(b + lds_off(wn * 128 + j * 32 + frow, 2 * kk + fch));
+    for (int j = 0; j < 2; ++j) fb[buf][j] = ld16(b + lds_off(wn * 64 + j * 32 + frow, 2 * kk + fch));
   };
   auto mfma = [&](int buf) {
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
-      for (int j = 0; j < 4; ++j)
+      for (int j = 0; j < 2; ++j)
         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, fa[buf][i]),
                                                             __builtin_bit_cast(bf16x8_t, fb[buf][j]), acc[i][j], 0, 0,
                                                             0);
@@ -200,28 +218,51 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(P p, TileGrid tg) {
     if (kt + 1 < nk) frags(cur ^ 1, 0, 0);
     mfma(1);
   }
+}
 
-  // ---- epilogue: accumulators -> LDS (wave-private 128x64 fp32) -> rows of 4 columns per lane
+template <class P>
+__global__ __launch_bounds__(NTHREADS) void gemm_bf16_kernel(P p, TileGrid tg) {
+  extern __shared__ __align__(16) bf16_t smem[];
+  int gorder, tm, tn;
+  if (!tg.decode(blockIdx.x, gorder, tm, tn)) return;
+  const typename P::GInfo gi = p.ginfo(gorder);
+
+  // wave w owns output rows wm*128.., columns wn*64..
+  const int t = threadIdx.x, lane = t & 63, w = t >> 6, wm = w >> 2, wn = w & 3;
+  const int m0 = tm * TM, n0 = tn * TN;
+  const int M = p.M, N = p.N;
+
+  f32x16_t acc[4][2];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  const bool interior = (m0 + TM <= M) && (n0 + TN <= N) && (p.kseg % TK == 0);
+  if (interior) main_loop<P, false>(p, gi, m0, n0, smem, acc);
+  else main_loop<P, true>(p, gi, m0, n0, smem, acc);
+
+  // ---- epilogue: accumulators -> LDS (wave-private 32 rows x 64 fp32) -> 4 columns of one row per lane
   __syncthreads();
-  float* wl = reinterpret_cast<float*>(smem) + w * (128 * 64);
+  float* wl = reinterpret_cast<float*>(smem) + w * (32 * 64);
   typename P::Epi est;
   p.epi_begin(est);
+  const int c4 = (lane & 15) << 2;
+  const int gcol = n0 + wn * 64 + c4;
 #pragma unroll
-  for (int jp = 0; jp < 4; jp += 2) {
+  for (int i = 0; i < 4; ++i) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int j = 0; j < 2; ++j)
 #pragma unroll
-      for (int jj = 0; jj < 2; ++jj)
-#pragma unroll
-        for (int r = 0; r < 16; ++r)
-          wl[(i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3)) * 64 + jj * 32 + (lane & 31)] = acc[i][jp + jj][r];
+      for (int r = 0; r < 16; ++r)
+        wl[(8 * (r >> 2) + 4 * (lane >> 5) + (r & 3)) * 64 + j * 32 + (lane & 31)] = acc[i][j][r];
     __syncthreads();
-    const int c4 = (lane & 15) << 2;
-    const int gcol = n0 + wn * 128 + jp * 32 + c4;
-#pragma unroll 4
-    for (int it = 0; it < 32; ++it) {
+#pragma unroll
+    for (int it = 0; it < 8; ++it) {
       const int row = it * 4 + (lane >> 4);
-      const int grow = m0 + wm * 128 + row;
+      const int grow = m0 + wm * 128 + i * 32 + row;
       const float4 v = *reinterpret_cast<const float4*>(wl + row * 64 + c4);
       if (grow < M && gcol < N) p.epi4(est, gi, grow, gcol, v);
     }
@@ -233,7 +274,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(P p, TileGrid tg) {
 template <class P>
 hipError_t launch(hipStream_t s, const P& p, int G) {
   const TileGrid tg = TileGrid::make(G, p.M, p.N, TM, TN);
-  hipLaunchKernelGGL((gemm_bf16_kernel<P>), dim3(tg.num_wg()), dim3(256), LDS_BYTES, s, p, tg);
+  hipLaunchKernelGGL((gemm_bf16_kernel<P>), dim3(tg.num_wg()), dim3(NTHREADS), LDS_BYTES, s, p, tg);
   return hipGetLastError();
 }
 
