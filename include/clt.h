@@ -72,8 +72,10 @@ typedef struct clt_config {
                              float scale per (layer, token) row (Sec. 3.1 cache format) */
   int32_t master_weights; /* 1: clt_adam_step updates fp32 master copies of W_enc/W_dec  */
   int32_t decode_mode;    /* dense GEMM decode, active-feature gather decode (Sec. 3.2),
-                             or chosen per step from the measured density               */
-  float gather_density_threshold; /* AUTO: gather when mean active fraction <= this      */
+                             or chosen per step, on the device, from the measured density */
+  float gather_density_threshold; /* AUTO: gather when the mean active fraction of the batch
+                             is <= this and no (layer, token) row has more than about 8x
+                             as many active features (else the step decodes densely)    */
   float C;                /* sparsity scale C of the App. B objective                     */
   float ste_bandwidth;    /* width eps of the rectangle kernel of the threshold gradient */
   float beta1, beta2, adam_eps; /* Adam (App. C Table 1: 0.9, 0.999)                     */
@@ -142,7 +144,9 @@ int clt_adam_step(clt_handle* handle, void* stream, int64_t t, float lr,
 
 /* Device pointers into the workspace, for inspection by tests and tools:
  * which = 0 decoder norms [L,F] float; 1 d y_hat [L,B,d] T; 2 d pre [L,B,F] T;
- * 3 sparsity column sums G [L,F] float.  Valid after the call that writes them. */
+ * 3 sparsity column sums G [L,F] float; 4 decode switch, 4 int32: {gather allowed by
+ * the measured density, longest active list, path taken by the last forward
+ * (1 dense, 2 gather), unused}.  Valid after the call that writes them. */
 int clt_workspace_view(const clt_handle* handle, int which, void** ptr, size_t* bytes);
 
 /* Optional per-kernel timing, for benchmarks and profiling (not part of the

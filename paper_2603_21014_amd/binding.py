@@ -202,7 +202,8 @@ def clt_adam_step(H: Handle, t: int, lr: float, params: dict, grads: dict, m: di
 
 
 _VIEWS = {"norms": (0, torch.float32, lambda c: (c.L, c.F)), "d_yhat": (1, None, lambda c: (c.L, c.B, c.d)),
-          "dpre": (2, None, lambda c: (c.L, c.B, c.F)), "G": (3, torch.float32, lambda c: (c.L, c.F))}
+          "dpre": (2, None, lambda c: (c.L, c.B, c.F)), "G": (3, torch.float32, lambda c: (c.L, c.F)),
+          "decode_switch": (4, torch.int32, lambda c: (4,))}
 
 
 def clt_workspace_view(H: Handle, which: str) -> torch.Tensor:
@@ -233,10 +234,12 @@ class CLTStep:
     """A handle with its workspace and the per-step buffers of one configuration."""
 
     def __init__(self, L, d, F, B, dtype="bf16", int8_inputs=False, master_weights=False, C_=4.0,
-                 ste_bandwidth=0.05, beta1=0.9, beta2=0.999, adam_eps=1e-8, device="cuda:0", keep_pre=True):
+                 ste_bandwidth=0.05, beta1=0.9, beta2=0.999, adam_eps=1e-8, device="cuda:0", keep_pre=True,
+                 decode_mode=DECODE_DENSE, gather_density_threshold=0.005):
         dt = DTYPE_BF16 if dtype == "bf16" else DTYPE_F32
         self.cfg = make_config(L, d, F, B, dt, INPUT_INT8_ROWSCALE if int8_inputs else INPUT_NATIVE,
-                               master_weights, DECODE_DENSE, 0.005, C_, ste_bandwidth, beta1, beta2, adam_eps)
+                               master_weights, decode_mode, gather_density_threshold, C_, ste_bandwidth, beta1,
+                               beta2, adam_eps)
         self.device = torch.device(device)
         ws = torch.empty(clt_workspace_bytes(self.cfg), dtype=torch.uint8, device=self.device)
         self.H = clt_init(self.cfg, ws)

@@ -21,7 +21,8 @@ constexpr size_t ALIGN = 256;
 inline size_t align_up(size_t v) { return (v + ALIGN - 1) / ALIGN * ALIGN; }
 
 struct Plan {
-  size_t norms, G, d_yhat, dpre, part_cols, part_cols2, part_rec, part_sp, total;
+  size_t norms, G, d_yhat, dpre, part_cols, part_cols2, part_rec, part_sp, l0, flags, g_idx, g_val, g_counts, total;
+  int kcap;
 };
 
 thread_local char g_err[256] = "";
@@ -37,12 +38,12 @@ void set_err(char* dst, const char* fmt, ...) {
 
 enum KernelId {
   K_NORMS, K_ENC, K_DEC, K_LOSS_SP, K_LOSS_REC, K_LOSS_FINAL, K_COLRED, K_DZ, K_STE, K_DWENC, K_DWDEC,
-  K_ADAM_WDEC, K_ADAM_WENC, K_ADAM_VEC, K_ZERO, K_COUNT
+  K_ADAM_WDEC, K_ADAM_WENC, K_ADAM_VEC, K_ZERO, K_DECIDE, K_COMPACT, K_GATHER, K_COUNT
 };
 static const char* const kKernelNames[K_COUNT] = {
   "decoder_norms", "encoder_jumprelu_gemm", "decode_gemm", "loss_sparsity", "loss_reconstruction", "loss_final",
   "column_reduce", "dz_gemm", "ste_reduce", "dW_enc_gemm", "dW_dec_gemm", "adam_W_dec", "adam_W_enc",
-  "adam_vectors", "zero_counters"};
+  "adam_vectors", "zero_counters", "decode_decide", "compact_active", "gather_decode"};
 
 struct ProfSpan { int kernel; hipEvent_t a, b; };
 
@@ -90,8 +91,12 @@ int check_config(const clt_config* c, char* err) {
     return CLT_ERR_INVALID_ARG;
   }
   if (c->master_weights != 0 && c->master_weights != 1) { set_err(err, "bad master_weights"); return CLT_ERR_INVALID_ARG; }
-  if (c->decode_mode != CLT_DECODE_DENSE) {
-    set_err(err, "decode_mode %d is not available in this build (dense = %d only)", c->decode_mode, CLT_DECODE_DENSE);
+  if (c->decode_mode != CLT_DECODE_DENSE && c->decode_mode != CLT_DECODE_GATHER && c->decode_mode != CLT_DECODE_AUTO) {
+    set_err(err, "bad decode_mode %d", c->decode_mode);
+    return CLT_ERR_INVALID_ARG;
+  }
+  if (c->decode_mode == CLT_DECODE_AUTO && !(c->gather_density_threshold >= 0.f && c->gather_density_threshold <= 1.f)) {
+    set_err(err, "gather_density_threshold must be in [0, 1]");
     return CLT_ERR_INVALID_ARG;
   }
   if (!(c->C > 0.f) || !(c->ste_bandwidth > 0.f) || !(c->beta1 >= 0.f && c->beta1 < 1.f) ||
@@ -117,6 +122,21 @@ Plan make_plan(const clt_config* c) {
   p.part_cols2 = o; o += align_up(rbs * L * F * 4);
   p.part_rec = o;   o += align_up(rbs * L * 8);
   p.part_sp = o;    o += align_up(rbs * L * 8);
+  p.l0 = o;         o += align_up(L * 4);
+  p.flags = o;      o += align_up(4 * 4);
+  // active-feature lists of the gather decode: forced gather must hold a fully dense row;
+  // the automatic switch only ever gathers below the threshold, so rows are capped at a
+  // multiple of it and a step with a longer row falls back to the dense decode
+  p.kcap = 0;
+  if (c->decode_mode == CLT_DECODE_GATHER) p.kcap = c->F;
+  if (c->decode_mode == CLT_DECODE_AUTO) {
+    size_t k = (size_t)(8.0 * c->gather_density_threshold * F) + 64;
+    k = (k + 7) / 8 * 8;
+    p.kcap = (int)(k < F ? k : F);
+  }
+  p.g_idx = o;      o += align_up(L * B * (size_t)p.kcap * 4);
+  p.g_val = o;      o += align_up(L * B * (size_t)p.kcap * 4);
+  p.g_counts = o;   o += align_up(L * B * 4);
   p.total = o;
   return p;
 }
@@ -284,6 +304,7 @@ int clt_workspace_view(const clt_handle* h, int which, void** ptr, size_t* bytes
     case 1: *ptr = h->ws + h->plan.d_yhat; *bytes = L * B * d * h->esz; break;
     case 2: *ptr = h->ws + h->plan.dpre; *bytes = L * B * F * h->esz; break;
     case 3: *ptr = h->ws + h->plan.G; *bytes = L * F * 4; break;
+    case 4: *ptr = h->ws + h->plan.flags; *bytes = 16; break;
     default: return CLT_ERR_INVALID_ARG;
   }
   return CLT_OK;
@@ -301,16 +322,29 @@ int clt_forward(clt_handle* h, void* stream, const void* x, const float* x_scale
   hipStream_t s = static_cast<hipStream_t>(stream);
   h->stage = 0;
   float* norms = reinterpret_cast<float*>(h->ws + h->plan.norms);
-  if (l0_per_layer) RUN(h, s, K_ZERO, launch_zero_i32(s, l0_per_layer, h->D.L));
+  int32_t* l0 = l0_per_layer ? l0_per_layer : reinterpret_cast<int32_t*>(h->ws + h->plan.l0);
+  int32_t* flags = reinterpret_cast<int32_t*>(h->ws + h->plan.flags);
+  RUN(h, s, K_ZERO, launch_zero_i32(s, l0, h->D.L));
   RUN(h, s, K_NORMS, launch_decoder_norms(s, h->bf16, h->D, W_dec, norms));
-  EncArgs ea{x, x_scale, W_enc, b_enc, theta, h->cfg.ste_bandwidth, z, pre, act_class, l0_per_layer};
-  DecArgs da{z, W_dec, b_dec, y_hat};
+  EncArgs ea{x, x_scale, W_enc, b_enc, theta, h->cfg.ste_bandwidth, z, pre, act_class, l0};
+  const int mode = h->cfg.decode_mode;
+  DecArgs da{z, W_dec, b_dec, y_hat, mode == CLT_DECODE_AUTO ? flags : nullptr, h->plan.kcap};
+  GatherLists gl{reinterpret_cast<int32_t*>(h->ws + h->plan.g_idx), reinterpret_cast<float*>(h->ws + h->plan.g_val),
+                 reinterpret_cast<int32_t*>(h->ws + h->plan.g_counts), h->plan.kcap};
   if (h->bf16) {
     RUN(h, s, K_ENC, launch_enc_bf16(s, h->D, ea, h->int8));
-    RUN(h, s, K_DEC, launch_dec_bf16(s, h->D, da));
   } else {
     RUN(h, s, K_ENC, launch_enc_f32(s, h->D, ea));
-    RUN(h, s, K_DEC, launch_dec_f32(s, h->D, da));
+  }
+  if (mode != CLT_DECODE_DENSE) {   // Sec. 3.2: density monitor, then the gather path where it pays
+    RUN(h, s, K_DECIDE, launch_decode_decide(s, h->D, l0, h->cfg.gather_density_threshold, mode == CLT_DECODE_GATHER,
+                                             flags));
+    RUN(h, s, K_COMPACT, launch_compact_active(s, h->bf16, h->D, z, act_class, gl, flags));
+    RUN(h, s, K_GATHER, launch_gather_decode(s, h->bf16, h->D, gl, W_dec, b_dec, y_hat, flags));
+  }
+  if (mode != CLT_DECODE_GATHER) {
+    if (h->bf16) RUN(h, s, K_DEC, launch_dec_bf16(s, h->D, da));
+    else RUN(h, s, K_DEC, launch_dec_f32(s, h->D, da));
   }
   h->stage = 1;
   return CLT_OK;

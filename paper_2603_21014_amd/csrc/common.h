@@ -70,6 +70,8 @@ struct EncArgs {       // pre = x W_enc + b_enc; JumpReLU; classes; L0 counts
 };
 struct DecArgs {       // y_hat[lp] = sum_{l<=lp} z[l] W_dec[p(l,lp)] + b_dec[lp]
   const void* z; const void* W_dec; const float* b_dec; float* y_hat;
+  const int32_t* skip_flags;   // optional decode switch (see GatherLists); NULL = always run
+  int kcap;
 };
 struct DzArgs {        // dz[l] = sum_{lp>=l} dyhat[lp] W_dec[p(l,lp)]^T + g_sp, kept where active|window
   const void* d_yhat; const void* W_dec; const void* z; const uint8_t* cls; const float* norms;
@@ -123,5 +125,22 @@ struct AdamScalars { float lr, beta1, beta2, eps, bc1, bc2; };   // bc = 1 - bet
 hipError_t launch_adam_matrix(hipStream_t s, bool bf16, size_t n, void* p, const void* g, float* m, float* v,
                               float* master_or_null, AdamScalars a);
 hipError_t launch_adam_vector(hipStream_t s, size_t n, float* p, const float* g, float* m, float* v, AdamScalars a);
+
+// ---- active-feature gather decode (kernels_gather.hip) -----------------------
+// Device-side decode switch, 4 ints in the workspace:
+//   [0] 1 when the measured density allows the gather path (or it is forced)
+//   [1] largest per-(layer, token) active count seen by the compaction
+//   [2] path taken by the last forward: 1 dense, 2 gather
+struct GatherLists { int32_t* idx; float* val; int32_t* counts; int kcap; };
+// flags[0] = (sum l0 <= threshold * L*B*F) or forced; flags[1] = 0
+hipError_t launch_decode_decide(hipStream_t s, Dims D, const int32_t* l0, float density_threshold, int forced,
+                                int32_t* flags);
+// per (layer, token) row: indices and values of the active features, in feature order
+hipError_t launch_compact_active(hipStream_t s, bool bf16, Dims D, const void* z, const uint8_t* cls, GatherLists g,
+                                 int32_t* flags);
+// y_hat[lp, b, :] = b_dec[lp] + sum_{l<=lp} sum_{active f} z[l,b,f] W_dec[p(l,lp)][f, :]; runs only when
+// flags say so (flags[0] != 0 and flags[1] <= kcap) and records the path in flags[2]
+hipError_t launch_gather_decode(hipStream_t s, bool bf16, Dims D, GatherLists g, const void* W_dec,
+                                const float* b_dec, float* y_hat, int32_t* flags);
 
 }  // namespace clt

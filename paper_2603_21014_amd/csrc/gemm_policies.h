@@ -69,6 +69,7 @@ struct EncPolicy {
   int M, N, kseg, lda, ldb;
   const TA* x; const T* W_enc; const float* b_enc; const float* theta; const float* x_scale;
   float half_eps; T* z; T* pre; uint8_t* cls; int32_t* l0;
+  __device__ bool skip() const { return false; }
   struct GInfo { int l; };
   struct Epi { int count; };
   __device__ GInfo ginfo(int order) const { return {order}; }
@@ -120,6 +121,9 @@ struct DecPolicy {
   Dims D;
   int M, N, kseg, lda, ldb;
   const T* z; const T* W_dec; const float* b_dec; float* y_hat;
+  const int32_t* skip_flags; int kcap;
+  // the dense decode stands down when the device-side switch selected the gather path
+  __device__ bool skip() const { return skip_flags && skip_flags[0] != 0 && skip_flags[1] <= kcap; }
   struct GInfo { int lp; };
   struct Epi {};
   __device__ GInfo ginfo(int order) const { return {D.L - 1 - order}; }   // longest K first
@@ -149,6 +153,7 @@ struct DzPolicy {
   int M, N, kseg, lda, ldb;
   const T* d_yhat; const T* W_dec; const T* z; const uint8_t* cls; const float* norms;
   float lam_c_over_b, C; T* dpre;
+  __device__ bool skip() const { return false; }
   struct GInfo { int l; };
   struct Epi {};
   __device__ GInfo ginfo(int order) const { return {order}; }             // K = (L-l) d, longest first
@@ -191,6 +196,7 @@ struct DWdecPolicy {
   Dims D;
   int M, N, kseg, lda, ldb;
   const T* z; const T* d_yhat; const T* W_dec; const float* G; const float* norms; T* dW_dec;
+  __device__ bool skip() const { return false; }
   struct GInfo { int p, l, lp; };
   struct Epi {};
   __device__ GInfo ginfo(int order) const {
@@ -222,6 +228,7 @@ struct DWencPolicy {
   Dims D;
   int M, N, kseg, lda, ldb;
   const TA* x; const T* dpre; T* dW_enc;
+  __device__ bool skip() const { return false; }
   struct GInfo { int l; };
   struct Epi {};
   __device__ GInfo ginfo(int order) const { return {order}; }

@@ -280,7 +280,7 @@ template <class P>
 __global__ __launch_bounds__(NTHREADS) void gemm_bf16_kernel(P p, TileGrid tg) {
   extern __shared__ __align__(16) bf16_t smem[];
   int gorder, tm, tn;
-  if (!tg.decode(blockIdx.x, gorder, tm, tn)) return;
+  if (!tg.decode(blockIdx.x, gorder, tm, tn) || p.skip()) return;
   const typename P::GInfo gi = p.ginfo(gorder);
 
   // wave w owns output rows wm*128.., columns wn*64..
@@ -377,7 +377,7 @@ hipError_t launch_enc_bf16(hipStream_t s, Dims D, const EncArgs& a, bool int8_x)
   return launch(s, p, D.L);
 }
 hipError_t launch_dec_bf16(hipStream_t s, Dims D, const DecArgs& a) {
-  DecPolicy<bf16_t> p{D, D.B, D.d, D.F, D.F, D.d, (const bf16_t*)a.z, (const bf16_t*)a.W_dec, a.b_dec, a.y_hat};
+  DecPolicy<bf16_t> p{D, D.B, D.d, D.F, D.F, D.d, (const bf16_t*)a.z, (const bf16_t*)a.W_dec, a.b_dec, a.y_hat, a.skip_flags, a.kcap};
   return launch(s, p, D.L);
 }
 hipError_t launch_dz_bf16(hipStream_t s, Dims D, const DzArgs& a) {

@@ -15,7 +15,7 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(P p, TileGrid tg) {
   __shared__ float As[FTK][FTM + 4];
   __shared__ float Bs[FTK][FTN + 4];
   int gorder, tm, tn;
-  if (!tg.decode(blockIdx.x, gorder, tm, tn)) return;
+  if (!tg.decode(blockIdx.x, gorder, tm, tn) || p.skip()) return;
   const typename P::GInfo gi = p.ginfo(gorder);
   const int t = threadIdx.x, tx = t & 15, ty = t >> 4;
   const int m0 = tm * FTM, n0 = tn * FTN;
@@ -91,7 +91,7 @@ hipError_t launch_enc_f32(hipStream_t s, Dims D, const EncArgs& a) {
   return launch(s, p, D.L);
 }
 hipError_t launch_dec_f32(hipStream_t s, Dims D, const DecArgs& a) {
-  DecPolicy<float> p{D, D.B, D.d, D.F, D.F, D.d, (const float*)a.z, (const float*)a.W_dec, a.b_dec, a.y_hat};
+  DecPolicy<float> p{D, D.B, D.d, D.F, D.F, D.d, (const float*)a.z, (const float*)a.W_dec, a.b_dec, a.y_hat, a.skip_flags, a.kcap};
   return launch(s, p, D.L);
 }
 hipError_t launch_dz_f32(hipStream_t s, Dims D, const DzArgs& a) {

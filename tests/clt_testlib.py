@@ -26,7 +26,7 @@ class GpuRun:
     """One forward/loss/backward/Adam pass of the HIP library; results as numpy."""
 
     def __init__(self, w: S.CLTWorkload, params, x, y, t=1, m=None, v=None, x_scale=None, y_scale=None,
-                 theta=None):
+                 theta=None, decode_mode=1, gather_density_threshold=0.005):
         from paper_2603_21014_amd import binding as K
         dev = "cuda:0"
         T = torch.float32 if w.dtype == "f32" else torch.bfloat16
@@ -41,7 +41,8 @@ class GpuRun:
         if w.master_weights:
             master = {k: params[k].to(dev, torch.float32).contiguous() for k in MATS}
         step = K.CLTStep(w.L, w.d, w.F, w.B, dtype=w.dtype, int8_inputs=w.int8_inputs,
-                         master_weights=w.master_weights, C_=w.C, ste_bandwidth=w.ste_eps, device=dev)
+                         master_weights=w.master_weights, C_=w.C, ste_bandwidth=w.ste_eps, device=dev,
+                         decode_mode=decode_mode, gather_density_threshold=gather_density_threshold)
         xg, yg = x.to(dev, TX).contiguous(), y.to(dev, TX).contiguous()
         xs = x_scale.to(dev) if x_scale is not None else None
         ys = y_scale.to(dev) if y_scale is not None else None
@@ -56,6 +57,7 @@ class GpuRun:
         cls = step.act_class.cpu().numpy()
         self.active, self.window = (cls & 1).astype(bool), (cls & 2).astype(bool)
         self.l0 = step.l0.cpu().numpy()
+        self.decode_switch = K.clt_workspace_view(step.H, "decode_switch").cpu().numpy()
         self.grads = {k: to_np(g) for k, g in step.grads.items()}
         step.adam_step(t, w.lr, gp, gm, gv, master)
         torch.cuda.synchronize()
@@ -158,7 +160,7 @@ def check_adam_outputs(w, g: GpuRun, o: OracleRun, tol):
             assert (np.abs(rounded - got) <= 0.51 * bf16_ulp(got)).all(), f"bf16 copy of master {k}"
 
 
-def run_both(w, theta=None, t=1, m=None, v=None):
+def run_both(w, theta=None, t=1, m=None, v=None, **gpu_kw):
     params = S.make_params(w)
     x, y = S.make_inputs(w)
     xs = ys = None
@@ -169,7 +171,7 @@ def run_both(w, theta=None, t=1, m=None, v=None):
         yin, ys = S.quantize_rows_int8(y)
         xo = O.dequantize_rows(xin.numpy(), xs.numpy())
         yo = O.dequantize_rows(yin.numpy(), ys.numpy())
-    g = GpuRun(w, params, xin, yin, t=t, m=m, v=v, x_scale=xs, y_scale=ys, theta=theta)
+    g = GpuRun(w, params, xin, yin, t=t, m=m, v=v, x_scale=xs, y_scale=ys, theta=theta, **gpu_kw)
     o = OracleRun(w, params, x, y, t=t, m=m, v=v, gpu_active=g.active, gpu_window=g.window, theta=theta,
                   x_np=xo, y_np=yo)
     return g, o

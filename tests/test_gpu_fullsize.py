@@ -1,0 +1,147 @@
+"""Full-size parity at the benchmark's workload (Llama-3.2-1B-shaped CLT, bf16,
+L=16, d=2048, F=8192, B=4096) in the launch configuration bench.py times.
+
+The naive oracle cannot run a whole step at this size in test time, so the
+comparison is on what it can compute one piece at a time, from the same seeded
+inputs and never from a GPU result:
+  * encoder, JumpReLU and both masks for EVERY token and layer;
+  * y_hat and d y_hat for sampled tokens at all target layers;
+  * dW_dec and db_dec on sampled (source, target, feature, column-range) slabs;
+  * every last-layer gradient that needs the full d y_hat of one layer only:
+    dpre, dtheta, db_enc of layer L-1 and sampled columns of dW_enc[L-1];
+  * Adam first moments on the same slabs.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import clt_oracle as O
+from workloads import clt_synth as S
+
+from clt_testlib import MASK_BAND, rel_l2
+
+pytestmark = pytest.mark.gpu
+TOL = 2e-2
+
+
+class LazyBlocks:
+    """W_dec[p] as a float64 numpy block, converted on demand from the bf16 host copy."""
+
+    def __init__(self, t):
+        self.t = t
+        self.shape = tuple(t.shape)
+
+    def __getitem__(self, p):
+        return self.t[p].float().numpy().astype(np.float64)
+
+
+@pytest.mark.timeout(1200)
+def test_llama1b_shaped_step_against_sampled_oracle():
+    from paper_2603_21014_amd import binding as K
+    w = S.WORKLOADS["llama1b"]
+    L, d, F, B = w.L, w.d, w.F, w.B
+    dev = "cuda:0"
+    T = torch.bfloat16
+    p32 = S.make_params(w, device=dev)
+    params = {k: (v.to(T) if k in ("W_enc", "W_dec") else v) for k, v in p32.items()}
+    del p32
+    x, y = (t.to(T) for t in S.make_inputs(w, device=dev))
+    m = {k: torch.zeros(v.shape, dtype=torch.float32, device=dev) for k, v in params.items()}
+    v_ = {k: torch.zeros(v.shape, dtype=torch.float32, device=dev) for k, v in params.items()}
+    step = K.CLTStep(L, d, F, B, dtype="bf16", C_=w.C, ste_bandwidth=w.ste_eps, device=dev, keep_pre=False)
+    print("running the GPU step", flush=True)
+    step.forward(x, params)
+    loss = step.loss(y, w.lambda0, to_host=True)
+    d_yhat_gpu = K.clt_workspace_view(step.H, "d_yhat")
+    step.backward(x, params)
+    dpre_last_gpu = K.clt_workspace_view(step.H, "dpre")[L - 1].float().cpu().numpy()
+    W_dec_host = params["W_dec"].cpu()          # before Adam changes it
+    W_enc_host = params["W_enc"].float().cpu().numpy()
+    step.adam_step(1, w.lr, params, m, v_)
+    torch.cuda.synchronize()
+    assert all(np.isfinite(loss))
+
+    xh, yh = x.float().cpu().numpy(), y.float().cpu().numpy()
+    theta = params["theta"].cpu().numpy().astype(np.float64)
+    b_enc = np.zeros((L, F)); b_dec = np.zeros((L, d))       # the workload's initial biases
+    Wd = LazyBlocks(W_dec_host)
+
+    # ---- encoder + JumpReLU + masks, every token
+    print("oracle: encoder for all tokens", flush=True)
+    pre = O.encoder_preact(xh, W_enc_host, b_enc)
+    cls = step.act_class.cpu().numpy()
+    act_gpu, win_gpu = (cls & 1).astype(bool), (cls & 2).astype(bool)
+    z, active = O.jumprelu(pre, theta, tie_break=act_gpu, band=MASK_BAND)    # raises outside the band
+    window = O.ste_window(pre, theta, w.ste_eps, tie_break=win_gpu, band=MASK_BAND)
+    assert (active == act_gpu).all() and (window == win_gpu).all()
+    assert (step.l0.cpu().numpy() == active.sum(axis=(1, 2))).all()
+    for l in range(L):
+        assert rel_l2(step.z[l].float().cpu().numpy(), z[l]) <= TOL, f"z[{l}]"
+    del pre
+
+    # ---- decode on sampled tokens, all targets
+    print("oracle: decode on sampled tokens", flush=True)
+    rng = np.random.default_rng(5)
+    toks = np.sort(rng.choice(B, size=12, replace=False))
+    yhat_o = O.decode(z[:, toks, :], Wd, b_dec)
+    yhat_g = step.y_hat[:, torch.as_tensor(toks, device=dev), :].cpu().numpy()
+    dy_g = d_yhat_gpu[:, torch.as_tensor(toks, device=dev), :].float().cpu().numpy()
+    for lp in range(L):
+        assert rel_l2(yhat_g[lp], yhat_o[lp]) <= TOL, f"y_hat[{lp}]"
+        assert rel_l2(dy_g[lp], 2.0 * (yhat_o[lp] - yh[lp][toks]) / B) <= TOL, f"d_yhat[{lp}]"
+
+    # ---- decoder-gradient slabs: dW_dec[p(l,lp)][f0:f0+8, j0:j0+64], db_dec[lp][j0:j0+64]
+    print("oracle: decoder gradient slabs", flush=True)
+    n_cache = {}
+
+    def norms_of(l, fs):
+        key = (l, fs.start)
+        if key not in n_cache:
+            acc = np.zeros(fs.stop - fs.start)
+            for l2 in range(l, L):
+                blk = W_dec_host[O.packed_index(l, l2, L), fs].float().numpy().astype(np.float64)
+                acc += np.sum(blk * blk, axis=1)
+            n_cache[key] = np.sqrt(acc)
+        return n_cache[key]
+
+    dW_g_all, m_g_all = step.grads["W_dec"], m["W_dec"]
+    for (l, lp, f0, j0) in [(0, 0, 16, 0), (0, 15, 4096, 1984), (7, 9, 8184, 640), (15, 15, 1000, 1024)]:
+        fs, js = slice(f0, f0 + 8), slice(j0, j0 + 64)
+        ycol = np.tile(b_dec[lp][js][None, :], (B, 1))
+        for l2 in range(lp + 1):
+            blk = W_dec_host[O.packed_index(l2, lp, L), :, js].float().numpy().astype(np.float64)
+            ycol += z[l2] @ blk
+        dcol = 2.0 * (ycol - yh[lp][:, js]) / B
+        p = O.packed_index(l, lp, L)
+        n = norms_of(l, fs)
+        zf = z[l][:, fs]
+        sech2 = 1.0 / np.cosh(w.C * zf * n[None, :]) ** 2
+        G = (w.lambda0 / B) * np.sum(w.C * zf * sech2, axis=0)
+        Wblk = W_dec_host[p, fs, js].float().numpy().astype(np.float64)
+        dW_o = zf.T @ dcol + (G / np.maximum(n, 1e-30))[:, None] * Wblk
+        dW_g = dW_g_all[p, fs, js].float().cpu().numpy()
+        assert rel_l2(dW_g, dW_o) <= TOL, f"dW_dec slab {(l, lp, f0, j0)}"
+        assert rel_l2(m_g_all[p, fs, js].cpu().numpy(), 0.1 * dW_o) <= TOL, "Adam m on the slab"
+        assert rel_l2(step.grads["b_dec"][lp, js].cpu().numpy(), dcol.sum(axis=0)) <= TOL, f"db_dec[{lp}]"
+
+    # ---- last source layer: needs d y_hat of the last target only
+    print("oracle: last-layer backward", flush=True)
+    l = L - 1
+    yfull = np.tile(b_dec[l][None, :], (B, 1))
+    for l2 in range(L):
+        yfull += z[l2] @ Wd[O.packed_index(l2, l, L)]
+    dy = 2.0 * (yfull - yh[l]) / B
+    Wll = Wd[O.packed_index(l, l, L)]
+    n = np.sqrt(np.sum(Wll * Wll, axis=1))
+    u = w.C * z[l] * n[None, :]
+    dz = dy @ Wll.T + (w.lambda0 / B) * w.C * n[None, :] / np.cosh(u) ** 2
+    dpre = np.where(active[l], dz, 0.0)
+    assert rel_l2(dpre_last_gpu, dpre) <= TOL, "dpre[L-1]"
+    dtheta = np.sum(np.where(window[l], -(theta[l][None, :] / w.ste_eps) * dz, 0.0), axis=0)
+    assert rel_l2(step.grads["theta"][l].cpu().numpy(), dtheta) <= TOL, "dtheta[L-1]"
+    assert rel_l2(step.grads["b_enc"][l].cpu().numpy(), dpre.sum(axis=0)) <= TOL, "db_enc[L-1]"
+    fs = slice(2048, 2048 + 64)
+    dWe = xh[l].astype(np.float64).T @ dpre[:, fs]
+    assert rel_l2(step.grads["W_enc"][l, :, fs].float().cpu().numpy(), dWe) <= TOL, "dW_enc[L-1] columns"
+    assert rel_l2(m["W_enc"][l, :, fs].cpu().numpy(), 0.1 * dWe) <= TOL, "Adam m of W_enc columns"
+    print(f"full-size parity ok; loss {loss}", flush=True)

@@ -110,6 +110,92 @@ def test_adam_later_step_with_given_moments(dtype):
         assert rel_l2(got - o.params[k], o.new_params[k] - o.params[k]) <= tol, k
 
 
+# ---------------------------------------------------------------- int8 activation cache
+@pytest.mark.parametrize("L,d,F,B", [(2, 64, 256, 96), (3, 264, 520, 300)])
+def test_int8_row_scaled_inputs(L, d, F, B):
+    """x and y as int8 codes with per-(layer, token) scales, dequantised inside the
+    kernels; the oracle consumes the dequantised values."""
+    w = S.scaled(S.WORKLOADS["llama1b_int8"], L=L, d=d, F=F, B=B, k_active=8)
+    g, o = run_both(w)
+    show(f"int8 L{L} d{d} F{F} B{B}", compare_step(w, g, o, TOL["bf16"]))
+
+
+# ---------------------------------------------------------------- gather decode and the switch
+DENSE, GATHER, AUTO = 1, 2, 0
+
+
+def sparse_theta(w, rho):
+    params = S.make_params(w)
+    x, _ = S.make_inputs(w)
+    return S.theta_for_density(x, params["W_enc"], params["b_enc"], rho)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("rho", [0.02, 0.3])
+def test_gather_decode_full_step_against_oracle(dtype, rho):
+    w = S.scaled(S.WORKLOADS["tiny"], dtype=dtype, L=3, d=264, F=520, B=100, seed=77)
+    theta = sparse_theta(w, rho)
+    g, o = run_both(w, theta=theta, decode_mode=GATHER)
+    assert g.decode_switch[2] == 2, "the gather path did not run"
+    assert abs(g.active.mean() - rho) < 0.3 * rho
+    show(f"gather {dtype} rho={rho}", compare_step(w, g, o, TOL[dtype]))
+
+
+def test_gather_wide_model_dim_and_empty_rows():
+    """d > 2048 takes two column passes; an infinite threshold leaves every list empty."""
+    w = S.scaled(S.WORKLOADS["gpt2"], L=2, d=2304, F=256, B=40, seed=78)
+    theta = sparse_theta(w, 0.05)
+    g, o = run_both(w, theta=theta, decode_mode=GATHER)
+    assert g.decode_switch[2] == 2
+    show("gather d=2304", compare_step(w, g, o, TOL["bf16"]))
+    params = S.make_params(w)
+    params["b_dec"] = torch.randn((w.L, w.d), generator=torch.Generator().manual_seed(3))
+    x, y = S.make_inputs(w)
+    g = GpuRun(w, params, x, y, theta=torch.full((w.L, w.F), float("inf")), decode_mode=GATHER)
+    assert g.decode_switch[1] == 0
+    for lp in range(w.L):
+        assert (g.y_hat[lp] == params["b_dec"][lp].numpy()[None, :]).all()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_gather_equals_dense(dtype):
+    w = S.scaled(S.WORKLOADS["tiny"], dtype=dtype, L=4, d=128, F=512, B=130, seed=79)
+    theta = sparse_theta(w, 0.03)
+    params = S.make_params(w)
+    x, y = S.make_inputs(w)
+    a = GpuRun(w, params, x, y, theta=theta, decode_mode=DENSE)
+    b = GpuRun(w, params, x, y, theta=theta, decode_mode=GATHER)
+    assert (a.z == b.z).all()
+    assert rel_l2(b.y_hat, a.y_hat) < 1e-5       # same fp32 sums, different order
+    c = GpuRun(w, params, x, y, theta=theta, decode_mode=GATHER)
+    assert (b.y_hat == c.y_hat).all()            # the gather path is deterministic
+
+
+def test_auto_switch_follows_measured_density():
+    w = S.scaled(S.WORKLOADS["tiny"], dtype="bf16", L=3, d=128, F=1024, B=256, seed=80)
+    params = S.make_params(w)
+    x, y = S.make_inputs(w)
+    # early-training density (about half the features active): dense path
+    g = GpuRun(w, params, x, y, decode_mode=AUTO, gather_density_threshold=0.02)
+    assert g.decode_switch[0] == 0 and g.decode_switch[2] == 1
+    # sparse regime: gather path, same result as the oracle
+    theta = sparse_theta(w, 0.01)
+    g = GpuRun(w, params, x, y, theta=theta, decode_mode=AUTO, gather_density_threshold=0.02)
+    o = OracleRun(w, params, x, y, gpu_active=g.active, gpu_window=g.window, theta=theta)
+    assert g.decode_switch[0] == 1 and g.decode_switch[2] == 2
+    show("auto -> gather", compare_step(w, g, o, TOL["bf16"]))
+    # one token with a huge norm lights up far more features than a capped list holds:
+    # the mean density is still below the threshold, but the step must decode densely
+    x2 = x.clone()
+    x2[:, 7, :] *= 300.0
+    x2 = x2.bfloat16().float()
+    g = GpuRun(w, params, x2, y, theta=theta, decode_mode=AUTO, gather_density_threshold=0.02)
+    o = OracleRun(w, params, x2, y, gpu_active=g.active, gpu_window=g.window, theta=theta)
+    kcap = (int(8.0 * 0.02 * w.F) + 64 + 7) // 8 * 8
+    assert g.decode_switch[0] == 1 and g.decode_switch[1] > kcap and g.decode_switch[2] == 1
+    show("auto -> dense fallback", compare_step(w, g, o, TOL["bf16"]))
+
+
 def test_rerun_is_bitwise_deterministic():
     w = S.scaled(S.WORKLOADS["gpt2"], L=3, d=256, F=512, B=300)
     params = S.make_params(w)
