@@ -54,6 +54,57 @@ def cpu_oracle_baseline(w, log):
                       f"measured {t_fb + t_adam:.1f}s, scaled by B*F (contractions) and F (Adam)"}
 
 
+def density_sweep(args, log):
+    """Sec. 3.2 crossover on this GPU: forward time of the dense decode against the
+    gather decode (compaction + gather) at forced activation densities, on the int8
+    Llama-shaped workload.  Prints one JSON line of its own."""
+    import torch
+    from paper_2603_21014_amd import binding as K
+    from workloads import clt_synth as S
+    w = S.WORKLOADS["llama1b_int8"]
+    dev, T = "cuda:0", torch.bfloat16
+    p32 = S.make_params(w, device=dev)
+    x32, y32 = S.make_inputs(w, device=dev)
+    xq, xs = S.quantize_rows_int8(x32)
+    xdq = xq.float() * xs[:, :, None]
+    params = {k: (v.to(T) if k in ("W_enc", "W_dec") else v) for k, v in p32.items()}
+    rows = []
+    steps = {name: K.CLTStep(w.L, w.d, w.F, w.B, dtype="bf16", int8_inputs=True, C_=w.C, ste_bandwidth=w.ste_eps,
+                             device=dev, keep_pre=False, decode_mode=mode)
+             for name, mode in (("dense", K.DECODE_DENSE), ("gather", K.DECODE_GATHER))}
+    for rho in (0.001, 0.0025, 0.005, 0.01, 0.05):
+        params["theta"] = S.theta_for_density(xdq, p32["W_enc"], p32["b_enc"], rho)
+        row = {"density": rho}
+        for name, st in steps.items():
+            for it in range(3):
+                if it == 1:
+                    K.clt_profile_enable(st.H, True)
+                st.forward(xq, params, xs)
+            torch.cuda.synchronize()
+            prof = K.clt_profile_query(st.H)
+            K.clt_profile_enable(st.H, False)
+            ms = {k: v[0] / max(v[1], 1) for k, v in prof.items()}
+            if name == "dense":
+                row["dense_decode_ms"] = round(ms["decode_gemm"], 3)
+            else:
+                row["gather_decode_ms"] = round(ms["compact_active"] + ms["gather_decode"], 3)
+                row["compact_ms"] = round(ms["compact_active"], 3)
+                k_mean = st.l0.double().mean().item() / w.B
+                row["active_per_token_layer"] = round(k_mean, 1)
+                gbytes = w.B * k_mean * w.P * w.d * 2.0
+                row["gather_GBps"] = round(gbytes / (ms["gather_decode"] * 1e-3) / 1e9, 1)
+        log(str(row))
+        rows.append(row)
+    cross = None
+    for a, b in zip(rows, rows[1:]):
+        fa, fb = a["gather_decode_ms"] - a["dense_decode_ms"], b["gather_decode_ms"] - b["dense_decode_ms"]
+        if fa <= 0 < fb:
+            tt = fa / (fa - fb)
+            cross = a["active_per_token_layer"] + tt * (b["active_per_token_layer"] - a["active_per_token_layer"])
+    print(json.dumps({"metric": "gather vs dense decode crossover (active features per token and layer)",
+                      "workload": w.name, "expansion": w.F / w.d, "crossover_k": cross, "rows": rows}), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -63,6 +114,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-timing", action="store_true",
                     help="skip the per-kernel HIP-event brackets (roofline entry becomes null)")
+    ap.add_argument("--density-sweep", action="store_true",
+                    help="time dense vs gather decode at forced densities instead of the train step")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         sys.exit("bench.py: this build runs the CLT train step on ONE GPU only (no sharding, no collectives); "
@@ -70,6 +123,9 @@ def main():
 
     def log(msg):
         print(f"[bench] {msg}", file=sys.stderr, flush=True)
+
+    if args.density_sweep:
+        return density_sweep(args, log)
 
     import torch
     from paper_2603_21014_amd import binding as K
