@@ -23,6 +23,25 @@ GEMM_PAIRS = {"encoder_jumprelu_gemm": "L", "dW_enc_gemm": "L", "decode_gemm": "
               "dW_dec_gemm": "P"}
 
 
+KERNEL_SYMBOL = {"decode_gemm": "gemm_bf16_kernel<DecPolicy>", "dz_gemm": "gemm_bf16_kernel<DzPolicy>",
+                 "dW_dec_gemm": "gemm_bf16_kernel<DWdecPolicy>", "encoder_jumprelu_gemm": "gemm_bf16_kernel<EncPolicy>",
+                 "dW_enc_gemm": "gemm_bf16_kernel<DWencPolicy>"}
+
+
+def profiled_traffic_bytes(workload, kernel):
+    """HBM-side bytes per launch of `kernel` from the committed rocprofv3 --pmc summary
+    (FETCH_SIZE + WRITE_SIZE, calibrated against a plain copy), or None."""
+    path = os.path.join(ROOT, "profiles", f"train_step_{workload}_hbm_traffic.md")
+    try:
+        for line in open(path):
+            cells = [c.strip() for c in line.split("|")]
+            if len(cells) > 3 and cells[1] == KERNEL_SYMBOL.get(kernel):
+                return (float(cells[2]) + float(cells[3])) * 1e9
+    except (OSError, ValueError):
+        pass
+    return None
+
+
 def cpu_oracle_baseline(w, log):
     """The oracle as it stands on a bounded sample of the workload: full L and d,
     F/16 features and B/16 tokens.  The contraction cost is linear in B*F, Adam
@@ -114,6 +133,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-timing", action="store_true",
                     help="skip the per-kernel HIP-event brackets (roofline entry becomes null)")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="end with one plain 1 GiB device copy (the last dispatch): reference for HBM byte counters")
     ap.add_argument("--density-sweep", action="store_true",
                     help="time dense vs gather decode at forced densities instead of the train step")
     args = ap.parse_args()
@@ -197,11 +218,19 @@ def main():
         dom = max((k for k in kernels if k in GEMM_PAIRS), key=lambda k: kernels[k]["avg_ms"])
         ach = kernels[dom]["tflops"]
         roof = {"kernel": dom, "bound": "mfma", "achieved": ach, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                "frac": round(ach / PEAK_BF16_TFLOPS, 4), "traffic": None,
+                "frac": round(ach / PEAK_BF16_TFLOPS, 4), "traffic": profiled_traffic_bytes(w.name, dom),
                 "avg_launch_ms": kernels[dom]["avg_ms"], "flop_per_launch": kernels[dom]["flop"]}
         for name, ent in sorted(kernels.items(), key=lambda kv: -kv[1]["avg_ms"] * kv[1]["launches_per_step"]):
             log(f"  {name:24s} {ent['avg_ms']:9.3f} ms x {ent['launches_per_step']:.0f}"
                 + (f"  {ent['tflops']:7.1f} TFLOP/s" if "tflops" in ent else ""))
+
+    if args.calibration_copy:
+        src = torch.empty(1 << 28, dtype=torch.int32, device=dev)
+        dst = torch.empty_like(src)
+        src.fill_(1)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
 
     cpu = None
     if not args.no_cpu_baseline:

@@ -18,26 +18,38 @@
 namespace clt {
 
 // Maps a workgroup index to (group order, tile row, tile column).
-// Workgroups are dealt round-robin to the 8 XCDs, each with a private L2, so
-// XCD x = wg % 8 takes a contiguous eighth of every group's tile list, and the
-// list itself runs through column panels SN tiles wide: the ~32 tiles an XCD
-// has in flight then form a compact 2-D block that shares few A and B panels.
+// Workgroups are dealt round-robin to the 8 XCDs, each with a private L2.  The
+// XCDs form teams of S (1, 2, 4 or 8): a team works on one group at a time and
+// each of its XCDs takes a contiguous 1/S of that group's tile list, sized so
+// that the ~32 tiles an XCD has in flight belong to one group.  The list runs
+// through column panels SN tiles wide, so those tiles form a compact 2-D block
+// that shares few A and B panels in the XCD's L2.  Groups arrive sorted by
+// decreasing K and are handed to the teams in snake order (0..n-1, n-1..0, ...),
+// which balances the teams' total work for the triangular sums.
 struct TileGrid {
-  int G, mt, nt, per_xcd;
+  int G, mt, nt, per_xcd, S, nteams, rounds;
   static constexpr int SN = 8;
   __host__ __device__ static TileGrid make(int G, int M, int N, int TM, int TN) {
     TileGrid t;
     t.G = G;
     t.mt = (M + TM - 1) / TM;
     t.nt = (N + TN - 1) / TN;
-    t.per_xcd = (t.mt * t.nt + 7) / 8;
+    const int tiles = t.mt * t.nt;
+    t.S = 1;
+    while (t.S < 8 && tiles > 32 * t.S) t.S *= 2;
+    t.nteams = 8 / t.S;
+    t.per_xcd = (tiles + t.S - 1) / t.S;
+    t.rounds = (G + t.nteams - 1) / t.nteams;
     return t;
   }
-  __host__ __device__ int num_wg() const { return G * per_xcd * 8; }
+  __host__ __device__ int num_wg() const { return rounds * per_xcd * 8; }
   __device__ bool decode(int wg, int& gorder, int& tm, int& tn) const {
     const int xcd = wg & 7, slot = wg >> 3;
-    gorder = slot / per_xcd;
-    const int t = xcd * per_xcd + (slot - gorder * per_xcd);
+    const int team = xcd / S, rank = xcd - team * S;
+    const int round = slot / per_xcd;
+    gorder = round * nteams + ((round & 1) ? nteams - 1 - team : team);
+    if (gorder >= G) return false;
+    const int t = rank * per_xcd + (slot - round * per_xcd);
     if (t >= mt * nt) return false;
     const int full = nt / SN, rem = nt - full * SN;
     const int tiles_full = full * mt * SN;
