@@ -142,6 +142,20 @@ int clt_adam_step(clt_handle* handle, void* stream, int64_t t, float lr,
                   const clt_tensors* params, const clt_tensors* grads,
                   const clt_tensors* m, const clt_tensors* v, const clt_tensors* master);
 
+/* clt_backward and clt_adam_step in one call, with the Adam update of W_enc and
+ * W_dec fused into the epilogues of the two weight-gradient GEMMs (App. C Table 1
+ * update rule on the fp32 accumulators): the matrix gradients are never stored
+ * unless grads->W_enc / grads->W_dec are given, and the weight, moment and master
+ * traffic of the optimiser runs under the contractions instead of after them.
+ * theta and W_dec are taken from params.  grads->b_enc, theta, b_dec are required
+ * (the vectors go through the separate Adam kernel).  Results equal the two
+ * separate calls except that the matrix gradients enter Adam in fp32 instead of
+ * after rounding to T. */
+int clt_backward_adam_step(clt_handle* handle, void* stream,
+                           const void* x, const float* x_scale, const void* z, const uint8_t* act_class,
+                           int64_t t, float lr, const clt_tensors* params, const clt_tensors* grads,
+                           const clt_tensors* m, const clt_tensors* v, const clt_tensors* master);
+
 /* Device pointers into the workspace, for inspection by tests and tools:
  * which = 0 decoder norms [L,F] float; 1 d y_hat [L,B,d] T; 2 d pre [L,B,F] T;
  * 3 sparsity column sums G [L,F] float; 4 decode switch, 4 int32: {gather allowed by

@@ -23,7 +23,7 @@ INPUT_NATIVE, INPUT_INT8_ROWSCALE = 0, 1
 DECODE_AUTO, DECODE_DENSE, DECODE_GATHER = 0, 1, 2
 
 EXPORTS = ("clt_workspace_bytes", "clt_init", "clt_destroy", "clt_last_error", "clt_forward",
-           "clt_loss", "clt_backward", "clt_adam_step", "clt_workspace_view",
+           "clt_loss", "clt_backward", "clt_adam_step", "clt_backward_adam_step", "clt_workspace_view",
            "clt_profile_enable", "clt_profile_num_kernels", "clt_profile_query")
 
 
@@ -59,6 +59,7 @@ def _load():
     lib.clt_loss.argtypes = [vp, vp, vp, fp, fp, vp, C.c_float, fp, C.POINTER(C.c_float)]
     lib.clt_backward.argtypes = [vp, vp, vp, fp, fp, vp, vp, vp, C.POINTER(clt_tensors)]
     lib.clt_adam_step.argtypes = [vp, vp, C.c_int64, C.c_float] + [C.POINTER(clt_tensors)] * 5
+    lib.clt_backward_adam_step.argtypes = [vp, vp, vp, fp, vp, vp, C.c_int64, C.c_float] + [C.POINTER(clt_tensors)] * 5
     lib.clt_workspace_view.argtypes = [vp, C.c_int, C.POINTER(vp), C.POINTER(C.c_size_t)]
     lib.clt_profile_enable.argtypes = [vp, C.c_int]
     lib.clt_profile_num_kernels.argtypes = []
@@ -201,6 +202,28 @@ def clt_adam_step(H: Handle, t: int, lr: float, params: dict, grads: dict, m: di
     _check(rc, H.h)
 
 
+def clt_backward_adam_step(H: Handle, x, z, act_class, t: int, lr: float, params: dict, grads: dict, m: dict, v: dict,
+                           master: dict = None, x_scale=None):
+    """grads must hold b_enc, theta, b_dec; W_enc / W_dec entries are optional (written when present)."""
+    s, f32 = H.shapes, torch.float32
+    p = _tensors(H, params, "params", H.T)
+    mm = _tensors(H, m, "m", f32)
+    vv = _tensors(H, v, "v", f32)
+    ms = _tensors(H, master, "master", f32, matrices_only=True) if master is not None else None
+    g = clt_tensors()
+    g.b_enc = _ptr(grads["b_enc"], s["b_enc"], f32, "grads.b_enc")
+    g.theta = _ptr(grads["theta"], s["theta"], f32, "grads.theta")
+    g.b_dec = _ptr(grads["b_dec"], s["b_dec"], f32, "grads.b_dec")
+    g.W_enc = _ptr(grads.get("W_enc"), s["W_enc"], H.T, "grads.W_enc", True)
+    g.W_dec = _ptr(grads.get("W_dec"), s["W_dec"], H.T, "grads.W_dec", True)
+    rc = _lib.clt_backward_adam_step(H.h, _stream(), _ptr(x, s["x"], H.TX, "x"),
+                                     _ptr(x_scale, s["scale"], f32, "x_scale", True), _ptr(z, s["z"], H.T, "z"),
+                                     _ptr(act_class, s["z"], torch.uint8, "act_class"), int(t), float(lr),
+                                     C.byref(p), C.byref(g), C.byref(mm), C.byref(vv),
+                                     C.byref(ms) if ms is not None else None)
+    _check(rc, H.h)
+
+
 _VIEWS = {"norms": (0, torch.float32, lambda c: (c.L, c.F)), "d_yhat": (1, None, lambda c: (c.L, c.B, c.d)),
           "dpre": (2, None, lambda c: (c.L, c.B, c.F)), "G": (3, torch.float32, lambda c: (c.L, c.F)),
           "decode_switch": (4, torch.int32, lambda c: (4,))}
@@ -235,7 +258,7 @@ class CLTStep:
 
     def __init__(self, L, d, F, B, dtype="bf16", int8_inputs=False, master_weights=False, C_=4.0,
                  ste_bandwidth=0.05, beta1=0.9, beta2=0.999, adam_eps=1e-8, device="cuda:0", keep_pre=True,
-                 decode_mode=DECODE_DENSE, gather_density_threshold=0.005):
+                 decode_mode=DECODE_DENSE, gather_density_threshold=0.005, matrix_grads=True):
         dt = DTYPE_BF16 if dtype == "bf16" else DTYPE_F32
         self.cfg = make_config(L, d, F, B, dt, INPUT_INT8_ROWSCALE if int8_inputs else INPUT_NATIVE,
                                master_weights, decode_mode, gather_density_threshold, C_, ste_bandwidth, beta1,
@@ -252,9 +275,11 @@ class CLTStep:
         self.y_hat = e(L, B, d, dtype=torch.float32)
         self.l0 = e(L, dtype=torch.int32)
         self.loss_dev = e(3, dtype=torch.float32)
-        self.grads = {"W_enc": e(L, d, F), "b_enc": e(L, F, dtype=torch.float32),
-                      "theta": e(L, F, dtype=torch.float32), "W_dec": e(P, F, d),
+        self.grads = {"b_enc": e(L, F, dtype=torch.float32), "theta": e(L, F, dtype=torch.float32),
                       "b_dec": e(L, d, dtype=torch.float32)}
+        if matrix_grads:    # not needed by the fused backward + Adam path
+            self.grads["W_enc"] = e(L, d, F)
+            self.grads["W_dec"] = e(P, F, d)
 
     def forward(self, x, params, x_scale=None):
         clt_forward(self.H, x, params["W_enc"], params["b_enc"], params["theta"], params["W_dec"], params["b_dec"],
@@ -269,8 +294,15 @@ class CLTStep:
     def adam_step(self, t, lr, params, m, v, master=None):
         clt_adam_step(self.H, t, lr, params, self.grads, m, v, master)
 
-    def train_step(self, x, y, params, m, v, t, lr, lambda0, master=None, x_scale=None, y_scale=None):
+    def backward_adam_step(self, x, params, m, v, t, lr, master=None, x_scale=None):
+        clt_backward_adam_step(self.H, x, self.z, self.act_class, t, lr, params, self.grads, m, v, master, x_scale)
+
+    def train_step(self, x, y, params, m, v, t, lr, lambda0, master=None, x_scale=None, y_scale=None, fused=True):
+        """forward, loss, backward and Adam; `fused` runs Adam inside the weight-gradient GEMMs."""
         self.forward(x, params, x_scale)
         self.loss(y, lambda0, y_scale)
-        self.backward(x, params, x_scale)
-        self.adam_step(t, lr, params, m, v, master)
+        if fused:
+            self.backward_adam_step(x, params, m, v, t, lr, master, x_scale)
+        else:
+            self.backward(x, params, x_scale)
+            self.adam_step(t, lr, params, m, v, master)

@@ -383,16 +383,13 @@ int clt_loss(clt_handle* h, void* stream, const void* y, const float* y_scale, c
   return CLT_OK;
 }
 
-int clt_backward(clt_handle* h, void* stream, const void* x, const float* x_scale, const float* theta,
-                 const void* W_dec, const void* z, const uint8_t* act_class, const clt_tensors* grads) {
-  if (!h) { set_err(g_err, "clt_backward: handle is NULL"); return CLT_ERR_INVALID_ARG; }
-  REQ(h, x); REQ(h, theta); REQ(h, W_dec); REQ(h, z); REQ(h, act_class);
-  if (h->int8) REQ(h, x_scale);
-  else if (x_scale) { set_err(h->err, "clt_backward: x_scale given but input_format is native"); return CLT_ERR_INVALID_ARG; }
-  int rc = check_tensors(h, "grads", grads, false);
-  if (rc != CLT_OK) return rc;
-  if (h->stage < 2) { set_err(h->err, "clt_backward: call clt_forward and clt_loss first"); return CLT_ERR_STATE; }
-  hipStream_t s = static_cast<hipStream_t>(stream);
+// Backward kernels in stream order.  With `fuse` set, the Adam update of W_enc and
+// W_dec happens in the epilogues of the two weight-gradient GEMMs (the matrix
+// gradients are written only where gW_enc / gW_dec are not NULL).
+static int backward_impl(clt_handle* h, hipStream_t s, const void* x, const float* x_scale, const float* theta,
+                         void* W_dec, void* W_enc, const void* z, const uint8_t* act_class, void* gW_enc,
+                         float* gb_enc, float* gtheta, void* gW_dec, float* gb_dec, const AdamFuseArgs& fenc,
+                         const AdamFuseArgs& fdec) {
   const Dims D = h->D;
   const int rbs = row_blocks(D.B);
   float* norms = reinterpret_cast<float*>(h->ws + h->plan.norms);
@@ -403,14 +400,14 @@ int clt_backward(clt_handle* h, void* stream, const void* x, const float* x_scal
   void* dpre = h->ws + h->plan.dpre;
 
   // db_dec from the column partials that clt_loss left behind
-  RUN(h, s, K_COLRED, launch_col_reduce(s, part, rbs, D.L * D.d, 1.0f, nullptr, 0.f, grads->b_dec));
+  RUN(h, s, K_COLRED, launch_col_reduce(s, part, rbs, D.L * D.d, 1.0f, nullptr, 0.f, gb_dec));
   DzArgs za{d_yhat, W_dec, z, act_class, norms, h->lambda0 * h->cfg.C / (float)D.B, h->cfg.C, dpre};
-  DWdecArgs wa{z, d_yhat, W_dec, G, norms, grads->W_dec};
-  DWencArgs ea{x, dpre, grads->W_enc};
+  DWdecArgs wa{z, d_yhat, W_dec, G, norms, gW_dec, fdec};
+  DWencArgs ea{x, dpre, gW_enc, W_enc, fenc};
   if (h->bf16) RUN(h, s, K_DZ, launch_dz_bf16(s, D, za)); else RUN(h, s, K_DZ, launch_dz_f32(s, D, za));
   RUN(h, s, K_STE, launch_ste_reduce(s, h->bf16, D, dpre, act_class, h->int8 ? x_scale : nullptr, part, part2));
-  RUN(h, s, K_COLRED, launch_col_reduce(s, part, rbs, D.L * D.F, 1.0f, theta, 1.0f / h->cfg.ste_bandwidth, grads->theta));
-  RUN(h, s, K_COLRED, launch_col_reduce(s, part2, rbs, D.L * D.F, 1.0f, nullptr, 0.f, grads->b_enc));
+  RUN(h, s, K_COLRED, launch_col_reduce(s, part, rbs, D.L * D.F, 1.0f, theta, 1.0f / h->cfg.ste_bandwidth, gtheta));
+  RUN(h, s, K_COLRED, launch_col_reduce(s, part2, rbs, D.L * D.F, 1.0f, nullptr, 0.f, gb_enc));
   if (h->bf16) {
     RUN(h, s, K_DWENC, launch_dwenc_bf16(s, D, ea, h->int8));
     RUN(h, s, K_DWDEC, launch_dwdec_bf16(s, D, wa));
@@ -419,6 +416,72 @@ int clt_backward(clt_handle* h, void* stream, const void* x, const float* x_scal
     RUN(h, s, K_DWDEC, launch_dwdec_f32(s, D, wa));
   }
   h->stage = 1;   // the loss by-products are consumed; a new clt_loss is needed before the next backward
+  return CLT_OK;
+}
+
+static AdamScalars adam_scalars(const clt_handle* h, int64_t t, float lr) {
+  AdamScalars a;
+  a.lr = lr; a.beta1 = h->cfg.beta1; a.beta2 = h->cfg.beta2; a.eps = h->cfg.adam_eps;
+  a.bc1 = (float)(1.0 - pow((double)h->cfg.beta1, (double)t));
+  a.bc2 = (float)(1.0 - pow((double)h->cfg.beta2, (double)t));
+  return a;
+}
+
+int clt_backward(clt_handle* h, void* stream, const void* x, const float* x_scale, const float* theta,
+                 const void* W_dec, const void* z, const uint8_t* act_class, const clt_tensors* grads) {
+  if (!h) { set_err(g_err, "clt_backward: handle is NULL"); return CLT_ERR_INVALID_ARG; }
+  REQ(h, x); REQ(h, theta); REQ(h, W_dec); REQ(h, z); REQ(h, act_class);
+  if (h->int8) REQ(h, x_scale);
+  else if (x_scale) { set_err(h->err, "clt_backward: x_scale given but input_format is native"); return CLT_ERR_INVALID_ARG; }
+  int rc = check_tensors(h, "grads", grads, false);
+  if (rc != CLT_OK) return rc;
+  if (h->stage < 2) { set_err(h->err, "clt_backward: call clt_forward and clt_loss first"); return CLT_ERR_STATE; }
+  const AdamFuseArgs none{nullptr, nullptr, nullptr, AdamScalars{}};
+  return backward_impl(h, static_cast<hipStream_t>(stream), x, x_scale, theta, const_cast<void*>(W_dec), nullptr, z,
+                       act_class, grads->W_enc, grads->b_enc, grads->theta, grads->W_dec, grads->b_dec, none, none);
+}
+
+int clt_backward_adam_step(clt_handle* h, void* stream, const void* x, const float* x_scale, const void* z,
+                           const uint8_t* act_class, int64_t t, float lr, const clt_tensors* params,
+                           const clt_tensors* grads, const clt_tensors* m, const clt_tensors* v,
+                           const clt_tensors* master) {
+  if (!h) { set_err(g_err, "clt_backward_adam_step: handle is NULL"); return CLT_ERR_INVALID_ARG; }
+  REQ(h, x); REQ(h, z); REQ(h, act_class);
+  if (h->int8) REQ(h, x_scale);
+  else if (x_scale) { set_err(h->err, "clt_backward_adam_step: x_scale given but input_format is native"); return CLT_ERR_INVALID_ARG; }
+  if (t < 1) { set_err(h->err, "clt_backward_adam_step: step count t must be >= 1"); return CLT_ERR_INVALID_ARG; }
+  if (!(lr >= 0.f)) { set_err(h->err, "clt_backward_adam_step: lr must be >= 0"); return CLT_ERR_INVALID_ARG; }
+  int rc;
+  if ((rc = check_tensors(h, "params", params, false)) != CLT_OK) return rc;
+  if ((rc = check_tensors(h, "m", m, false)) != CLT_OK) return rc;
+  if ((rc = check_tensors(h, "v", v, false)) != CLT_OK) return rc;
+  if (!grads || !grads->b_enc || !grads->theta || !grads->b_dec) {
+    set_err(h->err, "clt_backward_adam_step: grads->b_enc, theta and b_dec are required");
+    return CLT_ERR_INVALID_ARG;
+  }
+  if (misaligned(grads->b_enc) || misaligned(grads->theta) || misaligned(grads->b_dec) ||
+      (grads->W_enc && misaligned(grads->W_enc)) || (grads->W_dec && misaligned(grads->W_dec))) {
+    set_err(h->err, "clt_backward_adam_step: a gradient pointer is not 16-byte aligned");
+    return CLT_ERR_ALIGN;
+  }
+  if (h->cfg.master_weights) {
+    if ((rc = check_tensors(h, "master", master, true)) != CLT_OK) return rc;
+  } else if (master) {
+    set_err(h->err, "clt_backward_adam_step: master given but config.master_weights is 0");
+    return CLT_ERR_INVALID_ARG;
+  }
+  if (h->stage < 2) { set_err(h->err, "clt_backward_adam_step: call clt_forward and clt_loss first"); return CLT_ERR_STATE; }
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const Dims D = h->D;
+  const AdamScalars a = adam_scalars(h, t, lr);
+  const AdamFuseArgs fenc{(float*)m->W_enc, (float*)v->W_enc, master ? (float*)master->W_enc : nullptr, a};
+  const AdamFuseArgs fdec{(float*)m->W_dec, (float*)v->W_dec, master ? (float*)master->W_dec : nullptr, a};
+  rc = backward_impl(h, s, x, x_scale, params->theta, params->W_dec, params->W_enc, z, act_class, grads->W_enc,
+                     grads->b_enc, grads->theta, grads->W_dec, grads->b_dec, fenc, fdec);
+  if (rc != CLT_OK) return rc;
+  RUN(h, s, K_ADAM_VEC, launch_adam_vector(s, (size_t)D.L * D.F, params->b_enc, grads->b_enc, m->b_enc, v->b_enc, a));
+  RUN(h, s, K_ADAM_VEC, launch_adam_vector(s, (size_t)D.L * D.F, params->theta, grads->theta, m->theta, v->theta, a));
+  RUN(h, s, K_ADAM_VEC, launch_adam_vector(s, (size_t)D.L * D.d, params->b_dec, grads->b_dec, m->b_dec, v->b_dec, a));
   return CLT_OK;
 }
 
@@ -440,10 +503,7 @@ int clt_adam_step(clt_handle* h, void* stream, int64_t t, float lr, const clt_te
   }
   hipStream_t s = static_cast<hipStream_t>(stream);
   const Dims D = h->D;
-  AdamScalars a;
-  a.lr = lr; a.beta1 = h->cfg.beta1; a.beta2 = h->cfg.beta2; a.eps = h->cfg.adam_eps;
-  a.bc1 = (float)(1.0 - pow((double)h->cfg.beta1, (double)t));
-  a.bc2 = (float)(1.0 - pow((double)h->cfg.beta2, (double)t));
+  const AdamScalars a = adam_scalars(h, t, lr);
   const size_t n_enc = (size_t)D.L * D.d * D.F, n_dec = (size_t)D.P() * D.F * D.d;
   RUN(h, s, K_ADAM_WDEC, launch_adam_matrix(s, h->bf16, n_dec, params->W_dec, grads->W_dec, (float*)m->W_dec, (float*)v->W_dec,
                                master ? (float*)master->W_dec : nullptr, a));

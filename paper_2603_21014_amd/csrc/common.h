@@ -56,6 +56,8 @@ template <> struct Elem<bf16_t> {
   }
 };
 
+struct AdamScalars { float lr, beta1, beta2, eps, bc1, bc2; };   // bc = 1 - beta^t
+
 // act_class bits
 constexpr uint8_t CLS_ACTIVE = 1;
 constexpr uint8_t CLS_WINDOW = 2;
@@ -77,11 +79,15 @@ struct DzArgs {        // dz[l] = sum_{lp>=l} dyhat[lp] W_dec[p(l,lp)]^T + g_sp,
   const void* d_yhat; const void* W_dec; const void* z; const uint8_t* cls; const float* norms;
   float lam_c_over_b; float C; void* dpre;
 };
+// Optional Adam fused into the two weight-gradient GEMMs (m == nullptr: plain gradient output)
+struct AdamFuseArgs { float* m; float* v; float* master; AdamScalars a; };
 struct DWdecArgs {     // dW_dec[p] = z[l]^T dyhat[lp] + (G/n)[l,f] W_dec[p][f,:]
-  const void* z; const void* d_yhat; const void* W_dec; const float* G; const float* norms; void* dW_dec;
+  const void* z; const void* d_yhat; void* W_dec; const float* G; const float* norms; void* dW_dec;
+  AdamFuseArgs fuse;
 };
 struct DWencArgs {     // dW_enc[l] = x[l]^T dpre[l]
-  const void* x; const void* dpre; void* dW_enc;
+  const void* x; const void* dpre; void* dW_enc; void* W_enc;
+  AdamFuseArgs fuse;
 };
 
 hipError_t launch_enc_f32(hipStream_t s, Dims D, const EncArgs& a);
@@ -120,7 +126,6 @@ hipError_t launch_col_reduce(hipStream_t s, const float* part, int nparts, int n
 hipError_t launch_ste_reduce(hipStream_t s, bool bf16, Dims D, void* dpre, const uint8_t* cls,
                              const float* row_scale_or_null, float* part_theta, float* part_benc);
 
-struct AdamScalars { float lr, beta1, beta2, eps, bc1, bc2; };   // bc = 1 - beta^t
 // p, g in T (or p in T with fp32 master); m, v float
 hipError_t launch_adam_matrix(hipStream_t s, bool bf16, size_t n, void* p, const void* g, float* m, float* v,
                               float* master_or_null, AdamScalars a);

@@ -11,7 +11,10 @@
 //   M, N, kseg   tile-space extents and the length of one K segment
 //   ginfo(order) group visited at position `order` of the launch (longest K first)
 //   nseg(gi), a_seg(gi,s), b_seg(gi,s)   K segments of a group
-//   epi4(st, gi, row, col, v)  consumes 4 accumulators of one row, columns col..col+3
+//   epi_load(regs, gi, row, col)  issues the global loads the epilogue of that 4-column
+//                group needs (the kernels call it for a batch of groups first, so the
+//                loads of the whole batch of EPI_BATCH groups are in flight together)
+//   epi4(st, gi, row, col, v, regs)  consumes 4 accumulators of one row, columns col..col+3
 #pragma once
 #include "common.h"
 
@@ -66,6 +69,38 @@ struct TileGrid {
   }
 };
 
+// Adam fused into a weight-gradient epilogue: the fp32 gradient of 4 consecutive
+// parameters goes straight from the accumulators into the moments and the
+// weights (App. C Table 1 update rule; same arithmetic as adam_kernel).
+struct AdamFuse {
+  float* m; float* v; float* master; AdamScalars a;   // m == nullptr: not fused
+};
+struct AdamRegs { float4 m, v, p; };   // moments and the fp32 parameter (master copy or widened weight)
+template <typename T>
+__device__ __forceinline__ void adam_load4(AdamRegs& r, const AdamFuse& f, const T* w, size_t o) {
+  r.m = *reinterpret_cast<const float4*>(f.m + o);
+  r.v = *reinterpret_cast<const float4*>(f.v + o);
+  r.p = f.master ? *reinterpret_cast<const float4*>(f.master + o) : Elem<T>::load4(w + o);
+}
+template <typename T>
+__device__ __forceinline__ void adam_update4(const AdamFuse& f, T* w, size_t o, const AdamRegs& r, float4 g4) {
+  const float inv_bc1 = 1.0f / f.a.bc1, inv_bc2 = 1.0f / f.a.bc2;
+  const float4 m4 = r.m, v4 = r.v, p4 = r.p;
+  const float g[4] = {g4.x, g4.y, g4.z, g4.w};
+  float mm[4] = {m4.x, m4.y, m4.z, m4.w}, vv[4] = {v4.x, v4.y, v4.z, v4.w}, pp[4] = {p4.x, p4.y, p4.z, p4.w};
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    mm[k] = f.a.beta1 * mm[k] + (1.0f - f.a.beta1) * g[k];
+    vv[k] = f.a.beta2 * vv[k] + (1.0f - f.a.beta2) * g[k] * g[k];
+    pp[k] -= f.a.lr * (mm[k] * inv_bc1) / (sqrtf(vv[k] * inv_bc2) + f.a.eps);
+  }
+  *reinterpret_cast<float4*>(f.m + o) = make_float4(mm[0], mm[1], mm[2], mm[3]);
+  *reinterpret_cast<float4*>(f.v + o) = make_float4(vv[0], vv[1], vv[2], vv[3]);
+  const float4 pn = make_float4(pp[0], pp[1], pp[2], pp[3]);
+  if (f.master) *reinterpret_cast<float4*>(f.master + o) = pn;
+  Elem<T>::store4(w + o, pn);
+}
+
 __device__ __forceinline__ uint32_t pack_u8x4(uint32_t a, uint32_t b, uint32_t c, uint32_t d) {
   return a | (b << 8) | (c << 16) | (d << 24);
 }
@@ -88,13 +123,19 @@ struct EncPolicy {
   __device__ int nseg(const GInfo&) const { return 1; }
   __device__ const TA* a_seg(const GInfo& g, int) const { return x + (size_t)g.l * D.B * D.d; }
   __device__ const T* b_seg(const GInfo& g, int) const { return W_enc + (size_t)g.l * D.d * D.F; }
+  static constexpr int EPI_BATCH = 8;
+  struct EpiRegs { float4 b, th; float s; };
   __device__ void epi_begin(Epi& e) const { e.count = 0; }
-  __device__ void epi4(Epi& e, const GInfo& g, int row, int col, float4 v) const {
+  __device__ void epi_load(EpiRegs& r, const GInfo& g, int row, int col) const {
     const size_t vo = (size_t)g.l * D.F + col;
-    const float4 b = *reinterpret_cast<const float4*>(b_enc + vo);
-    const float4 th = *reinterpret_cast<const float4*>(theta + vo);
+    r.b = *reinterpret_cast<const float4*>(b_enc + vo);
+    r.th = *reinterpret_cast<const float4*>(theta + vo);
+    r.s = x_scale ? x_scale[(size_t)g.l * D.B + row] : 1.0f;
+  }
+  __device__ void epi4(Epi& e, const GInfo& g, int row, int col, float4 v, const EpiRegs& r) const {
+    const float4 b = r.b, th = r.th;
     if (x_scale) {   // int8 codes: the row scale multiplies the integer dot product
-      const float s = x_scale[(size_t)g.l * D.B + row];
+      const float s = r.s;
       v.x *= s; v.y *= s; v.z *= s; v.w *= s;
     }
     float p[4] = {v.x + b.x, v.y + b.y, v.z + b.z, v.w + b.w};
@@ -144,9 +185,14 @@ struct DecPolicy {
   __device__ const T* b_seg(const GInfo& g, int s) const {
     return W_dec + (size_t)packed_index(s, g.lp, D.L) * D.F * D.d;
   }
+  static constexpr int EPI_BATCH = 8;
+  struct EpiRegs { float4 b; };
   __device__ void epi_begin(Epi&) const {}
-  __device__ void epi4(Epi&, const GInfo& g, int row, int col, float4 v) const {
-    const float4 b = *reinterpret_cast<const float4*>(b_dec + (size_t)g.lp * D.d + col);
+  __device__ void epi_load(EpiRegs& r, const GInfo& g, int, int col) const {
+    r.b = *reinterpret_cast<const float4*>(b_dec + (size_t)g.lp * D.d + col);
+  }
+  __device__ void epi4(Epi&, const GInfo& g, int row, int col, float4 v, const EpiRegs& r) const {
+    const float4 b = r.b;
     *reinterpret_cast<float4*>(y_hat + ((size_t)g.lp * D.B + row) * D.d + col) =
         make_float4(v.x + b.x, v.y + b.y, v.z + b.z, v.w + b.w);
   }
@@ -174,14 +220,22 @@ struct DzPolicy {
   __device__ const T* b_seg(const GInfo& g, int s) const {
     return W_dec + (size_t)packed_index(g.l, g.l + s, D.L) * D.F * D.d;
   }
+  static constexpr int EPI_BATCH = 8;
+  struct EpiRegs { uint32_t c4; float4 z4, n4; };
   __device__ void epi_begin(Epi&) const {}
-  __device__ void epi4(Epi&, const GInfo& g, int row, int col, float4 v) const {
+  __device__ void epi_load(EpiRegs& r, const GInfo& g, int row, int col) const {
     const size_t o = ((size_t)g.l * D.B + row) * D.F + col;
-    const uint32_t c4 = *reinterpret_cast<const uint32_t*>(cls + o);
+    r.c4 = *reinterpret_cast<const uint32_t*>(cls + o);
+    r.z4 = Elem<T>::load4(z + o);
+    r.n4 = *reinterpret_cast<const float4*>(norms + (size_t)g.l * D.F + col);
+  }
+  __device__ void epi4(Epi&, const GInfo& g, int row, int col, float4 v, const EpiRegs& r) const {
+    const size_t o = ((size_t)g.l * D.B + row) * D.F + col;
+    const uint32_t c4 = r.c4;
     float4 out = make_float4(0.f, 0.f, 0.f, 0.f);
     if (c4) {
-      const float4 z4 = Elem<T>::load4(z + o);
-      const float4 n4 = *reinterpret_cast<const float4*>(norms + (size_t)g.l * D.F + col);
+      const float4 z4 = r.z4;
+      const float4 n4 = r.n4;
       const float zz[4] = {z4.x, z4.y, z4.z, z4.w}, nn[4] = {n4.x, n4.y, n4.z, n4.w};
       const float vv[4] = {v.x, v.y, v.z, v.w};
       float r[4];
@@ -207,25 +261,38 @@ struct DWdecPolicy {
   typedef T AType;
   Dims D;
   int M, N, kseg, lda, ldb;
-  const T* z; const T* d_yhat; const T* W_dec; const float* G; const float* norms; T* dW_dec;
+  const T* z; const T* d_yhat; T* W_dec; const float* G; const float* norms; T* dW_dec;   // dW_dec may be NULL when fused
+  AdamFuse fuse;
+  int p0;   // first decoder block of this launch (launches cover one source layer each)
   __device__ bool skip() const { return false; }
   struct GInfo { int p, l, lp; };
   struct Epi {};
   __device__ GInfo ginfo(int order) const {
-    int l = 0, r = order;
+    int l = 0, r = order + p0;
     while (r >= D.L - l) { r -= D.L - l; ++l; }
-    return {order, l, l + r};
+    return {order + p0, l, l + r};
   }
   __device__ int nseg(const GInfo&) const { return 1; }
   __device__ const T* a_seg(const GInfo& g, int) const { return z + (size_t)g.l * D.B * D.F; }
   __device__ const T* b_seg(const GInfo& g, int) const { return d_yhat + (size_t)g.lp * D.B * D.d; }
+  static constexpr int EPI_BATCH = 4;   // 18 registers per group: keep the batch within the register budget
+  struct EpiRegs { float Gf, nf; float4 w; AdamRegs ad; };
   __device__ void epi_begin(Epi&) const {}
-  __device__ void epi4(Epi&, const GInfo& g, int row, int col, float4 v) const {
+  __device__ void epi_load(EpiRegs& r, const GInfo& g, int row, int col) const {
     const size_t nf = (size_t)g.l * D.F + row;
-    const float coef = G[nf] / fmaxf(norms[nf], 1e-30f);
+    r.Gf = G[nf];
+    r.nf = norms[nf];
     const size_t o = ((size_t)g.p * D.F + row) * D.d + col;
-    const float4 w = Elem<T>::load4(W_dec + o);
-    Elem<T>::store4(dW_dec + o, make_float4(v.x + coef * w.x, v.y + coef * w.y, v.z + coef * w.z, v.w + coef * w.w));
+    r.w = Elem<T>::load4(W_dec + o);
+    if (fuse.m) adam_load4<T>(r.ad, fuse, W_dec, o);
+  }
+  __device__ void epi4(Epi&, const GInfo& g, int row, int col, float4 v, const EpiRegs& r) const {
+    const float coef = r.Gf / fmaxf(r.nf, 1e-30f);
+    const size_t o = ((size_t)g.p * D.F + row) * D.d + col;
+    const float4 w = r.w;
+    const float4 gr = make_float4(v.x + coef * w.x, v.y + coef * w.y, v.z + coef * w.z, v.w + coef * w.w);
+    if (dW_dec) Elem<T>::store4(dW_dec + o, gr);
+    if (fuse.m) adam_update4<T>(fuse, W_dec, o, r.ad, gr);
   }
   __device__ void epi_end(Epi&, const GInfo&) const {}
 };
@@ -239,7 +306,8 @@ struct DWencPolicy {
   typedef TA AType;
   Dims D;
   int M, N, kseg, lda, ldb;
-  const TA* x; const T* dpre; T* dW_enc;
+  const TA* x; const T* dpre; T* dW_enc;   // dW_enc may be NULL when fused
+  T* W_enc; AdamFuse fuse;
   __device__ bool skip() const { return false; }
   struct GInfo { int l; };
   struct Epi {};
@@ -247,9 +315,16 @@ struct DWencPolicy {
   __device__ int nseg(const GInfo&) const { return 1; }
   __device__ const TA* a_seg(const GInfo& g, int) const { return x + (size_t)g.l * D.B * D.d; }
   __device__ const T* b_seg(const GInfo& g, int) const { return dpre + (size_t)g.l * D.B * D.F; }
+  static constexpr int EPI_BATCH = 4;
+  struct EpiRegs { AdamRegs ad; };
   __device__ void epi_begin(Epi&) const {}
-  __device__ void epi4(Epi&, const GInfo& g, int row, int col, float4 v) const {
-    Elem<T>::store4(dW_enc + ((size_t)g.l * D.d + row) * D.F + col, v);
+  __device__ void epi_load(EpiRegs& r, const GInfo& g, int row, int col) const {
+    if (fuse.m) adam_load4<T>(r.ad, fuse, W_enc, ((size_t)g.l * D.d + row) * D.F + col);
+  }
+  __device__ void epi4(Epi&, const GInfo& g, int row, int col, float4 v, const EpiRegs& r) const {
+    const size_t o = ((size_t)g.l * D.d + row) * D.F + col;
+    if (dW_enc) Elem<T>::store4(dW_enc + o, v);
+    if (fuse.m) adam_update4<T>(fuse, W_enc, o, r.ad, v);
   }
   __device__ void epi_end(Epi&, const GInfo&) const {}
 };

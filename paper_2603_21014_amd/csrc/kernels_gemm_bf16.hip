@@ -325,12 +325,22 @@ __global__ __launch_bounds__(NTHREADS) void gemm_bf16_kernel(P p, TileGrid tg) {
       for (int r = 0; r < 16; ++r)
         wl[(8 * (r >> 2) + 4 * (lane >> 5) + (r & 3)) * 64 + j * 32 + (lane & 31)] = acc[i][j][r];
     __syncthreads();
+    constexpr int EB = P::EPI_BATCH;   // epilogue loads of EB row groups are issued before any is used
 #pragma unroll
-    for (int it = 0; it < 8; ++it) {
-      const int row = it * 4 + (lane >> 4);
-      const int grow = m0 + wm * 128 + i * 32 + row;
-      const float4 v = *reinterpret_cast<const float4*>(wl + row * 64 + c4);
-      if (grow < M && gcol < N) p.epi4(est, gi, grow, gcol, v);
+    for (int it0 = 0; it0 < 8; it0 += EB) {
+      typename P::EpiRegs er[EB];
+#pragma unroll
+      for (int u = 0; u < EB; ++u) {
+        const int grow = m0 + wm * 128 + i * 32 + (it0 + u) * 4 + (lane >> 4);
+        if (grow < M && gcol < N) p.epi_load(er[u], gi, grow, gcol);
+      }
+#pragma unroll
+      for (int u = 0; u < EB; ++u) {
+        const int row = (it0 + u) * 4 + (lane >> 4);
+        const int grow = m0 + wm * 128 + i * 32 + row;
+        const float4 v = *reinterpret_cast<const float4*>(wl + row * 64 + c4);
+        if (grow < M && gcol < N) p.epi4(est, gi, grow, gcol, v, er[u]);
+      }
     }
     __syncthreads();
   }
@@ -388,17 +398,25 @@ hipError_t launch_dz_bf16(hipStream_t s, Dims D, const DzArgs& a) {
 }
 hipError_t launch_dwdec_bf16(hipStream_t s, Dims D, const DWdecArgs& a) {
   DWdecPolicy<bf16_t> p{D, D.F, D.d, D.B, D.F, D.d,
-                        (const bf16_t*)a.z, (const bf16_t*)a.d_yhat, (const bf16_t*)a.W_dec, a.G, a.norms,
-                        (bf16_t*)a.dW_dec};
-  return launch(s, p, D.P());
+                        (const bf16_t*)a.z, (const bf16_t*)a.d_yhat, (bf16_t*)a.W_dec, a.G, a.norms,
+                        (bf16_t*)a.dW_dec, AdamFuse{a.fuse.m, a.fuse.v, a.fuse.master, a.fuse.a}, 0};
+  // One launch per source layer: tiles that share operand panels start together again at every
+  // launch, which keeps them in step along K and so keeps the panel reuse in the XCDs' L2s
+  // (over one long launch the 256 short tiles per block drift apart and the reuse is lost).
+  for (int l = 0; l < D.L; ++l) {
+    p.p0 = packed_index(l, l, D.L);
+    const hipError_t e = launch(s, p, D.L - l);
+    if (e != hipSuccess) return e;
+  }
+  return hipSuccess;
 }
 hipError_t launch_dwenc_bf16(hipStream_t s, Dims D, const DWencArgs& a, bool int8_x) {
   if (int8_x) {
     DWencPolicy<bf16_t, int8_t> p{D, D.d, D.F, D.B, D.d, D.F, (const int8_t*)a.x, (const bf16_t*)a.dpre,
-                                  (bf16_t*)a.dW_enc};
+                                  (bf16_t*)a.dW_enc, (bf16_t*)a.W_enc, AdamFuse{a.fuse.m, a.fuse.v, a.fuse.master, a.fuse.a}};
     return launch(s, p, D.L);
   }
-  DWencPolicy<bf16_t> p{D, D.d, D.F, D.B, D.d, D.F, (const bf16_t*)a.x, (const bf16_t*)a.dpre, (bf16_t*)a.dW_enc};
+  DWencPolicy<bf16_t> p{D, D.d, D.F, D.B, D.d, D.F, (const bf16_t*)a.x, (const bf16_t*)a.dpre, (bf16_t*)a.dW_enc, (bf16_t*)a.W_enc, AdamFuse{a.fuse.m, a.fuse.v, a.fuse.master, a.fuse.a}};
   return launch(s, p, D.L);
 }
 

@@ -26,7 +26,7 @@ class GpuRun:
     """One forward/loss/backward/Adam pass of the HIP library; results as numpy."""
 
     def __init__(self, w: S.CLTWorkload, params, x, y, t=1, m=None, v=None, x_scale=None, y_scale=None,
-                 theta=None, decode_mode=1, gather_density_threshold=0.005):
+                 theta=None, decode_mode=1, gather_density_threshold=0.005, fused=False):
         from paper_2603_21014_amd import binding as K
         dev = "cuda:0"
         T = torch.float32 if w.dtype == "f32" else torch.bfloat16
@@ -50,7 +50,10 @@ class GpuRun:
         self.loss = step.loss(yg, w.lambda0, ys, to_host=True)
         self.norms = to_np(K.clt_workspace_view(step.H, "norms"))
         self.d_yhat = to_np(K.clt_workspace_view(step.H, "d_yhat"))
-        step.backward(xg, gp, xs)
+        if fused:     # backward and Adam in one call, Adam inside the weight-gradient GEMM epilogues
+            step.backward_adam_step(xg, gp, gm, gv, t, w.lr, master, xs)
+        else:
+            step.backward(xg, gp, xs)
         self.dpre = to_np(K.clt_workspace_view(step.H, "dpre"))
         torch.cuda.synchronize()
         self.pre, self.z, self.y_hat = to_np(step.pre), to_np(step.z), to_np(step.y_hat)
@@ -59,7 +62,8 @@ class GpuRun:
         self.l0 = step.l0.cpu().numpy()
         self.decode_switch = K.clt_workspace_view(step.H, "decode_switch").cpu().numpy()
         self.grads = {k: to_np(g) for k, g in step.grads.items()}
-        step.adam_step(t, w.lr, gp, gm, gv, master)
+        if not fused:
+            step.adam_step(t, w.lr, gp, gm, gv, master)
         torch.cuda.synchronize()
         self.new_params = {k: to_np(p) for k, p in gp.items()}
         self.new_m = {k: to_np(a) for k, a in gm.items()}

@@ -110,6 +110,33 @@ def test_adam_later_step_with_given_moments(dtype):
         assert rel_l2(got - o.params[k], o.new_params[k] - o.params[k]) <= tol, k
 
 
+# ---------------------------------------------------------------- backward + Adam in one call
+@pytest.mark.parametrize("dtype,master", [("f32", False), ("bf16", False), ("bf16", True)])
+@pytest.mark.parametrize("L,d,F,B", [(3, 40, 72, 77), (2, 264, 520, 300)])
+def test_fused_backward_adam_step(dtype, master, L, d, F, B):
+    w = S.scaled(S.WORKLOADS["tiny"], dtype=dtype, L=L, d=d, F=F, B=B, seed=31 + d, master_weights=master)
+    g, o = run_both(w, fused=True)
+    show(f"fused {dtype} master={master} L{L} d{d}", compare_step(w, g, o, TOL[dtype]))
+
+
+def test_fused_equals_unfused_with_fp32_storage():
+    """With fp32 storage the gradient enters Adam unrounded on both paths: same gradients
+    bit for bit, same update up to the contraction order of the two compiled epilogues."""
+    w = S.scaled(S.WORKLOADS["tiny"], L=3, d=72, F=136, B=90, seed=33)
+    params = S.make_params(w)
+    x, y = S.make_inputs(w)
+    gen = torch.Generator().manual_seed(12)
+    m = {k: 1e-3 * torch.randn(p.shape, generator=gen) for k, p in params.items()}
+    v = {k: 1e-6 * torch.rand(p.shape, generator=gen) for k, p in params.items()}
+    a = GpuRun(w, params, x, y, t=5, m=m, v=v, fused=False)
+    b = GpuRun(w, params, x, y, t=5, m=m, v=v, fused=True)
+    old = {k: to_np(p) for k, p in params.items()}
+    for k in O.PARAM_NAMES:
+        assert (a.grads[k] == b.grads[k]).all(), k
+        assert rel_l2(b.new_m[k], a.new_m[k]) < 1e-6 and rel_l2(b.new_v[k], a.new_v[k]) < 1e-6, k
+        assert rel_l2(b.new_params[k] - old[k], a.new_params[k] - old[k]) < 1e-4, k
+
+
 # ---------------------------------------------------------------- int8 activation cache
 @pytest.mark.parametrize("L,d,F,B", [(2, 64, 256, 96), (3, 264, 520, 300)])
 def test_int8_row_scaled_inputs(L, d, F, B):
