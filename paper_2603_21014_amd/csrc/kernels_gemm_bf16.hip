@@ -159,6 +159,7 @@ __device__ __forceinline__ void main_loop(const P& p, const typename P::GInfo& g
   Stager<P::B_KC, bf16_t> sb;
   sa.init(lt, p.lda);
   sb.init(lt, p.ldb);
+
   // uniform cursors: current segment bases, k offset inside the segment
   int ld_seg = 0, ld_k0 = 0;
   const TA* Aseg = p.a_seg(gi, 0);
@@ -208,7 +209,10 @@ __device__ __forceinline__ void main_loop(const P& p, const typename P::GInfo& g
   };
 
   // One K step = the 32 MFMAs of this wave on tile `kt`; fragment reads of the
-  // next 16-wide slice overlap the MFMAs of the current one.
+  // next 16-wide slice overlap the MFMAs of the current one, and the MFMAs of a
+  // tile's last slice are held back until the first fragment read of the next
+  // tile is in flight (their operands stay in registers across the memory phase).
+  const int first_kt = 0;
   auto compute = [&](int kt) {
     const int cur = kt & 1;
 #ifdef CLT_EXP_NOMFMA
@@ -233,13 +237,13 @@ __device__ __forceinline__ void main_loop(const P& p, const typename P::GInfo& g
 #endif
     __builtin_amdgcn_s_setprio(1);
     X_FRAGS(cur, 0, 0);
+    if (kt != first_kt) X_MFMA(1);   // last slice of the previous tile, deferred to cover this read latency
     X_FRAGS(cur, 1, 1);
     X_MFMA(0);
     X_FRAGS(cur, 2, 0);
     X_MFMA(1);
     X_FRAGS(cur, 3, 1);
     X_MFMA(0);
-    X_MFMA(1);
     __builtin_amdgcn_s_setprio(0);
   };
 
@@ -251,9 +255,11 @@ __device__ __forceinline__ void main_loop(const P& p, const typename P::GInfo& g
   // right before computing it; group B (waves 4-7) writes its half of tile k+1
   // before computing tile k, so a stage is never written while the other group
   // still reads it (see the interval table in the design notes).
-  fetch();
-  stage(0);
+  // (the prologue is repeated inside each branch on purpose: every branch then only ever
+  // touches its own operand, which keeps the other operand's addressing out of its registers)
   if (loads_a) {
+    fetch();
+    stage(0);
     __syncthreads();
     for (int kt = 0; kt < nk; ++kt) {
       if (kt >= 1) X_STAGE(kt & 1);
@@ -262,7 +268,10 @@ __device__ __forceinline__ void main_loop(const P& p, const typename P::GInfo& g
       compute(kt);
       __syncthreads();
     }
+    X_MFMA(1);
   } else {
+    fetch();
+    stage(0);
     if (nk > 1) fetch();
     __syncthreads();
     for (int kt = 0; kt < nk; ++kt) {
@@ -273,6 +282,7 @@ __device__ __forceinline__ void main_loop(const P& p, const typename P::GInfo& g
       __syncthreads();
     }
     compute(nk - 1);
+    X_MFMA(1);
   }
 }
 
