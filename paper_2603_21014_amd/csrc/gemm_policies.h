@@ -123,7 +123,7 @@ struct EncPolicy {
   __device__ int nseg(const GInfo&) const { return 1; }
   __device__ const TA* a_seg(const GInfo& g, int) const { return x + (size_t)g.l * D.B * D.d; }
   __device__ const T* b_seg(const GInfo& g, int) const { return W_enc + (size_t)g.l * D.d * D.F; }
-  static constexpr int EPI_BATCH = 8;
+  static constexpr int EPI_BATCH = 8, EPI_BATCH_LATE = 8;
   struct EpiRegs { float4 b, th; float s; };
   __device__ void epi_begin(Epi& e) const { e.count = 0; }
   __device__ void epi_load(EpiRegs& r, const GInfo& g, int row, int col) const {
@@ -185,7 +185,7 @@ struct DecPolicy {
   __device__ const T* b_seg(const GInfo& g, int s) const {
     return W_dec + (size_t)packed_index(s, g.lp, D.L) * D.F * D.d;
   }
-  static constexpr int EPI_BATCH = 8;
+  static constexpr int EPI_BATCH = 8, EPI_BATCH_LATE = 8;
   struct EpiRegs { float4 b; };
   __device__ void epi_begin(Epi&) const {}
   __device__ void epi_load(EpiRegs& r, const GInfo& g, int, int col) const {
@@ -220,7 +220,7 @@ struct DzPolicy {
   __device__ const T* b_seg(const GInfo& g, int s) const {
     return W_dec + (size_t)packed_index(g.l, g.l + s, D.L) * D.F * D.d;
   }
-  static constexpr int EPI_BATCH = 8;
+  static constexpr int EPI_BATCH = 8, EPI_BATCH_LATE = 8;
   struct EpiRegs { uint32_t c4; float4 z4, n4; };
   __device__ void epi_begin(Epi&) const {}
   __device__ void epi_load(EpiRegs& r, const GInfo& g, int row, int col) const {
@@ -263,7 +263,7 @@ struct DWdecPolicy {
   int M, N, kseg, lda, ldb;
   const T* z; const T* d_yhat; T* W_dec; const float* G; const float* norms; T* dW_dec;   // dW_dec may be NULL when fused
   AdamFuse fuse;
-  int p0;   // first decoder block of this launch (launches cover one source layer each)
+  int p0;   // first decoder block of this launch
   __device__ bool skip() const { return false; }
   struct GInfo { int p, l, lp; };
   struct Epi {};
@@ -275,7 +275,8 @@ struct DWdecPolicy {
   __device__ int nseg(const GInfo&) const { return 1; }
   __device__ const T* a_seg(const GInfo& g, int) const { return z + (size_t)g.l * D.B * D.F; }
   __device__ const T* b_seg(const GInfo& g, int) const { return d_yhat + (size_t)g.lp * D.B * D.d; }
-  static constexpr int EPI_BATCH = 4;   // 18 registers per group: keep the batch within the register budget
+  // 18 registers per row group: 4 groups while most accumulators are still live, 8 afterwards
+  static constexpr int EPI_BATCH = 4, EPI_BATCH_LATE = 8;
   struct EpiRegs { float Gf, nf; float4 w; AdamRegs ad; };
   __device__ void epi_begin(Epi&) const {}
   __device__ void epi_load(EpiRegs& r, const GInfo& g, int row, int col) const {
@@ -315,7 +316,7 @@ struct DWencPolicy {
   __device__ int nseg(const GInfo&) const { return 1; }
   __device__ const TA* a_seg(const GInfo& g, int) const { return x + (size_t)g.l * D.B * D.d; }
   __device__ const T* b_seg(const GInfo& g, int) const { return dpre + (size_t)g.l * D.B * D.F; }
-  static constexpr int EPI_BATCH = 4;
+  static constexpr int EPI_BATCH = 4, EPI_BATCH_LATE = 8;
   struct EpiRegs { AdamRegs ad; };
   __device__ void epi_begin(Epi&) const {}
   __device__ void epi_load(EpiRegs& r, const GInfo& g, int row, int col) const {

@@ -22,6 +22,8 @@
 #include "common.h"
 #include "gemm_policies.h"
 
+#include <type_traits>
+
 namespace clt {
 namespace {
 
@@ -327,15 +329,17 @@ __global__ __launch_bounds__(NTHREADS) void gemm_bf16_kernel(P p, TileGrid tg) {
   p.epi_begin(est);
   const int c4 = (lane & 15) << 2;
   const int gcol = n0 + wn * 64 + c4;
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
+  // One 32-row slab of the wave's block.  The global loads the policy's epilogue needs are issued
+  // for EB row groups before any is consumed; later slabs can afford larger batches because the
+  // accumulators of the slabs already written out no longer occupy registers.
+  auto slab = [&](auto eb_tag, int i) {
+    constexpr int EB = decltype(eb_tag)::value;
 #pragma unroll
     for (int j = 0; j < 2; ++j)
 #pragma unroll
       for (int r = 0; r < 16; ++r)
         wl[(8 * (r >> 2) + 4 * (lane >> 5) + (r & 3)) * 64 + j * 32 + (lane & 31)] = acc[i][j][r];
     __syncthreads();
-    constexpr int EB = P::EPI_BATCH;   // epilogue loads of EB row groups are issued before any is used
 #pragma unroll
     for (int it0 = 0; it0 < 8; it0 += EB) {
       typename P::EpiRegs er[EB];
@@ -353,7 +357,11 @@ __global__ __launch_bounds__(NTHREADS) void gemm_bf16_kernel(P p, TileGrid tg) {
       }
     }
     __syncthreads();
-  }
+  };
+  slab(std::integral_constant<int, P::EPI_BATCH>{}, 0);
+  slab(std::integral_constant<int, P::EPI_BATCH_LATE>{}, 1);
+  slab(std::integral_constant<int, P::EPI_BATCH_LATE>{}, 2);
+  slab(std::integral_constant<int, P::EPI_BATCH_LATE>{}, 3);
   p.epi_end(est, gi);
 }
 
