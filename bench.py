@@ -44,15 +44,15 @@ def profiled_traffic_bytes(workload, kernel):
 
 def cpu_oracle_baseline(w, log):
     """The oracle as it stands on a bounded sample of the workload: full L and d,
-    F/16 features and B/16 tokens.  The contraction cost is linear in B*F, Adam
-    and the decoder norms in F, so the sample time is scaled back to the full
-    shape and expressed in tokens/s."""
+    F/4 features and B/8 tokens (about 10-20 s of host time).  The contraction cost
+    is linear in B*F, Adam and the decoder norms in F, so the sample time is scaled
+    back to the full shape and expressed in tokens/s."""
     import numpy as np
     import torch
     from oracle import clt_oracle as O
     from workloads import clt_synth as S
-    fs, bs = max(8, w.F // 16), max(1, w.B // 16)
-    ws = S.scaled(w, F=fs, B=bs, k_active=max(1, w.k_active // 16))
+    fs, bs = max(8, w.F // 4), max(1, w.B // 8)
+    ws = S.scaled(w, F=fs, B=bs, k_active=max(1, w.k_active // 4))
     params = {k: v.numpy().astype(np.float64) for k, v in S.make_params(ws).items()}
     x, y = (t.numpy().astype(np.float64) for t in S.make_inputs(ws))
     zeros = {k: np.zeros_like(v) for k, v in params.items()}

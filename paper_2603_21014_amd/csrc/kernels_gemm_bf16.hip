@@ -135,9 +135,6 @@ struct Stager {
   }
 };
 
-#ifdef CLT_EXP_CLOCK
-__device__ long long g_clk[2048];
-#endif
 constexpr int NTHREADS = 512;   // 8 wavefronts: two per SIMD, so one's memory phase hides under the other's MFMAs
 
 // K loop of one output tile.  EDGE = false assumes the tile lies fully inside the
@@ -147,13 +144,9 @@ __device__ __forceinline__ void main_loop(const P& p, const typename P::GInfo& g
                                           f32x16_t (&acc)[4][2]) {
   typedef typename P::AType TA;
   const int t = threadIdx.x, lane = t & 63, w = t >> 6, wm = w >> 2, wn = w & 3;
-#ifdef CLT_EXP_GROUP_ALT
-  const int lt = ((w >> 1) << 6) | lane;
-  const bool loads_a = (__builtin_amdgcn_readfirstlane(w) & 1) == 0;
-#else
   const int lt = t & 255;
-  const bool loads_a = __builtin_amdgcn_readfirstlane(w) < 4;   // waves 0-3 stage A, waves 4-7 stage B
-#endif
+  // waves 0-3 stage A, waves 4-7 stage B (waves w and w+4 share a SIMD, so each SIMD holds one of each group)
+  const bool loads_a = __builtin_amdgcn_readfirstlane(w) < 4;
   const int kseg = p.kseg, nseg = p.nseg(gi);
   const int nk = nseg * ((kseg + TK - 1) / TK);
 
@@ -217,35 +210,15 @@ __device__ __forceinline__ void main_loop(const P& p, const typename P::GInfo& g
   const int first_kt = 0;
   auto compute = [&](int kt) {
     const int cur = kt & 1;
-#ifdef CLT_EXP_NOMFMA
-#define X_MFMA(b) asm volatile("" :: "v"(fa[b][0]), "v"(fa[b][1]), "v"(fa[b][2]), "v"(fa[b][3]), "v"(fb[b][0]), "v"(fb[b][1]))
-#else
-#define X_MFMA(b) mfma(b)
-#endif
-#ifdef CLT_EXP_NOFRAG
-#define X_FRAGS(a, b, c)
-#else
-#define X_FRAGS(a, b, c) frags(a, b, c)
-#endif
-#ifdef CLT_EXP_NOGLOAD
-#define X_FETCH()
-#else
-#define X_FETCH() fetch()
-#endif
-#ifdef CLT_EXP_NOSTAGE
-#define X_STAGE(s)
-#else
-#define X_STAGE(s) stage(s)
-#endif
     __builtin_amdgcn_s_setprio(1);
-    X_FRAGS(cur, 0, 0);
-    if (kt != first_kt) X_MFMA(1);   // last slice of the previous tile, deferred to cover this read latency
-    X_FRAGS(cur, 1, 1);
-    X_MFMA(0);
-    X_FRAGS(cur, 2, 0);
-    X_MFMA(1);
-    X_FRAGS(cur, 3, 1);
-    X_MFMA(0);
+    frags(cur, 0, 0);
+    if (kt != first_kt) mfma(1);   // last slice of the previous tile, deferred to cover this read latency
+    frags(cur, 1, 1);
+    mfma(0);
+    frags(cur, 2, 0);
+    mfma(1);
+    frags(cur, 3, 1);
+    mfma(0);
     __builtin_amdgcn_s_setprio(0);
   };
 
@@ -264,13 +237,13 @@ __device__ __forceinline__ void main_loop(const P& p, const typename P::GInfo& g
     stage(0);
     __syncthreads();
     for (int kt = 0; kt < nk; ++kt) {
-      if (kt >= 1) X_STAGE(kt & 1);
-      if (kt + 1 < nk) X_FETCH();
+      if (kt >= 1) stage(kt & 1);
+      if (kt + 1 < nk) fetch();
       __syncthreads();
       compute(kt);
       __syncthreads();
     }
-    X_MFMA(1);
+    mfma(1);
   } else {
     fetch();
     stage(0);
@@ -279,12 +252,12 @@ __device__ __forceinline__ void main_loop(const P& p, const typename P::GInfo& g
     for (int kt = 0; kt < nk; ++kt) {
       if (kt >= 1) compute(kt - 1);
       __syncthreads();
-      if (kt + 1 < nk) X_STAGE((kt + 1) & 1);
-      if (kt + 2 < nk) X_FETCH();
+      if (kt + 1 < nk) stage((kt + 1) & 1);
+      if (kt + 2 < nk) fetch();
       __syncthreads();
     }
     compute(nk - 1);
-    X_MFMA(1);
+    mfma(1);
   }
 }
 
@@ -309,18 +282,8 @@ __global__ __launch_bounds__(NTHREADS) void gemm_bf16_kernel(P p, TileGrid tg) {
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
   const bool interior = (m0 + TM <= M) && (n0 + TN <= N) && (p.kseg % TK == 0);
-#ifdef CLT_EXP_CLOCK
-  const long long c0 = clock64(), w0 = wall_clock64();
-#endif
   if (interior) main_loop<P, false>(p, gi, m0, n0, smem, acc);
   else main_loop<P, true>(p, gi, m0, n0, smem, acc);
-#ifdef CLT_EXP_CLOCK
-  if (threadIdx.x == 0 && blockIdx.x < 1024) {
-    extern __device__ long long g_clk[2048];
-    g_clk[2 * blockIdx.x] = clock64() - c0;
-    g_clk[2 * blockIdx.x + 1] = wall_clock64() - w0;
-  }
-#endif
 
   // ---- epilogue: accumulators -> LDS (wave-private 32 rows x 64 fp32) -> 4 columns of one row per lane
   __syncthreads();
