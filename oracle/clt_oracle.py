@@ -17,8 +17,9 @@ reordering:
   cross-layer decode ............ Sec. 2.1, eq. (3); eq. (2) is its L = 1 case
   decoder norms ................. App. B: norm of the concatenation of all
                                   decoders that leave a source layer
-  objective ..................... App. B training objective, reconstruction and
-                                  sparsity terms (lambda_1 = 0)
+  objective ..................... App. B training objective: reconstruction,
+                                  sparsity and (optional, lambda_1 > 0) the
+                                  dead-feature penalty with theta = exp(tau)
   backward ...................... chain rule through the above; the threshold
                                   gets the rectangle-kernel straight-through
                                   pseudo-gradient
@@ -174,6 +175,26 @@ def loss_terms(y_hat, y, z, n, lambda0, C):
     return L_rec + L_sp, L_rec, L_sp
 
 
+def dead_feature_term(pre, theta, n, lambda1):
+    """App. B dead-feature penalty, mean over the B tokens:
+
+    L_dead = (lambda1/B) sum_{l, b, f} ReLU(theta[l,f] - pre[l,b,f]) * n[l,f]
+
+    where theta = exp(tau) is the JumpReLU threshold in its log parameterisation
+    and n the decoder norm of the feature.
+    """
+    pre = np.asarray(pre, F64)
+    theta = np.asarray(theta, F64)
+    B = pre.shape[1]
+    return lambda1 * np.sum(np.maximum(theta[:, None, :] - pre, 0.0) * n[:, None, :]) / B
+
+
+def threshold_value(param, log_threshold):
+    """The threshold theta from its stored parameter: theta itself, or exp(tau)."""
+    param = np.asarray(param, F64)
+    return np.exp(param) if log_threshold else param
+
+
 def forward(x, W_enc, b_enc, theta, W_dec, b_dec, tie_break=None, band=0.0):
     """Encoder, JumpReLU, cross-layer decode.  Returns a dict of intermediates."""
     pre = encoder_preact(x, W_enc, b_enc)
@@ -187,8 +208,10 @@ def forward(x, W_enc, b_enc, theta, W_dec, b_dec, tie_break=None, band=0.0):
 # backward
 # --------------------------------------------------------------------------
 def backward(x, y, theta, W_dec, fwd, lambda0, C, eps,
-             window_tie_break=None, band=0.0):
-    """Gradients of L_rec + L_sp w.r.t. the five parameter tensors.
+             window_tie_break=None, band=0.0, lambda1=0.0, log_threshold=False):
+    """Gradients of L_rec + L_sp (+ L_dead when lambda1 > 0) w.r.t. the five
+    parameter tensors.  `theta` is the threshold value; with log_threshold the
+    stored parameter is tau = log(theta) and "dtheta" is the gradient w.r.t. tau.
 
     d y_hat = 2 (y_hat - y) / B
     dz[l]   = sum_{l' >= l} d y_hat[l'] @ W_dec[p(l,l')]^T
@@ -198,6 +221,10 @@ def backward(x, y, theta, W_dec, fwd, lambda0, C, eps,
     dW_dec[p(l,l')] = z[l]^T @ d y_hat[l'] + (G[l,f]/n[l,f]) W_dec[p(l,l')][f,:]
               with G[l,f] = (lambda0/B) sum_b C z sech^2(C z n)
     db_dec  = sum_b d y_hat,  dW_enc[l] = x[l]^T @ dpre[l],  db_enc = sum_b dpre
+    Dead-feature term (true derivatives of ReLU(theta - pre) n, ReLU'(0) = 0):
+      dpre   += -(lambda1/B) n      where pre < theta
+      dtheta += +(lambda1/B) n sum_b [pre < theta]
+      G      += (lambda1/B) sum_b ReLU(theta - pre)      (the term's d/dn, enters dW_dec as G W / n)
     """
     x = np.asarray(x, F64)
     y = np.asarray(y, F64)
@@ -218,11 +245,19 @@ def backward(x, y, theta, W_dec, fwd, lambda0, C, eps,
         for lp in range(l, L):
             dz[l] += d_yhat[lp] @ np.asarray(W_dec[packed_index(l, lp, L)], F64).T
     dpre = np.where(active, dz, 0.0)
+    below = pre < theta[:, None, :]
+    if lambda1 != 0.0:
+        dpre = dpre + np.where(below, -(lambda1 / B) * n[:, None, :], 0.0)
+        G = G + (lambda1 / B) * np.sum(np.maximum(theta[:, None, :] - pre, 0.0), axis=1)
     win = ste_window(pre, theta, eps, window_tie_break, band)
     # sum over the window entries of the per-entry pseudo-derivative -(theta/eps) dz;
     # an empty window contributes exactly 0, also for a non-finite threshold
     with np.errstate(invalid="ignore"):
         dtheta = np.sum(np.where(win, -(theta[:, None, :] / eps) * dz, 0.0), axis=1)
+    if lambda1 != 0.0:
+        dtheta = dtheta + (lambda1 / B) * n * below.sum(axis=1)
+    if log_threshold:
+        dtheta = dtheta * theta          # chain rule through theta = exp(tau)
     db_enc = dpre.sum(axis=1)
 
     dW_dec = np.empty((num_blocks(L), F, d), F64)
@@ -263,19 +298,21 @@ PARAM_NAMES = ("W_enc", "b_enc", "theta", "W_dec", "b_dec")
 
 
 def train_step(x, y, params, m, v, t, lr, lambda0, C, eps,
-               beta1=0.9, beta2=0.999, adam_eps=1e-8):
+               beta1=0.9, beta2=0.999, adam_eps=1e-8, lambda1=0.0, log_threshold=False):
     """Forward, loss, backward and Adam on all five tensors.
 
-    `params`, `m`, `v` are dicts keyed by PARAM_NAMES.  Returns
-    (new_params, new_m, new_v, info) with info holding forward values, loss
-    terms and gradients.
+    `params`, `m`, `v` are dicts keyed by PARAM_NAMES (params["theta"] holds tau
+    when log_threshold).  Returns (new_params, new_m, new_v, info) with info
+    holding forward values, loss terms and gradients.
     """
-    fwd = forward(x, params["W_enc"], params["b_enc"], params["theta"],
-                  params["W_dec"], params["b_dec"])
+    theta = threshold_value(params["theta"], log_threshold)
+    fwd = forward(x, params["W_enc"], params["b_enc"], theta, params["W_dec"], params["b_dec"])
     L = np.asarray(x).shape[0]
     n = decoder_norms(params["W_dec"], L)
     total, rec, sp = loss_terms(fwd["y_hat"], y, fwd["z"], n, lambda0, C)
-    grads = backward(x, y, params["theta"], params["W_dec"], fwd, lambda0, C, eps)
+    total = total + dead_feature_term(fwd["pre"], theta, n, lambda1)
+    grads = backward(x, y, theta, params["W_dec"], fwd, lambda0, C, eps,
+                     lambda1=lambda1, log_threshold=log_threshold)
     new_p, new_m, new_v = {}, {}, {}
     for k in PARAM_NAMES:
         new_p[k], new_m[k], new_v[k] = adam_update(
