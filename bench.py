@@ -57,10 +57,13 @@ def cpu_oracle_baseline(w, log):
     x, y = (t.numpy().astype(np.float64) for t in S.make_inputs(ws))
     zeros = {k: np.zeros_like(v) for k, v in params.items()}
     t0 = time.perf_counter()
-    fwd = O.forward(x, params["W_enc"], params["b_enc"], params["theta"], params["W_dec"], params["b_dec"])
+    theta = O.threshold_value(params["theta"], ws.log_threshold)
+    fwd = O.forward(x, params["W_enc"], params["b_enc"], theta, params["W_dec"], params["b_dec"])
     n = O.decoder_norms(params["W_dec"], ws.L)
     O.loss_terms(fwd["y_hat"], y, fwd["z"], n, ws.lambda0, ws.C)
-    grads = O.backward(x, y, params["theta"], params["W_dec"], fwd, ws.lambda0, ws.C, ws.ste_eps)
+    O.dead_feature_term(fwd["pre"], theta, n, ws.lambda1)
+    grads = O.backward(x, y, theta, params["W_dec"], fwd, ws.lambda0, ws.C, ws.ste_eps, lambda1=ws.lambda1,
+                       log_threshold=ws.log_threshold)
     t1 = time.perf_counter()
     for k in O.PARAM_NAMES:
         O.adam_update(params[k], grads["d" + k], zeros[k], zeros[k], 1, ws.lr)
@@ -172,7 +175,8 @@ def main():
     m = {k: torch.zeros(v.shape, dtype=torch.float32, device=dev) for k, v in params.items()}
     v_ = {k: torch.zeros(v.shape, dtype=torch.float32, device=dev) for k, v in params.items()}
     step = K.CLTStep(w.L, w.d, w.F, w.B, dtype="bf16", int8_inputs=w.int8_inputs, master_weights=w.master_weights,
-                     C_=w.C, ste_bandwidth=w.ste_eps, device=dev, keep_pre=False)
+                     C_=w.C, ste_bandwidth=w.ste_eps, device=dev, keep_pre=w.lambda1 > 0,
+                     log_threshold=w.log_threshold)
     torch.cuda.synchronize()
     log(f"workload {w.name}: L={w.L} d={w.d} F={w.F} B={w.B}, inputs ready in {time.perf_counter() - t0:.1f}s, "
         f"{torch.cuda.memory_allocated() / 2**30:.1f} GiB allocated")
@@ -180,7 +184,7 @@ def main():
     t = 0
     for _ in range(args.warmup):
         t += 1
-        step.train_step(x, y, params, m, v_, t, w.lr, w.lambda0, master, xs, ys)
+        step.train_step(x, y, params, m, v_, t, w.lr, w.lambda0, master, xs, ys, lambda1=w.lambda1)
     torch.cuda.synchronize()
     log("warmup done")
     if not args.no_kernel_timing:
@@ -190,7 +194,7 @@ def main():
     e0.record()
     for _ in range(args.steps):
         t += 1
-        step.train_step(x, y, params, m, v_, t, w.lr, w.lambda0, master, xs, ys)
+        step.train_step(x, y, params, m, v_, t, w.lr, w.lambda0, master, xs, ys, lambda1=w.lambda1)
     e1.record()
     torch.cuda.synchronize()
     ms_per_step = e0.elapsed_time(e1) / args.steps

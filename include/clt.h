@@ -73,6 +73,10 @@ typedef struct clt_config {
   int32_t master_weights; /* 1: clt_adam_step updates fp32 master copies of W_enc/W_dec  */
   int32_t decode_mode;    /* dense GEMM decode, active-feature gather decode (Sec. 3.2),
                              or chosen per step, on the device, from the measured density */
+  int32_t log_threshold;  /* 0: the theta tensor holds the threshold itself; 1: it holds
+                             tau = log(theta) (App. B writes the threshold as exp(tau)), the
+                             kernels take exp() of it and theta's gradient and Adam step are
+                             those of tau                                                   */
   float gather_density_threshold; /* AUTO: gather when the mean active fraction of the batch
                              is <= this and no (layer, token) row has more than about 8x
                              as many active features (else the step decodes densely)    */
@@ -113,21 +117,29 @@ int clt_forward(clt_handle* handle, void* stream,
                 const void* W_dec, const float* b_dec,
                 void* z, void* pre, uint8_t* act_class, float* y_hat, int32_t* l0_per_layer);
 
-/* App. B objective with lambda_1 = 0, mean over the B tokens:
- *   L_rec = (1/B) sum (y_hat - y)^2,  L_sp = (lambda0/B) sum tanh(C z n[l,f]).
- * Needs the decoder norms of the preceding clt_forward on this handle.  Writes
- * loss_dev[0..2] = {L_rec + L_sp, L_rec, L_sp} (device) and keeps d y_hat and the
- * sparsity-gradient column sums in the workspace for clt_backward.  If
- * loss_host is not NULL the three floats are also copied there and the stream
- * is synchronised. */
+/* App. B objective, mean over the B tokens:
+ *   L_rec  = (1/B) sum (y_hat - y)^2,
+ *   L_sp   = (lambda0/B) sum tanh(C z n[l,f]),
+ *   L_dead = (lambda1/B) sum ReLU(theta[l,f] - pre[l,b,f]) n[l,f]   (dead-feature penalty).
+ * Needs the decoder norms of the preceding clt_forward on this handle.  pre is
+ * the pre-activation that clt_forward wrote and theta the threshold tensor as
+ * given to it; both may be NULL when lambda1 == 0 (term off, nothing read).
+ * Writes loss_dev[0..3] = {L_rec + L_sp + L_dead, L_rec, L_sp, L_dead} (device)
+ * and keeps d y_hat and the decoder-norm gradient column sums in the workspace
+ * for clt_backward.  If loss_host is not NULL the four floats are also copied
+ * there and the stream is synchronised. */
 int clt_loss(clt_handle* handle, void* stream,
              const void* y, const float* y_scale, const float* y_hat, const void* z,
-             float lambda0, float* loss_dev, float* loss_host);
+             const void* pre, const float* theta,
+             float lambda0, float lambda1, float* loss_dev, float* loss_host);
 
 /* Gradients of the objective evaluated by the preceding clt_loss, w.r.t. the
  * five learned tensors (grads->W_enc, W_dec in T; vectors float).  JumpReLU
  * passes gradient to pre where active; theta gets the rectangle-kernel
- * pseudo-gradient -(theta/eps) sum_b 1[in window] dz. */
+ * pseudo-gradient -(theta/eps) sum_b 1[in window] dz.  With lambda1 > 0 the
+ * dead-feature term adds -(lambda1/B) n to d pre and +(lambda1/B) n to d theta
+ * for every entry with pre < theta, and its decoder-norm derivative to dW_dec.
+ * With log_threshold the theta gradient is the one w.r.t. tau (times theta). */
 int clt_backward(clt_handle* handle, void* stream,
                  const void* x, const float* x_scale, const float* theta,
                  const void* W_dec, const void* z, const uint8_t* act_class,

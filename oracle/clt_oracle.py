@@ -208,7 +208,8 @@ def forward(x, W_enc, b_enc, theta, W_dec, b_dec, tie_break=None, band=0.0):
 # backward
 # --------------------------------------------------------------------------
 def backward(x, y, theta, W_dec, fwd, lambda0, C, eps,
-             window_tie_break=None, band=0.0, lambda1=0.0, log_threshold=False):
+             window_tie_break=None, band=0.0, lambda1=0.0, log_threshold=False,
+             below_tie_break=None):
     """Gradients of L_rec + L_sp (+ L_dead when lambda1 > 0) w.r.t. the five
     parameter tensors.  `theta` is the threshold value; with log_threshold the
     stored parameter is tau = log(theta) and "dtheta" is the gradient w.r.t. tau.
@@ -225,6 +226,8 @@ def backward(x, y, theta, W_dec, fwd, lambda0, C, eps,
       dpre   += -(lambda1/B) n      where pre < theta
       dtheta += +(lambda1/B) n sum_b [pre < theta]
       G      += (lambda1/B) sum_b ReLU(theta - pre)      (the term's d/dn, enters dW_dec as G W / n)
+    `below_tie_break` forces the decision pre < theta where |pre - theta| < band,
+    under the same rule as jumprelu's tie_break.
     """
     x = np.asarray(x, F64)
     y = np.asarray(y, F64)
@@ -246,6 +249,12 @@ def backward(x, y, theta, W_dec, fwd, lambda0, C, eps,
             dz[l] += d_yhat[lp] @ np.asarray(W_dec[packed_index(l, lp, L)], F64).T
     dpre = np.where(active, dz, 0.0)
     below = pre < theta[:, None, :]
+    if below_tie_break is not None:
+        tb = np.asarray(below_tie_break, bool)
+        inband = np.abs(pre - theta[:, None, :]) < band
+        if np.any((tb != below) & ~inband):
+            raise ValueError("below tie_break disagrees with the oracle outside the band")
+        below = np.where(inband, tb, below)
     if lambda1 != 0.0:
         dpre = dpre + np.where(below, -(lambda1 / B) * n[:, None, :], 0.0)
         G = G + (lambda1 / B) * np.sum(np.maximum(theta[:, None, :] - pre, 0.0), axis=1)

@@ -36,7 +36,7 @@ class CLTError(RuntimeError):
 class clt_config(C.Structure):
     _fields_ = [("size", C.c_uint32), ("L", C.c_int32), ("d", C.c_int32), ("F", C.c_int32), ("B", C.c_int32),
                 ("dtype", C.c_int32), ("input_format", C.c_int32), ("master_weights", C.c_int32),
-                ("decode_mode", C.c_int32), ("gather_density_threshold", C.c_float), ("C", C.c_float),
+                ("decode_mode", C.c_int32), ("log_threshold", C.c_int32), ("gather_density_threshold", C.c_float), ("C", C.c_float),
                 ("ste_bandwidth", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float), ("adam_eps", C.c_float)]
 
 
@@ -56,7 +56,7 @@ def _load():
     lib.clt_last_error.argtypes = [vp]
     lib.clt_last_error.restype = C.c_char_p
     lib.clt_forward.argtypes = [vp, vp] + [vp] * 12
-    lib.clt_loss.argtypes = [vp, vp, vp, fp, fp, vp, C.c_float, fp, C.POINTER(C.c_float)]
+    lib.clt_loss.argtypes = [vp, vp, vp, fp, fp, vp, vp, fp, C.c_float, C.c_float, fp, C.POINTER(C.c_float)]
     lib.clt_backward.argtypes = [vp, vp, vp, fp, fp, vp, vp, vp, C.POINTER(clt_tensors)]
     lib.clt_adam_step.argtypes = [vp, vp, C.c_int64, C.c_float] + [C.POINTER(clt_tensors)] * 5
     lib.clt_backward_adam_step.argtypes = [vp, vp, vp, fp, vp, vp, C.c_int64, C.c_float] + [C.POINTER(clt_tensors)] * 5
@@ -100,9 +100,9 @@ def _ptr(t, shape, dtype, name, optional=False):
 
 def make_config(L, d, F, B, dtype=DTYPE_BF16, input_format=INPUT_NATIVE, master_weights=False,
                 decode_mode=DECODE_DENSE, gather_density_threshold=0.005, C_=4.0, ste_bandwidth=0.05,
-                beta1=0.9, beta2=0.999, adam_eps=1e-8):
+                beta1=0.9, beta2=0.999, adam_eps=1e-8, log_threshold=False):
     return clt_config(C.sizeof(clt_config), L, d, F, B, dtype, input_format, int(master_weights), decode_mode,
-                      gather_density_threshold, C_, ste_bandwidth, beta1, beta2, adam_eps)
+                      int(log_threshold), gather_density_threshold, C_, ste_bandwidth, beta1, beta2, adam_eps)
 
 
 def clt_workspace_bytes(cfg: clt_config) -> int:
@@ -158,12 +158,15 @@ def clt_forward(H: Handle, x, W_enc, b_enc, theta, W_dec, b_dec, z, act_class, y
     _check(rc, H.h)
 
 
-def clt_loss(H: Handle, y, y_hat, z, lambda0, loss_dev, y_scale=None, to_host=False):
+def clt_loss(H: Handle, y, y_hat, z, lambda0, loss_dev, y_scale=None, to_host=False, lambda1=0.0, pre=None,
+             theta=None):
     s, f32 = H.shapes, torch.float32
-    host = (C.c_float * 3)() if to_host else None
+    host = (C.c_float * 4)() if to_host else None
+    dead = lambda1 > 0.0
     rc = _lib.clt_loss(H.h, _stream(), _ptr(y, s["y"], H.TX, "y"), _ptr(y_scale, s["scale"], f32, "y_scale", True),
-                       _ptr(y_hat, s["y_hat"], f32, "y_hat"), _ptr(z, s["z"], H.T, "z"), float(lambda0),
-                       _ptr(loss_dev, (3,), f32, "loss_dev"), host)
+                       _ptr(y_hat, s["y_hat"], f32, "y_hat"), _ptr(z, s["z"], H.T, "z"),
+                       _ptr(pre, s["z"], H.T, "pre", not dead), _ptr(theta, s["theta"], f32, "theta", not dead),
+                       float(lambda0), float(lambda1), _ptr(loss_dev, (4,), f32, "loss_dev"), host)
     _check(rc, H.h)
     return tuple(host) if to_host else None
 
@@ -258,11 +261,11 @@ class CLTStep:
 
     def __init__(self, L, d, F, B, dtype="bf16", int8_inputs=False, master_weights=False, C_=4.0,
                  ste_bandwidth=0.05, beta1=0.9, beta2=0.999, adam_eps=1e-8, device="cuda:0", keep_pre=True,
-                 decode_mode=DECODE_DENSE, gather_density_threshold=0.005, matrix_grads=True):
+                 decode_mode=DECODE_DENSE, gather_density_threshold=0.005, matrix_grads=True, log_threshold=False):
         dt = DTYPE_BF16 if dtype == "bf16" else DTYPE_F32
         self.cfg = make_config(L, d, F, B, dt, INPUT_INT8_ROWSCALE if int8_inputs else INPUT_NATIVE,
                                master_weights, decode_mode, gather_density_threshold, C_, ste_bandwidth, beta1,
-                               beta2, adam_eps)
+                               beta2, adam_eps, log_threshold)
         self.device = torch.device(device)
         ws = torch.empty(clt_workspace_bytes(self.cfg), dtype=torch.uint8, device=self.device)
         self.H = clt_init(self.cfg, ws)
@@ -274,7 +277,7 @@ class CLTStep:
         self.act_class = e(L, B, F, dtype=torch.uint8)
         self.y_hat = e(L, B, d, dtype=torch.float32)
         self.l0 = e(L, dtype=torch.int32)
-        self.loss_dev = e(3, dtype=torch.float32)
+        self.loss_dev = e(4, dtype=torch.float32)
         self.grads = {"b_enc": e(L, F, dtype=torch.float32), "theta": e(L, F, dtype=torch.float32),
                       "b_dec": e(L, d, dtype=torch.float32)}
         if matrix_grads:    # not needed by the fused backward + Adam path
@@ -285,8 +288,11 @@ class CLTStep:
         clt_forward(self.H, x, params["W_enc"], params["b_enc"], params["theta"], params["W_dec"], params["b_dec"],
                     self.z, self.act_class, self.y_hat, self.pre, self.l0, x_scale)
 
-    def loss(self, y, lambda0, y_scale=None, to_host=False):
-        return clt_loss(self.H, y, self.y_hat, self.z, lambda0, self.loss_dev, y_scale, to_host)
+    def loss(self, y, lambda0, y_scale=None, to_host=False, lambda1=0.0, params=None):
+        """`params` (for its theta tensor) is needed only when the dead-feature term is on (lambda1 > 0)."""
+        theta = params["theta"] if lambda1 > 0.0 else None
+        pre = self.pre if lambda1 > 0.0 else None
+        return clt_loss(self.H, y, self.y_hat, self.z, lambda0, self.loss_dev, y_scale, to_host, lambda1, pre, theta)
 
     def backward(self, x, params, x_scale=None):
         clt_backward(self.H, x, params["theta"], params["W_dec"], self.z, self.act_class, self.grads, x_scale)
@@ -297,10 +303,11 @@ class CLTStep:
     def backward_adam_step(self, x, params, m, v, t, lr, master=None, x_scale=None):
         clt_backward_adam_step(self.H, x, self.z, self.act_class, t, lr, params, self.grads, m, v, master, x_scale)
 
-    def train_step(self, x, y, params, m, v, t, lr, lambda0, master=None, x_scale=None, y_scale=None, fused=True):
+    def train_step(self, x, y, params, m, v, t, lr, lambda0, master=None, x_scale=None, y_scale=None, fused=True,
+                   lambda1=0.0):
         """forward, loss, backward and Adam; `fused` runs Adam inside the weight-gradient GEMMs."""
         self.forward(x, params, x_scale)
-        self.loss(y, lambda0, y_scale)
+        self.loss(y, lambda0, y_scale, False, lambda1, params)
         if fused:
             self.backward_adam_step(x, params, m, v, t, lr, master, x_scale)
         else:

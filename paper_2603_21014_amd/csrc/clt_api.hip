@@ -21,7 +21,7 @@ constexpr size_t ALIGN = 256;
 inline size_t align_up(size_t v) { return (v + ALIGN - 1) / ALIGN * ALIGN; }
 
 struct Plan {
-  size_t norms, G, d_yhat, dpre, part_cols, part_cols2, part_rec, part_sp, l0, flags, g_idx, g_val, g_counts, total;
+  size_t norms, G, d_yhat, dpre, part_cols, part_cols2, part_cols3, part_rec, part_sp, part_dead, l0, flags, g_idx, g_val, g_counts, total;
   int kcap;
 };
 
@@ -60,7 +60,7 @@ struct clt_handle {
   char* ws;
   Plan plan;
   int stage;              // 0 = fresh, 1 = forward done, 2 = loss done
-  float lambda0;
+  float lambda0, lambda1;
   char err[256];
 };
 
@@ -95,6 +95,7 @@ int check_config(const clt_config* c, char* err) {
     set_err(err, "bad decode_mode %d", c->decode_mode);
     return CLT_ERR_INVALID_ARG;
   }
+  if (c->log_threshold != 0 && c->log_threshold != 1) { set_err(err, "bad log_threshold"); return CLT_ERR_INVALID_ARG; }
   if (c->decode_mode == CLT_DECODE_AUTO && !(c->gather_density_threshold >= 0.f && c->gather_density_threshold <= 1.f)) {
     set_err(err, "gather_density_threshold must be in [0, 1]");
     return CLT_ERR_INVALID_ARG;
@@ -120,8 +121,10 @@ Plan make_plan(const clt_config* c) {
   p.dpre = o;       o += align_up(L * B * F * esz);
   p.part_cols = o;  o += align_up(rbs * L * wide * 4);
   p.part_cols2 = o; o += align_up(rbs * L * F * 4);
+  p.part_cols3 = o; o += align_up(rbs * L * F * 4);
   p.part_rec = o;   o += align_up(rbs * L * 8);
   p.part_sp = o;    o += align_up(rbs * L * 8);
+  p.part_dead = o;  o += align_up(rbs * L * 8);
   p.l0 = o;         o += align_up(L * 4);
   p.flags = o;      o += align_up(4 * 4);
   // active-feature lists of the gather decode: forced gather must hold a fully dense row;
@@ -246,6 +249,7 @@ int clt_init(clt_handle** handle, const clt_config* cfg, void* workspace, size_t
   h->plan = plan;
   h->stage = 0;
   h->lambda0 = 0.f;
+  h->lambda1 = 0.f;
   h->err[0] = 0;
   *handle = h;
   return CLT_OK;
@@ -326,7 +330,8 @@ int clt_forward(clt_handle* h, void* stream, const void* x, const float* x_scale
   int32_t* flags = reinterpret_cast<int32_t*>(h->ws + h->plan.flags);
   RUN(h, s, K_ZERO, launch_zero_i32(s, l0, h->D.L));
   RUN(h, s, K_NORMS, launch_decoder_norms(s, h->bf16, h->D, W_dec, norms));
-  EncArgs ea{x, x_scale, W_enc, b_enc, theta, h->cfg.ste_bandwidth, z, pre, act_class, l0};
+  EncArgs ea{x, x_scale, W_enc, b_enc, theta, h->cfg.ste_bandwidth, z, pre, act_class, l0,
+             h->cfg.log_threshold != 0};
   const int mode = h->cfg.decode_mode;
   DecArgs da{z, W_dec, b_dec, y_hat, mode == CLT_DECODE_AUTO ? flags : nullptr, h->plan.kcap};
   GatherLists gl{reinterpret_cast<int32_t*>(h->ws + h->plan.g_idx), reinterpret_cast<float*>(h->ws + h->plan.g_val),
@@ -351,12 +356,15 @@ int clt_forward(clt_handle* h, void* stream, const void* x, const float* x_scale
 }
 
 int clt_loss(clt_handle* h, void* stream, const void* y, const float* y_scale, const float* y_hat, const void* z,
-             float lambda0, float* loss_dev, float* loss_host) {
+             const void* pre, const float* theta, float lambda0, float lambda1, float* loss_dev, float* loss_host) {
   if (!h) { set_err(g_err, "clt_loss: handle is NULL"); return CLT_ERR_INVALID_ARG; }
   REQ(h, y); REQ(h, y_hat); REQ(h, z); REQ(h, loss_dev);
   if (h->int8) REQ(h, y_scale);
   else if (y_scale) { set_err(h->err, "clt_loss: y_scale given but input_format is native"); return CLT_ERR_INVALID_ARG; }
   if (!(lambda0 >= 0.f)) { set_err(h->err, "clt_loss: lambda0 must be >= 0"); return CLT_ERR_INVALID_ARG; }
+  if (!(lambda1 >= 0.f)) { set_err(h->err, "clt_loss: lambda1 must be >= 0"); return CLT_ERR_INVALID_ARG; }
+  const bool dead = lambda1 > 0.f;
+  if (dead) { REQ(h, pre); REQ(h, theta); }
   if (h->stage < 1) { set_err(h->err, "clt_loss: call clt_forward first (decoder norms missing)"); return CLT_ERR_STATE; }
   hipStream_t s = static_cast<hipStream_t>(stream);
   const Dims D = h->D;
@@ -364,20 +372,27 @@ int clt_loss(clt_handle* h, void* stream, const void* y, const float* y_scale, c
   float* norms = reinterpret_cast<float*>(h->ws + h->plan.norms);
   float* G = reinterpret_cast<float*>(h->ws + h->plan.G);
   float* part = reinterpret_cast<float*>(h->ws + h->plan.part_cols);
+  float* part2 = reinterpret_cast<float*>(h->ws + h->plan.part_cols2);
   double* prec = reinterpret_cast<double*>(h->ws + h->plan.part_rec);
   double* psp = reinterpret_cast<double*>(h->ws + h->plan.part_sp);
+  double* pdead = reinterpret_cast<double*>(h->ws + h->plan.part_dead);
   void* d_yhat = h->ws + h->plan.d_yhat;
   h->stage = 1;
-  // sparsity first: its column partials are folded into G before the same
-  // partial buffer is reused for the db_dec partials of the reconstruction pass
-  RUN(h, s, K_LOSS_SP, launch_loss_sparsity(s, h->bf16, D, z, norms, h->cfg.C, psp, part));
+  // sparsity (and dead-feature) terms first: their column partials are folded into G
+  // before the same partial buffer is reused for the db_dec partials of the reconstruction pass
+  RUN(h, s, K_LOSS_SP, launch_loss_sparsity(s, h->bf16, D, z, norms, h->cfg.C, psp, part, dead ? pre : nullptr, theta,
+                                            h->cfg.log_threshold != 0, pdead, part2));
   RUN(h, s, K_COLRED, launch_col_reduce(s, part, rbs, D.L * D.F, lambda0 / (float)D.B, nullptr, 0.f, G));
+  if (dead)
+    RUN(h, s, K_COLRED, launch_col_reduce(s, part2, rbs, D.L * D.F, lambda1 / (float)D.B, nullptr, 0.f, G, true));
   RUN(h, s, K_LOSS_REC, launch_loss_rec(s, h->bf16, h->int8, D, y_hat, y, y_scale, d_yhat, prec, part));
-  RUN(h, s, K_LOSS_FINAL, launch_loss_final(s, prec, rbs * D.L, psp, rbs * D.L, 1.0f / (float)D.B, lambda0, loss_dev));
+  RUN(h, s, K_LOSS_FINAL, launch_loss_final(s, prec, rbs * D.L, psp, rbs * D.L, dead ? pdead : nullptr,
+                                            1.0f / (float)D.B, lambda0, lambda1, loss_dev));
   h->lambda0 = lambda0;
+  h->lambda1 = lambda1;
   h->stage = 2;
   if (loss_host) {
-    HIPCHK(h, hipMemcpyAsync(loss_host, loss_dev, 3 * sizeof(float), hipMemcpyDeviceToHost, s));
+    HIPCHK(h, hipMemcpyAsync(loss_host, loss_dev, 4 * sizeof(float), hipMemcpyDeviceToHost, s));
     HIPCHK(h, hipStreamSynchronize(s));
   }
   return CLT_OK;
@@ -397,16 +412,21 @@ static int backward_impl(clt_handle* h, hipStream_t s, const void* x, const floa
   float* part = reinterpret_cast<float*>(h->ws + h->plan.part_cols);
   float* part2 = reinterpret_cast<float*>(h->ws + h->plan.part_cols2);
   void* d_yhat = h->ws + h->plan.d_yhat;
+  float* part3 = reinterpret_cast<float*>(h->ws + h->plan.part_cols3);
   void* dpre = h->ws + h->plan.dpre;
+  const float lam1_over_b = h->lambda1 / (float)D.B;
 
   // db_dec from the column partials that clt_loss left behind
   RUN(h, s, K_COLRED, launch_col_reduce(s, part, rbs, D.L * D.d, 1.0f, nullptr, 0.f, gb_dec));
-  DzArgs za{d_yhat, W_dec, z, act_class, norms, h->lambda0 * h->cfg.C / (float)D.B, h->cfg.C, dpre};
+  DzArgs za{d_yhat, W_dec, z, act_class, norms, h->lambda0 * h->cfg.C / (float)D.B, h->cfg.C, dpre,
+            lam1_over_b};
   DWdecArgs wa{z, d_yhat, W_dec, G, norms, gW_dec, fdec};
   DWencArgs ea{x, dpre, gW_enc, W_enc, fenc};
   if (h->bf16) RUN(h, s, K_DZ, launch_dz_bf16(s, D, za)); else RUN(h, s, K_DZ, launch_dz_f32(s, D, za));
-  RUN(h, s, K_STE, launch_ste_reduce(s, h->bf16, D, dpre, act_class, h->int8 ? x_scale : nullptr, part, part2));
-  RUN(h, s, K_COLRED, launch_col_reduce(s, part, rbs, D.L * D.F, 1.0f, theta, 1.0f / h->cfg.ste_bandwidth, gtheta));
+  RUN(h, s, K_STE, launch_ste_reduce(s, h->bf16, D, dpre, act_class, h->int8 ? x_scale : nullptr, norms, lam1_over_b,
+                                     part, part2, part3));
+  RUN(h, s, K_COLRED, launch_dtheta_final(s, part, part3, rbs, D.L * D.F, theta, h->cfg.log_threshold != 0, norms,
+                                          1.0f / h->cfg.ste_bandwidth, lam1_over_b, gtheta));
   RUN(h, s, K_COLRED, launch_col_reduce(s, part2, rbs, D.L * D.F, 1.0f, nullptr, 0.f, gb_enc));
   if (h->bf16) {
     RUN(h, s, K_DWENC, launch_dwenc_bf16(s, D, ea, h->int8));

@@ -61,6 +61,12 @@ struct AdamScalars { float lr, beta1, beta2, eps, bc1, bc2; };   // bc = 1 - bet
 // act_class bits
 constexpr uint8_t CLS_ACTIVE = 1;
 constexpr uint8_t CLS_WINDOW = 2;
+constexpr uint8_t CLS_BELOW = 4;   // pre < theta strictly (where the dead-feature term has a gradient)
+
+// The stored threshold parameter is theta itself or tau = log(theta) (App. B writes exp(tau)).
+__device__ __forceinline__ float threshold_value(float param, bool log_threshold) {
+  return log_threshold ? expf(param) : param;
+}
 
 // ---------------------------------------------------------------------------
 // Launch interface.  `bf16` selects the storage type T of matrices/activations.
@@ -69,6 +75,7 @@ constexpr uint8_t CLS_WINDOW = 2;
 struct EncArgs {       // pre = x W_enc + b_enc; JumpReLU; classes; L0 counts
   const void* x; const float* x_scale; const void* W_enc; const float* b_enc; const float* theta;
   float ste_eps; void* z; void* pre; uint8_t* cls; int32_t* l0;
+  bool log_threshold;     // theta holds tau = log(theta)
 };
 struct DecArgs {       // y_hat[lp] = sum_{l<=lp} z[l] W_dec[p(l,lp)] + b_dec[lp]
   const void* z; const void* W_dec; const float* b_dec; float* y_hat;
@@ -78,6 +85,7 @@ struct DecArgs {       // y_hat[lp] = sum_{l<=lp} z[l] W_dec[p(l,lp)] + b_dec[lp
 struct DzArgs {        // dz[l] = sum_{lp>=l} dyhat[lp] W_dec[p(l,lp)]^T + g_sp, kept where active|window
   const void* d_yhat; const void* W_dec; const void* z; const uint8_t* cls; const float* norms;
   float lam_c_over_b; float C; void* dpre;
+  float lam1_over_b;      // dead-feature coefficient lambda1 / B (0 = term off)
 };
 // Optional Adam fused into the two weight-gradient GEMMs (m == nullptr: plain gradient output)
 struct AdamFuseArgs { float* m; float* v; float* master; AdamScalars a; };
@@ -113,18 +121,29 @@ hipError_t launch_decoder_norms(hipStream_t s, bool bf16, Dims D, const void* W_
 hipError_t launch_loss_rec(hipStream_t s, bool bf16, bool int8_y, Dims D, const float* y_hat, const void* y,
                            const float* y_scale, void* d_yhat, double* loss_part, float* col_part);
 // L_sp partials and column partials of C z sech^2(C z n)
+// with pre != NULL also the dead-feature partial sums: sum relu(theta - pre) n into dead_part and the column
+// partials of relu(theta - pre) into dead_col_part
 hipError_t launch_loss_sparsity(hipStream_t s, bool bf16, Dims D, const void* z, const float* norms, float C,
-                                double* loss_part, float* col_part);
-// final loss: loss_dev = {rec + sp, rec, sp}
+                                double* loss_part, float* col_part, const void* pre, const float* theta,
+                                bool log_threshold, double* dead_part, float* dead_col_part);
+// final loss: loss_dev = {rec + sp + dead, rec, sp, dead}
 hipError_t launch_loss_final(hipStream_t s, const double* part_rec, int n_rec, const double* part_sp, int n_sp,
-                             float inv_B, float lambda0, float* loss_dev);
+                             const double* part_dead_or_null, float inv_B, float lambda0, float lambda1,
+                             float* loss_dev);
 // out[c] = alpha * sum_r part[r][c] (fixed order), optionally times -(theta[c]/eps)
 hipError_t launch_col_reduce(hipStream_t s, const float* part, int nparts, int ncols, float alpha,
-                             const float* theta_or_null, float inv_eps, float* out);
+                             const float* theta_or_null, float inv_eps, float* out, bool accumulate = false);
+// dtheta[c] = -(theta/eps) sum_r part_win[r][c] + lam1_over_b * norms[c] * sum_r part_below[r][c], times theta
+// when the parameter is log(theta)
+hipError_t launch_dtheta_final(hipStream_t s, const float* part_win, const float* part_below, int nparts, int ncols,
+                               const float* theta_param, bool log_threshold, const float* norms, float inv_eps,
+                               float lam1_over_b, float* out);
 // reads dz kept where active|window: column partials for dtheta (window) and db_enc (active);
 // zeroes entries that are in the window but not active so the buffer becomes dpre
+// (entries that are below the threshold get the dead-feature gradient -lam1_over_b * n; part_below counts them)
 hipError_t launch_ste_reduce(hipStream_t s, bool bf16, Dims D, void* dpre, const uint8_t* cls,
-                             const float* row_scale_or_null, float* part_theta, float* part_benc);
+                             const float* row_scale_or_null, const float* norms, float lam1_over_b,
+                             float* part_theta, float* part_benc, float* part_below);
 
 // p, g in T (or p in T with fp32 master); m, v float
 hipError_t launch_adam_matrix(hipStream_t s, bool bf16, size_t n, void* p, const void* g, float* m, float* v,

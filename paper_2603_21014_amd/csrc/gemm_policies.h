@@ -116,6 +116,7 @@ struct EncPolicy {
   int M, N, kseg, lda, ldb;
   const TA* x; const T* W_enc; const float* b_enc; const float* theta; const float* x_scale;
   float half_eps; T* z; T* pre; uint8_t* cls; int32_t* l0;
+  bool log_threshold;
   __device__ bool skip() const { return false; }
   struct GInfo { int l; };
   struct Epi { int count; };
@@ -130,6 +131,7 @@ struct EncPolicy {
     const size_t vo = (size_t)g.l * D.F + col;
     r.b = *reinterpret_cast<const float4*>(b_enc + vo);
     r.th = *reinterpret_cast<const float4*>(theta + vo);
+    if (log_threshold) r.th = make_float4(expf(r.th.x), expf(r.th.y), expf(r.th.z), expf(r.th.w));
     r.s = x_scale ? x_scale[(size_t)g.l * D.B + row] : 1.0f;
   }
   __device__ void epi4(Epi& e, const GInfo& g, int row, int col, float4 v, const EpiRegs& r) const {
@@ -147,7 +149,7 @@ struct EncPolicy {
       const bool act = p[i] > t[i];
       const bool win = fabsf(p[i] - t[i]) < half_eps;
       zz[i] = act ? p[i] : 0.0f;
-      c[i] = (act ? CLS_ACTIVE : 0) | (win ? CLS_WINDOW : 0);
+      c[i] = (act ? CLS_ACTIVE : 0) | (win ? CLS_WINDOW : 0) | (p[i] < t[i] ? CLS_BELOW : 0);
       e.count += act ? 1 : 0;
     }
     const size_t o = ((size_t)g.l * D.B + row) * D.F + col;
@@ -211,6 +213,7 @@ struct DzPolicy {
   int M, N, kseg, lda, ldb;
   const T* d_yhat; const T* W_dec; const T* z; const uint8_t* cls; const float* norms;
   float lam_c_over_b, C; T* dpre;
+  float lam1_over_b;
   __device__ bool skip() const { return false; }
   struct GInfo { int l; };
   struct Epi {};
@@ -233,19 +236,25 @@ struct DzPolicy {
     const size_t o = ((size_t)g.l * D.B + row) * D.F + col;
     const uint32_t c4 = r.c4;
     float4 out = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (c4) {
+    const float4 n4 = r.n4;
+    const float nn[4] = {n4.x, n4.y, n4.z, n4.w};
+    if (c4 & 0x03030303u) {          // some entry active or in the window: dz is kept there
       const float4 z4 = r.z4;
-      const float4 n4 = r.n4;
-      const float zz[4] = {z4.x, z4.y, z4.z, z4.w}, nn[4] = {n4.x, n4.y, n4.z, n4.w};
+      const float zz[4] = {z4.x, z4.y, z4.z, z4.w};
       const float vv[4] = {v.x, v.y, v.z, v.w};
       float r[4];
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         const float t = tanhf(C * zz[i] * nn[i]);
         const float gsp = lam_c_over_b * nn[i] * (1.0f - t * t);
-        r[i] = ((c4 >> (8 * i)) & 3u) ? vv[i] + gsp : 0.0f;
+        const uint32_t ci = (c4 >> (8 * i)) & 7u;
+        // elsewhere only the dead-feature gradient of pre < theta
+        r[i] = (ci & 3u) ? vv[i] + gsp : ((ci & CLS_BELOW) ? 0.0f - lam1_over_b * nn[i] : 0.0f);
       }
       out = make_float4(r[0], r[1], r[2], r[3]);
+    } else if (lam1_over_b != 0.f && c4) {
+      out = make_float4((c4 & 0x4u) ? -lam1_over_b * nn[0] : 0.f, (c4 & 0x400u) ? -lam1_over_b * nn[1] : 0.f,
+                        (c4 & 0x40000u) ? -lam1_over_b * nn[2] : 0.f, (c4 & 0x4000000u) ? -lam1_over_b * nn[3] : 0.f);
     }
     Elem<T>::store4(dpre + o, out);
   }

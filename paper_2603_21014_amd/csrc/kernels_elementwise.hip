@@ -92,22 +92,35 @@ __global__ __launch_bounds__(256) void loss_rec_kernel(Dims D, const float* __re
   if (threadIdx.x == 0) loss_part[(size_t)l * gridDim.x + rb] = tot;
 }
 
-// ---- sparsity loss: partial sum tanh(C z n); column partials of C z sech^2(C z n)
-template <typename T>
+// ---- sparsity loss: partial sum tanh(C z n); column partials of C z sech^2(C z n).
+// With DEAD also the App. B dead-feature term: partial sum relu(theta - pre) n and the
+// column partials of relu(theta - pre) (its derivative w.r.t. the decoder norm).
+template <typename T, bool DEAD>
 __global__ __launch_bounds__(256) void loss_sparsity_kernel(Dims D, const T* __restrict__ z,
                                                             const float* __restrict__ norms, float C,
                                                             double* __restrict__ loss_part,
-                                                            float* __restrict__ col_part) {
+                                                            float* __restrict__ col_part, const T* __restrict__ pre,
+                                                            const float* __restrict__ theta, bool log_threshold,
+                                                            double* __restrict__ dead_part,
+                                                            float* __restrict__ dead_col_part) {
   const int rb = blockIdx.x, l = blockIdx.y;
   const int r0 = rb * LOSS_ROWS_PER_BLOCK, r1 = min(D.B, r0 + LOSS_ROWS_PER_BLOCK);
-  double sp = 0.0;
+  double sp = 0.0, dead = 0.0;
   for (int c = threadIdx.x * 4; c < D.F; c += 1024) {
     const float4 n4 = *reinterpret_cast<const float4*>(norms + (size_t)l * D.F + c);
+    const float nn[4] = {n4.x, n4.y, n4.z, n4.w};
     const float cn[4] = {C * n4.x, C * n4.y, C * n4.z, C * n4.w};
-    float cs[4] = {0.f, 0.f, 0.f, 0.f};
-    float ts = 0.f;
+    float th[4] = {0.f, 0.f, 0.f, 0.f};
+    if (DEAD) {
+      const float4 t4 = *reinterpret_cast<const float4*>(theta + (size_t)l * D.F + c);
+      th[0] = threshold_value(t4.x, log_threshold); th[1] = threshold_value(t4.y, log_threshold);
+      th[2] = threshold_value(t4.z, log_threshold); th[3] = threshold_value(t4.w, log_threshold);
+    }
+    float cs[4] = {0.f, 0.f, 0.f, 0.f}, ds[4] = {0.f, 0.f, 0.f, 0.f};
+    float ts = 0.f, dsum = 0.f;
     for (int r = r0; r < r1; ++r) {
-      const float4 z4 = Elem<T>::load4(z + ((size_t)l * D.B + r) * D.F + c);
+      const size_t o = ((size_t)l * D.B + r) * D.F + c;
+      const float4 z4 = Elem<T>::load4(z + o);
       const float zz[4] = {z4.x, z4.y, z4.z, z4.w};
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
@@ -117,61 +130,117 @@ __global__ __launch_bounds__(256) void loss_sparsity_kernel(Dims D, const T* __r
           cs[i] += C * zz[i] * (1.0f - t * t);
         }
       }
+      if (DEAD) {
+        const float4 p4 = Elem<T>::load4(pre + o);
+        const float pp[4] = {p4.x, p4.y, p4.z, p4.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const float g = fmaxf(th[i] - pp[i], 0.f);
+          ds[i] += g;
+          dsum += g * nn[i];
+        }
+      }
     }
     sp += (double)ts;
-    *reinterpret_cast<float4*>(col_part + ((size_t)rb * D.L + l) * D.F + c) = make_float4(cs[0], cs[1], cs[2], cs[3]);
+    dead += (double)dsum;
+    const size_t po = ((size_t)rb * D.L + l) * D.F + c;
+    *reinterpret_cast<float4*>(col_part + po) = make_float4(cs[0], cs[1], cs[2], cs[3]);
+    if (DEAD) *reinterpret_cast<float4*>(dead_col_part + po) = make_float4(ds[0], ds[1], ds[2], ds[3]);
   }
   const double tot = block_sum_256(sp);
   if (threadIdx.x == 0) loss_part[(size_t)l * gridDim.x + rb] = tot;
+  if (DEAD) {
+    __syncthreads();
+    const double dt = block_sum_256(dead);
+    if (threadIdx.x == 0) dead_part[(size_t)l * gridDim.x + rb] = dt;
+  }
 }
 
 __global__ __launch_bounds__(256) void loss_final_kernel(const double* part_rec, int n_rec, const double* part_sp,
-                                                         int n_sp, float inv_B, float lambda0, float* loss_dev) {
-  double a = 0.0, b = 0.0;
+                                                         int n_sp, const double* part_dead, float inv_B, float lambda0,
+                                                         float lambda1, float* loss_dev) {
+  double a = 0.0, b = 0.0, c = 0.0;
   for (int i = threadIdx.x; i < n_rec; i += 256) a += part_rec[i];
   for (int i = threadIdx.x; i < n_sp; i += 256) b += part_sp[i];
+  if (part_dead)
+    for (int i = threadIdx.x; i < n_sp; i += 256) c += part_dead[i];
   a = block_sum_256(a);
   __syncthreads();
   b = block_sum_256(b);
+  __syncthreads();
+  c = block_sum_256(c);
   if (threadIdx.x == 0) {
     const double rec = a * (double)inv_B, sp = b * (double)inv_B * (double)lambda0;
-    loss_dev[0] = (float)(rec + sp);
+    const double dead = c * (double)inv_B * (double)lambda1;
+    loss_dev[0] = (float)(rec + sp + dead);
     loss_dev[1] = (float)rec;
     loss_dev[2] = (float)sp;
+    loss_dev[3] = (float)dead;
   }
 }
 
 __global__ __launch_bounds__(256) void col_reduce_kernel(const float* __restrict__ part, int nparts, int ncols,
                                                          float alpha, const float* __restrict__ theta, float inv_eps,
-                                                         float* __restrict__ out) {
+                                                         float* __restrict__ out, bool accumulate) {
   const int c = blockIdx.x * 256 + threadIdx.x;
   if (c >= ncols) return;
   float s = 0.f;
   for (int r = 0; r < nparts; ++r) s += part[(size_t)r * ncols + c];
   s *= alpha;
   if (theta) s = (s == 0.f) ? 0.f : s * -(theta[c] * inv_eps);   // empty window: exactly 0, also for theta = inf
-  out[c] = s;
+  out[c] = accumulate ? out[c] + s : s;
+}
+
+// Threshold gradient: straight-through part -(theta/eps) * (sum over window entries of dz), plus the
+// dead-feature part (lambda1/B) n * #(pre < theta); times theta when the parameter is tau = log(theta).
+__global__ __launch_bounds__(256) void dtheta_final_kernel(const float* __restrict__ part_win,
+                                                           const float* __restrict__ part_below, int nparts,
+                                                           int ncols, const float* __restrict__ theta_param,
+                                                           bool log_threshold, const float* __restrict__ norms,
+                                                           float inv_eps, float lam1_over_b,
+                                                           float* __restrict__ out) {
+  const int c = blockIdx.x * 256 + threadIdx.x;
+  if (c >= ncols) return;
+  float w = 0.f, nb = 0.f;
+  for (int r = 0; r < nparts; ++r) w += part_win[(size_t)r * ncols + c];
+  if (lam1_over_b != 0.f)
+    for (int r = 0; r < nparts; ++r) nb += part_below[(size_t)r * ncols + c];
+  const float th = threshold_value(theta_param[c], log_threshold);
+  float g = (w == 0.f) ? 0.f : w * -(th * inv_eps);   // empty window: exactly 0, also for theta = inf
+  if (lam1_over_b != 0.f) g += lam1_over_b * norms[c] * nb;
+  out[c] = log_threshold ? g * th : g;
 }
 
 // ---- straight-through reductions over the buffer that holds dz where a feature
-// is active or in the threshold window: column partials of dz over the window
-// (-> dtheta) and over the active set (-> db_enc); entries that are in the
-// window but inactive are zeroed so the buffer becomes dpre.  With a row scale
-// (int8 inputs) dpre rows are additionally multiplied by it, because the
-// encoder-weight gradient contracts them with the integer codes.
+// is active or in the threshold window, and the dead-feature gradient elsewhere
+// below the threshold: column partials of dz over the window (-> dtheta), of the
+// final dpre (-> db_enc) and of the below-threshold count; entries that are in the
+// window but inactive are rewritten to their dpre value (dead-feature gradient or 0),
+// so the buffer becomes dpre.  With a row scale (int8 inputs) dpre rows are also
+// multiplied by it, because the encoder-weight gradient contracts them with the
+// integer codes.
 template <typename T>
 __global__ __launch_bounds__(256) void ste_reduce_kernel(Dims D, T* __restrict__ dpre,
                                                          const uint8_t* __restrict__ cls,
                                                          const float* __restrict__ row_scale,
+                                                         const float* __restrict__ norms, float lam1_over_b,
                                                          float* __restrict__ part_theta,
-                                                         float* __restrict__ part_benc) {
+                                                         float* __restrict__ part_benc,
+                                                         float* __restrict__ part_below) {
   const int rb = blockIdx.x, l = blockIdx.y;
   const int r0 = rb * LOSS_ROWS_PER_BLOCK, r1 = min(D.B, r0 + LOSS_ROWS_PER_BLOCK);
+  const bool dead = lam1_over_b != 0.f;
   for (int c = threadIdx.x * 4; c < D.F; c += 1024) {
-    float st[4] = {0.f, 0.f, 0.f, 0.f}, sb[4] = {0.f, 0.f, 0.f, 0.f};
+    float st[4] = {0.f, 0.f, 0.f, 0.f}, sb[4] = {0.f, 0.f, 0.f, 0.f}, nb[4] = {0.f, 0.f, 0.f, 0.f};
+    float dg[4] = {0.f, 0.f, 0.f, 0.f};
+    if (dead) {
+      const float4 n4 = *reinterpret_cast<const float4*>(norms + (size_t)l * D.F + c);
+      dg[0] = -lam1_over_b * n4.x; dg[1] = -lam1_over_b * n4.y; dg[2] = -lam1_over_b * n4.z; dg[3] = -lam1_over_b * n4.w;
+    }
     for (int r = r0; r < r1; ++r) {
       const size_t o = ((size_t)l * D.B + r) * D.F + c;
-      const uint32_t c4 = *reinterpret_cast<const uint32_t*>(cls + o);
+      uint32_t c4 = *reinterpret_cast<const uint32_t*>(cls + o);
+      if (!dead) c4 &= 0x03030303u;       // without the dead-feature term only active / window entries matter
       if (!c4) continue;
       const float4 g4 = Elem<T>::load4(dpre + o);
       float g[4] = {g4.x, g4.y, g4.z, g4.w};
@@ -179,14 +248,16 @@ __global__ __launch_bounds__(256) void ste_reduce_kernel(Dims D, T* __restrict__
       const float s = row_scale ? row_scale[(size_t)l * D.B + r] : 1.0f;
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        const uint32_t ci = (c4 >> (8 * i)) & 3u;
+        const uint32_t ci = (c4 >> (8 * i)) & 7u;
         if (ci & CLS_WINDOW) st[i] += g[i];
-        if (ci & CLS_ACTIVE) {
+        if (ci & CLS_BELOW) nb[i] += 1.0f;
+        if (!(ci & CLS_ACTIVE) && (ci & CLS_WINDOW)) {   // held dz for the threshold gradient only
+          g[i] = (ci & CLS_BELOW) ? dg[i] : 0.f;
+          rewrite = true;
+        }
+        if (ci) {
           sb[i] += g[i];
           g[i] *= s;
-        } else if (ci) {
-          g[i] = 0.f;
-          rewrite = true;
         }
       }
       if (rewrite) Elem<T>::store4(dpre + o, make_float4(g[0], g[1], g[2], g[3]));
@@ -194,6 +265,7 @@ __global__ __launch_bounds__(256) void ste_reduce_kernel(Dims D, T* __restrict__
     const size_t po = ((size_t)rb * D.L + l) * D.F + c;
     *reinterpret_cast<float4*>(part_theta + po) = make_float4(st[0], st[1], st[2], st[3]);
     *reinterpret_cast<float4*>(part_benc + po) = make_float4(sb[0], sb[1], sb[2], sb[3]);
+    if (dead) *reinterpret_cast<float4*>(part_below + po) = make_float4(nb[0], nb[1], nb[2], nb[3]);
   }
 }
 
@@ -265,40 +337,51 @@ hipError_t launch_loss_rec(hipStream_t s, bool bf16, bool int8_y, Dims D, const 
 }
 
 hipError_t launch_loss_sparsity(hipStream_t s, bool bf16, Dims D, const void* z, const float* norms, float C,
-                                double* loss_part, float* col_part) {
+                                double* loss_part, float* col_part, const void* pre, const float* theta,
+                                bool log_threshold, double* dead_part, float* dead_col_part) {
   const dim3 grid(row_blocks(D.B), D.L);
-  if (bf16)
-    hipLaunchKernelGGL((loss_sparsity_kernel<bf16_t>), grid, dim3(256), 0, s, D, (const bf16_t*)z, norms, C,
-                       loss_part, col_part);
-  else
-    hipLaunchKernelGGL((loss_sparsity_kernel<float>), grid, dim3(256), 0, s, D, (const float*)z, norms, C, loss_part,
-                       col_part);
+#define CLT_LSP(T, DEAD)                                                                                      \
+  hipLaunchKernelGGL((loss_sparsity_kernel<T, DEAD>), grid, dim3(256), 0, s, D, (const T*)z, norms, C, loss_part, \
+                     col_part, (const T*)pre, theta, log_threshold, dead_part, dead_col_part)
+  if (bf16) { if (pre) CLT_LSP(bf16_t, true); else CLT_LSP(bf16_t, false); }
+  else { if (pre) CLT_LSP(float, true); else CLT_LSP(float, false); }
+#undef CLT_LSP
   return hipGetLastError();
 }
 
 hipError_t launch_loss_final(hipStream_t s, const double* part_rec, int n_rec, const double* part_sp, int n_sp,
-                             float inv_B, float lambda0, float* loss_dev) {
-  hipLaunchKernelGGL(loss_final_kernel, dim3(1), dim3(256), 0, s, part_rec, n_rec, part_sp, n_sp, inv_B, lambda0,
-                     loss_dev);
+                             const double* part_dead_or_null, float inv_B, float lambda0, float lambda1,
+                             float* loss_dev) {
+  hipLaunchKernelGGL(loss_final_kernel, dim3(1), dim3(256), 0, s, part_rec, n_rec, part_sp, n_sp, part_dead_or_null,
+                     inv_B, lambda0, lambda1, loss_dev);
   return hipGetLastError();
 }
 
 hipError_t launch_col_reduce(hipStream_t s, const float* part, int nparts, int ncols, float alpha,
-                             const float* theta_or_null, float inv_eps, float* out) {
+                             const float* theta_or_null, float inv_eps, float* out, bool accumulate) {
   hipLaunchKernelGGL(col_reduce_kernel, dim3((ncols + 255) / 256), dim3(256), 0, s, part, nparts, ncols, alpha,
-                     theta_or_null, inv_eps, out);
+                     theta_or_null, inv_eps, out, accumulate);
+  return hipGetLastError();
+}
+
+hipError_t launch_dtheta_final(hipStream_t s, const float* part_win, const float* part_below, int nparts, int ncols,
+                               const float* theta_param, bool log_threshold, const float* norms, float inv_eps,
+                               float lam1_over_b, float* out) {
+  hipLaunchKernelGGL(dtheta_final_kernel, dim3((ncols + 255) / 256), dim3(256), 0, s, part_win, part_below, nparts,
+                     ncols, theta_param, log_threshold, norms, inv_eps, lam1_over_b, out);
   return hipGetLastError();
 }
 
 hipError_t launch_ste_reduce(hipStream_t s, bool bf16, Dims D, void* dpre, const uint8_t* cls,
-                             const float* row_scale_or_null, float* part_theta, float* part_benc) {
+                             const float* row_scale_or_null, const float* norms, float lam1_over_b,
+                             float* part_theta, float* part_benc, float* part_below) {
   const dim3 grid(row_blocks(D.B), D.L);
   if (bf16)
     hipLaunchKernelGGL((ste_reduce_kernel<bf16_t>), grid, dim3(256), 0, s, D, (bf16_t*)dpre, cls, row_scale_or_null,
-                       part_theta, part_benc);
+                       norms, lam1_over_b, part_theta, part_benc, part_below);
   else
     hipLaunchKernelGGL((ste_reduce_kernel<float>), grid, dim3(256), 0, s, D, (float*)dpre, cls, row_scale_or_null,
-                       part_theta, part_benc);
+                       norms, lam1_over_b, part_theta, part_benc, part_below);
   return hipGetLastError();
 }
 

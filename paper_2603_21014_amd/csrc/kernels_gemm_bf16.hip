@@ -359,12 +359,12 @@ hipError_t launch_enc_bf16(hipStream_t s, Dims D, const EncArgs& a, bool int8_x)
   if (int8_x) {
     EncPolicy<bf16_t, int8_t> p{D, D.B, D.F, D.d, D.d, D.F,
                                 (const int8_t*)a.x, (const bf16_t*)a.W_enc, a.b_enc, a.theta, a.x_scale,
-                                0.5f * a.ste_eps, (bf16_t*)a.z, (bf16_t*)a.pre, a.cls, a.l0};
+                                0.5f * a.ste_eps, (bf16_t*)a.z, (bf16_t*)a.pre, a.cls, a.l0, a.log_threshold};
     return launch(s, p, D.L);
   }
   EncPolicy<bf16_t> p{D, D.B, D.F, D.d, D.d, D.F,
                       (const bf16_t*)a.x, (const bf16_t*)a.W_enc, a.b_enc, a.theta, nullptr,
-                      0.5f * a.ste_eps, (bf16_t*)a.z, (bf16_t*)a.pre, a.cls, a.l0};
+                      0.5f * a.ste_eps, (bf16_t*)a.z, (bf16_t*)a.pre, a.cls, a.l0, a.log_threshold};
   return launch(s, p, D.L);
 }
 hipError_t launch_dec_bf16(hipStream_t s, Dims D, const DecArgs& a) {
@@ -374,7 +374,7 @@ hipError_t launch_dec_bf16(hipStream_t s, Dims D, const DecArgs& a) {
 hipError_t launch_dz_bf16(hipStream_t s, Dims D, const DzArgs& a) {
   DzPolicy<bf16_t> p{D, D.B, D.F, D.d, D.d, D.d,
                      (const bf16_t*)a.d_yhat, (const bf16_t*)a.W_dec, (const bf16_t*)a.z, a.cls, a.norms,
-                     a.lam_c_over_b, a.C, (bf16_t*)a.dpre};
+                     a.lam_c_over_b, a.C, (bf16_t*)a.dpre, a.lam1_over_b};
   return launch(s, p, D.L);
 }
 hipError_t launch_dwdec_bf16(hipStream_t s, Dims D, const DWdecArgs& a) {

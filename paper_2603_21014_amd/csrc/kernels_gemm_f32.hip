@@ -93,7 +93,7 @@ hipError_t launch(hipStream_t s, const P& p, int G) {
 hipError_t launch_enc_f32(hipStream_t s, Dims D, const EncArgs& a) {
   EncPolicy<float> p{D, D.B, D.F, D.d, D.d, D.F,
                      (const float*)a.x, (const float*)a.W_enc, a.b_enc, a.theta, nullptr,
-                     0.5f * a.ste_eps, (float*)a.z, (float*)a.pre, a.cls, a.l0};
+                     0.5f * a.ste_eps, (float*)a.z, (float*)a.pre, a.cls, a.l0, a.log_threshold};
   return launch(s, p, D.L);
 }
 hipError_t launch_dec_f32(hipStream_t s, Dims D, const DecArgs& a) {
@@ -103,7 +103,7 @@ hipError_t launch_dec_f32(hipStream_t s, Dims D, const DecArgs& a) {
 hipError_t launch_dz_f32(hipStream_t s, Dims D, const DzArgs& a) {
   DzPolicy<float> p{D, D.B, D.F, D.d, D.d, D.d,
                     (const float*)a.d_yhat, (const float*)a.W_dec, (const float*)a.z, a.cls, a.norms,
-                    a.lam_c_over_b, a.C, (float*)a.dpre};
+                    a.lam_c_over_b, a.C, (float*)a.dpre, a.lam1_over_b};
   return launch(s, p, D.L);
 }
 hipError_t launch_dwdec_f32(hipStream_t s, Dims D, const DWdecArgs& a) {

@@ -42,14 +42,16 @@ class GpuRun:
             master = {k: params[k].to(dev, torch.float32).contiguous() for k in MATS}
         step = K.CLTStep(w.L, w.d, w.F, w.B, dtype=w.dtype, int8_inputs=w.int8_inputs,
                          master_weights=w.master_weights, C_=w.C, ste_bandwidth=w.ste_eps, device=dev,
-                         decode_mode=decode_mode, gather_density_threshold=gather_density_threshold)
+                         decode_mode=decode_mode, gather_density_threshold=gather_density_threshold,
+                         log_threshold=w.log_threshold)
         xg, yg = x.to(dev, TX).contiguous(), y.to(dev, TX).contiguous()
         xs = x_scale.to(dev) if x_scale is not None else None
         ys = y_scale.to(dev) if y_scale is not None else None
         step.forward(xg, gp, xs)
-        self.loss = step.loss(yg, w.lambda0, ys, to_host=True)
+        self.loss = step.loss(yg, w.lambda0, ys, to_host=True, lambda1=w.lambda1, params=gp)
         self.norms = to_np(K.clt_workspace_view(step.H, "norms"))
         self.d_yhat = to_np(K.clt_workspace_view(step.H, "d_yhat"))
+        self.G = to_np(K.clt_workspace_view(step.H, "G"))
         if fused:     # backward and Adam in one call, Adam inside the weight-gradient GEMM epilogues
             step.backward_adam_step(xg, gp, gm, gv, t, w.lr, master, xs)
         else:
@@ -59,6 +61,7 @@ class GpuRun:
         self.pre, self.z, self.y_hat = to_np(step.pre), to_np(step.z), to_np(step.y_hat)
         cls = step.act_class.cpu().numpy()
         self.active, self.window = (cls & 1).astype(bool), (cls & 2).astype(bool)
+        self.below = (cls & 4).astype(bool)
         self.l0 = step.l0.cpu().numpy()
         self.decode_switch = K.clt_workspace_view(step.H, "decode_switch").cpu().numpy()
         self.grads = {k: to_np(g) for k, g in step.grads.items()}
@@ -78,18 +81,23 @@ class OracleRun:
     asked to continue from that decision (it verifies the band itself)."""
 
     def __init__(self, w, params, x, y, t=1, m=None, v=None, gpu_active=None, gpu_window=None, theta=None,
-                 x_np=None, y_np=None):
+                 x_np=None, y_np=None, gpu_below=None):
         npar = {k: to_np(p) for k, p in params.items()}
         if theta is not None:
             npar["theta"] = to_np(theta)
         xn = to_np(x) if x_np is None else x_np
         yn = to_np(y) if y_np is None else y_np
-        self.fwd = O.forward(xn, npar["W_enc"], npar["b_enc"], npar["theta"], npar["W_dec"], npar["b_dec"],
+        self.x_np, self.y_np = xn, yn
+        self.theta = O.threshold_value(npar["theta"], w.log_threshold)
+        self.fwd = O.forward(xn, npar["W_enc"], npar["b_enc"], self.theta, npar["W_dec"], npar["b_dec"],
                              tie_break=gpu_active, band=MASK_BAND)
         self.n = O.decoder_norms(npar["W_dec"], w.L)
-        self.loss = O.loss_terms(self.fwd["y_hat"], yn, self.fwd["z"], self.n, w.lambda0, w.C)
-        self.bwd = O.backward(xn, yn, npar["theta"], npar["W_dec"], self.fwd, w.lambda0, w.C, w.ste_eps,
-                              window_tie_break=gpu_window, band=MASK_BAND)
+        tot, rec, sp = O.loss_terms(self.fwd["y_hat"], yn, self.fwd["z"], self.n, w.lambda0, w.C)
+        dead = O.dead_feature_term(self.fwd["pre"], self.theta, self.n, w.lambda1)
+        self.loss = (tot + dead, rec, sp, dead)
+        self.bwd = O.backward(xn, yn, self.theta, npar["W_dec"], self.fwd, w.lambda0, w.C, w.ste_eps,
+                              window_tie_break=gpu_window, band=MASK_BAND, lambda1=w.lambda1,
+                              log_threshold=w.log_threshold, below_tie_break=gpu_below)
         zeros = {k: np.zeros_like(a) for k, a in npar.items()}
         m = zeros if m is None else {k: to_np(a) for k, a in m.items()}
         v = zeros if v is None else {k: to_np(a) for k, a in v.items()}
@@ -103,7 +111,7 @@ class OracleRun:
 def compare_step(w, g: GpuRun, o: OracleRun, tol, check_adam=True):
     """Element-wise parity of every output of the step.  Returns the error table."""
     L = w.L
-    theta = o.params["theta"]
+    theta = o.theta
     pre_o = o.fwd["pre"]
     errs = {}
     # masks: identical except inside the band around the boundary
@@ -111,15 +119,18 @@ def compare_step(w, g: GpuRun, o: OracleRun, tol, check_adam=True):
     assert ((g.active == o.fwd["active"]) | band).all(), "active mask differs outside the band"
     wband = np.abs(np.abs(pre_o - theta[:, None, :]) - 0.5 * w.ste_eps) < MASK_BAND
     assert ((g.window == o.bwd["window"]) | wband).all(), "window mask differs outside the band"
+    assert ((g.below == (pre_o < theta[:, None, :])) | band).all(), "below-threshold mask differs outside the band"
+    assert not (g.below & g.active).any()
     assert (g.l0 == g.active.sum(axis=(1, 2))).all(), "l0_per_layer does not count the active mask"
     errs["pre"] = rel_l2(g.pre, pre_o)
     errs["z"] = rel_l2(g.z, o.fwd["z"])
     errs["norms"] = rel_l2(g.norms, o.n)
     for lp in range(L):
         errs[f"y_hat[{lp}]"] = rel_l2(g.y_hat[lp], o.fwd["y_hat"][lp])
-    for i, name in enumerate(("loss", "L_rec", "L_sp")):
+    for i, name in enumerate(("loss", "L_rec", "L_sp", "L_dead")):
         errs[name] = abs(g.loss[i] - o.loss[i]) / max(abs(o.loss[i]), 1e-30)
     errs["d_yhat"] = rel_l2(g.d_yhat, o.bwd["d_yhat"])
+    errs["G"] = rel_l2(g.G, o.bwd["G"])        # column sums of the objective's decoder-norm derivative
     if not w.int8_inputs:      # with int8 inputs the buffer holds dpre times the row scale of x
         errs["dpre"] = rel_l2(g.dpre, o.bwd["dpre"])
     for k in ("W_enc", "b_enc", "theta", "b_dec"):
@@ -177,5 +188,5 @@ def run_both(w, theta=None, t=1, m=None, v=None, **gpu_kw):
         yo = O.dequantize_rows(yin.numpy(), ys.numpy())
     g = GpuRun(w, params, xin, yin, t=t, m=m, v=v, x_scale=xs, y_scale=ys, theta=theta, **gpu_kw)
     o = OracleRun(w, params, x, y, t=t, m=m, v=v, gpu_active=g.active, gpu_window=g.window, theta=theta,
-                  x_np=xo, y_np=yo)
+                  x_np=xo, y_np=yo, gpu_below=g.below)
     return g, o

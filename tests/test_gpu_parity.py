@@ -147,6 +147,73 @@ def test_int8_row_scaled_inputs(L, d, F, B):
     show(f"int8 L{L} d{d} F{F} B{B}", compare_step(w, g, o, TOL["bf16"]))
 
 
+# ---------------------------------------------------------------- dead-feature penalty, log threshold
+def dead_term_matters(w, o, tol):
+    """The oracle with the term switched off differs from the oracle with it by far more than
+    the parity tolerance, in every output the term reaches: parity then proves it was computed."""
+    off = OracleRun(S.scaled(w, lambda1=0.0), {k: torch.tensor(v) for k, v in o.params.items()},
+                    None, None, gpu_active=o.fwd["active"], gpu_window=o.bwd["window"], x_np=o.x_np, y_np=o.y_np)
+    for k in ("dW_enc", "db_enc", "dtheta", "G", "dpre"):      # G is the term's way into dW_dec
+        assert rel_l2(off.bwd[k], o.bwd[k]) > 10 * tol, k
+    assert o.loss[3] > 10 * tol * o.loss[0]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("log_threshold", [False, True])
+@pytest.mark.parametrize("fused", [False, True])
+def test_dead_feature_term_full_step(dtype, log_threshold, fused):
+    """App. B third term, with the threshold stored directly or as its logarithm."""
+    w = S.scaled(S.WORKLOADS["tiny"], dtype=dtype, L=3, d=72, F=136, B=90, seed=41, lambda1=5.0,
+                 log_threshold=log_threshold)
+    g, o = run_both(w, fused=fused)
+    assert 0.2 < g.below.mean() < 0.8
+    dead_term_matters(w, o, TOL[dtype])
+    show(f"dead {dtype} log={log_threshold} fused={fused}", compare_step(w, g, o, TOL[dtype]))
+
+
+def test_dead_feature_term_bf16_several_tiles():
+    w = S.scaled(S.WORKLOADS["llama1b_dead"], L=3, d=512, F=768, B=300, k_active=16, lambda1=5.0)
+    g, o = run_both(w, fused=True)
+    dead_term_matters(w, o, TOL["bf16"])
+    show("dead bf16 multi-tile", compare_step(w, g, o, TOL["bf16"]))
+
+
+def test_dead_feature_term_int8_inputs():
+    """The row scale of the int8 codes also multiplies the dead-feature part of d pre on its
+    way into the encoder-weight gradient."""
+    w = S.scaled(S.WORKLOADS["llama1b_int8"], L=2, d=264, F=520, B=300, k_active=8, lambda1=5.0, log_threshold=True)
+    g, o = run_both(w)
+    dead_term_matters(w, o, TOL["bf16"])
+    show("dead int8", compare_step(w, g, o, TOL["bf16"]))
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_log_threshold_without_dead_term(dtype):
+    """Pure reparameterisation: same forward as theta = exp(tau), threshold gradient times theta."""
+    w = S.scaled(S.WORKLOADS["tiny"], dtype=dtype, L=2, d=64, F=256, B=128, seed=43, log_threshold=True)
+    g, o = run_both(w)
+    assert g.window.sum() > 100 and np.abs(o.bwd["dtheta"]).max() > 0
+    show(f"log-threshold {dtype}", compare_step(w, g, o, TOL[dtype]))
+
+
+def test_dead_term_needs_pre_and_theta():
+    from paper_2603_21014_amd import binding as K
+    w = S.scaled(S.WORKLOADS["tiny"], L=2, d=64, F=128, B=32)
+    step = K.CLTStep(w.L, w.d, w.F, w.B, dtype="f32", keep_pre=False)
+    params = {k: p.cuda() for k, p in S.make_params(w).items()}
+    x, y = (t.cuda() for t in S.make_inputs(w))
+    step.forward(x, params)
+    with pytest.raises(ValueError):
+        step.loss(y, 1.0, lambda1=0.5, params=params)          # no pre buffer was kept
+    with pytest.raises(K.CLTError) as e:                       # the ABI itself refuses the NULL pointer
+        K._check(K._lib.clt_loss(step.H.h, None, y.data_ptr(), None, step.y_hat.data_ptr(), step.z.data_ptr(),
+                                 None, None, 1.0, 0.5, step.loss_dev.data_ptr(), None), step.H.h)
+    assert e.value.code == -1
+    with pytest.raises(K.CLTError):
+        step.loss(y, 1.0, lambda1=-1.0, params=params)
+    torch.cuda.synchronize()
+
+
 # ---------------------------------------------------------------- gather decode and the switch
 DENSE, GATHER, AUTO = 1, 2, 0
 

@@ -127,3 +127,30 @@ def test_train_step_with_dead_term_moves_threshold_parameter():
     g = info["grads"]["dtheta"]
     assert (g >= 0).all() and (g > 0).any()          # only the dead term acts: it lowers the thresholds
     assert ((newp["theta"] - params["theta"])[g > 1e-6] < 0).all()
+
+
+def test_below_tie_break_is_honoured_only_inside_the_band():
+    rng = np.random.default_rng(13)
+    L, d, F, B = 2, 4, 6, 8
+    p = rand_problem(rng, L, d, F, B, theta=0.1)
+    fwd = O.forward(p["x"], p["W_enc"], p["b_enc"], p["theta"], p["W_dec"], p["b_dec"])
+    below = fwd["pre"] < p["theta"][:, None, :]
+    dist = np.abs(fwd["pre"] - p["theta"][:, None, :])
+    idx = np.unravel_index(np.argmin(dist), dist.shape)
+    band = 0.5 * (float(dist[idx]) + float(np.sort(dist.ravel())[1]))
+    assert (dist < band).sum() == 1
+    forced = below.copy()
+    forced[idx] = ~forced[idx]
+    kw = dict(lambda0=0.3, C=2.0, eps=0.05, lambda1=0.8)
+    base = O.backward(p["x"], p["y"], p["theta"], p["W_dec"], fwd, **kw)
+    flip = O.backward(p["x"], p["y"], p["theta"], p["W_dec"], fwd, band=band, below_tie_break=forced, **kw)
+    l, b, f = idx
+    n = O.decoder_norms(p["W_dec"], L)
+    sign = 1.0 if forced[idx] else -1.0        # one more (or one fewer) entry counted as below
+    assert abs((flip["dtheta"] - base["dtheta"])[l, f] - sign * 0.8 / B * n[l, f]) < 1e-12
+    assert abs((flip["dpre"] - base["dpre"])[idx] + sign * 0.8 / B * n[l, f]) < 1e-12
+    d_th = flip["dtheta"] - base["dtheta"]
+    d_th[l, f] = 0.0
+    assert not d_th.any()
+    with pytest.raises(ValueError):
+        O.backward(p["x"], p["y"], p["theta"], p["W_dec"], fwd, band=float(dist[idx]) * 0.5, below_tie_break=forced, **kw)

@@ -15,7 +15,8 @@ on cached OpenWebText activations (Sec. 3.1), which are not available here; the
 generator below stands in for them:
 
 * learned parameters: W_enc, W_dec ~ U(-1/sqrt(d), 1/sqrt(d)), biases 0,
-  theta = 0.03 (the dense, early-training regime of Sec. 3.2);
+  theta = 0.03 (the dense, early-training regime of Sec. 3.2), stored as
+  log(0.03) by the workloads that use the log-threshold parameterisation;
 * inputs: per-layer Gaussians scaled by (1 + 0.25 l); the "outlier" variant
   multiplies each token by a LogNormal(0, 0.5) norm and 4 fixed dims by 20
   (un-normalised residual-stream structure, cf. Sec. 3.1's normalisation);
@@ -49,6 +50,8 @@ class CLTWorkload:
     theta0: float = 0.03
     int8_inputs: bool = False
     master_weights: bool = False
+    lambda1: float = 0.0          # dead-feature coefficient of the App. B objective (0 = term off)
+    log_threshold: bool = False   # the theta tensor stores tau = log(theta)
 
     @property
     def P(self) -> int:
@@ -66,6 +69,8 @@ WORKLOADS = {
     "llama1b": CLTWorkload("llama1b", 16, 2048, 8192, 4096, "bf16", 64, True, 12.0, 1003),
     "gemma2b": CLTWorkload("gemma2b", 26, 2304, 16384, 2048, "bf16", 64, False, 12.0, 1004,
                            master_weights=True),
+    "llama1b_dead": CLTWorkload("llama1b_dead", 16, 2048, 8192, 4096, "bf16", 64, True, 12.0, 1003,
+                                lambda1=0.1, log_threshold=True),
     "llama1b_int8": CLTWorkload("llama1b_int8", 16, 2048, 8192, 4096, "bf16", 64, True, 12.0,
                                 1005, int8_inputs=True),
 }
@@ -100,7 +105,8 @@ def make_params(w: CLTWorkload, device="cpu"):
     return {
         "W_enc": _round_storage(W_enc, w.dtype),
         "b_enc": torch.zeros((w.L, w.F), device=device, dtype=torch.float32),
-        "theta": torch.full((w.L, w.F), w.theta0, device=device, dtype=torch.float32),
+        "theta": torch.full((w.L, w.F), math.log(w.theta0) if w.log_threshold else w.theta0, device=device,
+                            dtype=torch.float32),
         "W_dec": _round_storage(W_dec, w.dtype),
         "b_dec": torch.zeros((w.L, w.d), device=device, dtype=torch.float32),
     }
