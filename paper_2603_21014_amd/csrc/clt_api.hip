@@ -440,10 +440,13 @@ static int backward_impl(clt_handle* h, hipStream_t s, const void* x, const floa
 }
 
 static AdamScalars adam_scalars(const clt_handle* h, int64_t t, float lr) {
+  const double b1 = h->cfg.beta1, b2 = h->cfg.beta2;
   AdamScalars a;
-  a.lr = lr; a.beta1 = h->cfg.beta1; a.beta2 = h->cfg.beta2; a.eps = h->cfg.adam_eps;
-  a.bc1 = (float)(1.0 - pow((double)h->cfg.beta1, (double)t));
-  a.bc2 = (float)(1.0 - pow((double)h->cfg.beta2, (double)t));
+  a.b1 = h->cfg.beta1; a.omb1 = (float)(1.0 - b1);
+  a.b2 = h->cfg.beta2; a.omb2 = (float)(1.0 - b2);
+  a.inv_bc2 = (float)(1.0 / (1.0 - pow(b2, (double)t)));
+  a.neg_lr_over_bc1 = (float)(-(double)lr / (1.0 - pow(b1, (double)t)));
+  a.eps = h->cfg.adam_eps;
   return a;
 }
 

@@ -21,16 +21,14 @@ typedef uint16_t bf16_t;  // raw bf16 bits
 
 __device__ __forceinline__ float bf16_to_f32(bf16_t h) { return __uint_as_float(((uint32_t)h) << 16); }
 
-// Round-to-nearest-even float -> bf16 (NaN stays NaN).
-__device__ __forceinline__ bf16_t f32_to_bf16(float f) {
-  uint32_t u = __float_as_uint(f);
-  if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40);
-  u += 0x7fffu + ((u >> 16) & 1u);
-  return (bf16_t)(u >> 16);
-}
+// float -> bf16, round to nearest even (NaN stays NaN): gfx950's packed conversion instruction.
+typedef __bf16 hw_bf16x2 __attribute__((ext_vector_type(2)));
+typedef float hw_f32x2 __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
-  return (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16);
+  const hw_f32x2 f = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, hw_bf16x2));
 }
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) { return (bf16_t)(pack_bf16x2(f, 0.0f) & 0xffffu); }
 
 // Element-type traits for the two storage types.
 template <typename T> struct Elem;
@@ -56,7 +54,18 @@ template <> struct Elem<bf16_t> {
   }
 };
 
-struct AdamScalars { float lr, beta1, beta2, eps, bc1, bc2; };   // bc = 1 - beta^t
+// Adam (App. C Table 1) with bias correction, the step's scalars folded on the host:
+//   m' = b1 m + (1-b1) g,  v' = b2 v + (1-b2) g^2,
+//   p' = p - lr (m'/(1-b1^t)) / (sqrt(v'/(1-b2^t)) + eps)
+struct AdamScalars { float b1, omb1, b2, omb2, inv_bc2, neg_lr_over_bc1, eps; };
+// One element.  Square root and reciprocal are the hardware approximations (1 ulp each); the
+// correctly rounded forms cost ten times the instructions in epilogues that are ALU-bound.
+__device__ __forceinline__ void adam_element(float& p, float& m, float& v, float g, const AdamScalars& a) {
+  m = fmaf(a.b1, m, a.omb1 * g);
+  v = fmaf(a.b2, v, (a.omb2 * g) * g);
+  const float den = __builtin_amdgcn_sqrtf(v * a.inv_bc2) + a.eps;
+  p = fmaf(a.neg_lr_over_bc1 * m, __builtin_amdgcn_rcpf(den), p);
+}
 
 // act_class bits
 constexpr uint8_t CLS_ACTIVE = 1;

@@ -11,12 +11,16 @@
 //   M, N, kseg   tile-space extents and the length of one K segment
 //   ginfo(order) group visited at position `order` of the launch (longest K first)
 //   nseg(gi), a_seg(gi,s), b_seg(gi,s)   K segments of a group
-//   epi_load(regs, gi, row, col)  issues the global loads the epilogue of that 4-column
+//   epi_begin(st, gi, col, ok)    once per tile and lane: loads what depends on the lane's
+//                columns only (biases, thresholds, norms) when `ok` (col inside the matrix)
+//   epi_load(regs, gi, pos)       issues the global loads the epilogue of that 4-column
 //                group needs (the kernels call it for a batch of groups first, so the
 //                loads of the whole batch of EPI_BATCH groups are in flight together)
-//   epi4(st, gi, row, col, v, regs)  consumes 4 accumulators of one row, columns col..col+3
+//   epi4(st, gi, pos, v, regs)    consumes 4 accumulators of one row, columns col..col+3
 #pragma once
 #include "common.h"
+
+#include <type_traits>
 
 namespace clt {
 
@@ -46,7 +50,7 @@ struct TileGrid {
     return t;
   }
   __host__ __device__ int num_wg() const { return rounds * per_xcd * 8; }
-  __device__ bool decode(int wg, int& gorder, int& tm, int& tn) const {
+  __device__ __forceinline__ bool decode(int wg, int& gorder, int& tm, int& tn) const {
     const int xcd = wg & 7, slot = wg >> 3;
     const int team = xcd / S, rank = xcd - team * S;
     const int round = slot / per_xcd;
@@ -69,6 +73,25 @@ struct TileGrid {
   }
 };
 
+// Where a 4-column group of the epilogue lands: row = ru + rl, col = cu + cl.  ru and cu are
+// wave-uniform; rl and cl are the lane's fixed position inside its wave's block.  Element offsets
+// are formed as a uniform 64-bit part (scalar registers) plus a 32-bit per-lane byte offset that
+// is the same for every group of a tile, so the epilogue's memory accesses need no per-lane
+// 64-bit arithmetic.
+struct EpiPos {
+  int ru, cu, rl, cl;
+  __device__ __forceinline__ int row() const { return ru + rl; }
+  __device__ __forceinline__ int col() const { return cu + cl; }
+  // offsets of (row, col) in a row-major matrix with leading dimension ld that starts base_row rows in
+  __device__ __forceinline__ size_t uoff(size_t base_row, int ld) const { return (base_row + ru) * (size_t)ld + cu; }
+  __device__ __forceinline__ uint32_t loff(int ld) const { return (uint32_t)(rl * ld + cl); }
+};
+template <typename X>
+__device__ __forceinline__ X* epi_ptr(X* base, size_t uoff, uint32_t loff) {
+  typedef typename std::conditional<std::is_const<X>::value, const char, char>::type Byte;
+  return reinterpret_cast<X*>(reinterpret_cast<Byte*>(base + uoff) + loff * (uint32_t)sizeof(X));
+}
+
 // Adam fused into a weight-gradient epilogue: the fp32 gradient of 4 consecutive
 // parameters goes straight from the accumulators into the moments and the
 // weights (App. C Table 1 update rule; same arithmetic as adam_kernel).
@@ -77,32 +100,24 @@ struct AdamFuse {
 };
 struct AdamRegs { float4 m, v, p; };   // moments and the fp32 parameter (master copy or widened weight)
 template <typename T>
-__device__ __forceinline__ void adam_load4(AdamRegs& r, const AdamFuse& f, const T* w, size_t o) {
-  r.m = *reinterpret_cast<const float4*>(f.m + o);
-  r.v = *reinterpret_cast<const float4*>(f.v + o);
-  r.p = f.master ? *reinterpret_cast<const float4*>(f.master + o) : Elem<T>::load4(w + o);
+__device__ __forceinline__ void adam_load4(AdamRegs& r, const AdamFuse& f, const T* w, size_t uo, uint32_t lo) {
+  r.m = *reinterpret_cast<const float4*>(epi_ptr(f.m, uo, lo));
+  r.v = *reinterpret_cast<const float4*>(epi_ptr(f.v, uo, lo));
+  r.p = f.master ? *reinterpret_cast<const float4*>(epi_ptr(f.master, uo, lo)) : Elem<T>::load4(epi_ptr(w, uo, lo));
 }
 template <typename T>
-__device__ __forceinline__ void adam_update4(const AdamFuse& f, T* w, size_t o, const AdamRegs& r, float4 g4) {
-  const float inv_bc1 = 1.0f / f.a.bc1, inv_bc2 = 1.0f / f.a.bc2;
+__device__ __forceinline__ void adam_update4(const AdamFuse& f, T* w, size_t uo, uint32_t lo, const AdamRegs& r,
+                                             float4 g4) {
   const float4 m4 = r.m, v4 = r.v, p4 = r.p;
   const float g[4] = {g4.x, g4.y, g4.z, g4.w};
   float mm[4] = {m4.x, m4.y, m4.z, m4.w}, vv[4] = {v4.x, v4.y, v4.z, v4.w}, pp[4] = {p4.x, p4.y, p4.z, p4.w};
 #pragma unroll
-  for (int k = 0; k < 4; ++k) {
-    mm[k] = f.a.beta1 * mm[k] + (1.0f - f.a.beta1) * g[k];
-    vv[k] = f.a.beta2 * vv[k] + (1.0f - f.a.beta2) * g[k] * g[k];
-    pp[k] -= f.a.lr * (mm[k] * inv_bc1) / (sqrtf(vv[k] * inv_bc2) + f.a.eps);
-  }
-  *reinterpret_cast<float4*>(f.m + o) = make_float4(mm[0], mm[1], mm[2], mm[3]);
-  *reinterpret_cast<float4*>(f.v + o) = make_float4(vv[0], vv[1], vv[2], vv[3]);
+  for (int k = 0; k < 4; ++k) adam_element(pp[k], mm[k], vv[k], g[k], f.a);
+  *reinterpret_cast<float4*>(epi_ptr(f.m, uo, lo)) = make_float4(mm[0], mm[1], mm[2], mm[3]);
+  *reinterpret_cast<float4*>(epi_ptr(f.v, uo, lo)) = make_float4(vv[0], vv[1], vv[2], vv[3]);
   const float4 pn = make_float4(pp[0], pp[1], pp[2], pp[3]);
-  if (f.master) *reinterpret_cast<float4*>(f.master + o) = pn;
-  Elem<T>::store4(w + o, pn);
-}
-
-__device__ __forceinline__ uint32_t pack_u8x4(uint32_t a, uint32_t b, uint32_t c, uint32_t d) {
-  return a | (b << 8) | (c << 16) | (d << 24);
+  if (f.master) *reinterpret_cast<float4*>(epi_ptr(f.master, uo, lo)) = pn;
+  Elem<T>::store4(epi_ptr(w, uo, lo), pn);
 }
 
 // ---------------------------------------------------------------------------
@@ -119,23 +134,28 @@ struct EncPolicy {
   bool log_threshold;
   __device__ bool skip() const { return false; }
   struct GInfo { int l; };
-  struct Epi { int count; };
+  struct Epi { int count; float4 b, th; };
   __device__ GInfo ginfo(int order) const { return {order}; }
   __device__ int nseg(const GInfo&) const { return 1; }
   __device__ const TA* a_seg(const GInfo& g, int) const { return x + (size_t)g.l * D.B * D.d; }
   __device__ const T* b_seg(const GInfo& g, int) const { return W_enc + (size_t)g.l * D.d * D.F; }
   static constexpr int EPI_BATCH = 8, EPI_BATCH_LATE = 8;
-  struct EpiRegs { float4 b, th; float s; };
-  __device__ void epi_begin(Epi& e) const { e.count = 0; }
-  __device__ void epi_load(EpiRegs& r, const GInfo& g, int row, int col) const {
-    const size_t vo = (size_t)g.l * D.F + col;
-    r.b = *reinterpret_cast<const float4*>(b_enc + vo);
-    r.th = *reinterpret_cast<const float4*>(theta + vo);
-    if (log_threshold) r.th = make_float4(expf(r.th.x), expf(r.th.y), expf(r.th.z), expf(r.th.w));
-    r.s = x_scale ? x_scale[(size_t)g.l * D.B + row] : 1.0f;
+  struct EpiRegs { float s; };
+  __device__ void epi_begin(Epi& e, const GInfo& g, int col, bool ok) const {
+    e.count = 0;
+    e.b = e.th = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (ok) {
+      const size_t vo = (size_t)g.l * D.F + col;
+      e.b = *reinterpret_cast<const float4*>(b_enc + vo);
+      e.th = *reinterpret_cast<const float4*>(theta + vo);
+      if (log_threshold) e.th = make_float4(expf(e.th.x), expf(e.th.y), expf(e.th.z), expf(e.th.w));
+    }
   }
-  __device__ void epi4(Epi& e, const GInfo& g, int row, int col, float4 v, const EpiRegs& r) const {
-    const float4 b = r.b, th = r.th;
+  __device__ void epi_load(EpiRegs& r, const GInfo& g, const EpiPos& pos) const {
+    r.s = x_scale ? *epi_ptr(x_scale, (size_t)g.l * D.B + pos.ru, (uint32_t)pos.rl) : 1.0f;
+  }
+  __device__ void epi4(Epi& e, const GInfo& g, const EpiPos& pos, float4 v, const EpiRegs& r) const {
+    const float4 b = e.b, th = e.th;
     if (x_scale) {   // int8 codes: the row scale multiplies the integer dot product
       const float s = r.s;
       v.x *= s; v.y *= s; v.z *= s; v.w *= s;
@@ -143,19 +163,21 @@ struct EncPolicy {
     float p[4] = {v.x + b.x, v.y + b.y, v.z + b.z, v.w + b.w};
     const float t[4] = {th.x, th.y, th.z, th.w};
     float zz[4];
-    uint32_t c[4];
+    uint32_t c4 = 0;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const bool act = p[i] > t[i];
       const bool win = fabsf(p[i] - t[i]) < half_eps;
       zz[i] = act ? p[i] : 0.0f;
-      c[i] = (act ? CLS_ACTIVE : 0) | (win ? CLS_WINDOW : 0) | (p[i] < t[i] ? CLS_BELOW : 0);
-      e.count += act ? 1 : 0;
+      const uint32_t c = (act ? CLS_ACTIVE : 0u) | (win ? CLS_WINDOW : 0u) | (p[i] < t[i] ? CLS_BELOW : 0u);
+      c4 |= c << (8 * i);
     }
-    const size_t o = ((size_t)g.l * D.B + row) * D.F + col;
-    Elem<T>::store4(z + o, make_float4(zz[0], zz[1], zz[2], zz[3]));
-    if (pre) Elem<T>::store4(pre + o, make_float4(p[0], p[1], p[2], p[3]));
-    *reinterpret_cast<uint32_t*>(cls + o) = pack_u8x4(c[0], c[1], c[2], c[3]);
+    e.count += __popc(c4 & 0x01010101u);
+    const size_t uo = pos.uoff((size_t)g.l * D.B, D.F);
+    const uint32_t lo = pos.loff(D.F);
+    Elem<T>::store4(epi_ptr(z, uo, lo), make_float4(zz[0], zz[1], zz[2], zz[3]));
+    if (pre) Elem<T>::store4(epi_ptr(pre, uo, lo), make_float4(p[0], p[1], p[2], p[3]));
+    *reinterpret_cast<uint32_t*>(epi_ptr(cls, uo, lo)) = c4;
   }
   __device__ void epi_end(Epi& e, const GInfo& g) const {
     if (!l0) return;
@@ -180,7 +202,7 @@ struct DecPolicy {
   // the dense decode stands down when the device-side switch selected the gather path
   __device__ bool skip() const { return skip_flags && skip_flags[0] != 0 && skip_flags[1] <= kcap; }
   struct GInfo { int lp; };
-  struct Epi {};
+  struct Epi { float4 b; };
   __device__ GInfo ginfo(int order) const { return {D.L - 1 - order}; }   // longest K first
   __device__ int nseg(const GInfo& g) const { return g.lp + 1; }
   __device__ const T* a_seg(const GInfo&, int s) const { return z + (size_t)s * D.B * D.F; }
@@ -188,14 +210,14 @@ struct DecPolicy {
     return W_dec + (size_t)packed_index(s, g.lp, D.L) * D.F * D.d;
   }
   static constexpr int EPI_BATCH = 8, EPI_BATCH_LATE = 8;
-  struct EpiRegs { float4 b; };
-  __device__ void epi_begin(Epi&) const {}
-  __device__ void epi_load(EpiRegs& r, const GInfo& g, int, int col) const {
-    r.b = *reinterpret_cast<const float4*>(b_dec + (size_t)g.lp * D.d + col);
+  struct EpiRegs {};
+  __device__ void epi_begin(Epi& e, const GInfo& g, int col, bool ok) const {
+    e.b = ok ? *reinterpret_cast<const float4*>(b_dec + (size_t)g.lp * D.d + col) : make_float4(0.f, 0.f, 0.f, 0.f);
   }
-  __device__ void epi4(Epi&, const GInfo& g, int row, int col, float4 v, const EpiRegs& r) const {
-    const float4 b = r.b;
-    *reinterpret_cast<float4*>(y_hat + ((size_t)g.lp * D.B + row) * D.d + col) =
+  __device__ void epi_load(EpiRegs&, const GInfo&, const EpiPos&) const {}
+  __device__ void epi4(Epi& e, const GInfo& g, const EpiPos& pos, float4 v, const EpiRegs&) const {
+    const float4 b = e.b;
+    *reinterpret_cast<float4*>(epi_ptr(y_hat, pos.uoff((size_t)g.lp * D.B, D.d), pos.loff(D.d))) =
         make_float4(v.x + b.x, v.y + b.y, v.z + b.z, v.w + b.w);
   }
   __device__ void epi_end(Epi&, const GInfo&) const {}
@@ -204,6 +226,9 @@ struct DecPolicy {
 // ---------------------------------------------------------------------------
 // dz[l] = sum_{lp>=l} dyhat[lp] W_dec[p(l,lp)]^T + sparsity gradient, kept
 // where the feature is active or inside the threshold window (0 elsewhere).
+// The sparsity gradient (lambda0 C / B) n sech^2(C z n) is evaluated as
+// 4 e / (1 + e)^2 with e = exp(-2 |C z n|): no cancellation for large arguments
+// and one hardware exponential per element.
 // ---------------------------------------------------------------------------
 template <typename T>
 struct DzPolicy {
@@ -216,7 +241,7 @@ struct DzPolicy {
   float lam1_over_b;
   __device__ bool skip() const { return false; }
   struct GInfo { int l; };
-  struct Epi {};
+  struct Epi { float4 karg, kamp, dead; };   // per column: -2 log2(e) C n, 4 (lambda0 C / B) n, -(lambda1 / B) n
   __device__ GInfo ginfo(int order) const { return {order}; }             // K = (L-l) d, longest first
   __device__ int nseg(const GInfo& g) const { return D.L - g.l; }
   __device__ const T* a_seg(const GInfo& g, int s) const { return d_yhat + (size_t)(g.l + s) * D.B * D.d; }
@@ -224,39 +249,46 @@ struct DzPolicy {
     return W_dec + (size_t)packed_index(g.l, g.l + s, D.L) * D.F * D.d;
   }
   static constexpr int EPI_BATCH = 8, EPI_BATCH_LATE = 8;
-  struct EpiRegs { uint32_t c4; float4 z4, n4; };
-  __device__ void epi_begin(Epi&) const {}
-  __device__ void epi_load(EpiRegs& r, const GInfo& g, int row, int col) const {
-    const size_t o = ((size_t)g.l * D.B + row) * D.F + col;
-    r.c4 = *reinterpret_cast<const uint32_t*>(cls + o);
-    r.z4 = Elem<T>::load4(z + o);
-    r.n4 = *reinterpret_cast<const float4*>(norms + (size_t)g.l * D.F + col);
+  struct EpiRegs { uint32_t c4; float4 z4; };
+  __device__ void epi_begin(Epi& e, const GInfo& g, int col, bool ok) const {
+    float4 n4 = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (ok) n4 = *reinterpret_cast<const float4*>(norms + (size_t)g.l * D.F + col);
+    const float ka = -2.0f * 1.4426950408889634f * C, kb = 4.0f * lam_c_over_b, kd = 0.0f - lam1_over_b;
+    e.karg = make_float4(ka * n4.x, ka * n4.y, ka * n4.z, ka * n4.w);
+    e.kamp = make_float4(kb * n4.x, kb * n4.y, kb * n4.z, kb * n4.w);
+    e.dead = make_float4(kd * n4.x, kd * n4.y, kd * n4.z, kd * n4.w);
   }
-  __device__ void epi4(Epi&, const GInfo& g, int row, int col, float4 v, const EpiRegs& r) const {
-    const size_t o = ((size_t)g.l * D.B + row) * D.F + col;
+  __device__ void epi_load(EpiRegs& r, const GInfo& g, const EpiPos& pos) const {
+    const size_t uo = pos.uoff((size_t)g.l * D.B, D.F);
+    const uint32_t lo = pos.loff(D.F);
+    r.c4 = *reinterpret_cast<const uint32_t*>(epi_ptr(cls, uo, lo));
+    r.z4 = Elem<T>::load4(epi_ptr(z, uo, lo));
+  }
+  __device__ void epi4(Epi& e, const GInfo& g, const EpiPos& pos, float4 v, const EpiRegs& r) const {
     const uint32_t c4 = r.c4;
     float4 out = make_float4(0.f, 0.f, 0.f, 0.f);
-    const float4 n4 = r.n4;
-    const float nn[4] = {n4.x, n4.y, n4.z, n4.w};
+    const float dg[4] = {e.dead.x, e.dead.y, e.dead.z, e.dead.w};
     if (c4 & 0x03030303u) {          // some entry active or in the window: dz is kept there
       const float4 z4 = r.z4;
       const float zz[4] = {z4.x, z4.y, z4.z, z4.w};
       const float vv[4] = {v.x, v.y, v.z, v.w};
-      float r[4];
+      const float ka[4] = {e.karg.x, e.karg.y, e.karg.z, e.karg.w}, kb[4] = {e.kamp.x, e.kamp.y, e.kamp.z, e.kamp.w};
+      float o[4];
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        const float t = tanhf(C * zz[i] * nn[i]);
-        const float gsp = lam_c_over_b * nn[i] * (1.0f - t * t);
+        const float ex = __builtin_amdgcn_exp2f(ka[i] * fabsf(zz[i]));
+        const float s = 1.0f + ex;
+        const float gsp = kb[i] * ex * __builtin_amdgcn_rcpf(s * s);
         const uint32_t ci = (c4 >> (8 * i)) & 7u;
         // elsewhere only the dead-feature gradient of pre < theta
-        r[i] = (ci & 3u) ? vv[i] + gsp : ((ci & CLS_BELOW) ? 0.0f - lam1_over_b * nn[i] : 0.0f);
+        o[i] = (ci & 3u) ? vv[i] + gsp : ((ci & CLS_BELOW) ? dg[i] + 0.0f : 0.0f);
       }
-      out = make_float4(r[0], r[1], r[2], r[3]);
+      out = make_float4(o[0], o[1], o[2], o[3]);
     } else if (lam1_over_b != 0.f && c4) {
-      out = make_float4((c4 & 0x4u) ? -lam1_over_b * nn[0] : 0.f, (c4 & 0x400u) ? -lam1_over_b * nn[1] : 0.f,
-                        (c4 & 0x40000u) ? -lam1_over_b * nn[2] : 0.f, (c4 & 0x4000000u) ? -lam1_over_b * nn[3] : 0.f);
+      out = make_float4((c4 & 0x4u) ? dg[0] : 0.f, (c4 & 0x400u) ? dg[1] : 0.f, (c4 & 0x40000u) ? dg[2] : 0.f,
+                        (c4 & 0x4000000u) ? dg[3] : 0.f);
     }
-    Elem<T>::store4(dpre + o, out);
+    Elem<T>::store4(epi_ptr(dpre, pos.uoff((size_t)g.l * D.B, D.F), pos.loff(D.F)), out);
   }
   __device__ void epi_end(Epi&, const GInfo&) const {}
 };
@@ -287,22 +319,24 @@ struct DWdecPolicy {
   // 18 registers per row group: 4 groups while most accumulators are still live, 8 afterwards
   static constexpr int EPI_BATCH = 4, EPI_BATCH_LATE = 8;
   struct EpiRegs { float Gf, nf; float4 w; AdamRegs ad; };
-  __device__ void epi_begin(Epi&) const {}
-  __device__ void epi_load(EpiRegs& r, const GInfo& g, int row, int col) const {
-    const size_t nf = (size_t)g.l * D.F + row;
-    r.Gf = G[nf];
-    r.nf = norms[nf];
-    const size_t o = ((size_t)g.p * D.F + row) * D.d + col;
-    r.w = Elem<T>::load4(W_dec + o);
-    if (fuse.m) adam_load4<T>(r.ad, fuse, W_dec, o);
+  __device__ void epi_begin(Epi&, const GInfo&, int, bool) const {}
+  __device__ void epi_load(EpiRegs& r, const GInfo& g, const EpiPos& pos) const {
+    const size_t nf = (size_t)g.l * D.F + pos.ru;
+    r.Gf = *epi_ptr(G, nf, (uint32_t)pos.rl);
+    r.nf = *epi_ptr(norms, nf, (uint32_t)pos.rl);
+    const size_t uo = pos.uoff((size_t)g.p * D.F, D.d);
+    const uint32_t lo = pos.loff(D.d);
+    r.w = Elem<T>::load4(epi_ptr(W_dec, uo, lo));
+    if (fuse.m) adam_load4<T>(r.ad, fuse, W_dec, uo, lo);
   }
-  __device__ void epi4(Epi&, const GInfo& g, int row, int col, float4 v, const EpiRegs& r) const {
-    const float coef = r.Gf / fmaxf(r.nf, 1e-30f);
-    const size_t o = ((size_t)g.p * D.F + row) * D.d + col;
+  __device__ void epi4(Epi&, const GInfo& g, const EpiPos& pos, float4 v, const EpiRegs& r) const {
+    const float coef = r.Gf * __builtin_amdgcn_rcpf(fmaxf(r.nf, 1e-30f));
+    const size_t uo = pos.uoff((size_t)g.p * D.F, D.d);
+    const uint32_t lo = pos.loff(D.d);
     const float4 w = r.w;
-    const float4 gr = make_float4(v.x + coef * w.x, v.y + coef * w.y, v.z + coef * w.z, v.w + coef * w.w);
-    if (dW_dec) Elem<T>::store4(dW_dec + o, gr);
-    if (fuse.m) adam_update4<T>(fuse, W_dec, o, r.ad, gr);
+    const float4 gr = make_float4(fmaf(coef, w.x, v.x), fmaf(coef, w.y, v.y), fmaf(coef, w.z, v.z), fmaf(coef, w.w, v.w));
+    if (dW_dec) Elem<T>::store4(epi_ptr(dW_dec, uo, lo), gr);
+    if (fuse.m) adam_update4<T>(fuse, W_dec, uo, lo, r.ad, gr);
   }
   __device__ void epi_end(Epi&, const GInfo&) const {}
 };
@@ -327,14 +361,15 @@ struct DWencPolicy {
   __device__ const T* b_seg(const GInfo& g, int) const { return dpre + (size_t)g.l * D.B * D.F; }
   static constexpr int EPI_BATCH = 4, EPI_BATCH_LATE = 8;
   struct EpiRegs { AdamRegs ad; };
-  __device__ void epi_begin(Epi&) const {}
-  __device__ void epi_load(EpiRegs& r, const GInfo& g, int row, int col) const {
-    if (fuse.m) adam_load4<T>(r.ad, fuse, W_enc, ((size_t)g.l * D.d + row) * D.F + col);
+  __device__ void epi_begin(Epi&, const GInfo&, int, bool) const {}
+  __device__ void epi_load(EpiRegs& r, const GInfo& g, const EpiPos& pos) const {
+    if (fuse.m) adam_load4<T>(r.ad, fuse, W_enc, pos.uoff((size_t)g.l * D.d, D.F), pos.loff(D.F));
   }
-  __device__ void epi4(Epi&, const GInfo& g, int row, int col, float4 v, const EpiRegs& r) const {
-    const size_t o = ((size_t)g.l * D.d + row) * D.F + col;
-    if (dW_enc) Elem<T>::store4(dW_enc + o, v);
-    if (fuse.m) adam_update4<T>(fuse, W_enc, o, r.ad, v);
+  __device__ void epi4(Epi&, const GInfo& g, const EpiPos& pos, float4 v, const EpiRegs& r) const {
+    const size_t uo = pos.uoff((size_t)g.l * D.d, D.F);
+    const uint32_t lo = pos.loff(D.F);
+    if (dW_enc) Elem<T>::store4(epi_ptr(dW_enc, uo, lo), v);
+    if (fuse.m) adam_update4<T>(fuse, W_enc, uo, lo, r.ad, v);
   }
   __device__ void epi_end(Epi&, const GInfo&) const {}
 };

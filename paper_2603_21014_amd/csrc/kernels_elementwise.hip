@@ -274,7 +274,6 @@ template <typename T, bool MASTER>
 __global__ __launch_bounds__(256) void adam_kernel(size_t n4, T* __restrict__ p, const T* __restrict__ g,
                                                    float* __restrict__ m, float* __restrict__ v,
                                                    float* __restrict__ master, AdamScalars a) {
-  const float inv_bc1 = 1.0f / a.bc1, inv_bc2 = 1.0f / a.bc2;
   for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n4; i += (size_t)gridDim.x * 256) {
     const size_t o = i * 4;
     const float4 g4 = Elem<T>::load4(g + o);
@@ -284,11 +283,7 @@ __global__ __launch_bounds__(256) void adam_kernel(size_t n4, T* __restrict__ p,
     const float gg[4] = {g4.x, g4.y, g4.z, g4.w};
     float mm[4] = {m4.x, m4.y, m4.z, m4.w}, vv[4] = {v4.x, v4.y, v4.z, v4.w}, pp[4] = {p4.x, p4.y, p4.z, p4.w};
 #pragma unroll
-    for (int k = 0; k < 4; ++k) {
-      mm[k] = a.beta1 * mm[k] + (1.0f - a.beta1) * gg[k];
-      vv[k] = a.beta2 * vv[k] + (1.0f - a.beta2) * gg[k] * gg[k];
-      pp[k] -= a.lr * (mm[k] * inv_bc1) / (sqrtf(vv[k] * inv_bc2) + a.eps);
-    }
+    for (int k = 0; k < 4; ++k) adam_element(pp[k], mm[k], vv[k], gg[k], a);
     *reinterpret_cast<float4*>(m + o) = make_float4(mm[0], mm[1], mm[2], mm[3]);
     *reinterpret_cast<float4*>(v + o) = make_float4(vv[0], vv[1], vv[2], vv[3]);
     const float4 pn = make_float4(pp[0], pp[1], pp[2], pp[3]);

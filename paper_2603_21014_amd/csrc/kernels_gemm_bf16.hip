@@ -261,42 +261,33 @@ __device__ __forceinline__ void main_loop(const P& p, const typename P::GInfo& g
   }
 }
 
-template <class P>
-__global__ __launch_bounds__(NTHREADS) void gemm_bf16_kernel(P p, TileGrid tg) {
-  extern __shared__ __align__(16) bf16_t smem[];
-  int gorder, tm, tn;
-  if (!tg.decode(blockIdx.x, gorder, tm, tn) || p.skip()) return;
-  const typename P::GInfo gi = p.ginfo(gorder);
-
-  // wave w owns output rows wm*128.., columns wn*64..
-  const int t = threadIdx.x, lane = t & 63, w = t >> 6, wm = w >> 2, wn = w & 3;
-  const int m0 = tm * TM, n0 = tn * TN;
+// Epilogue of one tile: accumulators -> LDS (wave-private 32 rows x 64 fp32) -> 4 consecutive
+// columns of one row per lane -> the policy's fused epilogue.  The lane's position inside a row
+// group never changes and the group's origin is wave-uniform (EpiPos), so the policy's memory
+// accesses are a scalar base plus one fixed per-lane offset.  EDGE = false: the tile lies fully
+// inside the matrix, no predicates.
+template <class P, bool EDGE>
+__device__ __forceinline__ void epilogue(const P& p, const typename P::GInfo& gi, int m0, int n0, bf16_t* smem,
+                                         f32x16_t (&acc)[4][2]) {
+  const int t = threadIdx.x, lane = t & 63, w = t >> 6;
+  const int wu = __builtin_amdgcn_readfirstlane(w), wm = wu >> 2, wn = wu & 3;
   const int M = p.M, N = p.N;
-
-  f32x16_t acc[4][2];
-#pragma unroll
-  for (int i = 0; i < 4; ++i)
-#pragma unroll
-    for (int j = 0; j < 2; ++j)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-
-  const bool interior = (m0 + TM <= M) && (n0 + TN <= N) && (p.kseg % TK == 0);
-  if (interior) main_loop<P, false>(p, gi, m0, n0, smem, acc);
-  else main_loop<P, true>(p, gi, m0, n0, smem, acc);
-
-  // ---- epilogue: accumulators -> LDS (wave-private 32 rows x 64 fp32) -> 4 columns of one row per lane
   __syncthreads();
-  float* wl = reinterpret_cast<float*>(smem) + w * (32 * 64);
+  float* wl = reinterpret_cast<float*>(smem) + wu * (32 * 64);
+  EpiPos pos;
+  pos.cu = n0 + wn * 64;
+  pos.cl = (lane & 15) << 2;
+  pos.rl = lane >> 4;
+  pos.ru = 0;
+  const bool col_ok = !EDGE || pos.col() < N;
   typename P::Epi est;
-  p.epi_begin(est);
-  const int c4 = (lane & 15) << 2;
-  const int gcol = n0 + wn * 64 + c4;
+  p.epi_begin(est, gi, pos.col(), col_ok);
   // One 32-row slab of the wave's block.  The global loads the policy's epilogue needs are issued
   // for EB row groups before any is consumed; later slabs can afford larger batches because the
   // accumulators of the slabs already written out no longer occupy registers.
   auto slab = [&](auto eb_tag, int i) {
-    constexpr int EB = decltype(eb_tag)::value;
+    // (predicated edge tiles keep to batches of 4: the predicates' registers come on top)
+    constexpr int EB = (EDGE && decltype(eb_tag)::value > 4) ? 4 : decltype(eb_tag)::value;
 #pragma unroll
     for (int j = 0; j < 2; ++j)
 #pragma unroll
@@ -308,15 +299,14 @@ __global__ __launch_bounds__(NTHREADS) void gemm_bf16_kernel(P p, TileGrid tg) {
       typename P::EpiRegs er[EB];
 #pragma unroll
       for (int u = 0; u < EB; ++u) {
-        const int grow = m0 + wm * 128 + i * 32 + (it0 + u) * 4 + (lane >> 4);
-        if (grow < M && gcol < N) p.epi_load(er[u], gi, grow, gcol);
+        pos.ru = m0 + wm * 128 + i * 32 + (it0 + u) * 4;
+        if (!EDGE || (col_ok && pos.row() < M)) p.epi_load(er[u], gi, pos);
       }
 #pragma unroll
       for (int u = 0; u < EB; ++u) {
-        const int row = (it0 + u) * 4 + (lane >> 4);
-        const int grow = m0 + wm * 128 + i * 32 + row;
-        const float4 v = *reinterpret_cast<const float4*>(wl + row * 64 + c4);
-        if (grow < M && gcol < N) p.epi4(est, gi, grow, gcol, v, er[u]);
+        pos.ru = m0 + wm * 128 + i * 32 + (it0 + u) * 4;
+        const float4 v = *reinterpret_cast<const float4*>(wl + ((it0 + u) * 4 + pos.rl) * 64 + pos.cl);
+        if (!EDGE || (col_ok && pos.row() < M)) p.epi4(est, gi, pos, v, er[u]);
       }
     }
     __syncthreads();
@@ -326,6 +316,30 @@ __global__ __launch_bounds__(NTHREADS) void gemm_bf16_kernel(P p, TileGrid tg) {
   slab(std::integral_constant<int, P::EPI_BATCH_LATE>{}, 2);
   slab(std::integral_constant<int, P::EPI_BATCH_LATE>{}, 3);
   p.epi_end(est, gi);
+}
+
+template <class P>
+__global__ __launch_bounds__(NTHREADS) void gemm_bf16_kernel(P p, TileGrid tg) {
+  extern __shared__ __align__(16) bf16_t smem[];
+  int gorder, tm, tn;
+  if (!tg.decode(blockIdx.x, gorder, tm, tn) || p.skip()) return;
+  const typename P::GInfo gi = p.ginfo(gorder);
+  const int m0 = tm * TM, n0 = tn * TN;
+
+  // wave w owns output rows (w/4)*128.., columns (w%4)*64..
+  f32x16_t acc[4][2];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  const bool inside = (m0 + TM <= p.M) && (n0 + TN <= p.N);
+  if (inside && p.kseg % TK == 0) main_loop<P, false>(p, gi, m0, n0, smem, acc);
+  else main_loop<P, true>(p, gi, m0, n0, smem, acc);
+  if (inside) epilogue<P, false>(p, gi, m0, n0, smem, acc);
+  else epilogue<P, true>(p, gi, m0, n0, smem, acc);
 }
 
 template <class P>

@@ -63,19 +63,20 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(P p, TileGrid tg) {
   }
 
   typename P::Epi est;
-  p.epi_begin(est);
   const int col = n0 + tx * 4;
+  p.epi_begin(est, gi, col, col < N);
   if (col < N) {
     typename P::EpiRegs er[4];
+    EpiPos pos{m0, n0, 0, tx * 4};
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const int row = m0 + ty * 4 + i;
-      if (row < M) p.epi_load(er[i], gi, row, col);
+      pos.rl = ty * 4 + i;
+      if (pos.row() < M) p.epi_load(er[i], gi, pos);
     }
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const int row = m0 + ty * 4 + i;
-      if (row < M) p.epi4(est, gi, row, col, make_float4(acc[i][0], acc[i][1], acc[i][2], acc[i][3]), er[i]);
+      pos.rl = ty * 4 + i;
+      if (pos.row() < M) p.epi4(est, gi, pos, make_float4(acc[i][0], acc[i][1], acc[i][2], acc[i][3]), er[i]);
     }
   }
   p.epi_end(est, gi);
