@@ -30,6 +30,20 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
 }
 __device__ __forceinline__ bf16_t f32_to_bf16(float f) { return (bf16_t)(pack_bf16x2(f, 0.0f) & 0xffffu); }
 
+// Streaming (non-temporal) 16- and 8-byte accesses for data that is touched once per kernel
+// (optimizer state, weights in the update epilogues): they should not displace the operand
+// panels that the contractions reuse out of the L2.
+typedef float nt_f32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int nt_u32x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ float4 nt_load_f4(const float* p) {
+  const nt_f32x4 v = __builtin_nontemporal_load(reinterpret_cast<const nt_f32x4*>(p));
+  return make_float4(v[0], v[1], v[2], v[3]);
+}
+__device__ __forceinline__ void nt_store_f4(float* p, float4 v) {
+  const nt_f32x4 t = {v.x, v.y, v.z, v.w};
+  __builtin_nontemporal_store(t, reinterpret_cast<nt_f32x4*>(p));
+}
+
 // Element-type traits for the two storage types.
 template <typename T> struct Elem;
 template <> struct Elem<float> {
@@ -37,6 +51,8 @@ template <> struct Elem<float> {
   static __device__ __forceinline__ void store(float* p, float v) { *p = v; }
   static __device__ __forceinline__ void store4(float* p, float4 v) { *reinterpret_cast<float4*>(p) = v; }
   static __device__ __forceinline__ float4 load4(const float* p) { return *reinterpret_cast<const float4*>(p); }
+  static __device__ __forceinline__ float4 nt_load4(const float* p) { return nt_load_f4(p); }
+  static __device__ __forceinline__ void nt_store4(float* p, float4 v) { nt_store_f4(p, v); }
 };
 template <> struct Elem<bf16_t> {
   static __device__ __forceinline__ float load(const bf16_t* p) { return bf16_to_f32(*p); }
@@ -51,6 +67,15 @@ template <> struct Elem<bf16_t> {
     uint2 u = *reinterpret_cast<const uint2*>(p);
     return make_float4(__uint_as_float(u.x << 16), __uint_as_float(u.x & 0xffff0000u),
                        __uint_as_float(u.y << 16), __uint_as_float(u.y & 0xffff0000u));
+  }
+  static __device__ __forceinline__ float4 nt_load4(const bf16_t* p) {
+    const nt_u32x2 u = __builtin_nontemporal_load(reinterpret_cast<const nt_u32x2*>(p));
+    return make_float4(__uint_as_float(u[0] << 16), __uint_as_float(u[0] & 0xffff0000u),
+                       __uint_as_float(u[1] << 16), __uint_as_float(u[1] & 0xffff0000u));
+  }
+  static __device__ __forceinline__ void nt_store4(bf16_t* p, float4 v) {
+    const nt_u32x2 u = {pack_bf16x2(v.x, v.y), pack_bf16x2(v.z, v.w)};
+    __builtin_nontemporal_store(u, reinterpret_cast<nt_u32x2*>(p));
   }
 };
 

@@ -101,9 +101,9 @@ struct AdamFuse {
 struct AdamRegs { float4 m, v, p; };   // moments and the fp32 parameter (master copy or widened weight)
 template <typename T>
 __device__ __forceinline__ void adam_load4(AdamRegs& r, const AdamFuse& f, const T* w, size_t uo, uint32_t lo) {
-  r.m = *reinterpret_cast<const float4*>(epi_ptr(f.m, uo, lo));
-  r.v = *reinterpret_cast<const float4*>(epi_ptr(f.v, uo, lo));
-  r.p = f.master ? *reinterpret_cast<const float4*>(epi_ptr(f.master, uo, lo)) : Elem<T>::load4(epi_ptr(w, uo, lo));
+  r.m = nt_load_f4(epi_ptr(f.m, uo, lo));
+  r.v = nt_load_f4(epi_ptr(f.v, uo, lo));
+  r.p = f.master ? nt_load_f4(epi_ptr(f.master, uo, lo)) : Elem<T>::nt_load4(epi_ptr(w, uo, lo));
 }
 template <typename T>
 __device__ __forceinline__ void adam_update4(const AdamFuse& f, T* w, size_t uo, uint32_t lo, const AdamRegs& r,
@@ -113,11 +113,11 @@ __device__ __forceinline__ void adam_update4(const AdamFuse& f, T* w, size_t uo,
   float mm[4] = {m4.x, m4.y, m4.z, m4.w}, vv[4] = {v4.x, v4.y, v4.z, v4.w}, pp[4] = {p4.x, p4.y, p4.z, p4.w};
 #pragma unroll
   for (int k = 0; k < 4; ++k) adam_element(pp[k], mm[k], vv[k], g[k], f.a);
-  *reinterpret_cast<float4*>(epi_ptr(f.m, uo, lo)) = make_float4(mm[0], mm[1], mm[2], mm[3]);
-  *reinterpret_cast<float4*>(epi_ptr(f.v, uo, lo)) = make_float4(vv[0], vv[1], vv[2], vv[3]);
+  nt_store_f4(epi_ptr(f.m, uo, lo), make_float4(mm[0], mm[1], mm[2], mm[3]));
+  nt_store_f4(epi_ptr(f.v, uo, lo), make_float4(vv[0], vv[1], vv[2], vv[3]));
   const float4 pn = make_float4(pp[0], pp[1], pp[2], pp[3]);
-  if (f.master) *reinterpret_cast<float4*>(epi_ptr(f.master, uo, lo)) = pn;
-  Elem<T>::store4(epi_ptr(w, uo, lo), pn);
+  if (f.master) nt_store_f4(epi_ptr(f.master, uo, lo), pn);
+  Elem<T>::nt_store4(epi_ptr(w, uo, lo), pn);
 }
 
 // ---------------------------------------------------------------------------
@@ -304,14 +304,13 @@ struct DWdecPolicy {
   int M, N, kseg, lda, ldb;
   const T* z; const T* d_yhat; T* W_dec; const float* G; const float* norms; T* dW_dec;   // dW_dec may be NULL when fused
   AdamFuse fuse;
-  int p0;   // first decoder block of this launch
   __device__ bool skip() const { return false; }
   struct GInfo { int p, l, lp; };
   struct Epi {};
   __device__ GInfo ginfo(int order) const {
-    int l = 0, r = order + p0;
+    int l = 0, r = order;
     while (r >= D.L - l) { r -= D.L - l; ++l; }
-    return {order + p0, l, l + r};
+    return {order, l, l + r};
   }
   __device__ int nseg(const GInfo&) const { return 1; }
   __device__ const T* a_seg(const GInfo& g, int) const { return z + (size_t)g.l * D.B * D.F; }
@@ -326,7 +325,7 @@ struct DWdecPolicy {
     r.nf = *epi_ptr(norms, nf, (uint32_t)pos.rl);
     const size_t uo = pos.uoff((size_t)g.p * D.F, D.d);
     const uint32_t lo = pos.loff(D.d);
-    r.w = Elem<T>::load4(epi_ptr(W_dec, uo, lo));
+    r.w = Elem<T>::nt_load4(epi_ptr(W_dec, uo, lo));
     if (fuse.m) adam_load4<T>(r.ad, fuse, W_dec, uo, lo);
   }
   __device__ void epi4(Epi&, const GInfo& g, const EpiPos& pos, float4 v, const EpiRegs& r) const {

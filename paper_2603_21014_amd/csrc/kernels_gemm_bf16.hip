@@ -282,7 +282,8 @@ __device__ __forceinline__ void epilogue(const P& p, const typename P::GInfo& gi
   const bool col_ok = !EDGE || pos.col() < N;
   typename P::Epi est;
   p.epi_begin(est, gi, pos.col(), col_ok);
-  // One 32-row slab of the wave's block.  The global loads the policy's epilogue needs are issued
+  // One 32-row slab of the wave's block.  The LDS region is private to the wave and a wave's LDS
+  // accesses complete in issue order, so the transposition needs no barrier.  The global loads the policy's epilogue needs are issued
   // for EB row groups before any is consumed; later slabs can afford larger batches because the
   // accumulators of the slabs already written out no longer occupy registers.
   auto slab = [&](auto eb_tag, int i) {
@@ -293,7 +294,6 @@ __device__ __forceinline__ void epilogue(const P& p, const typename P::GInfo& gi
 #pragma unroll
       for (int r = 0; r < 16; ++r)
         wl[(8 * (r >> 2) + 4 * (lane >> 5) + (r & 3)) * 64 + j * 32 + (lane & 31)] = acc[i][j][r];
-    __syncthreads();
 #pragma unroll
     for (int it0 = 0; it0 < 8; it0 += EB) {
       typename P::EpiRegs er[EB];
@@ -309,7 +309,6 @@ __device__ __forceinline__ void epilogue(const P& p, const typename P::GInfo& gi
         if (!EDGE || (col_ok && pos.row() < M)) p.epi4(est, gi, pos, v, er[u]);
       }
     }
-    __syncthreads();
   };
   slab(std::integral_constant<int, P::EPI_BATCH>{}, 0);
   slab(std::integral_constant<int, P::EPI_BATCH_LATE>{}, 1);
@@ -394,16 +393,8 @@ hipError_t launch_dz_bf16(hipStream_t s, Dims D, const DzArgs& a) {
 hipError_t launch_dwdec_bf16(hipStream_t s, Dims D, const DWdecArgs& a) {
   DWdecPolicy<bf16_t> p{D, D.F, D.d, D.B, D.F, D.d,
                         (const bf16_t*)a.z, (const bf16_t*)a.d_yhat, (bf16_t*)a.W_dec, a.G, a.norms,
-                        (bf16_t*)a.dW_dec, AdamFuse{a.fuse.m, a.fuse.v, a.fuse.master, a.fuse.a}, 0};
-  // One launch per source layer: tiles that share operand panels start together again at every
-  // launch, which keeps them in step along K and so keeps the panel reuse in the XCDs' L2s
-  // (over one long launch the 256 short tiles per block drift apart and the reuse is lost).
-  for (int l = 0; l < D.L; ++l) {
-    p.p0 = packed_index(l, l, D.L);
-    const hipError_t e = launch(s, p, D.L - l);
-    if (e != hipSuccess) return e;
-  }
-  return hipSuccess;
+                        (bf16_t*)a.dW_dec, AdamFuse{a.fuse.m, a.fuse.v, a.fuse.master, a.fuse.a}};
+  return launch(s, p, D.P());
 }
 hipError_t launch_dwenc_bf16(hipStream_t s, Dims D, const DWencArgs& a, bool int8_x) {
   if (int8_x) {
