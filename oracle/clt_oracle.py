@@ -207,6 +207,16 @@ def forward(x, W_enc, b_enc, theta, W_dec, b_dec, tie_break=None, band=0.0):
 # --------------------------------------------------------------------------
 # backward
 # --------------------------------------------------------------------------
+def sparsity_norm_sums(z, n, lambda0, C):
+    """G[l,f] = (lambda0/B) sum_b C z sech^2(C z n): derivative of L_sp w.r.t. the decoder norm n[l,f]."""
+    z = np.asarray(z, F64)
+    B = z.shape[1]
+    u = C * z * n[:, None, :]
+    with np.errstate(over="ignore"):
+        sech2 = 1.0 / np.cosh(u) ** 2
+    return (lambda0 / B) * np.sum(C * z * sech2, axis=1)
+
+
 def backward(x, y, theta, W_dec, fwd, lambda0, C, eps,
              window_tie_break=None, band=0.0, lambda1=0.0, log_threshold=False,
              below_tie_break=None):
@@ -239,9 +249,10 @@ def backward(x, y, theta, W_dec, fwd, lambda0, C, eps,
 
     d_yhat = 2.0 * (y_hat - y) / B
     u = C * z * n[:, None, :]
-    sech2 = 1.0 / np.cosh(u) ** 2
+    with np.errstate(over="ignore"):
+        sech2 = 1.0 / np.cosh(u) ** 2
     g_sp = (lambda0 / B) * C * n[:, None, :] * sech2
-    G = (lambda0 / B) * np.sum(C * z * sech2, axis=1)          # [L, F]
+    G = sparsity_norm_sums(z, n, lambda0, C)                   # [L, F]
 
     dz = g_sp.copy()
     for l in range(L):

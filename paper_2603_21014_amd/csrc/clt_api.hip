@@ -21,7 +21,8 @@ constexpr size_t ALIGN = 256;
 inline size_t align_up(size_t v) { return (v + ALIGN - 1) / ALIGN * ALIGN; }
 
 struct Plan {
-  size_t norms, G, d_yhat, dpre, part_cols, part_cols2, part_cols3, part_rec, part_sp, part_dead, l0, flags, g_idx, g_val, g_counts, total;
+  size_t norms, G, d_yhat, dpre, part_cols, part_cols2, part_cols3, part_rec, part_sp, part_dead, l0, flags, g_idx, g_val, g_counts, g_counts_w,
+         fl_off, fl_cnt, fl_tok, fl_val, fl_seg, total;
   int kcap;
 };
 
@@ -38,12 +39,14 @@ void set_err(char* dst, const char* fmt, ...) {
 
 enum KernelId {
   K_NORMS, K_ENC, K_DEC, K_LOSS_SP, K_LOSS_REC, K_LOSS_FINAL, K_COLRED, K_DZ, K_STE, K_DWENC, K_DWDEC,
-  K_ADAM_WDEC, K_ADAM_WENC, K_ADAM_VEC, K_ZERO, K_DECIDE, K_COMPACT, K_GATHER, K_COUNT
+  K_ADAM_WDEC, K_ADAM_WENC, K_ADAM_VEC, K_ZERO, K_DECIDE, K_COMPACT, K_GATHER, K_SP_FILL, K_GATHER_DZ, K_FLISTS,
+  K_SP_DWDEC, K_COUNT
 };
 static const char* const kKernelNames[K_COUNT] = {
   "decoder_norms", "encoder_jumprelu_gemm", "decode_gemm", "loss_sparsity", "loss_reconstruction", "loss_final",
   "column_reduce", "dz_gemm", "ste_reduce", "dW_enc_gemm", "dW_dec_gemm", "adam_W_dec", "adam_W_enc",
-  "adam_vectors", "zero_counters", "decode_decide", "compact_active", "gather_decode"};
+  "adam_vectors", "zero_counters", "decode_decide", "compact_active", "gather_decode", "sparse_dpre_fill",
+  "gather_dz", "feature_lists", "sparse_dW_dec"};
 
 struct ProfSpan { int kernel; hipEvent_t a, b; };
 
@@ -140,6 +143,14 @@ Plan make_plan(const clt_config* c) {
   p.g_idx = o;      o += align_up(L * B * (size_t)p.kcap * 4);
   p.g_val = o;      o += align_up(L * B * (size_t)p.kcap * 4);
   p.g_counts = o;   o += align_up(L * B * 4);
+  p.g_counts_w = o; o += align_up(L * B * 4);
+  // per-feature token lists of the sparse backward (transpose of the row lists, same capacity)
+  const size_t gathers = p.kcap ? 1 : 0;
+  p.fl_off = o;     o += align_up(gathers * L * F * 4);
+  p.fl_cnt = o;     o += align_up(gathers * L * F * 4);
+  p.fl_tok = o;     o += align_up(L * B * (size_t)p.kcap * 4);
+  p.fl_val = o;     o += align_up(L * B * (size_t)p.kcap * 4);
+  p.fl_seg = o;     o += align_up(gathers * FL_SEGS * L * F * 4);
   p.total = o;
   return p;
 }
@@ -335,7 +346,8 @@ int clt_forward(clt_handle* h, void* stream, const void* x, const float* x_scale
   const int mode = h->cfg.decode_mode;
   DecArgs da{z, W_dec, b_dec, y_hat, mode == CLT_DECODE_AUTO ? flags : nullptr, h->plan.kcap};
   GatherLists gl{reinterpret_cast<int32_t*>(h->ws + h->plan.g_idx), reinterpret_cast<float*>(h->ws + h->plan.g_val),
-                 reinterpret_cast<int32_t*>(h->ws + h->plan.g_counts), h->plan.kcap};
+                 reinterpret_cast<int32_t*>(h->ws + h->plan.g_counts),
+                 reinterpret_cast<int32_t*>(h->ws + h->plan.g_counts_w), h->plan.kcap};
   if (h->bf16) {
     RUN(h, s, K_ENC, launch_enc_bf16(s, h->D, ea, h->int8));
   } else {
@@ -418,22 +430,44 @@ static int backward_impl(clt_handle* h, hipStream_t s, const void* x, const floa
 
   // db_dec from the column partials that clt_loss left behind
   RUN(h, s, K_COLRED, launch_col_reduce(s, part, rbs, D.L * D.d, 1.0f, nullptr, 0.f, gb_dec));
-  DzArgs za{d_yhat, W_dec, z, act_class, norms, h->lambda0 * h->cfg.C / (float)D.B, h->cfg.C, dpre,
-            lam1_over_b};
-  DWdecArgs wa{z, d_yhat, W_dec, G, norms, gW_dec, fdec};
+  // Backward through the decoder: dense GEMMs, or the gather kernels on the lists of the forward
+  // pass when the device-side switch selected them (AUTO enqueues both; the one not selected
+  // returns at once).
+  const int mode = h->cfg.decode_mode;
+  int32_t* flags = reinterpret_cast<int32_t*>(h->ws + h->plan.flags);
+  const int32_t* skip = mode == CLT_DECODE_AUTO ? flags : nullptr;
+  const int kcap = h->plan.kcap;
+  const float lam_c_over_b = h->lambda0 * h->cfg.C / (float)D.B;
+  DzArgs za{d_yhat, W_dec, z, act_class, norms, lam_c_over_b, h->cfg.C, dpre, lam1_over_b, skip, kcap};
+  DWdecArgs wa{z, d_yhat, W_dec, G, norms, gW_dec, fdec, skip, kcap};
   DWencArgs ea{x, dpre, gW_enc, W_enc, fenc};
-  if (h->bf16) RUN(h, s, K_DZ, launch_dz_bf16(s, D, za)); else RUN(h, s, K_DZ, launch_dz_f32(s, D, za));
+  GatherLists gl{reinterpret_cast<int32_t*>(h->ws + h->plan.g_idx), reinterpret_cast<float*>(h->ws + h->plan.g_val),
+                 reinterpret_cast<int32_t*>(h->ws + h->plan.g_counts),
+                 reinterpret_cast<int32_t*>(h->ws + h->plan.g_counts_w), kcap};
+  FeatureLists fl{reinterpret_cast<int32_t*>(h->ws + h->plan.fl_off), reinterpret_cast<int32_t*>(h->ws + h->plan.fl_cnt),
+                  reinterpret_cast<int32_t*>(h->ws + h->plan.fl_tok), reinterpret_cast<float*>(h->ws + h->plan.fl_val),
+                  reinterpret_cast<int32_t*>(h->ws + h->plan.fl_seg), kcap};
+  if (mode != CLT_DECODE_DENSE) {
+    RUN(h, s, K_SP_FILL, launch_sparse_dpre_fill(s, h->bf16, D, act_class, norms, lam1_over_b, dpre, flags, kcap));
+    RUN(h, s, K_GATHER_DZ, launch_gather_dz(s, h->bf16, D, gl, d_yhat, W_dec, norms, lam_c_over_b, h->cfg.C, dpre,
+                                            flags));
+  }
+  if (mode != CLT_DECODE_GATHER) {
+    if (h->bf16) RUN(h, s, K_DZ, launch_dz_bf16(s, D, za)); else RUN(h, s, K_DZ, launch_dz_f32(s, D, za));
+  }
   RUN(h, s, K_STE, launch_ste_reduce(s, h->bf16, D, dpre, act_class, h->int8 ? x_scale : nullptr, norms, lam1_over_b,
                                      part, part2, part3));
   RUN(h, s, K_COLRED, launch_dtheta_final(s, part, part3, rbs, D.L * D.F, theta, h->cfg.log_threshold != 0, norms,
                                           1.0f / h->cfg.ste_bandwidth, lam1_over_b, gtheta));
   RUN(h, s, K_COLRED, launch_col_reduce(s, part2, rbs, D.L * D.F, 1.0f, nullptr, 0.f, gb_enc));
-  if (h->bf16) {
-    RUN(h, s, K_DWENC, launch_dwenc_bf16(s, D, ea, h->int8));
-    RUN(h, s, K_DWDEC, launch_dwdec_bf16(s, D, wa));
-  } else {
-    RUN(h, s, K_DWENC, launch_dwenc_f32(s, D, ea));
-    RUN(h, s, K_DWDEC, launch_dwdec_f32(s, D, wa));
+  if (h->bf16) RUN(h, s, K_DWENC, launch_dwenc_bf16(s, D, ea, h->int8));
+  else RUN(h, s, K_DWENC, launch_dwenc_f32(s, D, ea));
+  if (mode != CLT_DECODE_DENSE) {
+    RUN(h, s, K_FLISTS, launch_feature_lists(s, h->bf16, D, act_class, z, fl, flags));
+    RUN(h, s, K_SP_DWDEC, launch_sparse_dwdec(s, h->bf16, D, fl, wa, flags));
+  }
+  if (mode != CLT_DECODE_GATHER) {
+    if (h->bf16) RUN(h, s, K_DWDEC, launch_dwdec_bf16(s, D, wa)); else RUN(h, s, K_DWDEC, launch_dwdec_f32(s, D, wa));
   }
   h->stage = 1;   // the loss by-products are consumed; a new clt_loss is needed before the next backward
   return CLT_OK;

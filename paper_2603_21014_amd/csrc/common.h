@@ -120,12 +120,16 @@ struct DzArgs {        // dz[l] = sum_{lp>=l} dyhat[lp] W_dec[p(l,lp)]^T + g_sp,
   const void* d_yhat; const void* W_dec; const void* z; const uint8_t* cls; const float* norms;
   float lam_c_over_b; float C; void* dpre;
   float lam1_over_b;      // dead-feature coefficient lambda1 / B (0 = term off)
+  const int32_t* skip_flags = nullptr;   // optional switch: stand down when the gather path is selected
+  int kcap = 0;
 };
 // Optional Adam fused into the two weight-gradient GEMMs (m == nullptr: plain gradient output)
 struct AdamFuseArgs { float* m; float* v; float* master; AdamScalars a; };
 struct DWdecArgs {     // dW_dec[p] = z[l]^T dyhat[lp] + (G/n)[l,f] W_dec[p][f,:]
   const void* z; const void* d_yhat; void* W_dec; const float* G; const float* norms; void* dW_dec;
   AdamFuseArgs fuse;
+  const int32_t* skip_flags = nullptr;   // as in DzArgs
+  int kcap = 0;
 };
 struct DWencArgs {     // dW_enc[l] = x[l]^T dpre[l]
   const void* x; const void* dpre; void* dW_enc; void* W_enc;
@@ -184,21 +188,45 @@ hipError_t launch_adam_matrix(hipStream_t s, bool bf16, size_t n, void* p, const
                               float* master_or_null, AdamScalars a);
 hipError_t launch_adam_vector(hipStream_t s, size_t n, float* p, const float* g, float* m, float* v, AdamScalars a);
 
-// ---- active-feature gather decode (kernels_gather.hip) -----------------------
-// Device-side decode switch, 4 ints in the workspace:
+// ---- active-feature gather paths (kernels_gather.hip) -------------------------
+// Device-side switch, 4 ints in the workspace:
 //   [0] 1 when the measured density allows the gather path (or it is forced)
-//   [1] largest per-(layer, token) active count seen by the compaction
+//   [1] longest per-(layer, token) list seen by the compaction (active + window-only entries)
 //   [2] path taken by the last forward: 1 dense, 2 gather
-struct GatherLists { int32_t* idx; float* val; int32_t* counts; int kcap; };
+// The gather kernels run only when flags[0] != 0 and flags[1] <= kcap; the dense kernels that
+// carry the same flags stand down in exactly that case.
+__host__ __device__ inline bool gather_selected(const int32_t* flags, int kcap) {
+  return flags[0] != 0 && flags[1] <= kcap;
+}
+// Per (layer, token) row of kcap slots: the active features in ascending order from the front
+// (counts[row] of them, val = z), the inactive features inside the threshold window from the
+// back (counts_w[row] of them, slot kcap-1 first, val = 0).
+struct GatherLists { int32_t* idx; float* val; int32_t* counts; int32_t* counts_w; int kcap; };
 // flags[0] = (sum l0 <= threshold * L*B*F) or forced; flags[1] = 0
 hipError_t launch_decode_decide(hipStream_t s, Dims D, const int32_t* l0, float density_threshold, int forced,
                                 int32_t* flags);
-// per (layer, token) row: indices and values of the active features, in feature order
 hipError_t launch_compact_active(hipStream_t s, bool bf16, Dims D, const void* z, const uint8_t* cls, GatherLists g,
                                  int32_t* flags);
-// y_hat[lp, b, :] = b_dec[lp] + sum_{l<=lp} sum_{active f} z[l,b,f] W_dec[p(l,lp)][f, :]; runs only when
-// flags say so (flags[0] != 0 and flags[1] <= kcap) and records the path in flags[2]
+// y_hat[lp, b, :] = b_dec[lp] + sum_{l<=lp} sum_{active f} z[l,b,f] W_dec[p(l,lp)][f, :]; records the path in flags[2]
 hipError_t launch_gather_decode(hipStream_t s, bool bf16, Dims D, GatherLists g, const void* W_dec,
                                 const float* b_dec, float* y_hat, int32_t* flags);
+
+// Sparse backward through the decoder (same switch).
+// dpre := 0, or the dead-feature gradient -(lambda1/B) n where pre < theta and the entry is not listed
+hipError_t launch_sparse_dpre_fill(hipStream_t s, bool bf16, Dims D, const uint8_t* cls, const float* norms,
+                                   float lam1_over_b, void* dpre, const int32_t* flags, int kcap);
+// dz at the listed entries only: sum_{lp>=l} <d_yhat[lp,b,:], W_dec[p(l,lp)][f,:]> + sparsity gradient -> dpre[l,b,f]
+hipError_t launch_gather_dz(hipStream_t s, bool bf16, Dims D, GatherLists g, const void* d_yhat, const void* W_dec,
+                            const float* norms, float lam_c_over_b, float C, void* dpre, const int32_t* flags);
+// Per (layer, feature): tokens on which the feature is active, ascending, with z (transpose of the row lists).
+// Layer l's entries start at l * B * kcap; off is layer-local.  seg holds FL_SEGS x L*F partial counts.
+constexpr int FL_SEGS = 16;
+struct FeatureLists { int32_t* off; int32_t* cnt; int32_t* tok; float* val; int32_t* seg; int kcap; };
+hipError_t launch_feature_lists(hipStream_t s, bool bf16, Dims D, const uint8_t* cls, const void* z, FeatureLists fl,
+                                const int32_t* flags);
+// dW_dec[p(l,lp)][f,:] = sum_{b in list(l,f)} z[l,b,f] d_yhat[lp,b,:] + (G/n)[l,f] W_dec[p][f,:], with the optional
+// fused Adam update of the row (every row is visited: Adam also moves rows without gradient)
+hipError_t launch_sparse_dwdec(hipStream_t s, bool bf16, Dims D, FeatureLists fl, const DWdecArgs& a,
+                               const int32_t* flags);
 
 }  // namespace clt

@@ -200,7 +200,7 @@ struct DecPolicy {
   const T* z; const T* W_dec; const float* b_dec; float* y_hat;
   const int32_t* skip_flags; int kcap;
   // the dense decode stands down when the device-side switch selected the gather path
-  __device__ bool skip() const { return skip_flags && skip_flags[0] != 0 && skip_flags[1] <= kcap; }
+  __device__ bool skip() const { return skip_flags && gather_selected(skip_flags, kcap); }
   struct GInfo { int lp; };
   struct Epi { float4 b; };
   __device__ GInfo ginfo(int order) const { return {D.L - 1 - order}; }   // longest K first
@@ -239,7 +239,9 @@ struct DzPolicy {
   const T* d_yhat; const T* W_dec; const T* z; const uint8_t* cls; const float* norms;
   float lam_c_over_b, C; T* dpre;
   float lam1_over_b;
-  __device__ bool skip() const { return false; }
+  const int32_t* skip_flags; int kcap;
+  // stands down when the device-side switch selected the sparse backward
+  __device__ bool skip() const { return skip_flags && gather_selected(skip_flags, kcap); }
   struct GInfo { int l; };
   struct Epi { float4 karg, kamp, dead; };   // per column: -2 log2(e) C n, 4 (lambda0 C / B) n, -(lambda1 / B) n
   __device__ GInfo ginfo(int order) const { return {order}; }             // K = (L-l) d, longest first
@@ -304,7 +306,8 @@ struct DWdecPolicy {
   int M, N, kseg, lda, ldb;
   const T* z; const T* d_yhat; T* W_dec; const float* G; const float* norms; T* dW_dec;   // dW_dec may be NULL when fused
   AdamFuse fuse;
-  __device__ bool skip() const { return false; }
+  const int32_t* skip_flags; int kcap;
+  __device__ bool skip() const { return skip_flags && gather_selected(skip_flags, kcap); }
   struct GInfo { int p, l, lp; };
   struct Epi {};
   __device__ GInfo ginfo(int order) const {

@@ -92,7 +92,8 @@ __global__ __launch_bounds__(256) void loss_rec_kernel(Dims D, const float* __re
   if (threadIdx.x == 0) loss_part[(size_t)l * gridDim.x + rb] = tot;
 }
 
-// ---- sparsity loss: partial sum tanh(C z n); column partials of C z sech^2(C z n).
+// ---- sparsity loss: partial sum tanh(C z n); column partials of C z sech^2(C z n)
+// (both from one hardware exponential).
 // With DEAD also the App. B dead-feature term: partial sum relu(theta - pre) n and the
 // column partials of relu(theta - pre) (its derivative w.r.t. the decoder norm).
 template <typename T, bool DEAD>
@@ -125,9 +126,12 @@ __global__ __launch_bounds__(256) void loss_sparsity_kernel(Dims D, const T* __r
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         if (zz[i] != 0.f) {
-          const float t = tanhf(cn[i] * zz[i]);
-          ts += t;
-          cs[i] += C * zz[i] * (1.0f - t * t);
+          // e = exp(-2|u|): tanh|u| = (1 - e) / (1 + e), sech^2 u = 4 e / (1 + e)^2 (no cancellation for large u)
+          const float u = cn[i] * zz[i];
+          const float e = __builtin_amdgcn_exp2f(-2.0f * 1.4426950408889634f * fabsf(u));
+          const float r = __builtin_amdgcn_rcpf(1.0f + e);
+          ts += copysignf((1.0f - e) * r, u);
+          cs[i] += C * zz[i] * (4.0f * e * r * r);
         }
       }
       if (DEAD) {

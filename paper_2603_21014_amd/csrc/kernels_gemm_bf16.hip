@@ -387,13 +387,13 @@ hipError_t launch_dec_bf16(hipStream_t s, Dims D, const DecArgs& a) {
 hipError_t launch_dz_bf16(hipStream_t s, Dims D, const DzArgs& a) {
   DzPolicy<bf16_t> p{D, D.B, D.F, D.d, D.d, D.d,
                      (const bf16_t*)a.d_yhat, (const bf16_t*)a.W_dec, (const bf16_t*)a.z, a.cls, a.norms,
-                     a.lam_c_over_b, a.C, (bf16_t*)a.dpre, a.lam1_over_b};
+                     a.lam_c_over_b, a.C, (bf16_t*)a.dpre, a.lam1_over_b, a.skip_flags, a.kcap};
   return launch(s, p, D.L);
 }
 hipError_t launch_dwdec_bf16(hipStream_t s, Dims D, const DWdecArgs& a) {
   DWdecPolicy<bf16_t> p{D, D.F, D.d, D.B, D.F, D.d,
                         (const bf16_t*)a.z, (const bf16_t*)a.d_yhat, (bf16_t*)a.W_dec, a.G, a.norms,
-                        (bf16_t*)a.dW_dec, AdamFuse{a.fuse.m, a.fuse.v, a.fuse.master, a.fuse.a}};
+                        (bf16_t*)a.dW_dec, AdamFuse{a.fuse.m, a.fuse.v, a.fuse.master, a.fuse.a}, a.skip_flags, a.kcap};
   return launch(s, p, D.P());
 }
 hipError_t launch_dwenc_bf16(hipStream_t s, Dims D, const DWencArgs& a, bool int8_x) {

@@ -104,13 +104,13 @@ hipError_t launch_dec_f32(hipStream_t s, Dims D, const DecArgs& a) {
 hipError_t launch_dz_f32(hipStream_t s, Dims D, const DzArgs& a) {
   DzPolicy<float> p{D, D.B, D.F, D.d, D.d, D.d,
                     (const float*)a.d_yhat, (const float*)a.W_dec, (const float*)a.z, a.cls, a.norms,
-                    a.lam_c_over_b, a.C, (float*)a.dpre, a.lam1_over_b};
+                    a.lam_c_over_b, a.C, (float*)a.dpre, a.lam1_over_b, a.skip_flags, a.kcap};
   return launch(s, p, D.L);
 }
 hipError_t launch_dwdec_f32(hipStream_t s, Dims D, const DWdecArgs& a) {
   DWdecPolicy<float> p{D, D.F, D.d, D.B, D.F, D.d,
                        (const float*)a.z, (const float*)a.d_yhat, (float*)a.W_dec, a.G, a.norms,
-                       (float*)a.dW_dec, AdamFuse{a.fuse.m, a.fuse.v, a.fuse.master, a.fuse.a}};
+                       (float*)a.dW_dec, AdamFuse{a.fuse.m, a.fuse.v, a.fuse.master, a.fuse.a}, a.skip_flags, a.kcap};
   return launch(s, p, D.P());
 }
 hipError_t launch_dwenc_f32(hipStream_t s, Dims D, const DWencArgs& a) {

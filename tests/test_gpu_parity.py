@@ -263,6 +263,47 @@ def test_gather_equals_dense(dtype):
     assert rel_l2(b.y_hat, a.y_hat) < 1e-5       # same fp32 sums, different order
     c = GpuRun(w, params, x, y, theta=theta, decode_mode=GATHER)
     assert (b.y_hat == c.y_hat).all()            # the gather path is deterministic
+    tol = 1e-5 if dtype == "f32" else 1e-2
+    for k in O.PARAM_NAMES:                      # sparse backward: same sums as the dense GEMMs, other order
+        assert rel_l2(b.grads[k], a.grads[k]) < tol, k
+        assert (b.grads[k] == c.grads[k]).all(), k
+        assert (b.new_params[k] == c.new_params[k]).all(), k
+
+
+@pytest.mark.parametrize("dtype,master", [("f32", False), ("bf16", False), ("bf16", True)])
+def test_sparse_backward_fused_adam(dtype, master):
+    """Backward through the decoder on the active-feature lists, Adam inside the row kernel."""
+    w = S.scaled(S.WORKLOADS["tiny"], dtype=dtype, L=3, d=264, F=520, B=150, seed=81, master_weights=master)
+    theta = sparse_theta(w, 0.04)
+    g, o = run_both(w, theta=theta, decode_mode=GATHER, fused=True)
+    assert g.decode_switch[2] == 2 and g.window.sum() > 20
+    show(f"sparse bwd fused {dtype} master={master}", compare_step(w, g, o, TOL[dtype]))
+
+
+def test_sparse_backward_many_layers():
+    """More than 8 targets per source: the row kernel walks them in two chunks."""
+    w = S.scaled(S.WORKLOADS["tiny"], dtype="bf16", L=11, d=64, F=256, B=48, seed=82)
+    theta = sparse_theta(w, 0.05)
+    for fused in (False, True):
+        g, o = run_both(w, theta=theta, decode_mode=GATHER, fused=fused)
+        show(f"sparse bwd L=11 fused={fused}", compare_step(w, g, o, TOL["bf16"]))
+
+
+def test_sparse_backward_with_dead_feature_term():
+    w = S.scaled(S.WORKLOADS["tiny"], dtype="bf16", L=3, d=128, F=512, B=130, seed=83, lambda1=5.0,
+                 log_threshold=True)
+    theta = torch.log(sparse_theta(w, 0.03))
+    g, o = run_both(w, theta=theta, decode_mode=GATHER, fused=True)
+    assert g.decode_switch[2] == 2
+    dead_term_matters(w, o, TOL["bf16"])
+    show("sparse bwd + dead term", compare_step(w, g, o, TOL["bf16"]))
+
+
+def test_sparse_backward_int8_inputs():
+    w = S.scaled(S.WORKLOADS["llama1b_int8"], L=2, d=264, F=520, B=300, k_active=8)
+    theta = sparse_theta(w, 0.03)
+    g, o = run_both(w, theta=theta, decode_mode=GATHER, fused=True)
+    show("sparse bwd int8", compare_step(w, g, o, TOL["bf16"]))
 
 
 def test_auto_switch_follows_measured_density():
