@@ -77,54 +77,78 @@ def cpu_oracle_baseline(w, log):
 
 
 def density_sweep(args, log):
-    """Sec. 3.2 crossover on this GPU: forward time of the dense decode against the
-    gather decode (compaction + gather) at forced activation densities, on the int8
-    Llama-shaped workload.  Prints one JSON line of its own."""
+    """Sec. 3.2 crossover on this GPU: the dense decode against the gather decode
+    (compaction + gather) at forced activation densities, and the whole train step
+    with the dense and with the list-driven backward.  Two input recipes at the int8
+    Llama shape: token norms with a heavy tail (a few tokens carry most of the active
+    features) and uniform token norms (what Sec. 3.1's normalisation produces).
+    Prints one JSON line of its own."""
     import torch
     from paper_2603_21014_amd import binding as K
     from workloads import clt_synth as S
-    w = S.WORKLOADS["llama1b_int8"]
     dev, T = "cuda:0", torch.bfloat16
-    p32 = S.make_params(w, device=dev)
-    x32, y32 = S.make_inputs(w, device=dev)
-    xq, xs = S.quantize_rows_int8(x32)
-    xdq = xq.float() * xs[:, :, None]
-    params = {k: (v.to(T) if k in ("W_enc", "W_dec") else v) for k, v in p32.items()}
-    rows = []
-    steps = {name: K.CLTStep(w.L, w.d, w.F, w.B, dtype="bf16", int8_inputs=True, C_=w.C, ste_bandwidth=w.ste_eps,
-                             device=dev, keep_pre=False, decode_mode=mode)
-             for name, mode in (("dense", K.DECODE_DENSE), ("gather", K.DECODE_GATHER))}
-    for rho in (0.001, 0.0025, 0.005, 0.01, 0.05):
-        params["theta"] = S.theta_for_density(xdq, p32["W_enc"], p32["b_enc"], rho)
-        row = {"density": rho}
-        for name, st in steps.items():
-            for it in range(3):
-                if it == 1:
-                    K.clt_profile_enable(st.H, True)
-                st.forward(xq, params, xs)
-            torch.cuda.synchronize()
-            prof = K.clt_profile_query(st.H)
-            K.clt_profile_enable(st.H, False)
-            ms = {k: v[0] / max(v[1], 1) for k, v in prof.items()}
-            if name == "dense":
-                row["dense_decode_ms"] = round(ms["decode_gemm"], 3)
-            else:
-                row["gather_decode_ms"] = round(ms["compact_active"] + ms["gather_decode"], 3)
-                row["compact_ms"] = round(ms["compact_active"], 3)
-                k_mean = st.l0.double().mean().item() / w.B
-                row["active_per_token_layer"] = round(k_mean, 1)
-                gbytes = w.B * k_mean * w.P * w.d * 2.0
-                row["gather_GBps"] = round(gbytes / (ms["gather_decode"] * 1e-3) / 1e9, 1)
-        log(str(row))
-        rows.append(row)
-    cross = None
-    for a, b in zip(rows, rows[1:]):
-        fa, fb = a["gather_decode_ms"] - a["dense_decode_ms"], b["gather_decode_ms"] - b["dense_decode_ms"]
-        if fa <= 0 < fb:
-            tt = fa / (fa - fb)
-            cross = a["active_per_token_layer"] + tt * (b["active_per_token_layer"] - a["active_per_token_layer"])
-    print(json.dumps({"metric": "gather vs dense decode crossover (active features per token and layer)",
-                      "workload": w.name, "expansion": w.F / w.d, "crossover_k": cross, "rows": rows}), flush=True)
+    out = {"metric": "gather vs dense decode crossover (active features per token and layer)", "recipes": {}}
+    for recipe, w in (("heavy_tailed_tokens", S.WORKLOADS["llama1b_int8"]),
+                      ("uniform_tokens", S.scaled(S.WORKLOADS["llama1b_int8"], outliers=False))):
+        p32 = S.make_params(w, device=dev)
+        x32, y32 = S.make_inputs(w, device=dev)
+        xq, xs = S.quantize_rows_int8(x32)
+        yq, ys = S.quantize_rows_int8(y32)
+        xdq = xq.float() * xs[:, :, None]
+        del x32, y32
+        params = {k: (v.to(T) if k in ("W_enc", "W_dec") else v.clone()) for k, v in p32.items()}
+        m = {k: torch.zeros(v.shape, dtype=torch.float32, device=dev) for k, v in params.items()}
+        v_ = {k: torch.zeros(v.shape, dtype=torch.float32, device=dev) for k, v in params.items()}
+        rows = []
+        steps = {name: K.CLTStep(w.L, w.d, w.F, w.B, dtype="bf16", int8_inputs=True, C_=w.C,
+                                 ste_bandwidth=w.ste_eps, device=dev, keep_pre=False, decode_mode=mode,
+                                 matrix_grads=False)
+                 for name, mode in (("dense", K.DECODE_DENSE), ("gather", K.DECODE_GATHER))}
+        t = 0
+        for rho in (0.00025, 0.0005, 0.001, 0.0025, 0.005, 0.01):
+            theta = S.theta_for_density(xdq, p32["W_enc"], p32["b_enc"], rho)
+            row = {"density": rho}
+            for name, st in steps.items():
+                params["theta"].copy_(theta)
+                for it in range(3):
+                    if it == 1:
+                        K.clt_profile_enable(st.H, True)
+                    t += 1
+                    # lr 0: the density stays put
+                    st.train_step(xq, yq, params, m, v_, t, 0.0, w.lambda0, None, xs, ys)
+                torch.cuda.synchronize()
+                prof = K.clt_profile_query(st.H)
+                K.clt_profile_enable(st.H, False)
+                ms = {k: v[0] / 2.0 for k, v in prof.items()}    # two profiled steps
+                row[name + "_step_ms"] = round(sum(ms.values()), 2)
+                if name == "dense":
+                    row["dense_decode_ms"] = round(ms["decode_gemm"], 3)
+                    row["dense_dz_ms"] = round(ms["dz_gemm"], 3)
+                    row["dense_dW_dec_ms"] = round(ms["dW_dec_gemm"], 3)
+                else:
+                    row["gather_decode_ms"] = round(ms["compact_active"] + ms["gather_decode"], 3)
+                    row["compact_ms"] = round(ms["compact_active"], 3)
+                    row["gather_dz_ms"] = round(ms["sparse_dpre_fill"] + ms["gather_dz"], 3)
+                    row["sparse_dW_dec_ms"] = round(ms["feature_lists"] + ms["sparse_dW_dec"], 3)
+                    k_mean = st.l0.double().mean().item() / w.B
+                    row["active_per_token_layer"] = round(k_mean, 1)
+                    gbytes = w.B * k_mean * w.P * w.d * 2.0
+                    row["gather_GBps"] = round(gbytes / (ms["gather_decode"] * 1e-3) / 1e9, 1)
+                    row["gather_dz_GBps"] = round(gbytes / (ms["gather_dz"] * 1e-3) / 1e9, 1)
+                    # every parameter's weight, moments read and written once by the row kernel
+                    row["sparse_dW_dec_GBps"] = round(w.P * w.F * w.d * 20.0 / (ms["sparse_dW_dec"] * 1e-3) / 1e9, 1)
+            log(recipe + " " + str(row))
+            rows.append(row)
+        cross = None
+        for a, b in zip(rows, rows[1:]):
+            fa, fb = a["gather_decode_ms"] - a["dense_decode_ms"], b["gather_decode_ms"] - b["dense_decode_ms"]
+            if fa <= 0 < fb:
+                tt = fa / (fa - fb)
+                cross = a["active_per_token_layer"] + tt * (b["active_per_token_layer"] - a["active_per_token_layer"])
+        out["recipes"][recipe] = {"workload": w.name, "expansion": w.F / w.d, "crossover_k": cross, "rows": rows}
+        del steps, params, m, v_, p32, xq, yq, xdq
+        torch.cuda.empty_cache()
+    print(json.dumps(out), flush=True)
 
 
 def main():

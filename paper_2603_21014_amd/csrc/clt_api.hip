@@ -140,8 +140,9 @@ Plan make_plan(const clt_config* c) {
     k = (k + 7) / 8 * 8;
     p.kcap = (int)(k < F ? k : F);
   }
-  p.g_idx = o;      o += align_up(L * B * (size_t)p.kcap * 4);
-  p.g_val = o;      o += align_up(L * B * (size_t)p.kcap * 4);
+  const size_t lstride = p.kcap ? (size_t)list_stride(p.kcap) : 0;
+  p.g_idx = o;      o += align_up(L * B * lstride * 4);
+  p.g_val = o;      o += align_up(L * B * lstride * 4);
   p.g_counts = o;   o += align_up(L * B * 4);
   p.g_counts_w = o; o += align_up(L * B * 4);
   // per-feature token lists of the sparse backward (transpose of the row lists, same capacity)
@@ -347,7 +348,7 @@ int clt_forward(clt_handle* h, void* stream, const void* x, const float* x_scale
   DecArgs da{z, W_dec, b_dec, y_hat, mode == CLT_DECODE_AUTO ? flags : nullptr, h->plan.kcap};
   GatherLists gl{reinterpret_cast<int32_t*>(h->ws + h->plan.g_idx), reinterpret_cast<float*>(h->ws + h->plan.g_val),
                  reinterpret_cast<int32_t*>(h->ws + h->plan.g_counts),
-                 reinterpret_cast<int32_t*>(h->ws + h->plan.g_counts_w), h->plan.kcap};
+                 reinterpret_cast<int32_t*>(h->ws + h->plan.g_counts_w), h->plan.kcap, list_stride(h->plan.kcap)};
   if (h->bf16) {
     RUN(h, s, K_ENC, launch_enc_bf16(s, h->D, ea, h->int8));
   } else {
@@ -443,7 +444,7 @@ static int backward_impl(clt_handle* h, hipStream_t s, const void* x, const floa
   DWencArgs ea{x, dpre, gW_enc, W_enc, fenc};
   GatherLists gl{reinterpret_cast<int32_t*>(h->ws + h->plan.g_idx), reinterpret_cast<float*>(h->ws + h->plan.g_val),
                  reinterpret_cast<int32_t*>(h->ws + h->plan.g_counts),
-                 reinterpret_cast<int32_t*>(h->ws + h->plan.g_counts_w), kcap};
+                 reinterpret_cast<int32_t*>(h->ws + h->plan.g_counts_w), kcap, list_stride(kcap)};
   FeatureLists fl{reinterpret_cast<int32_t*>(h->ws + h->plan.fl_off), reinterpret_cast<int32_t*>(h->ws + h->plan.fl_cnt),
                   reinterpret_cast<int32_t*>(h->ws + h->plan.fl_tok), reinterpret_cast<float*>(h->ws + h->plan.fl_val),
                   reinterpret_cast<int32_t*>(h->ws + h->plan.fl_seg), kcap};

@@ -30,18 +30,22 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
 }
 __device__ __forceinline__ bf16_t f32_to_bf16(float f) { return (bf16_t)(pack_bf16x2(f, 0.0f) & 0xffffu); }
 
-// Streaming (non-temporal) 16- and 8-byte accesses for data that is touched once per kernel
-// (optimizer state, weights in the update epilogues): they should not displace the operand
-// panels that the contractions reuse out of the L2.
+// Streaming (non-temporal) 16- and 8-byte accesses for the optimizer state and weights in the
+// update epilogues of the contractions: data touched once there should not displace the operand
+// panels that the contractions reuse out of the L2.  (Kernels that do nothing but stream are
+// faster with plain accesses and do not use these.)
 typedef float nt_f32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int nt_u32x2 __attribute__((ext_vector_type(2)));
+#define CLT_NT_LOAD(p) __builtin_nontemporal_load(p)
+#define CLT_NT_STORE(v, p) __builtin_nontemporal_store(v, p)
+__device__ __forceinline__ nt_f32x4 nt_load_v4(const float* p) { return CLT_NT_LOAD(reinterpret_cast<const nt_f32x4*>(p)); }
 __device__ __forceinline__ float4 nt_load_f4(const float* p) {
-  const nt_f32x4 v = __builtin_nontemporal_load(reinterpret_cast<const nt_f32x4*>(p));
+  const nt_f32x4 v = nt_load_v4(p);
   return make_float4(v[0], v[1], v[2], v[3]);
 }
 __device__ __forceinline__ void nt_store_f4(float* p, float4 v) {
   const nt_f32x4 t = {v.x, v.y, v.z, v.w};
-  __builtin_nontemporal_store(t, reinterpret_cast<nt_f32x4*>(p));
+  CLT_NT_STORE(t, reinterpret_cast<nt_f32x4*>(p));
 }
 
 // Element-type traits for the two storage types.
@@ -69,13 +73,13 @@ template <> struct Elem<bf16_t> {
                        __uint_as_float(u.y << 16), __uint_as_float(u.y & 0xffff0000u));
   }
   static __device__ __forceinline__ float4 nt_load4(const bf16_t* p) {
-    const nt_u32x2 u = __builtin_nontemporal_load(reinterpret_cast<const nt_u32x2*>(p));
+    const nt_u32x2 u = CLT_NT_LOAD(reinterpret_cast<const nt_u32x2*>(p));
     return make_float4(__uint_as_float(u[0] << 16), __uint_as_float(u[0] & 0xffff0000u),
                        __uint_as_float(u[1] << 16), __uint_as_float(u[1] & 0xffff0000u));
   }
   static __device__ __forceinline__ void nt_store4(bf16_t* p, float4 v) {
     const nt_u32x2 u = {pack_bf16x2(v.x, v.y), pack_bf16x2(v.z, v.w)};
-    __builtin_nontemporal_store(u, reinterpret_cast<nt_u32x2*>(p));
+    CLT_NT_STORE(u, reinterpret_cast<nt_u32x2*>(p));
   }
 };
 
@@ -200,8 +204,10 @@ __host__ __device__ inline bool gather_selected(const int32_t* flags, int kcap) 
 }
 // Per (layer, token) row of kcap slots: the active features in ascending order from the front
 // (counts[row] of them, val = z), the inactive features inside the threshold window from the
-// back (counts_w[row] of them, slot kcap-1 first, val = 0).
-struct GatherLists { int32_t* idx; float* val; int32_t* counts; int32_t* counts_w; int kcap; };
+// back (counts_w[row] of them, slot kcap-1 first, val = 0).  Rows are `stride` slots apart
+// (list_stride(kcap): never a multiple of 4 KB, or the heads of all rows would share one L2 channel).
+struct GatherLists { int32_t* idx; float* val; int32_t* counts; int32_t* counts_w; int kcap; int stride; };
+__host__ __device__ inline int list_stride(int kcap) { return kcap + 32; }
 // flags[0] = (sum l0 <= threshold * L*B*F) or forced; flags[1] = 0
 hipError_t launch_decode_decide(hipStream_t s, Dims D, const int32_t* l0, float density_threshold, int forced,
                                 int32_t* flags);

@@ -24,6 +24,8 @@
 // state once, like a plain Adam pass, and reads its d y_hat rows out of the L2.
 #include "common.h"
 
+#include <type_traits>
+
 namespace clt {
 namespace {
 
@@ -60,8 +62,8 @@ __global__ __launch_bounds__(256) void compact_active_kernel(Dims D, const T* __
   if (row >= (long)D.L * D.B) return;
   const T* zr = z + (size_t)row * D.F;
   const uint8_t* cr = cls + (size_t)row * D.F;
-  int32_t* oi = g.idx + (size_t)row * g.kcap;
-  float* ov = g.val + (size_t)row * g.kcap;
+  int32_t* oi = g.idx + (size_t)row * g.stride;
+  float* ov = g.val + (size_t)row * g.stride;
   int base = 0, base_w = 0;
   for (int f0 = 0; f0 < D.F; f0 += 256) {
     const int f = f0 + lane * 4;
@@ -116,8 +118,8 @@ __global__ __launch_bounds__(256) void gather_decode_kernel(Dims D, GatherLists 
     for (int l = 0; l <= lp; ++l) {
       const size_t row = (size_t)l * D.B + b;
       const int cnt = g.counts[row];
-      const int32_t* ii = g.idx + row * g.kcap;
-      const float* vv = g.val + row * g.kcap;
+      const int32_t* ii = g.idx + row * g.stride;
+      const float* vv = g.val + row * g.stride;
       const T* Wp = W_dec + (size_t)packed_index(l, lp, D.L) * D.F * D.d + col;
       int j = 0;
       for (; j + 4 <= cnt; j += 4) {          // four rows in flight per lane
@@ -178,6 +180,13 @@ template <> struct Row8<float> {
   }
 };
 
+// Address = wave-uniform base + the lane's fixed element offset (one 32-bit register per lane).
+template <typename X>
+__device__ __forceinline__ X* lane_ptr(X* uniform_base, uint32_t lane_elems) {   // base + lane offset, 32-bit lane part
+  typedef typename std::conditional<std::is_const<X>::value, const char, char>::type Byte;
+  return reinterpret_cast<X*>(reinterpret_cast<Byte*>(uniform_base) + lane_elems * (uint32_t)sizeof(X));
+}
+
 // dpre := 0 (or the dead-feature gradient below the threshold); the listed entries are overwritten by gather_dz.
 template <typename T>
 __global__ __launch_bounds__(256) void sparse_dpre_fill_kernel(Dims D, const uint8_t* __restrict__ cls,
@@ -202,73 +211,91 @@ __global__ __launch_bounds__(256) void sparse_dpre_fill_kernel(Dims D, const uin
   }
 }
 
-// One workgroup per (layer, token) row, 8 columns of d per lane, 8 listed entries per batch:
-// for every target l' >= l the token's d y_hat columns are loaded once and multiplied with the
-// decoder rows of the 8 entries; the 8 partial dot products are then summed over the workgroup.
+// 8 consecutive elements kept as loaded (16 bytes of bf16 or 32 bytes of fp32) until they are used
+template <typename T> struct Raw8;
+template <> struct Raw8<bf16_t> {
+  typedef uint4 type;
+  static __device__ __forceinline__ type load(const bf16_t* p) { return *reinterpret_cast<const uint4*>(p); }
+  static __device__ __forceinline__ float dot(const type& a, const type& b, float acc) {
+    const uint32_t x[4] = {a.x, a.y, a.z, a.w}, y[4] = {b.x, b.y, b.z, b.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      acc = fmaf(__uint_as_float(x[i] << 16), __uint_as_float(y[i] << 16), acc);
+      acc = fmaf(__uint_as_float(x[i] & 0xffff0000u), __uint_as_float(y[i] & 0xffff0000u), acc);
+    }
+    return acc;
+  }
+};
+template <> struct Raw8<float> {
+  struct type { float4 lo, hi; };
+  static __device__ __forceinline__ type load(const float* p) {
+    return type{*reinterpret_cast<const float4*>(p), *reinterpret_cast<const float4*>(p + 4)};
+  }
+  static __device__ __forceinline__ float dot(const type& a, const type& b, float acc) {
+    acc = fmaf(a.lo.x, b.lo.x, acc); acc = fmaf(a.lo.y, b.lo.y, acc); acc = fmaf(a.lo.z, b.lo.z, acc);
+    acc = fmaf(a.lo.w, b.lo.w, acc); acc = fmaf(a.hi.x, b.hi.x, acc); acc = fmaf(a.hi.y, b.hi.y, acc);
+    acc = fmaf(a.hi.z, b.hi.z, acc); acc = fmaf(a.hi.w, b.hi.w, acc);
+    return acc;
+  }
+};
+
+// One wavefront per listed entry: for each target l' >= l it streams the entry's decoder row and
+// the token's d y_hat row (64 lanes x 8 columns, 4 passes in flight), keeps one partial dot
+// product per lane and reduces over the wave at the end.  No workgroup barrier, few registers
+// (eight waves per SIMD), so many independent latency chains overlap.  A row's entries are dealt
+// to GDZ_PARTS workgroups of 4 waves, so that the few very long rows of a heavy-tailed batch do
+// not serialise on one workgroup.
+constexpr int GDZ_PARTS = 8;
 template <typename T>
 __global__ __launch_bounds__(256) void gather_dz_kernel(Dims D, GatherLists g, const T* __restrict__ d_yhat,
                                                         const T* __restrict__ W_dec, const float* __restrict__ norms,
                                                         float lam_c_over_b, float C, T* __restrict__ dpre,
                                                         const int32_t* __restrict__ flags) {
   if (!gather_selected(flags, g.kcap)) return;
-  __shared__ float red[4][8];
-  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-  const long rows = (long)D.L * D.B;
-  for (long row = blockIdx.x; row < rows; row += gridDim.x) {    // layer 0 (most targets) first
+  const int lane = threadIdx.x & 63, wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const long items = ((long)D.L * D.B + 7) / 8 * 8 * GDZ_PARTS;
+  for (long it = blockIdx.x; it < items; it += gridDim.x) {      // layer 0 (most targets) first
+    // items in groups of 8 rows x GDZ_PARTS parts, the row index fastest: workgroups go round-robin
+    // to the 8 XCDs, so all parts of a row run on one XCD and share its L2
+    const long grp = it / (8 * GDZ_PARTS);
+    const int within = (int)(it % (8 * GDZ_PARTS));
+    const long row = grp * 8 + (within & 7);
+    const int part = within >> 3;
+    if (row >= (long)D.L * D.B) continue;
     const int l = (int)(row / D.B), b = (int)(row % D.B);
     const int na = g.counts[row], n = na + g.counts_w[row];
-    const int32_t* ii = g.idx + (size_t)row * g.kcap;
-    const float* vv = g.val + (size_t)row * g.kcap;
-    for (int e0 = 0; e0 < n; e0 += 8) {
-      int f[8];
+    const int32_t* ii = g.idx + (size_t)row * g.stride;
+    const float* vv = g.val + (size_t)row * g.stride;
+    for (int e = part * 4 + wv; e < n; e += 4 * GDZ_PARTS) {
+      const int slot = e < na ? e : g.kcap - 1 - (e - na);      // front: active entries, back: window-only
+      const int fe = __builtin_amdgcn_readfirstlane(ii[slot]);
+      float part_sum = 0.f;
+      for (int lp = l; lp < D.L; ++lp) {
+        const T* dyr = d_yhat + ((size_t)lp * D.B + b) * D.d;
+        const T* wr = W_dec + ((size_t)packed_index(l, lp, D.L) * D.F + fe) * D.d;
+        for (int c0 = 0; c0 < D.d; c0 += 2048) {
+          typename Raw8<T>::type dy[4], wq[4];
 #pragma unroll
-      for (int u = 0; u < 8; ++u) {
-        const int e = e0 + u;                                    // slot: front for active, back for window-only
-        f[u] = e < n ? ii[e < na ? e : g.kcap - 1 - (e - na)] : -1;
-      }
-      float part[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-      for (int c0 = 0; c0 < D.d; c0 += 2048) {
-        const int col = c0 + tid * 8;
-        if (col < D.d) {
-          for (int lp = l; lp < D.L; ++lp) {
-            float dy[8];
-            Row8<T>::load(d_yhat + ((size_t)lp * D.B + b) * D.d + col, dy);
-            const T* Wp = W_dec + (size_t)packed_index(l, lp, D.L) * D.F * D.d + col;
-            float w[8][8];
+          for (int q = 0; q < 4; ++q) {
+            const uint32_t col = (uint32_t)(c0 + q * 512 + lane * 8);
+            if ((int)col < D.d) { dy[q] = Raw8<T>::load(lane_ptr(dyr, col)); wq[q] = Raw8<T>::load(lane_ptr(wr, col)); }
+          }
 #pragma unroll
-            for (int u = 0; u < 8; ++u)
-              if (f[u] >= 0) Row8<T>::load(Wp + (size_t)f[u] * D.d, w[u]);
-#pragma unroll
-            for (int u = 0; u < 8; ++u)
-              if (f[u] >= 0) {
-#pragma unroll
-                for (int k = 0; k < 8; ++k) part[u] = fmaf(w[u][k], dy[k], part[u]);
-              }
+          for (int q = 0; q < 4; ++q) {
+            const uint32_t col = (uint32_t)(c0 + q * 512 + lane * 8);
+            if ((int)col < D.d) part_sum = Raw8<T>::dot(wq[q], dy[q], part_sum);
           }
         }
       }
 #pragma unroll
-      for (int u = 0; u < 8; ++u) {
-#pragma unroll
-        for (int off = 32; off > 0; off >>= 1) part[u] += __shfl_xor(part[u], off, 64);
-      }
-      __syncthreads();                       // the previous batch's readers are done with red
+      for (int off = 32; off > 0; off >>= 1) part_sum += __shfl_xor(part_sum, off, 64);
       if (lane == 0) {
-#pragma unroll
-        for (int u = 0; u < 8; ++u) red[wv][u] = part[u];
-      }
-      __syncthreads();
-      if (tid < 8 && e0 + tid < n) {
-        const int e = e0 + tid;
-        const int slot = e < na ? e : g.kcap - 1 - (e - na);
-        const int fe = ii[slot];
         const float zv = vv[slot];
         const float nn = norms[(size_t)l * D.F + fe];
         const float ex = __builtin_amdgcn_exp2f(-2.0f * 1.4426950408889634f * C * nn * fabsf(zv));
         const float sden = 1.0f + ex;
         const float gsp = 4.0f * lam_c_over_b * nn * ex * __builtin_amdgcn_rcpf(sden * sden);
-        const float dz = ((red[0][tid] + red[1][tid]) + (red[2][tid] + red[3][tid])) + gsp;
-        Elem<T>::store(dpre + (size_t)row * D.F + fe, dz);
+        Elem<T>::store(dpre + (size_t)row * D.F + fe, part_sum + gsp);
       }
     }
   }
@@ -362,10 +389,120 @@ __global__ __launch_bounds__(256) void fl_fill_kernel(Dims D, const uint8_t* __r
   }
 }
 
-// One item = (layer l, feature f, chunk of up to 8 targets): a workgroup of 256 lanes, 8 columns
-// each, sums z * d y_hat rows over the feature's tokens (two tokens in flight), then finishes the
-// row of every target: norm term, optional gradient store, optional Adam update.
-constexpr int SD_TCH = 8;
+// One item = (layer l, feature f, pair of targets): a workgroup of 256 lanes, 8 columns each,
+// sums z * d y_hat rows over the feature's tokens (four tokens in flight), then finishes the row
+// of both targets: norm term, optional gradient store, optional Adam update.  Most rows of a
+// sparse step have no token at all and only stream their optimizer state.  Token indices and
+// values are wave-uniform, so every address is a scalar base plus the lane's fixed column offset.
+constexpr int SD_TCH = 2;
+
+template <typename T, int NT>
+__device__ __forceinline__ void sparse_dwdec_rows(const Dims& D, int l, int f, int lp0, int cnt,
+                                                  const int32_t* __restrict__ tk, const float* __restrict__ tv,
+                                                  float coef, const T* __restrict__ d_yhat, T* __restrict__ W_dec,
+                                                  T* __restrict__ dW_dec, const AdamFuseArgs& fuse, uint32_t col,
+                                                  bool ok1) {
+  // the lane owns columns col..col+3 and, when ok1, col+1024..col+1027: every access of the
+  // workgroup is one contiguous run of 256 x 4 elements
+  float acc[NT][2][4];
+#pragma unroll
+  for (int t = 0; t < NT; ++t)
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+#pragma unroll
+      for (int k = 0; k < 4; ++k) acc[t][h][k] = 0.f;
+  int j = 0;
+  for (; j + 4 <= cnt; j += 4) {
+    float4 r[4][NT][2];
+    float zv[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int b = __builtin_amdgcn_readfirstlane(tk[j + u]);
+      zv[u] = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(tv[j + u])));
+#pragma unroll
+      for (int t = 0; t < NT; ++t) {
+        const T* row = d_yhat + ((size_t)(lp0 + t) * D.B + b) * D.d;
+        r[u][t][0] = Elem<T>::load4(lane_ptr(row, col));
+        r[u][t][1] = ok1 ? Elem<T>::load4(lane_ptr(row, col + 1024)) : make_float4(0.f, 0.f, 0.f, 0.f);
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+#pragma unroll
+      for (int t = 0; t < NT; ++t)
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+          acc[t][h][0] = fmaf(zv[u], r[u][t][h].x, acc[t][h][0]);
+          acc[t][h][1] = fmaf(zv[u], r[u][t][h].y, acc[t][h][1]);
+          acc[t][h][2] = fmaf(zv[u], r[u][t][h].z, acc[t][h][2]);
+          acc[t][h][3] = fmaf(zv[u], r[u][t][h].w, acc[t][h][3]);
+        }
+  }
+  for (; j < cnt; ++j) {
+    const int b = __builtin_amdgcn_readfirstlane(tk[j]);
+    const float zv = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(tv[j])));
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+      const T* row = d_yhat + ((size_t)(lp0 + t) * D.B + b) * D.d;
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        if (h == 1 && !ok1) continue;
+        const float4 r = Elem<T>::load4(lane_ptr(row, col + 1024 * h));
+        acc[t][h][0] = fmaf(zv, r.x, acc[t][h][0]);
+        acc[t][h][1] = fmaf(zv, r.y, acc[t][h][1]);
+        acc[t][h][2] = fmaf(zv, r.z, acc[t][h][2]);
+        acc[t][h][3] = fmaf(zv, r.w, acc[t][h][3]);
+      }
+    }
+  }
+  // the rows' weights and optimizer state: all loads first, then the updates
+  // (native vector types: selects on the float4 class type would go through scratch memory)
+  nt_f32x4 w[NT][2], m4[NT][2], v4[NT][2], p4[NT][2];
+#pragma unroll
+  for (int t = 0; t < NT; ++t) {
+    const size_t o = ((size_t)packed_index(l, lp0 + t, D.L) * D.F + f) * D.d;
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      w[t][h] = m4[t][h] = v4[t][h] = p4[t][h] = nt_f32x4{0.f, 0.f, 0.f, 0.f};
+      if (h == 1 && !ok1) continue;
+      const uint32_t ch = col + 1024 * h;
+      const float4 wl = Elem<T>::load4(lane_ptr(W_dec + o, ch));
+      w[t][h] = nt_f32x4{wl.x, wl.y, wl.z, wl.w};
+      p4[t][h] = w[t][h];
+      if (fuse.m) {
+        m4[t][h] = *reinterpret_cast<const nt_f32x4*>(lane_ptr(fuse.m + o, ch));
+        v4[t][h] = *reinterpret_cast<const nt_f32x4*>(lane_ptr(fuse.v + o, ch));
+        if (fuse.master) p4[t][h] = *reinterpret_cast<const nt_f32x4*>(lane_ptr(fuse.master + o, ch));
+      }
+    }
+  }
+#pragma unroll
+  for (int t = 0; t < NT; ++t) {
+    const size_t o = ((size_t)packed_index(l, lp0 + t, D.L) * D.F + f) * D.d;
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      if (h == 1 && !ok1) continue;
+      const uint32_t ch = col + 1024 * h;
+      const nt_f32x4 wq = w[t][h];
+      const float g4[4] = {fmaf(coef, wq[0], acc[t][h][0]), fmaf(coef, wq[1], acc[t][h][1]),
+                           fmaf(coef, wq[2], acc[t][h][2]), fmaf(coef, wq[3], acc[t][h][3])};
+      if (dW_dec) Elem<T>::store4(lane_ptr(dW_dec + o, ch), make_float4(g4[0], g4[1], g4[2], g4[3]));
+      if (fuse.m) {
+        float mm[4] = {m4[t][h][0], m4[t][h][1], m4[t][h][2], m4[t][h][3]};
+        float vv[4] = {v4[t][h][0], v4[t][h][1], v4[t][h][2], v4[t][h][3]};
+        float pp[4] = {p4[t][h][0], p4[t][h][1], p4[t][h][2], p4[t][h][3]};
+#pragma unroll
+        for (int k = 0; k < 4; ++k) adam_element(pp[k], mm[k], vv[k], g4[k], fuse.a);
+        *reinterpret_cast<float4*>(lane_ptr(fuse.m + o, ch)) = make_float4(mm[0], mm[1], mm[2], mm[3]);
+        *reinterpret_cast<float4*>(lane_ptr(fuse.v + o, ch)) = make_float4(vv[0], vv[1], vv[2], vv[3]);
+        const float4 pn = make_float4(pp[0], pp[1], pp[2], pp[3]);
+        if (fuse.master) *reinterpret_cast<float4*>(lane_ptr(fuse.master + o, ch)) = pn;
+        Elem<T>::store4(lane_ptr(W_dec + o, ch), pn);
+      }
+    }
+  }
+}
+
 template <typename T>
 __global__ __launch_bounds__(256) void sparse_dwdec_kernel(Dims D, FeatureLists fl, const T* __restrict__ d_yhat,
                                                            T* __restrict__ W_dec, const float* __restrict__ G,
@@ -375,85 +512,45 @@ __global__ __launch_bounds__(256) void sparse_dwdec_kernel(Dims D, FeatureLists 
   const int tid = threadIdx.x;
   const int chunks = (D.L + SD_TCH - 1) / SD_TCH;          // chunk slots per (l, f); those past L - l are empty
   const long items = (long)D.L * D.F * chunks;
-  for (long it = blockIdx.x; it < items; it += gridDim.x) {
-    const int c = (int)(it % chunks);
-    const long lf = it / chunks;
-    const int l = (int)(lf / D.F), f = (int)(lf % D.F);
-    const int lp0 = l + c * SD_TCH;
-    if (lp0 >= D.L) continue;
-    const int nt = min(SD_TCH, D.L - lp0);
-    const int cnt = fl.cnt[lf];
-    const int32_t* tk = fl.tok + (size_t)l * D.B * fl.kcap + fl.off[lf];
-    const float* tv = fl.val + (size_t)l * D.B * fl.kcap + fl.off[lf];
-    const float coef = G[lf] * __builtin_amdgcn_rcpf(fmaxf(norms[lf], 1e-30f));
-    for (int c0 = 0; c0 < D.d; c0 += 2048) {
-      const int col = c0 + tid * 8;
-      if (col >= D.d) continue;
-      float acc[SD_TCH][8];
-#pragma unroll
-      for (int t = 0; t < SD_TCH; ++t)
-#pragma unroll
-        for (int k = 0; k < 8; ++k) acc[t][k] = 0.f;
-      int j = 0;
-      for (; j + 2 <= cnt; j += 2) {
-        const int bA = tk[j], bB = tk[j + 1];
-        const float vA = tv[j], vB = tv[j + 1];
-        float rA[SD_TCH][8], rB[SD_TCH][8];
-#pragma unroll
-        for (int t = 0; t < SD_TCH; ++t)
-          if (t < nt) {
-            Row8<T>::load(d_yhat + ((size_t)(lp0 + t) * D.B + bA) * D.d + col, rA[t]);
-            Row8<T>::load(d_yhat + ((size_t)(lp0 + t) * D.B + bB) * D.d + col, rB[t]);
-          }
-#pragma unroll
-        for (int t = 0; t < SD_TCH; ++t)
-          if (t < nt) {
-#pragma unroll
-            for (int k = 0; k < 8; ++k) acc[t][k] = fmaf(vA, rA[t][k], acc[t][k]);
-#pragma unroll
-            for (int k = 0; k < 8; ++k) acc[t][k] = fmaf(vB, rB[t][k], acc[t][k]);
-          }
+  // what an item needs before its rows can be touched; fetched one item ahead
+  struct Meta { int l, f, lp0, cnt, off; float Gf, nf; };
+  auto fetch_meta = [&](long it) {
+    Meta mt;
+    // order (l, target pair, f): the workgroups in flight walk a few long contiguous row ranges
+    mt.f = (int)(it % D.F);
+    const long lc = it / D.F;
+    const int c = (int)(lc % chunks);
+    mt.l = (int)(lc / chunks);
+    const long lf = (long)mt.l * D.F + mt.f;
+    mt.lp0 = mt.l + c * SD_TCH;
+    mt.cnt = 0; mt.off = 0; mt.Gf = 0.f; mt.nf = 1.f;
+    if (mt.lp0 < D.L) { mt.cnt = fl.cnt[lf]; mt.off = fl.off[lf]; mt.Gf = G[lf]; mt.nf = norms[lf]; }
+    return mt;
+  };
+  long it = blockIdx.x;
+  if (it >= items) return;
+  Meta cur = fetch_meta(it);
+  for (; it < items; it += gridDim.x) {
+    const long nx = it + gridDim.x;
+    Meta nxt = cur;
+    if (nx < items) nxt = fetch_meta(nx);
+    if (cur.lp0 < D.L) {
+      const int32_t* tk = fl.tok + (size_t)cur.l * D.B * fl.kcap + cur.off;
+      const float* tv = fl.val + (size_t)cur.l * D.B * fl.kcap + cur.off;
+      const float coef = cur.Gf * __builtin_amdgcn_rcpf(fmaxf(cur.nf, 1e-30f));
+      for (int c0 = 0; c0 < D.d; c0 += 2048) {
+        const int col = c0 + tid * 4;
+        if (col >= D.d) continue;
+        const bool ok1 = col + 1024 < D.d;
+        if (cur.lp0 + 1 < D.L)
+          sparse_dwdec_rows<T, 2>(D, cur.l, cur.f, cur.lp0, cur.cnt, tk, tv, coef, d_yhat, W_dec, dW_dec, fuse,
+                                  (uint32_t)col, ok1);
+        else
+          sparse_dwdec_rows<T, 1>(D, cur.l, cur.f, cur.lp0, cur.cnt, tk, tv, coef, d_yhat, W_dec, dW_dec, fuse,
+                                  (uint32_t)col, ok1);
       }
-      if (j < cnt) {
-        const int bA = tk[j];
-        const float vA = tv[j];
-#pragma unroll
-        for (int t = 0; t < SD_TCH; ++t)
-          if (t < nt) {
-            float rA[8];
-            Row8<T>::load(d_yhat + ((size_t)(lp0 + t) * D.B + bA) * D.d + col, rA);
-#pragma unroll
-            for (int k = 0; k < 8; ++k) acc[t][k] = fmaf(vA, rA[k], acc[t][k]);
-          }
-      }
-#pragma unroll
-      for (int t = 0; t < SD_TCH; ++t)
-        if (t < nt) {
-          const size_t o = ((size_t)packed_index(l, lp0 + t, D.L) * D.F + f) * D.d + col;
-#pragma unroll
-          for (int h = 0; h < 2; ++h) {                   // two groups of 4 columns
-            const size_t oh = o + 4 * h;
-            const float4 w = Elem<T>::nt_load4(W_dec + oh);
-            const float4 gr = make_float4(fmaf(coef, w.x, acc[t][4 * h]), fmaf(coef, w.y, acc[t][4 * h + 1]),
-                                          fmaf(coef, w.z, acc[t][4 * h + 2]), fmaf(coef, w.w, acc[t][4 * h + 3]));
-            if (dW_dec) Elem<T>::store4(dW_dec + oh, gr);
-            if (fuse.m) {
-              const float4 m4 = nt_load_f4(fuse.m + oh), v4 = nt_load_f4(fuse.v + oh);
-              const float4 p4 = fuse.master ? nt_load_f4(fuse.master + oh) : w;
-              const float g4[4] = {gr.x, gr.y, gr.z, gr.w};
-              float mm[4] = {m4.x, m4.y, m4.z, m4.w}, vv[4] = {v4.x, v4.y, v4.z, v4.w};
-              float pp[4] = {p4.x, p4.y, p4.z, p4.w};
-#pragma unroll
-              for (int k = 0; k < 4; ++k) adam_element(pp[k], mm[k], vv[k], g4[k], fuse.a);
-              nt_store_f4(fuse.m + oh, make_float4(mm[0], mm[1], mm[2], mm[3]));
-              nt_store_f4(fuse.v + oh, make_float4(vv[0], vv[1], vv[2], vv[3]));
-              const float4 pn = make_float4(pp[0], pp[1], pp[2], pp[3]);
-              if (fuse.master) nt_store_f4(fuse.master + oh, pn);
-              Elem<T>::nt_store4(W_dec + oh, pn);
-            }
-          }
-        }
     }
+    cur = nxt;
   }
 }
 
@@ -502,8 +599,8 @@ hipError_t launch_sparse_dpre_fill(hipStream_t s, bool bf16, Dims D, const uint8
 
 hipError_t launch_gather_dz(hipStream_t s, bool bf16, Dims D, GatherLists g, const void* d_yhat, const void* W_dec,
                             const float* norms, float lam_c_over_b, float C, void* dpre, const int32_t* flags) {
-  const size_t rows = (size_t)D.L * D.B;
-  const dim3 grid((unsigned)(rows < 256 * 64 ? rows : 256 * 64));
+  const size_t items = ((size_t)D.L * D.B + 7) / 8 * 8 * GDZ_PARTS;
+  const dim3 grid((unsigned)(items < 256 * 64 ? items : 256 * 64));
   if (bf16)
     hipLaunchKernelGGL((gather_dz_kernel<bf16_t>), grid, dim3(256), 0, s, D, g, (const bf16_t*)d_yhat,
                        (const bf16_t*)W_dec, norms, lam_c_over_b, C, (bf16_t*)dpre, flags);
