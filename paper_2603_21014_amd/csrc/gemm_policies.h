@@ -307,13 +307,14 @@ struct DWdecPolicy {
   const T* z; const T* d_yhat; T* W_dec; const float* G; const float* norms; T* dW_dec;   // dW_dec may be NULL when fused
   AdamFuse fuse;
   const int32_t* skip_flags; int kcap;
+  int p0;   // first decoder block of this launch
   __device__ bool skip() const { return skip_flags && gather_selected(skip_flags, kcap); }
   struct GInfo { int p, l, lp; };
   struct Epi {};
   __device__ GInfo ginfo(int order) const {
-    int l = 0, r = order;
+    int l = 0, r = order + p0;
     while (r >= D.L - l) { r -= D.L - l; ++l; }
-    return {order, l, l + r};
+    return {order + p0, l, l + r};
   }
   __device__ int nseg(const GInfo&) const { return 1; }
   __device__ const T* a_seg(const GInfo& g, int) const { return z + (size_t)g.l * D.B * D.F; }

@@ -393,8 +393,16 @@ hipError_t launch_dz_bf16(hipStream_t s, Dims D, const DzArgs& a) {
 hipError_t launch_dwdec_bf16(hipStream_t s, Dims D, const DWdecArgs& a) {
   DWdecPolicy<bf16_t> p{D, D.F, D.d, D.B, D.F, D.d,
                         (const bf16_t*)a.z, (const bf16_t*)a.d_yhat, (bf16_t*)a.W_dec, a.G, a.norms,
-                        (bf16_t*)a.dW_dec, AdamFuse{a.fuse.m, a.fuse.v, a.fuse.master, a.fuse.a}, a.skip_flags, a.kcap};
-  return launch(s, p, D.P());
+                        (bf16_t*)a.dW_dec, AdamFuse{a.fuse.m, a.fuse.v, a.fuse.master, a.fuse.a}, a.skip_flags, a.kcap, 0};
+  // One launch per source layer: the tiles that share operand panels start together again at
+  // every launch and stay in step along K, which keeps the panel reuse in the XCDs' L2s (same
+  // run time as one long launch, but half the traffic to the fabric).
+  for (int l = 0; l < D.L; ++l) {
+    p.p0 = packed_index(l, l, D.L);
+    const hipError_t e = launch(s, p, D.L - l);
+    if (e != hipSuccess) return e;
+  }
+  return hipSuccess;
 }
 hipError_t launch_dwenc_bf16(hipStream_t s, Dims D, const DWencArgs& a, bool int8_x) {
   if (int8_x) {
