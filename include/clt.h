@@ -71,8 +71,9 @@ typedef struct clt_config {
   int32_t input_format;   /* CLT_INPUT_INT8_ROWSCALE: x and y are int8 codes with one
                              float scale per (layer, token) row (Sec. 3.1 cache format) */
   int32_t master_weights; /* 1: clt_adam_step updates fp32 master copies of W_enc/W_dec  */
-  int32_t decode_mode;    /* dense GEMM decode, active-feature gather decode (Sec. 3.2),
-                             or chosen per step, on the device, from the measured density */
+  int32_t decode_mode;    /* dense GEMMs, active-feature gather kernels (Sec. 3.2: the decode, and here
+                             also the two backward contractions through the decoder), or chosen per
+                             step, on the device, from the measured density                        */
   int32_t log_threshold;  /* 0: the theta tensor holds the threshold itself; 1: it holds
                              tau = log(theta) (App. B writes the threshold as exp(tau)), the
                              kernels take exp() of it and theta's gradient and Adam step are
@@ -139,7 +140,9 @@ int clt_loss(clt_handle* handle, void* stream,
  * pseudo-gradient -(theta/eps) sum_b 1[in window] dz.  With lambda1 > 0 the
  * dead-feature term adds -(lambda1/B) n to d pre and +(lambda1/B) n to d theta
  * for every entry with pre < theta, and its decoder-norm derivative to dW_dec.
- * With log_threshold the theta gradient is the one w.r.t. tau (times theta). */
+ * With log_threshold the theta gradient is the one w.r.t. tau (times theta).
+ * When the preceding clt_forward decoded through the active-feature lists, dz and
+ * dW_dec are computed from those lists as well (same sums, zero terms skipped). */
 int clt_backward(clt_handle* handle, void* stream,
                  const void* x, const float* x_scale, const float* theta,
                  const void* W_dec, const void* z, const uint8_t* act_class,
