@@ -36,7 +36,10 @@ class LazyBlocks:
 
 
 @pytest.mark.timeout(1200)
-def test_llama1b_shaped_step_against_sampled_oracle():
+@pytest.mark.parametrize("mode", ["unfused", "fused", "sparse_fused"])
+def test_llama1b_shaped_step_against_sampled_oracle(mode):
+    """unfused: clt_backward + clt_adam_step; fused: clt_backward_adam_step, the call bench.py times;
+    sparse_fused: thresholds at 0.2 % density, forced gather mode (list-driven decode, dz and dW_dec)."""
     from paper_2603_21014_amd import binding as K
     w = S.WORKLOADS["llama1b"]
     L, d, F, B = w.L, w.d, w.F, w.B
@@ -45,24 +48,37 @@ def test_llama1b_shaped_step_against_sampled_oracle():
     p32 = S.make_params(w, device=dev)
     params = {k: (v.to(T) if k in ("W_enc", "W_dec") else v) for k, v in p32.items()}
     del p32
-    x, y = (t.to(T) for t in S.make_inputs(w, device=dev))
+    x32, y32 = S.make_inputs(w, device=dev)
+    if mode == "sparse_fused":
+        params["theta"] = S.theta_for_density(x32, params["W_enc"].float(), params["b_enc"], 0.002)
+    x, y = x32.to(T), y32.to(T)
+    del x32, y32
+    fused = mode != "unfused"
     m = {k: torch.zeros(v.shape, dtype=torch.float32, device=dev) for k, v in params.items()}
     v_ = {k: torch.zeros(v.shape, dtype=torch.float32, device=dev) for k, v in params.items()}
-    step = K.CLTStep(L, d, F, B, dtype="bf16", C_=w.C, ste_bandwidth=w.ste_eps, device=dev, keep_pre=False)
-    print("running the GPU step", flush=True)
+    step = K.CLTStep(L, d, F, B, dtype="bf16", C_=w.C, ste_bandwidth=w.ste_eps, device=dev, keep_pre=False,
+                     matrix_grads=not fused,
+                     decode_mode=K.DECODE_GATHER if mode == "sparse_fused" else K.DECODE_DENSE)
+    print(f"running the GPU step ({mode})", flush=True)
+    W_dec_host = params["W_dec"].cpu()          # before Adam changes it
+    W_enc_host = params["W_enc"].float().cpu().numpy()
+    theta = params["theta"].cpu().numpy().astype(np.float64)
     step.forward(x, params)
     loss = step.loss(y, w.lambda0, to_host=True)
     d_yhat_gpu = K.clt_workspace_view(step.H, "d_yhat")
-    step.backward(x, params)
+    if fused:
+        step.backward_adam_step(x, params, m, v_, 1, w.lr)
+    else:
+        step.backward(x, params)
     dpre_last_gpu = K.clt_workspace_view(step.H, "dpre")[L - 1].float().cpu().numpy()
-    W_dec_host = params["W_dec"].cpu()          # before Adam changes it
-    W_enc_host = params["W_enc"].float().cpu().numpy()
-    step.adam_step(1, w.lr, params, m, v_)
+    if not fused:
+        step.adam_step(1, w.lr, params, m, v_)
     torch.cuda.synchronize()
     assert all(np.isfinite(loss))
+    if mode == "sparse_fused":
+        assert K.clt_workspace_view(step.H, "decode_switch").cpu().numpy()[2] == 2
 
     xh, yh = x.float().cpu().numpy(), y.float().cpu().numpy()
-    theta = params["theta"].cpu().numpy().astype(np.float64)
     b_enc = np.zeros((L, F)); b_dec = np.zeros((L, d))       # the workload's initial biases
     Wd = LazyBlocks(W_dec_host)
 
@@ -104,7 +120,7 @@ def test_llama1b_shaped_step_against_sampled_oracle():
             n_cache[key] = np.sqrt(acc)
         return n_cache[key]
 
-    dW_g_all, m_g_all = step.grads["W_dec"], m["W_dec"]
+    dW_g_all, m_g_all = step.grads.get("W_dec"), m["W_dec"]
     for (l, lp, f0, j0) in [(0, 0, 16, 0), (0, 15, 4096, 1984), (7, 9, 8184, 640), (15, 15, 1000, 1024)]:
         fs, js = slice(f0, f0 + 8), slice(j0, j0 + 64)
         ycol = np.tile(b_dec[lp][js][None, :], (B, 1))
@@ -119,8 +135,9 @@ def test_llama1b_shaped_step_against_sampled_oracle():
         G = (w.lambda0 / B) * np.sum(w.C * zf * sech2, axis=0)
         Wblk = W_dec_host[p, fs, js].float().numpy().astype(np.float64)
         dW_o = zf.T @ dcol + (G / np.maximum(n, 1e-30))[:, None] * Wblk
-        dW_g = dW_g_all[p, fs, js].float().cpu().numpy()
-        assert rel_l2(dW_g, dW_o) <= TOL, f"dW_dec slab {(l, lp, f0, j0)}"
+        if dW_g_all is not None:
+            dW_g = dW_g_all[p, fs, js].float().cpu().numpy()
+            assert rel_l2(dW_g, dW_o) <= TOL, f"dW_dec slab {(l, lp, f0, j0)}"
         assert rel_l2(m_g_all[p, fs, js].cpu().numpy(), 0.1 * dW_o) <= TOL, "Adam m on the slab"
         assert rel_l2(step.grads["b_dec"][lp, js].cpu().numpy(), dcol.sum(axis=0)) <= TOL, f"db_dec[{lp}]"
 
@@ -142,6 +159,7 @@ def test_llama1b_shaped_step_against_sampled_oracle():
     assert rel_l2(step.grads["b_enc"][l].cpu().numpy(), dpre.sum(axis=0)) <= TOL, "db_enc[L-1]"
     fs = slice(2048, 2048 + 64)
     dWe = xh[l].astype(np.float64).T @ dpre[:, fs]
-    assert rel_l2(step.grads["W_enc"][l, :, fs].float().cpu().numpy(), dWe) <= TOL, "dW_enc[L-1] columns"
+    if not fused:
+        assert rel_l2(step.grads["W_enc"][l, :, fs].float().cpu().numpy(), dWe) <= TOL, "dW_enc[L-1] columns"
     assert rel_l2(m["W_enc"][l, :, fs].cpu().numpy(), 0.1 * dWe) <= TOL, "Adam m of W_enc columns"
     print(f"full-size parity ok; loss {loss}", flush=True)
