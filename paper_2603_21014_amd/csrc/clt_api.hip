@@ -80,7 +80,8 @@ int check_config(const clt_config* c, char* err) {
             c->L, c->d, c->F, c->B);
     return CLT_ERR_SHAPE;
   }
-  if ((double)c->L * c->B * (double)c->F >= 9.0e18 || (size_t)c->L * c->B > (size_t)1 << 31) {
+  if ((double)c->L * c->B * (double)c->F >= 9.0e18 || (size_t)c->L * c->B > (size_t)1 << 31 ||
+      (size_t)c->L * c->F >= (size_t)1 << 31) {
     set_err(err, "shape too large");
     return CLT_ERR_SHAPE;
   }

@@ -57,6 +57,16 @@ def test_bf16_outlier_inputs_llama_shaped_slice():
     show("bf16 llama slice", compare_step(w, g, o, TOL["bf16"]))
 
 
+@pytest.mark.parametrize("name,F,B", [("gpt2", 512, 256), ("gemma2b", 256, 128)])
+def test_config_shaped_slices_full_depth(name, F, B):
+    """The GPT-2 and Gemma-2 configs at their full depth and model width (L = 12 / 26 layers, d = 768 / 2304: all
+    decoder blocks, up to 26 K segments per tile, 3 / 9 column tiles), on a slice of features and tokens the
+    oracle can do in seconds; the call the benchmark times (Adam fused, fp32 master weights for Gemma)."""
+    w = S.scaled(S.WORKLOADS[name], F=F, B=B, k_active=8)
+    g, o = run_both(w, fused=True)
+    show(f"{name} slice L{w.L} d{w.d}", compare_step(w, g, o, TOL["bf16"]))
+
+
 def test_master_weights_bf16():
     w = S.scaled(S.WORKLOADS["gemma2b"], L=2, d=64, F=256, B=96)
     g, o = run_both(w)
