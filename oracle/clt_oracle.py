@@ -14,6 +14,9 @@ reordering:
                                   z = pre * H(pre - theta), strict ">", is the
                                   one of the JumpReLU literature the paper
                                   follows for its training recipe)
+  TopK .......................... Sec. 3.2 names it as the alternative activation
+                                  without a formula; taken as: per token and
+                                  layer keep the k largest pre-activations
   cross-layer decode ............ Sec. 2.1, eq. (3); eq. (2) is its L = 1 case
   decoder norms ................. App. B: norm of the concatenation of all
                                   decoders that leave a source layer
@@ -117,6 +120,39 @@ def jumprelu(pre, theta, tie_break=None, band=0.0):
     return z, active
 
 
+def topk_activation(pre, k, tie_break=None, band=0.0):
+    """TopK activation: for every (layer, token) row of pre [L, B, F] keep the k
+    largest entries (z = pre there, whatever its sign) and zero the rest; among
+    equal values the lower feature index wins.  Returns (z, active).
+
+    `tie_break` (boolean, same shape) is honoured only for entries within `band`
+    of the row's k-th largest value, where an implementation whose
+    pre-activation differs by rounding may rank differently; it must select
+    exactly k entries per row and agree with the oracle outside the band.
+    """
+    pre = np.asarray(pre, F64)
+    L, B, F = pre.shape
+    k = int(k)
+    if not 0 <= k <= F:
+        raise ValueError("k out of range")
+    active = np.zeros(pre.shape, bool)
+    if k > 0:
+        # stable sort of -pre: descending values, ascending index among equals
+        order = np.argsort(-pre, axis=2, kind="stable")
+        np.put_along_axis(active, order[:, :, :k], True, axis=2)
+    if tie_break is not None and 0 < k < F:
+        tb = np.asarray(tie_break, bool)
+        kth = np.take_along_axis(pre, order[:, :, k - 1:k], axis=2)      # [L, B, 1]
+        inband = np.abs(pre - kth) < band
+        if np.any((tb != active) & ~inband):
+            raise ValueError("top-k tie_break disagrees with the oracle outside the band")
+        if np.any(tb.sum(axis=2) != k):
+            raise ValueError("top-k tie_break does not select k entries in every row")
+        active = tb
+    z = np.where(active, pre, 0.0)
+    return z, active
+
+
 def ste_window(pre, theta, eps, tie_break=None, band=0.0):
     """Support of the rectangle kernel: |pre - theta| < eps / 2 (strict)."""
     pre = np.asarray(pre, F64)
@@ -195,10 +231,14 @@ def threshold_value(param, log_threshold):
     return np.exp(param) if log_threshold else param
 
 
-def forward(x, W_enc, b_enc, theta, W_dec, b_dec, tie_break=None, band=0.0):
-    """Encoder, JumpReLU, cross-layer decode.  Returns a dict of intermediates."""
+def forward(x, W_enc, b_enc, theta, W_dec, b_dec, tie_break=None, band=0.0, topk=None):
+    """Encoder, activation (JumpReLU with thresholds theta, or TopK with k = topk and
+    theta ignored), cross-layer decode.  Returns a dict of intermediates."""
     pre = encoder_preact(x, W_enc, b_enc)
-    z, active = jumprelu(pre, theta, tie_break, band)
+    if topk is None:
+        z, active = jumprelu(pre, theta, tie_break, band)
+    else:
+        z, active = topk_activation(pre, topk, tie_break, band)
     y_hat = decode(z, W_dec, b_dec)
     return {"pre": pre, "z": z, "active": active, "y_hat": y_hat,
             "l0_per_layer": active.sum(axis=(1, 2))}
@@ -219,7 +259,7 @@ def sparsity_norm_sums(z, n, lambda0, C):
 
 def backward(x, y, theta, W_dec, fwd, lambda0, C, eps,
              window_tie_break=None, band=0.0, lambda1=0.0, log_threshold=False,
-             below_tie_break=None):
+             below_tie_break=None, topk=False):
     """Gradients of L_rec + L_sp (+ L_dead when lambda1 > 0) w.r.t. the five
     parameter tensors.  `theta` is the threshold value; with log_threshold the
     stored parameter is tau = log(theta) and "dtheta" is the gradient w.r.t. tau.
@@ -238,6 +278,8 @@ def backward(x, y, theta, W_dec, fwd, lambda0, C, eps,
       G      += (lambda1/B) sum_b ReLU(theta - pre)      (the term's d/dn, enters dW_dec as G W / n)
     `below_tie_break` forces the decision pre < theta where |pre - theta| < band,
     under the same rule as jumprelu's tie_break.
+    With topk the activation was TopK: the selected set is piecewise constant in
+    the parameters, so d pre = dz on it and there is no threshold (dtheta = 0).
     """
     x = np.asarray(x, F64)
     y = np.asarray(y, F64)
@@ -269,7 +311,12 @@ def backward(x, y, theta, W_dec, fwd, lambda0, C, eps,
     if lambda1 != 0.0:
         dpre = dpre + np.where(below, -(lambda1 / B) * n[:, None, :], 0.0)
         G = G + (lambda1 / B) * np.sum(np.maximum(theta[:, None, :] - pre, 0.0), axis=1)
-    win = ste_window(pre, theta, eps, window_tie_break, band)
+    if topk:
+        if lambda1 != 0.0:
+            raise ValueError("the dead-feature term needs a threshold")
+        win = np.zeros(pre.shape, bool)
+    else:
+        win = ste_window(pre, theta, eps, window_tie_break, band)
     # sum over the window entries of the per-entry pseudo-derivative -(theta/eps) dz;
     # an empty window contributes exactly 0, also for a non-finite threshold
     with np.errstate(invalid="ignore"):
@@ -318,7 +365,7 @@ PARAM_NAMES = ("W_enc", "b_enc", "theta", "W_dec", "b_dec")
 
 
 def train_step(x, y, params, m, v, t, lr, lambda0, C, eps,
-               beta1=0.9, beta2=0.999, adam_eps=1e-8, lambda1=0.0, log_threshold=False):
+               beta1=0.9, beta2=0.999, adam_eps=1e-8, lambda1=0.0, log_threshold=False, topk=None):
     """Forward, loss, backward and Adam on all five tensors.
 
     `params`, `m`, `v` are dicts keyed by PARAM_NAMES (params["theta"] holds tau
@@ -326,13 +373,13 @@ def train_step(x, y, params, m, v, t, lr, lambda0, C, eps,
     holding forward values, loss terms and gradients.
     """
     theta = threshold_value(params["theta"], log_threshold)
-    fwd = forward(x, params["W_enc"], params["b_enc"], theta, params["W_dec"], params["b_dec"])
+    fwd = forward(x, params["W_enc"], params["b_enc"], theta, params["W_dec"], params["b_dec"], topk=topk)
     L = np.asarray(x).shape[0]
     n = decoder_norms(params["W_dec"], L)
     total, rec, sp = loss_terms(fwd["y_hat"], y, fwd["z"], n, lambda0, C)
     total = total + dead_feature_term(fwd["pre"], theta, n, lambda1)
     grads = backward(x, y, theta, params["W_dec"], fwd, lambda0, C, eps,
-                     lambda1=lambda1, log_threshold=log_threshold)
+                     lambda1=lambda1, log_threshold=log_threshold, topk=topk is not None)
     new_p, new_m, new_v = {}, {}, {}
     for k in PARAM_NAMES:
         new_p[k], new_m[k], new_v[k] = adam_update(
