@@ -58,12 +58,13 @@ def cpu_oracle_baseline(w, log):
     zeros = {k: np.zeros_like(v) for k, v in params.items()}
     t0 = time.perf_counter()
     theta = O.threshold_value(params["theta"], ws.log_threshold)
-    fwd = O.forward(x, params["W_enc"], params["b_enc"], theta, params["W_dec"], params["b_dec"])
+    topk = max(1, ws.topk // 4) if ws.topk else None          # the sample has a quarter of the features
+    fwd = O.forward(x, params["W_enc"], params["b_enc"], theta, params["W_dec"], params["b_dec"], topk=topk)
     n = O.decoder_norms(params["W_dec"], ws.L)
     O.loss_terms(fwd["y_hat"], y, fwd["z"], n, ws.lambda0, ws.C)
     O.dead_feature_term(fwd["pre"], theta, n, ws.lambda1)
     grads = O.backward(x, y, theta, params["W_dec"], fwd, ws.lambda0, ws.C, ws.ste_eps, lambda1=ws.lambda1,
-                       log_threshold=ws.log_threshold)
+                       log_threshold=ws.log_threshold, topk=topk is not None)
     t1 = time.perf_counter()
     for k in O.PARAM_NAMES:
         O.adam_update(params[k], grads["d" + k], zeros[k], zeros[k], 1, ws.lr)
@@ -157,6 +158,8 @@ def main():
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="llama1b")
+    ap.add_argument("--decode-mode", default="dense", choices=["dense", "gather", "auto"],
+                    help="dense GEMMs (default), the list-driven kernels of the sparse regime, or the device-side switch")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-timing", action="store_true",
                     help="skip the per-kernel HIP-event brackets (roofline entry becomes null)")
@@ -200,7 +203,9 @@ def main():
     v_ = {k: torch.zeros(v.shape, dtype=torch.float32, device=dev) for k, v in params.items()}
     step = K.CLTStep(w.L, w.d, w.F, w.B, dtype="bf16", int8_inputs=w.int8_inputs, master_weights=w.master_weights,
                      C_=w.C, ste_bandwidth=w.ste_eps, device=dev, keep_pre=w.lambda1 > 0,
-                     log_threshold=w.log_threshold)
+                     log_threshold=w.log_threshold, topk=w.topk or None,
+                     decode_mode={"dense": K.DECODE_DENSE, "gather": K.DECODE_GATHER, "auto": K.DECODE_AUTO}[args.decode_mode],
+                     gather_density_threshold=0.01, matrix_grads=False)
     torch.cuda.synchronize()
     log(f"workload {w.name}: L={w.L} d={w.d} F={w.F} B={w.B}, inputs ready in {time.perf_counter() - t0:.1f}s, "
         f"{torch.cuda.memory_allocated() / 2**30:.1f} GiB allocated")
@@ -243,11 +248,22 @@ def main():
                 ent["tflops"] = round(fl / (avg * 1e-3) / 1e12, 1)
                 ent["flop"] = fl
             kernels[name] = ent
-        dom = max((k for k in kernels if k in GEMM_PAIRS), key=lambda k: kernels[k]["avg_ms"])
-        ach = kernels[dom]["tflops"]
-        roof = {"kernel": dom, "bound": "mfma", "achieved": ach, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                "frac": round(ach / PEAK_BF16_TFLOPS, 4), "traffic": profiled_traffic_bytes(w.name, dom),
-                "avg_launch_ms": kernels[dom]["avg_ms"], "flop_per_launch": kernels[dom]["flop"]}
+        # algorithmic bytes of the list-driven kernels: decoder rows of the listed features (decode, dz), the
+        # weights and moments read and written once (row kernel of dW_dec)
+        rows_bytes = w.B * l0 * w.P * w.d * 2.0
+        hbm_bytes = {"gather_decode": rows_bytes, "gather_dz": rows_bytes, "sparse_dW_dec": 20.0 * w.P * w.F * w.d}
+        per_step = lambda k: kernels[k]["avg_ms"] * kernels[k]["launches_per_step"]
+        dom = max((k for k in kernels if k in GEMM_PAIRS or k in hbm_bytes), key=per_step)
+        if dom in GEMM_PAIRS:
+            ach = kernels[dom]["tflops"]
+            roof = {"kernel": dom, "bound": "mfma", "achieved": ach, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                    "frac": round(ach / PEAK_BF16_TFLOPS, 4), "traffic": profiled_traffic_bytes(w.name, dom),
+                    "avg_launch_ms": kernels[dom]["avg_ms"], "flop_per_launch": kernels[dom]["flop"]}
+        else:
+            ach = hbm_bytes[dom] / (kernels[dom]["avg_ms"] * 1e-3) / 1e9
+            roof = {"kernel": dom, "bound": "hbm", "achieved": round(ach, 1), "peak": 8000.0, "unit": "GB/s",
+                    "frac": round(ach / 8000.0, 4), "traffic": None, "avg_launch_ms": kernels[dom]["avg_ms"],
+                    "bytes_per_launch": hbm_bytes[dom]}
         for name, ent in sorted(kernels.items(), key=lambda kv: -kv[1]["avg_ms"] * kv[1]["launches_per_step"]):
             log(f"  {name:24s} {ent['avg_ms']:9.3f} ms x {ent['launches_per_step']:.0f}"
                 + (f"  {ent['tflops']:7.1f} TFLOP/s" if "tflops" in ent else ""))
@@ -269,7 +285,8 @@ def main():
         "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": w.name, "L": w.L, "d_model": w.d, "features_per_layer": w.F, "tokens": w.B,
-                   "decoder_blocks": w.P, "int8_inputs": w.int8_inputs, "master_weights": w.master_weights},
+                   "decoder_blocks": w.P, "int8_inputs": w.int8_inputs, "master_weights": w.master_weights,
+                   "activation": f"topk{w.topk}" if w.topk else "jumprelu", "decode_mode": args.decode_mode},
         "step_dense_tflops": flop / (ms_per_step * 1e-3) / 1e12,
         "step_frac_of_bf16_mfma_peak": flop / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
         "roofline": roof, "cpu_baseline": cpu, "kernels": kernels,

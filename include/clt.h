@@ -60,6 +60,7 @@ typedef enum clt_status {
 enum { CLT_DTYPE_F32 = 0, CLT_DTYPE_BF16 = 1 };
 enum { CLT_INPUT_NATIVE = 0, CLT_INPUT_INT8_ROWSCALE = 1 };
 enum { CLT_DECODE_AUTO = 0, CLT_DECODE_DENSE = 1, CLT_DECODE_GATHER = 2 };
+enum { CLT_ACT_JUMPRELU = 0, CLT_ACT_TOPK = 1 };
 
 /* Plain data; set .size = sizeof(clt_config).  Shapes: L >= 1, B >= 1,
  * d and F positive multiples of 8. */
@@ -78,6 +79,12 @@ typedef struct clt_config {
                              tau = log(theta) (App. B writes the threshold as exp(tau)), the
                              kernels take exp() of it and theta's gradient and Adam step are
                              those of tau                                                   */
+  int32_t activation;     /* CLT_ACT_JUMPRELU (eq. 1's z = pre 1[pre > theta]) or CLT_ACT_TOPK (Sec. 3.2
+                             names it): per token and layer the topk_k largest pre-activations are
+                             kept (z = pre there, the lower feature index wins among equal values),
+                             decided on the fp32 pre-activation.  With TopK the theta tensor is
+                             ignored by every call, its gradient is 0 and lambda1 must be 0.       */
+  int32_t topk_k;         /* 0 <= topk_k <= F; read only when activation == CLT_ACT_TOPK           */
   float gather_density_threshold; /* AUTO: gather when the mean active fraction of the batch
                              is <= this and no (layer, token) row has more than about 8x
                              as many active features (else the step decodes densely)    */

@@ -36,7 +36,8 @@ class CLTError(RuntimeError):
 class clt_config(C.Structure):
     _fields_ = [("size", C.c_uint32), ("L", C.c_int32), ("d", C.c_int32), ("F", C.c_int32), ("B", C.c_int32),
                 ("dtype", C.c_int32), ("input_format", C.c_int32), ("master_weights", C.c_int32),
-                ("decode_mode", C.c_int32), ("log_threshold", C.c_int32), ("gather_density_threshold", C.c_float), ("C", C.c_float),
+                ("decode_mode", C.c_int32), ("log_threshold", C.c_int32), ("activation", C.c_int32), ("topk_k", C.c_int32),
+                ("gather_density_threshold", C.c_float), ("C", C.c_float),
                 ("ste_bandwidth", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float), ("adam_eps", C.c_float)]
 
 
@@ -100,9 +101,11 @@ def _ptr(t, shape, dtype, name, optional=False):
 
 def make_config(L, d, F, B, dtype=DTYPE_BF16, input_format=INPUT_NATIVE, master_weights=False,
                 decode_mode=DECODE_DENSE, gather_density_threshold=0.005, C_=4.0, ste_bandwidth=0.05,
-                beta1=0.9, beta2=0.999, adam_eps=1e-8, log_threshold=False):
+                beta1=0.9, beta2=0.999, adam_eps=1e-8, log_threshold=False, topk=None):
+    """topk: None for JumpReLU, else k of the TopK activation."""
     return clt_config(C.sizeof(clt_config), L, d, F, B, dtype, input_format, int(master_weights), decode_mode,
-                      int(log_threshold), gather_density_threshold, C_, ste_bandwidth, beta1, beta2, adam_eps)
+                      int(log_threshold), 0 if topk is None else 1, 0 if topk is None else int(topk),
+                      gather_density_threshold, C_, ste_bandwidth, beta1, beta2, adam_eps)
 
 
 def clt_workspace_bytes(cfg: clt_config) -> int:
@@ -261,11 +264,12 @@ class CLTStep:
 
     def __init__(self, L, d, F, B, dtype="bf16", int8_inputs=False, master_weights=False, C_=4.0,
                  ste_bandwidth=0.05, beta1=0.9, beta2=0.999, adam_eps=1e-8, device="cuda:0", keep_pre=True,
-                 decode_mode=DECODE_DENSE, gather_density_threshold=0.005, matrix_grads=True, log_threshold=False):
+                 decode_mode=DECODE_DENSE, gather_density_threshold=0.005, matrix_grads=True, log_threshold=False,
+                 topk=None):
         dt = DTYPE_BF16 if dtype == "bf16" else DTYPE_F32
         self.cfg = make_config(L, d, F, B, dt, INPUT_INT8_ROWSCALE if int8_inputs else INPUT_NATIVE,
                                master_weights, decode_mode, gather_density_threshold, C_, ste_bandwidth, beta1,
-                               beta2, adam_eps, log_threshold)
+                               beta2, adam_eps, log_threshold, topk)
         self.device = torch.device(device)
         ws = torch.empty(clt_workspace_bytes(self.cfg), dtype=torch.uint8, device=self.device)
         self.H = clt_init(self.cfg, ws)

@@ -21,7 +21,7 @@ constexpr size_t ALIGN = 256;
 inline size_t align_up(size_t v) { return (v + ALIGN - 1) / ALIGN * ALIGN; }
 
 struct Plan {
-  size_t norms, G, d_yhat, dpre, part_cols, part_cols2, part_cols3, part_rec, part_sp, part_dead, l0, flags, g_idx, g_val, g_counts, g_counts_w,
+  size_t norms, G, d_yhat, dpre, part_cols, part_cols2, part_cols3, part_rec, part_sp, part_dead, l0, flags, pre32, g_idx, g_val, g_counts, g_counts_w,
          fl_off, fl_cnt, fl_tok, fl_val, fl_seg, total;
   int kcap;
 };
@@ -40,13 +40,13 @@ void set_err(char* dst, const char* fmt, ...) {
 enum KernelId {
   K_NORMS, K_ENC, K_DEC, K_LOSS_SP, K_LOSS_REC, K_LOSS_FINAL, K_COLRED, K_DZ, K_STE, K_DWENC, K_DWDEC,
   K_ADAM_WDEC, K_ADAM_WENC, K_ADAM_VEC, K_ZERO, K_DECIDE, K_COMPACT, K_GATHER, K_SP_FILL, K_GATHER_DZ, K_FLISTS,
-  K_SP_DWDEC, K_COUNT
+  K_SP_DWDEC, K_TOPK, K_COUNT
 };
 static const char* const kKernelNames[K_COUNT] = {
   "decoder_norms", "encoder_jumprelu_gemm", "decode_gemm", "loss_sparsity", "loss_reconstruction", "loss_final",
   "column_reduce", "dz_gemm", "ste_reduce", "dW_enc_gemm", "dW_dec_gemm", "adam_W_dec", "adam_W_enc",
   "adam_vectors", "zero_counters", "decode_decide", "compact_active", "gather_decode", "sparse_dpre_fill",
-  "gather_dz", "feature_lists", "sparse_dW_dec"};
+  "gather_dz", "feature_lists", "sparse_dW_dec", "topk_select"};
 
 struct ProfSpan { int kernel; hipEvent_t a, b; };
 
@@ -100,6 +100,12 @@ int check_config(const clt_config* c, char* err) {
     return CLT_ERR_INVALID_ARG;
   }
   if (c->log_threshold != 0 && c->log_threshold != 1) { set_err(err, "bad log_threshold"); return CLT_ERR_INVALID_ARG; }
+  if (c->activation != CLT_ACT_JUMPRELU && c->activation != CLT_ACT_TOPK) { set_err(err, "bad activation %d", c->activation); return CLT_ERR_INVALID_ARG; }
+  if (c->activation == CLT_ACT_TOPK && (c->topk_k < 0 || c->topk_k > c->F)) {
+    set_err(err, "topk_k must be in [0, F]");
+    return CLT_ERR_INVALID_ARG;
+  }
+  if (c->activation == CLT_ACT_TOPK && c->log_threshold) { set_err(err, "log_threshold has no meaning with TopK"); return CLT_ERR_INVALID_ARG; }
   if (c->decode_mode == CLT_DECODE_AUTO && !(c->gather_density_threshold >= 0.f && c->gather_density_threshold <= 1.f)) {
     set_err(err, "gather_density_threshold must be in [0, 1]");
     return CLT_ERR_INVALID_ARG;
@@ -131,6 +137,7 @@ Plan make_plan(const clt_config* c) {
   p.part_dead = o;  o += align_up(rbs * L * 8);
   p.l0 = o;         o += align_up(L * 4);
   p.flags = o;      o += align_up(4 * 4);
+  p.pre32 = o;      o += align_up(c->activation == CLT_ACT_TOPK ? L * B * F * 4 : 0);   // fp32 pre-activations for the selection
   // active-feature lists of the gather decode: forced gather must hold a fully dense row;
   // the automatic switch only ever gathers below the threshold, so rows are capped at a
   // multiple of it and a step with a longer row falls back to the dense decode
@@ -343,8 +350,10 @@ int clt_forward(clt_handle* h, void* stream, const void* x, const float* x_scale
   int32_t* flags = reinterpret_cast<int32_t*>(h->ws + h->plan.flags);
   RUN(h, s, K_ZERO, launch_zero_i32(s, l0, h->D.L));
   RUN(h, s, K_NORMS, launch_decoder_norms(s, h->bf16, h->D, W_dec, norms));
+  const bool topk = h->cfg.activation == CLT_ACT_TOPK;
+  float* pre32 = topk ? reinterpret_cast<float*>(h->ws + h->plan.pre32) : nullptr;
   EncArgs ea{x, x_scale, W_enc, b_enc, theta, h->cfg.ste_bandwidth, z, pre, act_class, l0,
-             h->cfg.log_threshold != 0};
+             h->cfg.log_threshold != 0, pre32};
   const int mode = h->cfg.decode_mode;
   DecArgs da{z, W_dec, b_dec, y_hat, mode == CLT_DECODE_AUTO ? flags : nullptr, h->plan.kcap};
   GatherLists gl{reinterpret_cast<int32_t*>(h->ws + h->plan.g_idx), reinterpret_cast<float*>(h->ws + h->plan.g_val),
@@ -355,6 +364,7 @@ int clt_forward(clt_handle* h, void* stream, const void* x, const float* x_scale
   } else {
     RUN(h, s, K_ENC, launch_enc_f32(s, h->D, ea));
   }
+  if (topk) RUN(h, s, K_TOPK, launch_topk_select(s, h->bf16, h->D, pre32, h->cfg.topk_k, z, act_class, l0));
   if (mode != CLT_DECODE_DENSE) {   // Sec. 3.2: density monitor, then the gather path where it pays
     RUN(h, s, K_DECIDE, launch_decode_decide(s, h->D, l0, h->cfg.gather_density_threshold, mode == CLT_DECODE_GATHER,
                                              flags));
@@ -378,6 +388,10 @@ int clt_loss(clt_handle* h, void* stream, const void* y, const float* y_scale, c
   if (!(lambda0 >= 0.f)) { set_err(h->err, "clt_loss: lambda0 must be >= 0"); return CLT_ERR_INVALID_ARG; }
   if (!(lambda1 >= 0.f)) { set_err(h->err, "clt_loss: lambda1 must be >= 0"); return CLT_ERR_INVALID_ARG; }
   const bool dead = lambda1 > 0.f;
+  if (dead && h->cfg.activation == CLT_ACT_TOPK) {
+    set_err(h->err, "clt_loss: the dead-feature term (lambda1 > 0) needs a threshold; activation is TopK");
+    return CLT_ERR_INVALID_ARG;
+  }
   if (dead) { REQ(h, pre); REQ(h, theta); }
   if (h->stage < 1) { set_err(h->err, "clt_loss: call clt_forward first (decoder norms missing)"); return CLT_ERR_STATE; }
   hipStream_t s = static_cast<hipStream_t>(stream);
@@ -459,8 +473,11 @@ static int backward_impl(clt_handle* h, hipStream_t s, const void* x, const floa
   }
   RUN(h, s, K_STE, launch_ste_reduce(s, h->bf16, D, dpre, act_class, h->int8 ? x_scale : nullptr, norms, lam1_over_b,
                                      part, part2, part3));
-  RUN(h, s, K_COLRED, launch_dtheta_final(s, part, part3, rbs, D.L * D.F, theta, h->cfg.log_threshold != 0, norms,
-                                          1.0f / h->cfg.ste_bandwidth, lam1_over_b, gtheta));
+  if (h->cfg.activation == CLT_ACT_TOPK)     // no threshold: the window partials are all zero, and so is the gradient
+    RUN(h, s, K_COLRED, launch_col_reduce(s, part, rbs, D.L * D.F, 1.0f, nullptr, 0.f, gtheta));
+  else
+    RUN(h, s, K_COLRED, launch_dtheta_final(s, part, part3, rbs, D.L * D.F, theta, h->cfg.log_threshold != 0, norms,
+                                            1.0f / h->cfg.ste_bandwidth, lam1_over_b, gtheta));
   RUN(h, s, K_COLRED, launch_col_reduce(s, part2, rbs, D.L * D.F, 1.0f, nullptr, 0.f, gb_enc));
   if (h->bf16) RUN(h, s, K_DWENC, launch_dwenc_bf16(s, D, ea, h->int8));
   else RUN(h, s, K_DWENC, launch_dwenc_f32(s, D, ea));

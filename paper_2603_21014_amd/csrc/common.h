@@ -114,6 +114,7 @@ struct EncArgs {       // pre = x W_enc + b_enc; JumpReLU; classes; L0 counts
   const void* x; const float* x_scale; const void* W_enc; const float* b_enc; const float* theta;
   float ste_eps; void* z; void* pre; uint8_t* cls; int32_t* l0;
   bool log_threshold;     // theta holds tau = log(theta)
+  float* pre32 = nullptr; // TopK activation: store only the fp32 pre-activation (activation applied by launch_topk_select)
 };
 struct DecArgs {       // y_hat[lp] = sum_{l<=lp} z[l] W_dec[p(l,lp)] + b_dec[lp]
   const void* z; const void* W_dec; const float* b_dec; float* y_hat;
@@ -158,6 +159,10 @@ constexpr int LOSS_ROWS_PER_BLOCK = 32;   // token rows per block of the row-blo
 inline int row_blocks(int B) { return (B + LOSS_ROWS_PER_BLOCK - 1) / LOSS_ROWS_PER_BLOCK; }
 
 hipError_t launch_zero_i32(hipStream_t s, int32_t* p, int n);
+// TopK activation (Sec. 3.2): per (layer, token) row of pre32 [L,B,F] the k largest entries (lower index wins
+// ties) -> z = pre there, 0 elsewhere; class byte CLS_ACTIVE or 0; l0[l] += k per row
+hipError_t launch_topk_select(hipStream_t s, bool bf16, Dims D, const float* pre32, int k, void* z, uint8_t* cls,
+                              int32_t* l0);
 hipError_t launch_decoder_norms(hipStream_t s, bool bf16, Dims D, const void* W_dec, float* norms);
 // L_rec partials, d_yhat = 2 r / B, column partials for db_dec
 hipError_t launch_loss_rec(hipStream_t s, bool bf16, bool int8_y, Dims D, const float* y_hat, const void* y,

@@ -132,6 +132,7 @@ struct EncPolicy {
   const TA* x; const T* W_enc; const float* b_enc; const float* theta; const float* x_scale;
   float half_eps; T* z; T* pre; uint8_t* cls; int32_t* l0;
   bool log_threshold;
+  float* pre32;   // TopK activation: the epilogue only stores the fp32 pre-activation here (and pre); no z, classes, L0
   __device__ bool skip() const { return false; }
   struct GInfo { int l; };
   struct Epi { int count; float4 b, th; };
@@ -147,7 +148,7 @@ struct EncPolicy {
     if (ok) {
       const size_t vo = (size_t)g.l * D.F + col;
       e.b = *reinterpret_cast<const float4*>(b_enc + vo);
-      e.th = *reinterpret_cast<const float4*>(theta + vo);
+      if (!pre32) e.th = *reinterpret_cast<const float4*>(theta + vo);
       if (log_threshold) e.th = make_float4(expf(e.th.x), expf(e.th.y), expf(e.th.z), expf(e.th.w));
     }
   }
@@ -161,6 +162,13 @@ struct EncPolicy {
       v.x *= s; v.y *= s; v.z *= s; v.w *= s;
     }
     float p[4] = {v.x + b.x, v.y + b.y, v.z + b.z, v.w + b.w};
+    if (pre32) {
+      const size_t uo = pos.uoff((size_t)g.l * D.B, D.F);
+      const uint32_t lo = pos.loff(D.F);
+      *reinterpret_cast<float4*>(epi_ptr(pre32, uo, lo)) = make_float4(p[0], p[1], p[2], p[3]);
+      if (pre) Elem<T>::store4(epi_ptr(pre, uo, lo), make_float4(p[0], p[1], p[2], p[3]));
+      return;
+    }
     const float t[4] = {th.x, th.y, th.z, th.w};
     float zz[4];
     uint32_t c4 = 0;

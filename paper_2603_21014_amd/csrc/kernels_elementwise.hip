@@ -296,6 +296,159 @@ __global__ __launch_bounds__(256) void adam_kernel(size_t n4, T* __restrict__ p,
   }
 }
 
+// ---- TopK activation: the k largest of a row's F fp32 pre-activations ----------------
+// One workgroup per (layer, token) row.  A radix select over the order-preserving integer image
+// of the floats finds the k-th largest value in four 8-bit passes (LDS histograms); a last pass
+// writes z and the class bytes.  Entries equal to the k-th value are taken in index order until
+// k entries are selected; that ordered count runs only for rows that have such ties to break.
+__device__ __forceinline__ uint32_t order_key(float x) {
+  const uint32_t u = __float_as_uint(x);
+  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);     // larger float <=> larger key (NaN sorts by its bits)
+}
+
+// NV4 > 0: the row (F <= 1024 * NV4) is held in registers, NV4 float4 per lane, and read from memory once;
+// NV4 = 0: any F, every pass re-reads the row (it stays in the L2).
+template <typename T, int NV4>
+__global__ __launch_bounds__(256) void topk_select_kernel(Dims D, const float* __restrict__ pre32, int k,
+                                                          T* __restrict__ z, uint8_t* __restrict__ cls,
+                                                          int32_t* __restrict__ l0) {
+  __shared__ int hist[256];
+  __shared__ int sh_bin, sh_rem, scan[256], wtot[4];
+  const int tid = threadIdx.x;
+  const size_t row = blockIdx.x;
+  const float* pr = pre32 + row * D.F;
+  const int F4 = D.F / 4;
+  const int rounds = NV4 > 0 ? NV4 : (F4 + 255) / 256;
+  float4 held[NV4 > 0 ? NV4 : 1];
+  if (NV4 > 0) {
+#pragma unroll
+    for (int j = 0; j < NV4; ++j) {
+      const int q = tid + 256 * j;
+      // padding sorts below every float (no float maps to key 0), so it is never selected
+      held[j] = q < F4 ? *reinterpret_cast<const float4*>(pr + 4 * q) : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+  }
+  auto value4 = [&](int j) -> float4 {        // the lane's j-th float4 (index 4 * (tid + 256 j)); in range only
+    if (NV4 > 0) return held[j];
+    return *reinterpret_cast<const float4*>(pr + 4 * (tid + 256 * j));
+  };
+  auto key4 = [&](int j, uint32_t (&key)[4]) {
+    const int q = tid + 256 * j;
+    if (q < F4) {
+      const float4 v = value4(j);
+      key[0] = order_key(v.x); key[1] = order_key(v.y); key[2] = order_key(v.z); key[3] = order_key(v.w);
+    } else {
+      key[0] = key[1] = key[2] = key[3] = 0u;
+    }
+  };
+
+  uint32_t prefix = 0;
+  int remaining = k;            // entries still to take among those whose key matches the prefix so far
+  if (k > 0 && k < D.F) {
+    for (int shift = 24; shift >= 0; shift -= 8) {
+      hist[tid] = 0;
+      __syncthreads();
+      const uint32_t himask = shift == 24 ? 0u : (0xffffffffu << (shift + 8));
+#pragma unroll NV4 > 0 ? NV4 : 1
+      for (int j = 0; j < rounds; ++j) {
+        uint32_t key[4];
+        key4(j, key);
+        if (tid + 256 * j < F4) {
+#pragma unroll
+          for (int i = 0; i < 4; ++i)
+            if ((key[i] & himask) == prefix) atomicAdd(&hist[(key[i] >> shift) & 255u], 1);
+        }
+      }
+      __syncthreads();
+      // the bin that holds the `remaining`-th largest entry: suffix sums over the 256 bins (lane = bin),
+      // wave scans plus the totals of the higher waves
+      {
+        const int h = hist[tid], lane = tid & 63, wv = tid >> 6;
+        int sfx = h;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+          const int u = __shfl_down(sfx, off, 64);
+          if (lane + off < 64) sfx += u;
+        }
+        if (lane == 0) wtot[wv] = sfx;
+        __syncthreads();
+        for (int w2 = wv + 1; w2 < 4; ++w2) sfx += wtot[w2];
+        const int above = sfx - h;                  // entries in higher bins
+        if (above < remaining && remaining <= sfx) { sh_bin = tid; sh_rem = remaining - above; }
+      }
+      __syncthreads();
+      prefix |= (uint32_t)sh_bin << shift;
+      remaining = sh_rem;
+      __syncthreads();
+    }
+  }
+  // prefix = key of the k-th largest value; `remaining` of the entries equal to it are selected
+  const bool all = k >= D.F, none = k <= 0;
+  int eq_total = 0;
+  if (!all && !none) {
+    int c = 0;
+#pragma unroll NV4 > 0 ? NV4 : 1
+    for (int j = 0; j < rounds; ++j) {
+      uint32_t key[4];
+      key4(j, key);
+      if (tid + 256 * j < F4) c += (key[0] == prefix) + (key[1] == prefix) + (key[2] == prefix) + (key[3] == prefix);
+    }
+    scan[tid] = c;
+    __syncthreads();
+    for (int off = 128; off > 0; off >>= 1) {
+      if (tid < off) scan[tid] += scan[tid + off];
+      __syncthreads();
+    }
+    eq_total = scan[0];
+    __syncthreads();
+  }
+  const bool ties = !all && !none && eq_total > remaining;     // uniform over the workgroup
+  int taken_before = 0;                                         // equal entries in earlier float4 rounds
+#pragma unroll NV4 > 0 ? NV4 : 1
+  for (int j = 0; j < rounds; ++j) {
+    const int q = tid + 256 * j;
+    const bool in = q < F4;
+    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (in) v = value4(j);
+    const float vv[4] = {v.x, v.y, v.z, v.w};
+    uint32_t key[4];
+    key4(j, key);
+    int rank0 = 0;                                              // equal entries before this lane's first one
+    if (ties) {
+      const int c = in ? (key[0] == prefix) + (key[1] == prefix) + (key[2] == prefix) + (key[3] == prefix) : 0;
+      scan[tid] = c;
+      __syncthreads();
+      for (int off = 1; off < 256; off <<= 1) {                 // inclusive scan over the 256 lanes
+        const int u = tid >= off ? scan[tid - off] : 0;
+        __syncthreads();
+        scan[tid] += u;
+        __syncthreads();
+      }
+      rank0 = taken_before + scan[tid] - c;
+      taken_before += scan[255];
+      __syncthreads();
+    }
+    if (in) {
+      float zz[4];
+      uint32_t c4 = 0;
+      int r = rank0;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        bool sel = all || (!none && key[i] > prefix);
+        if (!all && !none && key[i] == prefix) {
+          sel = !ties || r < remaining;
+          ++r;
+        }
+        zz[i] = sel ? vv[i] : 0.f;
+        c4 |= (sel ? (uint32_t)CLS_ACTIVE : 0u) << (8 * i);
+      }
+      Elem<T>::store4(z + row * D.F + 4 * q, make_float4(zz[0], zz[1], zz[2], zz[3]));
+      *reinterpret_cast<uint32_t*>(cls + row * D.F + 4 * q) = c4;
+    }
+  }
+  if (tid == 0 && l0) atomicAdd(l0 + (int)(row / D.B), all ? D.F : (none ? 0 : k));
+}
+
 inline int grid_for(size_t n, int per_block, int cap) {
   size_t b = (n + per_block - 1) / per_block;
   if (b < 1) b = 1;
@@ -307,6 +460,18 @@ inline int grid_for(size_t n, int per_block, int cap) {
 
 hipError_t launch_zero_i32(hipStream_t s, int32_t* p, int n) {
   hipLaunchKernelGGL(zero_i32_kernel, dim3((n + 255) / 256), dim3(256), 0, s, p, n);
+  return hipGetLastError();
+}
+
+hipError_t launch_topk_select(hipStream_t s, bool bf16, Dims D, const float* pre32, int k, void* z, uint8_t* cls,
+                              int32_t* l0) {
+  const dim3 grid((unsigned)((size_t)D.L * D.B));
+#define CLT_TOPK(T, NV4) \
+  hipLaunchKernelGGL((topk_select_kernel<T, NV4>), grid, dim3(256), 0, s, D, pre32, k, (T*)z, cls, l0)
+  const int nv4 = D.F <= 2048 ? 2 : (D.F <= 8192 ? 8 : 0);     // registers for rows up to 8192 features
+  if (bf16) { if (nv4 == 2) CLT_TOPK(bf16_t, 2); else if (nv4 == 8) CLT_TOPK(bf16_t, 8); else CLT_TOPK(bf16_t, 0); }
+  else { if (nv4 == 2) CLT_TOPK(float, 2); else if (nv4 == 8) CLT_TOPK(float, 8); else CLT_TOPK(float, 0); }
+#undef CLT_TOPK
   return hipGetLastError();
 }
 

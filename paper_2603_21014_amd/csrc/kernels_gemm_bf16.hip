@@ -372,12 +372,12 @@ hipError_t launch_enc_bf16(hipStream_t s, Dims D, const EncArgs& a, bool int8_x)
   if (int8_x) {
     EncPolicy<bf16_t, int8_t> p{D, D.B, D.F, D.d, D.d, D.F,
                                 (const int8_t*)a.x, (const bf16_t*)a.W_enc, a.b_enc, a.theta, a.x_scale,
-                                0.5f * a.ste_eps, (bf16_t*)a.z, (bf16_t*)a.pre, a.cls, a.l0, a.log_threshold};
+                                0.5f * a.ste_eps, (bf16_t*)a.z, (bf16_t*)a.pre, a.cls, a.l0, a.log_threshold, a.pre32};
     return launch(s, p, D.L);
   }
   EncPolicy<bf16_t> p{D, D.B, D.F, D.d, D.d, D.F,
                       (const bf16_t*)a.x, (const bf16_t*)a.W_enc, a.b_enc, a.theta, nullptr,
-                      0.5f * a.ste_eps, (bf16_t*)a.z, (bf16_t*)a.pre, a.cls, a.l0, a.log_threshold};
+                      0.5f * a.ste_eps, (bf16_t*)a.z, (bf16_t*)a.pre, a.cls, a.l0, a.log_threshold, a.pre32};
   return launch(s, p, D.L);
 }
 hipError_t launch_dec_bf16(hipStream_t s, Dims D, const DecArgs& a) {

@@ -94,7 +94,7 @@ hipError_t launch(hipStream_t s, const P& p, int G) {
 hipError_t launch_enc_f32(hipStream_t s, Dims D, const EncArgs& a) {
   EncPolicy<float> p{D, D.B, D.F, D.d, D.d, D.F,
                      (const float*)a.x, (const float*)a.W_enc, a.b_enc, a.theta, nullptr,
-                     0.5f * a.ste_eps, (float*)a.z, (float*)a.pre, a.cls, a.l0, a.log_threshold};
+                     0.5f * a.ste_eps, (float*)a.z, (float*)a.pre, a.cls, a.l0, a.log_threshold, a.pre32};
   return launch(s, p, D.L);
 }
 hipError_t launch_dec_f32(hipStream_t s, Dims D, const DecArgs& a) {

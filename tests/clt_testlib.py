@@ -43,7 +43,7 @@ class GpuRun:
         step = K.CLTStep(w.L, w.d, w.F, w.B, dtype=w.dtype, int8_inputs=w.int8_inputs,
                          master_weights=w.master_weights, C_=w.C, ste_bandwidth=w.ste_eps, device=dev,
                          decode_mode=decode_mode, gather_density_threshold=gather_density_threshold,
-                         log_threshold=w.log_threshold)
+                         log_threshold=w.log_threshold, topk=w.topk or None)
         xg, yg = x.to(dev, TX).contiguous(), y.to(dev, TX).contiguous()
         xs = x_scale.to(dev) if x_scale is not None else None
         ys = y_scale.to(dev) if y_scale is not None else None
@@ -90,14 +90,15 @@ class OracleRun:
         self.x_np, self.y_np = xn, yn
         self.theta = O.threshold_value(npar["theta"], w.log_threshold)
         self.fwd = O.forward(xn, npar["W_enc"], npar["b_enc"], self.theta, npar["W_dec"], npar["b_dec"],
-                             tie_break=gpu_active, band=MASK_BAND)
+                             tie_break=gpu_active, band=MASK_BAND, topk=w.topk or None)
         self.n = O.decoder_norms(npar["W_dec"], w.L)
         tot, rec, sp = O.loss_terms(self.fwd["y_hat"], yn, self.fwd["z"], self.n, w.lambda0, w.C)
         dead = O.dead_feature_term(self.fwd["pre"], self.theta, self.n, w.lambda1)
         self.loss = (tot + dead, rec, sp, dead)
         self.bwd = O.backward(xn, yn, self.theta, npar["W_dec"], self.fwd, w.lambda0, w.C, w.ste_eps,
-                              window_tie_break=gpu_window, band=MASK_BAND, lambda1=w.lambda1,
-                              log_threshold=w.log_threshold, below_tie_break=gpu_below)
+                              window_tie_break=None if w.topk else gpu_window, band=MASK_BAND, lambda1=w.lambda1,
+                              log_threshold=w.log_threshold, below_tie_break=None if w.topk else gpu_below,
+                              topk=bool(w.topk))
         zeros = {k: np.zeros_like(a) for k, a in npar.items()}
         m = zeros if m is None else {k: to_np(a) for k, a in m.items()}
         v = zeros if v is None else {k: to_np(a) for k, a in v.items()}
@@ -114,12 +115,19 @@ def compare_step(w, g: GpuRun, o: OracleRun, tol, check_adam=True):
     theta = o.theta
     pre_o = o.fwd["pre"]
     errs = {}
+    if w.topk:
+        # the oracle has verified the selection against its own ranking outside the band around each row's
+        # k-th value and that every row holds exactly k entries; there is no threshold, window or gradient of it
+        assert (g.active == o.fwd["active"]).all() and (g.active.sum(axis=2) == w.topk).all()
+        assert not g.window.any() and not g.below.any() and not g.grads["theta"].any()
+        theta = np.full(theta.shape, np.inf)             # keeps the threshold-based checks below trivially true
+        assert not o.bwd["window"].any()
     # masks: identical except inside the band around the boundary
     band = np.abs(pre_o - theta[:, None, :]) < MASK_BAND
-    assert ((g.active == o.fwd["active"]) | band).all(), "active mask differs outside the band"
+    assert ((g.active == o.fwd["active"]) | band | bool(w.topk)).all(), "active mask differs outside the band"
     wband = np.abs(np.abs(pre_o - theta[:, None, :]) - 0.5 * w.ste_eps) < MASK_BAND
     assert ((g.window == o.bwd["window"]) | wband).all(), "window mask differs outside the band"
-    assert ((g.below == (pre_o < theta[:, None, :])) | band).all(), "below-threshold mask differs outside the band"
+    assert ((g.below == (pre_o < theta[:, None, :])) | band | bool(w.topk)).all(), "below-threshold mask differs outside the band"
     assert not (g.below & g.active).any()
     assert (g.l0 == g.active.sum(axis=(1, 2))).all(), "l0_per_layer does not count the active mask"
     errs["pre"] = rel_l2(g.pre, pre_o)
@@ -142,6 +150,8 @@ def compare_step(w, g: GpuRun, o: OracleRun, tol, check_adam=True):
     if not w.int8_inputs:      # with int8 inputs the buffer holds dpre times the row scale of x
         errs["dpre"] = rel_l2(g.dpre, o.bwd["dpre"])
     for k in ("W_enc", "b_enc", "theta", "b_dec"):
+        if k == "theta" and w.topk:
+            continue                                     # exactly zero on both sides (asserted above)
         errs["d" + k] = rel_l2(g.grads[k], o.bwd["d" + k])
     for p in range(O.num_blocks(L)):
         errs[f"dW_dec[{p}]"] = rel_l2(g.grads["W_dec"][p], o.bwd["dW_dec"][p])

@@ -224,6 +224,68 @@ def test_dead_term_needs_pre_and_theta():
     torch.cuda.synchronize()
 
 
+# ---------------------------------------------------------------- TopK activation
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("L,d,F,B,k", [(3, 40, 72, 77, 5), (2, 264, 520, 300, 33), (2, 64, 1032, 40, 1)])
+def test_topk_activation_full_step(dtype, L, d, F, B, k):
+    """TopK instead of JumpReLU: exactly k features per token and layer, selected on the fp32 pre-activation."""
+    w = S.scaled(S.WORKLOADS["tiny"], dtype=dtype, L=L, d=d, F=F, B=B, seed=91 + F, topk=k)
+    for fused in (False, True):
+        g, o = run_both(w, fused=fused)
+        assert (g.l0 == k * B).all()
+        show(f"topk {dtype} F{F} k{k} fused={fused}", compare_step(w, g, o, TOL[dtype]))
+
+
+def test_topk_limits_and_ties():
+    """k = 0 (nothing), k = F (everything, the linear model) and a zero input row, whose pre-activations are all
+    equal to the bias: the first k features by index are selected."""
+    w = S.scaled(S.WORKLOADS["tiny"], L=2, d=64, F=128, B=32, topk=7)
+    params = S.make_params(w)
+    x, y = S.make_inputs(w)
+    x[:, 3, :] = 0.0
+    g = GpuRun(w, params, x, y)
+    o = OracleRun(w, params, x, y, gpu_active=g.active)
+    assert (g.active[:, 3, :7]).all() and not g.active[:, 3, 7:].any()
+    show("topk tie row", compare_step(w, g, o, TOL["f32"]))
+    for k, frac in ((0, 0.0), (w.F, 1.0)):
+        wk = S.scaled(w, topk=k)
+        if k == 0:       # topk = 0 means JumpReLU to the workload helper: drive the library directly
+            from paper_2603_21014_amd import binding as K
+            step = K.CLTStep(w.L, w.d, w.F, w.B, dtype="f32", topk=0)
+            gp = {kk: p.cuda() for kk, p in params.items()}
+            step.forward(x.cuda(), gp)
+            torch.cuda.synchronize()
+            assert not step.z.any() and not step.act_class.any() and not step.l0.any()
+            assert (step.y_hat.cpu() == params["b_dec"][:, None, :]).all()
+        else:
+            g = GpuRun(wk, params, x, y)
+            assert g.active.all() and rel_l2(g.z, g.pre) == 0.0
+            o = OracleRun(wk, params, x, y, gpu_active=g.active)
+            show("topk k=F", compare_step(wk, g, o, TOL["f32"]))
+
+
+def test_topk_with_gather_decode_and_sparse_backward():
+    w = S.scaled(S.WORKLOADS["tiny"], dtype="bf16", L=3, d=128, F=512, B=130, seed=93, topk=12)
+    g, o = run_both(w, decode_mode=2, fused=True)
+    assert g.decode_switch[2] == 2
+    show("topk + gather", compare_step(w, g, o, TOL["bf16"]))
+
+
+def test_topk_refuses_dead_feature_term():
+    from paper_2603_21014_amd import binding as K
+    w = S.scaled(S.WORKLOADS["tiny"], L=2, d=64, F=128, B=32)
+    step = K.CLTStep(w.L, w.d, w.F, w.B, dtype="f32", topk=4)
+    params = {k: p.cuda() for k, p in S.make_params(w).items()}
+    x, y = (t.cuda() for t in S.make_inputs(w))
+    step.forward(x, params)
+    with pytest.raises(K.CLTError) as e:
+        step.loss(y, 1.0, lambda1=0.5, params=params)
+    assert e.value.code == -1
+    with pytest.raises(K.CLTError):
+        K.clt_workspace_bytes(K.make_config(2, 64, 128, 32, topk=129))
+    torch.cuda.synchronize()
+
+
 # ---------------------------------------------------------------- gather decode and the switch
 DENSE, GATHER, AUTO = 1, 2, 0
 

@@ -52,6 +52,7 @@ class CLTWorkload:
     master_weights: bool = False
     lambda1: float = 0.0          # dead-feature coefficient of the App. B objective (0 = term off)
     log_threshold: bool = False   # the theta tensor stores tau = log(theta)
+    topk: int = 0                 # > 0: TopK activation with this k instead of JumpReLU (theta unused)
 
     @property
     def P(self) -> int:
@@ -71,6 +72,7 @@ WORKLOADS = {
                            master_weights=True),
     "llama1b_dead": CLTWorkload("llama1b_dead", 16, 2048, 8192, 4096, "bf16", 64, True, 12.0, 1003,
                                 lambda1=0.1, log_threshold=True),
+    "llama1b_topk": CLTWorkload("llama1b_topk", 16, 2048, 8192, 4096, "bf16", 64, True, 0.0, 1003, topk=64),
     "llama1b_int8": CLTWorkload("llama1b_int8", 16, 2048, 8192, 4096, "bf16", 64, True, 12.0,
                                 1005, int8_inputs=True),
 }
