@@ -14,6 +14,7 @@ from clt_testlib import GpuRun, OracleRun, compare_step, rel_l2, run_both, to_np
 pytestmark = pytest.mark.gpu
 
 TOL = {"f32": 1e-4, "bf16": 2e-2}
+DENSE, GATHER, AUTO = 1, 2, 0
 
 
 def show(name, errs):
@@ -286,8 +287,46 @@ def test_topk_refuses_dead_feature_term():
     torch.cuda.synchronize()
 
 
+# ---------------------------------------------------------------- seeded sweep over shapes and modes
+def _sweep_cases():
+    rng = np.random.default_rng(2024)
+    cases = []
+    for i in range(16):
+        L = int(rng.integers(1, 6))
+        d = 8 * int(rng.integers(1, 70))          # 8 .. 552: below, at and above one 256-wide tile
+        F = 8 * int(rng.integers(1, 80))
+        B = int(rng.integers(1, 330))
+        cases.append((i, L, d, F, B))
+    return cases
+
+
+@pytest.mark.parametrize("i,L,d,F,B", _sweep_cases())
+def test_seeded_shape_and_mode_sweep(i, L, d, F, B):
+    """Random shapes (every dimension ragged against every tile size) crossed with the options: storage type,
+    fused update, master weights, int8 inputs, dead-feature term / log threshold, TopK, list-driven kernels."""
+    rng = np.random.default_rng(100 + i)
+    dtype = "bf16" if rng.random() < 0.6 else "f32"
+    int8 = dtype == "bf16" and rng.random() < 0.3
+    topk = int(rng.integers(1, F + 1)) if rng.random() < 0.25 else 0
+    dead = (not topk) and rng.random() < 0.4
+    base = S.WORKLOADS["llama1b_int8"] if int8 else S.WORKLOADS["tiny"]
+    w = S.scaled(base, dtype=dtype, L=L, d=d, F=F, B=B, seed=500 + i, k_active=max(1, F // 16),
+                 master_weights=dtype == "bf16" and rng.random() < 0.4, topk=topk,
+                 lambda1=2.0 if dead else 0.0, log_threshold=dead and rng.random() < 0.5)
+    mode = [DENSE, GATHER, AUTO][int(rng.integers(0, 3))]
+    fused = bool(rng.random() < 0.5)
+    theta = None
+    if mode != DENSE and not topk and rng.random() < 0.7:        # a sparse regime for the list-driven kernels
+        theta = sparse_theta(w, 0.05)
+        if w.log_threshold:
+            theta = torch.log(theta.clamp_min(1e-3))
+    g, o = run_both(w, theta=theta, decode_mode=mode, fused=fused, gather_density_threshold=0.1)
+    show(f"sweep {i}: L{L} d{d} F{F} B{B} {dtype} int8={int8} topk={topk} dead={dead} log={w.log_threshold} "
+         f"master={w.master_weights} mode={mode} fused={fused} path={g.decode_switch[2]}",
+         compare_step(w, g, o, TOL[dtype]))
+
+
 # ---------------------------------------------------------------- gather decode and the switch
-DENSE, GATHER, AUTO = 1, 2, 0
 
 
 def sparse_theta(w, rho):
