@@ -182,7 +182,8 @@ int clt_backward_adam_step(clt_handle* handle, void* stream,
  * which = 0 decoder norms [L,F] float; 1 d y_hat [L,B,d] T; 2 d pre [L,B,F] T;
  * 3 sparsity column sums G [L,F] float; 4 decode switch, 4 int32: {gather allowed by
  * the measured density, longest active list, path taken by the last forward
- * (1 dense, 2 gather), unused}.  Valid after the call that writes them. */
+ * (1 dense, 2 gather), unused}; written by clt_forward in the gather and auto decode modes only.
+ * Valid after the call that writes them. */
 int clt_workspace_view(const clt_handle* handle, int which, void** ptr, size_t* bytes);
 
 /* Optional per-kernel timing, for benchmarks and profiling (not part of the
