@@ -121,6 +121,42 @@ def test_adam_later_step_with_given_moments(dtype):
         assert rel_l2(got - o.params[k], o.new_params[k] - o.params[k]) <= tol, k
 
 
+def test_five_training_steps_follow_the_oracle_trajectory():
+    """Five consecutive fused steps on the fp32 config, parameters and moments carried on the device, against
+    five oracle steps: the loss falls and follows the oracle's, the parameters stay within a fraction of the
+    distance they travelled (Adam's early steps move every weight by about lr whatever the gradient's size, so a
+    gradient near zero may take the other sign; that bounds the per-entry difference by 2 lr per step)."""
+    from paper_2603_21014_amd import binding as K
+    w = S.scaled(S.WORKLOADS["tiny"], L=3, d=64, F=128, B=96, seed=61)
+    params = S.make_params(w)
+    x, y = S.make_inputs(w)
+    dev = "cuda:0"
+    gp = {k: p.to(dev).contiguous() for k, p in params.items()}
+    gm = {k: torch.zeros_like(p) for k, p in gp.items()}
+    gv = {k: torch.zeros_like(p) for k, p in gp.items()}
+    step = K.CLTStep(w.L, w.d, w.F, w.B, dtype="f32", C_=w.C, ste_bandwidth=w.ste_eps, matrix_grads=False)
+    op = {k: to_np(p) for k, p in params.items()}
+    om = {k: np.zeros_like(v) for k, v in op.items()}
+    ov = {k: np.zeros_like(v) for k, v in op.items()}
+    xg, yg = x.to(dev), y.to(dev)
+    xn, yn = to_np(x), to_np(y)
+    g_losses, o_losses = [], []
+    for t in range(1, 6):
+        step.train_step(xg, yg, gp, gm, gv, t, w.lr, w.lambda0)
+        g_losses.append(step.loss_dev.cpu().numpy()[0])
+        op, om, ov, info = O.train_step(xn, yn, op, om, ov, t, w.lr, w.lambda0, w.C, w.ste_eps)
+        o_losses.append(info["loss"][0])
+    print("losses gpu", g_losses, "oracle", o_losses, flush=True)
+    assert all(b < a for a, b in zip(g_losses, g_losses[1:])), "the loss must fall on this problem"
+    for a, b in zip(g_losses, o_losses):
+        assert abs(a - b) <= 1e-3 * abs(b)
+    for k in O.PARAM_NAMES:
+        travelled = np.abs(op[k] - to_np(params[k]))
+        diff = np.abs(to_np(gp[k]) - op[k])
+        assert diff.max() <= 2 * 5 * w.lr * 1.001, k
+        assert np.linalg.norm(diff) <= 0.05 * np.linalg.norm(travelled), k
+
+
 # ---------------------------------------------------------------- backward + Adam in one call
 @pytest.mark.parametrize("dtype,master", [("f32", False), ("bf16", False), ("bf16", True)])
 @pytest.mark.parametrize("L,d,F,B", [(3, 40, 72, 77), (2, 264, 520, 300)])
