@@ -38,10 +38,10 @@ Storage conventions (they only transpose the paper's matrices):
                      target l' >= l; source-major packing, see packed_index
   b_dec  [L, d]
 
-Readings taken where the paper is silent are listed in the repository's design
-document; the ones that matter here: the loss sums over layers, model dims and
-features and takes the mean over the B tokens; the decoder norm is
-differentiated; dn/dW uses max(n, 1e-30) so an all-zero decoder row gives 0.
+Readings taken where the paper is silent: the loss sums over layers, model dims
+and features and takes the mean over the B tokens; the decoder norm is
+differentiated; dn/dW uses max(n, 1e-30) so an all-zero decoder row gives 0; the
+dead-feature term has its true derivatives (no straight-through), ReLU'(0) = 0.
 
 Parity pins (tests/test_oracle_*.py): brute-force Python loops, closed forms,
 special cases that reduce to torch.nn.functional.linear / torch.optim.Adam,

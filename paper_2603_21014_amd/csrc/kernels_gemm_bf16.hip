@@ -229,7 +229,9 @@ __device__ __forceinline__ void main_loop(const P& p, const typename P::GInfo& g
   // same number of barriers.  Group A (waves 0-3) writes its half of tile k
   // right before computing it; group B (waves 4-7) writes its half of tile k+1
   // before computing tile k, so a stage is never written while the other group
-  // still reads it (see the interval table in the design notes).
+  // still reads it: interval 2k = {A: memory(k), B: compute(k-1)}, interval 2k+1 =
+  // {A: compute(k), B: memory(k+1)}; stage k&1 is written by A in 2k and by B in 2k-1
+  // and read by both from 2k+1 (A) / 2k+2 (B) on, after a barrier.
   // (the prologue is repeated inside each branch on purpose: every branch then only ever
   // touches its own operand, which keeps the other operand's addressing out of its registers)
   if (loads_a) {

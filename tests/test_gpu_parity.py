@@ -23,7 +23,7 @@ def show(name, errs):
 
 
 def test_tiny_config_fp32_full_step():
-    """BASELINE config 1: L=4, d=64, F=256, B=128, fp32, one fwd+bwd+Adam step."""
+    """The smallest configuration: L=4, d=64, F=256, B=128, fp32 storage, one forward + backward + Adam step."""
     w = S.WORKLOADS["tiny"]
     g, o = run_both(w)
     assert 0.2 < g.active.mean() < 0.8
