@@ -73,6 +73,7 @@ WORKLOADS = {
     "llama1b_dead": CLTWorkload("llama1b_dead", 16, 2048, 8192, 4096, "bf16", 64, True, 12.0, 1003,
                                 lambda1=0.1, log_threshold=True),
     "llama1b_topk": CLTWorkload("llama1b_topk", 16, 2048, 8192, 4096, "bf16", 64, True, 0.0, 1003, topk=64),
+    "llama1b_topk16": CLTWorkload("llama1b_topk16", 16, 2048, 8192, 4096, "bf16", 64, True, 0.0, 1003, topk=16),
     "llama1b_int8": CLTWorkload("llama1b_int8", 16, 2048, 8192, 4096, "bf16", 64, True, 12.0,
                                 1005, int8_inputs=True),
 }
