@@ -504,7 +504,7 @@ __device__ __forceinline__ void sparse_dwdec_rows(const Dims& D, int l, int f, i
 }
 
 template <typename T>
-__global__ __launch_bounds__(256) void sparse_dwdec_kernel(Dims D, FeatureLists fl, const T* __restrict__ d_yhat,
+__global__ __launch_bounds__(256, 5) void sparse_dwdec_kernel(Dims D, FeatureLists fl, const T* __restrict__ d_yhat,
                                                            T* __restrict__ W_dec, const float* __restrict__ G,
                                                            const float* __restrict__ norms, T* __restrict__ dW_dec,
                                                            AdamFuseArgs fuse, const int32_t* __restrict__ flags) {
