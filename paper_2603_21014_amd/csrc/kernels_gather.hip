@@ -100,7 +100,73 @@ __global__ __launch_bounds__(256) void compact_active_kernel(Dims D, const T* __
   }
 }
 
-// Accumulates 8 columns per lane; d is walked in passes of 2048 columns.
+// Address = wave-uniform base + the lane's fixed element offset (one 32-bit register per lane).
+template <typename X>
+__device__ __forceinline__ X* lane_ptr(X* uniform_base, uint32_t lane_elems) {   // base + lane offset, 32-bit lane part
+  typedef typename std::conditional<std::is_const<X>::value, const char, char>::type Byte;
+  return reinterpret_cast<X*>(reinterpret_cast<Byte*>(uniform_base) + lane_elems * (uint32_t)sizeof(X));
+}
+
+// 8 consecutive elements kept as loaded (16 bytes of bf16 or 32 bytes of fp32) until they are used
+template <typename T> struct Raw8;
+template <> struct Raw8<bf16_t> {
+  typedef uint4 type;
+  static __device__ __forceinline__ type load(const bf16_t* p) { return *reinterpret_cast<const uint4*>(p); }
+  static __device__ __forceinline__ float dot(const type& a, const type& b, float acc) {
+    const uint32_t x[4] = {a.x, a.y, a.z, a.w}, y[4] = {b.x, b.y, b.z, b.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      acc = fmaf(__uint_as_float(x[i] << 16), __uint_as_float(y[i] << 16), acc);
+      acc = fmaf(__uint_as_float(x[i] & 0xffff0000u), __uint_as_float(y[i] & 0xffff0000u), acc);
+    }
+    return acc;
+  }
+  static __device__ __forceinline__ void axpy(float (&acc)[8], float v, const type& a) {
+    const uint32_t x[4] = {a.x, a.y, a.z, a.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      acc[2 * i] = fmaf(v, __uint_as_float(x[i] << 16), acc[2 * i]);
+      acc[2 * i + 1] = fmaf(v, __uint_as_float(x[i] & 0xffff0000u), acc[2 * i + 1]);
+    }
+  }
+};
+template <> struct Raw8<float> {
+  struct type { float4 lo, hi; };
+  static __device__ __forceinline__ type load(const float* p) {
+    return type{*reinterpret_cast<const float4*>(p), *reinterpret_cast<const float4*>(p + 4)};
+  }
+  static __device__ __forceinline__ float dot(const type& a, const type& b, float acc) {
+    acc = fmaf(a.lo.x, b.lo.x, acc); acc = fmaf(a.lo.y, b.lo.y, acc); acc = fmaf(a.lo.z, b.lo.z, acc);
+    acc = fmaf(a.lo.w, b.lo.w, acc); acc = fmaf(a.hi.x, b.hi.x, acc); acc = fmaf(a.hi.y, b.hi.y, acc);
+    acc = fmaf(a.hi.z, b.hi.z, acc); acc = fmaf(a.hi.w, b.hi.w, acc);
+    return acc;
+  }
+  static __device__ __forceinline__ void axpy(float (&acc)[8], float v, const type& a) {
+    acc[0] = fmaf(v, a.lo.x, acc[0]); acc[1] = fmaf(v, a.lo.y, acc[1]); acc[2] = fmaf(v, a.lo.z, acc[2]);
+    acc[3] = fmaf(v, a.lo.w, acc[3]); acc[4] = fmaf(v, a.hi.x, acc[4]); acc[5] = fmaf(v, a.hi.y, acc[5]);
+    acc[6] = fmaf(v, a.hi.z, acc[6]); acc[7] = fmaf(v, a.hi.w, acc[7]);
+  }
+};
+
+// One workgroup per (token, target): 8 columns per lane (d is walked in passes of 2048 columns), the
+// sources l <= l' and their lists in order.  Feature ids and values are wave-uniform, so a decoder row
+// is a scalar base plus the lane's fixed column offset; eight rows (16 bytes per lane each) are in
+// flight for long lists, four for short ones.
+template <typename T, int U>
+__device__ __forceinline__ void gather_rows(float (&acc)[8], const T* __restrict__ Wp, int ld, uint32_t col,
+                                            const int32_t* __restrict__ ii, const float* __restrict__ vv, int j) {
+  typename Raw8<T>::type r[U];
+  float v[U];
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    const int f = __builtin_amdgcn_readfirstlane(ii[j + u]);
+    v[u] = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(vv[j + u])));
+    r[u] = Raw8<T>::load(lane_ptr(Wp + (size_t)f * ld, col));
+  }
+#pragma unroll
+  for (int u = 0; u < U; ++u) Raw8<T>::axpy(acc, v[u], r[u]);
+}
+
 template <typename T>
 __global__ __launch_bounds__(256) void gather_decode_kernel(Dims D, GatherLists g, const T* __restrict__ W_dec,
                                                             const float* __restrict__ b_dec,
@@ -111,53 +177,24 @@ __global__ __launch_bounds__(256) void gather_decode_kernel(Dims D, GatherLists 
   if (blockIdx.x == 0 && threadIdx.x == 0) flags[2] = 2;
   for (int c0 = 0; c0 < D.d; c0 += 2048) {
     const int col = c0 + threadIdx.x * 8;
-    const bool ok = col < D.d;
+    if (col >= D.d) continue;
     float acc[8];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) acc[i] = ok ? b_dec[(size_t)lp * D.d + col + i] : 0.f;
+    for (int i = 0; i < 8; ++i) acc[i] = b_dec[(size_t)lp * D.d + col + i];
     for (int l = 0; l <= lp; ++l) {
       const size_t row = (size_t)l * D.B + b;
       const int cnt = g.counts[row];
       const int32_t* ii = g.idx + row * g.stride;
       const float* vv = g.val + row * g.stride;
-      const T* Wp = W_dec + (size_t)packed_index(l, lp, D.L) * D.F * D.d + col;
+      const T* Wp = W_dec + (size_t)packed_index(l, lp, D.L) * D.F * D.d;
       int j = 0;
-      for (; j + 4 <= cnt; j += 4) {          // four rows in flight per lane
-        float4 r[4][2];
-        float v[4];
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-          const T* rp = Wp + (size_t)ii[j + u] * D.d;
-          v[u] = vv[j + u];
-          if (ok) { r[u][0] = Elem<T>::load4(rp); r[u][1] = Elem<T>::load4(rp + 4); }
-        }
-        if (ok) {
-#pragma unroll
-          for (int u = 0; u < 4; ++u) {
-            acc[0] = fmaf(v[u], r[u][0].x, acc[0]); acc[1] = fmaf(v[u], r[u][0].y, acc[1]);
-            acc[2] = fmaf(v[u], r[u][0].z, acc[2]); acc[3] = fmaf(v[u], r[u][0].w, acc[3]);
-            acc[4] = fmaf(v[u], r[u][1].x, acc[4]); acc[5] = fmaf(v[u], r[u][1].y, acc[5]);
-            acc[6] = fmaf(v[u], r[u][1].z, acc[6]); acc[7] = fmaf(v[u], r[u][1].w, acc[7]);
-          }
-        }
-      }
-      for (; j < cnt; ++j) {
-        const T* rp = Wp + (size_t)ii[j] * D.d;
-        const float v = vv[j];
-        if (ok) {
-          const float4 r0 = Elem<T>::load4(rp), r1 = Elem<T>::load4(rp + 4);
-          acc[0] = fmaf(v, r0.x, acc[0]); acc[1] = fmaf(v, r0.y, acc[1]);
-          acc[2] = fmaf(v, r0.z, acc[2]); acc[3] = fmaf(v, r0.w, acc[3]);
-          acc[4] = fmaf(v, r1.x, acc[4]); acc[5] = fmaf(v, r1.y, acc[5]);
-          acc[6] = fmaf(v, r1.z, acc[6]); acc[7] = fmaf(v, r1.w, acc[7]);
-        }
-      }
+      for (; j + 8 <= cnt; j += 8) gather_rows<T, 8>(acc, Wp, D.d, (uint32_t)col, ii, vv, j);
+      if (j + 4 <= cnt) { gather_rows<T, 4>(acc, Wp, D.d, (uint32_t)col, ii, vv, j); j += 4; }
+      for (; j < cnt; ++j) gather_rows<T, 1>(acc, Wp, D.d, (uint32_t)col, ii, vv, j);
     }
-    if (ok) {
-      float* o = y_hat + ((size_t)lp * D.B + b) * D.d + col;
-      *reinterpret_cast<float4*>(o) = make_float4(acc[0], acc[1], acc[2], acc[3]);
-      *reinterpret_cast<float4*>(o + 4) = make_float4(acc[4], acc[5], acc[6], acc[7]);
-    }
+    float* o = y_hat + ((size_t)lp * D.B + b) * D.d + col;
+    *reinterpret_cast<float4*>(o) = make_float4(acc[0], acc[1], acc[2], acc[3]);
+    *reinterpret_cast<float4*>(o + 4) = make_float4(acc[4], acc[5], acc[6], acc[7]);
   }
 }
 
@@ -179,13 +216,6 @@ template <> struct Row8<float> {
     o[0] = a.x; o[1] = a.y; o[2] = a.z; o[3] = a.w; o[4] = b.x; o[5] = b.y; o[6] = b.z; o[7] = b.w;
   }
 };
-
-// Address = wave-uniform base + the lane's fixed element offset (one 32-bit register per lane).
-template <typename X>
-__device__ __forceinline__ X* lane_ptr(X* uniform_base, uint32_t lane_elems) {   // base + lane offset, 32-bit lane part
-  typedef typename std::conditional<std::is_const<X>::value, const char, char>::type Byte;
-  return reinterpret_cast<X*>(reinterpret_cast<Byte*>(uniform_base) + lane_elems * (uint32_t)sizeof(X));
-}
 
 // dpre := 0 (or the dead-feature gradient below the threshold); the listed entries are overwritten by gather_dz.
 template <typename T>
@@ -210,34 +240,6 @@ __global__ __launch_bounds__(256) void sparse_dpre_fill_kernel(Dims D, const uin
     Elem<T>::store4(dpre + i * 4, o);
   }
 }
-
-// 8 consecutive elements kept as loaded (16 bytes of bf16 or 32 bytes of fp32) until they are used
-template <typename T> struct Raw8;
-template <> struct Raw8<bf16_t> {
-  typedef uint4 type;
-  static __device__ __forceinline__ type load(const bf16_t* p) { return *reinterpret_cast<const uint4*>(p); }
-  static __device__ __forceinline__ float dot(const type& a, const type& b, float acc) {
-    const uint32_t x[4] = {a.x, a.y, a.z, a.w}, y[4] = {b.x, b.y, b.z, b.w};
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      acc = fmaf(__uint_as_float(x[i] << 16), __uint_as_float(y[i] << 16), acc);
-      acc = fmaf(__uint_as_float(x[i] & 0xffff0000u), __uint_as_float(y[i] & 0xffff0000u), acc);
-    }
-    return acc;
-  }
-};
-template <> struct Raw8<float> {
-  struct type { float4 lo, hi; };
-  static __device__ __forceinline__ type load(const float* p) {
-    return type{*reinterpret_cast<const float4*>(p), *reinterpret_cast<const float4*>(p + 4)};
-  }
-  static __device__ __forceinline__ float dot(const type& a, const type& b, float acc) {
-    acc = fmaf(a.lo.x, b.lo.x, acc); acc = fmaf(a.lo.y, b.lo.y, acc); acc = fmaf(a.lo.z, b.lo.z, acc);
-    acc = fmaf(a.lo.w, b.lo.w, acc); acc = fmaf(a.hi.x, b.hi.x, acc); acc = fmaf(a.hi.y, b.hi.y, acc);
-    acc = fmaf(a.hi.z, b.hi.z, acc); acc = fmaf(a.hi.w, b.hi.w, acc);
-    return acc;
-  }
-};
 
 // One wavefront per listed entry: for each target l' >= l it streams the entry's decoder row and
 // the token's d y_hat row (64 lanes x 8 columns, 4 passes in flight), keeps one partial dot
