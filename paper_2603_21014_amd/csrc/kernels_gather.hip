@@ -272,23 +272,33 @@ __global__ __launch_bounds__(256) void gather_dz_kernel(Dims D, GatherLists g, c
       const int slot = e < na ? e : g.kcap - 1 - (e - na);      // front: active entries, back: window-only
       const int fe = __builtin_amdgcn_readfirstlane(ii[slot]);
       float part_sum = 0.f;
-      for (int lp = l; lp < D.L; ++lp) {
-        const T* dyr = d_yhat + ((size_t)lp * D.B + b) * D.d;
-        const T* wr = W_dec + ((size_t)packed_index(l, lp, D.L) * D.F + fe) * D.d;
+      // the loads of two targets are in flight together
+      auto targets = [&](auto nt_tag, int lp) {
+        constexpr int NTG = decltype(nt_tag)::value;
         for (int c0 = 0; c0 < D.d; c0 += 2048) {
-          typename Raw8<T>::type dy[4], wq[4];
+          typename Raw8<T>::type dy[NTG][4], wq[NTG][4];
 #pragma unroll
-          for (int q = 0; q < 4; ++q) {
-            const uint32_t col = (uint32_t)(c0 + q * 512 + lane * 8);
-            if ((int)col < D.d) { dy[q] = Raw8<T>::load(lane_ptr(dyr, col)); wq[q] = Raw8<T>::load(lane_ptr(wr, col)); }
+          for (int t = 0; t < NTG; ++t) {
+            const T* dyr = d_yhat + ((size_t)(lp + t) * D.B + b) * D.d;
+            const T* wr = W_dec + ((size_t)packed_index(l, lp + t, D.L) * D.F + fe) * D.d;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+              const uint32_t col = (uint32_t)(c0 + q * 512 + lane * 8);
+              if ((int)col < D.d) { dy[t][q] = Raw8<T>::load(lane_ptr(dyr, col)); wq[t][q] = Raw8<T>::load(lane_ptr(wr, col)); }
+            }
           }
 #pragma unroll
-          for (int q = 0; q < 4; ++q) {
-            const uint32_t col = (uint32_t)(c0 + q * 512 + lane * 8);
-            if ((int)col < D.d) part_sum = Raw8<T>::dot(wq[q], dy[q], part_sum);
-          }
+          for (int t = 0; t < NTG; ++t)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+              const uint32_t col = (uint32_t)(c0 + q * 512 + lane * 8);
+              if ((int)col < D.d) part_sum = Raw8<T>::dot(wq[t][q], dy[t][q], part_sum);
+            }
         }
-      }
+      };
+      int lp = l;
+      for (; lp + 2 <= D.L; lp += 2) targets(std::integral_constant<int, 2>{}, lp);
+      if (lp < D.L) targets(std::integral_constant<int, 1>{}, lp);
 #pragma unroll
       for (int off = 32; off > 0; off >>= 1) part_sum += __shfl_xor(part_sum, off, 64);
       if (lane == 0) {
