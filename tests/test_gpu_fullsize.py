@@ -36,10 +36,11 @@ class LazyBlocks:
 
 
 @pytest.mark.timeout(1200)
-@pytest.mark.parametrize("mode", ["unfused", "fused", "sparse_fused"])
+@pytest.mark.parametrize("mode", ["unfused", "fused", "sparse_fused", "int8_fused"])
 def test_llama1b_shaped_step_against_sampled_oracle(mode):
     """unfused: clt_backward + clt_adam_step; fused: clt_backward_adam_step, the call bench.py times;
-    sparse_fused: thresholds at 0.2 % density, forced gather mode (list-driven decode, dz and dW_dec)."""
+    sparse_fused: thresholds at 0.2 % density, forced gather mode (list-driven decode, dz and dW_dec);
+    int8_fused: x and y as int8 codes with per-(layer, token) scales (the oracle consumes the dequantised values)."""
     from paper_2603_21014_amd import binding as K
     w = S.WORKLOADS["llama1b"]
     L, d, F, B = w.L, w.d, w.F, w.B
@@ -51,26 +52,34 @@ def test_llama1b_shaped_step_against_sampled_oracle(mode):
     x32, y32 = S.make_inputs(w, device=dev)
     if mode == "sparse_fused":
         params["theta"] = S.theta_for_density(x32, params["W_enc"].float(), params["b_enc"], 0.002)
-    x, y = x32.to(T), y32.to(T)
+    int8 = mode == "int8_fused"
+    xs = ys = None
+    if int8:
+        x, xs = S.quantize_rows_int8(x32)
+        y, ys = S.quantize_rows_int8(y32)
+    else:
+        x, y = x32.to(T), y32.to(T)
     del x32, y32
     fused = mode != "unfused"
     m = {k: torch.zeros(v.shape, dtype=torch.float32, device=dev) for k, v in params.items()}
     v_ = {k: torch.zeros(v.shape, dtype=torch.float32, device=dev) for k, v in params.items()}
     step = K.CLTStep(L, d, F, B, dtype="bf16", C_=w.C, ste_bandwidth=w.ste_eps, device=dev, keep_pre=False,
-                     matrix_grads=not fused,
+                     matrix_grads=not fused, int8_inputs=int8,
                      decode_mode=K.DECODE_GATHER if mode == "sparse_fused" else K.DECODE_DENSE)
     print(f"running the GPU step ({mode})", flush=True)
     W_dec_host = params["W_dec"].cpu()          # before Adam changes it
     W_enc_host = params["W_enc"].float().cpu().numpy()
     theta = params["theta"].cpu().numpy().astype(np.float64)
-    step.forward(x, params)
-    loss = step.loss(y, w.lambda0, to_host=True)
+    step.forward(x, params, xs)
+    loss = step.loss(y, w.lambda0, ys, to_host=True)
     d_yhat_gpu = K.clt_workspace_view(step.H, "d_yhat")
     if fused:
-        step.backward_adam_step(x, params, m, v_, 1, w.lr)
+        step.backward_adam_step(x, params, m, v_, 1, w.lr, None, xs)
     else:
         step.backward(x, params)
     dpre_last_gpu = K.clt_workspace_view(step.H, "dpre")[L - 1].float().cpu().numpy()
+    if int8:      # the buffer holds d pre times the row scale of x (what the encoder-weight gradient contracts with the codes)
+        dpre_last_gpu = dpre_last_gpu / xs[L - 1].cpu().numpy()[:, None]
     if not fused:
         step.adam_step(1, w.lr, params, m, v_)
     torch.cuda.synchronize()
@@ -78,7 +87,11 @@ def test_llama1b_shaped_step_against_sampled_oracle(mode):
     if mode == "sparse_fused":
         assert K.clt_workspace_view(step.H, "decode_switch").cpu().numpy()[2] == 2
 
-    xh, yh = x.float().cpu().numpy(), y.float().cpu().numpy()
+    if int8:
+        xh = O.dequantize_rows(x.cpu().numpy(), xs.cpu().numpy())
+        yh = O.dequantize_rows(y.cpu().numpy(), ys.cpu().numpy())
+    else:
+        xh, yh = x.float().cpu().numpy(), y.float().cpu().numpy()
     b_enc = np.zeros((L, F)); b_dec = np.zeros((L, d))       # the workload's initial biases
     Wd = LazyBlocks(W_dec_host)
 
