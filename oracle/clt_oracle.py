@@ -28,6 +28,12 @@ reordering:
                                   pseudo-gradient
   Adam .......................... App. C, Table 1 (betas, learning rate); bias
                                   correction on, eps outside the square root
+  activation normalisation ...... Sec. 3.1, last paragraph: every activation is
+                                  divided by a factor estimated from the first
+                                  N batches so that norms come out near one;
+                                  taken as: one factor per layer (and per side,
+                                  inputs and targets), the mean L2 norm of that
+                                  layer's token vectors over those batches
 
 Storage conventions (they only transpose the paper's matrices):
   x      [L, B, d]   MLP inputs h_l per layer and token
@@ -394,3 +400,29 @@ def train_step(x, y, params, m, v, t, lr, lambda0, C, eps,
 def dequantize_rows(q, s):
     """x[l, b, :] = q[l, b, :] * s[l, b] for symmetric int8 codes q."""
     return np.asarray(q, F64) * np.asarray(s, F64)[:, :, None]
+
+
+# --------------------------------------------------------------------------
+# activation normalisation (Sec. 3.1): factor from the first N batches
+# --------------------------------------------------------------------------
+def normalisation_factor(batches):
+    """c[l] = mean over every token of every batch of ||a[l, b, :]||_2.
+
+    batches: iterable of [L, B_i, d] arrays (the first N batches of one side,
+    inputs or targets).  A layer whose activations are all zero has no scale;
+    it gets c = 1 so that dividing by it leaves the zeros alone."""
+    total, count = None, 0
+    for a in batches:
+        a = np.asarray(a, F64)
+        row_norms = np.sqrt((a * a).sum(axis=2))      # [L, B_i]
+        s = row_norms.sum(axis=1)
+        total = s if total is None else total + s
+        count += a.shape[1]
+    c = total / count
+    return np.where(c > 0.0, c, 1.0)
+
+
+def normalise_activations(a, c):
+    """a[l, b, :] / c[l]."""
+    return np.asarray(a, F64) / np.asarray(c, F64)[:, None, None]
+
