@@ -115,6 +115,26 @@ int clt_destroy(clt_handle* handle);
  * clt_workspace_bytes on this thread when handle is NULL).  Never NULL. */
 const char* clt_last_error(const clt_handle* handle);
 
+/* Activation normalisation (Sec. 3.1, last paragraph): every activation is
+ * divided by a per-layer factor c[l], the mean L2 norm of that layer's token
+ * vectors over the first batches, so that norms come out near one.  Inputs
+ * and targets each have their own factors (call once per side).
+ *
+ * clt_norm_accumulate adds, for every layer, the sum over the B rows of
+ * ||a[l,b,:]||_2 to norm_sum[l] (device, [L] double, 16-byte aligned; the
+ * caller zeroes it before the first batch and counts the tokens).  a is
+ * [L,B,d] in the handle's input format; a_scale [L,B] for int8 rows (the norm
+ * of the codes times |scale|), else NULL.  Deterministic (fixed order). */
+int clt_norm_accumulate(clt_handle* handle, void* stream, const void* a, const float* a_scale, double* norm_sum);
+
+/* Divides by c[l] = norm_sum[l] / n_tokens.  int8 rows: the division folds
+ * into the dequantisation scale, scale_out[l,b] = scale_in[l,b] / c[l]
+ * (scale_out may be scale_in), the codes are untouched and a_in, a_out must be
+ * NULL.  Native rows: a_out = a_in / c[l] (a_out may be a_in), scales NULL.
+ * A layer whose norm_sum is 0 (all-zero activations) is left unscaled. */
+int clt_normalise(clt_handle* handle, void* stream, const double* norm_sum, int64_t n_tokens,
+                  const void* a_in, const float* scale_in, void* a_out, float* scale_out);
+
 /* Encoder + JumpReLU (eq. 1), decoder norms (App. B), cross-layer decode (eq. 3).
  * x_scale: [L,B] float for int8 inputs, else NULL.  Outputs: z, act_class,
  * y_hat are required; pre and l0_per_layer ([L] int32, active entries per

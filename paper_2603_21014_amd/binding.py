@@ -24,7 +24,8 @@ DECODE_AUTO, DECODE_DENSE, DECODE_GATHER = 0, 1, 2
 
 EXPORTS = ("clt_workspace_bytes", "clt_init", "clt_destroy", "clt_last_error", "clt_forward",
            "clt_loss", "clt_backward", "clt_adam_step", "clt_backward_adam_step", "clt_workspace_view",
-           "clt_profile_enable", "clt_profile_num_kernels", "clt_profile_query")
+           "clt_profile_enable", "clt_profile_num_kernels", "clt_profile_query", "clt_norm_accumulate",
+           "clt_normalise")
 
 
 class CLTError(RuntimeError):
@@ -62,6 +63,8 @@ def _load():
     lib.clt_adam_step.argtypes = [vp, vp, C.c_int64, C.c_float] + [C.POINTER(clt_tensors)] * 5
     lib.clt_backward_adam_step.argtypes = [vp, vp, vp, fp, vp, vp, C.c_int64, C.c_float] + [C.POINTER(clt_tensors)] * 5
     lib.clt_workspace_view.argtypes = [vp, C.c_int, C.POINTER(vp), C.POINTER(C.c_size_t)]
+    lib.clt_norm_accumulate.argtypes = [vp, vp, vp, fp, vp]
+    lib.clt_normalise.argtypes = [vp, vp, vp, C.c_int64, vp, fp, vp, fp]
     lib.clt_profile_enable.argtypes = [vp, C.c_int]
     lib.clt_profile_num_kernels.argtypes = []
     lib.clt_profile_query.argtypes = [vp, C.c_int, C.POINTER(C.c_char_p), C.POINTER(C.c_double),
@@ -146,6 +149,22 @@ def clt_init(cfg: clt_config, workspace: torch.Tensor) -> Handle:
     if workspace.dtype != torch.uint8 or not workspace.is_cuda or not workspace.is_contiguous():
         raise ValueError("workspace must be a contiguous uint8 device tensor")
     return Handle(cfg, workspace)
+
+
+def clt_norm_accumulate(H: Handle, a, norm_sum, a_scale=None):
+    s = H.shapes
+    rc = _lib.clt_norm_accumulate(H.h, _stream(), _ptr(a, s["x"], H.TX, "a"),
+                                  _ptr(a_scale, s["scale"], torch.float32, "a_scale", True),
+                                  _ptr(norm_sum, (H.cfg.L,), torch.float64, "norm_sum"))
+    _check(rc, H.h)
+
+
+def clt_normalise(H: Handle, norm_sum, n_tokens, a_in=None, scale_in=None, a_out=None, scale_out=None):
+    s, f32 = H.shapes, torch.float32
+    rc = _lib.clt_normalise(H.h, _stream(), _ptr(norm_sum, (H.cfg.L,), torch.float64, "norm_sum"), int(n_tokens),
+                            _ptr(a_in, s["x"], H.T, "a_in", True), _ptr(scale_in, s["scale"], f32, "scale_in", True),
+                            _ptr(a_out, s["x"], H.T, "a_out", True), _ptr(scale_out, s["scale"], f32, "scale_out", True))
+    _check(rc, H.h)
 
 
 def clt_forward(H: Handle, x, W_enc, b_enc, theta, W_dec, b_dec, z, act_class, y_hat,

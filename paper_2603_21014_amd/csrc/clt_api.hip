@@ -40,13 +40,13 @@ void set_err(char* dst, const char* fmt, ...) {
 enum KernelId {
   K_NORMS, K_ENC, K_DEC, K_LOSS_SP, K_LOSS_REC, K_LOSS_FINAL, K_COLRED, K_DZ, K_STE, K_DWENC, K_DWDEC,
   K_ADAM_WDEC, K_ADAM_WENC, K_ADAM_VEC, K_ZERO, K_DECIDE, K_COMPACT, K_GATHER, K_SP_FILL, K_GATHER_DZ, K_FLISTS,
-  K_SP_DWDEC, K_TOPK, K_COUNT
+  K_SP_DWDEC, K_TOPK, K_NORM_SUM, K_NORMALISE, K_COUNT
 };
 static const char* const kKernelNames[K_COUNT] = {
   "decoder_norms", "encoder_jumprelu_gemm", "decode_gemm", "loss_sparsity", "loss_reconstruction", "loss_final",
   "column_reduce", "dz_gemm", "ste_reduce", "dW_enc_gemm", "dW_dec_gemm", "adam_W_dec", "adam_W_enc",
   "adam_vectors", "zero_counters", "decode_decide", "compact_active", "gather_decode", "sparse_dpre_fill",
-  "gather_dz", "feature_lists", "sparse_dW_dec", "topk_select"};
+  "gather_dz", "feature_lists", "sparse_dW_dec", "topk_select", "activation_norm_sum", "normalise_activations"};
 
 struct ProfSpan { int kernel; hipEvent_t a, b; };
 
@@ -331,6 +331,41 @@ int clt_workspace_view(const clt_handle* h, int which, void** ptr, size_t* bytes
     case 4: *ptr = h->ws + h->plan.flags; *bytes = 16; break;
     default: return CLT_ERR_INVALID_ARG;
   }
+  return CLT_OK;
+}
+
+int clt_norm_accumulate(clt_handle* h, void* stream, const void* a, const float* a_scale, double* norm_sum) {
+  if (!h) { set_err(g_err, "clt_norm_accumulate: handle is NULL"); return CLT_ERR_INVALID_ARG; }
+  REQ(h, a); REQ(h, norm_sum);
+  if (h->int8) REQ(h, a_scale);
+  else if (a_scale) { set_err(h->err, "clt_norm_accumulate: a_scale given but input_format is native"); return CLT_ERR_INVALID_ARG; }
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  // the per-block partial sums borrow the reconstruction loss's partials, which never outlive a clt_loss call
+  double* part = reinterpret_cast<double*>(h->ws + h->plan.part_rec);
+  RUN(h, s, K_NORM_SUM, launch_norm_accumulate(s, h->bf16, h->int8, h->D, a, a_scale, part, norm_sum));
+  return CLT_OK;
+}
+
+int clt_normalise(clt_handle* h, void* stream, const double* norm_sum, int64_t n_tokens, const void* a_in,
+                  const float* scale_in, void* a_out, float* scale_out) {
+  if (!h) { set_err(g_err, "clt_normalise: handle is NULL"); return CLT_ERR_INVALID_ARG; }
+  REQ(h, norm_sum);
+  if (n_tokens < 1) { set_err(h->err, "clt_normalise: n_tokens must be >= 1"); return CLT_ERR_INVALID_ARG; }
+  if (h->int8) {
+    REQ(h, scale_in); REQ(h, scale_out);
+    if (a_in || a_out) {
+      set_err(h->err, "clt_normalise: int8 rows are normalised through their scales; a_in and a_out must be NULL");
+      return CLT_ERR_INVALID_ARG;
+    }
+  } else {
+    REQ(h, a_in); REQ(h, a_out);
+    if (scale_in || scale_out) {
+      set_err(h->err, "clt_normalise: scales given but input_format is native");
+      return CLT_ERR_INVALID_ARG;
+    }
+  }
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  RUN(h, s, K_NORMALISE, launch_normalise(s, h->bf16, h->int8, h->D, norm_sum, (double)n_tokens, a_in, scale_in, a_out, scale_out));
   return CLT_OK;
 }
 

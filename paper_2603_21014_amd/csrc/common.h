@@ -159,6 +159,12 @@ constexpr int LOSS_ROWS_PER_BLOCK = 32;   // token rows per block of the row-blo
 inline int row_blocks(int B) { return (B + LOSS_ROWS_PER_BLOCK - 1) / LOSS_ROWS_PER_BLOCK; }
 
 hipError_t launch_zero_i32(hipStream_t s, int32_t* p, int n);
+// activation normalisation (Sec. 3.1): norm_sum[l] += sum over the B rows of ||a[l,b,:]||_2 (part: row_blocks(B)*L
+// doubles of scratch); then a / c[l] with c[l] = norm_sum[l] / n_tokens, folded into the row scales for int8 rows
+hipError_t launch_norm_accumulate(hipStream_t s, bool bf16, bool int8_a, Dims D, const void* a, const float* a_scale,
+                                  double* part, double* norm_sum);
+hipError_t launch_normalise(hipStream_t s, bool bf16, bool int8_a, Dims D, const double* norm_sum, double n_tokens,
+                            const void* a_in, const float* scale_in, void* a_out, float* scale_out);
 // TopK activation (Sec. 3.2): per (layer, token) row of pre32 [L,B,F] the k largest entries (lower index wins
 // ties) -> z = pre there, 0 elsewhere; class byte CLS_ACTIVE or 0; l0[l] += k per row
 hipError_t launch_topk_select(hipStream_t s, bool bf16, Dims D, const float* pre32, int k, void* z, uint8_t* cls,

@@ -449,6 +449,75 @@ __global__ __launch_bounds__(256) void topk_select_kernel(Dims D, const float* _
   if (tid == 0 && l0) atomicAdd(l0 + (int)(row / D.B), all ? D.F : (none ? 0 : k));
 }
 
+// ---- activation normalisation (Sec. 3.1): the factor of a layer is the mean L2 norm of its
+// token vectors over the first batches.  Stage 1: grid = (row blocks, L), one wave per row, each
+// block leaves the sum of its rows' norms; stage 2 adds the blocks of a layer, in order, to the
+// running sum.  int8 rows: the norm of the codes times |row scale|.
+template <typename T, bool INT8>
+__global__ __launch_bounds__(256) void row_norm_sum_kernel(Dims D, const void* __restrict__ av,
+                                                           const float* __restrict__ a_scale,
+                                                           double* __restrict__ part) {
+  const int rb = blockIdx.x, l = blockIdx.y, lane = threadIdx.x & 63;
+  const int r0 = rb * LOSS_ROWS_PER_BLOCK, r1 = min(D.B, r0 + LOSS_ROWS_PER_BLOCK);
+  double s = 0.0;   // the same value in every lane of a wave
+  for (int r = r0 + (threadIdx.x >> 6); r < r1; r += 4) {
+    const size_t o = ((size_t)l * D.B + r) * D.d;
+    float acc = 0.f;
+    for (int j = lane * 4; j < D.d; j += 256) {
+      float4 v;
+      if (INT8) {
+        const uint32_t q = *reinterpret_cast<const uint32_t*>(reinterpret_cast<const int8_t*>(av) + o + j);
+        v = make_float4((float)(int8_t)q, (float)(int8_t)(q >> 8), (float)(int8_t)(q >> 16), (float)(int8_t)(q >> 24));
+      } else {
+        v = Elem<T>::load4(reinterpret_cast<const T*>(av) + o + j);
+      }
+      acc += (v.x * v.x + v.y * v.y) + (v.z * v.z + v.w * v.w);
+    }
+    float n = sqrtf(wave_sum(acc));
+    if (INT8) n *= fabsf(a_scale[(size_t)l * D.B + r]);
+    s += (double)n;
+  }
+  __shared__ double sh[4];
+  if (lane == 0) sh[threadIdx.x >> 6] = s;
+  __syncthreads();
+  if (threadIdx.x == 0) part[(size_t)l * gridDim.x + rb] = (sh[0] + sh[1]) + (sh[2] + sh[3]);
+}
+
+__global__ void norm_sum_final_kernel(int L, int nrb, const double* __restrict__ part, double* __restrict__ norm_sum) {
+  const int l = blockIdx.x * blockDim.x + threadIdx.x;
+  if (l >= L) return;
+  double s = 0.0;
+  for (int i = 0; i < nrb; ++i) s += part[(size_t)l * nrb + i];
+  norm_sum[l] += s;
+}
+
+// 1 / c[l] = n_tokens / norm_sum[l]; a layer that summed to zero has no scale and keeps factor 1
+__device__ __forceinline__ float inv_norm_factor(const double* norm_sum, int l, double n_tokens) {
+  const double s = norm_sum[l];
+  return s > 0.0 ? (float)(n_tokens / s) : 1.0f;
+}
+
+// int8 rows: the division folds into the dequantisation scale, the codes stay as they are
+__global__ void normalise_scale_kernel(Dims D, const double* __restrict__ norm_sum, double n_tokens,
+                                       const float* __restrict__ scale_in, float* __restrict__ scale_out) {
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= (size_t)D.L * D.B) return;
+  scale_out[i] = scale_in[i] * inv_norm_factor(norm_sum, (int)(i / D.B), n_tokens);
+}
+
+// native rows: a_out = a_in / c[l] (a_out may be a_in); grid = (chunks of a layer, L)
+template <typename T>
+__global__ __launch_bounds__(256) void normalise_rows_kernel(Dims D, const double* __restrict__ norm_sum,
+                                                             double n_tokens, const T* a_in, T* a_out) {
+  const int l = blockIdx.y;
+  const float k = inv_norm_factor(norm_sum, l, n_tokens);
+  const size_t n4 = (size_t)D.B * D.d / 4, base = (size_t)l * D.B * D.d;
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n4; i += (size_t)gridDim.x * 256) {
+    const float4 v = Elem<T>::load4(a_in + base + 4 * i);
+    Elem<T>::store4(a_out + base + 4 * i, make_float4(k * v.x, k * v.y, k * v.z, k * v.w));
+  }
+}
+
 inline int grid_for(size_t n, int per_block, int cap) {
   size_t b = (n + per_block - 1) / per_block;
   if (b < 1) b = 1;
@@ -575,6 +644,37 @@ hipError_t launch_adam_vector(hipStream_t s, size_t n, float* p, const float* g,
   const size_t n4 = n / 4;   // vectors have L*F or L*d elements, multiples of 8
   hipLaunchKernelGGL((adam_kernel<float, false>), dim3(grid_for(n4, 256, 256 * 32)), dim3(256), 0, s, n4, p, g, m, v,
                      (float*)nullptr, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_norm_accumulate(hipStream_t s, bool bf16, bool int8_a, Dims D, const void* a, const float* a_scale,
+                                  double* part, double* norm_sum) {
+  const dim3 grid(row_blocks(D.B), D.L);
+  if (!bf16)
+    hipLaunchKernelGGL((row_norm_sum_kernel<float, false>), grid, dim3(256), 0, s, D, a, a_scale, part);
+  else if (int8_a)
+    hipLaunchKernelGGL((row_norm_sum_kernel<bf16_t, true>), grid, dim3(256), 0, s, D, a, a_scale, part);
+  else
+    hipLaunchKernelGGL((row_norm_sum_kernel<bf16_t, false>), grid, dim3(256), 0, s, D, a, a_scale, part);
+  hipLaunchKernelGGL(norm_sum_final_kernel, dim3((D.L + 63) / 64), dim3(64), 0, s, D.L, (int)grid.x, part, norm_sum);
+  return hipGetLastError();
+}
+
+hipError_t launch_normalise(hipStream_t s, bool bf16, bool int8_a, Dims D, const double* norm_sum, double n_tokens,
+                            const void* a_in, const float* scale_in, void* a_out, float* scale_out) {
+  if (int8_a) {
+    const size_t n = (size_t)D.L * D.B;
+    hipLaunchKernelGGL(normalise_scale_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, D, norm_sum,
+                       n_tokens, scale_in, scale_out);
+  } else {
+    const dim3 grid(grid_for((size_t)D.B * D.d / 4, 256 * 4, 2048), D.L);
+    if (bf16)
+      hipLaunchKernelGGL((normalise_rows_kernel<bf16_t>), grid, dim3(256), 0, s, D, norm_sum, n_tokens,
+                         (const bf16_t*)a_in, (bf16_t*)a_out);
+    else
+      hipLaunchKernelGGL((normalise_rows_kernel<float>), grid, dim3(256), 0, s, D, norm_sum, n_tokens,
+                         (const float*)a_in, (float*)a_out);
+  }
   return hipGetLastError();
 }
 
