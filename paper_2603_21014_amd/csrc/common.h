@@ -57,6 +57,13 @@ template <> struct Elem<float> {
   static __device__ __forceinline__ float4 load4(const float* p) { return *reinterpret_cast<const float4*>(p); }
   static __device__ __forceinline__ float4 nt_load4(const float* p) { return nt_load_f4(p); }
   static __device__ __forceinline__ void nt_store4(float* p, float4 v) { nt_store_f4(p, v); }
+  // 4 elements as they come out of memory; widen4() turns them into floats.  Code that wants loads
+  // in flight across other work keeps the raw form until the values are used: arithmetic on a
+  // loaded value is where the wait for that load goes.
+  typedef float4 Raw4;
+  static __device__ __forceinline__ Raw4 load_raw4(const float* p) { return load4(p); }
+  static __device__ __forceinline__ Raw4 nt_load_raw4(const float* p) { return nt_load_f4(p); }
+  static __device__ __forceinline__ float4 widen4(Raw4 r) { return r; }
 };
 template <> struct Elem<bf16_t> {
   static __device__ __forceinline__ float load(const bf16_t* p) { return bf16_to_f32(*p); }
@@ -80,6 +87,13 @@ template <> struct Elem<bf16_t> {
   static __device__ __forceinline__ void nt_store4(bf16_t* p, float4 v) {
     const nt_u32x2 u = {pack_bf16x2(v.x, v.y), pack_bf16x2(v.z, v.w)};
     CLT_NT_STORE(u, reinterpret_cast<nt_u32x2*>(p));
+  }
+  typedef nt_u32x2 Raw4;
+  static __device__ __forceinline__ Raw4 load_raw4(const bf16_t* p) { return *reinterpret_cast<const nt_u32x2*>(p); }
+  static __device__ __forceinline__ Raw4 nt_load_raw4(const bf16_t* p) { return CLT_NT_LOAD(reinterpret_cast<const nt_u32x2*>(p)); }
+  static __device__ __forceinline__ float4 widen4(Raw4 u) {
+    return make_float4(__uint_as_float(u[0] << 16), __uint_as_float(u[0] & 0xffff0000u),
+                       __uint_as_float(u[1] << 16), __uint_as_float(u[1] & 0xffff0000u));
   }
 };
 

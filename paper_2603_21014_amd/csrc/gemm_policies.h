@@ -1,8 +1,8 @@
 // The five contractions of a CLT train step, each described as a "policy":
 // operand addressing (which memory dimension is the contraction index K), the
 // K segments of the triangular sums, and the fused epilogue.  The same policies
-// drive the fp32 FMA kernel (gemm_f32.h) and the bf16 MFMA kernel
-// (gemm_bf16.h).
+// drive the fp32 FMA kernel (kernels_gemm_f32.hip) and the bf16 MFMA kernel
+// (kernels_gemm_bf16.hip).
 //
 // A policy exposes
 //   A_KC / B_KC  true when the operand is contiguous along K in memory
@@ -14,9 +14,12 @@
 //   epi_begin(st, gi, col, ok)    once per tile and lane: loads what depends on the lane's
 //                columns only (biases, thresholds, norms) when `ok` (col inside the matrix)
 //   epi_load(regs, gi, pos)       issues the global loads the epilogue of that 4-column
-//                group needs (the kernels call it for a batch of groups first, so the
-//                loads of the whole batch of EPI_BATCH groups are in flight together)
+//                group needs and keeps the results as loaded (no arithmetic on them here: that
+//                is where the wait for the load would land).  The bf16 kernel calls it ahead of
+//                use: EPI_BATCH / EPI_BATCH_LATE / EPI_BATCH_LAST groups ahead in the first
+//                quarter / second quarter / second half of a wave's block
 //   epi4(st, gi, pos, v, regs)    consumes 4 accumulators of one row, columns col..col+3
+//   PERSISTENT   the bf16 kernel runs one workgroup per CU over many tiles (else one per tile)
 #pragma once
 #include "common.h"
 
@@ -98,17 +101,19 @@ __device__ __forceinline__ X* epi_ptr(X* base, size_t uoff, uint32_t loff) {
 struct AdamFuse {
   float* m; float* v; float* master; AdamScalars a;   // m == nullptr: not fused
 };
-struct AdamRegs { float4 m, v, p; };   // moments and the fp32 parameter (master copy or widened weight)
-template <typename T>
-__device__ __forceinline__ void adam_load4(AdamRegs& r, const AdamFuse& f, const T* w, size_t uo, uint32_t lo) {
+// Moments and the fp32 master parameter (when there is one) exactly as loaded; the stored weight
+// travels beside them in its raw form.  Nothing is computed on any of them before adam_update4,
+// so the loads stay in flight.
+struct AdamRegs { float4 m, v, master; };
+__device__ __forceinline__ void adam_load4(AdamRegs& r, const AdamFuse& f, size_t uo, uint32_t lo) {
   r.m = nt_load_f4(epi_ptr(f.m, uo, lo));
   r.v = nt_load_f4(epi_ptr(f.v, uo, lo));
-  r.p = f.master ? nt_load_f4(epi_ptr(f.master, uo, lo)) : Elem<T>::nt_load4(epi_ptr(w, uo, lo));
+  if (f.master) r.master = nt_load_f4(epi_ptr(f.master, uo, lo));
 }
 template <typename T>
 __device__ __forceinline__ void adam_update4(const AdamFuse& f, T* w, size_t uo, uint32_t lo, const AdamRegs& r,
-                                             float4 g4) {
-  const float4 m4 = r.m, v4 = r.v, p4 = r.p;
+                                             typename Elem<T>::Raw4 w_raw, float4 g4) {
+  const float4 m4 = r.m, v4 = r.v, p4 = f.master ? r.master : Elem<T>::widen4(w_raw);
   const float g[4] = {g4.x, g4.y, g4.z, g4.w};
   float mm[4] = {m4.x, m4.y, m4.z, m4.w}, vv[4] = {v4.x, v4.y, v4.z, v4.w}, pp[4] = {p4.x, p4.y, p4.z, p4.w};
 #pragma unroll
@@ -140,7 +145,8 @@ struct EncPolicy {
   __device__ int nseg(const GInfo&) const { return 1; }
   __device__ const TA* a_seg(const GInfo& g, int) const { return x + (size_t)g.l * D.B * D.d; }
   __device__ const T* b_seg(const GInfo& g, int) const { return W_enc + (size_t)g.l * D.d * D.F; }
-  static constexpr int EPI_BATCH = 8, EPI_BATCH_LATE = 8;
+  static constexpr int EPI_BATCH = 8, EPI_BATCH_LATE = 8, EPI_BATCH_LAST = 8;
+  static constexpr bool PERSISTENT = true;
   struct EpiRegs { float s; };
   __device__ void epi_begin(Epi& e, const GInfo& g, int col, bool ok) const {
     e.count = 0;
@@ -217,7 +223,8 @@ struct DecPolicy {
   __device__ const T* b_seg(const GInfo& g, int s) const {
     return W_dec + (size_t)packed_index(s, g.lp, D.L) * D.F * D.d;
   }
-  static constexpr int EPI_BATCH = 8, EPI_BATCH_LATE = 8;
+  static constexpr int EPI_BATCH = 8, EPI_BATCH_LATE = 8, EPI_BATCH_LAST = 8;
+  static constexpr bool PERSISTENT = true;
   struct EpiRegs {};
   __device__ void epi_begin(Epi& e, const GInfo& g, int col, bool ok) const {
     e.b = ok ? *reinterpret_cast<const float4*>(b_dec + (size_t)g.lp * D.d + col) : make_float4(0.f, 0.f, 0.f, 0.f);
@@ -258,8 +265,9 @@ struct DzPolicy {
   __device__ const T* b_seg(const GInfo& g, int s) const {
     return W_dec + (size_t)packed_index(g.l, g.l + s, D.L) * D.F * D.d;
   }
-  static constexpr int EPI_BATCH = 8, EPI_BATCH_LATE = 8;
-  struct EpiRegs { uint32_t c4; float4 z4; };
+  static constexpr int EPI_BATCH = 8, EPI_BATCH_LATE = 8, EPI_BATCH_LAST = 8;
+  static constexpr bool PERSISTENT = false;   // measured: 16.4 ms as a tile loop, 15.9 ms with one workgroup per tile
+  struct EpiRegs { uint32_t c4; typename Elem<T>::Raw4 z4; };
   __device__ void epi_begin(Epi& e, const GInfo& g, int col, bool ok) const {
     float4 n4 = make_float4(0.f, 0.f, 0.f, 0.f);
     if (ok) n4 = *reinterpret_cast<const float4*>(norms + (size_t)g.l * D.F + col);
@@ -272,14 +280,14 @@ struct DzPolicy {
     const size_t uo = pos.uoff((size_t)g.l * D.B, D.F);
     const uint32_t lo = pos.loff(D.F);
     r.c4 = *reinterpret_cast<const uint32_t*>(epi_ptr(cls, uo, lo));
-    r.z4 = Elem<T>::load4(epi_ptr(z, uo, lo));
+    r.z4 = Elem<T>::load_raw4(epi_ptr(z, uo, lo));
   }
   __device__ void epi4(Epi& e, const GInfo& g, const EpiPos& pos, float4 v, const EpiRegs& r) const {
     const uint32_t c4 = r.c4;
     float4 out = make_float4(0.f, 0.f, 0.f, 0.f);
     const float dg[4] = {e.dead.x, e.dead.y, e.dead.z, e.dead.w};
     if (c4 & 0x03030303u) {          // some entry active or in the window: dz is kept there
-      const float4 z4 = r.z4;
+      const float4 z4 = Elem<T>::widen4(r.z4);
       const float zz[4] = {z4.x, z4.y, z4.z, z4.w};
       const float vv[4] = {v.x, v.y, v.z, v.w};
       const float ka[4] = {e.karg.x, e.karg.y, e.karg.z, e.karg.w}, kb[4] = {e.kamp.x, e.kamp.y, e.kamp.z, e.kamp.w};
@@ -306,7 +314,9 @@ struct DzPolicy {
 // ---------------------------------------------------------------------------
 // dW_dec[p(l,lp)] = z[l]^T dyhat[lp] + (G[l,f] / n[l,f]) W_dec[p][f,:]
 // ---------------------------------------------------------------------------
-template <typename T>
+// ADAM: the update is fused into the epilogue (compile-time, so that the epilogue is one straight
+// run of code and every wait counts exactly the loads that were issued).
+template <typename T, bool ADAM>
 struct DWdecPolicy {
   static constexpr bool A_KC = false, B_KC = false;
   typedef T AType;
@@ -327,9 +337,10 @@ struct DWdecPolicy {
   __device__ int nseg(const GInfo&) const { return 1; }
   __device__ const T* a_seg(const GInfo& g, int) const { return z + (size_t)g.l * D.B * D.F; }
   __device__ const T* b_seg(const GInfo& g, int) const { return d_yhat + (size_t)g.lp * D.B * D.d; }
-  // 18 registers per row group: 4 groups while most accumulators are still live, 8 afterwards
-  static constexpr int EPI_BATCH = 4, EPI_BATCH_LATE = 8;
-  struct EpiRegs { float Gf, nf; float4 w; AdamRegs ad; };
+  // up to 16 registers per row group in flight: a short window while most accumulators are still live
+  static constexpr int EPI_BATCH = 4, EPI_BATCH_LATE = 8, EPI_BATCH_LAST = 8;
+  static constexpr bool PERSISTENT = !ADAM;
+  struct EpiRegs { float Gf, nf; typename Elem<T>::Raw4 w; AdamRegs ad; };
   __device__ void epi_begin(Epi&, const GInfo&, int, bool) const {}
   __device__ void epi_load(EpiRegs& r, const GInfo& g, const EpiPos& pos) const {
     const size_t nf = (size_t)g.l * D.F + pos.ru;
@@ -337,17 +348,17 @@ struct DWdecPolicy {
     r.nf = *epi_ptr(norms, nf, (uint32_t)pos.rl);
     const size_t uo = pos.uoff((size_t)g.p * D.F, D.d);
     const uint32_t lo = pos.loff(D.d);
-    r.w = Elem<T>::nt_load4(epi_ptr(W_dec, uo, lo));
-    if (fuse.m) adam_load4<T>(r.ad, fuse, W_dec, uo, lo);
+    r.w = Elem<T>::nt_load_raw4(epi_ptr(W_dec, uo, lo));
+    if (ADAM) adam_load4(r.ad, fuse, uo, lo);
   }
   __device__ void epi4(Epi&, const GInfo& g, const EpiPos& pos, float4 v, const EpiRegs& r) const {
     const float coef = r.Gf * __builtin_amdgcn_rcpf(fmaxf(r.nf, 1e-30f));
     const size_t uo = pos.uoff((size_t)g.p * D.F, D.d);
     const uint32_t lo = pos.loff(D.d);
-    const float4 w = r.w;
+    const float4 w = Elem<T>::widen4(r.w);
     const float4 gr = make_float4(fmaf(coef, w.x, v.x), fmaf(coef, w.y, v.y), fmaf(coef, w.z, v.z), fmaf(coef, w.w, v.w));
-    if (dW_dec) Elem<T>::store4(epi_ptr(dW_dec, uo, lo), gr);
-    if (fuse.m) adam_update4<T>(fuse, W_dec, uo, lo, r.ad, gr);
+    if (!ADAM || dW_dec) Elem<T>::store4(epi_ptr(dW_dec, uo, lo), gr);
+    if (ADAM) adam_update4<T>(fuse, W_dec, uo, lo, r.ad, r.w, gr);
   }
   __device__ void epi_end(Epi&, const GInfo&) const {}
 };
@@ -355,7 +366,7 @@ struct DWdecPolicy {
 // ---------------------------------------------------------------------------
 // dW_enc[l] = x[l]^T dpre[l]
 // ---------------------------------------------------------------------------
-template <typename T, typename TA = T>
+template <typename T, bool ADAM, typename TA = T>
 struct DWencPolicy {
   static constexpr bool A_KC = false, B_KC = false;
   typedef TA AType;
@@ -370,17 +381,22 @@ struct DWencPolicy {
   __device__ int nseg(const GInfo&) const { return 1; }
   __device__ const TA* a_seg(const GInfo& g, int) const { return x + (size_t)g.l * D.B * D.d; }
   __device__ const T* b_seg(const GInfo& g, int) const { return dpre + (size_t)g.l * D.B * D.F; }
-  static constexpr int EPI_BATCH = 4, EPI_BATCH_LATE = 8;
-  struct EpiRegs { AdamRegs ad; };
+  static constexpr int EPI_BATCH = 4, EPI_BATCH_LATE = 8, EPI_BATCH_LAST = 8;
+  static constexpr bool PERSISTENT = !ADAM;
+  struct EpiRegs { AdamRegs ad; typename Elem<T>::Raw4 w; };
   __device__ void epi_begin(Epi&, const GInfo&, int, bool) const {}
   __device__ void epi_load(EpiRegs& r, const GInfo& g, const EpiPos& pos) const {
-    if (fuse.m) adam_load4<T>(r.ad, fuse, W_enc, pos.uoff((size_t)g.l * D.d, D.F), pos.loff(D.F));
+    if (!ADAM) return;
+    const size_t uo = pos.uoff((size_t)g.l * D.d, D.F);
+    const uint32_t lo = pos.loff(D.F);
+    adam_load4(r.ad, fuse, uo, lo);
+    if (!fuse.master) r.w = Elem<T>::nt_load_raw4(epi_ptr(W_enc, uo, lo));
   }
   __device__ void epi4(Epi&, const GInfo& g, const EpiPos& pos, float4 v, const EpiRegs& r) const {
     const size_t uo = pos.uoff((size_t)g.l * D.d, D.F);
     const uint32_t lo = pos.loff(D.F);
-    if (dW_enc) Elem<T>::store4(epi_ptr(dW_enc, uo, lo), v);
-    if (fuse.m) adam_update4<T>(fuse, W_enc, uo, lo, r.ad, v);
+    if (!ADAM || dW_enc) Elem<T>::store4(epi_ptr(dW_enc, uo, lo), v);
+    if (ADAM) adam_update4<T>(fuse, W_enc, uo, lo, r.ad, r.w, v);
   }
   __device__ void epi_end(Epi&, const GInfo&) const {}
 };

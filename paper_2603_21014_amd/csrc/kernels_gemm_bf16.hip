@@ -141,9 +141,9 @@ constexpr int NTHREADS = 512;   // 8 wavefronts: two per SIMD, so one's memory p
 // matrices and kseg is a multiple of 64 (no predication at all).
 template <class P, bool EDGE>
 __device__ __forceinline__ void main_loop(const P& p, const typename P::GInfo& gi, int m0, int n0, bf16_t* smem,
-                                          f32x16_t (&acc)[4][2]) {
+                                          f32x16_t (&acc)[4][2], int t) {
   typedef typename P::AType TA;
-  const int t = threadIdx.x, lane = t & 63, w = t >> 6, wm = w >> 2, wn = w & 3;
+  const int lane = t & 63, w = t >> 6, wm = w >> 2, wn = w & 3;
   const int lt = t & 255;
   // waves 0-3 stage A, waves 4-7 stage B (waves w and w+4 share a SIMD, so each SIMD holds one of each group)
   const bool loads_a = __builtin_amdgcn_readfirstlane(w) < 4;
@@ -270,8 +270,8 @@ __device__ __forceinline__ void main_loop(const P& p, const typename P::GInfo& g
 // inside the matrix, no predicates.
 template <class P, bool EDGE>
 __device__ __forceinline__ void epilogue(const P& p, const typename P::GInfo& gi, int m0, int n0, bf16_t* smem,
-                                         f32x16_t (&acc)[4][2]) {
-  const int t = threadIdx.x, lane = t & 63, w = t >> 6;
+                                         f32x16_t (&acc)[4][2], int t) {
+  const int lane = t & 63, w = t >> 6;
   const int wu = __builtin_amdgcn_readfirstlane(w), wm = wu >> 2, wn = wu & 3;
   const int M = p.M, N = p.N;
   __syncthreads();
@@ -284,75 +284,117 @@ __device__ __forceinline__ void epilogue(const P& p, const typename P::GInfo& gi
   const bool col_ok = !EDGE || pos.col() < N;
   typename P::Epi est;
   p.epi_begin(est, gi, pos.col(), col_ok);
-  // One 32-row slab of the wave's block.  The LDS region is private to the wave and a wave's LDS
-  // accesses complete in issue order, so the transposition needs no barrier.  The global loads the policy's epilogue needs are issued
-  // for EB row groups before any is consumed; later slabs can afford larger batches because the
-  // accumulators of the slabs already written out no longer occupy registers.
-  auto slab = [&](auto eb_tag, int i) {
-    // (predicated edge tiles keep to batches of 4: the predicates' registers come on top)
-    constexpr int EB = (EDGE && decltype(eb_tag)::value > 4) ? 4 : decltype(eb_tag)::value;
-#pragma unroll
-    for (int j = 0; j < 2; ++j)
-#pragma unroll
-      for (int r = 0; r < 16; ++r)
-        wl[(8 * (r >> 2) + 4 * (lane >> 5) + (r & 3)) * 64 + j * 32 + (lane & 31)] = acc[i][j][r];
-#pragma unroll
-    for (int it0 = 0; it0 < 8; it0 += EB) {
-      typename P::EpiRegs er[EB];
-#pragma unroll
-      for (int u = 0; u < EB; ++u) {
-        pos.ru = m0 + wm * 128 + i * 32 + (it0 + u) * 4;
-        if (!EDGE || (col_ok && pos.row() < M)) p.epi_load(er[u], gi, pos);
-      }
-#pragma unroll
-      for (int u = 0; u < EB; ++u) {
-        pos.ru = m0 + wm * 128 + i * 32 + (it0 + u) * 4;
-        const float4 v = *reinterpret_cast<const float4*>(wl + ((it0 + u) * 4 + pos.rl) * 64 + pos.cl);
-        if (!EDGE || (col_ok && pos.row() < M)) p.epi4(est, gi, pos, v, er[u]);
-      }
-    }
+  // The wave's block is 32 row groups of 4 rows (4 slabs of 8).  Each slab goes through the wave's
+  // private LDS region (a wave's LDS accesses complete in issue order, so the transposition needs
+  // no barrier).  The global loads the policy's epilogue needs run ahead of their use as a rolling
+  // window: before group g is consumed the loads of all groups below g + depth have been issued, so
+  // loads stay in flight while earlier groups are computed and stored.  The window deepens slab by
+  // slab as the accumulators already written out stop occupying registers (predicated edge tiles
+  // keep to 4: the predicates' registers come on top).
+  constexpr int NG = 32;
+  // look-ahead (in row groups) while group g is consumed
+  auto depth = [](int g) constexpr {
+    const int d = g < 8 ? P::EPI_BATCH : (g < 16 ? P::EPI_BATCH_LATE : P::EPI_BATCH_LAST);
+    return (EDGE && d > 4) ? 4 : d;
   };
-  slab(std::integral_constant<int, P::EPI_BATCH>{}, 0);
-  slab(std::integral_constant<int, P::EPI_BATCH_LATE>{}, 1);
-  slab(std::integral_constant<int, P::EPI_BATCH_LATE>{}, 2);
-  slab(std::integral_constant<int, P::EPI_BATCH_LATE>{}, 3);
+  typename P::EpiRegs er[NG];
+  auto issue = [&](int g) {
+    pos.ru = m0 + wm * 128 + g * 4;
+    if (!EDGE || (col_ok && pos.row() < M)) p.epi_load(er[g], gi, pos);
+  };
+#pragma unroll
+  for (int g = 0; g < depth(0); ++g) issue(g);
+#pragma unroll
+  for (int g = 0; g < NG; ++g) {
+    if ((g & 7) == 0) {
+      const int i = g >> 3;
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+          wl[(8 * (r >> 2) + 4 * (lane >> 5) + (r & 3)) * 64 + j * 32 + (lane & 31)] = acc[i][j][r];
+    }
+    const int done = g == 0 ? depth(0) : g - 1 + depth(g - 1);
+    const int want = g + depth(g);
+#pragma unroll
+    for (int q = (done < NG ? done : NG); q < (want < NG ? want : NG); ++q) issue(q);
+    pos.ru = m0 + wm * 128 + g * 4;
+    const float4 v = *reinterpret_cast<const float4*>(wl + ((g & 7) * 4 + pos.rl) * 64 + pos.cl);
+    if (!EDGE || (col_ok && pos.row() < M)) p.epi4(est, gi, pos, v, er[g]);
+  }
   p.epi_end(est, gi);
 }
 
-template <class P>
-__global__ __launch_bounds__(NTHREADS) void gemm_bf16_kernel(P p, TileGrid tg) {
+// P::PERSISTENT: the grid is one workgroup per CU and workgroup i runs tiles i, i + gridDim.x, ...
+// of the XCD-aware tile order (gridDim.x is a multiple of 8, so all tiles of a workgroup belong
+// to the XCD it runs on).  Between two tiles of a CU there is then neither a workgroup dispatch
+// nor a wait for the finished tile's stores to drain (2 to 8 us per tile otherwise).  Policies
+// whose epilogue needs the whole register file (the fused Adam update) keep one tile per
+// workgroup: inside the tile loop their scalar operands would stay live across the main loop and
+// spill.  INTERIOR: no tile of the launch touches an edge, only the unpredicated code is built in.
+template <class P, bool INTERIOR>
+__global__ __launch_bounds__(NTHREADS) void gemm_bf16_kernel(P p, TileGrid tg, int nwg) {
   extern __shared__ __align__(16) bf16_t smem[];
-  int gorder, tm, tn;
-  if (!tg.decode(blockIdx.x, gorder, tm, tn) || p.skip()) return;
-  const typename P::GInfo gi = p.ginfo(gorder);
-  const int m0 = tm * TM, n0 = tn * TN;
+  if (p.skip()) return;
+  constexpr bool LOOP = P::PERSISTENT && INTERIOR;   // (the predicated code has no registers to spare for the loop either)
+  int vb = blockIdx.x;
+  do {
+    int gorder, tm, tn;
+    if (!tg.decode(vb, gorder, tm, tn)) continue;
+    const typename P::GInfo gi = p.ginfo(gorder);
+    const int m0 = tm * TM, n0 = tn * TN;
 
-  // wave w owns output rows (w/4)*128.., columns (w%4)*64..
-  f32x16_t acc[4][2];
+    // wave w owns output rows (w/4)*128.., columns (w%4)*64..
+    f32x16_t acc[4][2];
 #pragma unroll
-  for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < 4; ++i)
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+      for (int j = 0; j < 2; ++j)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+        for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  const bool inside = (m0 + TM <= p.M) && (n0 + TN <= p.N);
-  if (inside && p.kseg % TK == 0) main_loop<P, false>(p, gi, m0, n0, smem, acc);
-  else main_loop<P, true>(p, gi, m0, n0, smem, acc);
-  if (inside) epilogue<P, false>(p, gi, m0, n0, smem, acc);
-  else epilogue<P, true>(p, gi, m0, n0, smem, acc);
+    // The thread index is made opaque once per tile: everything a lane derives from it (LDS
+    // addresses, operand offsets, epilogue positions) is then recomputed per tile instead of
+    // being hoisted out of this loop, where it would stay live across both phases of every tile
+    // and push the kernel over its 256 registers.
+    int t = threadIdx.x;
+    asm volatile("" : "+v"(t));
+    if (INTERIOR) {   // no tile of this launch touches an edge
+      main_loop<P, false>(p, gi, m0, n0, smem, acc, t);
+      epilogue<P, false>(p, gi, m0, n0, smem, acc, t);
+    } else {
+      const bool inside = (m0 + TM <= p.M) && (n0 + TN <= p.N);
+      if (inside && p.kseg % TK == 0) main_loop<P, false>(p, gi, m0, n0, smem, acc, t);
+      else main_loop<P, true>(p, gi, m0, n0, smem, acc, t);
+      if (inside) epilogue<P, false>(p, gi, m0, n0, smem, acc, t);
+      else epilogue<P, true>(p, gi, m0, n0, smem, acc, t);
+    }
+    if (LOOP) __syncthreads();   // the next tile stages its operands in the LDS the epilogue transposed through
+  } while (LOOP && (vb += gridDim.x) < nwg);
 }
+
+int g_num_wg_slots = 0;   // workgroups of a persistent grid: the CU count, rounded down to a multiple of 8
 
 template <class P>
 hipError_t launch(hipStream_t s, const P& p, int G) {
   const TileGrid tg = TileGrid::make(G, p.M, p.N, TM, TN);
-  hipLaunchKernelGGL((gemm_bf16_kernel<P>), dim3(tg.num_wg()), dim3(NTHREADS), LDS_BYTES, s, p, tg);
+  const int nwg = tg.num_wg();
+  if (g_num_wg_slots < 8) return hipErrorNotInitialized;
+  if (p.M % TM == 0 && p.N % TN == 0 && p.kseg % TK == 0) {
+    const int grid = (P::PERSISTENT && nwg > g_num_wg_slots) ? g_num_wg_slots : nwg;
+    hipLaunchKernelGGL((gemm_bf16_kernel<P, true>), dim3(grid), dim3(NTHREADS), LDS_BYTES, s, p, tg, nwg);
+  } else {
+    hipLaunchKernelGGL((gemm_bf16_kernel<P, false>), dim3(nwg), dim3(NTHREADS), LDS_BYTES, s, p, tg, nwg);
+  }
   return hipGetLastError();
 }
 
 template <class P>
 hipError_t set_lds_attr() {
-  return hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_bf16_kernel<P>),
+  const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_bf16_kernel<P, true>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
+  if (e != hipSuccess) return e;
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_bf16_kernel<P, false>),
                              hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
 }
 
@@ -360,13 +402,20 @@ hipError_t set_lds_attr() {
 
 hipError_t init_gemm_bf16() {
   hipError_t e;
+  int dev = 0, cus = 0;
+  if ((e = hipGetDevice(&dev)) != hipSuccess) return e;
+  if ((e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev)) != hipSuccess) return e;
+  g_num_wg_slots = cus >= 8 ? cus / 8 * 8 : 8;
   if ((e = set_lds_attr<EncPolicy<bf16_t>>()) != hipSuccess) return e;
   if ((e = set_lds_attr<EncPolicy<bf16_t, int8_t>>()) != hipSuccess) return e;
   if ((e = set_lds_attr<DecPolicy<bf16_t>>()) != hipSuccess) return e;
   if ((e = set_lds_attr<DzPolicy<bf16_t>>()) != hipSuccess) return e;
-  if ((e = set_lds_attr<DWdecPolicy<bf16_t>>()) != hipSuccess) return e;
-  if ((e = set_lds_attr<DWencPolicy<bf16_t>>()) != hipSuccess) return e;
-  if ((e = set_lds_attr<DWencPolicy<bf16_t, int8_t>>()) != hipSuccess) return e;
+  if ((e = set_lds_attr<DWdecPolicy<bf16_t, false>>()) != hipSuccess) return e;
+  if ((e = set_lds_attr<DWdecPolicy<bf16_t, true>>()) != hipSuccess) return e;
+  if ((e = set_lds_attr<DWencPolicy<bf16_t, false>>()) != hipSuccess) return e;
+  if ((e = set_lds_attr<DWencPolicy<bf16_t, true>>()) != hipSuccess) return e;
+  if ((e = set_lds_attr<DWencPolicy<bf16_t, false, int8_t>>()) != hipSuccess) return e;
+  if ((e = set_lds_attr<DWencPolicy<bf16_t, true, int8_t>>()) != hipSuccess) return e;
   return hipSuccess;
 }
 
@@ -392,10 +441,11 @@ hipError_t launch_dz_bf16(hipStream_t s, Dims D, const DzArgs& a) {
                      a.lam_c_over_b, a.C, (bf16_t*)a.dpre, a.lam1_over_b, a.skip_flags, a.kcap};
   return launch(s, p, D.L);
 }
-hipError_t launch_dwdec_bf16(hipStream_t s, Dims D, const DWdecArgs& a) {
-  DWdecPolicy<bf16_t> p{D, D.F, D.d, D.B, D.F, D.d,
-                        (const bf16_t*)a.z, (const bf16_t*)a.d_yhat, (bf16_t*)a.W_dec, a.G, a.norms,
-                        (bf16_t*)a.dW_dec, AdamFuse{a.fuse.m, a.fuse.v, a.fuse.master, a.fuse.a}, a.skip_flags, a.kcap, 0};
+template <bool ADAM>
+static hipError_t launch_dwdec_mode(hipStream_t s, Dims D, const DWdecArgs& a) {
+  DWdecPolicy<bf16_t, ADAM> p{D, D.F, D.d, D.B, D.F, D.d,
+                              (const bf16_t*)a.z, (const bf16_t*)a.d_yhat, (bf16_t*)a.W_dec, a.G, a.norms,
+                              (bf16_t*)a.dW_dec, AdamFuse{a.fuse.m, a.fuse.v, a.fuse.master, a.fuse.a}, a.skip_flags, a.kcap, 0};
   // One launch per source layer: the tiles that share operand panels start together again at
   // every launch and stay in step along K, which keeps the panel reuse in the XCDs' L2s (same
   // run time as one long launch, but half the traffic to the fabric).
@@ -406,14 +456,18 @@ hipError_t launch_dwdec_bf16(hipStream_t s, Dims D, const DWdecArgs& a) {
   }
   return hipSuccess;
 }
-hipError_t launch_dwenc_bf16(hipStream_t s, Dims D, const DWencArgs& a, bool int8_x) {
-  if (int8_x) {
-    DWencPolicy<bf16_t, int8_t> p{D, D.d, D.F, D.B, D.d, D.F, (const int8_t*)a.x, (const bf16_t*)a.dpre,
+hipError_t launch_dwdec_bf16(hipStream_t s, Dims D, const DWdecArgs& a) {
+  return a.fuse.m ? launch_dwdec_mode<true>(s, D, a) : launch_dwdec_mode<false>(s, D, a);
+}
+template <bool ADAM, typename TA>
+static hipError_t launch_dwenc_mode(hipStream_t s, Dims D, const DWencArgs& a) {
+  DWencPolicy<bf16_t, ADAM, TA> p{D, D.d, D.F, D.B, D.d, D.F, (const TA*)a.x, (const bf16_t*)a.dpre,
                                   (bf16_t*)a.dW_enc, (bf16_t*)a.W_enc, AdamFuse{a.fuse.m, a.fuse.v, a.fuse.master, a.fuse.a}};
-    return launch(s, p, D.L);
-  }
-  DWencPolicy<bf16_t> p{D, D.d, D.F, D.B, D.d, D.F, (const bf16_t*)a.x, (const bf16_t*)a.dpre, (bf16_t*)a.dW_enc, (bf16_t*)a.W_enc, AdamFuse{a.fuse.m, a.fuse.v, a.fuse.master, a.fuse.a}};
   return launch(s, p, D.L);
+}
+hipError_t launch_dwenc_bf16(hipStream_t s, Dims D, const DWencArgs& a, bool int8_x) {
+  if (int8_x) return a.fuse.m ? launch_dwenc_mode<true, int8_t>(s, D, a) : launch_dwenc_mode<false, int8_t>(s, D, a);
+  return a.fuse.m ? launch_dwenc_mode<true, bf16_t>(s, D, a) : launch_dwenc_mode<false, bf16_t>(s, D, a);
 }
 
 }  // namespace clt

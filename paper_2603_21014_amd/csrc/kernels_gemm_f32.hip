@@ -107,13 +107,12 @@ hipError_t launch_dz_f32(hipStream_t s, Dims D, const DzArgs& a) {
                     a.lam_c_over_b, a.C, (float*)a.dpre, a.lam1_over_b, a.skip_flags, a.kcap};
   return launch(s, p, D.L);
 }
-hipError_t launch_dwdec_f32(hipStream_t s, Dims D, const DWdecArgs& a) {
-  DWdecPolicy<float> p{D, D.F, D.d, D.B, D.F, D.d,
-                       (const float*)a.z, (const float*)a.d_yhat, (float*)a.W_dec, a.G, a.norms,
-                       (float*)a.dW_dec, AdamFuse{a.fuse.m, a.fuse.v, a.fuse.master, a.fuse.a}, a.skip_flags, a.kcap, 0};
-  // One launch per source layer: the tiles that share operand panels start together again at
-  // every launch and stay in step along K, which keeps the panel reuse in the XCDs' L2s (same
-  // run time as one long launch, but half the traffic to the fabric).
+template <bool ADAM>
+static hipError_t launch_dwdec_mode(hipStream_t s, Dims D, const DWdecArgs& a) {
+  DWdecPolicy<float, ADAM> p{D, D.F, D.d, D.B, D.F, D.d,
+                             (const float*)a.z, (const float*)a.d_yhat, (float*)a.W_dec, a.G, a.norms,
+                             (float*)a.dW_dec, AdamFuse{a.fuse.m, a.fuse.v, a.fuse.master, a.fuse.a}, a.skip_flags, a.kcap, 0};
+  // one launch per source layer, like the bf16 path
   for (int l = 0; l < D.L; ++l) {
     p.p0 = packed_index(l, l, D.L);
     const hipError_t e = launch(s, p, D.L - l);
@@ -121,9 +120,17 @@ hipError_t launch_dwdec_f32(hipStream_t s, Dims D, const DWdecArgs& a) {
   }
   return hipSuccess;
 }
-hipError_t launch_dwenc_f32(hipStream_t s, Dims D, const DWencArgs& a) {
-  DWencPolicy<float> p{D, D.d, D.F, D.B, D.d, D.F, (const float*)a.x, (const float*)a.dpre, (float*)a.dW_enc, (float*)a.W_enc, AdamFuse{a.fuse.m, a.fuse.v, a.fuse.master, a.fuse.a}};
+hipError_t launch_dwdec_f32(hipStream_t s, Dims D, const DWdecArgs& a) {
+  return a.fuse.m ? launch_dwdec_mode<true>(s, D, a) : launch_dwdec_mode<false>(s, D, a);
+}
+template <bool ADAM>
+static hipError_t launch_dwenc_mode(hipStream_t s, Dims D, const DWencArgs& a) {
+  DWencPolicy<float, ADAM> p{D, D.d, D.F, D.B, D.d, D.F, (const float*)a.x, (const float*)a.dpre, (float*)a.dW_enc,
+                             (float*)a.W_enc, AdamFuse{a.fuse.m, a.fuse.v, a.fuse.master, a.fuse.a}};
   return launch(s, p, D.L);
+}
+hipError_t launch_dwenc_f32(hipStream_t s, Dims D, const DWencArgs& a) {
+  return a.fuse.m ? launch_dwenc_mode<true>(s, D, a) : launch_dwenc_mode<false>(s, D, a);
 }
 
 }  // namespace clt
