@@ -51,6 +51,16 @@ def test_bf16_several_tiles_and_segments():
     show("bf16 multi-tile", compare_step(w, g, o, TOL["bf16"]))
 
 
+@pytest.mark.parametrize("fused", [False, True])
+def test_bf16_more_interior_tiles_than_cus(fused):
+    """Every matrix extent is a multiple of the 256-tile and the launches hold more workgroup slots than the GPU has
+    CUs, empty slots included (encoder 5 groups x 72 tiles in 432 slots, decode 5 x 8, dW_dec up to 5 blocks x 36
+    tiles in 288 slots): the kernels without edge code walk their tiles in a loop, one workgroup per CU."""
+    w = S.scaled(S.WORKLOADS["gpt2"], L=5, d=512, F=4608, B=1024, k_active=32, seed=77)
+    g, o = run_both(w, fused=fused)
+    show(f"bf16 tile loop fused={fused}", compare_step(w, g, o, TOL["bf16"]))
+
+
 def test_bf16_outlier_inputs_llama_shaped_slice():
     """Config 3's input recipe (log-normal norms, outlier dims) at a slice of its shape."""
     w = S.scaled(S.WORKLOADS["llama1b"], L=3, d=2048, F=512, B=256)
