@@ -20,6 +20,7 @@
 //                quarter / second quarter / second half of a wave's block
 //   epi4(st, gi, pos, v, regs)    consumes 4 accumulators of one row, columns col..col+3
 //   PERSISTENT   the bf16 kernel runs one workgroup per CU over many tiles (else one per tile)
+//   UNIFORM_K    every group of a launch has the same K length
 #pragma once
 #include "common.h"
 
@@ -146,7 +147,7 @@ struct EncPolicy {
   __device__ const TA* a_seg(const GInfo& g, int) const { return x + (size_t)g.l * D.B * D.d; }
   __device__ const T* b_seg(const GInfo& g, int) const { return W_enc + (size_t)g.l * D.d * D.F; }
   static constexpr int EPI_BATCH = 8, EPI_BATCH_LATE = 8, EPI_BATCH_LAST = 8;
-  static constexpr bool PERSISTENT = true;
+  static constexpr bool PERSISTENT = true, UNIFORM_K = true;
   struct EpiRegs { float s; };
   __device__ void epi_begin(Epi& e, const GInfo& g, int col, bool ok) const {
     e.count = 0;
@@ -224,7 +225,7 @@ struct DecPolicy {
     return W_dec + (size_t)packed_index(s, g.lp, D.L) * D.F * D.d;
   }
   static constexpr int EPI_BATCH = 8, EPI_BATCH_LATE = 8, EPI_BATCH_LAST = 8;
-  static constexpr bool PERSISTENT = true;
+  static constexpr bool PERSISTENT = true, UNIFORM_K = false;
   struct EpiRegs {};
   __device__ void epi_begin(Epi& e, const GInfo& g, int col, bool ok) const {
     e.b = ok ? *reinterpret_cast<const float4*>(b_dec + (size_t)g.lp * D.d + col) : make_float4(0.f, 0.f, 0.f, 0.f);
@@ -266,7 +267,7 @@ struct DzPolicy {
     return W_dec + (size_t)packed_index(g.l, g.l + s, D.L) * D.F * D.d;
   }
   static constexpr int EPI_BATCH = 8, EPI_BATCH_LATE = 8, EPI_BATCH_LAST = 8;
-  static constexpr bool PERSISTENT = false;   // measured: 16.4 ms as a tile loop, 15.9 ms with one workgroup per tile
+  static constexpr bool PERSISTENT = false, UNIFORM_K = false;   // measured: 16.4 ms as a tile loop, 15.9 ms with one workgroup per tile
   struct EpiRegs { uint32_t c4; typename Elem<T>::Raw4 z4; };
   __device__ void epi_begin(Epi& e, const GInfo& g, int col, bool ok) const {
     float4 n4 = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -339,7 +340,7 @@ struct DWdecPolicy {
   __device__ const T* b_seg(const GInfo& g, int) const { return d_yhat + (size_t)g.lp * D.B * D.d; }
   // up to 16 registers per row group in flight: a short window while most accumulators are still live
   static constexpr int EPI_BATCH = 4, EPI_BATCH_LATE = 8, EPI_BATCH_LAST = 8;
-  static constexpr bool PERSISTENT = !ADAM;
+  static constexpr bool PERSISTENT = !ADAM, UNIFORM_K = true;
   struct EpiRegs { float Gf, nf; typename Elem<T>::Raw4 w; AdamRegs ad; };
   __device__ void epi_begin(Epi&, const GInfo&, int, bool) const {}
   __device__ void epi_load(EpiRegs& r, const GInfo& g, const EpiPos& pos) const {
@@ -382,7 +383,7 @@ struct DWencPolicy {
   __device__ const TA* a_seg(const GInfo& g, int) const { return x + (size_t)g.l * D.B * D.d; }
   __device__ const T* b_seg(const GInfo& g, int) const { return dpre + (size_t)g.l * D.B * D.F; }
   static constexpr int EPI_BATCH = 4, EPI_BATCH_LATE = 8, EPI_BATCH_LAST = 8;
-  static constexpr bool PERSISTENT = !ADAM;
+  static constexpr bool PERSISTENT = !ADAM, UNIFORM_K = true;
   struct EpiRegs { AdamRegs ad; typename Elem<T>::Raw4 w; };
   __device__ void epi_begin(Epi&, const GInfo&, int, bool) const {}
   __device__ void epi_load(EpiRegs& r, const GInfo& g, const EpiPos& pos) const {

@@ -381,7 +381,13 @@ hipError_t launch(hipStream_t s, const P& p, int G) {
   const int nwg = tg.num_wg();
   if (g_num_wg_slots < 8) return hipErrorNotInitialized;
   if (p.M % TM == 0 && p.N % TN == 0 && p.kseg % TK == 0) {
-    const int grid = (P::PERSISTENT && nwg > g_num_wg_slots) ? g_num_wg_slots : nwg;
+    // The tile loop gives every workgroup a fixed share (tiles i, i + grid, ...).  The shares are equal when all
+    // groups have the same K, or when every workgroup meets every round of groups equally often (the slots of
+    // a round are a multiple of the slots one pass of the grid covers; the snake order evens out the teams).
+    // Otherwise the hardware's dispatch of one workgroup per tile, longest groups first, balances better.
+    const int pass = g_num_wg_slots / 8;   // slots per XCD that one pass of the grid covers
+    const bool even_shares = P::UNIFORM_K || tg.per_xcd % pass == 0;
+    const int grid = (P::PERSISTENT && even_shares && nwg > g_num_wg_slots) ? g_num_wg_slots : nwg;
     hipLaunchKernelGGL((gemm_bf16_kernel<P, true>), dim3(grid), dim3(NTHREADS), LDS_BYTES, s, p, tg, nwg);
   } else {
     hipLaunchKernelGGL((gemm_bf16_kernel<P, false>), dim3(nwg), dim3(NTHREADS), LDS_BYTES, s, p, tg, nwg);
