@@ -56,10 +56,24 @@ __device__ __forceinline__ u32x4 i8x8_to_bf16x8(u32x2 q) {
   r[3] = i8x2_to_bf16x2((int)(int8_t)(q[1] >> 16), (int)(int8_t)(q[1] >> 24));
   return r;
 }
+// 8 operand elements as they come out of memory (int8: the codes in the first two dwords), and
+// their bf16 form.  The conversion happens when the tile goes to LDS, not at the load: arithmetic
+// on a loaded register is where the wait for that load lands, and the loads of a tile are meant
+// to stay in flight across the other group's compute phase.  (The predicated edge code still
+// zeroes out-of-range chunks right at the load; deferring that too costs it more registers
+// than it has.)
 template <typename TE> __device__ __forceinline__ u32x4 load8(const TE* p);
 template <> __device__ __forceinline__ u32x4 load8<bf16_t>(const bf16_t* p) { return ld16(p); }
 template <> __device__ __forceinline__ u32x4 load8<int8_t>(const int8_t* p) {
-  return i8x8_to_bf16x8(*reinterpret_cast<const u32x2*>(p));
+  const u32x2 q = *reinterpret_cast<const u32x2*>(p);
+  u32x4 r = {q[0], q[1], 0u, 0u};
+  return r;
+}
+template <typename TE> __device__ __forceinline__ u32x4 cook8(u32x4 raw);
+template <> __device__ __forceinline__ u32x4 cook8<bf16_t>(u32x4 raw) { return raw; }
+template <> __device__ __forceinline__ u32x4 cook8<int8_t>(u32x4 raw) {
+  u32x2 q = {raw[0], raw[1]};
+  return i8x8_to_bf16x8(q);
 }
 
 // ---------------------------------------------------------------------------
@@ -117,16 +131,19 @@ struct Stager {
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
         const int row = (lt >> 3) + 32 * i;
-        *reinterpret_cast<u32x4*>(lds + lds_off(row, c)) = r[i];
+        *reinterpret_cast<u32x4*>(lds + lds_off(row, c)) = cook8<TE>(r[i]);
       }
     } else {
       const int nb = lt & 31, kb = lt >> 5;
+      u32x4 q[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) q[i] = cook8<TE>(r[i]);
 #pragma unroll
       for (int n = 0; n < 8; ++n) {
         u32x4 o;
 #pragma unroll
         for (int w = 0; w < 4; ++w) {
-          const uint32_t lo = r[2 * w][n >> 1], hi = r[2 * w + 1][n >> 1];
+          const uint32_t lo = q[2 * w][n >> 1], hi = q[2 * w + 1][n >> 1];
           o[w] = (n & 1) ? __builtin_amdgcn_perm(hi, lo, 0x07060302u) : __builtin_amdgcn_perm(hi, lo, 0x05040100u);
         }
         *reinterpret_cast<u32x4*>(lds + lds_off(8 * nb + n, kb)) = o;
