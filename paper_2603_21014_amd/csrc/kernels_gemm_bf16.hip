@@ -59,9 +59,7 @@ __device__ __forceinline__ u32x4 i8x8_to_bf16x8(u32x2 q) {
 // 8 operand elements as they come out of memory (int8: the codes in the first two dwords), and
 // their bf16 form.  The conversion happens when the tile goes to LDS, not at the load: arithmetic
 // on a loaded register is where the wait for that load lands, and the loads of a tile are meant
-// to stay in flight across the other group's compute phase.  (The predicated edge code still
-// zeroes out-of-range chunks right at the load; deferring that too costs it more registers
-// than it has.)
+// to stay in flight across the other group's compute phase.
 template <typename TE> __device__ __forceinline__ u32x4 load8(const TE* p);
 template <> __device__ __forceinline__ u32x4 load8<bf16_t>(const bf16_t* p) { return ld16(p); }
 template <> __device__ __forceinline__ u32x4 load8<int8_t>(const int8_t* p) {
@@ -85,8 +83,8 @@ template <> __device__ __forceinline__ u32x4 cook8<int8_t>(u32x4 raw) {
 // Addresses are a wave-uniform base (tile origin, advanced along K by the
 // caller) plus one 32-bit per-lane byte offset that never changes, so a load
 // needs a single address register.  The EDGE variants predicate every chunk
-// and redirect out-of-range ones to the tensor base (always readable); they
-// return zeros there.
+// and redirect out-of-range ones to the tensor base (always readable); those
+// chunks reach LDS as zeros.
 // ---------------------------------------------------------------------------
 template <bool KC, typename TE>
 struct Stager {
@@ -106,10 +104,16 @@ struct Stager {
     }
   }
   // tile_base = operand + tile origin (row r0, k index k0), uniform
+  // EDGE: chunks outside the matrix are read from the tensor base and must reach LDS as zeros.  A
+  // K-contiguous operand remembers which chunks lie inside (bit i of `inside`) and zeroes the others
+  // when the tile goes to LDS, so that nothing is computed on the loaded registers here; a
+  // K-strided one zeroes them at once (its transposition mixes all 8 registers, and keeping the
+  // predicates until then costs the predicated code more registers than it has).
   template <bool EDGE>
-  __device__ __forceinline__ void load(u32x4 (&r)[8], const TE* seg_base, const TE* tile_base, int rows_left,
-                                       int k_left) const {
+  __device__ __forceinline__ void load(u32x4 (&r)[8], uint32_t& inside, const TE* seg_base, const TE* tile_base,
+                                       int rows_left, int k_left) const {
     const char* b = reinterpret_cast<const char*>(tile_base);
+    uint32_t in = 0;
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       const char* bi = b + (size_t)i * step;            // uniform
@@ -121,17 +125,22 @@ struct Stager {
         const TE* ptr = ok ? reinterpret_cast<const TE*>(bi + voff) : seg_base;
         const u32x4 v = load8<TE>(ptr);
         const u32x4 zero = {0u, 0u, 0u, 0u};
-        r[i] = ok ? v : zero;
+        if (KC) { r[i] = v; in |= (ok ? 1u : 0u) << i; }
+        else r[i] = ok ? v : zero;
       }
     }
+    if (EDGE && KC) inside = in;
   }
-  __device__ __forceinline__ void store(bf16_t* lds, const u32x4 (&r)[8], int lt) const {
+  template <bool EDGE>
+  __device__ __forceinline__ void store(bf16_t* lds, const u32x4 (&r)[8], uint32_t inside, int lt) const {
     if (KC) {
       const int c = lt & 7;
+      const u32x4 zero = {0u, 0u, 0u, 0u};
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
         const int row = (lt >> 3) + 32 * i;
-        *reinterpret_cast<u32x4*>(lds + lds_off(row, c)) = cook8<TE>(r[i]);
+        const u32x4 v = cook8<TE>(r[i]);
+        *reinterpret_cast<u32x4*>(lds + lds_off(row, c)) = (!EDGE || ((inside >> i) & 1u)) ? v : zero;
       }
     } else {
       const int nb = lt & 31, kb = lt >> 5;
@@ -180,10 +189,11 @@ __device__ __forceinline__ void main_loop(const P& p, const typename P::GInfo& g
   const size_t b_row0 = P::B_KC ? (size_t)n0 * p.ldb : (size_t)n0;
   const size_t a_kstep = P::A_KC ? 1 : (size_t)p.lda, b_kstep = P::B_KC ? 1 : (size_t)p.ldb;
   u32x4 rg[8];
+  uint32_t rg_inside = 0;   // EDGE, K-contiguous operand: which of the 8 chunks lie inside the matrix
 
   auto fetch = [&]() {
-    if (loads_a) sa.template load<EDGE>(rg, Aseg, Aseg + a_row0 + ld_k0 * a_kstep, p.M - m0, kseg - ld_k0);
-    else sb.template load<EDGE>(rg, Bseg, Bseg + b_row0 + ld_k0 * b_kstep, p.N - n0, kseg - ld_k0);
+    if (loads_a) sa.template load<EDGE>(rg, rg_inside, Aseg, Aseg + a_row0 + ld_k0 * a_kstep, p.M - m0, kseg - ld_k0);
+    else sb.template load<EDGE>(rg, rg_inside, Bseg, Bseg + b_row0 + ld_k0 * b_kstep, p.N - n0, kseg - ld_k0);
     ld_k0 += TK;
     if (ld_k0 >= kseg) {
       ld_k0 = 0;
@@ -196,8 +206,8 @@ __device__ __forceinline__ void main_loop(const P& p, const typename P::GInfo& g
   };
   auto stage = [&](int st) {
     bf16_t* base = smem + st * STAGE_ELEMS;
-    if (loads_a) sa.store(base, rg, lt);
-    else sb.store(base + 256 * TK, rg, lt);
+    if (loads_a) sa.template store<EDGE>(base, rg, rg_inside, lt);
+    else sb.template store<EDGE>(base + 256 * TK, rg, rg_inside, lt);
   };
 
   u32x4 fa[2][4], fb[2][2];
