@@ -446,7 +446,9 @@ __global__ __launch_bounds__(256) void topk_select_kernel(Dims D, const float* _
       *reinterpret_cast<uint32_t*>(cls + row * D.F + 4 * q) = c4;
     }
   }
-  if (tid == 0 && l0) atomicAdd(l0 + (int)(row / D.B), all ? D.F : (none ? 0 : k));
+  // every row selects the same number of entries, so one row per layer books the whole layer
+  // (a per-row add would send all B*L atomics of the launch to 16 addresses, one after the other)
+  if (tid == 0 && l0 && row % D.B == 0) atomicAdd(l0 + (int)(row / D.B), D.B * (all ? D.F : (none ? 0 : k)));
 }
 
 // ---- activation normalisation (Sec. 3.1): the factor of a layer is the mean L2 norm of its

@@ -40,9 +40,11 @@ __global__ void decode_decide_kernel(Dims D, const int32_t* __restrict__ l0, flo
   flags[2] = 1;
 }
 
-// One wavefront per (layer, token) row; lanes take 4 consecutive features per
-// pass, positions come from wave-wide exclusive scans of the per-lane counts.
+// One wavefront per (layer, token) row; lanes take 16 consecutive features per pass (two 8-byte
+// loads of class bytes: F is a multiple of 8, so a row start is 8-byte aligned), positions come
+// from wave-wide exclusive scans of the per-lane counts: 8 passes and 16 scans for 8192 features.
 // Active features fill the row's slots from the front, window-only features from the back.
+// z is read only where a group of 4 features holds an active one.
 __device__ __forceinline__ int wave_incl_scan(int v, int lane) {
 #pragma unroll
   for (int off = 1; off < 64; off <<= 1) {
@@ -65,29 +67,44 @@ __global__ __launch_bounds__(256) void compact_active_kernel(Dims D, const T* __
   int32_t* oi = g.idx + (size_t)row * g.stride;
   float* ov = g.val + (size_t)row * g.stride;
   int base = 0, base_w = 0;
-  for (int f0 = 0; f0 < D.F; f0 += 256) {
-    const int f = f0 + lane * 4;
-    uint32_t c4 = 0;
-    float4 z4 = make_float4(0.f, 0.f, 0.f, 0.f);
+  for (int f0 = 0; f0 < D.F; f0 += 1024) {
+    const int f = f0 + lane * 16;
+    uint32_t c[4] = {0u, 0u, 0u, 0u};
     if (f < D.F) {
-      c4 = *reinterpret_cast<const uint32_t*>(cr + f);
-      if (c4 & 0x01010101u) z4 = Elem<T>::load4(zr + f);
+      const uint2 lo = *reinterpret_cast<const uint2*>(cr + f);
+      c[0] = lo.x; c[1] = lo.y;
     }
-    const uint32_t a4 = c4 & 0x01010101u;                       // active
-    const uint32_t w4 = ((c4 >> 1) & 0x01010101u) & ~a4;        // in the window, not active
-    const int n = __popc(a4), nw = __popc(w4);
+    if (f + 8 < D.F) {
+      const uint2 hi = *reinterpret_cast<const uint2*>(cr + f + 8);
+      c[2] = hi.x; c[3] = hi.y;
+    }
+    uint32_t a[4], w[4];
+    int n = 0, nw = 0;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      a[j] = c[j] & 0x01010101u;                          // active
+      w[j] = ((c[j] >> 1) & 0x01010101u) & ~a[j];         // in the window, not active
+      n += __popc(a[j]);
+      nw += __popc(w[j]);
+    }
     const int incl = wave_incl_scan(n, lane), incl_w = wave_incl_scan(nw, lane);
     int pos = base + incl - n, pos_w = base_w + incl_w - nw;
-    const float zz[4] = {z4.x, z4.y, z4.z, z4.w};
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      if ((a4 >> (8 * i)) & 1u) {
-        if (pos < g.kcap) { oi[pos] = f + i; ov[pos] = zz[i]; }
-        ++pos;
-      }
-      if ((w4 >> (8 * i)) & 1u) {
-        if (pos_w < g.kcap) { oi[g.kcap - 1 - pos_w] = f + i; ov[g.kcap - 1 - pos_w] = 0.f; }
-        ++pos_w;
+    for (int j = 0; j < 4; ++j) {
+      if ((a[j] | w[j]) == 0u) continue;
+      float4 z4 = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (a[j]) z4 = Elem<T>::load4(zr + f + 4 * j);
+      const float zz[4] = {z4.x, z4.y, z4.z, z4.w};
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        if ((a[j] >> (8 * i)) & 1u) {
+          if (pos < g.kcap) { oi[pos] = f + 4 * j + i; ov[pos] = zz[i]; }
+          ++pos;
+        }
+        if ((w[j] >> (8 * i)) & 1u) {
+          if (pos_w < g.kcap) { oi[g.kcap - 1 - pos_w] = f + 4 * j + i; ov[g.kcap - 1 - pos_w] = 0.f; }
+          ++pos_w;
+        }
       }
     }
     base += __shfl(incl, 63, 64);
@@ -96,7 +113,11 @@ __global__ __launch_bounds__(256) void compact_active_kernel(Dims D, const T* __
   if (lane == 0) {
     g.counts[row] = base;
     g.counts_w[row] = base_w;
-    atomicMax(flags + 1, base + base_w);     // lists that collide make every gather kernel stand down
+    // longest list so far; lists that collide make every gather kernel stand down.  The value only
+    // grows, so a row that does not exceed what is already there (a stale read at worst costs an
+    // atomic that changes nothing) leaves the one hot address alone.
+    const int mine = base + base_w;
+    if (mine > *reinterpret_cast<volatile const int32_t*>(flags + 1)) atomicMax(flags + 1, mine);
   }
 }
 
