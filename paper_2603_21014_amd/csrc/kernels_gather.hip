@@ -355,14 +355,17 @@ __global__ __launch_bounds__(256) void fl_count_kernel(Dims D, const uint8_t* __
   o[0] = c[0]; o[1] = c[1]; o[2] = c[2]; o[3] = c[3];
 }
 
-// One workgroup per layer: layer-local exclusive scan over the features of the summed segment
-// counts; the segment counts are turned into each segment's first slot.
-__global__ __launch_bounds__(256) void fl_scan_kernel(Dims D, FeatureLists fl, const int32_t* __restrict__ flags) {
+// One workgroup of 1024 lanes per layer: layer-local exclusive scan over the features of the summed
+// segment counts; the segment counts are turned into each segment's first slot.  A lane owns a
+// run of consecutive features (8 at F = 8192, so neighbouring lanes share cache lines).
+constexpr int FL_SCAN_THREADS = 1024;
+__global__ __launch_bounds__(FL_SCAN_THREADS) void fl_scan_kernel(Dims D, FeatureLists fl,
+                                                                  const int32_t* __restrict__ flags) {
   if (!gather_selected(flags, fl.kcap)) return;
-  __shared__ int tot[256];
+  __shared__ int tot[FL_SCAN_THREADS];
   const int l = blockIdx.x, tid = threadIdx.x;
-  const int per = (D.F + 255) / 256;
-  const int f0 = tid * per, f1 = min(D.F, f0 + per);
+  const int per = (D.F + FL_SCAN_THREADS - 1) / FL_SCAN_THREADS;
+  const int f0 = min(D.F, tid * per), f1 = min(D.F, f0 + per);
   const size_t LF = (size_t)D.L * D.F;
   int sum = 0;
   for (int f = f0; f < f1; ++f) {
@@ -372,7 +375,7 @@ __global__ __launch_bounds__(256) void fl_scan_kernel(Dims D, FeatureLists fl, c
   }
   tot[tid] = sum;
   __syncthreads();
-  for (int off = 1; off < 256; off <<= 1) {              // inclusive scan of the 256 thread totals
+  for (int off = 1; off < FL_SCAN_THREADS; off <<= 1) {   // inclusive scan of the lane totals
     const int v = tid >= off ? tot[tid - off] : 0;
     __syncthreads();
     tot[tid] += v;
@@ -648,7 +651,7 @@ hipError_t launch_feature_lists(hipStream_t s, bool bf16, Dims D, const uint8_t*
   const int LF4 = D.L * D.F / 4;
   const dim3 grid((LF4 + 255) / 256, FL_SEGS);
   hipLaunchKernelGGL(fl_count_kernel, grid, dim3(256), 0, s, D, cls, fl, flags);
-  hipLaunchKernelGGL(fl_scan_kernel, dim3(D.L), dim3(256), 0, s, D, fl, flags);
+  hipLaunchKernelGGL(fl_scan_kernel, dim3(D.L), dim3(FL_SCAN_THREADS), 0, s, D, fl, flags);
   if (bf16)
     hipLaunchKernelGGL((fl_fill_kernel<bf16_t>), grid, dim3(256), 0, s, D, cls, (const bf16_t*)z, fl, flags);
   else
