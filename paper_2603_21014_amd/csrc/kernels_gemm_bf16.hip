@@ -481,11 +481,18 @@ static hipError_t launch_dwdec_mode(hipStream_t s, Dims D, const DWdecArgs& a) {
                               (bf16_t*)a.dW_dec, AdamFuse{a.fuse.m, a.fuse.v, a.fuse.master, a.fuse.a}, a.skip_flags, a.kcap, 0};
   // One launch per source layer: the tiles that share operand panels start together again at
   // every launch and stay in step along K, which keeps the panel reuse in the XCDs' L2s (same
-  // run time as one long launch, but half the traffic to the fabric).
-  for (int l = 0; l < D.L; ++l) {
+  // run time as one long launch, but half the traffic to the fabric).  Layers whose blocks hold
+  // fewer than 8 rounds of tiles for the CUs share a launch with the layers after them: a launch
+  // that ends on a partly filled round leaves CUs idle, and short launches do so often.
+  const int tiles_per_block = ((D.F + TM - 1) / TM) * ((D.d + TN - 1) / TN);
+  const int min_blocks = (8 * g_num_wg_slots + tiles_per_block - 1) / tiles_per_block;
+  for (int l = 0; l < D.L;) {
+    int l1 = l, blocks = 0;
+    do { blocks += D.L - l1; ++l1; } while (l1 < D.L && blocks < min_blocks);
     p.p0 = packed_index(l, l, D.L);
-    const hipError_t e = launch(s, p, D.L - l);
+    const hipError_t e = launch(s, p, blocks);
     if (e != hipSuccess) return e;
+    l = l1;
   }
   return hipSuccess;
 }
