@@ -42,6 +42,33 @@ def profiled_traffic_bytes(workload, kernel):
     return None
 
 
+def library_gemm_reference(w, dev, log):
+    """Context for the MFMA figures, not part of the step: what the vendor library (torch.matmul) sustains on this
+    very GPU for one plain bf16 GEMM of the decode's shape (M = tokens, N = d_model, K = 16 F: the longest group
+    of the triangular decode at L = 16) on random normal operands, measured after the timed region."""
+    import torch
+    M, N, Kd = w.B, w.d, 16 * w.F
+    g = torch.Generator(device=dev).manual_seed(1)
+    a = torch.randn((M, Kd), generator=g, device=dev, dtype=torch.float32).to(torch.bfloat16)
+    b = torch.randn((Kd, N), generator=g, device=dev, dtype=torch.float32).to(torch.bfloat16)
+    for _ in range(2):
+        torch.matmul(a, b)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record()
+    iters = 10
+    for _ in range(iters):
+        torch.matmul(a, b)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / iters
+    tf = 2.0 * M * N * Kd / (ms * 1e-3) / 1e12
+    log(f"vendor library bf16 GEMM {M}x{N}x{Kd}: {ms:.3f} ms, {tf:.0f} TFLOP/s")
+    del a, b
+    return {"what": "torch.matmul, bf16, random normal operands", "M": M, "N": N, "K": Kd, "ms": round(ms, 4),
+            "tflops": round(tf, 1)}
+
+
 def cpu_oracle_baseline(w, log):
     """The oracle as it stands on a bounded sample of the workload: full L and d,
     F/4 features and B/8 tokens (about 10-20 s of host time).  The contraction cost
@@ -158,6 +185,8 @@ def main():
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="llama1b")
+    ap.add_argument("--no-library-gemm", action="store_true",
+                    help="skip the vendor-library GEMM reference measured after the timed region")
     ap.add_argument("--decode-mode", default="dense", choices=["dense", "gather", "auto"],
                     help="dense GEMMs (default), the list-driven kernels of the sparse regime, or the device-side switch")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -276,6 +305,10 @@ def main():
         dst.copy_(src)
         torch.cuda.synchronize()
 
+    lib_gemm = None
+    if not args.no_library_gemm:
+        lib_gemm = library_gemm_reference(w, dev, log)
+
     cpu = None
     if not args.no_cpu_baseline:
         cpu = cpu_oracle_baseline(w, log)
@@ -289,7 +322,7 @@ def main():
                    "activation": f"topk{w.topk}" if w.topk else "jumprelu", "decode_mode": args.decode_mode},
         "step_dense_tflops": flop / (ms_per_step * 1e-3) / 1e12,
         "step_frac_of_bf16_mfma_peak": flop / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
-        "roofline": roof, "cpu_baseline": cpu, "kernels": kernels,
+        "roofline": roof, "cpu_baseline": cpu, "kernels": kernels, "library_gemm": lib_gemm,
     }
     print(json.dumps(out), flush=True)
 
