@@ -103,7 +103,7 @@ def _ptr(t, shape, dtype, name, optional=False):
 
 
 def make_config(L, d, F, B, dtype=DTYPE_BF16, input_format=INPUT_NATIVE, master_weights=False,
-                decode_mode=DECODE_DENSE, gather_density_threshold=0.005, C_=4.0, ste_bandwidth=0.05,
+                decode_mode=DECODE_DENSE, gather_density_threshold=0.004, C_=4.0, ste_bandwidth=0.05,
                 beta1=0.9, beta2=0.999, adam_eps=1e-8, log_threshold=False, topk=None):
     """topk: None for JumpReLU, else k of the TopK activation."""
     return clt_config(C.sizeof(clt_config), L, d, F, B, dtype, input_format, int(master_weights), decode_mode,
@@ -283,7 +283,7 @@ class CLTStep:
 
     def __init__(self, L, d, F, B, dtype="bf16", int8_inputs=False, master_weights=False, C_=4.0,
                  ste_bandwidth=0.05, beta1=0.9, beta2=0.999, adam_eps=1e-8, device="cuda:0", keep_pre=True,
-                 decode_mode=DECODE_DENSE, gather_density_threshold=0.005, matrix_grads=True, log_threshold=False,
+                 decode_mode=DECODE_DENSE, gather_density_threshold=0.004, matrix_grads=True, log_threshold=False,
                  topk=None):
         dt = DTYPE_BF16 if dtype == "bf16" else DTYPE_F32
         self.cfg = make_config(L, d, F, B, dt, INPUT_INT8_ROWSCALE if int8_inputs else INPUT_NATIVE,

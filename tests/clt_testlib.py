@@ -26,7 +26,7 @@ class GpuRun:
     """One forward/loss/backward/Adam pass of the HIP library; results as numpy."""
 
     def __init__(self, w: S.CLTWorkload, params, x, y, t=1, m=None, v=None, x_scale=None, y_scale=None,
-                 theta=None, decode_mode=1, gather_density_threshold=0.005, fused=False):
+                 theta=None, decode_mode=1, gather_density_threshold=0.004, fused=False):
         from paper_2603_21014_amd import binding as K
         dev = "cuda:0"
         T = torch.float32 if w.dtype == "f32" else torch.bfloat16
