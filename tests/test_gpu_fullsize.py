@@ -1,5 +1,6 @@
 """Full-size parity at the benchmark's workload (Llama-3.2-1B-shaped CLT, bf16,
-L=16, d=2048, F=8192, B=4096) in the launch configuration bench.py times.
+L=16, d=2048, F=8192, B=4096) in the launch configuration bench.py times, and at the
+GPT-2-small-shaped and Gemma-2-2B-shaped configurations (the latter with fp32 master weights).
 
 The naive oracle cannot run a whole step at this size in test time, so the
 comparison is on what it can compute one piece at a time, from the same seeded
@@ -36,18 +37,21 @@ class LazyBlocks:
 
 
 @pytest.mark.timeout(1200)
-@pytest.mark.parametrize("mode", ["unfused", "fused", "sparse_fused", "int8_fused"])
-def test_llama1b_shaped_step_against_sampled_oracle(mode):
+@pytest.mark.parametrize("workload,mode", [("llama1b", "unfused"), ("llama1b", "fused"), ("llama1b", "sparse_fused"),
+                                           ("llama1b", "int8_fused"), ("gpt2", "fused"), ("gemma2b", "fused")])
+def test_full_size_step_against_sampled_oracle(workload, mode):
     """unfused: clt_backward + clt_adam_step; fused: clt_backward_adam_step, the call bench.py times;
     sparse_fused: thresholds at 0.2 % density, forced gather mode (list-driven decode, dz and dW_dec);
-    int8_fused: x and y as int8 codes with per-(layer, token) scales (the oracle consumes the dequantised values)."""
+    int8_fused: x and y as int8 codes with per-(layer, token) scales (the oracle consumes the dequantised values).
+    gemma2b keeps fp32 master copies of the two weight matrices (217 GB of the GPU's memory in all)."""
     from paper_2603_21014_amd import binding as K
-    w = S.WORKLOADS["llama1b"]
+    w = S.WORKLOADS[workload]
     L, d, F, B = w.L, w.d, w.F, w.B
     dev = "cuda:0"
     T = torch.bfloat16
     p32 = S.make_params(w, device=dev)
     params = {k: (v.to(T) if k in ("W_enc", "W_dec") else v) for k, v in p32.items()}
+    master = {k: p32[k] for k in ("W_enc", "W_dec")} if w.master_weights else None
     del p32
     x32, y32 = S.make_inputs(w, device=dev)
     if mode == "sparse_fused":
@@ -64,9 +68,9 @@ def test_llama1b_shaped_step_against_sampled_oracle(mode):
     m = {k: torch.zeros(v.shape, dtype=torch.float32, device=dev) for k, v in params.items()}
     v_ = {k: torch.zeros(v.shape, dtype=torch.float32, device=dev) for k, v in params.items()}
     step = K.CLTStep(L, d, F, B, dtype="bf16", C_=w.C, ste_bandwidth=w.ste_eps, device=dev, keep_pre=False,
-                     matrix_grads=not fused, int8_inputs=int8,
+                     matrix_grads=not fused, int8_inputs=int8, master_weights=w.master_weights,
                      decode_mode=K.DECODE_GATHER if mode == "sparse_fused" else K.DECODE_DENSE)
-    print(f"running the GPU step ({mode})", flush=True)
+    print(f"running the GPU step ({workload}, {mode})", flush=True)
     W_dec_host = params["W_dec"].cpu()          # before Adam changes it
     W_enc_host = params["W_enc"].float().cpu().numpy()
     theta = params["theta"].cpu().numpy().astype(np.float64)
@@ -74,14 +78,14 @@ def test_llama1b_shaped_step_against_sampled_oracle(mode):
     loss = step.loss(y, w.lambda0, ys, to_host=True)
     d_yhat_gpu = K.clt_workspace_view(step.H, "d_yhat")
     if fused:
-        step.backward_adam_step(x, params, m, v_, 1, w.lr, None, xs)
+        step.backward_adam_step(x, params, m, v_, 1, w.lr, master, xs)
     else:
         step.backward(x, params)
     dpre_last_gpu = K.clt_workspace_view(step.H, "dpre")[L - 1].float().cpu().numpy()
     if int8:      # the buffer holds d pre times the row scale of x (what the encoder-weight gradient contracts with the codes)
         dpre_last_gpu = dpre_last_gpu / xs[L - 1].cpu().numpy()[:, None]
     if not fused:
-        step.adam_step(1, w.lr, params, m, v_)
+        step.adam_step(1, w.lr, params, m, v_, master)
     torch.cuda.synchronize()
     assert all(np.isfinite(loss))
     if mode == "sparse_fused":
@@ -134,7 +138,8 @@ def test_llama1b_shaped_step_against_sampled_oracle(mode):
         return n_cache[key]
 
     dW_g_all, m_g_all = step.grads.get("W_dec"), m["W_dec"]
-    for (l, lp, f0, j0) in [(0, 0, 16, 0), (0, 15, 4096, 1984), (7, 9, 8184, 640), (15, 15, 1000, 1024)]:
+    for (l, lp, f0, j0) in [(0, 0, 16, 0), (0, L - 1, F // 2, d - 64), (L // 2 - 1, L // 2 + 1, F - 8, d // 3 // 64 * 64),
+                            (L - 1, L - 1, 1000, d // 2)]:
         fs, js = slice(f0, f0 + 8), slice(j0, j0 + 64)
         ycol = np.tile(b_dec[lp][js][None, :], (B, 1))
         for l2 in range(lp + 1):
@@ -170,7 +175,7 @@ def test_llama1b_shaped_step_against_sampled_oracle(mode):
     dtheta = np.sum(np.where(window[l], -(theta[l][None, :] / w.ste_eps) * dz, 0.0), axis=0)
     assert rel_l2(step.grads["theta"][l].cpu().numpy(), dtheta) <= TOL, "dtheta[L-1]"
     assert rel_l2(step.grads["b_enc"][l].cpu().numpy(), dpre.sum(axis=0)) <= TOL, "db_enc[L-1]"
-    fs = slice(2048, 2048 + 64)
+    fs = slice(F // 4, F // 4 + 64)
     dWe = xh[l].astype(np.float64).T @ dpre[:, fs]
     if not fused:
         assert rel_l2(step.grads["W_enc"][l, :, fs].float().cpu().numpy(), dWe) <= TOL, "dW_enc[L-1] columns"
