@@ -133,7 +133,7 @@ def density_sweep(args, log):
                                  matrix_grads=False)
                  for name, mode in (("dense", K.DECODE_DENSE), ("gather", K.DECODE_GATHER))}
         t = 0
-        for rho in (0.00025, 0.0005, 0.001, 0.0025, 0.005, 0.01):
+        for rho in (0.00025, 0.0005, 0.001, 0.0025, 0.005, 0.01, 0.05):
             theta = S.theta_for_density(xdq, p32["W_enc"], p32["b_enc"], rho)
             row = {"density": rho}
             for name, st in steps.items():
