@@ -29,17 +29,61 @@ KERNEL_SYMBOL = {"decode_gemm": "gemm_bf16_kernel<DecPolicy>", "dz_gemm": "gemm_
 
 
 def profiled_traffic_bytes(workload, kernel):
-    """HBM-side bytes per launch of `kernel` from the committed rocprofv3 --pmc summary
-    (FETCH_SIZE + WRITE_SIZE, calibrated against a plain copy), or None."""
-    path = os.path.join(ROOT, "profiles", f"train_step_{workload}_hbm_traffic.md")
+    """HBM-side bytes per step of `kernel` from the committed rocprofv3 --pmc summary (FETCH_SIZE + WRITE_SIZE,
+    calibrated against a plain copy) and the name of that file, or (None, None).  Hardware counters cannot be
+    read from inside this process; the figure is the one of the profiled run, labelled with its source."""
+    rel = os.path.join("profiles", f"train_step_{workload}_hbm_traffic.md")
     try:
-        for line in open(path):
+        for line in open(os.path.join(ROOT, rel)):
             cells = [c.strip() for c in line.split("|")]
             if len(cells) > 3 and cells[1] == KERNEL_SYMBOL.get(kernel):
-                return (float(cells[2]) + float(cells[3])) * 1e9
+                return (float(cells[2]) + float(cells[3])) * 1e9, rel
     except (OSError, ValueError):
         pass
-    return None
+    return None, None
+
+
+def theta_for_density(x, W_enc, b_enc, rho):
+    """Input recipe of the density sweep: per-layer thresholds (constant over features) at which a fraction rho of
+    that layer's pre-activations lies above them, from a quantile of a subsample.  Chooses an input tensor only."""
+    import torch
+    L, F = x.shape[0], W_enc.shape[2]
+    out = torch.empty((L, F), device=x.device, dtype=torch.float32)
+    for l in range(L):
+        s = (x[l] @ W_enc[l] + b_enc[l]).reshape(-1)
+        if s.numel() > (1 << 22):
+            s = s[:: s.numel() // (1 << 22)]
+        kth = min(s.numel(), max(1, int(round(s.numel() * (1.0 - rho)))))
+        out[l] = torch.kthvalue(s, kth).values
+    return out
+
+
+def mfma_ceiling(dev, log, iters=40000):
+    """The MFMA-only loop of the contraction kernel (register operands, no memory traffic) on this GPU, on
+    all-zero and on pseudo-random bf16 operands: TFLOP/s from HIP events on the launch stream and the shader
+    clock from the kernel's own cycle counters.  The bf16 MFMA rate is limited by board power and the power
+    depends on the operand bits, so the two differ; the random-operand figure is the ceiling for real data."""
+    import torch
+    from paper_2603_21014_amd import binding as K
+    out = {}
+    counters = torch.zeros(4, dtype=torch.int64, device=dev)
+    for name, rnd in (("zero_operands", False), ("random_operands", True)):
+        K.clt_diag_mfma_loop(iters // 8, rnd, counters)      # warm-up
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        flop, hz = K.clt_diag_mfma_loop(iters, rnd, counters)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1)
+        c = counters.cpu().tolist()
+        clock = c[0] / c[1] * hz / 1e9 if c[1] > 0 else None
+        out[name] = {"tflops": round(flop / (ms * 1e-3) / 1e12, 1), "ms": round(ms, 3),
+                     "shader_clock_ghz": round(clock, 3) if clock else None}
+        log(f"MFMA-only loop, {name}: {out[name]['tflops']} TFLOP/s at {out[name]['shader_clock_ghz']} GHz")
+    out["what"] = ("v_mfma_f32_32x32x16_bf16 stream of the contraction kernel on register operands, 8 wavefronts per CU, "
+                   "no LDS or global memory")
+    return out
 
 
 def library_gemm_reference(w, dev, log):
@@ -99,7 +143,23 @@ def cpu_oracle_baseline(w, log):
     t_fb, t_adam = t1 - t0, t2 - t1
     full = t_fb * (w.F / fs) * (w.B / bs) + t_adam * (w.F / fs)
     log(f"cpu oracle sample: fwd+loss+bwd {t_fb:.2f}s, adam {t_adam:.2f}s -> full step est {full:.0f}s")
-    return {"value": w.B / full, "unit": "tokens/s", "cores": torch.get_num_threads(), "kind": "oracle",
+    # the oracle is numpy: its matmuls run on the BLAS pool's threads, everything else on one
+    threads = 1
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info() if p.get("user_api") == "blas"] or [1])
+    except Exception:
+        threads = int(os.environ.get("OMP_NUM_THREADS", "1") or 1)
+    model = "unknown"
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                model = line.split(":", 1)[1].strip()
+                break
+    except OSError:
+        pass
+    return {"value": w.B / full, "unit": "tokens/s", "cores": threads, "host_cpus": os.cpu_count(), "cpu_model": model,
+            "kind": "oracle",
             "sample": f"L={ws.L} d={ws.d} F={fs} (1/{w.F // fs}) B={bs} (1/{w.B // bs}) of {w.name}; "
                       f"measured {t_fb + t_adam:.1f}s, scaled by B*F (contractions) and F (Adam)"}
 
@@ -134,7 +194,7 @@ def density_sweep(args, log):
                  for name, mode in (("dense", K.DECODE_DENSE), ("gather", K.DECODE_GATHER))}
         t = 0
         for rho in (0.00025, 0.0005, 0.001, 0.0025, 0.005, 0.01, 0.05):
-            theta = S.theta_for_density(xdq, p32["W_enc"], p32["b_enc"], rho)
+            theta = theta_for_density(xdq, p32["W_enc"], p32["b_enc"], rho)
             row = {"density": rho}
             for name, st in steps.items():
                 params["theta"].copy_(theta)
@@ -189,6 +249,9 @@ def main():
                     help="skip the vendor-library GEMM reference measured after the timed region")
     ap.add_argument("--decode-mode", default="dense", choices=["dense", "gather", "auto"],
                     help="dense GEMMs (default), the list-driven kernels of the sparse regime, or the device-side switch")
+    ap.add_argument("--gather-density-threshold", type=float, default=0.004,
+                    help="auto mode: use the list-driven kernels at or below this mean active fraction (the measured "
+                         "whole-step break-even on an MI355X is 0.0043)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-timing", action="store_true",
                     help="skip the per-kernel HIP-event brackets (roofline entry becomes null)")
@@ -234,25 +297,27 @@ def main():
                      C_=w.C, ste_bandwidth=w.ste_eps, device=dev, keep_pre=w.lambda1 > 0,
                      log_threshold=w.log_threshold, topk=w.topk or None,
                      decode_mode={"dense": K.DECODE_DENSE, "gather": K.DECODE_GATHER, "auto": K.DECODE_AUTO}[args.decode_mode],
-                     gather_density_threshold=0.01, matrix_grads=False)
+                     gather_density_threshold=args.gather_density_threshold, matrix_grads=False)
     torch.cuda.synchronize()
     log(f"workload {w.name}: L={w.L} d={w.d} F={w.F} B={w.B}, inputs ready in {time.perf_counter() - t0:.1f}s, "
         f"{torch.cuda.memory_allocated() / 2**30:.1f} GiB allocated")
 
+    def one_step(t):
+        step.train_step(x, y, params, m, v_, t, w.lr, w.lambda0, master, xs, ys, lambda1=w.lambda1)
+
     t = 0
     for _ in range(args.warmup):
         t += 1
-        step.train_step(x, y, params, m, v_, t, w.lr, w.lambda0, master, xs, ys, lambda1=w.lambda1)
+        one_step(t)
     torch.cuda.synchronize()
     log("warmup done")
-    if not args.no_kernel_timing:
-        K.clt_profile_enable(step.H, True)
+    # timed region: exactly `steps` steps, no per-kernel event brackets, no host synchronisation inside
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     torch.cuda.synchronize()
     e0.record()
     for _ in range(args.steps):
         t += 1
-        step.train_step(x, y, params, m, v_, t, w.lr, w.lambda0, master, xs, ys, lambda1=w.lambda1)
+        one_step(t)
     e1.record()
     torch.cuda.synchronize()
     ms_per_step = e0.elapsed_time(e1) / args.steps
@@ -261,8 +326,20 @@ def main():
     log(f"{ms_per_step:.2f} ms/step, loss {loss[0]:.4g}, mean active features/token/layer {l0:.1f}")
 
     flop = w.dense_flop_per_step()
-    roof, kernels = None, None
+    roof, kernels, median_ms = None, None, None
     if not args.no_kernel_timing:
+        # second pass over the same steps: every kernel bracketed by HIP events on the launch stream (about 40
+        # event records per step, kept out of the timed region above), and each step timed on its own
+        K.clt_profile_enable(step.H, True)
+        evs = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
+        evs[0].record()
+        for i in range(args.steps):
+            t += 1
+            one_step(t)
+            evs[i + 1].record()
+        torch.cuda.synchronize()
+        per = sorted(evs[i].elapsed_time(evs[i + 1]) for i in range(args.steps))
+        median_ms = per[len(per) // 2] if len(per) % 2 else 0.5 * (per[len(per) // 2 - 1] + per[len(per) // 2])
         prof = K.clt_profile_query(step.H)
         K.clt_profile_enable(step.H, False)
         pair = 2.0 * w.B * w.F * w.d
@@ -285,14 +362,15 @@ def main():
         dom = max((k for k in kernels if k in GEMM_PAIRS or k in hbm_bytes), key=per_step)
         if dom in GEMM_PAIRS:
             ach = kernels[dom]["tflops"]
+            traffic, source = profiled_traffic_bytes(w.name, dom)
             roof = {"kernel": dom, "bound": "mfma", "achieved": ach, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                    "frac": round(ach / PEAK_BF16_TFLOPS, 4), "traffic": profiled_traffic_bytes(w.name, dom),
+                    "frac": round(ach / PEAK_BF16_TFLOPS, 4), "traffic": traffic, "traffic_source": source,
                     "avg_launch_ms": kernels[dom]["avg_ms"], "flop_per_launch": kernels[dom]["flop"]}
         else:
             ach = hbm_bytes[dom] / (kernels[dom]["avg_ms"] * 1e-3) / 1e9
             roof = {"kernel": dom, "bound": "hbm", "achieved": round(ach, 1), "peak": 8000.0, "unit": "GB/s",
-                    "frac": round(ach / 8000.0, 4), "traffic": None, "avg_launch_ms": kernels[dom]["avg_ms"],
-                    "bytes_per_launch": hbm_bytes[dom]}
+                    "frac": round(ach / 8000.0, 4), "traffic": None, "traffic_source": None,
+                    "avg_launch_ms": kernels[dom]["avg_ms"], "bytes_per_launch": hbm_bytes[dom]}
         for name, ent in sorted(kernels.items(), key=lambda kv: -kv[1]["avg_ms"] * kv[1]["launches_per_step"]):
             log(f"  {name:24s} {ent['avg_ms']:9.3f} ms x {ent['launches_per_step']:.0f}"
                 + (f"  {ent['tflops']:7.1f} TFLOP/s" if "tflops" in ent else ""))
@@ -305,9 +383,10 @@ def main():
         dst.copy_(src)
         torch.cuda.synchronize()
 
-    lib_gemm = None
+    lib_gemm = ceiling = None
     if not args.no_library_gemm:
         lib_gemm = library_gemm_reference(w, dev, log)
+        ceiling = mfma_ceiling(dev, log)
 
     cpu = None
     if not args.no_cpu_baseline:
@@ -319,10 +398,12 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": w.name, "L": w.L, "d_model": w.d, "features_per_layer": w.F, "tokens": w.B,
                    "decoder_blocks": w.P, "int8_inputs": w.int8_inputs, "master_weights": w.master_weights,
-                   "activation": f"topk{w.topk}" if w.topk else "jumprelu", "decode_mode": args.decode_mode},
+                   "activation": f"topk{w.topk}" if w.topk else "jumprelu", "decode_mode": args.decode_mode,
+                   "fused_adam": True},
+        "median_ms_per_step_profiled_pass": median_ms,
         "step_dense_tflops": flop / (ms_per_step * 1e-3) / 1e12,
         "step_frac_of_bf16_mfma_peak": flop / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
-        "roofline": roof, "cpu_baseline": cpu, "kernels": kernels, "library_gemm": lib_gemm,
+        "roofline": roof, "cpu_baseline": cpu, "kernels": kernels, "library_gemm": lib_gemm, "mfma_ceiling": ceiling,
     }
     print(json.dumps(out), flush=True)
 

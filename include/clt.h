@@ -8,8 +8,8 @@
  * all source layers l <= l',
  *     y_hat[l'] = sum_{l <= l'} z[l] W_dec[p(l,l')] + b_dec[l']                    (eq. 3)
  * trained on the objective of App. B (reconstruction + lambda0 * tanh sparsity
- * weighted by the decoder norm; the dead-feature term is not part of this
- * library) with Adam (App. C, Table 1).
+ * weighted by the decoder norm + lambda1 * dead-feature penalty, see clt_loss)
+ * with Adam (App. C, Table 1).
  *
  * Tensors (all DEVICE pointers owned by the caller, contiguous, row-major,
  * 16-byte aligned; the library never allocates, frees or keeps them):
@@ -19,8 +19,10 @@
  *   W_dec  [P,F,d]  T, P = L(L+1)/2 b_dec [L,d] float
  *   z, pre [L,B,F]  T               y_hat [L,B,d] float (always fp32)
  *   act_class [L,B,F] uint8: bit 0 = active (pre > theta), bit 1 = inside the
- *          straight-through window |pre - theta| < ste_bandwidth/2; both decided
- *          on the fp32 accumulator before any rounding.
+ *          straight-through window |pre - theta| < ste_bandwidth/2, bit 2 = below
+ *          the threshold (pre < theta strictly: where the dead-feature penalty of
+ *          App. B has a gradient); all three decided on the fp32 accumulator
+ *          before any rounding.  With the TopK activation only bit 0 is used.
  * Packed decoder: block p(l,l') = l*L - l(l-1)/2 + (l'-l), 0 <= l <= l' < L
  * (source-major: all decoders that leave source layer l are contiguous, which
  * is the "concatenation" whose row norm the sparsity term uses); each block is
@@ -164,11 +166,12 @@ int clt_loss(clt_handle* handle, void* stream,
              const void* pre, const float* theta,
              float lambda0, float lambda1, float* loss_dev, float* loss_host);
 
-/* Gradients of the objective evaluated by the preceding clt_loss, w.r.t. the
- * five learned tensors (grads->W_enc, W_dec in T; vectors float).  JumpReLU
- * passes gradient to pre where active; theta gets the rectangle-kernel
- * pseudo-gradient -(theta/eps) sum_b 1[in window] dz.  With lambda1 > 0 the
- * dead-feature term adds -(lambda1/B) n to d pre and +(lambda1/B) n to d theta
+/* Backward pass of the App. B objective through eq. 3 and eq. 1 (chain rule;
+ * the paper leaves it to autograd): gradients of the objective evaluated by the
+ * preceding clt_loss, w.r.t. the five learned tensors (grads->W_enc, W_dec in T;
+ * vectors float).  JumpReLU passes gradient to pre where active; theta gets the
+ * rectangle-kernel pseudo-gradient -(theta/eps) sum_b 1[in window] dz.  With
+ * lambda1 > 0 the dead-feature term adds -(lambda1/B) n to d pre and +(lambda1/B) n to d theta
  * for every entry with pre < theta, and its decoder-norm derivative to dW_dec.
  * With log_threshold the theta gradient is the one w.r.t. tau (times theta).
  * When the preceding clt_forward decoded through the active-feature lists, dz and
@@ -178,18 +181,20 @@ int clt_backward(clt_handle* handle, void* stream,
                  const void* W_dec, const void* z, const uint8_t* act_class,
                  const clt_tensors* grads);
 
-/* One Adam step (1-based step count t, bias correction on, eps outside the
- * square root, no weight decay) on all five tensors.  m and v hold float
- * moments for every tensor.  master: NULL, or fp32 master copies of W_enc and
+/* One Adam step (App. C Table 1: betas 0.9 / 0.999, learning rate 2e-4 there;
+ * 1-based step count t, bias correction on, eps outside the square root, no
+ * weight decay) on all five tensors.  m and v hold float moments for every
+ * tensor.  master: NULL, or fp32 master copies of W_enc and
  * W_dec (its vector members are ignored) that are updated and then rounded
  * into params. */
 int clt_adam_step(clt_handle* handle, void* stream, int64_t t, float lr,
                   const clt_tensors* params, const clt_tensors* grads,
                   const clt_tensors* m, const clt_tensors* v, const clt_tensors* master);
 
-/* clt_backward and clt_adam_step in one call, with the Adam update of W_enc and
- * W_dec fused into the epilogues of the two weight-gradient GEMMs (App. C Table 1
- * update rule on the fp32 accumulators): the matrix gradients are never stored
+/* clt_backward (App. B objective) and clt_adam_step (App. C Table 1) in one
+ * call, with the Adam update of W_enc and W_dec fused into the epilogues of the
+ * two weight-gradient GEMMs (same update rule, applied to the fp32
+ * accumulators): the matrix gradients are never stored
  * unless grads->W_enc / grads->W_dec are given, and the weight, moment and master
  * traffic of the optimiser runs under the contractions instead of after them.
  * theta and W_dec are taken from params.  grads->b_enc, theta, b_dec are required
@@ -202,7 +207,9 @@ int clt_backward_adam_step(clt_handle* handle, void* stream,
                            const clt_tensors* m, const clt_tensors* v, const clt_tensors* master);
 
 /* Device pointers into the workspace, for inspection by tests and tools:
- * which = 0 decoder norms [L,F] float; 1 d y_hat [L,B,d] T; 2 d pre [L,B,F] T;
+ * which = 0 decoder norms [L,F] float; 1 d y_hat [L,B,d] T; 2 d pre [L,B,F] T
+ * (with int8 inputs every row holds d pre times that row's x_scale: the form
+ * the encoder-weight gradient contracts with the integer codes);
  * 3 sparsity column sums G [L,F] float; 4 decode switch, 4 int32: {gather allowed by
  * the measured density, longest active list, path taken by the last forward
  * (1 dense, 2 gather), unused}; written by clt_forward in the gather and auto decode modes only.
@@ -218,6 +225,21 @@ int clt_workspace_view(const clt_handle* handle, int which, void** ptr, size_t* 
 int clt_profile_enable(clt_handle* handle, int on);
 int clt_profile_num_kernels(void);
 int clt_profile_query(clt_handle* handle, int kernel, const char** name, double* total_ms, int64_t* launches);
+
+/* Diagnostic, not part of the method: the MFMA instruction stream of the bf16
+ * contraction kernels (one workgroup of 8 wavefronts per compute unit, per
+ * iteration 32 v_mfma_f32_32x32x16_bf16 per wavefront) on operands held in
+ * registers, all zero or (random_operands != 0) pseudo-random bf16.  It gives
+ * the rate the matrix cores sustain on this board with no memory traffic at
+ * all, which depends on the operand content (board power limit).  Enqueues
+ * one kernel on `stream`; the caller times it.  counters_dev: device, 4 x
+ * uint64, 16-byte aligned; after the kernel [0] holds the shader cycles and
+ * [1] the ticks of the constant-rate counter that one wavefront spent in its
+ * loop (shader clock = [0] / [1] * wall_clock_hz).  *flop (host) receives the
+ * floating-point operations of the launch, *wall_clock_hz the counter's rate;
+ * both may be NULL. */
+int clt_diag_mfma_loop(void* stream, int iters, int random_operands, uint64_t* counters_dev,
+                       double* flop, double* wall_clock_hz);
 
 #ifdef __cplusplus
 }

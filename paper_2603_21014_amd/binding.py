@@ -25,7 +25,7 @@ DECODE_AUTO, DECODE_DENSE, DECODE_GATHER = 0, 1, 2
 EXPORTS = ("clt_workspace_bytes", "clt_init", "clt_destroy", "clt_last_error", "clt_forward",
            "clt_loss", "clt_backward", "clt_adam_step", "clt_backward_adam_step", "clt_workspace_view",
            "clt_profile_enable", "clt_profile_num_kernels", "clt_profile_query", "clt_norm_accumulate",
-           "clt_normalise")
+           "clt_normalise", "clt_diag_mfma_loop")
 
 
 class CLTError(RuntimeError):
@@ -69,6 +69,7 @@ def _load():
     lib.clt_profile_num_kernels.argtypes = []
     lib.clt_profile_query.argtypes = [vp, C.c_int, C.POINTER(C.c_char_p), C.POINTER(C.c_double),
                                       C.POINTER(C.c_int64)]
+    lib.clt_diag_mfma_loop.argtypes = [vp, C.c_int, C.c_int, vp, C.POINTER(C.c_double), C.POINTER(C.c_double)]
     for n in EXPORTS:
         if n != "clt_last_error":
             getattr(lib, n).restype = C.c_int
@@ -278,19 +279,32 @@ def clt_profile_query(H: Handle) -> dict:
     return out
 
 
+def clt_diag_mfma_loop(iters: int, random_operands: bool, counters: torch.Tensor):
+    """Enqueues the MFMA-only loop; returns (flop of the launch, rate of the constant-rate counter in Hz).
+    counters: int64 device tensor of 4 elements; [0] shader cycles, [1] constant-rate ticks of one wavefront."""
+    flop, hz = C.c_double(), C.c_double()
+    _check(_lib.clt_diag_mfma_loop(_stream(), int(iters), int(bool(random_operands)),
+                                   _ptr(counters, (4,), torch.int64, "counters"), C.byref(flop), C.byref(hz)))
+    return flop.value, hz.value
+
+
 class CLTStep:
     """A handle with its workspace and the per-step buffers of one configuration."""
 
     def __init__(self, L, d, F, B, dtype="bf16", int8_inputs=False, master_weights=False, C_=4.0,
                  ste_bandwidth=0.05, beta1=0.9, beta2=0.999, adam_eps=1e-8, device="cuda:0", keep_pre=True,
                  decode_mode=DECODE_DENSE, gather_density_threshold=0.004, matrix_grads=True, log_threshold=False,
-                 topk=None):
+                 topk=None, workspace=None):
+        """workspace: a uint8 device tensor of at least clt_workspace_bytes(config) bytes that the caller
+        owns (256-byte aligned); by default one is allocated here."""
         dt = DTYPE_BF16 if dtype == "bf16" else DTYPE_F32
         self.cfg = make_config(L, d, F, B, dt, INPUT_INT8_ROWSCALE if int8_inputs else INPUT_NATIVE,
                                master_weights, decode_mode, gather_density_threshold, C_, ste_bandwidth, beta1,
                                beta2, adam_eps, log_threshold, topk)
         self.device = torch.device(device)
-        ws = torch.empty(clt_workspace_bytes(self.cfg), dtype=torch.uint8, device=self.device)
+        ws = workspace
+        if ws is None:
+            ws = torch.empty(clt_workspace_bytes(self.cfg), dtype=torch.uint8, device=self.device)
         self.H = clt_init(self.cfg, ws)
         T = self.H.T
         P = L * (L + 1) // 2
@@ -306,6 +320,10 @@ class CLTStep:
         if matrix_grads:    # not needed by the fused backward + Adam path
             self.grads["W_enc"] = e(L, d, F)
             self.grads["W_dec"] = e(P, F, d)
+
+    def workspace_fill(self, byte: int):
+        """Overwrites the whole workspace (nothing in it is meant to outlive a step)."""
+        self.H.workspace.fill_(byte)
 
     def forward(self, x, params, x_scale=None):
         clt_forward(self.H, x, params["W_enc"], params["b_enc"], params["theta"], params["W_dec"], params["b_dec"],

@@ -10,7 +10,8 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(PKG, "csrc")
 BUILD = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "libclt.so")
-SOURCES = ["clt_api.hip", "kernels_gemm_f32.hip", "kernels_gemm_bf16.hip", "kernels_elementwise.hip", "kernels_gather.hip"]
+SOURCES = ["clt_api.hip", "kernels_gemm_f32.hip", "kernels_gemm_bf16.hip", "kernels_elementwise.hip", "kernels_gather.hip",
+           "kernels_diag.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
          # packed fp32 arithmetic is switched off for all device code
@@ -33,7 +34,7 @@ def _compile(src: str) -> str:
 
 def build(verbose: bool = True) -> str:
     os.makedirs(BUILD, exist_ok=True)
-    with ThreadPoolExecutor(max_workers=min(5, len(SOURCES))) as ex:
+    with ThreadPoolExecutor(max_workers=min(6, len(SOURCES))) as ex:
         objs = list(ex.map(_compile, SOURCES))
     cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]
     r = subprocess.run(cmd, capture_output=True, text=True)

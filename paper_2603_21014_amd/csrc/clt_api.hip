@@ -318,6 +318,27 @@ int clt_profile_query(clt_handle* h, int kernel, const char** name, double* tota
   return CLT_OK;
 }
 
+int clt_diag_mfma_loop(void* stream, int iters, int random_operands, uint64_t* counters_dev, double* flop,
+                       double* wall_clock_hz) {
+  if (!counters_dev || misaligned(counters_dev) || iters < 1 || iters > (1 << 24)) {
+    set_err(g_err, "clt_diag_mfma_loop: counters_dev must be a 16-byte aligned device pointer to 4 x uint64 and 1 <= iters <= 2^24");
+    return CLT_ERR_INVALID_ARG;
+  }
+  int dev = 0, cus = 0, khz = 0;
+  if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+      hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, dev) != hipSuccess || cus < 1) {
+    set_err(g_err, "clt_diag_mfma_loop: no usable HIP device");
+    (void)hipGetLastError();
+    return CLT_ERR_HIP;
+  }
+  const hipError_t e = launch_mfma_loop(static_cast<hipStream_t>(stream), cus, iters, random_operands != 0,
+                                        reinterpret_cast<unsigned long long*>(counters_dev));
+  if (e != hipSuccess) { set_err(g_err, "clt_diag_mfma_loop: launch failed: %s", hipGetErrorString(e)); return CLT_ERR_HIP; }
+  if (flop) *flop = (double)cus * 8.0 * (double)iters * 32.0 * 32768.0;
+  if (wall_clock_hz) *wall_clock_hz = 1e3 * (double)khz;
+  return CLT_OK;
+}
+
 const char* clt_last_error(const clt_handle* handle) { return handle ? handle->err : g_err; }
 
 int clt_workspace_view(const clt_handle* h, int which, void** ptr, size_t* bytes) {

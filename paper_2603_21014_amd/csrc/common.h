@@ -217,6 +217,11 @@ hipError_t launch_adam_matrix(hipStream_t s, bool bf16, size_t n, void* p, const
                               float* master_or_null, AdamScalars a);
 hipError_t launch_adam_vector(hipStream_t s, size_t n, float* p, const float* g, float* m, float* v, AdamScalars a);
 
+// Diagnostic (kernels_diag.hip): the contraction kernel's MFMA stream on register operands (zeros or
+// pseudo-random bf16), `workgroups` x 8 waves x iters x 32 v_mfma_f32_32x32x16_bf16; out[0] / out[1] = shader
+// cycles / constant-rate ticks that wave 0 spent in its loop
+hipError_t launch_mfma_loop(hipStream_t s, int workgroups, int iters, int random_operands, unsigned long long* out);
+
 // ---- active-feature gather paths (kernels_gather.hip) -------------------------
 // Device-side switch, 4 ints in the workspace:
 //   [0] 1 when the measured density allows the gather path (or it is forced)

@@ -12,18 +12,112 @@ MATS = ("W_enc", "W_dec")
 MASK_BAND = 1e-3     # pre-activations this close to a decision boundary may fall either way
 
 
+ELEM_RMS = 4.0       # weight of the local scale in the element-wise error bound (see max_elem)
+
+
 def rel_l2(a, b):
     a = np.asarray(a, np.float64)
     b = np.asarray(b, np.float64)
     return float(np.linalg.norm(a - b) / max(np.linalg.norm(b), 1e-30))
 
 
+def max_elem(a, b):
+    """Worst element of a against the reference b: max |a - b| / (|b| + ELEM_RMS * scale).
+
+    A norm over a whole tensor lets one wrong element, or one wrong row of a large matrix, hide; this bounds
+    every element on its own.  The size of an element's legitimate error is its own magnitude (rounding of the
+    stored value) plus the magnitude of the terms that were summed into it and into the values it was computed
+    from: an element near zero is a cancelled sum of terms that are not small.  That scale is taken from the
+    reference: the RMS of the tensor (per layer / decoder block: the last two dimensions), or the RMS of the
+    element's own row or column where that is larger -- tokens with heavy-tailed norms and outlier model
+    dimensions make whole rows and columns of the step's matrices tens of times larger than the rest, and their
+    rounding errors with them.  With bf16 operands (relative rounding 2^-9 each, a few such roundings per term)
+    a sum carries an error of about 0.5 % of that scale, with a tail of five to six times that over millions of
+    elements, hence the factor ELEM_RMS at the 2e-2 tolerance; a wrong element is off by about the scale itself.
+    RMS values are taken over the reference's non-zero entries: the masked tensors of the step (z, dpre in the
+    sparse regime) are exact zeros wherever the mask is off, and those zeros say nothing about the size of the
+    terms behind the entries that are kept.  A reference that is identically zero must be reproduced exactly."""
+    a = np.asarray(a, np.float64)
+    b = np.asarray(b, np.float64)
+    if b.size == 0:
+        return 0.0
+    if b.ndim < 2:
+        a, b = a.reshape(1, -1), b.reshape(1, -1)
+    sq, nzm = b * b, (b != 0)
+
+    def rms(axis):
+        n = nzm.sum(axis=axis, keepdims=True)
+        return np.sqrt(sq.sum(axis=axis, keepdims=True) / np.maximum(n, 1))
+
+    scale = np.maximum(rms((-2, -1)), np.maximum(rms(-1), rms(-2)))
+    den = np.abs(b) + ELEM_RMS * scale
+    err = np.abs(a - b)
+    exact = den == 0.0
+    if np.any(exact & (err != 0.0)):
+        return float("inf")
+    return float(np.max(np.where(exact, 0.0, err / np.where(exact, 1.0, den))))
+
+
+def both_errs(errs, name, a, b):
+    """Records the tensor-norm error and the worst-element error of a against b."""
+    errs[name] = rel_l2(a, b)
+    errs["elem:" + name] = max_elem(a, b)
+
+
+def theta_for_density(x, W_enc, b_enc, rho):
+    """Per-layer threshold (constant over features) at which a fraction `rho` of that layer's pre-activations
+    lies above it: puts a test in the sparse regime of Sec. 3.2.  It only chooses an input (the threshold tensor
+    handed to both sides), from a quantile of a subsample; neither side's result depends on how it was found."""
+    L, F = x.shape[0], W_enc.shape[2]
+    out = torch.empty((L, F), device=x.device, dtype=torch.float32)
+    for l in range(L):
+        s = (x[l] @ W_enc[l] + b_enc[l]).reshape(-1)
+        if s.numel() > (1 << 22):
+            s = s[:: s.numel() // (1 << 22)]
+        kth = min(s.numel(), max(1, int(round(s.numel() * (1.0 - rho)))))
+        out[l] = torch.kthvalue(s, kth).values
+    return out
+
+
 def to_np(t):
     return t.detach().float().cpu().numpy().astype(np.float64)
 
 
+GUARD_BYTES = 1024   # canary band on each side of every buffer the library writes
+GUARD_BYTE = 0xA5
+
+
+class GuardedBuffers:
+    """Device buffers with a band of canary bytes directly before and after each one.  The library gets
+    plain pointers and sizes, so a kernel that writes one element past a tensor (a ragged tile, a list
+    one slot too long) would otherwise land in a neighbouring allocation unnoticed."""
+
+    def __init__(self, dev):
+        self.dev = dev
+        self.items = []
+
+    def empty(self, name, shape, dtype):
+        n = int(np.prod(shape)) * torch.empty((), dtype=dtype).element_size()
+        raw = torch.full((GUARD_BYTES + n + GUARD_BYTES,), GUARD_BYTE, dtype=torch.uint8, device=self.dev)
+        self.items.append((name, raw, n))
+        return raw[GUARD_BYTES:GUARD_BYTES + n].view(dtype).view(tuple(shape))
+
+    def like(self, name, t, dtype=None):
+        out = self.empty(name, t.shape, dtype or t.dtype)
+        out.copy_(t)
+        return out
+
+    def check(self, after):
+        torch.cuda.synchronize()
+        for name, raw, n in self.items:
+            ok = bool((raw[:GUARD_BYTES] == GUARD_BYTE).all()) and bool((raw[GUARD_BYTES + n:] == GUARD_BYTE).all())
+            assert ok, f"canary bytes around '{name}' were overwritten by {after}"
+
+
 class GpuRun:
-    """One forward/loss/backward/Adam pass of the HIP library; results as numpy."""
+    """One forward/loss/backward/Adam pass of the HIP library; results as numpy.  Every buffer the
+    library may write (outputs, gradients, parameters and optimizer state, the workspace) sits between
+    canary bands that are checked after each call."""
 
     def __init__(self, w: S.CLTWorkload, params, x, y, t=1, m=None, v=None, x_scale=None, y_scale=None,
                  theta=None, decode_mode=1, gather_density_threshold=0.004, fused=False):
@@ -31,31 +125,45 @@ class GpuRun:
         dev = "cuda:0"
         T = torch.float32 if w.dtype == "f32" else torch.bfloat16
         TX = torch.int8 if w.int8_inputs else T
-        gp = {k: p.to(dev, T if k in MATS else torch.float32).contiguous() for k, p in params.items()}
+        gb = GuardedBuffers(dev)
+        gp = {k: gb.like("params." + k, p, T if k in MATS else torch.float32) for k, p in params.items()}
         if theta is not None:
-            gp["theta"] = theta.to(dev, torch.float32).contiguous()
-        zeros = lambda: {k: torch.zeros(p.shape, dtype=torch.float32, device=dev) for k, p in gp.items()}
-        gm = zeros() if m is None else {k: a.to(dev, torch.float32).contiguous() for k, a in m.items()}
-        gv = zeros() if v is None else {k: a.to(dev, torch.float32).contiguous() for k, a in v.items()}
+            gp["theta"].copy_(theta)
+        state = lambda name, src: {k: (gb.empty(f"{name}.{k}", p.shape, torch.float32).zero_() if src is None
+                                       else gb.like(f"{name}.{k}", src[k], torch.float32)) for k, p in gp.items()}
+        gm, gv = state("m", m), state("v", v)
         master = None
         if w.master_weights:
-            master = {k: params[k].to(dev, torch.float32).contiguous() for k in MATS}
+            master = {k: gb.like("master." + k, params[k], torch.float32) for k in MATS}
+        cfg = K.make_config(w.L, w.d, w.F, w.B, K.DTYPE_F32 if w.dtype == "f32" else K.DTYPE_BF16,
+                            K.INPUT_INT8_ROWSCALE if w.int8_inputs else K.INPUT_NATIVE, w.master_weights, decode_mode,
+                            gather_density_threshold, w.C, w.ste_eps, log_threshold=w.log_threshold, topk=w.topk or None)
+        ws = gb.empty("workspace", (K.clt_workspace_bytes(cfg),), torch.uint8)
         step = K.CLTStep(w.L, w.d, w.F, w.B, dtype=w.dtype, int8_inputs=w.int8_inputs,
                          master_weights=w.master_weights, C_=w.C, ste_bandwidth=w.ste_eps, device=dev,
                          decode_mode=decode_mode, gather_density_threshold=gather_density_threshold,
-                         log_threshold=w.log_threshold, topk=w.topk or None)
+                         log_threshold=w.log_threshold, topk=w.topk or None, workspace=ws)
+        for name in ("z", "pre", "act_class", "y_hat", "l0", "loss_dev"):
+            t_ = getattr(step, name)
+            setattr(step, name, gb.empty(name, t_.shape, t_.dtype))
+        step.grads = {k: gb.empty("grads." + k, g_.shape, g_.dtype) for k, g_ in step.grads.items()}
         xg, yg = x.to(dev, TX).contiguous(), y.to(dev, TX).contiguous()
         xs = x_scale.to(dev) if x_scale is not None else None
         ys = y_scale.to(dev) if y_scale is not None else None
+        self.x_scale = to_np(xs) if xs is not None else None
         step.forward(xg, gp, xs)
+        gb.check("clt_forward")
         self.loss = step.loss(yg, w.lambda0, ys, to_host=True, lambda1=w.lambda1, params=gp)
+        gb.check("clt_loss")
         self.norms = to_np(K.clt_workspace_view(step.H, "norms"))
         self.d_yhat = to_np(K.clt_workspace_view(step.H, "d_yhat"))
         self.G = to_np(K.clt_workspace_view(step.H, "G"))
         if fused:     # backward and Adam in one call, Adam inside the weight-gradient GEMM epilogues
             step.backward_adam_step(xg, gp, gm, gv, t, w.lr, master, xs)
+            gb.check("clt_backward_adam_step")
         else:
             step.backward(xg, gp, xs)
+            gb.check("clt_backward")
         self.dpre = to_np(K.clt_workspace_view(step.H, "dpre"))
         torch.cuda.synchronize()
         self.pre, self.z, self.y_hat = to_np(step.pre), to_np(step.z), to_np(step.y_hat)
@@ -67,12 +175,14 @@ class GpuRun:
         self.grads = {k: to_np(g) for k, g in step.grads.items()}
         if not fused:
             step.adam_step(t, w.lr, gp, gm, gv, master)
+            gb.check("clt_adam_step")
         torch.cuda.synchronize()
         self.new_params = {k: to_np(p) for k, p in gp.items()}
         self.new_m = {k: to_np(a) for k, a in gm.items()}
         self.new_v = {k: to_np(a) for k, a in gv.items()}
         self.new_master = {k: to_np(a) for k, a in master.items()} if master else None
         self.step = step
+        self.device_state = (gp, gm, gv, master)
 
 
 class OracleRun:
@@ -130,14 +240,14 @@ def compare_step(w, g: GpuRun, o: OracleRun, tol, check_adam=True):
     assert ((g.below == (pre_o < theta[:, None, :])) | band | bool(w.topk)).all(), "below-threshold mask differs outside the band"
     assert not (g.below & g.active).any()
     assert (g.l0 == g.active.sum(axis=(1, 2))).all(), "l0_per_layer does not count the active mask"
-    errs["pre"] = rel_l2(g.pre, pre_o)
-    errs["z"] = rel_l2(g.z, o.fwd["z"])
-    errs["norms"] = rel_l2(g.norms, o.n)
+    both_errs(errs, "pre", g.pre, pre_o)
+    both_errs(errs, "z", g.z, o.fwd["z"])
+    both_errs(errs, "norms", g.norms, o.n)
     for lp in range(L):
-        errs[f"y_hat[{lp}]"] = rel_l2(g.y_hat[lp], o.fwd["y_hat"][lp])
+        both_errs(errs, f"y_hat[{lp}]", g.y_hat[lp], o.fwd["y_hat"][lp])
     for i, name in enumerate(("loss", "L_rec", "L_sp", "L_dead")):
         errs[name] = abs(g.loss[i] - o.loss[i]) / max(abs(o.loss[i]), 1e-30)
-    errs["d_yhat"] = rel_l2(g.d_yhat, o.bwd["d_yhat"])
+    both_errs(errs, "d_yhat", g.d_yhat, o.bwd["d_yhat"])
     # Column sums of the objective's decoder-norm derivative.  z sech^2(C z n) amplifies a relative
     # error of z by about 2 C z n, so with bf16 storage the reference is the oracle's sum over the
     # oracle's z rounded the way it is stored (the dead-feature part is linear and needs no such care).
@@ -146,15 +256,15 @@ def compare_step(w, g: GpuRun, o: OracleRun, tol, check_adam=True):
         z_r = torch.from_numpy(o.fwd["z"]).to(torch.bfloat16).double().numpy()
         G_ref = G_ref - O.sparsity_norm_sums(o.fwd["z"], o.n, w.lambda0, w.C) \
             + O.sparsity_norm_sums(z_r, o.n, w.lambda0, w.C)
-    errs["G"] = rel_l2(g.G, G_ref)
-    if not w.int8_inputs:      # with int8 inputs the buffer holds dpre times the row scale of x
-        errs["dpre"] = rel_l2(g.dpre, o.bwd["dpre"])
+    both_errs(errs, "G", g.G, G_ref)
+    # with int8 inputs the buffer holds dpre times the row scale of x (what dW_enc contracts with the codes)
+    both_errs(errs, "dpre", g.dpre / g.x_scale[:, :, None] if w.int8_inputs else g.dpre, o.bwd["dpre"])
     for k in ("W_enc", "b_enc", "theta", "b_dec"):
         if k == "theta" and w.topk:
             continue                                     # exactly zero on both sides (asserted above)
-        errs["d" + k] = rel_l2(g.grads[k], o.bwd["d" + k])
+        both_errs(errs, "d" + k, g.grads[k], o.bwd["d" + k])
     for p in range(O.num_blocks(L)):
-        errs[f"dW_dec[{p}]"] = rel_l2(g.grads["W_dec"][p], o.bwd["dW_dec"][p])
+        both_errs(errs, f"dW_dec[{p}]", g.grads["W_dec"][p], o.bwd["dW_dec"][p])
     bad = {k: e for k, e in errs.items() if not e <= tol}
     assert not bad, f"parity failures (tol {tol}): {bad}"
     if check_adam:

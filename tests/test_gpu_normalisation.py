@@ -8,7 +8,7 @@ import torch
 from oracle import clt_oracle as O
 from workloads import clt_synth as S
 
-from clt_testlib import GpuRun, OracleRun, compare_step, to_np
+from clt_testlib import GpuRun, OracleRun, compare_step, theta_for_density, to_np
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -117,7 +117,7 @@ def test_train_step_on_normalised_int8_cache():
 
     params = S.make_params(w)
     # thresholds for the normalised scale: a fraction of the features active
-    theta = S.theta_for_density(torch.from_numpy(xo).float(), params["W_enc"], params["b_enc"], 0.05)
+    theta = theta_for_density(torch.from_numpy(xo).float(), params["W_enc"], params["b_enc"], 0.05)
     g = GpuRun(w, params, qx, qy, x_scale=fx.cpu(), y_scale=fy.cpu(), theta=theta)
     o = OracleRun(w, params, x, y, gpu_active=g.active, gpu_window=g.window, theta=theta, x_np=xo, y_np=yo,
                   gpu_below=g.below)

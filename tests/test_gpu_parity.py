@@ -9,7 +9,7 @@ import torch
 from oracle import clt_oracle as O
 from workloads import clt_synth as S
 
-from clt_testlib import GpuRun, OracleRun, compare_step, rel_l2, run_both, to_np
+from clt_testlib import GpuRun, OracleRun, compare_step, rel_l2, run_both, theta_for_density, to_np
 
 pytestmark = pytest.mark.gpu
 
@@ -283,6 +283,39 @@ def test_topk_activation_full_step(dtype, L, d, F, B, k):
         show(f"topk {dtype} F{F} k{k} fused={fused}", compare_step(w, g, o, TOL[dtype]))
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("F,k", [(2056, 61), (4096, 1), (8192, 61), (8192, 64), (8192, 8192), (8200, 67), (16384, 1),
+                                 (16384, 61), (16384, 64), (16384, 16384)])
+def test_topk_wide_rows(dtype, F, k):
+    """Rows wider than 2048 features: 2048 < F <= 8192 keeps the row in registers (eight float4 per lane, with
+    padding lanes when F is not a multiple of 1024), F > 8192 re-reads the row in every radix pass.  Two token rows
+    are built to tie at the k-th value across more than one 256-lane round of the selection: an all-zero input row
+    (every pre-activation equals the bias, the first k features win) and, in layer 1, encoder columns that repeat
+    with a period of 1024 features (each value occurs F/1024 or more times, once per round; the copies are the same
+    sum of the same products in the same order, so they tie exactly, and with k not a multiple of the repeat count
+    the k-th value's copies are selected only in part)."""
+    L, d, B = 2, 64, 40
+    w = S.scaled(S.WORKLOADS["tiny"], dtype=dtype, L=L, d=d, F=F, B=B, seed=95 + F, topk=k, k_active=8)
+    params = S.make_params(w)
+    period = 1024
+    params["W_enc"][1] = params["W_enc"][1][:, :period].repeat(1, (F + period - 1) // period)[:, :F]
+    x, y = S.make_inputs(w)
+    x[:, 3, :] = 0.0
+    g = GpuRun(w, params, x, y, fused=True)
+    assert (g.l0 == k * B).all() and (g.active.sum(axis=2) == k).all()
+    assert g.active[:, 3, :k].all() and not g.active[:, 3, k:].any()
+    o = OracleRun(w, params, x, y, gpu_active=g.active)
+    # among exact copies the lower feature index wins: a copy is selected only if the copy one period below it is
+    partial = False
+    for lo in range(period, F, period):
+        n = min(period, F - lo)
+        upper, lower = g.active[1][:, lo:lo + n], g.active[1][:, lo - period:lo - period + n]
+        assert not (upper & ~lower).any(), "tie order among equal values"
+        partial |= bool((lower & ~upper).any())
+    assert partial or k == F or k % (F // period) == 0, "no row had a tie group cut by the k-th value"
+    show(f"topk wide {dtype} F{F} k{k}", compare_step(w, g, o, TOL[dtype]))
+
+
 def test_topk_limits_and_ties():
     """k = 0 (nothing), k = F (everything, the linear model) and a zero input row, whose pre-activations are all
     equal to the bias: the first k features by index are selected."""
@@ -378,7 +411,7 @@ def test_seeded_shape_and_mode_sweep(i, L, d, F, B):
 def sparse_theta(w, rho):
     params = S.make_params(w)
     x, _ = S.make_inputs(w)
-    return S.theta_for_density(x, params["W_enc"], params["b_enc"], rho)
+    return theta_for_density(x, params["W_enc"], params["b_enc"], rho)
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
@@ -486,6 +519,47 @@ def test_auto_switch_follows_measured_density():
     kcap = (int(8.0 * 0.02 * w.F) + 64 + 7) // 8 * 8
     assert g.decode_switch[0] == 1 and g.decode_switch[1] > kcap and g.decode_switch[2] == 1
     show("auto -> dense fallback", compare_step(w, g, o, TOL["bf16"]))
+
+
+def test_restored_state_reproduces_the_step_bitwise():
+    """Two fused steps from a saved copy of (parameters, moments) against the same two steps after restoring that
+    copy into the same buffers: every bit of the state and of the loss must come out the same (the step keeps no
+    hidden state in its workspace between calls, and the dense path has a fixed summation order)."""
+    from paper_2603_21014_amd import binding as K
+    w = S.scaled(S.WORKLOADS["gpt2"], L=3, d=256, F=520, B=300, seed=62, master_weights=True)
+    dev = "cuda:0"
+    params = S.make_params(w)
+    x, y = (t.to(dev, torch.bfloat16) for t in S.make_inputs(w))
+    gp = {k: p.to(dev, torch.bfloat16 if k in ("W_enc", "W_dec") else torch.float32) for k, p in params.items()}
+    gm = {k: torch.zeros(p.shape, dtype=torch.float32, device=dev) for k, p in gp.items()}
+    gv = {k: torch.zeros(p.shape, dtype=torch.float32, device=dev) for k, p in gp.items()}
+    master = {k: params[k].to(dev) for k in ("W_enc", "W_dec")}
+    step = K.CLTStep(w.L, w.d, w.F, w.B, dtype="bf16", master_weights=True, C_=w.C, ste_bandwidth=w.ste_eps,
+                     matrix_grads=False)
+    step.train_step(x, y, gp, gm, gv, 1, w.lr, w.lambda0, master)          # some history in the moments
+    state = [gp, gm, gv, master]
+    saved = [{k: t.clone() for k, t in s.items()} for s in state]
+
+    def two_steps():
+        losses = []
+        for t in (2, 3):
+            step.train_step(x, y, gp, gm, gv, t, w.lr, w.lambda0, master)
+            losses.append(step.loss_dev.cpu().clone())
+        return losses, [{k: t.clone() for k, t in s.items()} for s in state]
+
+    loss_a, end_a = two_steps()
+    step.workspace_fill(0xCD)                                            # nothing may survive in the workspace
+    for s, c in zip(state, saved):
+        for k in s:
+            s[k].copy_(c[k])
+    loss_b, end_b = two_steps()
+    torch.cuda.synchronize()
+    for a, b in zip(loss_a, loss_b):
+        assert torch.equal(a, b)
+    for sa, sb in zip(end_a, end_b):
+        for k in sa:
+            assert torch.equal(sa[k], sb[k]), k
+    assert not torch.equal(end_a[0]["W_dec"], saved[0]["W_dec"])
 
 
 def test_rerun_is_bitwise_deterministic():

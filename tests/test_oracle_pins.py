@@ -332,6 +332,69 @@ def test_tie_break_only_inside_band():
         O.jumprelu(pre, theta, tie_break=np.array([[[True, False]]]), band=1e-3)
 
 
+def test_window_tie_break_only_inside_band():
+    """Hand-made distances to the window edge eps/2 = 0.05: well inside, just inside the edge, just outside it,
+    well outside.  A forced decision is taken only for the two entries within the band around the edge, changes
+    the threshold gradient by exactly those entries' terms, and is refused anywhere else."""
+    theta = np.array([[0.2, 0.2, 0.2, 0.2]])
+    pre = np.array([[[0.21, 0.2496, 0.1497, 0.4]]])          # |pre - theta| = 0.01, 0.0496, 0.0503, 0.2
+    eps, band = 0.1, 1e-3
+    assert O.ste_window(pre, theta, eps).tolist() == [[[True, True, False, False]]]
+    forced = np.array([[[True, False, True, False]]])         # both edge entries flipped
+    assert O.ste_window(pre, theta, eps, tie_break=forced, band=band).tolist() == forced.tolist()
+    for bad in ([[[False, True, False, False]]], [[[True, True, False, True]]]):     # flips outside the band
+        with pytest.raises(ValueError):
+            O.ste_window(pre, theta, eps, tie_break=np.array(bad), band=band)
+    with pytest.raises(ValueError):                           # the same edge flip with a band too narrow to hold it
+        O.ste_window(pre, theta, eps, tie_break=forced, band=1e-4)
+    # through backward: d theta = -(theta/eps) * (sum of dz over the window), so the forced window moves it by
+    # -(theta/eps) * (dz[entry 2] - dz[entry 1]) and nothing else changes
+    rng = np.random.default_rng(35)
+    L, d, F, B = 1, 3, 4, 1
+    p = rand_problem(rng, L, d, F, B, theta=0.2)
+    fwd = {"pre": pre, "active": pre > theta[:, None, :], "z": np.where(pre > theta[:, None, :], pre, 0.0)}
+    fwd["y_hat"] = O.decode(fwd["z"], p["W_dec"], p["b_dec"])
+    own = O.backward(p["x"], p["y"], theta, p["W_dec"], fwd, 1.0, 2.0, eps)
+    flip = O.backward(p["x"], p["y"], theta, p["W_dec"], fwd, 1.0, 2.0, eps, window_tie_break=forced, band=band)
+    dz = own["dz"][0, 0]
+    np.testing.assert_allclose(flip["dtheta"][0] - own["dtheta"][0],
+                               -(0.2 / eps) * np.array([0.0, -dz[1], dz[2], 0.0]), rtol=1e-12, atol=1e-15)
+    for k in ("dW_enc", "db_enc", "dW_dec", "db_dec", "dpre"):
+        assert (flip[k] == own[k]).all(), k
+
+
+@pytest.mark.parametrize("inf", [np.inf, -np.inf])
+def test_infinite_threshold_has_zero_threshold_gradient(inf):
+    """theta = +inf (nothing active, eq. 1 reduces to z = 0) and theta = -inf (JumpReLU is the identity, the linear
+    model): no pre-activation is within eps/2 of the threshold, so the rectangle kernel is zero everywhere and the
+    threshold pseudo-gradient is exactly 0 -- a sum over an empty set, not (theta/eps) times an empty sum, which
+    would be inf * 0.  Every other gradient stays finite; at -inf they are those of the linear model."""
+    rng = np.random.default_rng(36)
+    L, d, F, B = 2, 3, 5, 4
+    p = rand_problem(rng, L, d, F, B)
+    theta = np.full((L, F), inf)
+    fwd = O.forward(p["x"], p["W_enc"], p["b_enc"], theta, p["W_dec"], p["b_dec"])
+    gr = O.backward(p["x"], p["y"], theta, p["W_dec"], fwd, 1.0, 2.0, 0.1)
+    assert not gr["window"].any()
+    assert (gr["dtheta"] == 0.0).all()
+    for k in ("dW_enc", "db_enc", "dW_dec", "db_dec"):
+        assert np.isfinite(gr[k]).all(), k
+    if inf > 0:
+        assert not fwd["active"].any() and not gr["dW_enc"].any() and not gr["db_enc"].any()
+    else:
+        assert fwd["active"].all() and (fwd["z"] == fwd["pre"]).all()
+        assert (gr["dpre"] == gr["dz"]).all()
+        # the linear model's encoder-bias gradient by central differences (no mask can flip)
+        def loss_at(b_enc):
+            f = O.forward(p["x"], p["W_enc"], b_enc, theta, p["W_dec"], p["b_dec"])
+            return O.loss_terms(f["y_hat"], p["y"], f["z"], O.decoder_norms(p["W_dec"], L), 1.0, 2.0)[0]
+        h = 1e-6
+        for (l, f) in ((0, 0), (1, 3)):
+            bp, bm = p["b_enc"].copy(), p["b_enc"].copy()
+            bp[l, f] += h; bm[l, f] -= h
+            assert abs((loss_at(bp) - loss_at(bm)) / (2 * h) - gr["db_enc"][l, f]) < 1e-6 * max(1.0, abs(gr["db_enc"][l, f]))
+
+
 # ---------------------------------------------------------------- Adam
 def test_adam_first_step_closed_form():
     rng = np.random.default_rng(41)

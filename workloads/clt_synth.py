@@ -159,18 +159,3 @@ def quantize_rows_int8(t: torch.Tensor):
     s = torch.where(absmax > 0, absmax / 127.0, torch.ones_like(absmax))
     q = torch.clamp(torch.round(t / s[:, :, None]), -127, 127).to(torch.int8)
     return q, s.to(torch.float32)
-
-
-def theta_for_density(x: torch.Tensor, W_enc: torch.Tensor, b_enc: torch.Tensor, rho: float):
-    """Per-layer threshold (constant over features) at which a fraction `rho`
-    of that layer's pre-activations is above it; used by the density sweep."""
-    L = x.shape[0]
-    F = W_enc.shape[2]
-    out = torch.empty((L, F), device=x.device, dtype=torch.float32)
-    for l in range(L):
-        s = (x[l] @ W_enc[l] + b_enc[l]).reshape(-1)
-        if s.numel() > (1 << 22):
-            s = s[:: s.numel() // (1 << 22)]
-        kth = min(s.numel(), max(1, int(round(s.numel() * (1.0 - rho)))))
-        out[l] = torch.kthvalue(s, kth).values
-    return out
