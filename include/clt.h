@@ -132,6 +132,24 @@ const char* clt_last_error(const clt_handle* handle);
  * of the codes times |scale|), else NULL.  Deterministic (fixed order). */
 int clt_norm_accumulate(clt_handle* handle, void* stream, const void* a, const float* a_scale, double* norm_sum);
 
+/* clt_norm_accumulate for callers that cannot allocate device memory or bring a
+ * workspace (code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc): no handle, no workspace, and the call allocates nothing.
+ * Same kernels and same result, bit for bit, as clt_norm_accumulate; the
+ * per-block partial sums live in a 512 KB array that the library itself holds
+ * on every GPU it runs on until the process ends.  Limit: L * ceil(B / 32) <=
+ * 65536 partial sums (e.g. L = 16 with up to 131072 tokens per call), beyond
+ * it the call fails with CLT_ERR_WORKSPACE; 1 <= L <= 128, d a positive
+ * multiple of 8; dtype / input_format as in clt_config (a is [L,B,d] in that
+ * format, a_scale [L,B] exactly when the rows are int8 codes).  The array's
+ * address is looked up on the first call on a device (or by clt_init): make
+ * that call before any graph capture.  Nothing in the array has to be cleared
+ * between calls (every partial sum a call reads it has written first), but all
+ * calls on one GPU share it: calls that overlap on one GPU, on different
+ * streams or threads, race and must be serialised by the caller. */
+int clt_norm_accumulate_static(void* stream, int32_t L, int32_t B, int32_t d, int32_t dtype, int32_t input_format,
+                               const void* a, const float* a_scale, double* norm_sum);
+
 /* Divides by c[l] = norm_sum[l] / n_tokens.  int8 rows: the division folds
  * into the dequantisation scale, scale_out[l,b] = scale_in[l,b] / c[l]
  * (scale_out may be scale_in), the codes are untouched and a_in, a_out must be

@@ -25,7 +25,7 @@ DECODE_AUTO, DECODE_DENSE, DECODE_GATHER = 0, 1, 2
 EXPORTS = ("clt_workspace_bytes", "clt_init", "clt_destroy", "clt_last_error", "clt_forward",
            "clt_loss", "clt_backward", "clt_adam_step", "clt_backward_adam_step", "clt_workspace_view",
            "clt_profile_enable", "clt_profile_num_kernels", "clt_profile_query", "clt_norm_accumulate",
-           "clt_normalise", "clt_diag_mfma_loop")
+           "clt_normalise", "clt_diag_mfma_loop", "clt_norm_accumulate_static")
 
 
 class CLTError(RuntimeError):
@@ -69,6 +69,7 @@ def _load():
     lib.clt_profile_num_kernels.argtypes = []
     lib.clt_profile_query.argtypes = [vp, C.c_int, C.POINTER(C.c_char_p), C.POINTER(C.c_double),
                                       C.POINTER(C.c_int64)]
+    lib.clt_norm_accumulate_static.argtypes = [vp, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32, vp, fp, vp]
     lib.clt_diag_mfma_loop.argtypes = [vp, C.c_int, C.c_int, vp, C.POINTER(C.c_double), C.POINTER(C.c_double)]
     for n in EXPORTS:
         if n != "clt_last_error":
@@ -158,6 +159,23 @@ def clt_norm_accumulate(H: Handle, a, norm_sum, a_scale=None):
                                   _ptr(a_scale, s["scale"], torch.float32, "a_scale", True),
                                   _ptr(norm_sum, (H.cfg.L,), torch.float64, "norm_sum"))
     _check(rc, H.h)
+
+
+def clt_norm_accumulate_static(a, norm_sum, a_scale=None):
+    """clt_norm_accumulate without a handle or workspace (the library's own static scratch); a is [L,B,d] float32,
+    bfloat16 or int8 (then a_scale [L,B] float32 is required)."""
+    if a is None or a.dim() != 3:
+        raise ValueError("a must be a [L, B, d] device tensor")
+    L, B, d = a.shape
+    int8 = a.dtype == torch.int8
+    dt = DTYPE_F32 if a.dtype == torch.float32 else DTYPE_BF16
+    if a.dtype not in (torch.float32, torch.bfloat16, torch.int8):
+        raise ValueError(f"a: unsupported dtype {a.dtype}")
+    rc = _lib.clt_norm_accumulate_static(_stream(), L, B, d, dt, INPUT_INT8_ROWSCALE if int8 else INPUT_NATIVE,
+                                         _ptr(a, (L, B, d), a.dtype, "a"),
+                                         _ptr(a_scale, (L, B), torch.float32, "a_scale", True),
+                                         _ptr(norm_sum, (L,), torch.float64, "norm_sum"))
+    _check(rc)
 
 
 def clt_normalise(H: Handle, norm_sum, n_tokens, a_in=None, scale_in=None, a_out=None, scale_out=None):

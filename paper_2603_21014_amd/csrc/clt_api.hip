@@ -258,6 +258,15 @@ int clt_init(clt_handle** handle, const clt_config* cfg, void* workspace, size_t
       return CLT_ERR_HIP;
     }
   }
+  {   // set-up for clt_norm_accumulate_static on this device (address of the library's own scratch array)
+    double* unused = nullptr;
+    e = static_scratch(&unused);
+    if (e != hipSuccess) {
+      set_err(g_err, "clt_init: cannot resolve the static scratch array (%s)", hipGetErrorString(e));
+      (void)hipGetLastError();
+      return CLT_ERR_HIP;
+    }
+  }
   clt_handle* h = new (std::nothrow) clt_handle;
   if (!h) { set_err(g_err, "clt_init: out of host memory"); return CLT_ERR_INVALID_ARG; }
   h->cfg = *cfg;
@@ -364,6 +373,46 @@ int clt_norm_accumulate(clt_handle* h, void* stream, const void* a, const float*
   // the per-block partial sums borrow the reconstruction loss's partials, which never outlive a clt_loss call
   double* part = reinterpret_cast<double*>(h->ws + h->plan.part_rec);
   RUN(h, s, K_NORM_SUM, launch_norm_accumulate(s, h->bf16, h->int8, h->D, a, a_scale, part, norm_sum));
+  return CLT_OK;
+}
+
+int clt_norm_accumulate_static(void* stream, int32_t L, int32_t B, int32_t d, int32_t dtype, int32_t input_format,
+                               const void* a, const float* a_scale, double* norm_sum) {
+  const bool int8 = input_format == CLT_INPUT_INT8_ROWSCALE;
+  if ((dtype != CLT_DTYPE_F32 && dtype != CLT_DTYPE_BF16) || (input_format != CLT_INPUT_NATIVE && !int8) ||
+      (int8 && dtype != CLT_DTYPE_BF16)) {
+    set_err(g_err, "clt_norm_accumulate_static: bad dtype %d / input_format %d", dtype, input_format);
+    return CLT_ERR_INVALID_ARG;
+  }
+  if (L < 1 || L > 128 || B < 1 || d < 8 || (d % 8)) {
+    set_err(g_err, "clt_norm_accumulate_static: unsupported shape L=%d B=%d d=%d (need 1<=L<=128, B>=1, d a positive multiple of 8)", L, B, d);
+    return CLT_ERR_SHAPE;
+  }
+  const size_t need = (size_t)L * row_blocks(B);
+  if (need > STATIC_SCRATCH_DOUBLES) {
+    set_err(g_err, "clt_norm_accumulate_static: L * ceil(B/%d) = %zu partial sums exceed the library's static scratch of %zu; "
+            "use clt_norm_accumulate with a workspace, or split the batch", LOSS_ROWS_PER_BLOCK, need, STATIC_SCRATCH_DOUBLES);
+    return CLT_ERR_WORKSPACE;
+  }
+  if (!a || !norm_sum || (int8 && !a_scale)) {
+    set_err(g_err, "clt_norm_accumulate_static: a, norm_sum%s must not be NULL", int8 ? ", a_scale" : "");
+    return CLT_ERR_INVALID_ARG;
+  }
+  if (!int8 && a_scale) { set_err(g_err, "clt_norm_accumulate_static: a_scale given but input_format is native"); return CLT_ERR_INVALID_ARG; }
+  if (misaligned(a) || misaligned(norm_sum) || (a_scale && misaligned(a_scale))) {
+    set_err(g_err, "clt_norm_accumulate_static: a pointer is not 16-byte aligned");
+    return CLT_ERR_ALIGN;
+  }
+  double* part = nullptr;
+  hipError_t e = static_scratch(&part);
+  if (e != hipSuccess) {
+    set_err(g_err, "clt_norm_accumulate_static: cannot resolve the scratch array on this device: %s", hipGetErrorString(e));
+    (void)hipGetLastError();
+    return CLT_ERR_HIP;
+  }
+  e = launch_norm_accumulate(static_cast<hipStream_t>(stream), dtype == CLT_DTYPE_BF16, int8, Dims{L, d, 8, B}, a, a_scale,
+                             part, norm_sum);
+  if (e != hipSuccess) { set_err(g_err, "clt_norm_accumulate_static: launch failed: %s", hipGetErrorString(e)); return CLT_ERR_HIP; }
   return CLT_OK;
 }
 

@@ -177,6 +177,9 @@ hipError_t launch_zero_i32(hipStream_t s, int32_t* p, int n);
 // doubles of scratch); then a / c[l] with c[l] = norm_sum[l] / n_tokens, folded into the row scales for int8 rows
 hipError_t launch_norm_accumulate(hipStream_t s, bool bf16, bool int8_a, Dims D, const void* a, const float* a_scale,
                                   double* part, double* norm_sum);
+// Capacity of the library-owned scratch array (doubles) and its device address on the current GPU
+constexpr size_t STATIC_SCRATCH_DOUBLES = 65536;
+hipError_t static_scratch(double** ptr);
 hipError_t launch_normalise(hipStream_t s, bool bf16, bool int8_a, Dims D, const double* norm_sum, double n_tokens,
                             const void* a_in, const float* scale_in, void* a_out, float* scale_out);
 // TopK activation (Sec. 3.2): per (layer, token) row of pre32 [L,B,F] the k largest entries (lower index wins

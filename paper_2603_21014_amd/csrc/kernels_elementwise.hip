@@ -520,6 +520,13 @@ __global__ __launch_bounds__(256) void normalise_rows_kernel(Dims D, const doubl
   }
 }
 
+// Scratch of the entry point that allocates nothing: the per-block partial sums of the activation-norm
+// reduction, held in the library's own device memory instead of a caller workspace.  One copy per GPU
+// for the life of the process (512 KB); every call on a GPU uses that GPU's copy.
+static __device__ __align__(256) double scratch[STATIC_SCRATCH_DOUBLES];
+constexpr int MAX_DEVICES = 64;
+double* g_scratch_ptr[MAX_DEVICES] = {};   // device address of `scratch` on each GPU, resolved once
+
 inline int grid_for(size_t n, int per_block, int cap) {
   size_t b = (n + per_block - 1) / per_block;
   if (b < 1) b = 1;
@@ -660,6 +667,25 @@ hipError_t launch_norm_accumulate(hipStream_t s, bool bf16, bool int8_a, Dims D,
     hipLaunchKernelGGL((row_norm_sum_kernel<bf16_t, false>), grid, dim3(256), 0, s, D, a, a_scale, part);
   hipLaunchKernelGGL(norm_sum_final_kernel, dim3((D.L + 63) / 64), dim3(64), 0, s, D.L, (int)grid.x, part, norm_sum);
   return hipGetLastError();
+}
+
+// Device address of this GPU's `scratch` array (the array's name is only a host-side handle for
+// hipGetSymbolAddress; kernels get the resolved pointer as an argument).  Resolved once per device,
+// with that device current.
+hipError_t static_scratch(double** ptr) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= MAX_DEVICES) return hipErrorInvalidDevice;
+  double* p = __atomic_load_n(&g_scratch_ptr[dev], __ATOMIC_ACQUIRE);
+  if (!p) {
+    e = hipGetSymbolAddress(reinterpret_cast<void**>(&p), HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!p) return hipErrorInvalidSymbol;
+    __atomic_store_n(&g_scratch_ptr[dev], p, __ATOMIC_RELEASE);   // every thread resolves the same address
+  }
+  *ptr = p;
+  return hipSuccess;
 }
 
 hipError_t launch_normalise(hipStream_t s, bool bf16, bool int8_a, Dims D, const double* norm_sum, double n_tokens,
