@@ -58,31 +58,55 @@ def theta_for_density(x, W_enc, b_enc, rho):
     return out
 
 
-def mfma_ceiling(dev, log, iters=40000):
-    """The MFMA-only loop of the contraction kernel (register operands, no memory traffic) on this GPU, on
-    all-zero and on pseudo-random bf16 operands: TFLOP/s from HIP events on the launch stream and the shader
-    clock from the kernel's own cycle counters.  The bf16 MFMA rate is limited by board power and the power
-    depends on the operand bits, so the two differ; the random-operand figure is the ceiling for real data."""
+DIAG_VARIANTS = (
+    # (name, mode bits of clt_diag_mfma_loop without the data bit)
+    ("mfma_only", 0),
+    ("mfma+lds_reads", 2),
+    ("mfma+lds_reads+lds_writes", 6),
+    ("mfma+lds+loads_from_L2", 14),
+    ("mfma+lds+loads_half_from_infinity_cache", 30),
+)
+
+
+def run_diag(dev, mode, iters, counters, buf):
+    """One timed launch of the diagnostic loop: (TFLOP/s, ms, shader clock in GHz or None)."""
     import torch
     from paper_2603_21014_amd import binding as K
+    K.clt_diag_mfma_loop(max(1, iters // 8), mode, counters, buf)      # warm-up (and the buffer fill)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record()
+    flop, hz = K.clt_diag_mfma_loop(iters, mode, counters, buf)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1)
+    c = counters.cpu().tolist()
+    clock = c[0] / c[1] * hz / 1e9 if c[1] > 0 else None
+    return {"tflops": round(flop / (ms * 1e-3) / 1e12, 1), "ms": round(ms, 3),
+            "shader_clock_ghz": round(clock, 3) if clock else None}
+
+
+def mfma_ceiling(dev, log, iters=40000, all_variants=False):
+    """The MFMA stream of the contraction kernel on this GPU with its operands in registers (no memory traffic
+    at all), on all-zero and on pseudo-random bf16 data: TFLOP/s from HIP events on the launch stream and the
+    shader clock from the kernel's own cycle counters.  The bf16 MFMA rate is limited by board power and the
+    power depends on the operand bits, so the two differ; the random-data figure is the ceiling for real data.
+    all_variants adds the LDS and memory traffic of the real kernel back one part at a time (same loop, no data
+    flow between the parts): what each part costs in clock and rate."""
+    import torch
     out = {}
     counters = torch.zeros(4, dtype=torch.int64, device=dev)
-    for name, rnd in (("zero_operands", False), ("random_operands", True)):
-        K.clt_diag_mfma_loop(iters // 8, rnd, counters)      # warm-up
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        torch.cuda.synchronize()
-        e0.record()
-        flop, hz = K.clt_diag_mfma_loop(iters, rnd, counters)
-        e1.record()
-        torch.cuda.synchronize()
-        ms = e0.elapsed_time(e1)
-        c = counters.cpu().tolist()
-        clock = c[0] / c[1] * hz / 1e9 if c[1] > 0 else None
-        out[name] = {"tflops": round(flop / (ms * 1e-3) / 1e12, 1), "ms": round(ms, 3),
-                     "shader_clock_ghz": round(clock, 3) if clock else None}
-        log(f"MFMA-only loop, {name}: {out[name]['tflops']} TFLOP/s at {out[name]['shader_clock_ghz']} GHz")
-    out["what"] = ("v_mfma_f32_32x32x16_bf16 stream of the contraction kernel on register operands, 8 wavefronts per CU, "
-                   "no LDS or global memory")
+    buf = None
+    if all_variants:
+        cus = torch.cuda.get_device_properties(0).multi_processor_count
+        buf = torch.empty(cus * (576 << 10), dtype=torch.uint8, device=dev)
+    for vname, mode in (DIAG_VARIANTS if all_variants else DIAG_VARIANTS[:1]):
+        for dname, rnd in (("zero_data", 0), ("random_data", 1)):
+            r = run_diag(dev, mode | rnd, iters, counters, buf if mode & 8 else None)
+            out.setdefault(vname, {})[dname] = r
+            log(f"diagnostic loop {vname}, {dname}: {r['tflops']} TFLOP/s at {r['shader_clock_ghz']} GHz")
+    out["what"] = ("v_mfma_f32_32x32x16_bf16 stream of the contraction kernel, 8 wavefronts per CU, operands in "
+                   "registers (mfma_only: no LDS or global memory access)")
     return out
 
 
@@ -239,6 +263,45 @@ def density_sweep(args, log):
     print(json.dumps(out), flush=True)
 
 
+def power_probe(args, log):
+    """What limits the bf16 MFMA rate on this board (one JSON line): the diagnostic loop's variants, then the
+    forward pass of the library on the workload's data and on all-zero inputs and weights (same kernels, same
+    instruction count; only the operand bits differ), with the decode contraction's time for each."""
+    import torch
+    from paper_2603_21014_amd import binding as K
+    from workloads import clt_synth as S
+    dev, T = "cuda:0", torch.bfloat16
+    out = {"metric": "bf16 MFMA rate against operand content and data movement", "loop": mfma_ceiling(dev, log, all_variants=True)}
+    w = S.WORKLOADS[args.workload]
+    p32 = S.make_params(w, device=dev)
+    params = {k: (v.to(T) if k in ("W_enc", "W_dec") else v) for k, v in p32.items()}
+    del p32
+    x, _ = S.make_inputs(w, device=dev)
+    x = x.to(T)
+    step = K.CLTStep(w.L, w.d, w.F, w.B, dtype="bf16", C_=w.C, ste_bandwidth=w.ste_eps, device=dev, keep_pre=False,
+                     matrix_grads=False)
+    pair = 2.0 * w.B * w.F * w.d
+    out["decode_gemm"] = {}
+    for name in ("workload_data", "zero_data"):
+        if name == "zero_data":
+            x.zero_(); params["W_dec"].zero_(); params["W_enc"].zero_()
+        for it in range(4):
+            if it == 1:
+                K.clt_profile_enable(step.H, True)
+            step.forward(x, params)
+        torch.cuda.synchronize()
+        prof = K.clt_profile_query(step.H)
+        K.clt_profile_enable(step.H, False)
+        ms = prof["decode_gemm"][0] / prof["decode_gemm"][1]
+        ems = prof["encoder_jumprelu_gemm"][0] / prof["encoder_jumprelu_gemm"][1]
+        out["decode_gemm"][name] = {"ms": round(ms, 3), "tflops": round(w.P * pair / (ms * 1e-3) / 1e12, 1),
+                                    "encoder_ms": round(ems, 3), "encoder_tflops": round(w.L * pair / (ems * 1e-3) / 1e12, 1),
+                                    "active_fraction": round(step.l0.double().sum().item() / (w.L * w.B * w.F), 4)}
+        log(f"forward on {name}: decode {ms:.3f} ms = {out['decode_gemm'][name]['tflops']} TFLOP/s, "
+            f"encoder {ems:.3f} ms = {out['decode_gemm'][name]['encoder_tflops']} TFLOP/s")
+    print(json.dumps(out), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -257,6 +320,10 @@ def main():
                     help="skip the per-kernel HIP-event brackets (roofline entry becomes null)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="end with one plain 1 GiB device copy (the last dispatch): reference for HBM byte counters")
+    ap.add_argument("--power-probe", action="store_true",
+                    help="instead of the train step: the contraction kernel's instruction stream taken apart (MFMA "
+                         "only, + LDS reads, + LDS writes, + loads), on zero and on random data, and the decode "
+                         "contraction itself on zero and on the workload's data")
     ap.add_argument("--density-sweep", action="store_true",
                     help="time dense vs gather decode at forced densities instead of the train step")
     args = ap.parse_args()
@@ -269,6 +336,8 @@ def main():
 
     if args.density_sweep:
         return density_sweep(args, log)
+    if args.power_probe:
+        return power_probe(args, log)
 
     import torch
     from paper_2603_21014_amd import binding as K

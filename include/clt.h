@@ -244,19 +244,32 @@ int clt_profile_enable(clt_handle* handle, int on);
 int clt_profile_num_kernels(void);
 int clt_profile_query(clt_handle* handle, int kernel, const char** name, double* total_ms, int64_t* launches);
 
-/* Diagnostic, not part of the method: the MFMA instruction stream of the bf16
+/* Diagnostic, not part of the method: the instruction stream of the bf16
  * contraction kernels (one workgroup of 8 wavefronts per compute unit, per
- * iteration 32 v_mfma_f32_32x32x16_bf16 per wavefront) on operands held in
- * registers, all zero or (random_operands != 0) pseudo-random bf16.  It gives
- * the rate the matrix cores sustain on this board with no memory traffic at
- * all, which depends on the operand content (board power limit).  Enqueues
- * one kernel on `stream`; the caller times it.  counters_dev: device, 4 x
- * uint64, 16-byte aligned; after the kernel [0] holds the shader cycles and
- * [1] the ticks of the constant-rate counter that one wavefront spent in its
- * loop (shader clock = [0] / [1] * wall_clock_hz).  *flop (host) receives the
- * floating-point operations of the launch, *wall_clock_hz the counter's rate;
- * both may be NULL. */
-int clt_diag_mfma_loop(void* stream, int iters, int random_operands, uint64_t* counters_dev,
+ * iteration 32 v_mfma_f32_32x32x16_bf16 per wavefront), taken apart to show
+ * what the matrix cores sustain on this board and what each kind of data
+ * movement costs them.  The bf16 MFMA rate is limited by board power, and the
+ * power depends on the operand bits, so every variant runs on all-zero or on
+ * pseudo-random data.  mode is a sum of
+ *    1  pseudo-random data instead of zeros
+ *    2  MFMA operands are read from LDS (six 16-byte reads per lane for every
+ *       eight MFMAs, the contraction kernels' pattern) instead of held in registers
+ *    4  eight 16-byte LDS writes per lane and iteration (staging of a 256x64 + 64x256 tile)
+ *    8  eight 16-byte loads per lane and iteration (64 KB per workgroup) from a
+ *       region that stays in the L2
+ *   16  (with 8) every second of those loads from a region that only fits the
+ *       Infinity Cache
+ * Built combinations: 0, 2, 6, 14, 30, 8, 24 (+1).  There is no data flow between
+ * the parts and no barrier: the kernel computes nothing, it only does the work.
+ * Enqueues on `stream` (a fill of buf first when a load bit is set); the caller
+ * times it.  buf: device scratch, 16-byte aligned, at least (64 KB + 512 KB) x
+ * compute units bytes when a load bit is set, else ignored.  counters_dev:
+ * device, 4 x uint64, 16-byte aligned; after the kernel [0] holds the shader
+ * cycles and [1] the ticks of the constant-rate counter that one wavefront
+ * spent in its loop (shader clock = [0] / [1] * wall_clock_hz).  *flop (host)
+ * receives the floating-point operations of the launch, *wall_clock_hz the
+ * counter's rate; both may be NULL. */
+int clt_diag_mfma_loop(void* stream, int iters, int mode, void* buf, size_t buf_bytes, uint64_t* counters_dev,
                        double* flop, double* wall_clock_hz);
 
 #ifdef __cplusplus

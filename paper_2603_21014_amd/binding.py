@@ -70,7 +70,7 @@ def _load():
     lib.clt_profile_query.argtypes = [vp, C.c_int, C.POINTER(C.c_char_p), C.POINTER(C.c_double),
                                       C.POINTER(C.c_int64)]
     lib.clt_norm_accumulate_static.argtypes = [vp, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32, vp, fp, vp]
-    lib.clt_diag_mfma_loop.argtypes = [vp, C.c_int, C.c_int, vp, C.POINTER(C.c_double), C.POINTER(C.c_double)]
+    lib.clt_diag_mfma_loop.argtypes = [vp, C.c_int, C.c_int, vp, C.c_size_t, vp, C.POINTER(C.c_double), C.POINTER(C.c_double)]
     for n in EXPORTS:
         if n != "clt_last_error":
             getattr(lib, n).restype = C.c_int
@@ -297,11 +297,18 @@ def clt_profile_query(H: Handle) -> dict:
     return out
 
 
-def clt_diag_mfma_loop(iters: int, random_operands: bool, counters: torch.Tensor):
-    """Enqueues the MFMA-only loop; returns (flop of the launch, rate of the constant-rate counter in Hz).
-    counters: int64 device tensor of 4 elements; [0] shader cycles, [1] constant-rate ticks of one wavefront."""
+DIAG_RANDOM_DATA, DIAG_LDS_READS, DIAG_LDS_WRITES, DIAG_LOADS_L2, DIAG_LOADS_FAR = 1, 2, 4, 8, 16
+
+
+def clt_diag_mfma_loop(iters: int, mode: int, counters: torch.Tensor, buf: torch.Tensor = None):
+    """Enqueues the diagnostic MFMA loop (see include/clt.h for the mode bits); returns (flop of the launch, rate
+    of the constant-rate counter in Hz).  counters: int64 device tensor of 4 elements; [0] shader cycles, [1]
+    constant-rate ticks of one wavefront.  buf: uint8 device scratch for the modes that load from memory."""
     flop, hz = C.c_double(), C.c_double()
-    _check(_lib.clt_diag_mfma_loop(_stream(), int(iters), int(bool(random_operands)),
+    if buf is not None and (buf.dtype != torch.uint8 or not buf.is_cuda or not buf.is_contiguous()):
+        raise ValueError("buf must be a contiguous uint8 device tensor")
+    _check(_lib.clt_diag_mfma_loop(_stream(), int(iters), int(mode), buf.data_ptr() if buf is not None else None,
+                                   buf.numel() if buf is not None else 0,
                                    _ptr(counters, (4,), torch.int64, "counters"), C.byref(flop), C.byref(hz)))
     return flop.value, hz.value
 

@@ -327,10 +327,10 @@ int clt_profile_query(clt_handle* h, int kernel, const char** name, double* tota
   return CLT_OK;
 }
 
-int clt_diag_mfma_loop(void* stream, int iters, int random_operands, uint64_t* counters_dev, double* flop,
-                       double* wall_clock_hz) {
-  if (!counters_dev || misaligned(counters_dev) || iters < 1 || iters > (1 << 24)) {
-    set_err(g_err, "clt_diag_mfma_loop: counters_dev must be a 16-byte aligned device pointer to 4 x uint64 and 1 <= iters <= 2^24");
+int clt_diag_mfma_loop(void* stream, int iters, int mode, void* buf, size_t buf_bytes, uint64_t* counters_dev,
+                       double* flop, double* wall_clock_hz) {
+  if (!counters_dev || misaligned(counters_dev) || iters < 1 || iters > (1 << 24) || mode < 0 || mode > 31) {
+    set_err(g_err, "clt_diag_mfma_loop: counters_dev must be a 16-byte aligned device pointer to 4 x uint64, 1 <= iters <= 2^24, 0 <= mode <= 31");
     return CLT_ERR_INVALID_ARG;
   }
   int dev = 0, cus = 0, khz = 0;
@@ -340,9 +340,22 @@ int clt_diag_mfma_loop(void* stream, int iters, int random_operands, uint64_t* c
     (void)hipGetLastError();
     return CLT_ERR_HIP;
   }
-  const hipError_t e = launch_mfma_loop(static_cast<hipStream_t>(stream), cus, iters, random_operands != 0,
-                                        reinterpret_cast<unsigned long long*>(counters_dev));
-  if (e != hipSuccess) { set_err(g_err, "clt_diag_mfma_loop: launch failed: %s", hipGetErrorString(e)); return CLT_ERR_HIP; }
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const size_t need = (size_t)cus * (DIAG_NEAR_BYTES + DIAG_FAR_BYTES);
+  if (mode & (DIAG_LOADS_L2 | DIAG_LOADS_FAR)) {
+    if (!(mode & DIAG_LOADS_L2) || !buf || misaligned(buf) || buf_bytes < need) {
+      set_err(g_err, "clt_diag_mfma_loop: the load modes need mode bit 8 and a 16-byte aligned device buffer of at least %zu bytes", need);
+      return CLT_ERR_INVALID_ARG;
+    }
+    const hipError_t ef = launch_diag_fill(s, buf, need, mode & DIAG_RANDOM_DATA);
+    if (ef != hipSuccess) { set_err(g_err, "clt_diag_mfma_loop: fill failed: %s", hipGetErrorString(ef)); return CLT_ERR_HIP; }
+  }
+  const hipError_t e = launch_mfma_loop(s, cus, iters, mode, buf, reinterpret_cast<unsigned long long*>(counters_dev));
+  if (e != hipSuccess) {
+    set_err(g_err, "clt_diag_mfma_loop: mode %d is not built or the launch failed: %s", mode, hipGetErrorString(e));
+    (void)hipGetLastError();
+    return e == hipErrorInvalidValue ? CLT_ERR_INVALID_ARG : CLT_ERR_HIP;
+  }
   if (flop) *flop = (double)cus * 8.0 * (double)iters * 32.0 * 32768.0;
   if (wall_clock_hz) *wall_clock_hz = 1e3 * (double)khz;
   return CLT_OK;

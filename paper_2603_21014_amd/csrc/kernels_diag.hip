@@ -1,11 +1,14 @@
-// Diagnostic kernel, not part of the training step: the MFMA instruction stream of the bf16
-// contraction kernel (8 wavefronts per workgroup, one workgroup per CU, 32
-// v_mfma_f32_32x32x16_bf16 per K step and wave on 4x2 accumulators) with its operands held in
-// registers -- no LDS, no global memory.  Its rate is the ceiling the matrix cores reach on this
-// board for a given operand content: the bf16 MFMA rate is limited by board power, and the power an
-// MFMA draws depends on how many operand bits toggle, so the loop is run on all-zero operands and on
-// pseudo-random ones.  Wave 0 of workgroup 0 brackets its loop with the shader-cycle counter and the
-// constant-rate counter, which gives the shader clock the loop ran at.
+// Diagnostic kernel, not part of the training step: the instruction stream of the bf16 contraction
+// kernel (8 wavefronts per workgroup, one workgroup per CU, 32 v_mfma_f32_32x32x16_bf16 per K step
+// and wave on 4x2 accumulators), taken apart.  The bare loop keeps its operands in registers -- no
+// LDS, no global memory; mode bits add back, one by one and at the contraction kernel's own rates,
+// the fragment reads from LDS, the staging writes to LDS and the operand loads from memory (out of
+// the L2, or half of them out of the Infinity Cache).  There is no data flow between these parts and
+// no barrier: the kernel computes nothing meaningful, it only draws the power of each part.  The bf16
+// MFMA rate is limited by board power, and the power an MFMA draws depends on how many operand bits
+// toggle, so every variant can run on all-zero or on pseudo-random data.  Wave 0 of workgroup 0
+// brackets its loop with the shader-cycle counter and the constant-rate counter, which gives the
+// shader clock the loop ran at.
 #include "common.h"
 
 namespace clt {
@@ -14,6 +17,8 @@ namespace {
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float f32x16_t __attribute__((ext_vector_type(16)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int TK = 64, STAGE_ELEMS = 2 * 256 * TK, LDS_BYTES = 2 * STAGE_ELEMS * 2;   // as in the contraction kernel
 
 __device__ __forceinline__ uint32_t mix(uint32_t h) {
   h ^= h >> 16; h *= 0x7feb352du; h ^= h >> 15; h *= 0x846ca68bu; h ^= h >> 16;
@@ -26,21 +31,40 @@ __device__ __forceinline__ uint32_t rand_bf16x2(uint32_t h) {
   const uint32_t hi = (g & 0x807fu) | ((125u + (g >> 8) % 3u) << 7);
   return lo | (hi << 16);
 }
+__device__ __forceinline__ int lds_off(int row, int c) { return row * TK + (((c ^ row ^ (row >> 3)) & 7) << 3); }
 
-__global__ __launch_bounds__(512) void mfma_loop_kernel(int iters, int random_operands, unsigned long long* out) {
+__global__ void fill_kernel(uint32_t* p, size_t n, int random_data) {
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x)
+    p[i] = random_data ? rand_bf16x2(mix((uint32_t)i * 2654435761u + (uint32_t)(i >> 32))) : 0u;
+}
+
+template <int MODE>
+__global__ __launch_bounds__(512) void mfma_loop_kernel(int iters, int random_data, const char* __restrict__ buf,
+                                                        unsigned long long* out) {
+  constexpr bool LDS_READS = MODE & DIAG_LDS_READS, LDS_WRITES = MODE & DIAG_LDS_WRITES;
+  constexpr bool LOADS = MODE & DIAG_LOADS_L2, FAR = MODE & DIAG_LOADS_FAR;
+  extern __shared__ __align__(16) uint16_t smem[];
   const uint32_t t = blockIdx.x * 512u + threadIdx.x;
-  u32x4 fa[2][4], fb[2][2];
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, wm = w >> 2, wn = w & 3, lt = threadIdx.x & 255;
+  if (LDS_READS || LDS_WRITES) {
+    for (int i = threadIdx.x; i < LDS_BYTES / 4; i += 512)
+      reinterpret_cast<uint32_t*>(smem)[i] = random_data ? rand_bf16x2(mix(t * 977u + i)) : 0u;
+    __syncthreads();
+  }
+  u32x4 fa[2][4], fb[2][2], rg[8];
 #pragma unroll
   for (int b = 0; b < 2; ++b) {
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
-      for (int c = 0; c < 4; ++c) fa[b][i][c] = random_operands ? rand_bf16x2(mix(t * 64u + b * 32u + i * 4u + c)) : 0u;
+      for (int c = 0; c < 4; ++c) fa[b][i][c] = random_data ? rand_bf16x2(mix(t * 64u + b * 32u + i * 4u + c)) : 0u;
 #pragma unroll
     for (int j = 0; j < 2; ++j)
 #pragma unroll
-      for (int c = 0; c < 4; ++c) fb[b][j][c] = random_operands ? rand_bf16x2(mix(t * 64u + 16u + b * 32u + j * 4u + c)) : 0u;
+      for (int c = 0; c < 4; ++c) fb[b][j][c] = random_data ? rand_bf16x2(mix(t * 64u + 16u + b * 32u + j * 4u + c)) : 0u;
   }
+#pragma unroll
+  for (int i = 0; i < 8; ++i) rg[i] = fa[i & 1][i >> 1];
   f32x16_t acc[4][2];
 #pragma unroll
   for (int i = 0; i < 4; ++i)
@@ -48,11 +72,37 @@ __global__ __launch_bounds__(512) void mfma_loop_kernel(int iters, int random_op
     for (int j = 0; j < 2; ++j)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+  // operand loads: per K step every wave reads 8 x 1 KB (16 bytes per lane), 64 KB per workgroup.  The near
+  // region (64 KB per workgroup, 2 MB per XCD) stays in the L2; the far region (512 KB per workgroup, 16 MB per
+  // XCD, 128 MB in all) does not, but fits the Infinity Cache.
+  const char* near = buf + (size_t)blockIdx.x * DIAG_NEAR_BYTES + (size_t)(w * 64 + lane) * 16;
+  const char* far = buf + (size_t)gridDim.x * DIAG_NEAR_BYTES + (size_t)blockIdx.x * DIAG_FAR_BYTES + (size_t)(w * 64 + lane) * 16;
+  const int frow = lane & 31, fch = lane >> 5;
   const long long c0 = clock64(), w0 = wall_clock64();
   for (int it = 0; it < iters; ++it) {
+    if (LDS_WRITES) {      // the tile fetched during the previous step goes to LDS, 8 x 16 bytes per lane
+      uint16_t* st = smem + (it & 1) * STAGE_ELEMS + (w >> 2) * 256 * TK;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) *reinterpret_cast<u32x4*>(st + lds_off((lt >> 3) + 32 * i, lt & 7)) = rg[i];
+    }
+    if (LOADS) {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        if (FAR && (i & 1)) rg[i] = *reinterpret_cast<const u32x4*>(far + (((size_t)it * 4 + (i >> 1)) * 8192) % DIAG_FAR_BYTES);
+        else rg[i] = *reinterpret_cast<const u32x4*>(near + (size_t)i * 8192);
+      }
+    }
 #pragma unroll
     for (int s = 0; s < 4; ++s) {         // the four 16-wide slices of one K step of 64
       const int b = s & 1;
+      if (LDS_READS) {
+        const uint16_t* a = smem + (it & 1) * STAGE_ELEMS;
+        const uint16_t* bb = a + 256 * TK;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) fa[b][i] = *reinterpret_cast<const u32x4*>(a + lds_off(wm * 128 + i * 32 + frow, 2 * s + fch));
+#pragma unroll
+        for (int j = 0; j < 2; ++j) fb[b][j] = *reinterpret_cast<const u32x4*>(bb + lds_off(wn * 64 + j * 32 + frow, 2 * s + fch));
+      }
 #pragma unroll
       for (int i = 0; i < 4; ++i)
 #pragma unroll
@@ -71,17 +121,49 @@ __global__ __launch_bounds__(512) void mfma_loop_kernel(int iters, int random_op
     for (int j = 0; j < 2; ++j)
 #pragma unroll
       for (int r = 0; r < 16; ++r) sum += acc[i][j][r];
+  uint32_t keep = 0;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) keep ^= rg[i][0] ^ rg[i][3];
   if (t == 0) {
     out[0] = (unsigned long long)(c1 - c0);
     out[1] = (unsigned long long)(w1 - w0);
   }
-  if (sum == 1.2345678e-30f) out[2] = t;   // never true in practice; makes the accumulators observable
+  if (sum == 1.2345678e-30f && keep == 0x12345u) out[2] = t;   // never true in practice; makes the results observable
+}
+
+template <int MODE>
+hipError_t launch_mode(hipStream_t s, int workgroups, int iters, int random_data, const void* buf, unsigned long long* out) {
+  const bool lds = MODE & (DIAG_LDS_READS | DIAG_LDS_WRITES);
+  if (lds) {
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&mfma_loop_kernel<MODE>),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
+    if (e != hipSuccess) return e;
+  }
+  hipLaunchKernelGGL((mfma_loop_kernel<MODE>), dim3(workgroups), dim3(512), lds ? LDS_BYTES : 0, s, iters, random_data,
+                     static_cast<const char*>(buf), out);
+  return hipGetLastError();
 }
 
 }  // namespace
 
-hipError_t launch_mfma_loop(hipStream_t s, int workgroups, int iters, int random_operands, unsigned long long* out) {
-  hipLaunchKernelGGL(mfma_loop_kernel, dim3(workgroups), dim3(512), 0, s, iters, random_operands, out);
+hipError_t launch_mfma_loop(hipStream_t s, int workgroups, int iters, int mode, const void* buf, unsigned long long* out) {
+  const int rnd = mode & DIAG_RANDOM_DATA;
+  switch (mode & ~DIAG_RANDOM_DATA) {
+    case 0: return launch_mode<0>(s, workgroups, iters, rnd, buf, out);
+    case DIAG_LDS_READS: return launch_mode<DIAG_LDS_READS>(s, workgroups, iters, rnd, buf, out);
+    case DIAG_LDS_READS | DIAG_LDS_WRITES: return launch_mode<DIAG_LDS_READS | DIAG_LDS_WRITES>(s, workgroups, iters, rnd, buf, out);
+    case DIAG_LDS_READS | DIAG_LDS_WRITES | DIAG_LOADS_L2:
+      return launch_mode<DIAG_LDS_READS | DIAG_LDS_WRITES | DIAG_LOADS_L2>(s, workgroups, iters, rnd, buf, out);
+    case DIAG_LDS_READS | DIAG_LDS_WRITES | DIAG_LOADS_L2 | DIAG_LOADS_FAR:
+      return launch_mode<DIAG_LDS_READS | DIAG_LDS_WRITES | DIAG_LOADS_L2 | DIAG_LOADS_FAR>(s, workgroups, iters, rnd, buf, out);
+    case DIAG_LOADS_L2: return launch_mode<DIAG_LOADS_L2>(s, workgroups, iters, rnd, buf, out);
+    case DIAG_LOADS_L2 | DIAG_LOADS_FAR: return launch_mode<DIAG_LOADS_L2 | DIAG_LOADS_FAR>(s, workgroups, iters, rnd, buf, out);
+    default: return hipErrorInvalidValue;
+  }
+}
+
+hipError_t launch_diag_fill(hipStream_t s, void* buf, size_t bytes, int random_data) {
+  hipLaunchKernelGGL(fill_kernel, dim3(4096), dim3(256), 0, s, static_cast<uint32_t*>(buf), bytes / 4, random_data);
   return hipGetLastError();
 }
 
