@@ -21,7 +21,7 @@ constexpr size_t ALIGN = 256;
 inline size_t align_up(size_t v) { return (v + ALIGN - 1) / ALIGN * ALIGN; }
 
 struct Plan {
-  size_t norms, G, d_yhat, dpre, part_cols, part_cols2, part_cols3, part_rec, part_sp, part_dead, l0, flags, pre32, g_idx, g_val, g_counts, g_counts_w,
+  size_t norms, G, d_yhat, dpre, part_cols, part_cols2, part_cols3, part_rec, part_sp, part_dead, l0, flags, xcd_sync, pre32, g_idx, g_val, g_counts, g_counts_w,
          fl_off, fl_cnt, fl_tok, fl_val, fl_seg, total;
   int kcap;
 };
@@ -137,6 +137,7 @@ Plan make_plan(const clt_config* c) {
   p.part_dead = o;  o += align_up(rbs * L * 8);
   p.l0 = o;         o += align_up(L * 4);
   p.flags = o;      o += align_up(4 * 4);
+  p.xcd_sync = o;   o += align_up(8 * 64 * 4);   // pacing counters of the dense decode, one 256-byte line per XCD
   p.pre32 = o;      o += align_up(c->activation == CLT_ACT_TOPK ? L * B * F * 4 : 0);   // fp32 pre-activations for the selection
   // active-feature lists of the gather decode: forced gather must hold a fully dense row;
   // the automatic switch only ever gathers below the threshold, so rows are capped at a
@@ -329,8 +330,8 @@ int clt_profile_query(clt_handle* h, int kernel, const char** name, double* tota
 
 int clt_diag_mfma_loop(void* stream, int iters, int mode, void* buf, size_t buf_bytes, uint64_t* counters_dev,
                        double* flop, double* wall_clock_hz) {
-  if (!counters_dev || misaligned(counters_dev) || iters < 1 || iters > (1 << 24) || mode < 0 || mode > 31) {
-    set_err(g_err, "clt_diag_mfma_loop: counters_dev must be a 16-byte aligned device pointer to 4 x uint64, 1 <= iters <= 2^24, 0 <= mode <= 31");
+  if (!counters_dev || misaligned(counters_dev) || iters < 1 || iters > (1 << 24) || mode < 0 || mode > 127) {
+    set_err(g_err, "clt_diag_mfma_loop: counters_dev must be a 16-byte aligned device pointer to 4 x uint64, 1 <= iters <= 2^24, 0 <= mode <= 127");
     return CLT_ERR_INVALID_ARG;
   }
   int dev = 0, cus = 0, khz = 0;
@@ -473,7 +474,8 @@ int clt_forward(clt_handle* h, void* stream, const void* x, const float* x_scale
   EncArgs ea{x, x_scale, W_enc, b_enc, theta, h->cfg.ste_bandwidth, z, pre, act_class, l0,
              h->cfg.log_threshold != 0, pre32};
   const int mode = h->cfg.decode_mode;
-  DecArgs da{z, W_dec, b_dec, y_hat, mode == CLT_DECODE_AUTO ? flags : nullptr, h->plan.kcap};
+  DecArgs da{z, W_dec, b_dec, y_hat, mode == CLT_DECODE_AUTO ? flags : nullptr, h->plan.kcap,
+             reinterpret_cast<uint32_t*>(h->ws + h->plan.xcd_sync)};
   GatherLists gl{reinterpret_cast<int32_t*>(h->ws + h->plan.g_idx), reinterpret_cast<float*>(h->ws + h->plan.g_val),
                  reinterpret_cast<int32_t*>(h->ws + h->plan.g_counts),
                  reinterpret_cast<int32_t*>(h->ws + h->plan.g_counts_w), h->plan.kcap, list_stride(h->plan.kcap)};

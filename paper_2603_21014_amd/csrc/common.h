@@ -134,6 +134,7 @@ struct DecArgs {       // y_hat[lp] = sum_{l<=lp} z[l] W_dec[p(l,lp)] + b_dec[lp
   const void* z; const void* W_dec; const float* b_dec; float* y_hat;
   const int32_t* skip_flags;   // optional decode switch (see GatherLists); NULL = always run
   int kcap;
+  uint32_t* xcd_sync = nullptr;   // bf16 kernel: 8 x 64 words of pacing counters (zeroed by the launch), or NULL
 };
 struct DzArgs {        // dz[l] = sum_{lp>=l} dyhat[lp] W_dec[p(l,lp)]^T + g_sp, kept where active|window
   const void* d_yhat; const void* W_dec; const void* z; const uint8_t* cls; const float* norms;
@@ -224,7 +225,8 @@ hipError_t launch_adam_vector(hipStream_t s, size_t n, float* p, const float* g,
 // iters x 32 v_mfma_f32_32x32x16_bf16; mode bits add the LDS and memory traffic of the real kernel; out[0] / out[1] =
 // shader cycles / constant-rate ticks that wave 0 spent in its loop.  buf: workgroups * (NEAR + FAR) bytes when a
 // load bit is set.
-constexpr int DIAG_RANDOM_DATA = 1, DIAG_LDS_READS = 2, DIAG_LDS_WRITES = 4, DIAG_LOADS_L2 = 8, DIAG_LOADS_FAR = 16;
+constexpr int DIAG_RANDOM_DATA = 1, DIAG_LDS_READS = 2, DIAG_LDS_WRITES = 4, DIAG_LOADS_L2 = 8, DIAG_LOADS_FAR = 16,
+              DIAG_FOUR_WAVES = 32, DIAG_LDS_DMA = 64;
 constexpr size_t DIAG_NEAR_BYTES = 64u << 10, DIAG_FAR_BYTES = 512u << 10;
 hipError_t launch_mfma_loop(hipStream_t s, int workgroups, int iters, int mode, const void* buf, unsigned long long* out);
 hipError_t launch_diag_fill(hipStream_t s, void* buf, size_t bytes, int random_data);

@@ -131,6 +131,7 @@ __device__ __forceinline__ void adam_update4(const AdamFuse& f, T* w, size_t uo,
 // ---------------------------------------------------------------------------
 template <typename T, typename TA = T>
 struct EncPolicy {
+  static constexpr bool XCD_SYNC = false;
   static constexpr bool A_KC = true, B_KC = false;
   typedef TA AType;
   Dims D;
@@ -208,12 +209,14 @@ struct EncPolicy {
 // ---------------------------------------------------------------------------
 template <typename T>
 struct DecPolicy {
+  static constexpr bool XCD_SYNC = true;
   static constexpr bool A_KC = true, B_KC = false;
   typedef T AType;
   Dims D;
   int M, N, kseg, lda, ldb;
   const T* z; const T* W_dec; const float* b_dec; float* y_hat;
   const int32_t* skip_flags; int kcap;
+  uint32_t* xcd_sync;   // 8 counters, 64 words apart, zero at launch (or NULL): see main_loop
   // the dense decode stands down when the device-side switch selected the gather path
   __device__ bool skip() const { return skip_flags && gather_selected(skip_flags, kcap); }
   struct GInfo { int lp; };
@@ -248,6 +251,7 @@ struct DecPolicy {
 // ---------------------------------------------------------------------------
 template <typename T>
 struct DzPolicy {
+  static constexpr bool XCD_SYNC = false;
   static constexpr bool A_KC = true, B_KC = true;
   typedef T AType;
   Dims D;
@@ -319,6 +323,7 @@ struct DzPolicy {
 // run of code and every wait counts exactly the loads that were issued).
 template <typename T, bool ADAM>
 struct DWdecPolicy {
+  static constexpr bool XCD_SYNC = false;
   static constexpr bool A_KC = false, B_KC = false;
   typedef T AType;
   Dims D;
@@ -369,6 +374,7 @@ struct DWdecPolicy {
 // ---------------------------------------------------------------------------
 template <typename T, bool ADAM, typename TA = T>
 struct DWencPolicy {
+  static constexpr bool XCD_SYNC = false;
   static constexpr bool A_KC = false, B_KC = false;
   typedef TA AType;
   Dims D;

@@ -131,6 +131,122 @@ __global__ __launch_bounds__(512) void mfma_loop_kernel(int iters, int random_da
   if (sum == 1.2345678e-30f && keep == 0x12345u) out[2] = t;   // never true in practice; makes the results observable
 }
 
+// The same parts arranged the way a kernel with ONE wavefront per SIMD would have them: 4 waves of 256 lanes,
+// each owning a 128x128 block as 4x4 accumulators (256 registers), eight fragment reads feed sixteen MFMAs
+// (2/3 of the LDS read traffic of the 4x2 arrangement), fragments double-buffered so the reads of the next
+// 16-wide slice are in flight under the MFMAs of the current one.  DMA: the staging writes are direct
+// global-to-LDS loads instead of loads into registers followed by LDS writes.
+__shared__ __align__(16) uint32_t dma_lds[4][1024];   // 4 KB per wave: landing zone of the direct-to-LDS loads
+
+template <int MODE>
+__global__ __launch_bounds__(256) void mfma_loop4_kernel(int iters, int random_data, const char* __restrict__ buf,
+                                                         unsigned long long* out) {
+  constexpr bool LDS_READS = MODE & DIAG_LDS_READS, LDS_WRITES = MODE & DIAG_LDS_WRITES;
+  constexpr bool LOADS = MODE & DIAG_LOADS_L2, FAR = MODE & DIAG_LOADS_FAR, DMA = MODE & DIAG_LDS_DMA;
+  extern __shared__ __align__(16) uint16_t smem[];
+  const uint32_t t = blockIdx.x * 256u + threadIdx.x;
+  const int lane = threadIdx.x & 63, w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), wm = w >> 1, wn = w & 1;
+  const int lt = threadIdx.x;
+  if (LDS_READS || LDS_WRITES) {
+    for (int i = threadIdx.x; i < LDS_BYTES / 4; i += 256)
+      reinterpret_cast<uint32_t*>(smem)[i] = random_data ? rand_bf16x2(mix(t * 977u + i)) : 0u;
+    __syncthreads();
+  }
+  u32x4 fa[2][4], fb[2][4], rg[16];
+#pragma unroll
+  for (int b = 0; b < 2; ++b)
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        fa[b][i][c] = random_data ? rand_bf16x2(mix(t * 64u + b * 32u + i * 4u + c)) : 0u;
+        fb[b][i][c] = random_data ? rand_bf16x2(mix(t * 64u + 16u + b * 32u + i * 4u + c)) : 0u;
+      }
+#pragma unroll
+  for (int i = 0; i < 16; ++i) rg[i] = fa[i & 1][(i >> 1) & 3];
+  f32x16_t acc[4][4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+  // twice the workgroup count of the 8-wave kernel would double the regions; this kernel also runs one
+  // workgroup per CU, so the same regions serve: 16 loads of 1 KB per wave and K step, 64 KB per workgroup
+  const char* near = buf + (size_t)blockIdx.x * DIAG_NEAR_BYTES + (size_t)(w * 64 + lane) * 16;
+  const char* far = buf + (size_t)gridDim.x * DIAG_NEAR_BYTES + (size_t)blockIdx.x * DIAG_FAR_BYTES + (size_t)(w * 64 + lane) * 16;
+  const int frow = lane & 31, fch = lane >> 5;
+  auto frags = [&](int st, int s, int b) {
+    const uint16_t* a = smem + st * STAGE_ELEMS;
+    const uint16_t* bb = a + 256 * TK;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) fa[b][i] = *reinterpret_cast<const u32x4*>(a + lds_off(wm * 128 + i * 32 + frow, 2 * s + fch));
+#pragma unroll
+    for (int j = 0; j < 4; ++j) fb[b][j] = *reinterpret_cast<const u32x4*>(bb + lds_off(wn * 128 + j * 32 + frow, 2 * s + fch));
+  };
+  if (LDS_READS) frags(0, 0, 0);
+  const long long c0 = clock64(), w0 = wall_clock64();
+  for (int it = 0; it < iters; ++it) {
+    if (LDS_WRITES && !DMA) {      // the tile fetched during the previous step goes to LDS, 16 x 16 bytes per lane
+      uint16_t* st = smem + (it & 1) * STAGE_ELEMS;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) *reinterpret_cast<u32x4*>(st + (i >> 3) * 256 * TK + lds_off((lt >> 3) + 32 * (i & 7), lt & 7)) = rg[i];
+    }
+    if (LOADS) {
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const char* src = (FAR && (i & 1)) ? far + (((size_t)it * 8 + (i >> 1)) * 4096) % DIAG_FAR_BYTES : near + (size_t)i * 4096;
+        if (DMA)
+          __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src),
+                                           (__attribute__((address_space(3))) void*)(&dma_lds[w][(i & 3) * 256]), 16, 0, 0);
+        else
+          rg[i] = *reinterpret_cast<const u32x4*>(src);
+      }
+    }
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {         // the four 16-wide slices of one K step of 64
+      const int b = s & 1;
+      if (LDS_READS) frags(s == 3 ? (it + 1) & 1 : it & 1, (s + 1) & 3, b ^ 1);   // next slice under these MFMAs
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, fa[b][i]),
+                                                              __builtin_bit_cast(bf16x8_t, fb[b][j]), acc[i][j], 0, 0, 0);
+    }
+    asm volatile("" : "+v"(fa[0][0]), "+v"(fb[0][0]));
+  }
+  const long long c1 = clock64(), w1 = wall_clock64();
+  float sum = 0.f;
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) sum += acc[i][j][r];
+  uint32_t keep = DMA ? dma_lds[w][lane] : 0u;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) keep ^= rg[i][0] ^ rg[i][3];
+  if (t == 0) {
+    out[0] = (unsigned long long)(c1 - c0);
+    out[1] = (unsigned long long)(w1 - w0);
+  }
+  if (sum == 1.2345678e-30f && keep == 0x12345u) out[2] = t;
+}
+
+template <int MODE>
+hipError_t launch_mode4(hipStream_t s, int workgroups, int iters, int random_data, const void* buf, unsigned long long* out) {
+  const bool lds = MODE & (DIAG_LDS_READS | DIAG_LDS_WRITES);
+  if (lds) {
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&mfma_loop4_kernel<MODE>),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
+    if (e != hipSuccess) return e;
+  }
+  hipLaunchKernelGGL((mfma_loop4_kernel<MODE>), dim3(workgroups), dim3(256), lds ? LDS_BYTES : 0, s, iters, random_data,
+                     static_cast<const char*>(buf), out);
+  return hipGetLastError();
+}
+
 template <int MODE>
 hipError_t launch_mode(hipStream_t s, int workgroups, int iters, int random_data, const void* buf, unsigned long long* out) {
   const bool lds = MODE & (DIAG_LDS_READS | DIAG_LDS_WRITES);
@@ -148,7 +264,15 @@ hipError_t launch_mode(hipStream_t s, int workgroups, int iters, int random_data
 
 hipError_t launch_mfma_loop(hipStream_t s, int workgroups, int iters, int mode, const void* buf, unsigned long long* out) {
   const int rnd = mode & DIAG_RANDOM_DATA;
+  constexpr int W4 = DIAG_FOUR_WAVES, RW = DIAG_LDS_READS | DIAG_LDS_WRITES, LD = DIAG_LOADS_L2, DMA = DIAG_LDS_DMA;
   switch (mode & ~DIAG_RANDOM_DATA) {
+    case W4: return launch_mode4<0>(s, workgroups, iters, rnd, buf, out);
+    case W4 | DIAG_LDS_READS: return launch_mode4<DIAG_LDS_READS>(s, workgroups, iters, rnd, buf, out);
+    case W4 | RW: return launch_mode4<RW>(s, workgroups, iters, rnd, buf, out);
+    case W4 | RW | LD: return launch_mode4<RW | LD>(s, workgroups, iters, rnd, buf, out);
+    case W4 | RW | LD | DIAG_LOADS_FAR: return launch_mode4<RW | LD | DIAG_LOADS_FAR>(s, workgroups, iters, rnd, buf, out);
+    case W4 | RW | LD | DMA: return launch_mode4<RW | LD | DMA>(s, workgroups, iters, rnd, buf, out);
+    case W4 | RW | LD | DIAG_LOADS_FAR | DMA: return launch_mode4<RW | LD | DIAG_LOADS_FAR | DMA>(s, workgroups, iters, rnd, buf, out);
     case 0: return launch_mode<0>(s, workgroups, iters, rnd, buf, out);
     case DIAG_LDS_READS: return launch_mode<DIAG_LDS_READS>(s, workgroups, iters, rnd, buf, out);
     case DIAG_LDS_READS | DIAG_LDS_WRITES: return launch_mode<DIAG_LDS_READS | DIAG_LDS_WRITES>(s, workgroups, iters, rnd, buf, out);

@@ -22,6 +22,7 @@
 #include "common.h"
 #include "gemm_policies.h"
 
+#include <cstdlib>
 #include <type_traits>
 
 namespace clt {
@@ -167,7 +168,7 @@ constexpr int NTHREADS = 512;   // 8 wavefronts: two per SIMD, so one's memory p
 // matrices and kseg is a multiple of 64 (no predication at all).
 template <class P, bool EDGE>
 __device__ __forceinline__ void main_loop(const P& p, const typename P::GInfo& gi, int m0, int n0, bf16_t* smem,
-                                          f32x16_t (&acc)[4][2], int t) {
+                                          f32x16_t (&acc)[4][2], int t, uint32_t& sync_count) {
   typedef typename P::AType TA;
   const int lane = t & 63, w = t >> 6, wm = w >> 2, wn = w & 3;
   const int lt = t & 255;
@@ -201,6 +202,26 @@ __device__ __forceinline__ void main_loop(const P& p, const typename P::GInfo& g
       if (ld_seg < nseg) {
         Aseg = p.a_seg(gi, ld_seg);
         Bseg = p.b_seg(gi, ld_seg);
+      }
+    }
+  };
+  // Keeping an XCD's workgroups in step (policies with an xcd_sync member, persistent launches only).  The 32
+  // tiles an XCD works on share 12 operand panels through its 4 MB L2, which holds about ten K steps of them:
+  // tiles that drift further apart fetch every panel from the fabric again.  At the start of every K segment
+  // the workgroup books itself on its XCD's counter and its first wave waits, for a bounded time, until all
+  // 32 have done so (every workgroup of an XCD walks the same groups in the same order, so the n-th booking
+  // of each belongs together).  Only a pacing aid: a wait that runs into its bound just goes on.
+  auto xcd_sync = [&]() {
+    if constexpr (P::XCD_SYNC) {
+      ++sync_count;
+      if (p.xcd_sync && t == 0) {
+        uint32_t* ctr = p.xcd_sync + (blockIdx.x & 7) * 64;
+        const uint32_t want = (gridDim.x >> 3) * sync_count;
+        __hip_atomic_fetch_add(ctr, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        for (int spin = 0; spin < 400; ++spin) {
+          if (__hip_atomic_load(ctr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= want) break;
+          __builtin_amdgcn_s_sleep(2);
+        }
       }
     }
   };
@@ -267,7 +288,10 @@ __device__ __forceinline__ void main_loop(const P& p, const typename P::GInfo& g
     __syncthreads();
     for (int kt = 0; kt < nk; ++kt) {
       if (kt >= 1) stage(kt & 1);
-      if (kt + 1 < nk) fetch();
+      if (kt + 1 < nk) {
+        if (ld_k0 == 0) xcd_sync();   // the fetch opens a new K segment
+        fetch();
+      }
       __syncthreads();
       compute(kt);
       __syncthreads();
@@ -364,6 +388,7 @@ __global__ __launch_bounds__(NTHREADS) void gemm_bf16_kernel(P p, TileGrid tg, i
   extern __shared__ __align__(16) bf16_t smem[];
   if (p.skip()) return;
   constexpr bool LOOP = P::PERSISTENT && INTERIOR;   // (the predicated code has no registers to spare for the loop either)
+  uint32_t sync_count = 0;   // K segments this workgroup has opened so far (see xcd_sync in main_loop)
   int vb = blockIdx.x;
   do {
     int gorder, tm, tn;
@@ -387,12 +412,12 @@ __global__ __launch_bounds__(NTHREADS) void gemm_bf16_kernel(P p, TileGrid tg, i
     int t = threadIdx.x;
     asm volatile("" : "+v"(t));
     if (INTERIOR) {   // no tile of this launch touches an edge
-      main_loop<P, false>(p, gi, m0, n0, smem, acc, t);
+      main_loop<P, false>(p, gi, m0, n0, smem, acc, t, sync_count);
       epilogue<P, false>(p, gi, m0, n0, smem, acc, t);
     } else {
       const bool inside = (m0 + TM <= p.M) && (n0 + TN <= p.N);
-      if (inside && p.kseg % TK == 0) main_loop<P, false>(p, gi, m0, n0, smem, acc, t);
-      else main_loop<P, true>(p, gi, m0, n0, smem, acc, t);
+      if (inside && p.kseg % TK == 0) main_loop<P, false>(p, gi, m0, n0, smem, acc, t, sync_count);
+      else main_loop<P, true>(p, gi, m0, n0, smem, acc, t, sync_count);
       if (inside) epilogue<P, false>(p, gi, m0, n0, smem, acc, t);
       else epilogue<P, true>(p, gi, m0, n0, smem, acc, t);
     }
@@ -415,6 +440,18 @@ hipError_t launch(hipStream_t s, const P& p, int G) {
     const int pass = g_num_wg_slots / 8;   // slots per XCD that one pass of the grid covers
     const bool even_shares = P::UNIFORM_K || tg.per_xcd % pass == 0;
     const int grid = (P::PERSISTENT && even_shares && nwg > g_num_wg_slots) ? g_num_wg_slots : nwg;
+    if constexpr (P::XCD_SYNC) {
+      // pacing needs every workgroup of an XCD to open the same K segments: a tile loop in which no slot is empty
+      const bool full = grid < nwg && (tg.mt * tg.nt) % tg.S == 0 && G % tg.nteams == 0 && nwg % grid == 0;
+      P q = p;
+      if (!full || getenv("CLT_NO_XCD_PACING")) q.xcd_sync = nullptr;
+      if (q.xcd_sync) {
+        const hipError_t ez = launch_zero_i32(s, reinterpret_cast<int32_t*>(q.xcd_sync), 8 * 64);
+        if (ez != hipSuccess) return ez;
+      }
+      hipLaunchKernelGGL((gemm_bf16_kernel<P, true>), dim3(grid), dim3(NTHREADS), LDS_BYTES, s, q, tg, nwg);
+      return hipGetLastError();
+    }
     hipLaunchKernelGGL((gemm_bf16_kernel<P, true>), dim3(grid), dim3(NTHREADS), LDS_BYTES, s, p, tg, nwg);
   } else {
     hipLaunchKernelGGL((gemm_bf16_kernel<P, false>), dim3(nwg), dim3(NTHREADS), LDS_BYTES, s, p, tg, nwg);
@@ -465,7 +502,8 @@ hipError_t launch_enc_bf16(hipStream_t s, Dims D, const EncArgs& a, bool int8_x)
   return launch(s, p, D.L);
 }
 hipError_t launch_dec_bf16(hipStream_t s, Dims D, const DecArgs& a) {
-  DecPolicy<bf16_t> p{D, D.B, D.d, D.F, D.F, D.d, (const bf16_t*)a.z, (const bf16_t*)a.W_dec, a.b_dec, a.y_hat, a.skip_flags, a.kcap};
+  DecPolicy<bf16_t> p{D, D.B, D.d, D.F, D.F, D.d, (const bf16_t*)a.z, (const bf16_t*)a.W_dec, a.b_dec, a.y_hat, a.skip_flags, a.kcap,
+                      a.xcd_sync};
   return launch(s, p, D.L);
 }
 hipError_t launch_dz_bf16(hipStream_t s, Dims D, const DzArgs& a) {

@@ -98,7 +98,7 @@ hipError_t launch_enc_f32(hipStream_t s, Dims D, const EncArgs& a) {
   return launch(s, p, D.L);
 }
 hipError_t launch_dec_f32(hipStream_t s, Dims D, const DecArgs& a) {
-  DecPolicy<float> p{D, D.B, D.d, D.F, D.F, D.d, (const float*)a.z, (const float*)a.W_dec, a.b_dec, a.y_hat, a.skip_flags, a.kcap};
+  DecPolicy<float> p{D, D.B, D.d, D.F, D.F, D.d, (const float*)a.z, (const float*)a.W_dec, a.b_dec, a.y_hat, a.skip_flags, a.kcap, nullptr};
   return launch(s, p, D.L);
 }
 hipError_t launch_dz_f32(hipStream_t s, Dims D, const DzArgs& a) {

@@ -176,6 +176,15 @@ def test_fused_backward_adam_step(dtype, master, L, d, F, B):
     show(f"fused {dtype} master={master} L{L} d{d}", compare_step(w, g, o, TOL[dtype]))
 
 
+@pytest.mark.parametrize("B,master", [(2048, False), (4096, True)])
+def test_bf16_fused_update_many_tiles_per_cu(B, master):
+    """The fused update at a size where every CU sees several tiles of both weight-gradient launches (dW_dec 21
+    blocks x 88 tiles, dW_enc 6 x 88, no edge tiles, 32 / 64 K steps per tile), with and without master weights."""
+    w = S.scaled(S.WORKLOADS["gpt2"], L=6, d=1024, F=5632, B=B, k_active=32, seed=78, master_weights=master)
+    g, o = run_both(w, fused=True)
+    show(f"bf16 fused update, many tiles, B={B} master={master}", compare_step(w, g, o, TOL["bf16"]))
+
+
 def test_fused_equals_unfused_with_fp32_storage():
     """With fp32 storage the gradient enters Adam unrounded on both paths: same gradients
     bit for bit, same update up to the contraction order of the two compiled epilogues."""
