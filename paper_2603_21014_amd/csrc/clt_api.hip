@@ -121,7 +121,9 @@ int check_config(const clt_config* c, char* err) {
 Plan make_plan(const clt_config* c) {
   const size_t L = c->L, d = c->d, F = c->F, B = c->B;
   const size_t esz = c->dtype == CLT_DTYPE_BF16 ? 2 : 4;
-  const size_t rbs = row_blocks(c->B);
+  // row blocks of the column-partial arrays: 32-row blocks of the reduction kernels, or the 128-row half
+  // tiles of the dz epilogue that folds the straight-through reductions in (whichever is more)
+  const size_t rbs = row_blocks(c->B) > fold_row_blocks(c->B) ? row_blocks(c->B) : fold_row_blocks(c->B);
   const size_t wide = F > d ? F : d;
   Plan p;
   size_t o = 0;
@@ -575,6 +577,10 @@ static int backward_impl(clt_handle* h, hipStream_t s, const void* x, const floa
   const int kcap = h->plan.kcap;
   const float lam_c_over_b = h->lambda0 * h->cfg.C / (float)D.B;
   DzArgs za{d_yhat, W_dec, z, act_class, norms, lam_c_over_b, h->cfg.C, dpre, lam1_over_b, skip, kcap};
+  // dense bf16 step: the dz epilogue writes the final d pre and the column partials itself
+  const bool fold = h->bf16 && mode == CLT_DECODE_DENSE;
+  if (fold) { za.x_scale = h->int8 ? x_scale : nullptr; za.part_theta = part; za.part_benc = part2; za.part_below = part3; }
+  const int nparts = fold ? fold_row_blocks(D.B) : rbs;
   DWdecArgs wa{z, d_yhat, W_dec, G, norms, gW_dec, fdec, skip, kcap};
   DWencArgs ea{x, dpre, gW_enc, W_enc, fenc};
   GatherLists gl{reinterpret_cast<int32_t*>(h->ws + h->plan.g_idx), reinterpret_cast<float*>(h->ws + h->plan.g_val),
@@ -591,14 +597,15 @@ static int backward_impl(clt_handle* h, hipStream_t s, const void* x, const floa
   if (mode != CLT_DECODE_GATHER) {
     if (h->bf16) RUN(h, s, K_DZ, launch_dz_bf16(s, D, za)); else RUN(h, s, K_DZ, launch_dz_f32(s, D, za));
   }
-  RUN(h, s, K_STE, launch_ste_reduce(s, h->bf16, D, dpre, act_class, h->int8 ? x_scale : nullptr, norms, lam1_over_b,
-                                     part, part2, part3));
+  if (!fold)
+    RUN(h, s, K_STE, launch_ste_reduce(s, h->bf16, D, dpre, act_class, h->int8 ? x_scale : nullptr, norms, lam1_over_b,
+                                       part, part2, part3));
   if (h->cfg.activation == CLT_ACT_TOPK)     // no threshold: the window partials are all zero, and so is the gradient
-    RUN(h, s, K_COLRED, launch_col_reduce(s, part, rbs, D.L * D.F, 1.0f, nullptr, 0.f, gtheta));
+    RUN(h, s, K_COLRED, launch_col_reduce(s, part, nparts, D.L * D.F, 1.0f, nullptr, 0.f, gtheta));
   else
-    RUN(h, s, K_COLRED, launch_dtheta_final(s, part, part3, rbs, D.L * D.F, theta, h->cfg.log_threshold != 0, norms,
+    RUN(h, s, K_COLRED, launch_dtheta_final(s, part, part3, nparts, D.L * D.F, theta, h->cfg.log_threshold != 0, norms,
                                             1.0f / h->cfg.ste_bandwidth, lam1_over_b, gtheta));
-  RUN(h, s, K_COLRED, launch_col_reduce(s, part2, rbs, D.L * D.F, 1.0f, nullptr, 0.f, gb_enc));
+  RUN(h, s, K_COLRED, launch_col_reduce(s, part2, nparts, D.L * D.F, 1.0f, nullptr, 0.f, gb_enc));
   if (h->bf16) RUN(h, s, K_DWENC, launch_dwenc_bf16(s, D, ea, h->int8));
   else RUN(h, s, K_DWENC, launch_dwenc_f32(s, D, ea));
   if (mode != CLT_DECODE_DENSE) {

@@ -142,7 +142,12 @@ struct DzArgs {        // dz[l] = sum_{lp>=l} dyhat[lp] W_dec[p(l,lp)]^T + g_sp,
   float lam1_over_b;      // dead-feature coefficient lambda1 / B (0 = term off)
   const int32_t* skip_flags = nullptr;   // optional switch: stand down when the gather path is selected
   int kcap = 0;
+  // bf16 kernel only, all four or none: the straight-through reductions folded into the epilogue (then dpre is
+  // final and launch_ste_reduce is not needed).  Column partials per 128-row half tile, fold_row_blocks(B) of
+  // them: [half tile][L][F].  x_scale: the row scales of int8 inputs, or NULL.
+  const float* x_scale = nullptr; float* part_theta = nullptr; float* part_benc = nullptr; float* part_below = nullptr;
 };
+inline int fold_row_blocks(int B) { return 2 * ((B + 255) / 256); }
 // Optional Adam fused into the two weight-gradient GEMMs (m == nullptr: plain gradient output)
 struct AdamFuseArgs { float* m; float* v; float* master; AdamScalars a; };
 struct DWdecArgs {     // dW_dec[p] = z[l]^T dyhat[lp] + (G/n)[l,f] W_dec[p][f,:]

@@ -11,8 +11,9 @@
 //   M, N, kseg   tile-space extents and the length of one K segment
 //   ginfo(order) group visited at position `order` of the launch (longest K first)
 //   nseg(gi), a_seg(gi,s), b_seg(gi,s)   K segments of a group
-//   epi_begin(st, gi, col, ok)    once per tile and lane: loads what depends on the lane's
-//                columns only (biases, thresholds, norms) when `ok` (col inside the matrix)
+//   epi_begin(st, gi, col, ok, row0)   once per tile and lane: loads what depends on the lane's
+//                columns only (biases, thresholds, norms) when `ok` (col inside the matrix); row0 is the
+//                first row of the block whose rows this lane will see (wave-uniform in the bf16 kernel)
 //   epi_load(regs, gi, pos)       issues the global loads the epilogue of that 4-column
 //                group needs and keeps the results as loaded (no arithmetic on them here: that
 //                is where the wait for the load would land).  The bf16 kernel calls it ahead of
@@ -150,7 +151,7 @@ struct EncPolicy {
   static constexpr int EPI_BATCH = 8, EPI_BATCH_LATE = 8, EPI_BATCH_LAST = 8;
   static constexpr bool PERSISTENT = true, UNIFORM_K = true;
   struct EpiRegs { float s; };
-  __device__ void epi_begin(Epi& e, const GInfo& g, int col, bool ok) const {
+  __device__ void epi_begin(Epi& e, const GInfo& g, int col, bool ok, int row0) const {
     e.count = 0;
     e.b = e.th = make_float4(0.f, 0.f, 0.f, 0.f);
     if (ok) {
@@ -230,7 +231,7 @@ struct DecPolicy {
   static constexpr int EPI_BATCH = 8, EPI_BATCH_LATE = 8, EPI_BATCH_LAST = 8;
   static constexpr bool PERSISTENT = true, UNIFORM_K = false;
   struct EpiRegs {};
-  __device__ void epi_begin(Epi& e, const GInfo& g, int col, bool ok) const {
+  __device__ void epi_begin(Epi& e, const GInfo& g, int col, bool ok, int row0) const {
     e.b = ok ? *reinterpret_cast<const float4*>(b_dec + (size_t)g.lp * D.d + col) : make_float4(0.f, 0.f, 0.f, 0.f);
   }
   __device__ void epi_load(EpiRegs&, const GInfo&, const EpiPos&) const {}
@@ -249,8 +250,14 @@ struct DecPolicy {
 // 4 e / (1 + e)^2 with e = exp(-2 |C z n|): no cancellation for large arguments
 // and one hardware exponential per element.
 // ---------------------------------------------------------------------------
-template <typename T>
+// FOLD (bf16 kernel, dense mode): the epilogue also does what ste_reduce_kernel does after the plain
+// variant -- it writes the final d pre (an inactive entry inside the threshold window only lends its dz
+// to the threshold gradient; rows times the x scale for int8 inputs) and leaves, per 128-row half tile,
+// the column sums of dz over the window (-> d theta), of d pre (-> d b_enc) and of the below-threshold
+// count, summed in a fixed order: a lane over its 32 rows, then the 4 lanes that share its columns.
+template <typename T, bool FOLD_ = false>
 struct DzPolicy {
+  static constexpr bool FOLD = FOLD_;
   static constexpr bool XCD_SYNC = false;
   static constexpr bool A_KC = true, B_KC = true;
   typedef T AType;
@@ -260,10 +267,12 @@ struct DzPolicy {
   float lam_c_over_b, C; T* dpre;
   float lam1_over_b;
   const int32_t* skip_flags; int kcap;
+  const float* x_scale; float* part_theta; float* part_benc; float* part_below;   // FOLD only
   // stands down when the device-side switch selected the sparse backward
   __device__ bool skip() const { return skip_flags && gather_selected(skip_flags, kcap); }
   struct GInfo { int l; };
-  struct Epi { float4 karg, kamp, dead; };   // per column: -2 log2(e) C n, 4 (lambda0 C / B) n, -(lambda1 / B) n
+  // per column: -2 log2(e) C n, 4 (lambda0 C / B) n, -(lambda1 / B) n; FOLD: the three column sums and where they go
+  struct Epi { float4 karg, kamp, dead; float4 st, sb, nb; int col, prow; bool ok; };
   __device__ GInfo ginfo(int order) const { return {order}; }             // K = (L-l) d, longest first
   __device__ int nseg(const GInfo& g) const { return D.L - g.l; }
   __device__ const T* a_seg(const GInfo& g, int s) const { return d_yhat + (size_t)(g.l + s) * D.B * D.d; }
@@ -272,20 +281,27 @@ struct DzPolicy {
   }
   static constexpr int EPI_BATCH = 8, EPI_BATCH_LATE = 8, EPI_BATCH_LAST = 8;
   static constexpr bool PERSISTENT = false, UNIFORM_K = false;   // measured: 16.4 ms as a tile loop, 15.9 ms with one workgroup per tile
-  struct EpiRegs { uint32_t c4; typename Elem<T>::Raw4 z4; };
-  __device__ void epi_begin(Epi& e, const GInfo& g, int col, bool ok) const {
+  struct EpiRegs { uint32_t c4; typename Elem<T>::Raw4 z4; float s; };
+  __device__ void epi_begin(Epi& e, const GInfo& g, int col, bool ok, int row0) const {
     float4 n4 = make_float4(0.f, 0.f, 0.f, 0.f);
     if (ok) n4 = *reinterpret_cast<const float4*>(norms + (size_t)g.l * D.F + col);
     const float ka = -2.0f * 1.4426950408889634f * C, kb = 4.0f * lam_c_over_b, kd = 0.0f - lam1_over_b;
     e.karg = make_float4(ka * n4.x, ka * n4.y, ka * n4.z, ka * n4.w);
     e.kamp = make_float4(kb * n4.x, kb * n4.y, kb * n4.z, kb * n4.w);
     e.dead = make_float4(kd * n4.x, kd * n4.y, kd * n4.z, kd * n4.w);
+    if (FOLD) {
+      e.st = e.sb = e.nb = make_float4(0.f, 0.f, 0.f, 0.f);
+      e.col = col;
+      e.ok = ok;
+      e.prow = row0 >> 7;     // the wave's 128-row half tile
+    }
   }
   __device__ void epi_load(EpiRegs& r, const GInfo& g, const EpiPos& pos) const {
     const size_t uo = pos.uoff((size_t)g.l * D.B, D.F);
     const uint32_t lo = pos.loff(D.F);
     r.c4 = *reinterpret_cast<const uint32_t*>(epi_ptr(cls, uo, lo));
     r.z4 = Elem<T>::load_raw4(epi_ptr(z, uo, lo));
+    if (FOLD) r.s = x_scale ? *epi_ptr(x_scale, (size_t)g.l * D.B + pos.ru, (uint32_t)pos.rl) : 1.0f;
   }
   __device__ void epi4(Epi& e, const GInfo& g, const EpiPos& pos, float4 v, const EpiRegs& r) const {
     const uint32_t c4 = r.c4;
@@ -296,24 +312,57 @@ struct DzPolicy {
       const float zz[4] = {z4.x, z4.y, z4.z, z4.w};
       const float vv[4] = {v.x, v.y, v.z, v.w};
       const float ka[4] = {e.karg.x, e.karg.y, e.karg.z, e.karg.w}, kb[4] = {e.kamp.x, e.kamp.y, e.kamp.z, e.kamp.w};
-      float o[4];
+      float o[4], win[4];
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         const float ex = __builtin_amdgcn_exp2f(ka[i] * fabsf(zz[i]));
         const float s = 1.0f + ex;
         const float gsp = kb[i] * ex * __builtin_amdgcn_rcpf(s * s);
         const uint32_t ci = (c4 >> (8 * i)) & 7u;
+        const float dzv = vv[i] + gsp;
         // elsewhere only the dead-feature gradient of pre < theta
-        o[i] = (ci & 3u) ? vv[i] + gsp : ((ci & CLS_BELOW) ? dg[i] + 0.0f : 0.0f);
+        const float below = (ci & CLS_BELOW) ? dg[i] + 0.0f : 0.0f;
+        if (FOLD) {
+          win[i] = (ci & CLS_WINDOW) ? dzv : 0.0f;
+          o[i] = (ci & CLS_ACTIVE) ? dzv : below;
+        } else {
+          o[i] = (ci & 3u) ? dzv : below;
+        }
       }
       out = make_float4(o[0], o[1], o[2], o[3]);
+      if (FOLD) { e.st.x += win[0]; e.st.y += win[1]; e.st.z += win[2]; e.st.w += win[3]; }
     } else if (lam1_over_b != 0.f && c4) {
       out = make_float4((c4 & 0x4u) ? dg[0] : 0.f, (c4 & 0x400u) ? dg[1] : 0.f, (c4 & 0x40000u) ? dg[2] : 0.f,
                         (c4 & 0x4000000u) ? dg[3] : 0.f);
     }
+    if (FOLD) {
+      e.sb.x += out.x; e.sb.y += out.y; e.sb.z += out.z; e.sb.w += out.w;
+      if (lam1_over_b != 0.f) {
+        e.nb.x += (c4 & 0x4u) ? 1.f : 0.f; e.nb.y += (c4 & 0x400u) ? 1.f : 0.f;
+        e.nb.z += (c4 & 0x40000u) ? 1.f : 0.f; e.nb.w += (c4 & 0x4000000u) ? 1.f : 0.f;
+      }
+      const float s = r.s;   // int8 inputs: the encoder-weight gradient contracts d pre with the integer codes
+      out = make_float4(out.x * s, out.y * s, out.z * s, out.w * s);
+    }
     Elem<T>::store4(epi_ptr(dpre, pos.uoff((size_t)g.l * D.B, D.F), pos.loff(D.F)), out);
   }
-  __device__ void epi_end(Epi&, const GInfo&) const {}
+  __device__ void epi_end(Epi& e, const GInfo& g) const {
+    if (!FOLD) return;
+    float* const dst[3] = {part_theta, part_benc, part_below};
+    float4* const src[3] = {&e.st, &e.sb, &e.nb};
+#pragma unroll
+    for (int q = 0; q < 3; ++q) {
+      if (q == 2 && lam1_over_b == 0.f) break;
+      float a[4] = {src[q]->x, src[q]->y, src[q]->z, src[q]->w};
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {      // the 4 lanes that own these columns (lane / 16 = row inside a row group)
+        a[i] += __shfl_xor(a[i], 16, 64);
+        a[i] += __shfl_xor(a[i], 32, 64);
+      }
+      if (e.ok && (threadIdx.x & 48) == 0)
+        *reinterpret_cast<float4*>(dst[q] + ((size_t)e.prow * D.L + g.l) * D.F + e.col) = make_float4(a[0], a[1], a[2], a[3]);
+    }
+  }
 };
 
 // ---------------------------------------------------------------------------
@@ -347,7 +396,7 @@ struct DWdecPolicy {
   static constexpr int EPI_BATCH = 4, EPI_BATCH_LATE = 8, EPI_BATCH_LAST = 8;
   static constexpr bool PERSISTENT = !ADAM, UNIFORM_K = true;
   struct EpiRegs { float Gf, nf; typename Elem<T>::Raw4 w; AdamRegs ad; };
-  __device__ void epi_begin(Epi&, const GInfo&, int, bool) const {}
+  __device__ void epi_begin(Epi&, const GInfo&, int, bool, int) const {}
   __device__ void epi_load(EpiRegs& r, const GInfo& g, const EpiPos& pos) const {
     const size_t nf = (size_t)g.l * D.F + pos.ru;
     r.Gf = *epi_ptr(G, nf, (uint32_t)pos.rl);
@@ -391,7 +440,7 @@ struct DWencPolicy {
   static constexpr int EPI_BATCH = 4, EPI_BATCH_LATE = 8, EPI_BATCH_LAST = 8;
   static constexpr bool PERSISTENT = !ADAM, UNIFORM_K = true;
   struct EpiRegs { AdamRegs ad; typename Elem<T>::Raw4 w; };
-  __device__ void epi_begin(Epi&, const GInfo&, int, bool) const {}
+  __device__ void epi_begin(Epi&, const GInfo&, int, bool, int) const {}
   __device__ void epi_load(EpiRegs& r, const GInfo& g, const EpiPos& pos) const {
     if (!ADAM) return;
     const size_t uo = pos.uoff((size_t)g.l * D.d, D.F);

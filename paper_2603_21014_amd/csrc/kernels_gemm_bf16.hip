@@ -334,7 +334,7 @@ __device__ __forceinline__ void epilogue(const P& p, const typename P::GInfo& gi
   pos.ru = 0;
   const bool col_ok = !EDGE || pos.col() < N;
   typename P::Epi est;
-  p.epi_begin(est, gi, pos.col(), col_ok);
+  p.epi_begin(est, gi, pos.col(), col_ok, m0 + wm * 128);
   // The wave's block is 32 row groups of 4 rows (4 slabs of 8).  Each slab goes through the wave's
   // private LDS region (a wave's LDS accesses complete in issue order, so the transposition needs
   // no barrier).  The global loads the policy's epilogue needs run ahead of their use as a rolling
@@ -480,6 +480,7 @@ hipError_t init_gemm_bf16() {
   if ((e = set_lds_attr<EncPolicy<bf16_t, int8_t>>()) != hipSuccess) return e;
   if ((e = set_lds_attr<DecPolicy<bf16_t>>()) != hipSuccess) return e;
   if ((e = set_lds_attr<DzPolicy<bf16_t>>()) != hipSuccess) return e;
+  if ((e = set_lds_attr<DzPolicy<bf16_t, true>>()) != hipSuccess) return e;
   if ((e = set_lds_attr<DWdecPolicy<bf16_t, false>>()) != hipSuccess) return e;
   if ((e = set_lds_attr<DWdecPolicy<bf16_t, true>>()) != hipSuccess) return e;
   if ((e = set_lds_attr<DWencPolicy<bf16_t, false>>()) != hipSuccess) return e;
@@ -506,11 +507,16 @@ hipError_t launch_dec_bf16(hipStream_t s, Dims D, const DecArgs& a) {
                       a.xcd_sync};
   return launch(s, p, D.L);
 }
-hipError_t launch_dz_bf16(hipStream_t s, Dims D, const DzArgs& a) {
-  DzPolicy<bf16_t> p{D, D.B, D.F, D.d, D.d, D.d,
-                     (const bf16_t*)a.d_yhat, (const bf16_t*)a.W_dec, (const bf16_t*)a.z, a.cls, a.norms,
-                     a.lam_c_over_b, a.C, (bf16_t*)a.dpre, a.lam1_over_b, a.skip_flags, a.kcap};
+template <bool FOLD>
+static hipError_t launch_dz_mode(hipStream_t s, Dims D, const DzArgs& a) {
+  DzPolicy<bf16_t, FOLD> p{D, D.B, D.F, D.d, D.d, D.d,
+                           (const bf16_t*)a.d_yhat, (const bf16_t*)a.W_dec, (const bf16_t*)a.z, a.cls, a.norms,
+                           a.lam_c_over_b, a.C, (bf16_t*)a.dpre, a.lam1_over_b, a.skip_flags, a.kcap,
+                           a.x_scale, a.part_theta, a.part_benc, a.part_below};
   return launch(s, p, D.L);
+}
+hipError_t launch_dz_bf16(hipStream_t s, Dims D, const DzArgs& a) {
+  return a.part_theta ? launch_dz_mode<true>(s, D, a) : launch_dz_mode<false>(s, D, a);
 }
 template <bool ADAM>
 static hipError_t launch_dwdec_mode(hipStream_t s, Dims D, const DWdecArgs& a) {

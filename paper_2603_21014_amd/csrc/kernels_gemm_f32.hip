@@ -64,7 +64,7 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(P p, TileGrid tg) {
 
   typename P::Epi est;
   const int col = n0 + tx * 4;
-  p.epi_begin(est, gi, col, col < N);
+  p.epi_begin(est, gi, col, col < N, m0);
   if (col < N) {
     typename P::EpiRegs er[4];
     EpiPos pos{m0, n0, 0, tx * 4};
@@ -104,7 +104,8 @@ hipError_t launch_dec_f32(hipStream_t s, Dims D, const DecArgs& a) {
 hipError_t launch_dz_f32(hipStream_t s, Dims D, const DzArgs& a) {
   DzPolicy<float> p{D, D.B, D.F, D.d, D.d, D.d,
                     (const float*)a.d_yhat, (const float*)a.W_dec, (const float*)a.z, a.cls, a.norms,
-                    a.lam_c_over_b, a.C, (float*)a.dpre, a.lam1_over_b, a.skip_flags, a.kcap};
+                    a.lam_c_over_b, a.C, (float*)a.dpre, a.lam1_over_b, a.skip_flags, a.kcap,
+                    nullptr, nullptr, nullptr, nullptr};
   return launch(s, p, D.L);
 }
 template <bool ADAM>
