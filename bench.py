@@ -366,7 +366,8 @@ def main():
                      C_=w.C, ste_bandwidth=w.ste_eps, device=dev, keep_pre=w.lambda1 > 0,
                      log_threshold=w.log_threshold, topk=w.topk or None,
                      decode_mode={"dense": K.DECODE_DENSE, "gather": K.DECODE_GATHER, "auto": K.DECODE_AUTO}[args.decode_mode],
-                     gather_density_threshold=args.gather_density_threshold, matrix_grads=False)
+                     gather_density_threshold=args.gather_density_threshold, matrix_grads=False,
+                     reuse_decoder_norms=True)
     torch.cuda.synchronize()
     log(f"workload {w.name}: L={w.L} d={w.d} F={w.F} B={w.B}, inputs ready in {time.perf_counter() - t0:.1f}s, "
         f"{torch.cuda.memory_allocated() / 2**30:.1f} GiB allocated")
@@ -468,7 +469,7 @@ def main():
         "config": {"workload": w.name, "L": w.L, "d_model": w.d, "features_per_layer": w.F, "tokens": w.B,
                    "decoder_blocks": w.P, "int8_inputs": w.int8_inputs, "master_weights": w.master_weights,
                    "activation": f"topk{w.topk}" if w.topk else "jumprelu", "decode_mode": args.decode_mode,
-                   "fused_adam": True},
+                   "fused_adam": True, "reuse_decoder_norms": True},
         "median_ms_per_step_profiled_pass": median_ms,
         "step_dense_tflops": flop / (ms_per_step * 1e-3) / 1e12,
         "step_frac_of_bf16_mfma_peak": flop / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,

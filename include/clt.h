@@ -87,6 +87,14 @@ typedef struct clt_config {
                              decided on the fp32 pre-activation.  With TopK the theta tensor is
                              ignored by every call, its gradient is 0 and lambda1 must be 0.       */
   int32_t topk_k;         /* 0 <= topk_k <= F; read only when activation == CLT_ACT_TOPK           */
+  int32_t reuse_decoder_norms; /* 0: every clt_forward computes the decoder norms (App. B) from W_dec.
+                             1: a training loop that owns its weights may skip that pass over W_dec: a
+                             clt_backward_adam_step that updates W_dec inside its weight-gradient GEMM
+                             (bf16, dense mode, F and d multiples of 256) also leaves the row sums of
+                             squares of the UPDATED weights, and the next clt_forward on this handle
+                             that is given the same W_dec pointer forms the norms from them.  The
+                             caller promises that nothing else writes W_dec between those two calls.
+                             Whenever the sums are not there, clt_forward reads W_dec as with 0.      */
   float gather_density_threshold; /* AUTO: gather when the mean active fraction of the batch
                              is <= this and no (layer, token) row has more than about 8x
                              as many active features (else the step decodes densely).

@@ -21,7 +21,7 @@ constexpr size_t ALIGN = 256;
 inline size_t align_up(size_t v) { return (v + ALIGN - 1) / ALIGN * ALIGN; }
 
 struct Plan {
-  size_t norms, G, d_yhat, dpre, part_cols, part_cols2, part_cols3, part_rec, part_sp, part_dead, l0, flags, xcd_sync, pre32, g_idx, g_val, g_counts, g_counts_w,
+  size_t norms, G, d_yhat, dpre, part_cols, part_cols2, part_cols3, part_rec, part_sp, part_dead, l0, flags, xcd_sync, n2_part, pre32, g_idx, g_val, g_counts, g_counts_w,
          fl_off, fl_cnt, fl_tok, fl_val, fl_seg, total;
   int kcap;
 };
@@ -40,13 +40,14 @@ void set_err(char* dst, const char* fmt, ...) {
 enum KernelId {
   K_NORMS, K_ENC, K_DEC, K_LOSS_SP, K_LOSS_REC, K_LOSS_FINAL, K_COLRED, K_DZ, K_STE, K_DWENC, K_DWDEC,
   K_ADAM_WDEC, K_ADAM_WENC, K_ADAM_VEC, K_ZERO, K_DECIDE, K_COMPACT, K_GATHER, K_SP_FILL, K_GATHER_DZ, K_FLISTS,
-  K_SP_DWDEC, K_TOPK, K_NORM_SUM, K_NORMALISE, K_COUNT
+  K_SP_DWDEC, K_TOPK, K_NORM_SUM, K_NORMALISE, K_NORMS_REUSE, K_COUNT
 };
 static const char* const kKernelNames[K_COUNT] = {
   "decoder_norms", "encoder_jumprelu_gemm", "decode_gemm", "loss_sparsity", "loss_reconstruction", "loss_final",
   "column_reduce", "dz_gemm", "ste_reduce", "dW_enc_gemm", "dW_dec_gemm", "adam_W_dec", "adam_W_enc",
   "adam_vectors", "zero_counters", "decode_decide", "compact_active", "gather_decode", "sparse_dpre_fill",
-  "gather_dz", "feature_lists", "sparse_dW_dec", "topk_select", "activation_norm_sum", "normalise_activations"};
+  "gather_dz", "feature_lists", "sparse_dW_dec", "topk_select", "activation_norm_sum", "normalise_activations",
+  "decoder_norms_from_update"};
 
 struct ProfSpan { int kernel; hipEvent_t a, b; };
 
@@ -63,6 +64,8 @@ struct clt_handle {
   char* ws;
   Plan plan;
   int stage;              // 0 = fresh, 1 = forward done, 2 = loss done
+  bool n2_eligible;       // the configuration can hand decoder norms from the update to the next forward
+  const void* n2_for;     // W_dec pointer whose updated row sums of squares sit in the workspace, or NULL
   float lambda0, lambda1;
   char err[256];
 };
@@ -100,6 +103,7 @@ int check_config(const clt_config* c, char* err) {
     return CLT_ERR_INVALID_ARG;
   }
   if (c->log_threshold != 0 && c->log_threshold != 1) { set_err(err, "bad log_threshold"); return CLT_ERR_INVALID_ARG; }
+  if (c->reuse_decoder_norms != 0 && c->reuse_decoder_norms != 1) { set_err(err, "bad reuse_decoder_norms"); return CLT_ERR_INVALID_ARG; }
   if (c->activation != CLT_ACT_JUMPRELU && c->activation != CLT_ACT_TOPK) { set_err(err, "bad activation %d", c->activation); return CLT_ERR_INVALID_ARG; }
   if (c->activation == CLT_ACT_TOPK && (c->topk_k < 0 || c->topk_k > c->F)) {
     set_err(err, "topk_k must be in [0, F]");
@@ -140,6 +144,9 @@ Plan make_plan(const clt_config* c) {
   p.l0 = o;         o += align_up(L * 4);
   p.flags = o;      o += align_up(4 * 4);
   p.xcd_sync = o;   o += align_up(8 * 64 * 4);   // pacing counters of the dense decode, one 256-byte line per XCD
+  // row sums of squares of the updated decoder weights, [P][d / 64][F] (reuse_decoder_norms, eligible shapes only)
+  const bool n2 = c->reuse_decoder_norms && c->dtype == CLT_DTYPE_BF16 && F % 256 == 0 && d % 256 == 0;
+  p.n2_part = o;    o += align_up(n2 ? (L * (L + 1) / 2) * (d / 64) * F * 4 : 0);
   p.pre32 = o;      o += align_up(c->activation == CLT_ACT_TOPK ? L * B * F * 4 : 0);   // fp32 pre-activations for the selection
   // active-feature lists of the gather decode: forced gather must hold a fully dense row;
   // the automatic switch only ever gathers below the threshold, so rows are capped at a
@@ -280,6 +287,8 @@ int clt_init(clt_handle** handle, const clt_config* cfg, void* workspace, size_t
   h->ws = static_cast<char*>(workspace);
   h->plan = plan;
   h->stage = 0;
+  h->n2_eligible = cfg->reuse_decoder_norms && h->bf16 && cfg->F % 256 == 0 && cfg->d % 256 == 0;
+  h->n2_for = nullptr;
   h->lambda0 = 0.f;
   h->lambda1 = 0.f;
   h->err[0] = 0;
@@ -470,7 +479,11 @@ int clt_forward(clt_handle* h, void* stream, const void* x, const float* x_scale
   int32_t* l0 = l0_per_layer ? l0_per_layer : reinterpret_cast<int32_t*>(h->ws + h->plan.l0);
   int32_t* flags = reinterpret_cast<int32_t*>(h->ws + h->plan.flags);
   RUN(h, s, K_ZERO, launch_zero_i32(s, l0, h->D.L));
-  RUN(h, s, K_NORMS, launch_decoder_norms(s, h->bf16, h->D, W_dec, norms));
+  if (h->n2_for && h->n2_for == W_dec)   // the last fused update left the sums of squares of exactly these weights
+    RUN(h, s, K_NORMS_REUSE, launch_norms_from_partials(s, h->D, reinterpret_cast<const float*>(h->ws + h->plan.n2_part), norms));
+  else
+    RUN(h, s, K_NORMS, launch_decoder_norms(s, h->bf16, h->D, W_dec, norms));
+  h->n2_for = nullptr;
   const bool topk = h->cfg.activation == CLT_ACT_TOPK;
   float* pre32 = topk ? reinterpret_cast<float*>(h->ws + h->plan.pre32) : nullptr;
   EncArgs ea{x, x_scale, W_enc, b_enc, theta, h->cfg.ste_bandwidth, z, pre, act_class, l0,
@@ -582,6 +595,7 @@ static int backward_impl(clt_handle* h, hipStream_t s, const void* x, const floa
   if (fold) { za.x_scale = h->int8 ? x_scale : nullptr; za.part_theta = part; za.part_benc = part2; za.part_below = part3; }
   const int nparts = fold ? fold_row_blocks(D.B) : rbs;
   DWdecArgs wa{z, d_yhat, W_dec, G, norms, gW_dec, fdec, skip, kcap};
+  if (h->n2_eligible && fdec.m && mode == CLT_DECODE_DENSE) wa.n2_part = reinterpret_cast<float*>(h->ws + h->plan.n2_part);
   DWencArgs ea{x, dpre, gW_enc, W_enc, fenc};
   GatherLists gl{reinterpret_cast<int32_t*>(h->ws + h->plan.g_idx), reinterpret_cast<float*>(h->ws + h->plan.g_val),
                  reinterpret_cast<int32_t*>(h->ws + h->plan.g_counts),
@@ -679,9 +693,12 @@ int clt_backward_adam_step(clt_handle* h, void* stream, const void* x, const flo
   const AdamScalars a = adam_scalars(h, t, lr);
   const AdamFuseArgs fenc{(float*)m->W_enc, (float*)v->W_enc, master ? (float*)master->W_enc : nullptr, a};
   const AdamFuseArgs fdec{(float*)m->W_dec, (float*)v->W_dec, master ? (float*)master->W_dec : nullptr, a};
+  h->n2_for = nullptr;
   rc = backward_impl(h, s, x, x_scale, params->theta, params->W_dec, params->W_enc, z, act_class, grads->W_enc,
                      grads->b_enc, grads->theta, grads->W_dec, grads->b_dec, fenc, fdec);
   if (rc != CLT_OK) return rc;
+  // the dense weight-gradient GEMM has updated W_dec and left the row sums of squares of the new weights
+  if (h->n2_eligible && h->cfg.decode_mode == CLT_DECODE_DENSE) h->n2_for = params->W_dec;
   RUN(h, s, K_ADAM_VEC, launch_adam_vector(s, (size_t)D.L * D.F, params->b_enc, grads->b_enc, m->b_enc, v->b_enc, a));
   RUN(h, s, K_ADAM_VEC, launch_adam_vector(s, (size_t)D.L * D.F, params->theta, grads->theta, m->theta, v->theta, a));
   RUN(h, s, K_ADAM_VEC, launch_adam_vector(s, (size_t)D.L * D.d, params->b_dec, grads->b_dec, m->b_dec, v->b_dec, a));
@@ -707,6 +724,7 @@ int clt_adam_step(clt_handle* h, void* stream, int64_t t, float lr, const clt_te
   hipStream_t s = static_cast<hipStream_t>(stream);
   const Dims D = h->D;
   const AdamScalars a = adam_scalars(h, t, lr);
+  h->n2_for = nullptr;   // W_dec changes here without new row sums
   const size_t n_enc = (size_t)D.L * D.d * D.F, n_dec = (size_t)D.P() * D.F * D.d;
   RUN(h, s, K_ADAM_WDEC, launch_adam_matrix(s, h->bf16, n_dec, params->W_dec, grads->W_dec, (float*)m->W_dec, (float*)v->W_dec,
                                master ? (float*)master->W_dec : nullptr, a));

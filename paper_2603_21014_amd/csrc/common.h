@@ -64,6 +64,8 @@ template <> struct Elem<float> {
   static __device__ __forceinline__ Raw4 load_raw4(const float* p) { return load4(p); }
   static __device__ __forceinline__ Raw4 nt_load_raw4(const float* p) { return nt_load_f4(p); }
   static __device__ __forceinline__ float4 widen4(Raw4 r) { return r; }
+  static __device__ __forceinline__ Raw4 narrow4(float4 v) { return v; }
+  static __device__ __forceinline__ void nt_store_raw4(float* p, Raw4 v) { nt_store_f4(p, v); }
 };
 template <> struct Elem<bf16_t> {
   static __device__ __forceinline__ float load(const bf16_t* p) { return bf16_to_f32(*p); }
@@ -95,6 +97,11 @@ template <> struct Elem<bf16_t> {
     return make_float4(__uint_as_float(u[0] << 16), __uint_as_float(u[0] & 0xffff0000u),
                        __uint_as_float(u[1] << 16), __uint_as_float(u[1] & 0xffff0000u));
   }
+  static __device__ __forceinline__ Raw4 narrow4(float4 v) {
+    const Raw4 u = {pack_bf16x2(v.x, v.y), pack_bf16x2(v.z, v.w)};
+    return u;
+  }
+  static __device__ __forceinline__ void nt_store_raw4(bf16_t* p, Raw4 u) { CLT_NT_STORE(u, reinterpret_cast<nt_u32x2*>(p)); }
 };
 
 // Adam (App. C Table 1) with bias correction, the step's scalars folded on the host:
@@ -155,6 +162,9 @@ struct DWdecArgs {     // dW_dec[p] = z[l]^T dyhat[lp] + (G/n)[l,f] W_dec[p][f,:
   AdamFuseArgs fuse;
   const int32_t* skip_flags = nullptr;   // as in DzArgs
   int kcap = 0;
+  // optional, bf16 kernel with the fused update and F, d multiples of 256: [P][d / 64][F] sums of squares of the
+  // updated weights (see launch_norms_from_partials)
+  float* n2_part = nullptr;
 };
 struct DWencArgs {     // dW_enc[l] = x[l]^T dpre[l]
   const void* x; const void* dpre; void* dW_enc; void* W_enc;
@@ -193,6 +203,9 @@ hipError_t launch_normalise(hipStream_t s, bool bf16, bool int8_a, Dims D, const
 hipError_t launch_topk_select(hipStream_t s, bool bf16, Dims D, const float* pre32, int k, void* z, uint8_t* cls,
                               int32_t* l0);
 hipError_t launch_decoder_norms(hipStream_t s, bool bf16, Dims D, const void* W_dec, float* norms);
+// the same norms from the partial sums of squares a fused weight-gradient launch left behind:
+// n[l,f] = sqrt(sum over the blocks p(l, l..L-1) and their d / 64 column runs of n2_part[p][run][f]), in that order
+hipError_t launch_norms_from_partials(hipStream_t s, Dims D, const float* n2_part, float* norms);
 // L_rec partials, d_yhat = 2 r / B, column partials for db_dec
 hipError_t launch_loss_rec(hipStream_t s, bool bf16, bool int8_y, Dims D, const float* y_hat, const void* y,
                            const float* y_scale, void* d_yhat, double* loss_part, float* col_part);

@@ -85,6 +85,7 @@ struct TileGrid {
 // 64-bit arithmetic.
 struct EpiPos {
   int ru, cu, rl, cl;
+  float* lds = nullptr;   // bf16 kernel: 128 floats of LDS private to the wave, free for the policy during the epilogue
   __device__ __forceinline__ int row() const { return ru + rl; }
   __device__ __forceinline__ int col() const { return cu + cl; }
   // offsets of (row, col) in a row-major matrix with leading dimension ld that starts base_row rows in
@@ -95,6 +96,19 @@ template <typename X>
 __device__ __forceinline__ X* epi_ptr(X* base, size_t uoff, uint32_t loff) {
   typedef typename std::conditional<std::is_const<X>::value, const char, char>::type Byte;
   return reinterpret_cast<X*>(reinterpret_cast<Byte*>(base + uoff) + loff * (uint32_t)sizeof(X));
+}
+
+// Sum over each row of 16 lanes, result in all of them: four adds on data-parallel-primitive operands (swaps
+// inside quads, then mirrored half rows and rows), no LDS round trips.
+template <int CTRL> __device__ __forceinline__ float dpp_move(float x) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), CTRL, 0xF, 0xF, true));
+}
+__device__ __forceinline__ float row16_sum(float v) {
+  v += dpp_move<0xB1>(v);    // quad_perm [1,0,3,2]
+  v += dpp_move<0x4E>(v);    // quad_perm [2,3,0,1]
+  v += dpp_move<0x141>(v);   // row_half_mirror: the other quad of the half row
+  v += dpp_move<0x140>(v);   // row_mirror: the other half row
+  return v;
 }
 
 // Adam fused into a weight-gradient epilogue: the fp32 gradient of 4 consecutive
@@ -112,9 +126,10 @@ __device__ __forceinline__ void adam_load4(AdamRegs& r, const AdamFuse& f, size_
   r.v = nt_load_f4(epi_ptr(f.v, uo, lo));
   if (f.master) r.master = nt_load_f4(epi_ptr(f.master, uo, lo));
 }
+// Returns the four weights as stored (after rounding to T).
 template <typename T>
-__device__ __forceinline__ void adam_update4(const AdamFuse& f, T* w, size_t uo, uint32_t lo, const AdamRegs& r,
-                                             typename Elem<T>::Raw4 w_raw, float4 g4) {
+__device__ __forceinline__ float4 adam_update4(const AdamFuse& f, T* w, size_t uo, uint32_t lo, const AdamRegs& r,
+                                               typename Elem<T>::Raw4 w_raw, float4 g4) {
   const float4 m4 = r.m, v4 = r.v, p4 = f.master ? r.master : Elem<T>::widen4(w_raw);
   const float g[4] = {g4.x, g4.y, g4.z, g4.w};
   float mm[4] = {m4.x, m4.y, m4.z, m4.w}, vv[4] = {v4.x, v4.y, v4.z, v4.w}, pp[4] = {p4.x, p4.y, p4.z, p4.w};
@@ -124,7 +139,9 @@ __device__ __forceinline__ void adam_update4(const AdamFuse& f, T* w, size_t uo,
   nt_store_f4(epi_ptr(f.v, uo, lo), make_float4(vv[0], vv[1], vv[2], vv[3]));
   const float4 pn = make_float4(pp[0], pp[1], pp[2], pp[3]);
   if (f.master) nt_store_f4(epi_ptr(f.master, uo, lo), pn);
-  Elem<T>::nt_store4(epi_ptr(w, uo, lo), pn);
+  const typename Elem<T>::Raw4 stored = Elem<T>::narrow4(pn);
+  Elem<T>::nt_store_raw4(epi_ptr(w, uo, lo), stored);
+  return Elem<T>::widen4(stored);
 }
 
 // ---------------------------------------------------------------------------
@@ -196,7 +213,7 @@ struct EncPolicy {
     if (pre) Elem<T>::store4(epi_ptr(pre, uo, lo), make_float4(p[0], p[1], p[2], p[3]));
     *reinterpret_cast<uint32_t*>(epi_ptr(cls, uo, lo)) = c4;
   }
-  __device__ void epi_end(Epi& e, const GInfo& g) const {
+  __device__ void epi_end(Epi& e, const GInfo& g, float*) const {
     if (!l0) return;
     int c = e.count;
 #pragma unroll
@@ -240,7 +257,7 @@ struct DecPolicy {
     *reinterpret_cast<float4*>(epi_ptr(y_hat, pos.uoff((size_t)g.lp * D.B, D.d), pos.loff(D.d))) =
         make_float4(v.x + b.x, v.y + b.y, v.z + b.z, v.w + b.w);
   }
-  __device__ void epi_end(Epi&, const GInfo&) const {}
+  __device__ void epi_end(Epi&, const GInfo&, float*) const {}
 };
 
 // ---------------------------------------------------------------------------
@@ -346,7 +363,7 @@ struct DzPolicy {
     }
     Elem<T>::store4(epi_ptr(dpre, pos.uoff((size_t)g.l * D.B, D.F), pos.loff(D.F)), out);
   }
-  __device__ void epi_end(Epi& e, const GInfo& g) const {
+  __device__ void epi_end(Epi& e, const GInfo& g, float*) const {
     if (!FOLD) return;
     float* const dst[3] = {part_theta, part_benc, part_below};
     float4* const src[3] = {&e.st, &e.sb, &e.nb};
@@ -370,7 +387,9 @@ struct DzPolicy {
 // ---------------------------------------------------------------------------
 // ADAM: the update is fused into the epilogue (compile-time, so that the epilogue is one straight
 // run of code and every wait counts exactly the loads that were issued).
-template <typename T, bool ADAM>
+// N2: the epilogue of the fused update also leaves the sums of squares of the updated weights (compile-time for
+// the same reason as ADAM: one straight run of code).
+template <typename T, bool ADAM, bool N2 = false>
 struct DWdecPolicy {
   static constexpr bool XCD_SYNC = false;
   static constexpr bool A_KC = false, B_KC = false;
@@ -381,9 +400,12 @@ struct DWdecPolicy {
   AdamFuse fuse;
   const int32_t* skip_flags; int kcap;
   int p0;   // first decoder block of this launch
+  // optional (fused update, bf16 kernel, no edge tiles): sums of squares of the UPDATED weights over each run of
+  // 64 columns of a row, [P][N / 64][F], from which the next step's decoder norms are formed without reading W_dec
+  float* n2_part;
   __device__ bool skip() const { return skip_flags && gather_selected(skip_flags, kcap); }
   struct GInfo { int p, l, lp; };
-  struct Epi {};
+  struct Epi { int row0, run; };
   __device__ GInfo ginfo(int order) const {
     int l = 0, r = order + p0;
     while (r >= D.L - l) { r -= D.L - l; ++l; }
@@ -393,10 +415,14 @@ struct DWdecPolicy {
   __device__ const T* a_seg(const GInfo& g, int) const { return z + (size_t)g.l * D.B * D.F; }
   __device__ const T* b_seg(const GInfo& g, int) const { return d_yhat + (size_t)g.lp * D.B * D.d; }
   // up to 16 registers per row group in flight: a short window while most accumulators are still live
-  static constexpr int EPI_BATCH = 4, EPI_BATCH_LATE = 8, EPI_BATCH_LAST = 8;
+  // (one group less with the sums of squares, whose registers come on top)
+  static constexpr int EPI_BATCH = N2 ? 3 : 4, EPI_BATCH_LATE = N2 ? 6 : 8, EPI_BATCH_LAST = N2 ? 7 : 8;
   static constexpr bool PERSISTENT = !ADAM, UNIFORM_K = true;
   struct EpiRegs { float Gf, nf; typename Elem<T>::Raw4 w; AdamRegs ad; };
-  __device__ void epi_begin(Epi&, const GInfo&, int, bool, int) const {}
+  __device__ void epi_begin(Epi& e, const GInfo&, int col, bool, int row0) const {
+    e.row0 = row0;
+    e.run = col >> 6;
+  }
   __device__ void epi_load(EpiRegs& r, const GInfo& g, const EpiPos& pos) const {
     const size_t nf = (size_t)g.l * D.F + pos.ru;
     r.Gf = *epi_ptr(G, nf, (uint32_t)pos.rl);
@@ -406,16 +432,30 @@ struct DWdecPolicy {
     r.w = Elem<T>::nt_load_raw4(epi_ptr(W_dec, uo, lo));
     if (ADAM) adam_load4(r.ad, fuse, uo, lo);
   }
-  __device__ void epi4(Epi&, const GInfo& g, const EpiPos& pos, float4 v, const EpiRegs& r) const {
+  __device__ void epi4(Epi& e, const GInfo& g, const EpiPos& pos, float4 v, const EpiRegs& r) const {
     const float coef = r.Gf * __builtin_amdgcn_rcpf(fmaxf(r.nf, 1e-30f));
     const size_t uo = pos.uoff((size_t)g.p * D.F, D.d);
     const uint32_t lo = pos.loff(D.d);
     const float4 w = Elem<T>::widen4(r.w);
     const float4 gr = make_float4(fmaf(coef, w.x, v.x), fmaf(coef, w.y, v.y), fmaf(coef, w.z, v.z), fmaf(coef, w.w, v.w));
     if (!ADAM || dW_dec) Elem<T>::store4(epi_ptr(dW_dec, uo, lo), gr);
-    if (ADAM) adam_update4<T>(fuse, W_dec, uo, lo, r.ad, r.w, gr);
+    if (ADAM) {
+      const float4 wn = adam_update4<T>(fuse, W_dec, uo, lo, r.ad, r.w, gr);
+      if (N2) {   // 16 lanes hold the 64 columns of one row of the wave's block
+        const float s2 = row16_sum((wn.x * wn.x + wn.y * wn.y) + (wn.z * wn.z + wn.w * wn.w));
+        // collected in the wave's LDS scratch (row inside the wave's 128-row block), written out once in epi_end
+        if ((threadIdx.x & 15) == 0) pos.lds[(pos.ru - e.row0) + pos.rl] = s2;
+      }
+    }
   }
-  __device__ void epi_end(Epi&, const GInfo&) const {}
+  __device__ void epi_end(Epi& e, const GInfo& g, float* lds) const {
+    if (!ADAM || !N2) return;
+    const int lane = threadIdx.x & 63;
+    if (lane < 32) {    // the wave's 128 row sums, 512 contiguous bytes
+      const float4 v = *reinterpret_cast<const float4*>(lds + 4 * lane);
+      *reinterpret_cast<float4*>(n2_part + ((size_t)g.p * (N >> 6) + e.run) * (size_t)M + e.row0 + 4 * lane) = v;
+    }
+  }
 };
 
 // ---------------------------------------------------------------------------
@@ -454,7 +494,7 @@ struct DWencPolicy {
     if (!ADAM || dW_enc) Elem<T>::store4(epi_ptr(dW_enc, uo, lo), v);
     if (ADAM) adam_update4<T>(fuse, W_enc, uo, lo, r.ad, r.w, v);
   }
-  __device__ void epi_end(Epi&, const GInfo&) const {}
+  __device__ void epi_end(Epi&, const GInfo&, float*) const {}
 };
 
 }  // namespace clt

@@ -55,6 +55,26 @@ __global__ __launch_bounds__(256) void decoder_norms_kernel(Dims D, const T* __r
   if (lane == 0) norms[row] = sqrtf(acc);
 }
 
+// The same norms from per-(block, 64-column run, feature) sums of squares, [P][d / 64][F]: fixed order
+__global__ __launch_bounds__(256) void norms_from_partials_kernel(Dims D, const float* __restrict__ n2_part,
+                                                                  float* __restrict__ norms) {
+  const long i = (long)blockIdx.x * 256 + threadIdx.x;      // l * F + f
+  if (i >= (long)D.L * D.F) return;
+  const int l = (int)(i / D.F), f = (int)(i - (long)l * D.F);
+  const int runs = D.d >> 6;
+  const float* base = n2_part + (size_t)packed_index(l, l, D.L) * runs * D.F + f;
+  // eight independent chains keep eight loads in flight per lane; the order of the sum stays fixed
+  const int n = (D.L - l) * runs;
+  float a[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  int j = 0;
+  for (; j + 8 <= n; j += 8) {
+#pragma unroll
+    for (int q = 0; q < 8; ++q) a[q] += base[(size_t)(j + q) * D.F];
+  }
+  for (; j < n; ++j) a[j & 7] += base[(size_t)j * D.F];
+  norms[i] = sqrtf(((a[0] + a[1]) + (a[2] + a[3])) + ((a[4] + a[5]) + (a[6] + a[7])));
+}
+
 // ---- reconstruction loss: r = y_hat - y; partial sum r^2; d_yhat = 2 r / B;
 // column partial sums of d_yhat (for db_dec).  grid = (row blocks, L), each
 // thread owns 4 consecutive columns and walks the block's rows.
@@ -560,6 +580,12 @@ hipError_t launch_decoder_norms(hipStream_t s, bool bf16, Dims D, const void* W_
     hipLaunchKernelGGL((decoder_norms_kernel<bf16_t>), grid, dim3(256), 0, s, D, (const bf16_t*)W_dec, norms);
   else
     hipLaunchKernelGGL((decoder_norms_kernel<float>), grid, dim3(256), 0, s, D, (const float*)W_dec, norms);
+  return hipGetLastError();
+}
+
+hipError_t launch_norms_from_partials(hipStream_t s, Dims D, const float* n2_part, float* norms) {
+  const long rows = (long)D.L * D.F;
+  hipLaunchKernelGGL(norms_from_partials_kernel, dim3((unsigned)((rows + 255) / 256)), dim3(256), 0, s, D, n2_part, norms);
   return hipGetLastError();
 }
 

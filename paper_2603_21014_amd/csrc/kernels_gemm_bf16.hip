@@ -328,6 +328,8 @@ __device__ __forceinline__ void epilogue(const P& p, const typename P::GInfo& gi
   __syncthreads();
   float* wl = reinterpret_cast<float*>(smem) + wu * (32 * 64);
   EpiPos pos;
+  // (the transposition uses the first 64 KB of LDS, 8 KB per wave; the policy's scratch lies behind it)
+  pos.lds = reinterpret_cast<float*>(smem) + 8 * (32 * 64) + wu * 128;
   pos.cu = n0 + wn * 64;
   pos.cl = (lane & 15) << 2;
   pos.rl = lane >> 4;
@@ -373,7 +375,7 @@ __device__ __forceinline__ void epilogue(const P& p, const typename P::GInfo& gi
     const float4 v = *reinterpret_cast<const float4*>(wl + ((g & 7) * 4 + pos.rl) * 64 + pos.cl);
     if (!EDGE || (col_ok && pos.row() < M)) p.epi4(est, gi, pos, v, er[g]);
   }
-  p.epi_end(est, gi);
+  p.epi_end(est, gi, pos.lds);
 }
 
 // P::PERSISTENT: the grid is one workgroup per CU and workgroup i runs tiles i, i + gridDim.x, ...
@@ -483,6 +485,7 @@ hipError_t init_gemm_bf16() {
   if ((e = set_lds_attr<DzPolicy<bf16_t, true>>()) != hipSuccess) return e;
   if ((e = set_lds_attr<DWdecPolicy<bf16_t, false>>()) != hipSuccess) return e;
   if ((e = set_lds_attr<DWdecPolicy<bf16_t, true>>()) != hipSuccess) return e;
+  if ((e = set_lds_attr<DWdecPolicy<bf16_t, true, true>>()) != hipSuccess) return e;
   if ((e = set_lds_attr<DWencPolicy<bf16_t, false>>()) != hipSuccess) return e;
   if ((e = set_lds_attr<DWencPolicy<bf16_t, true>>()) != hipSuccess) return e;
   if ((e = set_lds_attr<DWencPolicy<bf16_t, false, int8_t>>()) != hipSuccess) return e;
@@ -518,11 +521,12 @@ static hipError_t launch_dz_mode(hipStream_t s, Dims D, const DzArgs& a) {
 hipError_t launch_dz_bf16(hipStream_t s, Dims D, const DzArgs& a) {
   return a.part_theta ? launch_dz_mode<true>(s, D, a) : launch_dz_mode<false>(s, D, a);
 }
-template <bool ADAM>
+template <bool ADAM, bool N2>
 static hipError_t launch_dwdec_mode(hipStream_t s, Dims D, const DWdecArgs& a) {
-  DWdecPolicy<bf16_t, ADAM> p{D, D.F, D.d, D.B, D.F, D.d,
+  DWdecPolicy<bf16_t, ADAM, N2> p{D, D.F, D.d, D.B, D.F, D.d,
                               (const bf16_t*)a.z, (const bf16_t*)a.d_yhat, (bf16_t*)a.W_dec, a.G, a.norms,
-                              (bf16_t*)a.dW_dec, AdamFuse{a.fuse.m, a.fuse.v, a.fuse.master, a.fuse.a}, a.skip_flags, a.kcap, 0};
+                              (bf16_t*)a.dW_dec, AdamFuse{a.fuse.m, a.fuse.v, a.fuse.master, a.fuse.a}, a.skip_flags, a.kcap, 0,
+                              N2 ? a.n2_part : nullptr};
   // One launch per source layer: the tiles that share operand panels start together again at
   // every launch and stay in step along K, which keeps the panel reuse in the XCDs' L2s (same
   // run time as one long launch, but half the traffic to the fabric).  Layers whose blocks hold
@@ -541,7 +545,10 @@ static hipError_t launch_dwdec_mode(hipStream_t s, Dims D, const DWdecArgs& a) {
   return hipSuccess;
 }
 hipError_t launch_dwdec_bf16(hipStream_t s, Dims D, const DWdecArgs& a) {
-  return a.fuse.m ? launch_dwdec_mode<true>(s, D, a) : launch_dwdec_mode<false>(s, D, a);
+  if (!a.fuse.m) return launch_dwdec_mode<false, false>(s, D, a);
+  // the row sums of squares need every tile to take the unpredicated epilogue (all 16 lanes of a row at work)
+  if (a.n2_part && D.F % TM == 0 && D.d % TN == 0) return launch_dwdec_mode<true, true>(s, D, a);
+  return launch_dwdec_mode<true, false>(s, D, a);
 }
 template <bool ADAM, typename TA>
 static hipError_t launch_dwenc_mode(hipStream_t s, Dims D, const DWencArgs& a) {

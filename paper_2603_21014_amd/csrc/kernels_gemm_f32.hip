@@ -79,7 +79,7 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(P p, TileGrid tg) {
       if (pos.row() < M) p.epi4(est, gi, pos, make_float4(acc[i][0], acc[i][1], acc[i][2], acc[i][3]), er[i]);
     }
   }
-  p.epi_end(est, gi);
+  p.epi_end(est, gi, nullptr);
 }
 
 template <class P>
@@ -112,7 +112,7 @@ template <bool ADAM>
 static hipError_t launch_dwdec_mode(hipStream_t s, Dims D, const DWdecArgs& a) {
   DWdecPolicy<float, ADAM> p{D, D.F, D.d, D.B, D.F, D.d,
                              (const float*)a.z, (const float*)a.d_yhat, (float*)a.W_dec, a.G, a.norms,
-                             (float*)a.dW_dec, AdamFuse{a.fuse.m, a.fuse.v, a.fuse.master, a.fuse.a}, a.skip_flags, a.kcap, 0};
+                             (float*)a.dW_dec, AdamFuse{a.fuse.m, a.fuse.v, a.fuse.master, a.fuse.a}, a.skip_flags, a.kcap, 0, nullptr};
   // one launch per source layer, like the bf16 path
   for (int l = 0; l < D.L; ++l) {
     p.p0 = packed_index(l, l, D.L);

@@ -120,7 +120,10 @@ class GpuRun:
     canary bands that are checked after each call."""
 
     def __init__(self, w: S.CLTWorkload, params, x, y, t=1, m=None, v=None, x_scale=None, y_scale=None,
-                 theta=None, decode_mode=1, gather_density_threshold=0.004, fused=False):
+                 theta=None, decode_mode=1, gather_density_threshold=0.004, fused=False, pre_steps=0,
+                 reuse_decoder_norms=False):
+        """pre_steps: fused training steps run on the device before the step whose results are kept (that step
+        then has step count t + pre_steps and starts from self.start_params / start_m / start_v)."""
         from paper_2603_21014_amd import binding as K
         dev = "cuda:0"
         T = torch.float32 if w.dtype == "f32" else torch.bfloat16
@@ -137,12 +140,14 @@ class GpuRun:
             master = {k: gb.like("master." + k, params[k], torch.float32) for k in MATS}
         cfg = K.make_config(w.L, w.d, w.F, w.B, K.DTYPE_F32 if w.dtype == "f32" else K.DTYPE_BF16,
                             K.INPUT_INT8_ROWSCALE if w.int8_inputs else K.INPUT_NATIVE, w.master_weights, decode_mode,
-                            gather_density_threshold, w.C, w.ste_eps, log_threshold=w.log_threshold, topk=w.topk or None)
+                            gather_density_threshold, w.C, w.ste_eps, log_threshold=w.log_threshold, topk=w.topk or None,
+                            reuse_decoder_norms=reuse_decoder_norms)
         ws = gb.empty("workspace", (K.clt_workspace_bytes(cfg),), torch.uint8)
         step = K.CLTStep(w.L, w.d, w.F, w.B, dtype=w.dtype, int8_inputs=w.int8_inputs,
                          master_weights=w.master_weights, C_=w.C, ste_bandwidth=w.ste_eps, device=dev,
                          decode_mode=decode_mode, gather_density_threshold=gather_density_threshold,
-                         log_threshold=w.log_threshold, topk=w.topk or None, workspace=ws)
+                         log_threshold=w.log_threshold, topk=w.topk or None, workspace=ws,
+                         reuse_decoder_norms=reuse_decoder_norms)
         for name in ("z", "pre", "act_class", "y_hat", "l0", "loss_dev"):
             t_ = getattr(step, name)
             setattr(step, name, gb.empty(name, t_.shape, t_.dtype))
@@ -151,6 +156,13 @@ class GpuRun:
         xs = x_scale.to(dev) if x_scale is not None else None
         ys = y_scale.to(dev) if y_scale is not None else None
         self.x_scale = to_np(xs) if xs is not None else None
+        for i in range(pre_steps):
+            step.train_step(xg, yg, gp, gm, gv, t + i, w.lr, w.lambda0, master, xs, ys, lambda1=w.lambda1)
+            gb.check(f"training step {i + 1}")
+        t += pre_steps
+        cpu = lambda d_: {k: a.detach().float().cpu() for k, a in d_.items()}
+        self.start_params, self.start_m, self.start_v = cpu(gp), cpu(gm), cpu(gv)
+        K.clt_profile_enable(step.H, True)
         step.forward(xg, gp, xs)
         gb.check("clt_forward")
         self.loss = step.loss(yg, w.lambda0, ys, to_host=True, lambda1=w.lambda1, params=gp)
@@ -181,6 +193,8 @@ class GpuRun:
         self.new_m = {k: to_np(a) for k, a in gm.items()}
         self.new_v = {k: to_np(a) for k, a in gv.items()}
         self.new_master = {k: to_np(a) for k, a in master.items()} if master else None
+        self.kernel_launches = {k: n for k, (_, n) in K.clt_profile_query(step.H).items() if n}
+        K.clt_profile_enable(step.H, False)
         self.step = step
         self.device_state = (gp, gm, gv, master)
 

@@ -185,6 +185,38 @@ def test_bf16_fused_update_many_tiles_per_cu(B, master):
     show(f"bf16 fused update, many tiles, B={B} master={master}", compare_step(w, g, o, TOL["bf16"]))
 
 
+def test_decoder_norms_reused_from_the_fused_update():
+    """reuse_decoder_norms: the fused update of step t leaves the row sums of squares of the new decoder weights
+    and the forward pass of step t + 1 forms the norms from them instead of reading W_dec.  The third step of a
+    run is compared with the oracle started from the device's state after two steps; without the option the same
+    step reads W_dec and must agree up to the summation order."""
+    w = S.scaled(S.WORKLOADS["gpt2"], L=3, d=512, F=768, B=300, k_active=16, seed=88)
+    params = S.make_params(w)
+    x, y = S.make_inputs(w)
+    g = GpuRun(w, params, x, y, fused=True, pre_steps=2, reuse_decoder_norms=True)
+    assert g.kernel_launches.get("decoder_norms_from_update") == 1 and "decoder_norms" not in g.kernel_launches
+    o = OracleRun(w, g.start_params, x, y, t=3, m=g.start_m, v=g.start_v, gpu_active=g.active, gpu_window=g.window)
+    show("norms from the update, step 3", compare_step(w, g, o, TOL["bf16"], check_adam=False))
+    for k in O.PARAM_NAMES:      # Adam from two steps of history: moments and the distance moved
+        assert rel_l2(g.new_m[k], o.new_m[k]) <= TOL["bf16"] and rel_l2(g.new_v[k], o.new_v[k]) <= 2 * TOL["bf16"], k
+    plain = GpuRun(w, params, x, y, fused=True, pre_steps=2)
+    assert plain.kernel_launches.get("decoder_norms") == 1 and "decoder_norms_from_update" not in plain.kernel_launches
+    assert rel_l2(g.norms, plain.norms) < 1e-6 and (g.active == plain.active).all()
+    for k in O.PARAM_NAMES:
+        assert rel_l2(g.new_params[k], plain.new_params[k]) < 1e-5, k
+    # an unfused update in between changes W_dec without new row sums: the next forward must read W_dec again
+    from paper_2603_21014_amd import binding as K
+    step, (gp, gm, gv, _) = g.step, g.device_state
+    xg, yg = x.to("cuda:0", torch.bfloat16), y.to("cuda:0", torch.bfloat16)
+    step.train_step(xg, yg, gp, gm, gv, 4, w.lr, w.lambda0, fused=False)
+    K.clt_profile_enable(step.H, True)
+    step.forward(xg, gp)
+    launches = {k: n for k, (_, n) in K.clt_profile_query(step.H).items() if n}
+    assert launches.get("decoder_norms") == 1 and "decoder_norms_from_update" not in launches
+    want = O.decoder_norms(to_np(gp["W_dec"]), w.L)
+    assert rel_l2(to_np(K.clt_workspace_view(step.H, "norms")), want) < 1e-5
+
+
 def test_fused_equals_unfused_with_fp32_storage():
     """With fp32 storage the gradient enters Adam unrounded on both paths: same gradients
     bit for bit, same update up to the contraction order of the two compiled epilogues."""
