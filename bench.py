@@ -65,6 +65,13 @@ DIAG_VARIANTS = (
     ("mfma+lds_reads+lds_writes", 6),
     ("mfma+lds+loads_from_L2", 14),
     ("mfma+lds+loads_half_from_infinity_cache", 30),
+    # the same parts arranged for one wavefront per SIMD (4 waves, 4x4 accumulators each), and with direct-to-LDS staging
+    ("one_wave_per_simd:mfma_only", 32),
+    ("one_wave_per_simd:mfma+lds_reads+lds_writes", 38),
+    ("one_wave_per_simd:mfma+lds+loads_from_L2", 46),
+    ("one_wave_per_simd:mfma+lds+loads_half_from_infinity_cache", 62),
+    ("one_wave_per_simd:mfma+lds_reads+direct_to_lds_loads_from_L2", 110),
+    ("one_wave_per_simd:mfma+lds_reads+direct_to_lds_loads_half_from_infinity_cache", 126),
 )
 
 
@@ -428,9 +435,19 @@ def main():
         # weights and moments read and written once (row kernel of dW_dec)
         rows_bytes = w.B * l0 * w.P * w.d * 2.0
         hbm_bytes = {"gather_decode": rows_bytes, "gather_dz": rows_bytes, "sparse_dW_dec": 20.0 * w.P * w.F * w.d}
+        # the two weight-gradient kernels carry the fused Adam update: per parameter the bf16 weight and the fp32
+        # moments (and master copy) are read and written once (20 or 30 bytes), plus the operands once.  Where
+        # that takes longer at 8 TB/s than the kernel's flop at the MFMA peak, HBM is the roof that bounds it.
+        per_param = 30.0 if w.master_weights else 20.0
+        act = 2.0 * w.L * w.B          # bytes of one bf16 [L, B, .] activation per unit of width
+        fused_bytes = {"dW_dec_gemm": per_param * w.P * w.F * w.d + act * (w.F + w.d),
+                       "dW_enc_gemm": per_param * w.L * w.F * w.d + act * (w.F + w.d) * (0.5 if w.int8_inputs else 1.0)}
+        for k, b in fused_bytes.items():
+            if k in kernels and b / 8e12 > kernels[k]["flop"] / (PEAK_BF16_TFLOPS * 1e12):
+                hbm_bytes[k] = b
         per_step = lambda k: kernels[k]["avg_ms"] * kernels[k]["launches_per_step"]
         dom = max((k for k in kernels if k in GEMM_PAIRS or k in hbm_bytes), key=per_step)
-        if dom in GEMM_PAIRS:
+        if dom in GEMM_PAIRS and dom not in hbm_bytes:
             ach = kernels[dom]["tflops"]
             traffic, source = profiled_traffic_bytes(w.name, dom)
             roof = {"kernel": dom, "bound": "mfma", "achieved": ach, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
@@ -441,6 +458,8 @@ def main():
             roof = {"kernel": dom, "bound": "hbm", "achieved": round(ach, 1), "peak": 8000.0, "unit": "GB/s",
                     "frac": round(ach / 8000.0, 4), "traffic": None, "traffic_source": None,
                     "avg_launch_ms": kernels[dom]["avg_ms"], "bytes_per_launch": hbm_bytes[dom]}
+            if dom in GEMM_PAIRS:     # context: the same kernel against the MFMA roof it is not bound by
+                roof["mfma_tflops"] = kernels[dom]["tflops"]
         for name, ent in sorted(kernels.items(), key=lambda kv: -kv[1]["avg_ms"] * kv[1]["launches_per_step"]):
             log(f"  {name:24s} {ent['avg_ms']:9.3f} ms x {ent['launches_per_step']:.0f}"
                 + (f"  {ent['tflops']:7.1f} TFLOP/s" if "tflops" in ent else ""))

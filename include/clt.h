@@ -267,7 +267,13 @@ int clt_profile_query(clt_handle* handle, int kernel, const char** name, double*
  *       region that stays in the L2
  *   16  (with 8) every second of those loads from a region that only fits the
  *       Infinity Cache
- * Built combinations: 0, 2, 6, 14, 30, 8, 24 (+1).  There is no data flow between
+ *   32  the arrangement of a kernel with ONE wavefront per SIMD instead: 4
+ *       wavefronts per compute unit, each with 4x4 accumulators, eight LDS
+ *       reads for sixteen MFMAs (2/3 of the LDS read traffic), 64 MFMAs per
+ *       wavefront and iteration
+ *   64  (with 32 + 8) the staging goes global memory -> LDS directly instead of
+ *       through registers and LDS writes
+ * Built combinations: 0, 2, 6, 14, 30, 8, 24, 32, 34, 38, 46, 62, 110, 126 (+1).  There is no data flow between
  * the parts and no barrier: the kernel computes nothing, it only does the work.
  * Enqueues on `stream` (a fill of buf first when a load bit is set); the caller
  * times it.  buf: device scratch, 16-byte aligned, at least (64 KB + 512 KB) x
