@@ -28,7 +28,11 @@ pytestmark = pytest.mark.gpu
 TOL = 2e-2
 
 
-def close(a, b, what, tol=TOL):
+def close(a, b, what, tol=TOL, floor=0.0):
+    """floor: magnitudes below it count as zero on both sides (sums of fp32 terms that have passed through the
+    flushed-denormal range are not expected to agree with an fp64 sum)."""
+    if floor > 0.0:
+        a, b = np.where(np.abs(a) < floor, 0.0, a), np.where(np.abs(b) < floor, 0.0, b)
     r, e = rel_l2(a, b), max_elem(a, b)
     assert r <= tol and e <= tol, f"{what}: relative L2 {r:.3e}, worst element {e:.3e} (tolerance {tol})"
 
@@ -171,7 +175,9 @@ def test_full_size_step_against_sampled_oracle(workload, mode):
         del z_r
     if w.lambda0 > 0:
         assert abs(loss[2] - L_sp) <= TOL * L_sp, f"L_sp {loss[2]} vs {L_sp}"
-        close(G_gpu, G_o, "G")
+        # (at the forced densities of the list-driven runs tanh is saturated and G is of the order of 1e-36:
+        # exp(-2 C z n) and the products after it underflow in fp32)
+        close(G_gpu, G_o, "G", floor=1e-30)
     else:
         assert loss[2] == 0.0 and not G_gpu.any()
     assert loss[3] == 0.0 and abs(loss[0] - (loss[1] + loss[2])) <= 1e-6 * abs(loss[0])

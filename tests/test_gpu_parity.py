@@ -202,8 +202,10 @@ def test_decoder_norms_reused_from_the_fused_update():
     plain = GpuRun(w, params, x, y, fused=True, pre_steps=2)
     assert plain.kernel_launches.get("decoder_norms") == 1 and "decoder_norms_from_update" not in plain.kernel_launches
     assert rel_l2(g.norms, plain.norms) < 1e-6 and (g.active == plain.active).all()
+    # the two runs differ by the summation order of the norms (1e-7 relative); after three steps that flips the bf16
+    # rounding of a few updated weights (one flip in a thousand weights is a relative L2 distance of 1.2e-4)
     for k in O.PARAM_NAMES:
-        assert rel_l2(g.new_params[k], plain.new_params[k]) < 1e-5, k
+        assert rel_l2(g.new_params[k], plain.new_params[k]) < 1e-4, k
     # an unfused update in between changes W_dec without new row sums: the next forward must read W_dec again
     from paper_2603_21014_amd import binding as K
     step, (gp, gm, gv, _) = g.step, g.device_state
