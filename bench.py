@@ -61,13 +61,13 @@ def theta_for_density(x, W_enc, b_enc, rho):
 DIAG_VARIANTS = (
     # (name, mode bits of clt_diag_mfma_loop without the data bit)
     ("mfma_only", 0),
+    ("mfma_only_32x32x16_shape", 128),
     ("mfma+lds_reads", 2),
     ("mfma+lds_reads+lds_writes", 6),
     ("mfma+lds+loads_from_L2", 14),
     ("mfma+lds+loads_half_from_infinity_cache", 30),
-    # the same parts arranged for one wavefront per SIMD (4 waves, 4x4 accumulators each), and with direct-to-LDS staging
+    # the same parts arranged for one wavefront per SIMD (4 waves, 8x8 accumulators each), and with direct-to-LDS staging
     ("one_wave_per_simd:mfma_only", 32),
-    ("one_wave_per_simd:mfma+lds_reads+lds_writes", 38),
     ("one_wave_per_simd:mfma+lds+loads_from_L2", 46),
     ("one_wave_per_simd:mfma+lds+loads_half_from_infinity_cache", 62),
     ("one_wave_per_simd:mfma+lds_reads+direct_to_lds_loads_from_L2", 110),
@@ -112,7 +112,7 @@ def mfma_ceiling(dev, log, iters=40000, all_variants=False):
             r = run_diag(dev, mode | rnd, iters, counters, buf if mode & 8 else None)
             out.setdefault(vname, {})[dname] = r
             log(f"diagnostic loop {vname}, {dname}: {r['tflops']} TFLOP/s at {r['shader_clock_ghz']} GHz")
-    out["what"] = ("v_mfma_f32_32x32x16_bf16 stream of the contraction kernel, 8 wavefronts per CU, operands in "
+    out["what"] = ("v_mfma_f32_16x16x32_bf16 stream of the contraction kernel, 8 wavefronts per CU, operands in "
                    "registers (mfma_only: no LDS or global memory access)")
     return out
 

@@ -254,26 +254,29 @@ int clt_profile_query(clt_handle* handle, int kernel, const char** name, double*
 
 /* Diagnostic, not part of the method: the instruction stream of the bf16
  * contraction kernels (one workgroup of 8 wavefronts per compute unit, per
- * iteration 32 v_mfma_f32_32x32x16_bf16 per wavefront), taken apart to show
+ * iteration 64 v_mfma_f32_16x16x32_bf16 per wavefront), taken apart to show
  * what the matrix cores sustain on this board and what each kind of data
  * movement costs them.  The bf16 MFMA rate is limited by board power, and the
  * power depends on the operand bits, so every variant runs on all-zero or on
  * pseudo-random data.  mode is a sum of
  *    1  pseudo-random data instead of zeros
- *    2  MFMA operands are read from LDS (six 16-byte reads per lane for every
- *       eight MFMAs, the contraction kernels' pattern) instead of held in registers
+ *    2  MFMA operands are read from LDS (twelve 16-byte reads per lane for every
+ *       32 MFMAs, the contraction kernels' pattern) instead of held in registers
  *    4  eight 16-byte LDS writes per lane and iteration (staging of a 256x64 + 64x256 tile)
  *    8  eight 16-byte loads per lane and iteration (64 KB per workgroup) from a
  *       region that stays in the L2
  *   16  (with 8) every second of those loads from a region that only fits the
  *       Infinity Cache
  *   32  the arrangement of a kernel with ONE wavefront per SIMD instead: 4
- *       wavefronts per compute unit, each with 4x4 accumulators, eight LDS
- *       reads for sixteen MFMAs (2/3 of the LDS read traffic), 64 MFMAs per
+ *       wavefronts per compute unit, each with 8x8 accumulators, sixteen LDS
+ *       reads for 64 MFMAs (2/3 of the LDS read traffic), 128 MFMAs per
  *       wavefront and iteration
  *   64  (with 32 + 8) the staging goes global memory -> LDS directly instead of
  *       through registers and LDS writes
- * Built combinations: 0, 2, 6, 14, 30, 8, 24, 32, 34, 38, 46, 62, 110, 126 (+1).  There is no data flow between
+ *  128  (alone) the bare loop on the other bf16 shape, 32 v_mfma_f32_32x32x16_bf16
+ *       per wavefront and iteration: the same flop with four times the
+ *       accumulator registers read and written per instruction
+ * Built combinations: 0, 2, 6, 14, 30, 8, 24, 32, 34, 38, 46, 62, 110, 126, 128 (+1).  There is no data flow between
  * the parts and no barrier: the kernel computes nothing, it only does the work.
  * Enqueues on `stream` (a fill of buf first when a load bit is set); the caller
  * times it.  buf: device scratch, 16-byte aligned, at least (64 KB + 512 KB) x

@@ -341,8 +341,8 @@ int clt_profile_query(clt_handle* h, int kernel, const char** name, double* tota
 
 int clt_diag_mfma_loop(void* stream, int iters, int mode, void* buf, size_t buf_bytes, uint64_t* counters_dev,
                        double* flop, double* wall_clock_hz) {
-  if (!counters_dev || misaligned(counters_dev) || iters < 1 || iters > (1 << 24) || mode < 0 || mode > 127) {
-    set_err(g_err, "clt_diag_mfma_loop: counters_dev must be a 16-byte aligned device pointer to 4 x uint64, 1 <= iters <= 2^24, 0 <= mode <= 127");
+  if (!counters_dev || misaligned(counters_dev) || iters < 1 || iters > (1 << 24) || mode < 0 || mode > 255) {
+    set_err(g_err, "clt_diag_mfma_loop: counters_dev must be a 16-byte aligned device pointer to 4 x uint64, 1 <= iters <= 2^24, 0 <= mode <= 255");
     return CLT_ERR_INVALID_ARG;
   }
   int dev = 0, cus = 0, khz = 0;

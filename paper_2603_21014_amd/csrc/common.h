@@ -240,11 +240,11 @@ hipError_t launch_adam_matrix(hipStream_t s, bool bf16, size_t n, void* p, const
 hipError_t launch_adam_vector(hipStream_t s, size_t n, float* p, const float* g, float* m, float* v, AdamScalars a);
 
 // Diagnostic (kernels_diag.hip): the contraction kernel's instruction stream taken apart.  `workgroups` x 8 waves x
-// iters x 32 v_mfma_f32_32x32x16_bf16; mode bits add the LDS and memory traffic of the real kernel; out[0] / out[1] =
+// iters x 64 v_mfma_f32_16x16x32_bf16; mode bits add the LDS and memory traffic of the real kernel; out[0] / out[1] =
 // shader cycles / constant-rate ticks that wave 0 spent in its loop.  buf: workgroups * (NEAR + FAR) bytes when a
 // load bit is set.
 constexpr int DIAG_RANDOM_DATA = 1, DIAG_LDS_READS = 2, DIAG_LDS_WRITES = 4, DIAG_LOADS_L2 = 8, DIAG_LOADS_FAR = 16,
-              DIAG_FOUR_WAVES = 32, DIAG_LDS_DMA = 64;
+              DIAG_FOUR_WAVES = 32, DIAG_LDS_DMA = 64, DIAG_MFMA_32X32 = 128;
 constexpr size_t DIAG_NEAR_BYTES = 64u << 10, DIAG_FAR_BYTES = 512u << 10;
 hipError_t launch_mfma_loop(hipStream_t s, int workgroups, int iters, int mode, const void* buf, unsigned long long* out);
 hipError_t launch_diag_fill(hipStream_t s, void* buf, size_t bytes, int random_data);

@@ -1,6 +1,6 @@
 // Diagnostic kernel, not part of the training step: the instruction stream of the bf16 contraction
-// kernel (8 wavefronts per workgroup, one workgroup per CU, 32 v_mfma_f32_32x32x16_bf16 per K step
-// and wave on 4x2 accumulators), taken apart.  The bare loop keeps its operands in registers -- no
+// kernel (8 wavefronts per workgroup, one workgroup per CU, 64 v_mfma_f32_16x16x32_bf16 per K step
+// and wave on 8x4 accumulators), taken apart.  The bare loop keeps its operands in registers -- no
 // LDS, no global memory; mode bits add back, one by one and at the contraction kernel's own rates,
 // the fragment reads from LDS, the staging writes to LDS and the operand loads from memory (out of
 // the L2, or half of them out of the Infinity Cache).  There is no data flow between these parts and
@@ -16,6 +16,7 @@ namespace {
 
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float f32x16_t __attribute__((ext_vector_type(16)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int TK = 64, STAGE_ELEMS = 2 * 256 * TK, LDS_BYTES = 2 * STAGE_ELEMS * 2;   // as in the contraction kernel
@@ -51,33 +52,43 @@ __global__ __launch_bounds__(512) void mfma_loop_kernel(int iters, int random_da
       reinterpret_cast<uint32_t*>(smem)[i] = random_data ? rand_bf16x2(mix(t * 977u + i)) : 0u;
     __syncthreads();
   }
-  u32x4 fa[2][4], fb[2][2], rg[8];
+  u32x4 fa[2][4], fb[2][4], rg[8];
 #pragma unroll
-  for (int b = 0; b < 2; ++b) {
+  for (int b = 0; b < 2; ++b)
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
-      for (int c = 0; c < 4; ++c) fa[b][i][c] = random_data ? rand_bf16x2(mix(t * 64u + b * 32u + i * 4u + c)) : 0u;
-#pragma unroll
-    for (int j = 0; j < 2; ++j)
-#pragma unroll
-      for (int c = 0; c < 4; ++c) fb[b][j][c] = random_data ? rand_bf16x2(mix(t * 64u + 16u + b * 32u + j * 4u + c)) : 0u;
-  }
+      for (int c = 0; c < 4; ++c) {
+        fa[b][i][c] = random_data ? rand_bf16x2(mix(t * 64u + b * 32u + i * 4u + c)) : 0u;
+        fb[b][i][c] = random_data ? rand_bf16x2(mix(t * 64u + 16u + b * 32u + i * 4u + c)) : 0u;
+      }
 #pragma unroll
   for (int i = 0; i < 8; ++i) rg[i] = fa[i & 1][i >> 1];
-  f32x16_t acc[4][2];
+  f32x4_t acc[8][4];
 #pragma unroll
-  for (int i = 0; i < 4; ++i)
+  for (int i = 0; i < 8; ++i)
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int j = 0; j < 4; ++j)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+      for (int r = 0; r < 4; ++r) acc[i][j][r] = 0.f;
   // operand loads: per K step every wave reads 8 x 1 KB (16 bytes per lane), 64 KB per workgroup.  The near
   // region (64 KB per workgroup, 2 MB per XCD) stays in the L2; the far region (512 KB per workgroup, 16 MB per
   // XCD, 128 MB in all) does not, but fits the Infinity Cache.
   const char* near = buf + (size_t)blockIdx.x * DIAG_NEAR_BYTES + (size_t)(w * 64 + lane) * 16;
   const char* far = buf + (size_t)gridDim.x * DIAG_NEAR_BYTES + (size_t)blockIdx.x * DIAG_FAR_BYTES + (size_t)(w * 64 + lane) * 16;
-  const int frow = lane & 31, fch = lane >> 5;
+  // fragment reads as in the contraction kernel: row lane%16, lane groups 0,1,2,3 take k chunks 0,2,1,3 of a slice
+  const int frow = lane & 15, fch = ((lane >> 3) & 2) | (lane >> 5);
+  auto read_a = [&](int st, int sl, int q, int b) {
+    const uint16_t* a = smem + st * STAGE_ELEMS;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) fa[b][i] = *reinterpret_cast<const u32x4*>(a + lds_off(wm * 128 + (4 * q + i) * 16 + frow, 4 * sl + fch));
+  };
+  auto read_b = [&](int st, int sl, int b) {
+    const uint16_t* bb = smem + st * STAGE_ELEMS + 256 * TK;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) fb[b][j] = *reinterpret_cast<const u32x4*>(bb + lds_off(wn * 64 + j * 16 + frow, 4 * sl + fch));
+  };
+  if (LDS_READS) { read_b(0, 0, 0); read_a(0, 0, 0, 0); }
   const long long c0 = clock64(), w0 = wall_clock64();
   for (int it = 0; it < iters; ++it) {
     if (LDS_WRITES) {      // the tile fetched during the previous step goes to LDS, 8 x 16 bytes per lane
@@ -93,22 +104,20 @@ __global__ __launch_bounds__(512) void mfma_loop_kernel(int iters, int random_da
       }
     }
 #pragma unroll
-    for (int s = 0; s < 4; ++s) {         // the four 16-wide slices of one K step of 64
-      const int b = s & 1;
-      if (LDS_READS) {
-        const uint16_t* a = smem + (it & 1) * STAGE_ELEMS;
-        const uint16_t* bb = a + 256 * TK;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) fa[b][i] = *reinterpret_cast<const u32x4*>(a + lds_off(wm * 128 + i * 32 + frow, 2 * s + fch));
-#pragma unroll
-        for (int j = 0; j < 2; ++j) fb[b][j] = *reinterpret_cast<const u32x4*>(bb + lds_off(wn * 64 + j * 32 + frow, 2 * s + fch));
+    for (int g = 0; g < 4; ++g) {         // two 32-wide slices of one K step of 64, two groups of four A fragments in each
+      const int sl = g >> 1, q = g & 1;
+      if (LDS_READS) {                    // the next group's fragments under these MFMAs
+        const int st = g == 3 ? (it + 1) & 1 : it & 1, nsl = ((g + 1) >> 1) & 1, nq = (g + 1) & 1;
+        if (nq == 0) read_b(st, nsl, nsl);
+        read_a(st, nsl, nq, nq);
       }
 #pragma unroll
       for (int i = 0; i < 4; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, fa[b][i]),
-                                                              __builtin_bit_cast(bf16x8_t, fb[b][j]), acc[i][j], 0, 0, 0);
+        for (int j = 0; j < 4; ++j)
+          acc[4 * q + i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, fa[q][i]),
+                                                                      __builtin_bit_cast(bf16x8_t, fb[sl][j]),
+                                                                      acc[4 * q + i][j], 0, 0, 0);
     }
     // keeps the operand registers from being folded into constants and the loop from being unrolled away
     asm volatile("" : "+v"(fa[0][0]), "+v"(fb[0][0]));
@@ -116,11 +125,11 @@ __global__ __launch_bounds__(512) void mfma_loop_kernel(int iters, int random_da
   const long long c1 = clock64(), w1 = wall_clock64();
   float sum = 0.f;
 #pragma unroll
-  for (int i = 0; i < 4; ++i)
+  for (int i = 0; i < 8; ++i)
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int j = 0; j < 4; ++j)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) sum += acc[i][j][r];
+      for (int r = 0; r < 4; ++r) sum += acc[i][j][r];
   uint32_t keep = 0;
 #pragma unroll
   for (int i = 0; i < 8; ++i) keep ^= rg[i][0] ^ rg[i][3];
@@ -131,11 +140,62 @@ __global__ __launch_bounds__(512) void mfma_loop_kernel(int iters, int random_da
   if (sum == 1.2345678e-30f && keep == 0x12345u) out[2] = t;   // never true in practice; makes the results observable
 }
 
+// The bare loop with the other bf16 MFMA shape, v_mfma_f32_32x32x16_bf16 on 4x2 accumulators: the same flop per
+// wave and iteration from half as many instructions, each reading and writing four times the accumulator
+// registers.  For the comparison of the two shapes at the board's power limit only.
+__global__ __launch_bounds__(512) void mfma_loop32_kernel(int iters, int random_data, unsigned long long* out) {
+  const uint32_t t = blockIdx.x * 512u + threadIdx.x;
+  u32x4 fa[2][4], fb[2][2];
+#pragma unroll
+  for (int b = 0; b < 2; ++b) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int c = 0; c < 4; ++c) fa[b][i][c] = random_data ? rand_bf16x2(mix(t * 64u + b * 32u + i * 4u + c)) : 0u;
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int c = 0; c < 4; ++c) fb[b][j][c] = random_data ? rand_bf16x2(mix(t * 64u + 16u + b * 32u + j * 4u + c)) : 0u;
+  }
+  f32x16_t acc[4][2];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+  const long long c0 = clock64(), w0 = wall_clock64();
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int s = 0; s < 4; ++s)
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, fa[s & 1][i]),
+                                                              __builtin_bit_cast(bf16x8_t, fb[s & 1][j]), acc[i][j], 0, 0, 0);
+    asm volatile("" : "+v"(fa[0][0]), "+v"(fb[0][0]));
+  }
+  const long long c1 = clock64(), w1 = wall_clock64();
+  float sum = 0.f;
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) sum += acc[i][j][r];
+  if (t == 0) {
+    out[0] = (unsigned long long)(c1 - c0);
+    out[1] = (unsigned long long)(w1 - w0);
+  }
+  if (sum == 1.2345678e-30f) out[2] = t;
+}
+
 // The same parts arranged the way a kernel with ONE wavefront per SIMD would have them: 4 waves of 256 lanes,
-// each owning a 128x128 block as 4x4 accumulators (256 registers), eight fragment reads feed sixteen MFMAs
-// (2/3 of the LDS read traffic of the 4x2 arrangement), fragments double-buffered so the reads of the next
-// 16-wide slice are in flight under the MFMAs of the current one.  DMA: the staging writes are direct
-// global-to-LDS loads instead of loads into registers followed by LDS writes.
+// each owning a 128x128 block as 8x8 accumulators (256 registers), sixteen fragment reads feed sixty-four MFMAs
+// per 32-wide slice (2/3 of the LDS read traffic of the 8x4 arrangement), the reads of the next group of 32
+// MFMAs in flight under the current one.  DMA: the staging writes are direct global-to-LDS loads instead of
+// loads into registers followed by LDS writes.
 __shared__ __align__(16) uint32_t dma_lds[4][1024];   // 4 KB per wave: landing zone of the direct-to-LDS loads
 
 template <int MODE>
@@ -152,39 +212,41 @@ __global__ __launch_bounds__(256) void mfma_loop4_kernel(int iters, int random_d
       reinterpret_cast<uint32_t*>(smem)[i] = random_data ? rand_bf16x2(mix(t * 977u + i)) : 0u;
     __syncthreads();
   }
-  u32x4 fa[2][4], fb[2][4], rg[16];
+  u32x4 fa[2][4], fb[2][8], rg[16];
 #pragma unroll
   for (int b = 0; b < 2; ++b)
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < 8; ++i)
 #pragma unroll
       for (int c = 0; c < 4; ++c) {
-        fa[b][i][c] = random_data ? rand_bf16x2(mix(t * 64u + b * 32u + i * 4u + c)) : 0u;
-        fb[b][i][c] = random_data ? rand_bf16x2(mix(t * 64u + 16u + b * 32u + i * 4u + c)) : 0u;
+        if (i < 4) fa[b][i][c] = random_data ? rand_bf16x2(mix(t * 128u + b * 64u + i * 4u + c)) : 0u;
+        fb[b][i][c] = random_data ? rand_bf16x2(mix(t * 128u + 32u + b * 64u + i * 4u + c)) : 0u;
       }
 #pragma unroll
-  for (int i = 0; i < 16; ++i) rg[i] = fa[i & 1][(i >> 1) & 3];
-  f32x16_t acc[4][4];
+  for (int i = 0; i < 16; ++i) rg[i] = fb[i & 1][(i >> 1) & 7];
+  f32x4_t acc[8][8];
 #pragma unroll
-  for (int i = 0; i < 4; ++i)
+  for (int i = 0; i < 8; ++i)
 #pragma unroll
-    for (int j = 0; j < 4; ++j)
+    for (int j = 0; j < 8; ++j)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+      for (int r = 0; r < 4; ++r) acc[i][j][r] = 0.f;
   // twice the workgroup count of the 8-wave kernel would double the regions; this kernel also runs one
   // workgroup per CU, so the same regions serve: 16 loads of 1 KB per wave and K step, 64 KB per workgroup
   const char* near = buf + (size_t)blockIdx.x * DIAG_NEAR_BYTES + (size_t)(w * 64 + lane) * 16;
   const char* far = buf + (size_t)gridDim.x * DIAG_NEAR_BYTES + (size_t)blockIdx.x * DIAG_FAR_BYTES + (size_t)(w * 64 + lane) * 16;
-  const int frow = lane & 31, fch = lane >> 5;
-  auto frags = [&](int st, int s, int b) {
+  const int frow = lane & 15, fch = ((lane >> 3) & 2) | (lane >> 5);
+  auto read_a = [&](int st, int sl, int q, int b) {
     const uint16_t* a = smem + st * STAGE_ELEMS;
-    const uint16_t* bb = a + 256 * TK;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) fa[b][i] = *reinterpret_cast<const u32x4*>(a + lds_off(wm * 128 + i * 32 + frow, 2 * s + fch));
-#pragma unroll
-    for (int j = 0; j < 4; ++j) fb[b][j] = *reinterpret_cast<const u32x4*>(bb + lds_off(wn * 128 + j * 32 + frow, 2 * s + fch));
+    for (int i = 0; i < 4; ++i) fa[b][i] = *reinterpret_cast<const u32x4*>(a + lds_off(wm * 128 + (4 * q + i) * 16 + frow, 4 * sl + fch));
   };
-  if (LDS_READS) frags(0, 0, 0);
+  auto read_b = [&](int st, int sl, int b) {
+    const uint16_t* bb = smem + st * STAGE_ELEMS + 256 * TK;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) fb[b][j] = *reinterpret_cast<const u32x4*>(bb + lds_off(wn * 128 + j * 16 + frow, 4 * sl + fch));
+  };
+  if (LDS_READS) { read_b(0, 0, 0); read_a(0, 0, 0, 0); }
   const long long c0 = clock64(), w0 = wall_clock64();
   for (int it = 0; it < iters; ++it) {
     if (LDS_WRITES && !DMA) {      // the tile fetched during the previous step goes to LDS, 16 x 16 bytes per lane
@@ -204,26 +266,31 @@ __global__ __launch_bounds__(256) void mfma_loop4_kernel(int iters, int random_d
       }
     }
 #pragma unroll
-    for (int s = 0; s < 4; ++s) {         // the four 16-wide slices of one K step of 64
-      const int b = s & 1;
-      if (LDS_READS) frags(s == 3 ? (it + 1) & 1 : it & 1, (s + 1) & 3, b ^ 1);   // next slice under these MFMAs
+    for (int g = 0; g < 4; ++g) {         // two 32-wide slices of one K step of 64, two groups of four A fragments in each
+      const int sl = g >> 1, q = g & 1;
+      if (LDS_READS) {                    // the next group's fragments under these MFMAs
+        const int st = g == 3 ? (it + 1) & 1 : it & 1, nsl = ((g + 1) >> 1) & 1, nq = (g + 1) & 1;
+        if (nq == 0) read_b(st, nsl, nsl);
+        read_a(st, nsl, nq, nq);
+      }
 #pragma unroll
       for (int i = 0; i < 4; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, fa[b][i]),
-                                                              __builtin_bit_cast(bf16x8_t, fb[b][j]), acc[i][j], 0, 0, 0);
+        for (int j = 0; j < 8; ++j)
+          acc[4 * q + i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, fa[q][i]),
+                                                                      __builtin_bit_cast(bf16x8_t, fb[sl][j]),
+                                                                      acc[4 * q + i][j], 0, 0, 0);
     }
     asm volatile("" : "+v"(fa[0][0]), "+v"(fb[0][0]));
   }
   const long long c1 = clock64(), w1 = wall_clock64();
   float sum = 0.f;
 #pragma unroll
-  for (int i = 0; i < 4; ++i)
+  for (int i = 0; i < 8; ++i)
 #pragma unroll
-    for (int j = 0; j < 4; ++j)
+    for (int j = 0; j < 8; ++j)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) sum += acc[i][j][r];
+      for (int r = 0; r < 4; ++r) sum += acc[i][j][r];
   uint32_t keep = DMA ? dma_lds[w][lane] : 0u;
 #pragma unroll
   for (int i = 0; i < 16; ++i) keep ^= rg[i][0] ^ rg[i][3];
@@ -266,6 +333,9 @@ hipError_t launch_mfma_loop(hipStream_t s, int workgroups, int iters, int mode, 
   const int rnd = mode & DIAG_RANDOM_DATA;
   constexpr int W4 = DIAG_FOUR_WAVES, RW = DIAG_LDS_READS | DIAG_LDS_WRITES, LD = DIAG_LOADS_L2, DMA = DIAG_LDS_DMA;
   switch (mode & ~DIAG_RANDOM_DATA) {
+    case DIAG_MFMA_32X32:
+      hipLaunchKernelGGL(mfma_loop32_kernel, dim3(workgroups), dim3(512), 0, s, iters, rnd, out);
+      return hipGetLastError();
     case W4: return launch_mode4<0>(s, workgroups, iters, rnd, buf, out);
     case W4 | DIAG_LDS_READS: return launch_mode4<DIAG_LDS_READS>(s, workgroups, iters, rnd, buf, out);
     case W4 | RW: return launch_mode4<RW>(s, workgroups, iters, rnd, buf, out);
