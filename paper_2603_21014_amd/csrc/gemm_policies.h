@@ -297,7 +297,7 @@ struct DzPolicy {
     return W_dec + (size_t)packed_index(g.l, g.l + s, D.L) * D.F * D.d;
   }
   static constexpr int EPI_BATCH = 8, EPI_BATCH_LATE = 8, EPI_BATCH_LAST = 8;
-  static constexpr bool PERSISTENT = false, UNIFORM_K = false;   // measured: 16.4 ms as a tile loop, 15.9 ms with one workgroup per tile
+  static constexpr bool PERSISTENT = false, UNIFORM_K = false;   // measured: no faster as a tile loop (15.4 ms either way)
   struct EpiRegs { uint32_t c4; typename Elem<T>::Raw4 z4; float s; };
   __device__ void epi_begin(Epi& e, const GInfo& g, int col, bool ok, int row0) const {
     float4 n4 = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -417,7 +417,7 @@ struct DWdecPolicy {
   // up to 16 registers per row group in flight: a short window while most accumulators are still live
   // (one group less with the sums of squares, whose registers come on top)
   static constexpr int EPI_BATCH = N2 ? 3 : 4, EPI_BATCH_LATE = N2 ? 6 : 8, EPI_BATCH_LAST = N2 ? 7 : 8;
-  static constexpr bool PERSISTENT = !ADAM, UNIFORM_K = true;
+  static constexpr bool PERSISTENT = true, UNIFORM_K = true;
   struct EpiRegs { float Gf, nf; typename Elem<T>::Raw4 w; AdamRegs ad; };
   __device__ void epi_begin(Epi& e, const GInfo&, int col, bool, int row0) const {
     e.row0 = row0;
@@ -478,7 +478,7 @@ struct DWencPolicy {
   __device__ const TA* a_seg(const GInfo& g, int) const { return x + (size_t)g.l * D.B * D.d; }
   __device__ const T* b_seg(const GInfo& g, int) const { return dpre + (size_t)g.l * D.B * D.F; }
   static constexpr int EPI_BATCH = 4, EPI_BATCH_LATE = 8, EPI_BATCH_LAST = 8;
-  static constexpr bool PERSISTENT = !ADAM, UNIFORM_K = true;
+  static constexpr bool PERSISTENT = true, UNIFORM_K = true;
   struct EpiRegs { AdamRegs ad; typename Elem<T>::Raw4 w; };
   __device__ void epi_begin(Epi&, const GInfo&, int, bool, int) const {}
   __device__ void epi_load(EpiRegs& r, const GInfo& g, const EpiPos& pos) const {

@@ -396,10 +396,8 @@ __device__ __forceinline__ void epilogue(const P& p, const typename P::GInfo& gi
 // P::PERSISTENT: the grid is one workgroup per CU and workgroup i runs tiles i, i + gridDim.x, ...
 // of the XCD-aware tile order (gridDim.x is a multiple of 8, so all tiles of a workgroup belong
 // to the XCD it runs on).  Between two tiles of a CU there is then neither a workgroup dispatch
-// nor a wait for the finished tile's stores to drain (2 to 8 us per tile otherwise).  Policies
-// whose epilogue needs the whole register file (the fused Adam update) keep one tile per
-// workgroup: inside the tile loop their scalar operands would stay live across the main loop and
-// spill.  INTERIOR: no tile of the launch touches an edge, only the unpredicated code is built in.
+// nor a wait for the finished tile's stores to drain (2 to 8 us per tile otherwise).
+// INTERIOR: no tile of the launch touches an edge, only the unpredicated code is built in.
 template <class P, bool INTERIOR>
 __global__ __launch_bounds__(NTHREADS) void gemm_bf16_kernel(P p, TileGrid tg, int nwg) {
   extern __shared__ __align__(16) bf16_t smem[];
