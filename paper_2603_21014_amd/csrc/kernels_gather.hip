@@ -426,8 +426,8 @@ __global__ __launch_bounds__(256) void fl_fill_kernel(Dims D, const uint8_t* __r
 }
 
 // One item = (layer l, feature f, pair of targets): a workgroup of 256 lanes, 8 columns each,
-// sums z * d y_hat rows over the feature's tokens (four tokens in flight), then finishes the row
-// of both targets: norm term, optional gradient store, optional Adam update.  Most rows of a
+// requests the rows' weights and optimizer state, sums z * d y_hat rows over the feature's tokens (four tokens in
+// flight) meanwhile, then finishes the row of both targets: norm term, optional gradient store, optional Adam update.  Most rows of a
 // sparse step have no token at all and only stream their optimizer state.  Token indices and
 // values are wave-uniform, so every address is a scalar base plus the lane's fixed column offset.
 constexpr int SD_TCH = 2;
@@ -439,7 +439,29 @@ __device__ __forceinline__ void sparse_dwdec_rows(const Dims& D, int l, int f, i
                                                   T* __restrict__ dW_dec, const AdamFuseArgs& fuse, uint32_t col,
                                                   bool ok1) {
   // the lane owns columns col..col+3 and, when ok1, col+1024..col+1027: every access of the
-  // workgroup is one contiguous run of 256 x 4 elements
+  // workgroup is one contiguous run of 256 x 4 elements.
+  // The rows' weights and optimizer state are requested first: they come from HBM and do not depend on the
+  // token lists, so their latency lies under the gathering of the d y_hat rows below.
+  // (native vector types: selects on the float4 class type would go through scratch memory)
+  typename Elem<T>::Raw4 wr[NT][2];
+  nt_f32x4 m4[NT][2], v4[NT][2], p4[NT][2];
+#pragma unroll
+  for (int t = 0; t < NT; ++t) {
+    const size_t o = ((size_t)packed_index(l, lp0 + t, D.L) * D.F + f) * D.d;
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      m4[t][h] = v4[t][h] = p4[t][h] = nt_f32x4{0.f, 0.f, 0.f, 0.f};
+      wr[t][h] = Elem<T>::narrow4(make_float4(0.f, 0.f, 0.f, 0.f));
+      if (h == 1 && !ok1) continue;
+      const uint32_t ch = col + 1024 * h;
+      wr[t][h] = Elem<T>::load_raw4(lane_ptr(W_dec + o, ch));
+      if (fuse.m) {
+        m4[t][h] = *reinterpret_cast<const nt_f32x4*>(lane_ptr(fuse.m + o, ch));
+        v4[t][h] = *reinterpret_cast<const nt_f32x4*>(lane_ptr(fuse.v + o, ch));
+        if (fuse.master) p4[t][h] = *reinterpret_cast<const nt_f32x4*>(lane_ptr(fuse.master + o, ch));
+      }
+    }
+  }
   float acc[NT][2][4];
 #pragma unroll
   for (int t = 0; t < NT; ++t)
@@ -449,7 +471,8 @@ __device__ __forceinline__ void sparse_dwdec_rows(const Dims& D, int l, int f, i
       for (int k = 0; k < 4; ++k) acc[t][h][k] = 0.f;
   int j = 0;
   for (; j + 4 <= cnt; j += 4) {
-    float4 r[4][NT][2];
+    // (the gathered rows stay in their storage type until they are used: half the registers for bf16)
+    typename Elem<T>::Raw4 r[4][NT][2];
     float zv[4];
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
@@ -458,8 +481,8 @@ __device__ __forceinline__ void sparse_dwdec_rows(const Dims& D, int l, int f, i
 #pragma unroll
       for (int t = 0; t < NT; ++t) {
         const T* row = d_yhat + ((size_t)(lp0 + t) * D.B + b) * D.d;
-        r[u][t][0] = Elem<T>::load4(lane_ptr(row, col));
-        r[u][t][1] = ok1 ? Elem<T>::load4(lane_ptr(row, col + 1024)) : make_float4(0.f, 0.f, 0.f, 0.f);
+        r[u][t][0] = Elem<T>::load_raw4(lane_ptr(row, col));
+        r[u][t][1] = Elem<T>::load_raw4(lane_ptr(row, ok1 ? col + 1024 : col));
       }
     }
 #pragma unroll
@@ -468,10 +491,11 @@ __device__ __forceinline__ void sparse_dwdec_rows(const Dims& D, int l, int f, i
       for (int t = 0; t < NT; ++t)
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
-          acc[t][h][0] = fmaf(zv[u], r[u][t][h].x, acc[t][h][0]);
-          acc[t][h][1] = fmaf(zv[u], r[u][t][h].y, acc[t][h][1]);
-          acc[t][h][2] = fmaf(zv[u], r[u][t][h].z, acc[t][h][2]);
-          acc[t][h][3] = fmaf(zv[u], r[u][t][h].w, acc[t][h][3]);
+          const float4 q = Elem<T>::widen4(r[u][t][h]);
+          acc[t][h][0] = fmaf(zv[u], q.x, acc[t][h][0]);
+          acc[t][h][1] = fmaf(zv[u], q.y, acc[t][h][1]);
+          acc[t][h][2] = fmaf(zv[u], q.z, acc[t][h][2]);
+          acc[t][h][3] = fmaf(zv[u], q.w, acc[t][h][3]);
         }
   }
   for (; j < cnt; ++j) {
@@ -491,27 +515,15 @@ __device__ __forceinline__ void sparse_dwdec_rows(const Dims& D, int l, int f, i
       }
     }
   }
-  // the rows' weights and optimizer state: all loads first, then the updates
-  // (native vector types: selects on the float4 class type would go through scratch memory)
-  nt_f32x4 w[NT][2], m4[NT][2], v4[NT][2], p4[NT][2];
+  nt_f32x4 w[NT][2];
 #pragma unroll
-  for (int t = 0; t < NT; ++t) {
-    const size_t o = ((size_t)packed_index(l, lp0 + t, D.L) * D.F + f) * D.d;
+  for (int t = 0; t < NT; ++t)
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
-      w[t][h] = m4[t][h] = v4[t][h] = p4[t][h] = nt_f32x4{0.f, 0.f, 0.f, 0.f};
-      if (h == 1 && !ok1) continue;
-      const uint32_t ch = col + 1024 * h;
-      const float4 wl = Elem<T>::load4(lane_ptr(W_dec + o, ch));
+      const float4 wl = Elem<T>::widen4(wr[t][h]);
       w[t][h] = nt_f32x4{wl.x, wl.y, wl.z, wl.w};
-      p4[t][h] = w[t][h];
-      if (fuse.m) {
-        m4[t][h] = *reinterpret_cast<const nt_f32x4*>(lane_ptr(fuse.m + o, ch));
-        v4[t][h] = *reinterpret_cast<const nt_f32x4*>(lane_ptr(fuse.v + o, ch));
-        if (fuse.master) p4[t][h] = *reinterpret_cast<const nt_f32x4*>(lane_ptr(fuse.master + o, ch));
-      }
+      if (!fuse.master) p4[t][h] = w[t][h];
     }
-  }
 #pragma unroll
   for (int t = 0; t < NT; ++t) {
     const size_t o = ((size_t)packed_index(l, lp0 + t, D.L) * D.F + f) * D.d;
@@ -540,7 +552,7 @@ __device__ __forceinline__ void sparse_dwdec_rows(const Dims& D, int l, int f, i
 }
 
 template <typename T>
-__global__ __launch_bounds__(256, 5) void sparse_dwdec_kernel(Dims D, FeatureLists fl, const T* __restrict__ d_yhat,
+__global__ __launch_bounds__(256, 4) void sparse_dwdec_kernel(Dims D, FeatureLists fl, const T* __restrict__ d_yhat,
                                                            T* __restrict__ W_dec, const float* __restrict__ G,
                                                            const float* __restrict__ norms, T* __restrict__ dW_dec,
                                                            AdamFuseArgs fuse, const int32_t* __restrict__ flags) {
