@@ -89,8 +89,8 @@ typedef struct clt_config {
   int32_t topk_k;         /* 0 <= topk_k <= F; read only when activation == CLT_ACT_TOPK           */
   int32_t reuse_decoder_norms; /* 0: every clt_forward computes the decoder norms (App. B) from W_dec.
                              1: a training loop that owns its weights may skip that pass over W_dec: a
-                             clt_backward_adam_step that updates W_dec inside its weight-gradient GEMM
-                             (bf16, dense mode, F and d multiples of 256) also leaves the row sums of
+                             clt_backward_adam_step that updates W_dec inside its weight-gradient kernel
+                             (bf16, any decode mode, F and d multiples of 256) also leaves the row sums of
                              squares of the UPDATED weights, and the next clt_forward on this handle
                              that is given the same W_dec pointer forms the norms from them.  The
                              caller promises that nothing else writes W_dec between those two calls.

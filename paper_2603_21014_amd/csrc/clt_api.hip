@@ -13,6 +13,8 @@
 
 #include "common.h"
 
+#include <algorithm>
+
 using namespace clt;
 
 namespace {
@@ -146,7 +148,8 @@ Plan make_plan(const clt_config* c) {
   p.xcd_sync = o;   o += align_up(8 * 64 * 4);   // pacing counters of the dense decode, one 256-byte line per XCD
   // row sums of squares of the updated decoder weights, [P][d / 64][F] (reuse_decoder_norms, eligible shapes only)
   const bool n2 = c->reuse_decoder_norms && c->dtype == CLT_DTYPE_BF16 && F % 256 == 0 && d % 256 == 0;
-  p.n2_part = o;    o += align_up(n2 ? (L * (L + 1) / 2) * (d / 64) * F * 4 : 0);
+  // (per block and feature: d / 64 runs in the dense kernel's layout, 8 slots per 2048 columns in the row kernel's)
+  p.n2_part = o;    o += align_up(n2 ? (L * (L + 1) / 2) * std::max<size_t>(d / 64, 8 * ((d + 2047) / 2048)) * F * 4 : 0);
   p.pre32 = o;      o += align_up(c->activation == CLT_ACT_TOPK ? L * B * F * 4 : 0);   // fp32 pre-activations for the selection
   // active-feature lists of the gather decode: forced gather must hold a fully dense row;
   // the automatic switch only ever gathers below the threshold, so rows are capped at a
@@ -480,7 +483,8 @@ int clt_forward(clt_handle* h, void* stream, const void* x, const float* x_scale
   int32_t* flags = reinterpret_cast<int32_t*>(h->ws + h->plan.flags);
   RUN(h, s, K_ZERO, launch_zero_i32(s, l0, h->D.L));
   if (h->n2_for && h->n2_for == W_dec)   // the last fused update left the sums of squares of exactly these weights
-    RUN(h, s, K_NORMS_REUSE, launch_norms_from_partials(s, h->D, reinterpret_cast<const float*>(h->ws + h->plan.n2_part), norms));
+    RUN(h, s, K_NORMS_REUSE, launch_norms_from_partials(s, h->D, reinterpret_cast<const float*>(h->ws + h->plan.n2_part), norms,
+                                                            h->cfg.decode_mode == CLT_DECODE_DENSE ? nullptr : flags, h->plan.kcap));
   else
     RUN(h, s, K_NORMS, launch_decoder_norms(s, h->bf16, h->D, W_dec, norms));
   h->n2_for = nullptr;
@@ -595,7 +599,7 @@ static int backward_impl(clt_handle* h, hipStream_t s, const void* x, const floa
   if (fold) { za.x_scale = h->int8 ? x_scale : nullptr; za.part_theta = part; za.part_benc = part2; za.part_below = part3; }
   const int nparts = fold ? fold_row_blocks(D.B) : rbs;
   DWdecArgs wa{z, d_yhat, W_dec, G, norms, gW_dec, fdec, skip, kcap};
-  if (h->n2_eligible && fdec.m && mode == CLT_DECODE_DENSE) wa.n2_part = reinterpret_cast<float*>(h->ws + h->plan.n2_part);
+  if (h->n2_eligible && fdec.m) wa.n2_part = reinterpret_cast<float*>(h->ws + h->plan.n2_part);
   DWencArgs ea{x, dpre, gW_enc, W_enc, fenc};
   GatherLists gl{reinterpret_cast<int32_t*>(h->ws + h->plan.g_idx), reinterpret_cast<float*>(h->ws + h->plan.g_val),
                  reinterpret_cast<int32_t*>(h->ws + h->plan.g_counts),
@@ -697,8 +701,9 @@ int clt_backward_adam_step(clt_handle* h, void* stream, const void* x, const flo
   rc = backward_impl(h, s, x, x_scale, params->theta, params->W_dec, params->W_enc, z, act_class, grads->W_enc,
                      grads->b_enc, grads->theta, grads->W_dec, grads->b_dec, fenc, fdec);
   if (rc != CLT_OK) return rc;
-  // the dense weight-gradient GEMM has updated W_dec and left the row sums of squares of the new weights
-  if (h->n2_eligible && h->cfg.decode_mode == CLT_DECODE_DENSE) h->n2_for = params->W_dec;
+  // the weight-gradient kernel that ran (dense GEMM or row kernel) has updated W_dec and left the row sums of
+  // squares of the new weights
+  if (h->n2_eligible) h->n2_for = params->W_dec;
   RUN(h, s, K_ADAM_VEC, launch_adam_vector(s, (size_t)D.L * D.F, params->b_enc, grads->b_enc, m->b_enc, v->b_enc, a));
   RUN(h, s, K_ADAM_VEC, launch_adam_vector(s, (size_t)D.L * D.F, params->theta, grads->theta, m->theta, v->theta, a));
   RUN(h, s, K_ADAM_VEC, launch_adam_vector(s, (size_t)D.L * D.d, params->b_dec, grads->b_dec, m->b_dec, v->b_dec, a));

@@ -117,6 +117,19 @@ __device__ __forceinline__ void adam_element(float& p, float& m, float& v, float
   p = fmaf(a.neg_lr_over_bc1 * m, __builtin_amdgcn_rcpf(den), p);
 }
 
+// Sum over each row of 16 lanes, result in all of them: four adds on data-parallel-primitive operands (swaps
+// inside quads, then mirrored half rows and rows), no LDS round trips.
+template <int CTRL> __device__ __forceinline__ float dpp_move(float x) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), CTRL, 0xF, 0xF, true));
+}
+__device__ __forceinline__ float row16_sum(float v) {
+  v += dpp_move<0xB1>(v);    // quad_perm [1,0,3,2]
+  v += dpp_move<0x4E>(v);    // quad_perm [2,3,0,1]
+  v += dpp_move<0x141>(v);   // row_half_mirror: the other quad of the half row
+  v += dpp_move<0x140>(v);   // row_mirror: the other half row
+  return v;
+}
+
 // act_class bits
 constexpr uint8_t CLS_ACTIVE = 1;
 constexpr uint8_t CLS_WINDOW = 2;
@@ -205,7 +218,9 @@ hipError_t launch_topk_select(hipStream_t s, bool bf16, Dims D, const float* pre
 hipError_t launch_decoder_norms(hipStream_t s, bool bf16, Dims D, const void* W_dec, float* norms);
 // the same norms from the partial sums of squares a fused weight-gradient launch left behind:
 // n[l,f] = sqrt(sum over the blocks p(l, l..L-1) and their d / 64 column runs of n2_part[p][run][f]), in that order
-hipError_t launch_norms_from_partials(hipStream_t s, Dims D, const float* n2_part, float* norms);
+// (flags: the device-side decode switch of the step that left the sums, NULL when only the dense kernels run)
+hipError_t launch_norms_from_partials(hipStream_t s, Dims D, const float* n2_part, float* norms, const int32_t* flags,
+                                      int kcap);
 // L_rec partials, d_yhat = 2 r / B, column partials for db_dec
 hipError_t launch_loss_rec(hipStream_t s, bool bf16, bool int8_y, Dims D, const float* y_hat, const void* y,
                            const float* y_scale, void* d_yhat, double* loss_part, float* col_part);
@@ -289,6 +304,8 @@ hipError_t launch_feature_lists(hipStream_t s, bool bf16, Dims D, const uint8_t*
                                 const int32_t* flags);
 // dW_dec[p(l,lp)][f,:] = sum_{b in list(l,f)} z[l,b,f] d_yhat[lp,b,:] + (G/n)[l,f] W_dec[p][f,:], with the optional
 // fused Adam update of the row (every row is visited: Adam also moves rows without gradient)
+// (a.n2_part, bf16 with the fused update and d a multiple of 64: the row kernel leaves the same sums of squares of the
+// updated weights as the dense fused kernel)
 hipError_t launch_sparse_dwdec(hipStream_t s, bool bf16, Dims D, FeatureLists fl, const DWdecArgs& a,
                                const int32_t* flags);
 

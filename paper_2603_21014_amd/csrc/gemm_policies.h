@@ -98,19 +98,6 @@ __device__ __forceinline__ X* epi_ptr(X* base, size_t uoff, uint32_t loff) {
   return reinterpret_cast<X*>(reinterpret_cast<Byte*>(base + uoff) + loff * (uint32_t)sizeof(X));
 }
 
-// Sum over each row of 16 lanes, result in all of them: four adds on data-parallel-primitive operands (swaps
-// inside quads, then mirrored half rows and rows), no LDS round trips.
-template <int CTRL> __device__ __forceinline__ float dpp_move(float x) {
-  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), CTRL, 0xF, 0xF, true));
-}
-__device__ __forceinline__ float row16_sum(float v) {
-  v += dpp_move<0xB1>(v);    // quad_perm [1,0,3,2]
-  v += dpp_move<0x4E>(v);    // quad_perm [2,3,0,1]
-  v += dpp_move<0x141>(v);   // row_half_mirror: the other quad of the half row
-  v += dpp_move<0x140>(v);   // row_mirror: the other half row
-  return v;
-}
-
 // Adam fused into a weight-gradient epilogue: the fp32 gradient of 4 consecutive
 // parameters goes straight from the accumulators into the moments and the
 // weights (App. C Table 1 update rule; same arithmetic as adam_kernel).

@@ -55,23 +55,37 @@ __global__ __launch_bounds__(256) void decoder_norms_kernel(Dims D, const T* __r
   if (lane == 0) norms[row] = sqrtf(acc);
 }
 
-// The same norms from per-(block, 64-column run, feature) sums of squares, [P][d / 64][F]: fixed order
+// The same norms from sums of squares that the last fused update left, in a fixed order.  The dense kernel leaves
+// them per (block, 64-column run, feature), [P][d / 64][F]; the list-driven row kernel per (block, feature, slot),
+// [P][F][8 ceil(d / 2048)].  Which of the two ran is what the device-side switch decided in that step (flags).
 __global__ __launch_bounds__(256) void norms_from_partials_kernel(Dims D, const float* __restrict__ n2_part,
-                                                                  float* __restrict__ norms) {
+                                                                  float* __restrict__ norms,
+                                                                  const int32_t* __restrict__ flags, int kcap) {
   const long i = (long)blockIdx.x * 256 + threadIdx.x;      // l * F + f
   if (i >= (long)D.L * D.F) return;
   const int l = (int)(i / D.F), f = (int)(i - (long)l * D.F);
-  const int runs = D.d >> 6;
-  const float* base = n2_part + (size_t)packed_index(l, l, D.L) * runs * D.F + f;
-  // eight independent chains keep eight loads in flight per lane; the order of the sum stays fixed
-  const int n = (D.L - l) * runs;
   float a[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-  int j = 0;
-  for (; j + 8 <= n; j += 8) {
+  if (flags && gather_selected(flags, kcap)) {
+    const int slots = 8 * ((D.d + 2047) / 2048);
+    const float* base = n2_part + ((size_t)packed_index(l, l, D.L) * D.F + f) * slots;
+    for (int j = 0; j < D.L - l; ++j)
+      for (int q = 0; q < slots; q += 8) {
+        const float4 u = *reinterpret_cast<const float4*>(base + (size_t)j * D.F * slots + q);
+        const float4 w = *reinterpret_cast<const float4*>(base + (size_t)j * D.F * slots + q + 4);
+        a[0] += u.x; a[1] += u.y; a[2] += u.z; a[3] += u.w; a[4] += w.x; a[5] += w.y; a[6] += w.z; a[7] += w.w;
+      }
+  } else {
+    const int runs = D.d >> 6;
+    const float* base = n2_part + (size_t)packed_index(l, l, D.L) * runs * D.F + f;
+    // eight independent chains keep eight loads in flight per lane; the order of the sum stays fixed
+    const int n = (D.L - l) * runs;
+    int j = 0;
+    for (; j + 8 <= n; j += 8) {
 #pragma unroll
-    for (int q = 0; q < 8; ++q) a[q] += base[(size_t)(j + q) * D.F];
+      for (int q = 0; q < 8; ++q) a[q] += base[(size_t)(j + q) * D.F];
+    }
+    for (; j < n; ++j) a[j & 7] += base[(size_t)j * D.F];
   }
-  for (; j < n; ++j) a[j & 7] += base[(size_t)j * D.F];
   norms[i] = sqrtf(((a[0] + a[1]) + (a[2] + a[3])) + ((a[4] + a[5]) + (a[6] + a[7])));
 }
 
@@ -583,9 +597,11 @@ hipError_t launch_decoder_norms(hipStream_t s, bool bf16, Dims D, const void* W_
   return hipGetLastError();
 }
 
-hipError_t launch_norms_from_partials(hipStream_t s, Dims D, const float* n2_part, float* norms) {
+hipError_t launch_norms_from_partials(hipStream_t s, Dims D, const float* n2_part, float* norms, const int32_t* flags,
+                                      int kcap) {
   const long rows = (long)D.L * D.F;
-  hipLaunchKernelGGL(norms_from_partials_kernel, dim3((unsigned)((rows + 255) / 256)), dim3(256), 0, s, D, n2_part, norms);
+  hipLaunchKernelGGL(norms_from_partials_kernel, dim3((unsigned)((rows + 255) / 256)), dim3(256), 0, s, D, n2_part, norms,
+                     flags, kcap);
   return hipGetLastError();
 }
 

@@ -432,12 +432,12 @@ __global__ __launch_bounds__(256) void fl_fill_kernel(Dims D, const uint8_t* __r
 // values are wave-uniform, so every address is a scalar base plus the lane's fixed column offset.
 constexpr int SD_TCH = 2;
 
-template <typename T, int NT>
+template <typename T, int NT, bool MASTER>
 __device__ __forceinline__ void sparse_dwdec_rows(const Dims& D, int l, int f, int lp0, int cnt,
                                                   const int32_t* __restrict__ tk, const float* __restrict__ tv,
                                                   float coef, const T* __restrict__ d_yhat, T* __restrict__ W_dec,
                                                   T* __restrict__ dW_dec, const AdamFuseArgs& fuse, uint32_t col,
-                                                  bool ok1) {
+                                                  bool ok1, float* __restrict__ n2_part, int n2_slots, int n2_slot0) {
   // the lane owns columns col..col+3 and, when ok1, col+1024..col+1027: every access of the
   // workgroup is one contiguous run of 256 x 4 elements.
   // The rows' weights and optimizer state are requested first: they come from HBM and do not depend on the
@@ -458,7 +458,7 @@ __device__ __forceinline__ void sparse_dwdec_rows(const Dims& D, int l, int f, i
       if (fuse.m) {
         m4[t][h] = *reinterpret_cast<const nt_f32x4*>(lane_ptr(fuse.m + o, ch));
         v4[t][h] = *reinterpret_cast<const nt_f32x4*>(lane_ptr(fuse.v + o, ch));
-        if (fuse.master) p4[t][h] = *reinterpret_cast<const nt_f32x4*>(lane_ptr(fuse.master + o, ch));
+        if (MASTER) p4[t][h] = *reinterpret_cast<const nt_f32x4*>(lane_ptr(fuse.master + o, ch));
       }
     }
   }
@@ -522,11 +522,12 @@ __device__ __forceinline__ void sparse_dwdec_rows(const Dims& D, int l, int f, i
     for (int h = 0; h < 2; ++h) {
       const float4 wl = Elem<T>::widen4(wr[t][h]);
       w[t][h] = nt_f32x4{wl.x, wl.y, wl.z, wl.w};
-      if (!fuse.master) p4[t][h] = w[t][h];
+      if (!MASTER) p4[t][h] = w[t][h];
     }
 #pragma unroll
   for (int t = 0; t < NT; ++t) {
     const size_t o = ((size_t)packed_index(l, lp0 + t, D.L) * D.F + f) * D.d;
+    float n2_half[2] = {0.f, 0.f};
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
       if (h == 1 && !ok1) continue;
@@ -544,18 +545,30 @@ __device__ __forceinline__ void sparse_dwdec_rows(const Dims& D, int l, int f, i
         *reinterpret_cast<float4*>(lane_ptr(fuse.m + o, ch)) = make_float4(mm[0], mm[1], mm[2], mm[3]);
         *reinterpret_cast<float4*>(lane_ptr(fuse.v + o, ch)) = make_float4(vv[0], vv[1], vv[2], vv[3]);
         const float4 pn = make_float4(pp[0], pp[1], pp[2], pp[3]);
-        if (fuse.master) *reinterpret_cast<float4*>(lane_ptr(fuse.master + o, ch)) = pn;
-        Elem<T>::store4(lane_ptr(W_dec + o, ch), pn);
+        if (MASTER) *reinterpret_cast<float4*>(lane_ptr(fuse.master + o, ch)) = pn;
+        const typename Elem<T>::Raw4 stored = Elem<T>::narrow4(pn);
+        *reinterpret_cast<typename Elem<T>::Raw4*>(lane_ptr(W_dec + o, ch)) = stored;
+        if (n2_part) {   // sum of squares of the wave's 256 weights as stored, for the next step's norms: one slot per wave and half
+          const float4 wn = Elem<T>::widen4(stored);
+          const int b16 = __float_as_int(row16_sum((wn.x * wn.x + wn.y * wn.y) + (wn.z * wn.z + wn.w * wn.w)));
+          n2_half[h] = (__int_as_float(__builtin_amdgcn_readlane(b16, 0)) + __int_as_float(__builtin_amdgcn_readlane(b16, 16))) +
+                       (__int_as_float(__builtin_amdgcn_readlane(b16, 32)) + __int_as_float(__builtin_amdgcn_readlane(b16, 48)));
+        }
       }
     }
+    if (n2_part && fuse.m && (threadIdx.x & 63) == 0)     // both halves of the wave's slot pair at once
+      *reinterpret_cast<float2*>(n2_part + ((size_t)packed_index(l, lp0 + t, D.L) * D.F + f) * n2_slots + n2_slot0) =
+          make_float2(n2_half[0], n2_half[1]);
   }
 }
 
-template <typename T>
+// MASTER: fp32 master weights travel with the moments (compile-time: their 16 registers are not held otherwise)
+template <typename T, bool MASTER>
 __global__ __launch_bounds__(256, 4) void sparse_dwdec_kernel(Dims D, FeatureLists fl, const T* __restrict__ d_yhat,
                                                            T* __restrict__ W_dec, const float* __restrict__ G,
                                                            const float* __restrict__ norms, T* __restrict__ dW_dec,
-                                                           AdamFuseArgs fuse, const int32_t* __restrict__ flags) {
+                                                           AdamFuseArgs fuse, const int32_t* __restrict__ flags,
+                                                           float* __restrict__ n2_part) {
   if (!gather_selected(flags, fl.kcap)) return;
   const int tid = threadIdx.x;
   const int chunks = (D.L + SD_TCH - 1) / SD_TCH;          // chunk slots per (l, f); those past L - l are empty
@@ -586,16 +599,27 @@ __global__ __launch_bounds__(256, 4) void sparse_dwdec_kernel(Dims D, FeatureLis
       const int32_t* tk = fl.tok + (size_t)cur.l * D.B * fl.kcap + cur.off;
       const float* tv = fl.val + (size_t)cur.l * D.B * fl.kcap + cur.off;
       const float coef = cur.Gf * __builtin_amdgcn_rcpf(fmaxf(cur.nf, 1e-30f));
+      // row sums of squares of the updated weights (n2_part, d a multiple of 256): [P][F][8 slots per 2048 columns],
+      // slot = (wave, half) of the lanes that own the columns; slots whose columns do not exist hold zero
+      const int n2_slots = 8 * ((D.d + 2047) / 2048);
       for (int c0 = 0; c0 < D.d; c0 += 2048) {
         const int col = c0 + tid * 4;
-        if (col >= D.d) continue;
         const bool ok1 = col + 1024 < D.d;
+        const int slot0 = (c0 >> 11) * 8 + (tid >> 6) * 2;
+        if (n2_part && (tid & 63) == 0) {
+          const int nt = cur.lp0 + 1 < D.L ? 2 : 1;
+          for (int t = 0; t < nt; ++t) {
+            float* q = n2_part + ((size_t)packed_index(cur.l, cur.lp0 + t, D.L) * D.F + cur.f) * n2_slots + slot0;
+            if (col >= D.d) { q[0] = 0.f; q[1] = 0.f; }
+          }
+        }
+        if (col >= D.d) continue;
         if (cur.lp0 + 1 < D.L)
-          sparse_dwdec_rows<T, 2>(D, cur.l, cur.f, cur.lp0, cur.cnt, tk, tv, coef, d_yhat, W_dec, dW_dec, fuse,
-                                  (uint32_t)col, ok1);
+          sparse_dwdec_rows<T, 2, MASTER>(D, cur.l, cur.f, cur.lp0, cur.cnt, tk, tv, coef, d_yhat, W_dec, dW_dec, fuse,
+                                  (uint32_t)col, ok1, n2_part, n2_slots, slot0);
         else
-          sparse_dwdec_rows<T, 1>(D, cur.l, cur.f, cur.lp0, cur.cnt, tk, tv, coef, d_yhat, W_dec, dW_dec, fuse,
-                                  (uint32_t)col, ok1);
+          sparse_dwdec_rows<T, 1, MASTER>(D, cur.l, cur.f, cur.lp0, cur.cnt, tk, tv, coef, d_yhat, W_dec, dW_dec, fuse,
+                                  (uint32_t)col, ok1, n2_part, n2_slots, slot0);
       }
     }
     cur = nxt;
@@ -675,12 +699,14 @@ hipError_t launch_sparse_dwdec(hipStream_t s, bool bf16, Dims D, FeatureLists fl
                                const int32_t* flags) {
   const size_t items = (size_t)D.L * D.F * ((D.L + SD_TCH - 1) / SD_TCH);
   const dim3 grid((unsigned)(items < 256 * 64 ? items : 256 * 64));
-  if (bf16)
-    hipLaunchKernelGGL((sparse_dwdec_kernel<bf16_t>), grid, dim3(256), 0, s, D, fl, (const bf16_t*)a.d_yhat,
-                       (bf16_t*)a.W_dec, a.G, a.norms, (bf16_t*)a.dW_dec, a.fuse, flags);
-  else
-    hipLaunchKernelGGL((sparse_dwdec_kernel<float>), grid, dim3(256), 0, s, D, fl, (const float*)a.d_yhat,
-                       (float*)a.W_dec, a.G, a.norms, (float*)a.dW_dec, a.fuse, flags);
+  const bool master = a.fuse.m && a.fuse.master;
+  float* n2 = (bf16 && a.fuse.m && D.d % 256 == 0) ? a.n2_part : nullptr;
+#define CLT_SD(T, M)                                                                                              \
+  hipLaunchKernelGGL((sparse_dwdec_kernel<T, M>), grid, dim3(256), 0, s, D, fl, (const T*)a.d_yhat, (T*)a.W_dec, a.G, \
+                     a.norms, (T*)a.dW_dec, a.fuse, flags, n2)
+  if (bf16) { if (master) CLT_SD(bf16_t, true); else CLT_SD(bf16_t, false); }
+  else { if (master) CLT_SD(float, true); else CLT_SD(float, false); }
+#undef CLT_SD
   return hipGetLastError();
 }
 

@@ -206,6 +206,15 @@ def test_decoder_norms_reused_from_the_fused_update():
     # rounding of a few updated weights (one flip in a thousand weights is a relative L2 distance of 1.2e-4)
     for k in O.PARAM_NAMES:
         assert rel_l2(g.new_params[k], plain.new_params[k]) < 1e-4, k
+    # the list-driven row kernel of dW_dec leaves the same row sums (forced gather mode, same workload)
+    gg = GpuRun(w, params, x, y, fused=True, pre_steps=2, reuse_decoder_norms=True, decode_mode=GATHER)
+    assert gg.kernel_launches.get("decoder_norms_from_update") == 1 and "decoder_norms" not in gg.kernel_launches
+    assert gg.kernel_launches.get("sparse_dW_dec") == 1
+    og = OracleRun(w, gg.start_params, x, y, t=3, m=gg.start_m, v=gg.start_v, gpu_active=gg.active, gpu_window=gg.window)
+    show("norms from the list-driven update, step 3", compare_step(w, gg, og, TOL["bf16"], check_adam=False))
+    pg = GpuRun(w, params, x, y, fused=True, pre_steps=2, decode_mode=GATHER)
+    assert pg.kernel_launches.get("decoder_norms") == 1
+    assert rel_l2(gg.norms, pg.norms) < 1e-6
     # an unfused update in between changes W_dec without new row sums: the next forward must read W_dec again
     from paper_2603_21014_amd import binding as K
     step, (gp, gm, gv, _) = g.step, g.device_state
