@@ -215,6 +215,17 @@ def test_decoder_norms_reused_from_the_fused_update():
     pg = GpuRun(w, params, x, y, fused=True, pre_steps=2, decode_mode=GATHER)
     assert pg.kernel_launches.get("decoder_norms") == 1
     assert rel_l2(gg.norms, pg.norms) < 1e-6
+    # automatic mode: whichever of the two kernels the device-side switch picked leaves the sums, and the norms
+    # kernel reads the same switch to know their layout
+    for thr, picked in ((1.0, "sparse_dW_dec"), (0.0, "dW_dec_gemm")):
+        ga = GpuRun(w, params, x, y, fused=True, pre_steps=2, reuse_decoder_norms=True, decode_mode=AUTO,
+                    gather_density_threshold=thr)
+        assert ga.kernel_launches.get("decoder_norms_from_update") == 1 and "decoder_norms" not in ga.kernel_launches
+        assert ga.kernel_launches.get(picked, 0) >= 1
+        pa = GpuRun(w, params, x, y, fused=True, pre_steps=2, decode_mode=AUTO, gather_density_threshold=thr)
+        assert rel_l2(ga.norms, pa.norms) < 1e-6, (thr, rel_l2(ga.norms, pa.norms))
+        oa = OracleRun(w, ga.start_params, x, y, t=3, m=ga.start_m, v=ga.start_v, gpu_active=ga.active, gpu_window=ga.window)
+        show(f"norms from the update, automatic mode, threshold {thr}", compare_step(w, ga, oa, TOL["bf16"], check_adam=False))
     # an unfused update in between changes W_dec without new row sums: the next forward must read W_dec again
     from paper_2603_21014_amd import binding as K
     step, (gp, gm, gv, _) = g.step, g.device_state
