@@ -265,7 +265,7 @@ __global__ __launch_bounds__(256) void sparse_dpre_fill_kernel(Dims D, const uin
 // One wavefront per listed entry: for each target l' >= l it streams the entry's decoder row and
 // the token's d y_hat row (64 lanes x 8 columns, 4 passes in flight), keeps one partial dot
 // product per lane and reduces over the wave at the end.  No workgroup barrier, few registers
-// (eight waves per SIMD), so many independent latency chains overlap.  A row's entries are dealt
+// (93 registers with bf16 storage: five waves per SIMD), so many independent latency chains overlap.  A row's entries are dealt
 // to GDZ_PARTS workgroups of 4 waves, so that the few very long rows of a heavy-tailed batch do
 // not serialise on one workgroup.
 constexpr int GDZ_PARTS = 8;
