@@ -271,6 +271,12 @@ int clt_init(clt_handle** handle, const clt_config* cfg, void* workspace, size_t
       return CLT_ERR_HIP;
     }
   }
+  e = init_gather();
+  if (e != hipSuccess) {
+    set_err(g_err, "clt_init: cannot configure the gather kernels (%s)", hipGetErrorString(e));
+    (void)hipGetLastError();
+    return CLT_ERR_HIP;
+  }
   {   // set-up for clt_norm_accumulate_static on this device (address of the library's own scratch array)
     double* unused = nullptr;
     e = static_scratch(&unused);

@@ -294,6 +294,7 @@ hipError_t launch_gather_decode(hipStream_t s, bool bf16, Dims D, GatherLists g,
 hipError_t launch_sparse_dpre_fill(hipStream_t s, bool bf16, Dims D, const uint8_t* cls, const float* norms,
                                    float lam1_over_b, void* dpre, const int32_t* flags, int kcap);
 // dz at the listed entries only: sum_{lp>=l} <d_yhat[lp,b,:], W_dec[p(l,lp)][f,:]> + sparsity gradient -> dpre[l,b,f]
+hipError_t init_gather();   // once per process, after the device is chosen
 hipError_t launch_gather_dz(hipStream_t s, bool bf16, Dims D, GatherLists g, const void* d_yhat, const void* W_dec,
                             const float* norms, float lam_c_over_b, float C, void* dpre, const int32_t* flags);
 // Per (layer, feature): tokens on which the feature is active, ascending, with z (transpose of the row lists).

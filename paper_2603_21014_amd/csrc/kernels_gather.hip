@@ -24,6 +24,8 @@
 // state once, like a plain Adam pass, and reads its d y_hat rows out of the L2.
 #include "common.h"
 
+#include <cstdlib>
+
 #include <type_traits>
 
 namespace clt {
@@ -329,6 +331,108 @@ __global__ __launch_bounds__(256) void gather_dz_kernel(Dims D, GatherLists g, c
         const float sden = 1.0f + ex;
         const float gsp = 4.0f * lam_c_over_b * nn * ex * __builtin_amdgcn_rcpf(sden * sden);
         Elem<T>::store(dpre + (size_t)row * D.F + fe, part_sum + gsp);
+      }
+    }
+  }
+}
+
+// The same entries with the token's d y_hat rows staged in LDS: one workgroup of 16 waves per (layer, token) row,
+// the rows of up to `tcap` targets (at most 64 KB) are copied to LDS once and every wave streams the decoder rows
+// of its entries (four per batch of 64) against them, two targets' rows in flight.  Only decoder rows are left on the
+// vector-memory path (d y_hat is fetched once per row instead of once per entry), and 64 registers allow eight waves
+// per SIMD.  Launched with one workgroup per row, so long and short rows are balanced by the dispatcher; this is the
+// kernel the library uses whenever a row of d y_hat fits LDS, gather_dz_kernel above is the fallback.
+template <typename T> struct Raw8Lds;
+template <> struct Raw8Lds<bf16_t> {
+  static __device__ __forceinline__ Raw8<bf16_t>::type load(const bf16_t* p) { return *reinterpret_cast<const uint4*>(p); }
+};
+template <> struct Raw8Lds<float> {
+  static __device__ __forceinline__ Raw8<float>::type load(const float* p) {
+    return Raw8<float>::type{*reinterpret_cast<const float4*>(p), *reinterpret_cast<const float4*>(p + 4)};
+  }
+};
+template <typename T>
+__global__ __launch_bounds__(1024, 2) void gather_dz_lds_kernel(Dims D, GatherLists g, const T* __restrict__ d_yhat,
+                                                                const T* __restrict__ W_dec,
+                                                                const float* __restrict__ norms, float lam_c_over_b,
+                                                                float C, T* __restrict__ dpre,
+                                                                const int32_t* __restrict__ flags, int tcap) {
+  extern __shared__ __align__(16) unsigned char gdz_smem[];
+  T* dys = reinterpret_cast<T*>(gdz_smem);      // [tcap][d]
+  if (!gather_selected(flags, g.kcap)) return;
+  const int tid = threadIdx.x, lane = tid & 63, wv = __builtin_amdgcn_readfirstlane(tid >> 6);
+  constexpr int PIECE = 16 / (int)sizeof(T);      // elements per 16-byte piece
+  const int ppr = D.d / PIECE;                    // pieces per row
+  const long rows = (long)D.L * D.B;
+  for (long row = blockIdx.x; row < rows; row += gridDim.x) {      // layer 0 (most targets) first
+    const int l = (int)(row / D.B), b = (int)(row % D.B);
+    const int na = g.counts[row], n = na + g.counts_w[row];
+    const int32_t* ii = g.idx + (size_t)row * g.stride;
+    const float* vv = g.val + (size_t)row * g.stride;
+    for (int e0 = 0; e0 < n; e0 += 64) {
+      float sum[4] = {0.f, 0.f, 0.f, 0.f};
+      int slot[4], fe[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int e = e0 + u * 16 + wv;
+        const int ec = e < n ? e : e0;                               // (a valid slot; nothing is computed or stored for it)
+        slot[u] = ec < na ? ec : g.kcap - 1 - (ec - na);             // front: active entries, back: window-only
+        fe[u] = __builtin_amdgcn_readfirstlane(ii[slot[u]]);
+      }
+      for (int lp0 = l; lp0 < D.L; lp0 += tcap) {
+        const int tc = min(tcap, D.L - lp0);
+        __syncthreads();                                             // the previous chunk's rows are no longer read
+        for (int i = tid; i < tc * ppr; i += 1024) {
+          const int t = i / ppr, c = (i - t * ppr) * PIECE;
+          *reinterpret_cast<uint4*>(dys + (size_t)t * D.d + c) =
+              *reinterpret_cast<const uint4*>(d_yhat + ((size_t)(lp0 + t) * D.B + b) * D.d + c);
+        }
+        __syncthreads();
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          if (e0 + u * 16 + wv >= n) continue;                       // wave-uniform
+          float ps = sum[u];
+          const T* wrow0 = W_dec + ((size_t)packed_index(l, lp0, D.L) * D.F + fe[u]) * D.d;
+          const size_t blk = (size_t)D.F * D.d;
+          for (int t = 0; t < tc; t += 2) {
+            const bool two = t + 1 < tc;
+            for (int c0 = 0; c0 < D.d; c0 += 2048) {
+              typename Raw8<T>::type wq[2][4];
+#pragma unroll
+              for (int q = 0; q < 4; ++q) {
+                const uint32_t col = (uint32_t)(c0 + q * 512 + lane * 8);
+                if ((int)col < D.d) {
+                  wq[0][q] = Raw8<T>::load(lane_ptr(wrow0 + (size_t)t * blk, col));
+                  wq[1][q] = Raw8<T>::load(lane_ptr(wrow0 + (size_t)(two ? t + 1 : t) * blk, col));
+                }
+              }
+#pragma unroll
+              for (int q = 0; q < 4; ++q) {
+                const uint32_t col = (uint32_t)(c0 + q * 512 + lane * 8);
+                if ((int)col < D.d) {
+                  ps = Raw8<T>::dot(wq[0][q], Raw8Lds<T>::load(dys + (size_t)t * D.d + col), ps);
+                  if (two) ps = Raw8<T>::dot(wq[1][q], Raw8Lds<T>::load(dys + (size_t)(t + 1) * D.d + col), ps);
+                }
+              }
+            }
+          }
+          sum[u] = ps;
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        if (e0 + u * 16 + wv >= n) continue;
+        float ps = sum[u];
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) ps += __shfl_xor(ps, off, 64);
+        if (lane == 0) {
+          const float zv = vv[slot[u]];
+          const float nn = norms[(size_t)l * D.F + fe[u]];
+          const float ex = __builtin_amdgcn_exp2f(-2.0f * 1.4426950408889634f * C * nn * fabsf(zv));
+          const float sden = 1.0f + ex;
+          const float gsp = 4.0f * lam_c_over_b * nn * ex * __builtin_amdgcn_rcpf(sden * sden);
+          Elem<T>::store(dpre + (size_t)row * D.F + fe[u], ps + gsp);
+        }
       }
     }
   }
@@ -671,6 +775,24 @@ hipError_t launch_sparse_dpre_fill(hipStream_t s, bool bf16, Dims D, const uint8
 
 hipError_t launch_gather_dz(hipStream_t s, bool bf16, Dims D, GatherLists g, const void* d_yhat, const void* W_dec,
                             const float* norms, float lam_c_over_b, float C, void* dpre, const int32_t* flags) {
+  const size_t esz = bf16 ? 2 : 4;
+  int tcap = (int)(65536 / ((size_t)D.d * esz));      // targets whose d y_hat rows fit 64 KB of LDS
+  if (tcap > D.L) tcap = D.L;
+  if (D.d % 8 == 0 && tcap >= 1 && !getenv("CLT_GDZ_NO_LDS")) {
+    // One workgroup per row, no loop over rows: the dispatcher hands rows out as workgroups retire, so the long
+    // rows of a heavy-tailed batch (the same tokens in every layer) do not pile up on a few resident workgroups.
+    const size_t rows = (size_t)D.L * D.B;
+    const dim3 grid((unsigned)(rows < ((size_t)1 << 30) ? rows : ((size_t)1 << 30)));
+    const size_t lds = (size_t)tcap * D.d * esz;
+    if (bf16)
+      hipLaunchKernelGGL((gather_dz_lds_kernel<bf16_t>), grid, dim3(1024), lds, s, D, g, (const bf16_t*)d_yhat,
+                         (const bf16_t*)W_dec, norms, lam_c_over_b, C, (bf16_t*)dpre, flags, tcap);
+    else
+      hipLaunchKernelGGL((gather_dz_lds_kernel<float>), grid, dim3(1024), lds, s, D, g, (const float*)d_yhat,
+                         (const float*)W_dec, norms, lam_c_over_b, C, (float*)dpre, flags, tcap);
+    return hipGetLastError();
+  }
+  // rows too wide for LDS staging, or not a multiple of 8 columns (or CLT_GDZ_NO_LDS set, for comparison runs)
   const size_t items = ((size_t)D.L * D.B + 7) / 8 * 8 * GDZ_PARTS;
   const dim3 grid((unsigned)(items < 256 * 64 ? items : 256 * 64));
   if (bf16)
@@ -680,6 +802,13 @@ hipError_t launch_gather_dz(hipStream_t s, bool bf16, Dims D, GatherLists g, con
     hipLaunchKernelGGL((gather_dz_kernel<float>), grid, dim3(256), 0, s, D, g, (const float*)d_yhat,
                        (const float*)W_dec, norms, lam_c_over_b, C, (float*)dpre, flags);
   return hipGetLastError();
+}
+hipError_t init_gather() {
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gather_dz_lds_kernel<bf16_t>),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, 65536);
+  if (e != hipSuccess) return e;
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(&gather_dz_lds_kernel<float>),
+                             hipFuncAttributeMaxDynamicSharedMemorySize, 65536);
 }
 
 hipError_t launch_feature_lists(hipStream_t s, bool bf16, Dims D, const uint8_t* cls, const void* z, FeatureLists fl,

@@ -504,6 +504,23 @@ def test_gather_wide_model_dim_and_empty_rows():
         assert (g.y_hat[lp] == params["b_dec"][lp].numpy()[None, :]).all()
 
 
+def test_gather_dz_lds_chunks_and_fallback(monkeypatch):
+    """Backward through the lists when a token's d y_hat rows exceed 64 KB of LDS (fp32, d=2048: eight targets per
+    chunk, nine targets from layer 0, so a second chunk of one), and the one-wave-per-entry kernel, which otherwise
+    runs only when d is not a multiple of 8, forced on the same input: both against the oracle."""
+    w = S.scaled(S.WORKLOADS["tiny"], dtype="f32", L=9, d=2048, F=256, B=24, seed=84)
+    theta = sparse_theta(w, 0.3)                 # about 77 entries a row: two batches of 64
+    g, o = run_both(w, theta=theta, decode_mode=GATHER)
+    assert g.decode_switch[2] == 2
+    show("gather_dz, chunked LDS staging", compare_step(w, g, o, TOL["f32"]))
+    monkeypatch.setenv("CLT_GDZ_NO_LDS", "1")
+    params = S.make_params(w)
+    x, y = S.make_inputs(w)
+    h = GpuRun(w, params, x, y, theta=theta, decode_mode=GATHER)
+    for k in O.PARAM_NAMES:                      # same products, other summation order
+        assert rel_l2(h.grads[k], g.grads[k]) < 1e-5, k
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_gather_equals_dense(dtype):
     w = S.scaled(S.WORKLOADS["tiny"], dtype=dtype, L=4, d=128, F=512, B=130, seed=79)
