@@ -730,6 +730,125 @@ __global__ __launch_bounds__(256, 4) void sparse_dwdec_kernel(Dims D, FeatureLis
   }
 }
 
+// The same rows cut into eight column slices, one per XCD (workgroups go round-robin to the XCDs, so blockIdx & 7
+// names the slice): an XCD's L2 then only ever sees its d/8 columns of d y_hat, and with the (source, target) pairs
+// walked target-major that is B * d/8 elements at a time (2 MB at L=16 d=2048 B=4096), so the gathered d y_hat rows
+// come out of the L2.  One wave per (pair, feature, slice), four consecutive features per workgroup, lanes own 4
+// columns per pass of 256; 40 registers, eight waves per SIMD.  The weights and optimizer state, touched once, are
+// streamed with non-temporal accesses so that they do not displace the slice (plain accesses: 10 % slower).  The
+// sums run over the feature's tokens in list order, as in the kernel above: same gradient and update, bit for bit.
+// This is the kernel the library uses whenever d is a multiple of 32.
+template <typename T, bool MASTER>
+__global__ __launch_bounds__(256, 8) void sparse_dwdec_sliced_kernel(Dims D, FeatureLists fl, const T* __restrict__ d_yhat,
+                                                                     T* __restrict__ W_dec, const float* __restrict__ G,
+                                                                     const float* __restrict__ norms, T* __restrict__ dW_dec,
+                                                                     AdamFuseArgs fuse, const int32_t* __restrict__ flags,
+                                                                     float* __restrict__ n2_part) {
+  if (!gather_selected(flags, fl.kcap)) return;
+  const int lane = threadIdx.x & 63, wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int slice = blockIdx.x & 7, wg = blockIdx.x >> 3, nwg = gridDim.x >> 3;      // (the grid is a multiple of 8)
+  const int sw = D.d / 8, q4 = sw / 4;                     // slice width in columns and in lane quads (d % 32 == 0)
+  const int passes = (q4 + 63) / 64;
+  const int F4 = (D.F + 3) / 4;
+  const long items = (long)(D.L * (D.L + 1) / 2) * F4;
+  struct Meta { int l, lp, f, cnt, off; float Gf, nf; };
+  // (one item per workgroup as long as the grid allows it: handed out in order by the dispatcher, the workgroups in
+  //  flight stay within a narrow window of items, which is what keeps their d y_hat rows in the L2)
+  for (long it = wg; it < items; it += nwg) {
+    Meta cur;
+    const int pq = (int)(it / F4);                         // pair ordinal, target-major: (0,0) (0,1) (1,1) (0,2) ...
+    cur.f = (int)(it % F4) * 4 + wv;
+    int lpq = (int)((__builtin_amdgcn_sqrtf(8.0f * (float)pq + 1.0f) - 1.0f) * 0.5f);
+    while ((lpq + 1) * (lpq + 2) / 2 <= pq) ++lpq;
+    while (lpq * (lpq + 1) / 2 > pq) --lpq;
+    cur.lp = lpq;
+    cur.l = pq - lpq * (lpq + 1) / 2;
+    if (cur.f < D.F) {
+      const long lf = (long)cur.l * D.F + cur.f;
+      cur.cnt = fl.cnt[lf]; cur.off = fl.off[lf]; cur.Gf = G[lf]; cur.nf = norms[lf];
+      const int32_t* tk = fl.tok + (size_t)cur.l * D.B * fl.kcap + cur.off;
+      const float* tv = fl.val + (size_t)cur.l * D.B * fl.kcap + cur.off;
+      const float coef = cur.Gf * __builtin_amdgcn_rcpf(fmaxf(cur.nf, 1e-30f));
+      const size_t o = ((size_t)packed_index(cur.l, cur.lp, D.L) * D.F + cur.f) * D.d;
+      const T* dyt = d_yhat + (size_t)cur.lp * D.B * D.d;
+      for (int ps = 0; ps < passes; ++ps) {
+        const int qd = ps * 64 + lane;
+        const bool on = qd < q4;
+        const uint32_t col = (uint32_t)(slice * sw + (on ? qd : 0) * 4);      // (idle lanes shadow quad 0, store nothing)
+        typename Elem<T>::Raw4 wr;
+        nt_f32x4 m4 = {0.f, 0.f, 0.f, 0.f}, v4 = m4, p4 = m4;
+        wr = Elem<T>::nt_load_raw4(lane_ptr(W_dec + o, col));
+        if (fuse.m) {
+          m4 = nt_load_v4(lane_ptr(fuse.m + o, col));
+          v4 = nt_load_v4(lane_ptr(fuse.v + o, col));
+          if (MASTER) p4 = nt_load_v4(lane_ptr(fuse.master + o, col));
+        }
+        float acc[4] = {0.f, 0.f, 0.f, 0.f};
+        int j = 0;
+        for (; j + 4 <= cur.cnt; j += 4) {
+          typename Elem<T>::Raw4 r[4];
+          float zv[4];
+#pragma unroll
+          for (int u = 0; u < 4; ++u) {
+            const int b = __builtin_amdgcn_readfirstlane(tk[j + u]);
+            zv[u] = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(tv[j + u])));
+            r[u] = Elem<T>::load_raw4(lane_ptr(dyt + (size_t)b * D.d, col));
+          }
+#pragma unroll
+          for (int u = 0; u < 4; ++u) {
+            const float4 q = Elem<T>::widen4(r[u]);
+            acc[0] = fmaf(zv[u], q.x, acc[0]);
+            acc[1] = fmaf(zv[u], q.y, acc[1]);
+            acc[2] = fmaf(zv[u], q.z, acc[2]);
+            acc[3] = fmaf(zv[u], q.w, acc[3]);
+          }
+        }
+        for (; j < cur.cnt; ++j) {
+          const int b = __builtin_amdgcn_readfirstlane(tk[j]);
+          const float zv = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(tv[j])));
+          const float4 q = Elem<T>::widen4(Elem<T>::load_raw4(lane_ptr(dyt + (size_t)b * D.d, col)));
+          acc[0] = fmaf(zv, q.x, acc[0]);
+          acc[1] = fmaf(zv, q.y, acc[1]);
+          acc[2] = fmaf(zv, q.z, acc[2]);
+          acc[3] = fmaf(zv, q.w, acc[3]);
+        }
+        const float4 wl = Elem<T>::widen4(wr);
+        const float w4[4] = {wl.x, wl.y, wl.z, wl.w};
+        float g4[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) g4[k] = fmaf(coef, w4[k], acc[k]);
+        if (dW_dec && on) Elem<T>::store4(lane_ptr(dW_dec + o, col), make_float4(g4[0], g4[1], g4[2], g4[3]));
+        if (fuse.m) {
+          float mm[4] = {m4[0], m4[1], m4[2], m4[3]};
+          float vv[4] = {v4[0], v4[1], v4[2], v4[3]};
+          float pp[4];
+#pragma unroll
+          for (int k = 0; k < 4; ++k) pp[k] = MASTER ? p4[k] : w4[k];
+#pragma unroll
+          for (int k = 0; k < 4; ++k) adam_element(pp[k], mm[k], vv[k], g4[k], fuse.a);
+          const float4 pn = make_float4(pp[0], pp[1], pp[2], pp[3]);
+          const typename Elem<T>::Raw4 stored = Elem<T>::narrow4(pn);
+          if (on) {
+            nt_store_f4(lane_ptr(fuse.m + o, col), make_float4(mm[0], mm[1], mm[2], mm[3]));
+            nt_store_f4(lane_ptr(fuse.v + o, col), make_float4(vv[0], vv[1], vv[2], vv[3]));
+            if (MASTER) nt_store_f4(lane_ptr(fuse.master + o, col), pn);
+            Elem<T>::nt_store_raw4(lane_ptr(W_dec + o, col), stored);
+          }
+          if (n2_part) {      // sum of squares of the pass's weights as stored, for the next step's norms: slot (slice, pass)
+            const float4 wn = Elem<T>::widen4(stored);
+            const float sq = on ? (wn.x * wn.x + wn.y * wn.y) + (wn.z * wn.z + wn.w * wn.w) : 0.f;
+            const int b16 = __float_as_int(row16_sum(sq));
+            const float tot = (__int_as_float(__builtin_amdgcn_readlane(b16, 0)) + __int_as_float(__builtin_amdgcn_readlane(b16, 16))) +
+                              (__int_as_float(__builtin_amdgcn_readlane(b16, 32)) + __int_as_float(__builtin_amdgcn_readlane(b16, 48)));
+            if (lane == 0)
+              n2_part[((size_t)packed_index(cur.l, cur.lp, D.L) * D.F + cur.f) * (8 * passes) + slice * passes + ps] = tot;
+          }
+        }
+      }
+    }
+  }
+}
+
 }  // namespace
 
 hipError_t launch_decode_decide(hipStream_t s, Dims D, const int32_t* l0, float density_threshold, int forced,
@@ -826,10 +945,23 @@ hipError_t launch_feature_lists(hipStream_t s, bool bf16, Dims D, const uint8_t*
 
 hipError_t launch_sparse_dwdec(hipStream_t s, bool bf16, Dims D, FeatureLists fl, const DWdecArgs& a,
                                const int32_t* flags) {
-  const size_t items = (size_t)D.L * D.F * ((D.L + SD_TCH - 1) / SD_TCH);
-  const dim3 grid((unsigned)(items < 256 * 64 ? items : 256 * 64));
   const bool master = a.fuse.m && a.fuse.master;
   float* n2 = (bf16 && a.fuse.m && D.d % 256 == 0) ? a.n2_part : nullptr;
+  // Both kernels get one workgroup per item while the grid allows it (see the comment in the sliced kernel).
+  if (D.d % 32 == 0 && !getenv("CLT_SD_ROWS")) {
+    const size_t per_xcd = (size_t)(D.L * (D.L + 1) / 2) * ((D.F + 3) / 4), gx = (size_t)1 << 27;
+    const dim3 grid((unsigned)(8 * (per_xcd < gx ? per_xcd : gx)));
+#define CLT_SDS(T, M)                                                                                              \
+  hipLaunchKernelGGL((sparse_dwdec_sliced_kernel<T, M>), grid, dim3(256), 0, s, D, fl, (const T*)a.d_yhat,         \
+                     (T*)a.W_dec, a.G, a.norms, (T*)a.dW_dec, a.fuse, flags, n2)
+    if (bf16) { if (master) CLT_SDS(bf16_t, true); else CLT_SDS(bf16_t, false); }
+    else { if (master) CLT_SDS(float, true); else CLT_SDS(float, false); }
+#undef CLT_SDS
+    return hipGetLastError();
+  }
+  // d not a multiple of 32 (or CLT_SD_ROWS set, for comparison runs): whole rows per workgroup
+  const size_t items = (size_t)D.L * D.F * ((D.L + SD_TCH - 1) / SD_TCH), gcap = (size_t)1 << 30;
+  const dim3 grid((unsigned)(items < gcap ? items : gcap));
 #define CLT_SD(T, M)                                                                                              \
   hipLaunchKernelGGL((sparse_dwdec_kernel<T, M>), grid, dim3(256), 0, s, D, fl, (const T*)a.d_yhat, (T*)a.W_dec, a.G, \
                      a.norms, (T*)a.dW_dec, a.fuse, flags, n2)

@@ -550,6 +550,28 @@ def test_sparse_backward_fused_adam(dtype, master):
     show(f"sparse bwd fused {dtype} master={master}", compare_step(w, g, o, TOL[dtype]))
 
 
+@pytest.mark.parametrize("dtype,d", [("bf16", 256), ("f32", 96), ("bf16", 2304)])
+def test_sparse_backward_column_slices_match_whole_rows(monkeypatch, dtype, d):
+    """The row kernel of dW_dec cut into eight column slices (one per XCD; d a multiple of 32) sums a feature's
+    tokens in the same order as the kernel that takes whole rows: gradients and the fused update must agree bit for
+    bit.  d = 2304: two passes of lanes per slice, the second one ragged."""
+    w = S.scaled(S.WORKLOADS["tiny"], dtype=dtype, L=4, d=d, F=264, B=90, seed=85, master_weights=dtype == "bf16")
+    theta = sparse_theta(w, 0.06)
+    params = S.make_params(w)
+    x, y = S.make_inputs(w)
+    for fused in (False, True):
+        monkeypatch.delenv("CLT_SD_ROWS", raising=False)
+        a = GpuRun(w, params, x, y, theta=theta, decode_mode=GATHER, fused=fused)
+        monkeypatch.setenv("CLT_SD_ROWS", "1")
+        b = GpuRun(w, params, x, y, theta=theta, decode_mode=GATHER, fused=fused)
+        assert a.decode_switch[2] == 2
+        if not fused:
+            assert (a.grads["W_dec"] == b.grads["W_dec"]).all()
+        for k in O.PARAM_NAMES:
+            assert (a.new_params[k] == b.new_params[k]).all(), k
+            assert (a.new_m[k] == b.new_m[k]).all() and (a.new_v[k] == b.new_v[k]).all(), k
+
+
 def test_sparse_backward_many_layers():
     """More than 8 targets per source: the row kernel walks them in two chunks."""
     w = S.scaled(S.WORKLOADS["tiny"], dtype="bf16", L=11, d=64, F=256, B=48, seed=82)
