@@ -253,9 +253,17 @@ def density_sweep(args, log):
                     row["active_per_token_layer"] = round(k_mean, 1)
                     gbytes = w.B * k_mean * w.P * w.d * 2.0
                     row["gather_GBps"] = round(gbytes / (ms["gather_decode"] * 1e-3) / 1e9, 1)
-                    row["gather_dz_GBps"] = round(gbytes / (ms["gather_dz"] * 1e-3) / 1e9, 1)
+                    # lists of at most 128 entries per token: the row kernel of dW_dec takes the dot products of dz
+                    # as well and "gather_dz" is only the kernel that sums them
+                    longest = int(K.clt_workspace_view(st.H, "decode_switch")[3].item())
+                    row["dz_in_row_kernel"] = longest <= w.B * 128
+                    row["gather_dz_GBps"] = (None if row["dz_in_row_kernel"]
+                                             else round(gbytes / (ms["gather_dz"] * 1e-3) / 1e9, 1))
+                    row["lists_backward_decoder_ms"] = round(row["gather_dz_ms"] + row["sparse_dW_dec_ms"], 3)
+                    row["dense_backward_decoder_ms"] = None
                     # every parameter's weight, moments read and written once by the row kernel
                     row["sparse_dW_dec_GBps"] = round(w.P * w.F * w.d * 20.0 / (ms["sparse_dW_dec"] * 1e-3) / 1e9, 1)
+            row["dense_backward_decoder_ms"] = round(row["dense_dz_ms"] + row["dense_dW_dec_ms"], 3)
             log(recipe + " " + str(row))
             rows.append(row)
         cross = None
@@ -319,9 +327,9 @@ def main():
                     help="skip the vendor-library GEMM reference measured after the timed region")
     ap.add_argument("--decode-mode", default="dense", choices=["dense", "gather", "auto"],
                     help="dense GEMMs (default), the list-driven kernels of the sparse regime, or the device-side switch")
-    ap.add_argument("--gather-density-threshold", type=float, default=0.004,
+    ap.add_argument("--gather-density-threshold", type=float, default=0.007,
                     help="auto mode: use the list-driven kernels at or below this mean active fraction (the measured "
-                         "whole-step break-even on an MI355X is 0.0043)")
+                         "whole-step break-even on an MI355X is 0.008)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-timing", action="store_true",
                     help="skip the per-kernel HIP-event brackets (roofline entry becomes null)")

@@ -98,9 +98,10 @@ typedef struct clt_config {
   float gather_density_threshold; /* AUTO: gather when the mean active fraction of the batch
                              is <= this and no (layer, token) row has more than about 8x
                              as many active features (else the step decodes densely).
-                             On an MI355X the whole step breaks even near 0.0043 (35 active
-                             of 8192 features), whatever the expansion factor: the dense
-                             cost grows with F, the list-driven one with the active count.  */
+                             On an MI355X the whole step breaks even near 0.008 (about 70
+                             active of 8192 features), whatever the expansion factor: the
+                             dense cost grows with F, the list-driven one with the active
+                             count; the binding's default is 0.007.                         */
   float C;                /* sparsity scale C of the App. B objective                     */
   float ste_bandwidth;    /* width eps of the rectangle kernel of the threshold gradient */
   float beta1, beta2, adam_eps; /* Adam (App. C Table 1: 0.9, 0.999)                     */

@@ -23,9 +23,10 @@ constexpr size_t ALIGN = 256;
 inline size_t align_up(size_t v) { return (v + ALIGN - 1) / ALIGN * ALIGN; }
 
 struct Plan {
-  size_t norms, G, d_yhat, dpre, part_cols, part_cols2, part_cols3, part_rec, part_sp, part_dead, l0, flags, xcd_sync, n2_part, pre32, g_idx, g_val, g_counts, g_counts_w,
+  size_t norms, G, d_yhat, dpre, part_cols, part_cols2, part_cols3, part_rec, part_sp, part_dead, l0, flags, xcd_sync, n2_part, pre32, g_idx, g_val, g_counts, g_counts_w, dz_part,
          fl_off, fl_cnt, fl_tok, fl_val, fl_seg, total;
   int kcap;
+  int ecap;
 };
 
 thread_local char g_err[256] = "";
@@ -173,6 +174,10 @@ Plan make_plan(const clt_config* c) {
   p.fl_tok = o;     o += align_up(L * B * (size_t)p.kcap * 4);
   p.fl_val = o;     o += align_up(L * B * (size_t)p.kcap * 4);
   p.fl_seg = o;     o += align_up(gathers * FL_SEGS * L * F * 4);
+  // partial dot products of the fused dz: (pair, column slice, entry), entries per layer capped (longer lists take
+  // the separate gather kernel)
+  p.ecap = (int)(B * (size_t)std::min(p.kcap, FUSED_DZ_ENTRIES_PER_TOKEN));
+  p.dz_part = o;    o += align_up((L * (L + 1) / 2) * 8 * (size_t)p.ecap * 4);
   p.total = o;
   return p;
 }
@@ -612,11 +617,19 @@ static int backward_impl(clt_handle* h, hipStream_t s, const void* x, const floa
                  reinterpret_cast<int32_t*>(h->ws + h->plan.g_counts_w), kcap, list_stride(kcap)};
   FeatureLists fl{reinterpret_cast<int32_t*>(h->ws + h->plan.fl_off), reinterpret_cast<int32_t*>(h->ws + h->plan.fl_cnt),
                   reinterpret_cast<int32_t*>(h->ws + h->plan.fl_tok), reinterpret_cast<float*>(h->ws + h->plan.fl_val),
-                  reinterpret_cast<int32_t*>(h->ws + h->plan.fl_seg), kcap};
+                  reinterpret_cast<int32_t*>(h->ws + h->plan.fl_seg), kcap,
+                  sparse_dwdec_takes_dz(D) && h->plan.ecap ? reinterpret_cast<float*>(h->ws + h->plan.dz_part) : nullptr,
+                  h->plan.ecap};
   if (mode != CLT_DECODE_DENSE) {
+    // The row kernel of dW_dec runs before the rest of the backward: when the lists are short enough it also takes
+    // the dot products that make up dz at the listed entries, and the separate gather kernel stands down.  (It
+    // updates W_dec in place when Adam is fused: nothing after it reads the decoder.)
     RUN(h, s, K_SP_FILL, launch_sparse_dpre_fill(s, h->bf16, D, act_class, norms, lam1_over_b, dpre, flags, kcap));
+    RUN(h, s, K_FLISTS, launch_feature_lists(s, h->bf16, D, act_class, z, fl, flags));
     RUN(h, s, K_GATHER_DZ, launch_gather_dz(s, h->bf16, D, gl, d_yhat, W_dec, norms, lam_c_over_b, h->cfg.C, dpre,
-                                            flags));
+                                            flags, &fl));
+    RUN(h, s, K_SP_DWDEC, launch_sparse_dwdec(s, h->bf16, D, fl, wa, flags));
+    RUN(h, s, K_GATHER_DZ, launch_dz_from_partials(s, h->bf16, D, fl, norms, lam_c_over_b, h->cfg.C, dpre, flags));
   }
   if (mode != CLT_DECODE_GATHER) {
     if (h->bf16) RUN(h, s, K_DZ, launch_dz_bf16(s, D, za)); else RUN(h, s, K_DZ, launch_dz_f32(s, D, za));
@@ -632,10 +645,6 @@ static int backward_impl(clt_handle* h, hipStream_t s, const void* x, const floa
   RUN(h, s, K_COLRED, launch_col_reduce(s, part2, nparts, D.L * D.F, 1.0f, nullptr, 0.f, gb_enc));
   if (h->bf16) RUN(h, s, K_DWENC, launch_dwenc_bf16(s, D, ea, h->int8));
   else RUN(h, s, K_DWENC, launch_dwenc_f32(s, D, ea));
-  if (mode != CLT_DECODE_DENSE) {
-    RUN(h, s, K_FLISTS, launch_feature_lists(s, h->bf16, D, act_class, z, fl, flags));
-    RUN(h, s, K_SP_DWDEC, launch_sparse_dwdec(s, h->bf16, D, fl, wa, flags));
-  }
   if (mode != CLT_DECODE_GATHER) {
     if (h->bf16) RUN(h, s, K_DWDEC, launch_dwdec_bf16(s, D, wa)); else RUN(h, s, K_DWDEC, launch_dwdec_f32(s, D, wa));
   }

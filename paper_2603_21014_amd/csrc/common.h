@@ -293,16 +293,30 @@ hipError_t launch_gather_decode(hipStream_t s, bool bf16, Dims D, GatherLists g,
 // dpre := 0, or the dead-feature gradient -(lambda1/B) n where pre < theta and the entry is not listed
 hipError_t launch_sparse_dpre_fill(hipStream_t s, bool bf16, Dims D, const uint8_t* cls, const float* norms,
                                    float lam1_over_b, void* dpre, const int32_t* flags, int kcap);
-// dz at the listed entries only: sum_{lp>=l} <d_yhat[lp,b,:], W_dec[p(l,lp)][f,:]> + sparsity gradient -> dpre[l,b,f]
 hipError_t init_gather();   // once per process, after the device is chosen
-hipError_t launch_gather_dz(hipStream_t s, bool bf16, Dims D, GatherLists g, const void* d_yhat, const void* W_dec,
-                            const float* norms, float lam_c_over_b, float C, void* dpre, const int32_t* flags);
-// Per (layer, feature): tokens on which the feature is active, ascending, with z (transpose of the row lists).
+// Per (layer, feature): tokens on which the feature is active or inside the threshold window, ascending, with z
+// (0 for the window-only ones; transpose of the row lists).
 // Layer l's entries start at l * B * kcap; off is layer-local.  seg holds FL_SEGS x L*F partial counts.
 constexpr int FL_SEGS = 16;
-struct FeatureLists { int32_t* off; int32_t* cnt; int32_t* tok; float* val; int32_t* seg; int kcap; };
+// dz_part / ecap: room for the partial dot products of the fused dz (see fused_dz_selected), P x 8 x ecap floats.
+struct FeatureLists { int32_t* off; int32_t* cnt; int32_t* tok; float* val; int32_t* seg; int kcap; float* dz_part; int ecap; };
+// flags[3] = longest per-layer total of the feature lists (raised by launch_feature_lists, cleared by
+// launch_decode_decide).  While it fits ecap, the row kernel of dW_dec also takes the dot products d y_hat . W_dec of
+// its (entry, target, column slice) and launch_dz_from_partials sums them into d pre; launch_gather_dz stands down.
+__host__ __device__ inline bool fused_dz_selected(const int32_t* flags, const FeatureLists& fl) {
+  return fl.dz_part != nullptr && gather_selected(flags, fl.kcap) && flags[3] <= fl.ecap;
+}
+constexpr int FUSED_DZ_ENTRIES_PER_TOKEN = 128;      // ecap = B * min(kcap, this)
+bool sparse_dwdec_takes_dz(Dims D);                  // whether launch_sparse_dwdec will use the kernel that can (else: dz_part = NULL)
+// dz at the listed entries only: sum_{lp>=l} <d_yhat[lp,b,:], W_dec[p(l,lp)][f,:]> + sparsity gradient -> dpre[l,b,f]
+hipError_t launch_gather_dz(hipStream_t s, bool bf16, Dims D, GatherLists g, const void* d_yhat, const void* W_dec,
+                            const float* norms, float lam_c_over_b, float C, void* dpre, const int32_t* flags,
+                            const FeatureLists* fused);      // fused: stands down when fused_dz_selected(flags, *fused)
 hipError_t launch_feature_lists(hipStream_t s, bool bf16, Dims D, const uint8_t* cls, const void* z, FeatureLists fl,
-                                const int32_t* flags);
+                                int32_t* flags);
+// d pre at the listed entries from the partial dot products the row kernel of dW_dec left (fused_dz_selected only)
+hipError_t launch_dz_from_partials(hipStream_t s, bool bf16, Dims D, FeatureLists fl, const float* norms,
+                                   float lam_c_over_b, float C, void* dpre, const int32_t* flags);
 // dW_dec[p(l,lp)][f,:] = sum_{b in list(l,f)} z[l,b,f] d_yhat[lp,b,:] + (G/n)[l,f] W_dec[p][f,:], with the optional
 // fused Adam update of the row (every row is visited: Adam also moves rows without gradient)
 // (a.n2_part, bf16 with the fused update and d a multiple of 64: the row kernel leaves the same sums of squares of the

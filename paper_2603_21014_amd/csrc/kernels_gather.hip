@@ -40,6 +40,7 @@ __global__ void decode_decide_kernel(Dims D, const int32_t* __restrict__ l0, flo
   flags[0] = (forced || dens <= (double)thr) ? 1 : 0;
   flags[1] = 0;
   flags[2] = 1;
+  flags[3] = 0;
 }
 
 // One wavefront per (layer, token) row; lanes take 16 consecutive features per pass (two 8-byte
@@ -275,8 +276,8 @@ template <typename T>
 __global__ __launch_bounds__(256) void gather_dz_kernel(Dims D, GatherLists g, const T* __restrict__ d_yhat,
                                                         const T* __restrict__ W_dec, const float* __restrict__ norms,
                                                         float lam_c_over_b, float C, T* __restrict__ dpre,
-                                                        const int32_t* __restrict__ flags) {
-  if (!gather_selected(flags, g.kcap)) return;
+                                                        const int32_t* __restrict__ flags, FeatureLists fused) {
+  if (!gather_selected(flags, g.kcap) || fused_dz_selected(flags, fused)) return;
   const int lane = threadIdx.x & 63, wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const long items = ((long)D.L * D.B + 7) / 8 * 8 * GDZ_PARTS;
   for (long it = blockIdx.x; it < items; it += gridDim.x) {      // layer 0 (most targets) first
@@ -356,10 +357,11 @@ __global__ __launch_bounds__(1024, 2) void gather_dz_lds_kernel(Dims D, GatherLi
                                                                 const T* __restrict__ W_dec,
                                                                 const float* __restrict__ norms, float lam_c_over_b,
                                                                 float C, T* __restrict__ dpre,
-                                                                const int32_t* __restrict__ flags, int tcap) {
+                                                                const int32_t* __restrict__ flags, int tcap,
+                                                                FeatureLists fused) {
   extern __shared__ __align__(16) unsigned char gdz_smem[];
   T* dys = reinterpret_cast<T*>(gdz_smem);      // [tcap][d]
-  if (!gather_selected(flags, g.kcap)) return;
+  if (!gather_selected(flags, g.kcap) || fused_dz_selected(flags, fused)) return;
   const int tid = threadIdx.x, lane = tid & 63, wv = __builtin_amdgcn_readfirstlane(tid >> 6);
   constexpr int PIECE = 16 / (int)sizeof(T);      // elements per 16-byte piece
   const int ppr = D.d / PIECE;                    // pieces per row
@@ -452,8 +454,9 @@ __global__ __launch_bounds__(256) void fl_count_kernel(Dims D, const uint8_t* __
   int c[4] = {0, 0, 0, 0};
   for (int b = b0; b < b1; ++b) {
     const uint32_t a4 = *reinterpret_cast<const uint32_t*>(cls + ((size_t)l * D.B + b) * D.F + f);
+    const uint32_t listed = (a4 | (a4 >> 1)) & 0x01010101u;      // active, or inside the threshold window
 #pragma unroll
-    for (int i = 0; i < 4; ++i) c[i] += (int)((a4 >> (8 * i)) & 1u);
+    for (int i = 0; i < 4; ++i) c[i] += (int)((listed >> (8 * i)) & 1u);
   }
   int32_t* o = fl.seg + (size_t)sgm * D.L * D.F + (size_t)q * 4;
   o[0] = c[0]; o[1] = c[1]; o[2] = c[2]; o[3] = c[3];
@@ -464,7 +467,7 @@ __global__ __launch_bounds__(256) void fl_count_kernel(Dims D, const uint8_t* __
 // run of consecutive features (8 at F = 8192, so neighbouring lanes share cache lines).
 constexpr int FL_SCAN_THREADS = 1024;
 __global__ __launch_bounds__(FL_SCAN_THREADS) void fl_scan_kernel(Dims D, FeatureLists fl,
-                                                                  const int32_t* __restrict__ flags) {
+                                                                  int32_t* __restrict__ flags) {
   if (!gather_selected(flags, fl.kcap)) return;
   __shared__ int tot[FL_SCAN_THREADS];
   const int l = blockIdx.x, tid = threadIdx.x;
@@ -485,6 +488,7 @@ __global__ __launch_bounds__(FL_SCAN_THREADS) void fl_scan_kernel(Dims D, Featur
     tot[tid] += v;
     __syncthreads();
   }
+  if (tid == FL_SCAN_THREADS - 1) atomicMax(&flags[3], tot[tid]);      // the longest layer decides whether the fused dz has room
   int run = tot[tid] - sum;
   for (int f = f0; f < f1; ++f) {
     const size_t lf = (size_t)l * D.F + f;
@@ -515,7 +519,8 @@ __global__ __launch_bounds__(256) void fl_fill_kernel(Dims D, const uint8_t* __r
   const size_t base = (size_t)l * D.B * fl.kcap;        // layer l's region of the lists
   for (int b = b0; b < b1; ++b) {
     const size_t o = ((size_t)l * D.B + b) * D.F + f;
-    const uint32_t a4 = *reinterpret_cast<const uint32_t*>(cls + o) & 0x01010101u;
+    const uint32_t c4 = *reinterpret_cast<const uint32_t*>(cls + o);
+    const uint32_t a4 = (c4 | (c4 >> 1)) & 0x01010101u;      // as counted: active or in the window (z = 0 there)
     if (!a4) continue;
     const float4 z4 = Elem<T>::load4(z + o);
     const float zz[4] = {z4.x, z4.y, z4.z, z4.w};
@@ -730,6 +735,21 @@ __global__ __launch_bounds__(256, 4) void sparse_dwdec_kernel(Dims D, FeatureLis
   }
 }
 
+// Sums of four values over the wave at once: on return the lanes with lane % 4 == u hold the sum of the u-th value.
+// Two exchange steps inside quads halve the values each lane carries, two rotations finish the rows of 16 lanes,
+// two shuffles the four rows.
+__device__ __forceinline__ float wave_sum4(float a, float b, float c, float d, int lane) {
+  const bool o1 = lane & 1, o2 = lane & 2;
+  const float r1 = (o1 ? b : a) + dpp_move<0xB1>(o1 ? a : b);      // even lanes: a of the pair, odd lanes: b
+  const float r2 = (o1 ? d : c) + dpp_move<0xB1>(o1 ? c : d);
+  float r = (o2 ? r2 : r1) + dpp_move<0x4E>(o2 ? r1 : r2);         // lane % 4 = 0, 1, 2, 3: a, b, c, d of the quad
+  r += dpp_move<0x128>(r);                                          // row_ror:8
+  r += dpp_move<0x124>(r);                                          // row_ror:4
+  r += __shfl_xor(r, 16, 64);
+  r += __shfl_xor(r, 32, 64);
+  return r;
+}
+
 // The same rows cut into eight column slices, one per XCD (workgroups go round-robin to the XCDs, so blockIdx & 7
 // names the slice): an XCD's L2 then only ever sees its d/8 columns of d y_hat, and with the (source, target) pairs
 // walked target-major that is B * d/8 elements at a time (2 MB at L=16 d=2048 B=4096), so the gathered d y_hat rows
@@ -751,6 +771,7 @@ __global__ __launch_bounds__(256, 8) void sparse_dwdec_sliced_kernel(Dims D, Fea
   const int passes = (q4 + 63) / 64;
   const int F4 = (D.F + 3) / 4;
   const long items = (long)(D.L * (D.L + 1) / 2) * F4;
+  const bool dz_on = fused_dz_selected(flags, fl);
   struct Meta { int l, lp, f, cnt, off; float Gf, nf; };
   // (one item per workgroup as long as the grid allows it: handed out in order by the dispatcher, the workgroups in
   //  flight stay within a narrow window of items, which is what keeps their d y_hat rows in the L2)
@@ -771,6 +792,7 @@ __global__ __launch_bounds__(256, 8) void sparse_dwdec_sliced_kernel(Dims D, Fea
       const float coef = cur.Gf * __builtin_amdgcn_rcpf(fmaxf(cur.nf, 1e-30f));
       const size_t o = ((size_t)packed_index(cur.l, cur.lp, D.L) * D.F + cur.f) * D.d;
       const T* dyt = d_yhat + (size_t)cur.lp * D.B * D.d;
+      float* dz_out = dz_on ? fl.dz_part + ((size_t)packed_index(cur.l, cur.lp, D.L) * 8 + slice) * fl.ecap + cur.off : nullptr;
       for (int ps = 0; ps < passes; ++ps) {
         const int qd = ps * 64 + lane;
         const bool on = qd < q4;
@@ -784,10 +806,28 @@ __global__ __launch_bounds__(256, 8) void sparse_dwdec_sliced_kernel(Dims D, Fea
           if (MASTER) p4 = nt_load_v4(lane_ptr(fuse.master + o, col));
         }
         float acc[4] = {0.f, 0.f, 0.f, 0.f};
+        // Fused dz: the token's d y_hat columns are in registers anyway, so their dot product with the row's weights
+        // (before the update) costs four multiply-adds per lane and, for four tokens at a time, one sum over the
+        // wave; lane t % 64 keeps token t's sum and the wave stores 64 of them at a time, one slot per
+        // (pair, slice, entry).
+        float dz_keep = 0.f;
+        const float4 wl = Elem<T>::widen4(wr);
+        const float4 wz = on ? wl : make_float4(0.f, 0.f, 0.f, 0.f);
+        auto dz_group = [&](int j0, int nval, const float (&pd)[4]) {      // tokens j0 .. j0 + nval - 1, j0 % 4 == 0
+          const float r = wave_sum4(pd[0], pd[1], pd[2], pd[3], lane);
+          if ((lane & 60) == (j0 & 63)) dz_keep = r;
+          const int last = j0 + nval - 1;
+          if ((last & 63) == 63 || last == cur.cnt - 1) {
+            if (lane <= (last & 63)) {
+              float* slot = dz_out + (last & ~63) + lane;
+              *slot = ps == 0 ? dz_keep : *slot + dz_keep;      // (a slice wider than 256 columns: one pass after the other)
+            }
+          }
+        };
         int j = 0;
         for (; j + 4 <= cur.cnt; j += 4) {
           typename Elem<T>::Raw4 r[4];
-          float zv[4];
+          float zv[4], pd[4];
 #pragma unroll
           for (int u = 0; u < 4; ++u) {
             const int b = __builtin_amdgcn_readfirstlane(tk[j + u]);
@@ -801,18 +841,28 @@ __global__ __launch_bounds__(256, 8) void sparse_dwdec_sliced_kernel(Dims D, Fea
             acc[1] = fmaf(zv[u], q.y, acc[1]);
             acc[2] = fmaf(zv[u], q.z, acc[2]);
             acc[3] = fmaf(zv[u], q.w, acc[3]);
+            pd[u] = fmaf(wz.x, q.x, fmaf(wz.y, q.y, fmaf(wz.z, q.z, wz.w * q.w)));
           }
+          if (dz_out) dz_group(j, 4, pd);
         }
-        for (; j < cur.cnt; ++j) {
-          const int b = __builtin_amdgcn_readfirstlane(tk[j]);
-          const float zv = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(tv[j])));
-          const float4 q = Elem<T>::widen4(Elem<T>::load_raw4(lane_ptr(dyt + (size_t)b * D.d, col)));
-          acc[0] = fmaf(zv, q.x, acc[0]);
-          acc[1] = fmaf(zv, q.y, acc[1]);
-          acc[2] = fmaf(zv, q.z, acc[2]);
-          acc[3] = fmaf(zv, q.w, acc[3]);
+        if (j < cur.cnt) {
+          const int nval = cur.cnt - j;
+          float pd[4] = {0.f, 0.f, 0.f, 0.f};
+          for (int u = 0; u < nval; ++u) {
+            const int b = __builtin_amdgcn_readfirstlane(tk[j + u]);
+            const float zv = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(tv[j + u])));
+            const float4 q = Elem<T>::widen4(Elem<T>::load_raw4(lane_ptr(dyt + (size_t)b * D.d, col)));
+            acc[0] = fmaf(zv, q.x, acc[0]);
+            acc[1] = fmaf(zv, q.y, acc[1]);
+            acc[2] = fmaf(zv, q.z, acc[2]);
+            acc[3] = fmaf(zv, q.w, acc[3]);
+            const float pu = fmaf(wz.x, q.x, fmaf(wz.y, q.y, fmaf(wz.z, q.z, wz.w * q.w)));
+            pd[0] = u == 0 ? pu : pd[0];
+            pd[1] = u == 1 ? pu : pd[1];
+            pd[2] = u == 2 ? pu : pd[2];
+          }
+          if (dz_out) dz_group(j, nval, pd);
         }
-        const float4 wl = Elem<T>::widen4(wr);
         const float w4[4] = {wl.x, wl.y, wl.z, wl.w};
         float g4[4];
 #pragma unroll
@@ -846,6 +896,36 @@ __global__ __launch_bounds__(256, 8) void sparse_dwdec_sliced_kernel(Dims D, Fea
         }
       }
     }
+  }
+}
+
+// Fused dz, second half: 16 lanes per (layer, feature) sum the partial dot products of each listed entry over the
+// targets and the eight column slices, always in that order, add the gradient of the sparsity term and write d pre.
+template <typename T>
+__global__ __launch_bounds__(256) void dz_from_partials_kernel(Dims D, FeatureLists fl, const float* __restrict__ norms,
+                                                               float lam_c_over_b, float C, T* __restrict__ dpre,
+                                                               const int32_t* __restrict__ flags) {
+  if (!fused_dz_selected(flags, fl)) return;
+  const int sub = threadIdx.x & 15;
+  const long lf = (long)blockIdx.x * 16 + (threadIdx.x >> 4);
+  if (lf >= (long)D.L * D.F) return;
+  const int l = (int)(lf / D.F), f = (int)(lf % D.F);
+  const int cnt = fl.cnt[lf], off = fl.off[lf];
+  const float nn = norms[lf];
+  const int32_t* tk = fl.tok + (size_t)l * D.B * fl.kcap + off;
+  const float* tv = fl.val + (size_t)l * D.B * fl.kcap + off;
+  for (int j = sub; j < cnt; j += 16) {
+    float acc = 0.f;
+    for (int lp = l; lp < D.L; ++lp) {
+      const float* q = fl.dz_part + (size_t)packed_index(l, lp, D.L) * 8 * fl.ecap + off + j;
+#pragma unroll
+      for (int s8 = 0; s8 < 8; ++s8) acc += q[(size_t)s8 * fl.ecap];
+    }
+    const float zv = tv[j];
+    const float ex = __builtin_amdgcn_exp2f(-2.0f * 1.4426950408889634f * C * nn * fabsf(zv));
+    const float sden = 1.0f + ex;
+    const float gsp = 4.0f * lam_c_over_b * nn * ex * __builtin_amdgcn_rcpf(sden * sden);
+    Elem<T>::store(dpre + ((size_t)l * D.B + tk[j]) * D.F + f, acc + gsp);
   }
 }
 
@@ -893,7 +973,10 @@ hipError_t launch_sparse_dpre_fill(hipStream_t s, bool bf16, Dims D, const uint8
 }
 
 hipError_t launch_gather_dz(hipStream_t s, bool bf16, Dims D, GatherLists g, const void* d_yhat, const void* W_dec,
-                            const float* norms, float lam_c_over_b, float C, void* dpre, const int32_t* flags) {
+                            const float* norms, float lam_c_over_b, float C, void* dpre, const int32_t* flags,
+                            const FeatureLists* fused) {
+  FeatureLists fz{};
+  if (fused) fz = *fused;
   const size_t esz = bf16 ? 2 : 4;
   int tcap = (int)(65536 / ((size_t)D.d * esz));      // targets whose d y_hat rows fit 64 KB of LDS
   if (tcap > D.L) tcap = D.L;
@@ -905,10 +988,10 @@ hipError_t launch_gather_dz(hipStream_t s, bool bf16, Dims D, GatherLists g, con
     const size_t lds = (size_t)tcap * D.d * esz;
     if (bf16)
       hipLaunchKernelGGL((gather_dz_lds_kernel<bf16_t>), grid, dim3(1024), lds, s, D, g, (const bf16_t*)d_yhat,
-                         (const bf16_t*)W_dec, norms, lam_c_over_b, C, (bf16_t*)dpre, flags, tcap);
+                         (const bf16_t*)W_dec, norms, lam_c_over_b, C, (bf16_t*)dpre, flags, tcap, fz);
     else
       hipLaunchKernelGGL((gather_dz_lds_kernel<float>), grid, dim3(1024), lds, s, D, g, (const float*)d_yhat,
-                         (const float*)W_dec, norms, lam_c_over_b, C, (float*)dpre, flags, tcap);
+                         (const float*)W_dec, norms, lam_c_over_b, C, (float*)dpre, flags, tcap, fz);
     return hipGetLastError();
   }
   // rows too wide for LDS staging, or not a multiple of 8 columns (or CLT_GDZ_NO_LDS set, for comparison runs)
@@ -916,10 +999,10 @@ hipError_t launch_gather_dz(hipStream_t s, bool bf16, Dims D, GatherLists g, con
   const dim3 grid((unsigned)(items < 256 * 64 ? items : 256 * 64));
   if (bf16)
     hipLaunchKernelGGL((gather_dz_kernel<bf16_t>), grid, dim3(256), 0, s, D, g, (const bf16_t*)d_yhat,
-                       (const bf16_t*)W_dec, norms, lam_c_over_b, C, (bf16_t*)dpre, flags);
+                       (const bf16_t*)W_dec, norms, lam_c_over_b, C, (bf16_t*)dpre, flags, fz);
   else
     hipLaunchKernelGGL((gather_dz_kernel<float>), grid, dim3(256), 0, s, D, g, (const float*)d_yhat,
-                       (const float*)W_dec, norms, lam_c_over_b, C, (float*)dpre, flags);
+                       (const float*)W_dec, norms, lam_c_over_b, C, (float*)dpre, flags, fz);
   return hipGetLastError();
 }
 hipError_t init_gather() {
@@ -931,7 +1014,7 @@ hipError_t init_gather() {
 }
 
 hipError_t launch_feature_lists(hipStream_t s, bool bf16, Dims D, const uint8_t* cls, const void* z, FeatureLists fl,
-                                const int32_t* flags) {
+                                int32_t* flags) {
   const int LF4 = D.L * D.F / 4;
   const dim3 grid((LF4 + 255) / 256, FL_SEGS);
   hipLaunchKernelGGL(fl_count_kernel, grid, dim3(256), 0, s, D, cls, fl, flags);
@@ -940,6 +1023,21 @@ hipError_t launch_feature_lists(hipStream_t s, bool bf16, Dims D, const uint8_t*
     hipLaunchKernelGGL((fl_fill_kernel<bf16_t>), grid, dim3(256), 0, s, D, cls, (const bf16_t*)z, fl, flags);
   else
     hipLaunchKernelGGL((fl_fill_kernel<float>), grid, dim3(256), 0, s, D, cls, (const float*)z, fl, flags);
+  return hipGetLastError();
+}
+
+bool sparse_dwdec_takes_dz(Dims D) { return D.d % 32 == 0 && !getenv("CLT_SD_ROWS") && !getenv("CLT_NO_FUSED_DZ"); }
+
+hipError_t launch_dz_from_partials(hipStream_t s, bool bf16, Dims D, FeatureLists fl, const float* norms,
+                                   float lam_c_over_b, float C, void* dpre, const int32_t* flags) {
+  if (!fl.dz_part) return hipSuccess;
+  const dim3 grid((unsigned)(((size_t)D.L * D.F + 15) / 16));
+  if (bf16)
+    hipLaunchKernelGGL((dz_from_partials_kernel<bf16_t>), grid, dim3(256), 0, s, D, fl, norms, lam_c_over_b, C,
+                       (bf16_t*)dpre, flags);
+  else
+    hipLaunchKernelGGL((dz_from_partials_kernel<float>), grid, dim3(256), 0, s, D, fl, norms, lam_c_over_b, C,
+                       (float*)dpre, flags);
   return hipGetLastError();
 }
 

@@ -559,6 +559,7 @@ def test_sparse_backward_column_slices_match_whole_rows(monkeypatch, dtype, d):
     theta = sparse_theta(w, 0.06)
     params = S.make_params(w)
     x, y = S.make_inputs(w)
+    monkeypatch.setenv("CLT_NO_FUSED_DZ", "1")       # (dz from the separate gather kernel both times)
     for fused in (False, True):
         monkeypatch.delenv("CLT_SD_ROWS", raising=False)
         a = GpuRun(w, params, x, y, theta=theta, decode_mode=GATHER, fused=fused)
@@ -570,6 +571,39 @@ def test_sparse_backward_column_slices_match_whole_rows(monkeypatch, dtype, d):
         for k in O.PARAM_NAMES:
             assert (a.new_params[k] == b.new_params[k]).all(), k
             assert (a.new_m[k] == b.new_m[k]).all() and (a.new_v[k] == b.new_v[k]).all(), k
+
+
+@pytest.mark.parametrize("dtype,d,rho", [("bf16", 256, 0.05), ("f32", 96, 0.05), ("bf16", 2304, 0.05), ("f32", 64, 0.6)])
+def test_dz_taken_inside_the_row_kernel_of_dw_dec(monkeypatch, dtype, d, rho):
+    """With lists of at most 128 entries per token the row kernel of dW_dec also takes the dot products that make up
+    dz at the listed entries (per target and column slice, summed by a second kernel) and the separate gather kernel
+    stands down; CLT_NO_FUSED_DZ switches that off.  Both ways against each other (same products, other summation
+    order) and against the oracle; rho = 0.6 makes lists longer than the room for partial sums, so the separate
+    kernel runs either way and the results are identical."""
+    w = S.scaled(S.WORKLOADS["tiny"], dtype=dtype, L=4, d=d, F=264, B=90, seed=86, master_weights=dtype == "bf16")
+    theta = sparse_theta(w, rho)
+    params = S.make_params(w)
+    x, y = S.make_inputs(w)
+    for fused in (False, True):
+        monkeypatch.delenv("CLT_NO_FUSED_DZ", raising=False)
+        a = GpuRun(w, params, x, y, theta=theta, decode_mode=GATHER, fused=fused)
+        monkeypatch.setenv("CLT_NO_FUSED_DZ", "1")
+        b = GpuRun(w, params, x, y, theta=theta, decode_mode=GATHER, fused=fused)
+        monkeypatch.delenv("CLT_NO_FUSED_DZ", raising=False)
+        assert a.decode_switch[2] == 2 and a.window.sum() > 0
+        longest = int(a.decode_switch[3])
+        assert longest == int((a.active | a.window).sum(axis=(1, 2)).max())
+        took_dz = longest <= w.B * 128
+        assert took_dz == (rho < 0.5)
+        tol = 1e-5 if dtype == "f32" else 1e-2
+        assert rel_l2(a.dpre, b.dpre) < tol
+        if not took_dz:
+            assert (a.dpre == b.dpre).all()
+        if not fused:
+            for k in O.PARAM_NAMES:
+                assert rel_l2(a.grads[k], b.grads[k]) < tol, k
+    o = OracleRun(w, params, x, y, theta=theta, gpu_active=a.active, gpu_window=a.window)
+    show(f"fused dz {dtype} d={d} rho={rho}", compare_step(w, a, o, TOL[dtype]))
 
 
 def test_sparse_backward_many_layers():
