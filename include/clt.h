@@ -36,6 +36,13 @@
  * passed as void*; NULL = the default stream) and the functions do not
  * synchronise, except clt_loss when asked for a host copy of the loss.
  * Calls on one handle must not overlap (they share its workspace).
+ *
+ * Environment switches, read at every call, for comparison runs and tests only
+ * (each selects the slower of two kernels that compute the same thing):
+ *   CLT_NO_XCD_PACING  the decode GEMM without the per-XCD pacing of its K segments
+ *   CLT_GDZ_NO_LDS     list-driven dz: one wave per entry instead of d y_hat rows staged in LDS
+ *   CLT_SD_ROWS        list-driven dW_dec: whole rows per workgroup instead of eight column slices
+ *   CLT_NO_FUSED_DZ    list-driven dz as a kernel of its own even where the dW_dec kernel could take it
  */
 #ifndef CLT_H_
 #define CLT_H_
