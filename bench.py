@@ -223,8 +223,13 @@ def density_sweep(args, log):
                                  ste_bandwidth=w.ste_eps, device=dev, keep_pre=False, decode_mode=mode,
                                  matrix_grads=False)
                  for name, mode in (("dense", K.DECODE_DENSE), ("gather", K.DECODE_GATHER))}
+        # dense forward decode, list-driven backward: the automatic mode with the first threshold at 0, the second at 1
+        steps["hybrid"] = K.CLTStep(w.L, w.d, w.F, w.B, dtype="bf16", int8_inputs=True, C_=w.C,
+                                    ste_bandwidth=w.ste_eps, device=dev, keep_pre=False, decode_mode=K.DECODE_AUTO,
+                                    gather_density_threshold=0.0, list_backward_density_threshold=1.0,
+                                    matrix_grads=False)
         t = 0
-        for rho in (0.00025, 0.0005, 0.001, 0.0025, 0.005, 0.01, 0.05):
+        for rho in (0.00025, 0.0005, 0.001, 0.0025, 0.005, 0.01, 0.015, 0.02, 0.05):
             theta = theta_for_density(xdq, p32["W_enc"], p32["b_enc"], rho)
             row = {"density": rho}
             for name, st in steps.items():
@@ -240,6 +245,9 @@ def density_sweep(args, log):
                 K.clt_profile_enable(st.H, False)
                 ms = {k: v[0] / 2.0 for k, v in prof.items()}    # two profiled steps
                 row[name + "_step_ms"] = round(sum(ms.values()), 2)
+                if name == "hybrid":      # (lists too long for the fused dz: the automatic mode goes back to the dense kernels)
+                    row["hybrid_backward_on_lists"] = bool(int(K.clt_workspace_view(st.H, "decode_switch")[0].item()) & 2)
+                    continue
                 if name == "dense":
                     row["dense_decode_ms"] = round(ms["decode_gemm"], 3)
                     row["dense_dz_ms"] = round(ms["dz_gemm"], 3)
@@ -327,9 +335,12 @@ def main():
                     help="skip the vendor-library GEMM reference measured after the timed region")
     ap.add_argument("--decode-mode", default="dense", choices=["dense", "gather", "auto"],
                     help="dense GEMMs (default), the list-driven kernels of the sparse regime, or the device-side switch")
-    ap.add_argument("--gather-density-threshold", type=float, default=0.007,
-                    help="auto mode: use the list-driven kernels at or below this mean active fraction (the measured "
-                         "whole-step break-even on an MI355X is 0.008)")
+    ap.add_argument("--gather-density-threshold", type=float, default=0.004,
+                    help="auto mode: the forward decode gathers at or below this mean active fraction (measured "
+                         "break-even on an MI355X: 0.003-0.0045)")
+    ap.add_argument("--list-backward-density-threshold", type=float, default=0.012,
+                    help="auto mode: the backward through the decoder runs on the active-feature lists at or below "
+                         "this mean active fraction (measured break-even: about 0.014)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-timing", action="store_true",
                     help="skip the per-kernel HIP-event brackets (roofline entry becomes null)")
@@ -381,7 +392,8 @@ def main():
                      C_=w.C, ste_bandwidth=w.ste_eps, device=dev, keep_pre=w.lambda1 > 0,
                      log_threshold=w.log_threshold, topk=w.topk or None,
                      decode_mode={"dense": K.DECODE_DENSE, "gather": K.DECODE_GATHER, "auto": K.DECODE_AUTO}[args.decode_mode],
-                     gather_density_threshold=args.gather_density_threshold, matrix_grads=False,
+                     gather_density_threshold=args.gather_density_threshold,
+                     list_backward_density_threshold=args.list_backward_density_threshold, matrix_grads=False,
                      reuse_decoder_norms=True)
     torch.cuda.synchronize()
     log(f"workload {w.name}: L={w.L} d={w.d} F={w.F} B={w.B}, inputs ready in {time.perf_counter() - t0:.1f}s, "

@@ -102,13 +102,23 @@ typedef struct clt_config {
                              that is given the same W_dec pointer forms the norms from them.  The
                              caller promises that nothing else writes W_dec between those two calls.
                              Whenever the sums are not there, clt_forward reads W_dec as with 0.      */
-  float gather_density_threshold; /* AUTO: gather when the mean active fraction of the batch
-                             is <= this and no (layer, token) row has more than about 8x
-                             as many active features (else the step decodes densely).
-                             On an MI355X the whole step breaks even near 0.008 (about 70
-                             active of 8192 features), whatever the expansion factor: the
-                             dense cost grows with F, the list-driven one with the active
-                             count; the binding's default is 0.007.                         */
+  float gather_density_threshold; /* AUTO: the forward decode gathers when the mean active
+                             fraction of the batch is <= this and no (layer, token) row has
+                             more than about 8x the larger of the two thresholds in listed
+                             features (else the step decodes densely).  On an MI355X the
+                             gather decode breaks even with the dense one near 0.003-0.0045
+                             (24-38 active of 8192 features; binding default 0.004).     */
+  float list_backward_density_threshold; /* AUTO: the backward through the decoder (dz, dW_dec
+                             and its Adam update) runs on the active-feature lists when the
+                             mean active fraction is <= this (same row limit); 0 = the same
+                             as gather_density_threshold.  The list-driven backward pays up
+                             to a higher density than the gather decode: it breaks even
+                             near 0.015 (about 125 of 8192), whatever the expansion factor
+                             (the dense cost grows with F, the list-driven one with the
+                             active count); binding default 0.012.  The workspace holds room
+                             for the partial sums of dz sized from this threshold (at most
+                             320 listed entries per token and layer); a step whose lists are
+                             longer goes backward through the dense kernels.                */
   float C;                /* sparsity scale C of the App. B objective                     */
   float ste_bandwidth;    /* width eps of the rectangle kernel of the threshold gradient */
   float beta1, beta2, adam_eps; /* Adam (App. C Table 1: 0.9, 0.999)                     */

@@ -39,7 +39,8 @@ class clt_config(C.Structure):
                 ("dtype", C.c_int32), ("input_format", C.c_int32), ("master_weights", C.c_int32),
                 ("decode_mode", C.c_int32), ("log_threshold", C.c_int32), ("activation", C.c_int32), ("topk_k", C.c_int32),
                 ("reuse_decoder_norms", C.c_int32),
-                ("gather_density_threshold", C.c_float), ("C", C.c_float),
+                ("gather_density_threshold", C.c_float), ("list_backward_density_threshold", C.c_float),
+                ("C", C.c_float),
                 ("ste_bandwidth", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float), ("adam_eps", C.c_float)]
 
 
@@ -106,13 +107,16 @@ def _ptr(t, shape, dtype, name, optional=False):
 
 
 def make_config(L, d, F, B, dtype=DTYPE_BF16, input_format=INPUT_NATIVE, master_weights=False,
-                decode_mode=DECODE_DENSE, gather_density_threshold=0.007, C_=4.0, ste_bandwidth=0.05,
-                beta1=0.9, beta2=0.999, adam_eps=1e-8, log_threshold=False, topk=None, reuse_decoder_norms=False):
+                decode_mode=DECODE_DENSE, gather_density_threshold=0.004, C_=4.0, ste_bandwidth=0.05,
+                beta1=0.9, beta2=0.999, adam_eps=1e-8, log_threshold=False, topk=None, reuse_decoder_norms=False,
+                list_backward_density_threshold=0.0):
     """topk: None for JumpReLU, else k of the TopK activation.  reuse_decoder_norms: see include/clt.h (the caller
-    promises that only clt_backward_adam_step writes W_dec between steps)."""
+    promises that only clt_backward_adam_step writes W_dec between steps).  list_backward_density_threshold: AUTO
+    mode's second threshold, for the backward through the decoder (0 = the same as gather_density_threshold)."""
     return clt_config(C.sizeof(clt_config), L, d, F, B, dtype, input_format, int(master_weights), decode_mode,
                       int(log_threshold), 0 if topk is None else 1, 0 if topk is None else int(topk),
-                      int(reuse_decoder_norms), gather_density_threshold, C_, ste_bandwidth, beta1, beta2, adam_eps)
+                      int(reuse_decoder_norms), gather_density_threshold, list_backward_density_threshold, C_, ste_bandwidth,
+                      beta1, beta2, adam_eps)
 
 
 def clt_workspace_bytes(cfg: clt_config) -> int:
@@ -320,14 +324,15 @@ class CLTStep:
 
     def __init__(self, L, d, F, B, dtype="bf16", int8_inputs=False, master_weights=False, C_=4.0,
                  ste_bandwidth=0.05, beta1=0.9, beta2=0.999, adam_eps=1e-8, device="cuda:0", keep_pre=True,
-                 decode_mode=DECODE_DENSE, gather_density_threshold=0.007, matrix_grads=True, log_threshold=False,
-                 topk=None, workspace=None, reuse_decoder_norms=False):
+                 decode_mode=DECODE_DENSE, gather_density_threshold=0.004, matrix_grads=True, log_threshold=False,
+                 topk=None, workspace=None, reuse_decoder_norms=False, list_backward_density_threshold=0.012):
         """workspace: a uint8 device tensor of at least clt_workspace_bytes(config) bytes that the caller
         owns (256-byte aligned); by default one is allocated here."""
         dt = DTYPE_BF16 if dtype == "bf16" else DTYPE_F32
         self.cfg = make_config(L, d, F, B, dt, INPUT_INT8_ROWSCALE if int8_inputs else INPUT_NATIVE,
                                master_weights, decode_mode, gather_density_threshold, C_, ste_bandwidth, beta1,
-                               beta2, adam_eps, log_threshold, topk, reuse_decoder_norms)
+                               beta2, adam_eps, log_threshold, topk, reuse_decoder_norms,
+                               list_backward_density_threshold)
         self.device = torch.device(device)
         ws = workspace
         if ws is None:

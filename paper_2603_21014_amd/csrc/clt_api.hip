@@ -117,12 +117,22 @@ int check_config(const clt_config* c, char* err) {
     set_err(err, "gather_density_threshold must be in [0, 1]");
     return CLT_ERR_INVALID_ARG;
   }
+  if (c->decode_mode == CLT_DECODE_AUTO &&
+      !(c->list_backward_density_threshold >= 0.f && c->list_backward_density_threshold <= 1.f)) {
+    set_err(err, "list_backward_density_threshold must be in [0, 1]");
+    return CLT_ERR_INVALID_ARG;
+  }
   if (!(c->C > 0.f) || !(c->ste_bandwidth > 0.f) || !(c->beta1 >= 0.f && c->beta1 < 1.f) ||
       !(c->beta2 >= 0.f && c->beta2 < 1.f) || !(c->adam_eps > 0.f)) {
     set_err(err, "bad scalar: need C>0, ste_bandwidth>0, 0<=beta<1, adam_eps>0");
     return CLT_ERR_INVALID_ARG;
   }
   return CLT_OK;
+}
+
+// AUTO: the density up to which the backward through the decoder takes the lists (0 = as the forward decode)
+float backward_threshold(const clt_config* c) {
+  return c->list_backward_density_threshold > 0.f ? c->list_backward_density_threshold : c->gather_density_threshold;
 }
 
 Plan make_plan(const clt_config* c) {
@@ -158,7 +168,7 @@ Plan make_plan(const clt_config* c) {
   p.kcap = 0;
   if (c->decode_mode == CLT_DECODE_GATHER) p.kcap = c->F;
   if (c->decode_mode == CLT_DECODE_AUTO) {
-    size_t k = (size_t)(8.0 * c->gather_density_threshold * F) + 64;
+    size_t k = (size_t)(8.0 * std::max(c->gather_density_threshold, backward_threshold(c)) * F) + 64;
     k = (k + 7) / 8 * 8;
     p.kcap = (int)(k < F ? k : F);
   }
@@ -176,7 +186,10 @@ Plan make_plan(const clt_config* c) {
   p.fl_seg = o;     o += align_up(gathers * FL_SEGS * L * F * 4);
   // partial dot products of the fused dz: (pair, column slice, entry), entries per layer capped (longer lists take
   // the separate gather kernel)
-  p.ecap = (int)(B * (size_t)std::min(p.kcap, FUSED_DZ_ENTRIES_PER_TOKEN));
+  int per_token = FUSED_DZ_ENTRIES_PER_TOKEN;
+  if (c->decode_mode == CLT_DECODE_AUTO)      // what the backward threshold admits, a quarter more for window entries
+    per_token = std::min(FUSED_DZ_ENTRIES_PER_TOKEN_MAX, (int)(1.25 * backward_threshold(c) * F) + 32);
+  p.ecap = (int)(B * (size_t)std::min(p.kcap, per_token));
   p.dz_part = o;    o += align_up((L * (L + 1) / 2) * 8 * (size_t)p.ecap * 4);
   p.total = o;
   return p;
@@ -516,8 +529,8 @@ int clt_forward(clt_handle* h, void* stream, const void* x, const float* x_scale
   }
   if (topk) RUN(h, s, K_TOPK, launch_topk_select(s, h->bf16, h->D, pre32, h->cfg.topk_k, z, act_class, l0));
   if (mode != CLT_DECODE_DENSE) {   // Sec. 3.2: density monitor, then the gather path where it pays
-    RUN(h, s, K_DECIDE, launch_decode_decide(s, h->D, l0, h->cfg.gather_density_threshold, mode == CLT_DECODE_GATHER,
-                                             flags));
+    RUN(h, s, K_DECIDE, launch_decode_decide(s, h->D, l0, h->cfg.gather_density_threshold, backward_threshold(&h->cfg),
+                                             mode == CLT_DECODE_GATHER, flags));
     RUN(h, s, K_COMPACT, launch_compact_active(s, h->bf16, h->D, z, act_class, gl, flags));
     RUN(h, s, K_GATHER, launch_gather_decode(s, h->bf16, h->D, gl, W_dec, b_dec, y_hat, flags));
   }
@@ -625,7 +638,7 @@ static int backward_impl(clt_handle* h, hipStream_t s, const void* x, const floa
     // the dot products that make up dz at the listed entries, and the separate gather kernel stands down.  (It
     // updates W_dec in place when Adam is fused: nothing after it reads the decoder.)
     RUN(h, s, K_SP_FILL, launch_sparse_dpre_fill(s, h->bf16, D, act_class, norms, lam1_over_b, dpre, flags, kcap));
-    RUN(h, s, K_FLISTS, launch_feature_lists(s, h->bf16, D, act_class, z, fl, flags));
+    RUN(h, s, K_FLISTS, launch_feature_lists(s, h->bf16, D, act_class, z, fl, flags, mode == CLT_DECODE_AUTO));
     RUN(h, s, K_GATHER_DZ, launch_gather_dz(s, h->bf16, D, gl, d_yhat, W_dec, norms, lam_c_over_b, h->cfg.C, dpre,
                                             flags, &fl));
     RUN(h, s, K_SP_DWDEC, launch_sparse_dwdec(s, h->bf16, D, fl, wa, flags));

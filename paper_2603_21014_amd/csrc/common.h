@@ -266,13 +266,20 @@ hipError_t launch_diag_fill(hipStream_t s, void* buf, size_t bytes, int random_d
 
 // ---- active-feature gather paths (kernels_gather.hip) -------------------------
 // Device-side switch, 4 ints in the workspace:
-//   [0] 1 when the measured density allows the gather path (or it is forced)
+//   [0] bit 0: the measured density allows the gather decode (or it is forced); bit 1: it allows the list-driven
+//       backward through the decoder (or it is forced)
 //   [1] longest per-(layer, token) list seen by the compaction (active + window-only entries)
 //   [2] path taken by the last forward: 1 dense, 2 gather
-// The gather kernels run only when flags[0] != 0 and flags[1] <= kcap; the dense kernels that
+//   [3] longest per-layer total of the feature lists (see fused_dz_selected)
+// The list-driven kernels run only when their bit of flags[0] is set and flags[1] <= kcap; the dense kernels that
 // carry the same flags stand down in exactly that case.
 __host__ __device__ inline bool gather_selected(const int32_t* flags, int kcap) {
-  return flags[0] != 0 && flags[1] <= kcap;
+  return (flags[0] & 1) != 0 && flags[1] <= kcap;
+}
+// The backward through the decoder (dz, dW_dec) has a switch of its own, flags[0] bit 1: its list-driven kernels pay
+// up to a higher density than the gather decode does.
+__host__ __device__ inline bool lists_backward_selected(const int32_t* flags, int kcap) {
+  return (flags[0] & 2) != 0 && flags[1] <= kcap;
 }
 // Per (layer, token) row of kcap slots: the active features in ascending order from the front
 // (counts[row] of them, val = z), the inactive features inside the threshold window from the
@@ -281,8 +288,8 @@ __host__ __device__ inline bool gather_selected(const int32_t* flags, int kcap) 
 struct GatherLists { int32_t* idx; float* val; int32_t* counts; int32_t* counts_w; int kcap; int stride; };
 __host__ __device__ inline int list_stride(int kcap) { return kcap + 32; }
 // flags[0] = (sum l0 <= threshold * L*B*F) or forced; flags[1] = 0
-hipError_t launch_decode_decide(hipStream_t s, Dims D, const int32_t* l0, float density_threshold, int forced,
-                                int32_t* flags);
+hipError_t launch_decode_decide(hipStream_t s, Dims D, const int32_t* l0, float density_threshold,
+                                float backward_density_threshold, int forced, int32_t* flags);
 hipError_t launch_compact_active(hipStream_t s, bool bf16, Dims D, const void* z, const uint8_t* cls, GatherLists g,
                                  int32_t* flags);
 // y_hat[lp, b, :] = b_dec[lp] + sum_{l<=lp} sum_{active f} z[l,b,f] W_dec[p(l,lp)][f, :]; records the path in flags[2]
@@ -304,16 +311,19 @@ struct FeatureLists { int32_t* off; int32_t* cnt; int32_t* tok; float* val; int3
 // launch_decode_decide).  While it fits ecap, the row kernel of dW_dec also takes the dot products d y_hat . W_dec of
 // its (entry, target, column slice) and launch_dz_from_partials sums them into d pre; launch_gather_dz stands down.
 __host__ __device__ inline bool fused_dz_selected(const int32_t* flags, const FeatureLists& fl) {
-  return fl.dz_part != nullptr && gather_selected(flags, fl.kcap) && flags[3] <= fl.ecap;
+  return fl.dz_part != nullptr && lists_backward_selected(flags, fl.kcap) && flags[3] <= fl.ecap;
 }
-constexpr int FUSED_DZ_ENTRIES_PER_TOKEN = 128;      // ecap = B * min(kcap, this)
+constexpr int FUSED_DZ_ENTRIES_PER_TOKEN = 128;      // forced gather mode: ecap = B * min(kcap, this)
+constexpr int FUSED_DZ_ENTRIES_PER_TOKEN_MAX = 320;  // automatic mode: sized from the backward threshold, up to this
 bool sparse_dwdec_takes_dz(Dims D);                  // whether launch_sparse_dwdec will use the kernel that can (else: dz_part = NULL)
 // dz at the listed entries only: sum_{lp>=l} <d_yhat[lp,b,:], W_dec[p(l,lp)][f,:]> + sparsity gradient -> dpre[l,b,f]
 hipError_t launch_gather_dz(hipStream_t s, bool bf16, Dims D, GatherLists g, const void* d_yhat, const void* W_dec,
                             const float* norms, float lam_c_over_b, float C, void* dpre, const int32_t* flags,
                             const FeatureLists* fused);      // fused: stands down when fused_dz_selected(flags, *fused)
+// dense_when_too_long (automatic mode): a layer total beyond ecap clears bit 1 of flags[0], which hands the backward
+// through the decoder back to the dense kernels.
 hipError_t launch_feature_lists(hipStream_t s, bool bf16, Dims D, const uint8_t* cls, const void* z, FeatureLists fl,
-                                int32_t* flags);
+                                int32_t* flags, bool dense_when_too_long);
 // d pre at the listed entries from the partial dot products the row kernel of dW_dec left (fused_dz_selected only)
 hipError_t launch_dz_from_partials(hipStream_t s, bool bf16, Dims D, FeatureLists fl, const float* norms,
                                    float lam_c_over_b, float C, void* dpre, const int32_t* flags);

@@ -273,7 +273,7 @@ struct DzPolicy {
   const int32_t* skip_flags; int kcap;
   const float* x_scale; float* part_theta; float* part_benc; float* part_below;   // FOLD only
   // stands down when the device-side switch selected the sparse backward
-  __device__ bool skip() const { return skip_flags && gather_selected(skip_flags, kcap); }
+  __device__ bool skip() const { return skip_flags && lists_backward_selected(skip_flags, kcap); }
   struct GInfo { int l; };
   // per column: -2 log2(e) C n, 4 (lambda0 C / B) n, -(lambda1 / B) n; FOLD: the three column sums and where they go
   struct Epi { float4 karg, kamp, dead; float4 st, sb, nb; int col, prow; bool ok; };
@@ -390,7 +390,7 @@ struct DWdecPolicy {
   // optional (fused update, bf16 kernel, no edge tiles): sums of squares of the UPDATED weights over each run of
   // 64 columns of a row, [P][N / 64][F], from which the next step's decoder norms are formed without reading W_dec
   float* n2_part;
-  __device__ bool skip() const { return skip_flags && gather_selected(skip_flags, kcap); }
+  __device__ bool skip() const { return skip_flags && lists_backward_selected(skip_flags, kcap); }
   struct GInfo { int p, l, lp; };
   struct Epi { int row0, run; };
   __device__ GInfo ginfo(int order) const {

@@ -65,7 +65,7 @@ __global__ __launch_bounds__(256) void norms_from_partials_kernel(Dims D, const 
   if (i >= (long)D.L * D.F) return;
   const int l = (int)(i / D.F), f = (int)(i - (long)l * D.F);
   float a[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-  if (flags && gather_selected(flags, kcap)) {
+  if (flags && lists_backward_selected(flags, kcap)) {
     const int slots = 8 * ((D.d + 2047) / 2048);
     const float* base = n2_part + ((size_t)packed_index(l, l, D.L) * D.F + f) * slots;
     for (int j = 0; j < D.L - l; ++j)

@@ -31,13 +31,13 @@
 namespace clt {
 namespace {
 
-__global__ void decode_decide_kernel(Dims D, const int32_t* __restrict__ l0, float thr, int forced,
+__global__ void decode_decide_kernel(Dims D, const int32_t* __restrict__ l0, float thr, float thr_bwd, int forced,
                                      int32_t* __restrict__ flags) {
   if (threadIdx.x != 0 || blockIdx.x != 0) return;
   long long tot = 0;
   for (int l = 0; l < D.L; ++l) tot += l0[l];
   const double dens = (double)tot / ((double)D.L * D.B * D.F);
-  flags[0] = (forced || dens <= (double)thr) ? 1 : 0;
+  flags[0] = ((forced || dens <= (double)thr) ? 1 : 0) | ((forced || dens <= (double)thr_bwd) ? 2 : 0);
   flags[1] = 0;
   flags[2] = 1;
   flags[3] = 0;
@@ -247,7 +247,7 @@ __global__ __launch_bounds__(256) void sparse_dpre_fill_kernel(Dims D, const uin
                                                                const float* __restrict__ norms, float lam1_over_b,
                                                                T* __restrict__ dpre, const int32_t* __restrict__ flags,
                                                                int kcap) {
-  if (!gather_selected(flags, kcap)) return;
+  if (!lists_backward_selected(flags, kcap)) return;
   const size_t n4 = (size_t)D.L * D.B * D.F / 4, per_layer4 = (size_t)D.B * D.F / 4;
   const int F4 = D.F / 4;
   for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n4; i += (size_t)gridDim.x * 256) {
@@ -277,7 +277,7 @@ __global__ __launch_bounds__(256) void gather_dz_kernel(Dims D, GatherLists g, c
                                                         const T* __restrict__ W_dec, const float* __restrict__ norms,
                                                         float lam_c_over_b, float C, T* __restrict__ dpre,
                                                         const int32_t* __restrict__ flags, FeatureLists fused) {
-  if (!gather_selected(flags, g.kcap) || fused_dz_selected(flags, fused)) return;
+  if (!lists_backward_selected(flags, g.kcap) || fused_dz_selected(flags, fused)) return;
   const int lane = threadIdx.x & 63, wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const long items = ((long)D.L * D.B + 7) / 8 * 8 * GDZ_PARTS;
   for (long it = blockIdx.x; it < items; it += gridDim.x) {      // layer 0 (most targets) first
@@ -361,7 +361,7 @@ __global__ __launch_bounds__(1024, 2) void gather_dz_lds_kernel(Dims D, GatherLi
                                                                 FeatureLists fused) {
   extern __shared__ __align__(16) unsigned char gdz_smem[];
   T* dys = reinterpret_cast<T*>(gdz_smem);      // [tcap][d]
-  if (!gather_selected(flags, g.kcap) || fused_dz_selected(flags, fused)) return;
+  if (!lists_backward_selected(flags, g.kcap) || fused_dz_selected(flags, fused)) return;
   const int tid = threadIdx.x, lane = tid & 63, wv = __builtin_amdgcn_readfirstlane(tid >> 6);
   constexpr int PIECE = 16 / (int)sizeof(T);      // elements per 16-byte piece
   const int ppr = D.d / PIECE;                    // pieces per row
@@ -444,7 +444,7 @@ __global__ __launch_bounds__(1024, 2) void gather_dz_lds_kernel(Dims D, GatherLi
 // Each thread owns 4 consecutive features of one layer and one token segment.
 __global__ __launch_bounds__(256) void fl_count_kernel(Dims D, const uint8_t* __restrict__ cls, FeatureLists fl,
                                                        const int32_t* __restrict__ flags) {
-  if (!gather_selected(flags, fl.kcap)) return;
+  if (!lists_backward_selected(flags, fl.kcap)) return;
   const int LF4 = D.L * D.F / 4;
   const int q = blockIdx.x * 256 + threadIdx.x, sgm = blockIdx.y;
   if (q >= LF4) return;
@@ -467,8 +467,8 @@ __global__ __launch_bounds__(256) void fl_count_kernel(Dims D, const uint8_t* __
 // run of consecutive features (8 at F = 8192, so neighbouring lanes share cache lines).
 constexpr int FL_SCAN_THREADS = 1024;
 __global__ __launch_bounds__(FL_SCAN_THREADS) void fl_scan_kernel(Dims D, FeatureLists fl,
-                                                                  int32_t* __restrict__ flags) {
-  if (!gather_selected(flags, fl.kcap)) return;
+                                                                  int32_t* __restrict__ flags, int dense_beyond) {
+  if (!lists_backward_selected(flags, fl.kcap)) return;
   __shared__ int tot[FL_SCAN_THREADS];
   const int l = blockIdx.x, tid = threadIdx.x;
   const int per = (D.F + FL_SCAN_THREADS - 1) / FL_SCAN_THREADS;
@@ -488,7 +488,12 @@ __global__ __launch_bounds__(FL_SCAN_THREADS) void fl_scan_kernel(Dims D, Featur
     tot[tid] += v;
     __syncthreads();
   }
-  if (tid == FL_SCAN_THREADS - 1) atomicMax(&flags[3], tot[tid]);      // the longest layer decides whether the fused dz has room
+  if (tid == FL_SCAN_THREADS - 1) {
+    atomicMax(&flags[3], tot[tid]);      // the longest layer decides whether the fused dz has room
+    // Automatic mode: lists too long for the fused dz are long enough for the dense kernels to win, so the backward
+    // is handed back to them (they run after this kernel and look at the same bit; so do the list kernels).
+    if (dense_beyond > 0 && tot[tid] > dense_beyond) atomicAnd(&flags[0], ~2);
+  }
   int run = tot[tid] - sum;
   for (int f = f0; f < f1; ++f) {
     const size_t lf = (size_t)l * D.F + f;
@@ -507,7 +512,7 @@ __global__ __launch_bounds__(FL_SCAN_THREADS) void fl_scan_kernel(Dims D, Featur
 template <typename T>
 __global__ __launch_bounds__(256) void fl_fill_kernel(Dims D, const uint8_t* __restrict__ cls, const T* __restrict__ z,
                                                       FeatureLists fl, const int32_t* __restrict__ flags) {
-  if (!gather_selected(flags, fl.kcap)) return;
+  if (!lists_backward_selected(flags, fl.kcap)) return;
   const int LF4 = D.L * D.F / 4;
   const int q = blockIdx.x * 256 + threadIdx.x, sgm = blockIdx.y;
   if (q >= LF4) return;
@@ -678,7 +683,7 @@ __global__ __launch_bounds__(256, 4) void sparse_dwdec_kernel(Dims D, FeatureLis
                                                            const float* __restrict__ norms, T* __restrict__ dW_dec,
                                                            AdamFuseArgs fuse, const int32_t* __restrict__ flags,
                                                            float* __restrict__ n2_part) {
-  if (!gather_selected(flags, fl.kcap)) return;
+  if (!lists_backward_selected(flags, fl.kcap)) return;
   const int tid = threadIdx.x;
   const int chunks = (D.L + SD_TCH - 1) / SD_TCH;          // chunk slots per (l, f); those past L - l are empty
   const long items = (long)D.L * D.F * chunks;
@@ -764,7 +769,7 @@ __global__ __launch_bounds__(256, 8) void sparse_dwdec_sliced_kernel(Dims D, Fea
                                                                      const float* __restrict__ norms, T* __restrict__ dW_dec,
                                                                      AdamFuseArgs fuse, const int32_t* __restrict__ flags,
                                                                      float* __restrict__ n2_part) {
-  if (!gather_selected(flags, fl.kcap)) return;
+  if (!lists_backward_selected(flags, fl.kcap)) return;
   const int lane = threadIdx.x & 63, wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int slice = blockIdx.x & 7, wg = blockIdx.x >> 3, nwg = gridDim.x >> 3;      // (the grid is a multiple of 8)
   const int sw = D.d / 8, q4 = sw / 4;                     // slice width in columns and in lane quads (d % 32 == 0)
@@ -931,9 +936,10 @@ __global__ __launch_bounds__(256) void dz_from_partials_kernel(Dims D, FeatureLi
 
 }  // namespace
 
-hipError_t launch_decode_decide(hipStream_t s, Dims D, const int32_t* l0, float density_threshold, int forced,
-                                int32_t* flags) {
-  hipLaunchKernelGGL(decode_decide_kernel, dim3(1), dim3(64), 0, s, D, l0, density_threshold, forced, flags);
+hipError_t launch_decode_decide(hipStream_t s, Dims D, const int32_t* l0, float density_threshold,
+                                float backward_density_threshold, int forced, int32_t* flags) {
+  hipLaunchKernelGGL(decode_decide_kernel, dim3(1), dim3(64), 0, s, D, l0, density_threshold,
+                     backward_density_threshold, forced, flags);
   return hipGetLastError();
 }
 
@@ -1014,11 +1020,12 @@ hipError_t init_gather() {
 }
 
 hipError_t launch_feature_lists(hipStream_t s, bool bf16, Dims D, const uint8_t* cls, const void* z, FeatureLists fl,
-                                int32_t* flags) {
+                                int32_t* flags, bool dense_when_too_long) {
   const int LF4 = D.L * D.F / 4;
   const dim3 grid((LF4 + 255) / 256, FL_SEGS);
   hipLaunchKernelGGL(fl_count_kernel, grid, dim3(256), 0, s, D, cls, fl, flags);
-  hipLaunchKernelGGL(fl_scan_kernel, dim3(D.L), dim3(FL_SCAN_THREADS), 0, s, D, fl, flags);
+  hipLaunchKernelGGL(fl_scan_kernel, dim3(D.L), dim3(FL_SCAN_THREADS), 0, s, D, fl, flags,
+                     dense_when_too_long && fl.dz_part ? fl.ecap : 0);
   if (bf16)
     hipLaunchKernelGGL((fl_fill_kernel<bf16_t>), grid, dim3(256), 0, s, D, cls, (const bf16_t*)z, fl, flags);
   else

@@ -121,7 +121,7 @@ class GpuRun:
 
     def __init__(self, w: S.CLTWorkload, params, x, y, t=1, m=None, v=None, x_scale=None, y_scale=None,
                  theta=None, decode_mode=1, gather_density_threshold=0.004, fused=False, pre_steps=0,
-                 reuse_decoder_norms=False):
+                 reuse_decoder_norms=False, list_backward_density_threshold=0.0):
         """pre_steps: fused training steps run on the device before the step whose results are kept (that step
         then has step count t + pre_steps and starts from self.start_params / start_m / start_v)."""
         from paper_2603_21014_amd import binding as K
@@ -141,13 +141,15 @@ class GpuRun:
         cfg = K.make_config(w.L, w.d, w.F, w.B, K.DTYPE_F32 if w.dtype == "f32" else K.DTYPE_BF16,
                             K.INPUT_INT8_ROWSCALE if w.int8_inputs else K.INPUT_NATIVE, w.master_weights, decode_mode,
                             gather_density_threshold, w.C, w.ste_eps, log_threshold=w.log_threshold, topk=w.topk or None,
-                            reuse_decoder_norms=reuse_decoder_norms)
+                            reuse_decoder_norms=reuse_decoder_norms,
+                            list_backward_density_threshold=list_backward_density_threshold)
         ws = gb.empty("workspace", (K.clt_workspace_bytes(cfg),), torch.uint8)
         step = K.CLTStep(w.L, w.d, w.F, w.B, dtype=w.dtype, int8_inputs=w.int8_inputs,
                          master_weights=w.master_weights, C_=w.C, ste_bandwidth=w.ste_eps, device=dev,
                          decode_mode=decode_mode, gather_density_threshold=gather_density_threshold,
                          log_threshold=w.log_threshold, topk=w.topk or None, workspace=ws,
-                         reuse_decoder_norms=reuse_decoder_norms)
+                         reuse_decoder_norms=reuse_decoder_norms,
+                         list_backward_density_threshold=list_backward_density_threshold)
         for name in ("z", "pre", "act_class", "y_hat", "l0", "loss_dev"):
             t_ = getattr(step, name)
             setattr(step, name, gb.empty(name, t_.shape, t_.dtype))

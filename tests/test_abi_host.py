@@ -28,7 +28,7 @@ def test_library_exports_every_declared_symbol(K):
 
 
 def test_config_struct_matches_header(K):
-    assert ctypes.sizeof(K.clt_config) == 4 * 13 + 4 * 6
+    assert ctypes.sizeof(K.clt_config) == 4 * 13 + 4 * 7
     assert ctypes.sizeof(K.clt_tensors) == 5 * ctypes.sizeof(ctypes.c_void_p)
 
 

@@ -643,7 +643,7 @@ def test_auto_switch_follows_measured_density():
     theta = sparse_theta(w, 0.01)
     g = GpuRun(w, params, x, y, theta=theta, decode_mode=AUTO, gather_density_threshold=0.02)
     o = OracleRun(w, params, x, y, gpu_active=g.active, gpu_window=g.window, theta=theta)
-    assert g.decode_switch[0] == 1 and g.decode_switch[2] == 2
+    assert g.decode_switch[0] == 3 and g.decode_switch[2] == 2      # both the decode and the backward on the lists
     show("auto -> gather", compare_step(w, g, o, TOL["bf16"]))
     # one token with a huge norm lights up far more features than a capped list holds:
     # the mean density is still below the threshold, but the step must decode densely
@@ -653,8 +653,59 @@ def test_auto_switch_follows_measured_density():
     g = GpuRun(w, params, x2, y, theta=theta, decode_mode=AUTO, gather_density_threshold=0.02)
     o = OracleRun(w, params, x2, y, gpu_active=g.active, gpu_window=g.window, theta=theta)
     kcap = (int(8.0 * 0.02 * w.F) + 64 + 7) // 8 * 8
-    assert g.decode_switch[0] == 1 and g.decode_switch[1] > kcap and g.decode_switch[2] == 1
+    assert g.decode_switch[0] == 3 and g.decode_switch[1] > kcap and g.decode_switch[2] == 1
     show("auto -> dense fallback", compare_step(w, g, o, TOL["bf16"]))
+
+
+@pytest.mark.parametrize("dtype,fused", [("bf16", True), ("f32", False), ("bf16", False)])
+def test_auto_dense_decode_with_list_driven_backward(dtype, fused):
+    """The automatic mode has two thresholds: between them the forward decode stays a dense GEMM while dz, dW_dec and
+    its Adam update run on the active-feature lists (whose kernels pay up to a higher density).  Against the oracle,
+    and the forward bit-identical to the dense mode's."""
+    w = S.scaled(S.WORKLOADS["tiny"], dtype=dtype, L=3, d=128, F=1024, B=256, seed=87, master_weights=dtype == "bf16")
+    params = S.make_params(w)
+    x, y = S.make_inputs(w)
+    theta = sparse_theta(w, 0.01)
+    g = GpuRun(w, params, x, y, theta=theta, decode_mode=AUTO, gather_density_threshold=0.002,
+               list_backward_density_threshold=0.05, fused=fused)
+    assert g.decode_switch[0] == 2 and g.decode_switch[2] == 1      # backward on the lists, decode dense
+    dn = GpuRun(w, params, x, y, theta=theta, decode_mode=DENSE, fused=fused)
+    assert (g.y_hat == dn.y_hat).all() and g.loss[0] == dn.loss[0]
+    # the list-driven kernels did the work: the scan of the feature lists left their longest layer total
+    assert int(g.decode_switch[3]) == int((g.active | g.window).sum(axis=(1, 2)).max())
+    o = OracleRun(w, params, x, y, gpu_active=g.active, gpu_window=g.window, theta=theta)
+    show(f"auto: dense decode, lists backward {dtype} fused={fused}", compare_step(w, g, o, TOL[dtype]))
+    # above both thresholds everything is dense, below both everything on the lists
+    hi = GpuRun(w, params, x, y, theta=theta, decode_mode=AUTO, gather_density_threshold=0.002,
+                list_backward_density_threshold=0.005, fused=fused)
+    assert hi.decode_switch[0] == 0 and hi.decode_switch[2] == 1 and hi.decode_switch[3] == 0
+    lo = GpuRun(w, params, x, y, theta=theta, decode_mode=AUTO, gather_density_threshold=0.02,
+                list_backward_density_threshold=0.05, fused=fused)
+    assert lo.decode_switch[0] == 3 and lo.decode_switch[2] == 2
+
+
+def test_auto_hands_long_lists_back_to_the_dense_backward():
+    """Automatic mode, mean density below the backward threshold, but one layer's lists are longer than the room for
+    the partial sums of the fused dz (sized from that threshold): the scan of the feature lists clears the backward
+    bit and dz / dW_dec run as dense GEMMs -- the separate gather dz kernel would be slower than those."""
+    w = S.scaled(S.WORKLOADS["tiny"], dtype="bf16", L=3, d=128, F=1024, B=256, seed=88)
+    params = S.make_params(w)
+    x, y = S.make_inputs(w)
+    theta = sparse_theta(w, 0.01)
+    theta[0] = sparse_theta(w, 0.12)[0]          # 123 of 1024 per token in layer 0, mean density 0.047
+    room = int(1.25 * 0.05 * w.F) + 32           # 96 entries per token
+    g = GpuRun(w, params, x, y, theta=theta, decode_mode=AUTO, gather_density_threshold=0.002,
+               list_backward_density_threshold=0.05, fused=True)
+    assert abs(g.active.mean() - 0.047) < 0.01
+    assert int(g.decode_switch[3]) > room * w.B and g.decode_switch[0] == 0 and g.decode_switch[2] == 1
+    dn = GpuRun(w, params, x, y, theta=theta, decode_mode=DENSE, fused=True)
+    # the dense kernels ran: the decoder update has the dense mode's bits (the vectors' gradients are reduced by
+    # another kernel in the automatic mode, in another order)
+    assert (g.new_params["W_dec"] == dn.new_params["W_dec"]).all()
+    for k in O.PARAM_NAMES:
+        assert rel_l2(g.new_params[k], dn.new_params[k]) < 1e-3, k
+    o = OracleRun(w, params, x, y, gpu_active=g.active, gpu_window=g.window, theta=theta)
+    show("auto: long lists -> dense backward", compare_step(w, g, o, TOL["bf16"]))
 
 
 def test_restored_state_reproduces_the_step_bitwise():
