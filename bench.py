@@ -338,9 +338,9 @@ def main():
     ap.add_argument("--gather-density-threshold", type=float, default=0.004,
                     help="auto mode: the forward decode gathers at or below this mean active fraction (measured "
                          "break-even on an MI355X: 0.003-0.0045)")
-    ap.add_argument("--list-backward-density-threshold", type=float, default=0.012,
+    ap.add_argument("--list-backward-density-threshold", type=float, default=0.016,
                     help="auto mode: the backward through the decoder runs on the active-feature lists at or below "
-                         "this mean active fraction (measured break-even: about 0.014)")
+                         "this mean active fraction (measured break-even: about 0.02)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-timing", action="store_true",
                     help="skip the per-kernel HIP-event brackets (roofline entry becomes null)")

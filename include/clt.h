@@ -113,9 +113,9 @@ typedef struct clt_config {
                              mean active fraction is <= this (same row limit); 0 = the same
                              as gather_density_threshold.  The list-driven backward pays up
                              to a higher density than the gather decode: it breaks even
-                             near 0.015 (about 125 of 8192), whatever the expansion factor
+                             near 0.02 (about 165 of 8192), whatever the expansion factor
                              (the dense cost grows with F, the list-driven one with the
-                             active count); binding default 0.012.  The workspace holds room
+                             active count); binding default 0.016.  The workspace holds room
                              for the partial sums of dz sized from this threshold (at most
                              320 listed entries per token and layer); a step whose lists are
                              longer goes backward through the dense kernels.                */

@@ -743,34 +743,48 @@ __global__ __launch_bounds__(256, 4) void sparse_dwdec_kernel(Dims D, FeatureLis
 // Sums of four values over the wave at once: on return the lanes with lane % 4 == u hold the sum of the u-th value.
 // Two exchange steps inside quads halve the values each lane carries, two rotations finish the rows of 16 lanes,
 // two shuffles the four rows.
-__device__ __forceinline__ float wave_sum4(float a, float b, float c, float d, int lane) {
+__device__ __forceinline__ float wave_sum4(float a, float b, float c, float d, int lane, int addr16, int addr32) {
   const bool o1 = lane & 1, o2 = lane & 2;
   const float r1 = (o1 ? b : a) + dpp_move<0xB1>(o1 ? a : b);      // even lanes: a of the pair, odd lanes: b
   const float r2 = (o1 ? d : c) + dpp_move<0xB1>(o1 ? c : d);
   float r = (o2 ? r2 : r1) + dpp_move<0x4E>(o2 ? r1 : r2);         // lane % 4 = 0, 1, 2, 3: a, b, c, d of the quad
   r += dpp_move<0x128>(r);                                          // row_ror:8
   r += dpp_move<0x124>(r);                                          // row_ror:4
-  r += __shfl_xor(r, 16, 64);
-  r += __shfl_xor(r, 32, 64);
+  // (addr16 / addr32: byte addresses of lanes lane ^ 16 and lane ^ 32, computed once by the caller)
+  r += __int_as_float(__builtin_amdgcn_ds_bpermute(addr16, __float_as_int(r)));
+  r += __int_as_float(__builtin_amdgcn_ds_bpermute(addr32, __float_as_int(r)));
   return r;
+}
+
+// bf16 pairs as the dot-product instruction takes them
+typedef __bf16 bf16x2_hw __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ float dot2_bf16(uint32_t a, uint32_t b, float c) {
+  return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_hw, a), __builtin_bit_cast(bf16x2_hw, b), c, false);
 }
 
 // The same rows cut into eight column slices, one per XCD (workgroups go round-robin to the XCDs, so blockIdx & 7
 // names the slice): an XCD's L2 then only ever sees its d/8 columns of d y_hat, and with the (source, target) pairs
 // walked target-major that is B * d/8 elements at a time (2 MB at L=16 d=2048 B=4096), so the gathered d y_hat rows
 // come out of the L2.  One wave per (pair, feature, slice), four consecutive features per workgroup, lanes own 4
-// columns per pass of 256; 40 registers, eight waves per SIMD.  The weights and optimizer state, touched once, are
-// streamed with non-temporal accesses so that they do not displace the slice (plain accesses: 10 % slower).  The
-// sums run over the feature's tokens in list order, as in the kernel above: same gradient and update, bit for bit.
-// This is the kernel the library uses whenever d is a multiple of 32.
+// columns per pass of 256; 44-48 registers with bf16 storage, eight waves per SIMD.  The weights and optimizer state,
+// touched once, are streamed with non-temporal accesses so that they do not displace the slice (plain accesses: 10 %
+// slower).  The sums run over the feature's tokens in list order; with fp32 storage exactly as in the kernel above
+// (same gradient and update, bit for bit).  At more than a few tokens per feature the kernel is bound by vector
+// instruction issue, hence the bf16 token loop below.  This is the kernel the library uses whenever d is a
+// multiple of 32.
 template <typename T, bool MASTER>
-__global__ __launch_bounds__(256, 8) void sparse_dwdec_sliced_kernel(Dims D, FeatureLists fl, const T* __restrict__ d_yhat,
+__global__ __launch_bounds__(256, sizeof(T) == 2 ? 8 : 6) void sparse_dwdec_sliced_kernel(Dims D, FeatureLists fl, const T* __restrict__ d_yhat,
                                                                      T* __restrict__ W_dec, const float* __restrict__ G,
                                                                      const float* __restrict__ norms, T* __restrict__ dW_dec,
                                                                      AdamFuseArgs fuse, const int32_t* __restrict__ flags,
-                                                                     float* __restrict__ n2_part) {
+                                                                     float* __restrict__ n2_part,
+                                                                     const int32_t* __restrict__ fl_tok,
+                                                                     const float* __restrict__ fl_val) {
+  // (fl_tok, fl_val: fl.tok and fl.val once more, as parameters of their own that nothing else aliases: the wave-uniform
+  //  reads of the token lists can then go through the scalar unit)
   if (!lists_backward_selected(flags, fl.kcap)) return;
   const int lane = threadIdx.x & 63, wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int addr16 = (lane ^ 16) << 2, addr32 = (lane ^ 32) << 2;
   const int slice = blockIdx.x & 7, wg = blockIdx.x >> 3, nwg = gridDim.x >> 3;      // (the grid is a multiple of 8)
   const int sw = D.d / 8, q4 = sw / 4;                     // slice width in columns and in lane quads (d % 32 == 0)
   const int passes = (q4 + 63) / 64;
@@ -792,8 +806,8 @@ __global__ __launch_bounds__(256, 8) void sparse_dwdec_sliced_kernel(Dims D, Fea
     if (cur.f < D.F) {
       const long lf = (long)cur.l * D.F + cur.f;
       cur.cnt = fl.cnt[lf]; cur.off = fl.off[lf]; cur.Gf = G[lf]; cur.nf = norms[lf];
-      const int32_t* tk = fl.tok + (size_t)cur.l * D.B * fl.kcap + cur.off;
-      const float* tv = fl.val + (size_t)cur.l * D.B * fl.kcap + cur.off;
+      const int32_t* tk = fl_tok + (size_t)cur.l * D.B * fl.kcap + cur.off;
+      const float* tv = fl_val + (size_t)cur.l * D.B * fl.kcap + cur.off;
       const float coef = cur.Gf * __builtin_amdgcn_rcpf(fmaxf(cur.nf, 1e-30f));
       const size_t o = ((size_t)packed_index(cur.l, cur.lp, D.L) * D.F + cur.f) * D.d;
       const T* dyt = d_yhat + (size_t)cur.lp * D.B * D.d;
@@ -817,9 +831,8 @@ __global__ __launch_bounds__(256, 8) void sparse_dwdec_sliced_kernel(Dims D, Fea
         // (pair, slice, entry).
         float dz_keep = 0.f;
         const float4 wl = Elem<T>::widen4(wr);
-        const float4 wz = on ? wl : make_float4(0.f, 0.f, 0.f, 0.f);
         auto dz_group = [&](int j0, int nval, const float (&pd)[4]) {      // tokens j0 .. j0 + nval - 1, j0 % 4 == 0
-          const float r = wave_sum4(pd[0], pd[1], pd[2], pd[3], lane);
+          const float r = wave_sum4(pd[0], pd[1], pd[2], pd[3], lane, addr16, addr32);
           if ((lane & 60) == (j0 & 63)) dz_keep = r;
           const int last = j0 + nval - 1;
           if ((last & 63) == 63 || last == cur.cnt - 1) {
@@ -829,44 +842,84 @@ __global__ __launch_bounds__(256, 8) void sparse_dwdec_sliced_kernel(Dims D, Fea
             }
           }
         };
-        int j = 0;
-        for (; j + 4 <= cur.cnt; j += 4) {
-          typename Elem<T>::Raw4 r[4];
-          float zv[4], pd[4];
+        if constexpr (sizeof(T) == 2) {
+          // bf16 storage.  The rows come through buffer loads (descriptor of the target's d y_hat, the lane's column
+          // offset in a register, the token's row offset as the scalar operand: no vector arithmetic per token) and
+          // stay packed: z * row enters the gradient two tokens at a time as a packed dot product (the two tokens'
+          // values of a column brought into one register by a byte permute, (z_a, z_b) as the scalar operand; z is a
+          // bf16 value, so nothing is rounded), the dz product two columns at a time.
+          const __amdgpu_buffer_rsrc_t rows = __builtin_amdgcn_make_buffer_rsrc(
+              const_cast<T*>(dyt), 0, (int)((size_t)D.B * D.d * 2), 0x00020000);
+          const uint32_t voff = col * 2, row_bytes = (uint32_t)D.d * 2;
+          const uint32_t wzx = on ? wr[0] : 0u, wzy = on ? wr[1] : 0u;
+          for (int j = 0; j < cur.cnt; j += 4) {
+            const int nval = cur.cnt - j < 4 ? cur.cnt - j : 4;
+            nt_u32x2 q[4];
+            uint32_t zb[4], bt[4];
+            // (four list entries at once whatever nval is: past the feature's own entries lie other lists or, at the
+            //  very end, the arrays that follow in the workspace; what is read there is replaced by token 0 with z = 0)
 #pragma unroll
-          for (int u = 0; u < 4; ++u) {
-            const int b = __builtin_amdgcn_readfirstlane(tk[j + u]);
-            zv[u] = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(tv[j + u])));
-            r[u] = Elem<T>::load_raw4(lane_ptr(dyt + (size_t)b * D.d, col));
-          }
+            for (int u = 0; u < 4; ++u) { bt[u] = (uint32_t)tk[j + u]; zb[u] = __float_as_uint(tv[j + u]); }
 #pragma unroll
-          for (int u = 0; u < 4; ++u) {
-            const float4 q = Elem<T>::widen4(r[u]);
-            acc[0] = fmaf(zv[u], q.x, acc[0]);
-            acc[1] = fmaf(zv[u], q.y, acc[1]);
-            acc[2] = fmaf(zv[u], q.z, acc[2]);
-            acc[3] = fmaf(zv[u], q.w, acc[3]);
-            pd[u] = fmaf(wz.x, q.x, fmaf(wz.y, q.y, fmaf(wz.z, q.z, wz.w * q.w)));
+            for (int u = 0; u < 4; ++u) {
+              if (u >= nval) { bt[u] = 0u; zb[u] = 0u; }
+              q[u] = __builtin_amdgcn_raw_buffer_load_b64(rows, voff, bt[u] * row_bytes, 0);
+            }
+            float pd[4];
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+              const uint32_t zp = (zb[2 * h] >> 16) | (zb[2 * h + 1] & 0xffff0000u);
+              const nt_u32x2 qa = q[2 * h], qb = q[2 * h + 1];
+              acc[0] = dot2_bf16(__builtin_amdgcn_perm(qb[0], qa[0], 0x05040100u), zp, acc[0]);
+              acc[1] = dot2_bf16(__builtin_amdgcn_perm(qb[0], qa[0], 0x07060302u), zp, acc[1]);
+              acc[2] = dot2_bf16(__builtin_amdgcn_perm(qb[1], qa[1], 0x05040100u), zp, acc[2]);
+              acc[3] = dot2_bf16(__builtin_amdgcn_perm(qb[1], qa[1], 0x07060302u), zp, acc[3]);
+              pd[2 * h] = dot2_bf16(qa[0], wzx, dot2_bf16(qa[1], wzy, 0.f));
+              pd[2 * h + 1] = dot2_bf16(qb[0], wzx, dot2_bf16(qb[1], wzy, 0.f));
+            }
+            if (dz_out) dz_group(j, nval, pd);
           }
-          if (dz_out) dz_group(j, 4, pd);
-        }
-        if (j < cur.cnt) {
-          const int nval = cur.cnt - j;
-          float pd[4] = {0.f, 0.f, 0.f, 0.f};
-          for (int u = 0; u < nval; ++u) {
-            const int b = __builtin_amdgcn_readfirstlane(tk[j + u]);
-            const float zv = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(tv[j + u])));
-            const float4 q = Elem<T>::widen4(Elem<T>::load_raw4(lane_ptr(dyt + (size_t)b * D.d, col)));
-            acc[0] = fmaf(zv, q.x, acc[0]);
-            acc[1] = fmaf(zv, q.y, acc[1]);
-            acc[2] = fmaf(zv, q.z, acc[2]);
-            acc[3] = fmaf(zv, q.w, acc[3]);
-            const float pu = fmaf(wz.x, q.x, fmaf(wz.y, q.y, fmaf(wz.z, q.z, wz.w * q.w)));
-            pd[0] = u == 0 ? pu : pd[0];
-            pd[1] = u == 1 ? pu : pd[1];
-            pd[2] = u == 2 ? pu : pd[2];
+        } else {
+          const float4 wz = on ? wl : make_float4(0.f, 0.f, 0.f, 0.f);
+          int j = 0;
+          for (; j + 4 <= cur.cnt; j += 4) {
+            typename Elem<T>::Raw4 r[4];
+            float zv[4], pd[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+              const int b = __builtin_amdgcn_readfirstlane(tk[j + u]);
+              zv[u] = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(tv[j + u])));
+              r[u] = Elem<T>::load_raw4(lane_ptr(dyt + (size_t)b * D.d, col));
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+              const float4 q = Elem<T>::widen4(r[u]);
+              acc[0] = fmaf(zv[u], q.x, acc[0]);
+              acc[1] = fmaf(zv[u], q.y, acc[1]);
+              acc[2] = fmaf(zv[u], q.z, acc[2]);
+              acc[3] = fmaf(zv[u], q.w, acc[3]);
+              pd[u] = fmaf(wz.x, q.x, fmaf(wz.y, q.y, fmaf(wz.z, q.z, wz.w * q.w)));
+            }
+            if (dz_out) dz_group(j, 4, pd);
           }
-          if (dz_out) dz_group(j, nval, pd);
+          if (j < cur.cnt) {
+            const int nval = cur.cnt - j;
+            float pd[4] = {0.f, 0.f, 0.f, 0.f};
+            for (int u = 0; u < nval; ++u) {
+              const int b = __builtin_amdgcn_readfirstlane(tk[j + u]);
+              const float zv = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(tv[j + u])));
+              const float4 q = Elem<T>::widen4(Elem<T>::load_raw4(lane_ptr(dyt + (size_t)b * D.d, col)));
+              acc[0] = fmaf(zv, q.x, acc[0]);
+              acc[1] = fmaf(zv, q.y, acc[1]);
+              acc[2] = fmaf(zv, q.z, acc[2]);
+              acc[3] = fmaf(zv, q.w, acc[3]);
+              const float pu = fmaf(wz.x, q.x, fmaf(wz.y, q.y, fmaf(wz.z, q.z, wz.w * q.w)));
+              pd[0] = u == 0 ? pu : pd[0];
+              pd[1] = u == 1 ? pu : pd[1];
+              pd[2] = u == 2 ? pu : pd[2];
+            }
+            if (dz_out) dz_group(j, nval, pd);
+          }
         }
         const float w4[4] = {wl.x, wl.y, wl.z, wl.w};
         float g4[4];
@@ -1033,7 +1086,11 @@ hipError_t launch_feature_lists(hipStream_t s, bool bf16, Dims D, const uint8_t*
   return hipGetLastError();
 }
 
-bool sparse_dwdec_takes_dz(Dims D) { return D.d % 32 == 0 && !getenv("CLT_SD_ROWS") && !getenv("CLT_NO_FUSED_DZ"); }
+// The sliced kernel: d in eight slices of whole lane quads, and one target's d y_hat within reach of a 32-bit byte offset
+static bool sparse_dwdec_sliced(Dims D) {
+  return D.d % 32 == 0 && (size_t)D.B * D.d * 2 < ((size_t)1 << 31) && !getenv("CLT_SD_ROWS");
+}
+bool sparse_dwdec_takes_dz(Dims D) { return sparse_dwdec_sliced(D) && !getenv("CLT_NO_FUSED_DZ"); }
 
 hipError_t launch_dz_from_partials(hipStream_t s, bool bf16, Dims D, FeatureLists fl, const float* norms,
                                    float lam_c_over_b, float C, void* dpre, const int32_t* flags) {
@@ -1053,12 +1110,12 @@ hipError_t launch_sparse_dwdec(hipStream_t s, bool bf16, Dims D, FeatureLists fl
   const bool master = a.fuse.m && a.fuse.master;
   float* n2 = (bf16 && a.fuse.m && D.d % 256 == 0) ? a.n2_part : nullptr;
   // Both kernels get one workgroup per item while the grid allows it (see the comment in the sliced kernel).
-  if (D.d % 32 == 0 && !getenv("CLT_SD_ROWS")) {
+  if (sparse_dwdec_sliced(D)) {
     const size_t per_xcd = (size_t)(D.L * (D.L + 1) / 2) * ((D.F + 3) / 4), gx = (size_t)1 << 27;
     const dim3 grid((unsigned)(8 * (per_xcd < gx ? per_xcd : gx)));
 #define CLT_SDS(T, M)                                                                                              \
   hipLaunchKernelGGL((sparse_dwdec_sliced_kernel<T, M>), grid, dim3(256), 0, s, D, fl, (const T*)a.d_yhat,         \
-                     (T*)a.W_dec, a.G, a.norms, (T*)a.dW_dec, a.fuse, flags, n2)
+                     (T*)a.W_dec, a.G, a.norms, (T*)a.dW_dec, a.fuse, flags, n2, fl.tok, fl.val)
     if (bf16) { if (master) CLT_SDS(bf16_t, true); else CLT_SDS(bf16_t, false); }
     else { if (master) CLT_SDS(float, true); else CLT_SDS(float, false); }
 #undef CLT_SDS

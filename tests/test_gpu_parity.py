@@ -552,9 +552,10 @@ def test_sparse_backward_fused_adam(dtype, master):
 
 @pytest.mark.parametrize("dtype,d", [("bf16", 256), ("f32", 96), ("bf16", 2304)])
 def test_sparse_backward_column_slices_match_whole_rows(monkeypatch, dtype, d):
-    """The row kernel of dW_dec cut into eight column slices (one per XCD; d a multiple of 32) sums a feature's
-    tokens in the same order as the kernel that takes whole rows: gradients and the fused update must agree bit for
-    bit.  d = 2304: two passes of lanes per slice, the second one ragged."""
+    """The row kernel of dW_dec cut into eight column slices (one per XCD; d a multiple of 32) against the kernel that
+    takes whole rows.  With fp32 storage both sum a feature's tokens in the same order, one multiply-add each:
+    gradients and the fused update must agree bit for bit; with bf16 storage the slices use packed dot products and
+    agree to rounding.  d = 2304: two passes of lanes per slice, the second one ragged."""
     w = S.scaled(S.WORKLOADS["tiny"], dtype=dtype, L=4, d=d, F=264, B=90, seed=85, master_weights=dtype == "bf16")
     theta = sparse_theta(w, 0.06)
     params = S.make_params(w)
@@ -566,11 +567,17 @@ def test_sparse_backward_column_slices_match_whole_rows(monkeypatch, dtype, d):
         monkeypatch.setenv("CLT_SD_ROWS", "1")
         b = GpuRun(w, params, x, y, theta=theta, decode_mode=GATHER, fused=fused)
         assert a.decode_switch[2] == 2
-        if not fused:
-            assert (a.grads["W_dec"] == b.grads["W_dec"]).all()
-        for k in O.PARAM_NAMES:
-            assert (a.new_params[k] == b.new_params[k]).all(), k
-            assert (a.new_m[k] == b.new_m[k]).all() and (a.new_v[k] == b.new_v[k]).all(), k
+        if dtype == "f32":
+            if not fused:
+                assert (a.grads["W_dec"] == b.grads["W_dec"]).all()
+            for k in O.PARAM_NAMES:
+                assert (a.new_params[k] == b.new_params[k]).all(), k
+                assert (a.new_m[k] == b.new_m[k]).all() and (a.new_v[k] == b.new_v[k]).all(), k
+        else:      # bf16: the slices take two tokens per packed dot product, the whole rows one per multiply-add
+            if not fused:
+                assert rel_l2(a.grads["W_dec"], b.grads["W_dec"]) < 3e-3      # (the gradient is stored as bf16)
+            for k in O.PARAM_NAMES:
+                assert rel_l2(a.new_m[k], b.new_m[k]) < 1e-5 and rel_l2(a.new_v[k], b.new_v[k]) < 1e-5, k
 
 
 @pytest.mark.parametrize("dtype,d,rho", [("bf16", 256, 0.05), ("f32", 96, 0.05), ("bf16", 2304, 0.05), ("f32", 64, 0.6)])
