@@ -772,6 +772,9 @@ __device__ __forceinline__ float dot2_bf16(uint32_t a, uint32_t b, float c) {
 // (same gradient and update, bit for bit).  At more than a few tokens per feature the kernel is bound by vector
 // instruction issue, hence the bf16 token loop below.  This is the kernel the library uses whenever d is a
 // multiple of 32.
+#ifndef SD_ITEMS_PER_WG
+#define SD_ITEMS_PER_WG 2
+#endif
 template <typename T, bool MASTER>
 __global__ __launch_bounds__(256, sizeof(T) == 2 ? 8 : 6) void sparse_dwdec_sliced_kernel(Dims D, FeatureLists fl, const T* __restrict__ d_yhat,
                                                                      T* __restrict__ W_dec, const float* __restrict__ G,
@@ -792,9 +795,11 @@ __global__ __launch_bounds__(256, sizeof(T) == 2 ? 8 : 6) void sparse_dwdec_slic
   const long items = (long)(D.L * (D.L + 1) / 2) * F4;
   const bool dz_on = fused_dz_selected(flags, fl);
   struct Meta { int l, lp, f, cnt, off; float Gf, nf; };
-  // (one item per workgroup as long as the grid allows it: handed out in order by the dispatcher, the workgroups in
-  //  flight stay within a narrow window of items, which is what keeps their d y_hat rows in the L2)
-  for (long it = wg; it < items; it += nwg) {
+  // (SD_ITEMS_PER_WG consecutive items per workgroup as long as the grid allows it: handed out in order by the
+  //  dispatcher, the workgroups in flight stay within a narrow window of items, which is what keeps their d y_hat rows
+  //  in the L2; more than one item, so that a launch that stands down costs fewer empty workgroups)
+  for (long itb = (long)wg * SD_ITEMS_PER_WG; itb < items; itb += (long)nwg * SD_ITEMS_PER_WG)
+  for (long it = itb; it < itb + SD_ITEMS_PER_WG && it < items; ++it) {
     Meta cur;
     const int pq = (int)(it / F4);                         // pair ordinal, target-major: (0,0) (0,1) (1,1) (0,2) ...
     cur.f = (int)(it % F4) * 4 + wv;
@@ -1111,7 +1116,8 @@ hipError_t launch_sparse_dwdec(hipStream_t s, bool bf16, Dims D, FeatureLists fl
   float* n2 = (bf16 && a.fuse.m && D.d % 256 == 0) ? a.n2_part : nullptr;
   // Both kernels get one workgroup per item while the grid allows it (see the comment in the sliced kernel).
   if (sparse_dwdec_sliced(D)) {
-    const size_t per_xcd = (size_t)(D.L * (D.L + 1) / 2) * ((D.F + 3) / 4), gx = (size_t)1 << 27;
+    const size_t per_xcd = ((size_t)(D.L * (D.L + 1) / 2) * ((D.F + 3) / 4) + SD_ITEMS_PER_WG - 1) / SD_ITEMS_PER_WG,
+                 gx = (size_t)1 << 27;
     const dim3 grid((unsigned)(8 * (per_xcd < gx ? per_xcd : gx)));
 #define CLT_SDS(T, M)                                                                                              \
   hipLaunchKernelGGL((sparse_dwdec_sliced_kernel<T, M>), grid, dim3(256), 0, s, D, fl, (const T*)a.d_yhat,         \
