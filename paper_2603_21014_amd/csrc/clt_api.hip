@@ -618,10 +618,14 @@ static int backward_impl(clt_handle* h, hipStream_t s, const void* x, const floa
   const int kcap = h->plan.kcap;
   const float lam_c_over_b = h->lambda0 * h->cfg.C / (float)D.B;
   DzArgs za{d_yhat, W_dec, z, act_class, norms, lam_c_over_b, h->cfg.C, dpre, lam1_over_b, skip, kcap};
-  // dense bf16 step: the dz epilogue writes the final d pre and the column partials itself
-  const bool fold = h->bf16 && mode == CLT_DECODE_DENSE;
+  // dense bf16 backward: the dz epilogue writes the final d pre and the column partials itself.  In the automatic mode
+  // that holds for the steps that go backward densely; the others take the reduction kernel, whose partials come in
+  // another number of row blocks, and the kernels that sum them look at the switch.
+  const bool fold = h->bf16 && mode != CLT_DECODE_GATHER;
   if (fold) { za.x_scale = h->int8 ? x_scale : nullptr; za.part_theta = part; za.part_benc = part2; za.part_below = part3; }
   const int nparts = fold ? fold_row_blocks(D.B) : rbs;
+  PartsSwitch psw;
+  if (fold && mode == CLT_DECODE_AUTO) psw = PartsSwitch{flags, kcap, rbs};
   DWdecArgs wa{z, d_yhat, W_dec, G, norms, gW_dec, fdec, skip, kcap};
   if (h->n2_eligible && fdec.m) wa.n2_part = reinterpret_cast<float*>(h->ws + h->plan.n2_part);
   DWencArgs ea{x, dpre, gW_enc, W_enc, fenc};
@@ -647,15 +651,15 @@ static int backward_impl(clt_handle* h, hipStream_t s, const void* x, const floa
   if (mode != CLT_DECODE_GATHER) {
     if (h->bf16) RUN(h, s, K_DZ, launch_dz_bf16(s, D, za)); else RUN(h, s, K_DZ, launch_dz_f32(s, D, za));
   }
-  if (!fold)
+  if (!fold || mode == CLT_DECODE_AUTO)
     RUN(h, s, K_STE, launch_ste_reduce(s, h->bf16, D, dpre, act_class, h->int8 ? x_scale : nullptr, norms, lam1_over_b,
-                                       part, part2, part3));
+                                       part, part2, part3, fold ? flags : nullptr, kcap));
   if (h->cfg.activation == CLT_ACT_TOPK)     // no threshold: the window partials are all zero, and so is the gradient
-    RUN(h, s, K_COLRED, launch_col_reduce(s, part, nparts, D.L * D.F, 1.0f, nullptr, 0.f, gtheta));
+    RUN(h, s, K_COLRED, launch_col_reduce(s, part, nparts, D.L * D.F, 1.0f, nullptr, 0.f, gtheta, false, psw));
   else
     RUN(h, s, K_COLRED, launch_dtheta_final(s, part, part3, nparts, D.L * D.F, theta, h->cfg.log_threshold != 0, norms,
-                                            1.0f / h->cfg.ste_bandwidth, lam1_over_b, gtheta));
-  RUN(h, s, K_COLRED, launch_col_reduce(s, part2, nparts, D.L * D.F, 1.0f, nullptr, 0.f, gb_enc));
+                                            1.0f / h->cfg.ste_bandwidth, lam1_over_b, gtheta, psw));
+  RUN(h, s, K_COLRED, launch_col_reduce(s, part2, nparts, D.L * D.F, 1.0f, nullptr, 0.f, gb_enc, false, psw));
   if (h->bf16) RUN(h, s, K_DWENC, launch_dwenc_bf16(s, D, ea, h->int8));
   else RUN(h, s, K_DWENC, launch_dwenc_f32(s, D, ea));
   if (mode != CLT_DECODE_GATHER) {

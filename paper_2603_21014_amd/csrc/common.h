@@ -234,20 +234,27 @@ hipError_t launch_loss_sparsity(hipStream_t s, bool bf16, Dims D, const void* z,
 hipError_t launch_loss_final(hipStream_t s, const double* part_rec, int n_rec, const double* part_sp, int n_sp,
                              const double* part_dead_or_null, float inv_B, float lambda0, float lambda1,
                              float* loss_dev);
+// Automatic mode: the column partials of the backward come in nparts row blocks when the dense dz epilogue wrote
+// them and in nparts_lists when the list-driven backward ran (launch_ste_reduce); which, the device-side switch says.
+struct PartsSwitch { const int32_t* flags = nullptr; int kcap = 0; int nparts_lists = 0; };
 // out[c] = alpha * sum_r part[r][c] (fixed order), optionally times -(theta[c]/eps)
 hipError_t launch_col_reduce(hipStream_t s, const float* part, int nparts, int ncols, float alpha,
-                             const float* theta_or_null, float inv_eps, float* out, bool accumulate = false);
+                             const float* theta_or_null, float inv_eps, float* out, bool accumulate = false,
+                             PartsSwitch sw = PartsSwitch{});
 // dtheta[c] = -(theta/eps) sum_r part_win[r][c] + lam1_over_b * norms[c] * sum_r part_below[r][c], times theta
 // when the parameter is log(theta)
 hipError_t launch_dtheta_final(hipStream_t s, const float* part_win, const float* part_below, int nparts, int ncols,
                                const float* theta_param, bool log_threshold, const float* norms, float inv_eps,
-                               float lam1_over_b, float* out);
+                               float lam1_over_b, float* out, PartsSwitch sw = PartsSwitch{});
 // reads dz kept where active|window: column partials for dtheta (window) and db_enc (active);
 // zeroes entries that are in the window but not active so the buffer becomes dpre
 // (entries that are below the threshold get the dead-feature gradient -lam1_over_b * n; part_below counts them)
+// (only_if_lists: automatic mode with the dz epilogue doing this work for the dense backward -- the kernel then runs
+//  only when the list-driven backward was selected)
 hipError_t launch_ste_reduce(hipStream_t s, bool bf16, Dims D, void* dpre, const uint8_t* cls,
                              const float* row_scale_or_null, const float* norms, float lam1_over_b,
-                             float* part_theta, float* part_benc, float* part_below);
+                             float* part_theta, float* part_benc, float* part_below,
+                             const int32_t* only_if_lists = nullptr, int kcap = 0);
 
 // p, g in T (or p in T with fp32 master); m, v float
 hipError_t launch_adam_matrix(hipStream_t s, bool bf16, size_t n, void* p, const void* g, float* m, float* v,

@@ -219,9 +219,10 @@ __global__ __launch_bounds__(256) void loss_final_kernel(const double* part_rec,
 
 __global__ __launch_bounds__(256) void col_reduce_kernel(const float* __restrict__ part, int nparts, int ncols,
                                                          float alpha, const float* __restrict__ theta, float inv_eps,
-                                                         float* __restrict__ out, bool accumulate) {
+                                                         float* __restrict__ out, bool accumulate, PartsSwitch sw) {
   const int c = blockIdx.x * 256 + threadIdx.x;
   if (c >= ncols) return;
+  if (sw.flags && lists_backward_selected(sw.flags, sw.kcap)) nparts = sw.nparts_lists;
   float s = 0.f;
   for (int r = 0; r < nparts; ++r) s += part[(size_t)r * ncols + c];
   s *= alpha;
@@ -236,9 +237,10 @@ __global__ __launch_bounds__(256) void dtheta_final_kernel(const float* __restri
                                                            int ncols, const float* __restrict__ theta_param,
                                                            bool log_threshold, const float* __restrict__ norms,
                                                            float inv_eps, float lam1_over_b,
-                                                           float* __restrict__ out) {
+                                                           float* __restrict__ out, PartsSwitch sw) {
   const int c = blockIdx.x * 256 + threadIdx.x;
   if (c >= ncols) return;
+  if (sw.flags && lists_backward_selected(sw.flags, sw.kcap)) nparts = sw.nparts_lists;
   float w = 0.f, nb = 0.f;
   for (int r = 0; r < nparts; ++r) w += part_win[(size_t)r * ncols + c];
   if (lam1_over_b != 0.f)
@@ -264,7 +266,9 @@ __global__ __launch_bounds__(256) void ste_reduce_kernel(Dims D, T* __restrict__
                                                          const float* __restrict__ norms, float lam1_over_b,
                                                          float* __restrict__ part_theta,
                                                          float* __restrict__ part_benc,
-                                                         float* __restrict__ part_below) {
+                                                         float* __restrict__ part_below,
+                                                         const int32_t* __restrict__ only_if_lists, int kcap) {
+  if (only_if_lists && !lists_backward_selected(only_if_lists, kcap)) return;
   const int rb = blockIdx.x, l = blockIdx.y;
   const int r0 = rb * LOSS_ROWS_PER_BLOCK, r1 = min(D.B, r0 + LOSS_ROWS_PER_BLOCK);
   const bool dead = lam1_over_b != 0.f;
@@ -642,30 +646,31 @@ hipError_t launch_loss_final(hipStream_t s, const double* part_rec, int n_rec, c
 }
 
 hipError_t launch_col_reduce(hipStream_t s, const float* part, int nparts, int ncols, float alpha,
-                             const float* theta_or_null, float inv_eps, float* out, bool accumulate) {
+                             const float* theta_or_null, float inv_eps, float* out, bool accumulate, PartsSwitch sw) {
   hipLaunchKernelGGL(col_reduce_kernel, dim3((ncols + 255) / 256), dim3(256), 0, s, part, nparts, ncols, alpha,
-                     theta_or_null, inv_eps, out, accumulate);
+                     theta_or_null, inv_eps, out, accumulate, sw);
   return hipGetLastError();
 }
 
 hipError_t launch_dtheta_final(hipStream_t s, const float* part_win, const float* part_below, int nparts, int ncols,
                                const float* theta_param, bool log_threshold, const float* norms, float inv_eps,
-                               float lam1_over_b, float* out) {
+                               float lam1_over_b, float* out, PartsSwitch sw) {
   hipLaunchKernelGGL(dtheta_final_kernel, dim3((ncols + 255) / 256), dim3(256), 0, s, part_win, part_below, nparts,
-                     ncols, theta_param, log_threshold, norms, inv_eps, lam1_over_b, out);
+                     ncols, theta_param, log_threshold, norms, inv_eps, lam1_over_b, out, sw);
   return hipGetLastError();
 }
 
 hipError_t launch_ste_reduce(hipStream_t s, bool bf16, Dims D, void* dpre, const uint8_t* cls,
                              const float* row_scale_or_null, const float* norms, float lam1_over_b,
-                             float* part_theta, float* part_benc, float* part_below) {
+                             float* part_theta, float* part_benc, float* part_below,
+                             const int32_t* only_if_lists, int kcap) {
   const dim3 grid(row_blocks(D.B), D.L);
   if (bf16)
     hipLaunchKernelGGL((ste_reduce_kernel<bf16_t>), grid, dim3(256), 0, s, D, (bf16_t*)dpre, cls, row_scale_or_null,
-                       norms, lam1_over_b, part_theta, part_benc, part_below);
+                       norms, lam1_over_b, part_theta, part_benc, part_below, only_if_lists, kcap);
   else
     hipLaunchKernelGGL((ste_reduce_kernel<float>), grid, dim3(256), 0, s, D, (float*)dpre, cls, row_scale_or_null,
-                       norms, lam1_over_b, part_theta, part_benc, part_below);
+                       norms, lam1_over_b, part_theta, part_benc, part_below, only_if_lists, kcap);
   return hipGetLastError();
 }
 
