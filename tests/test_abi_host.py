@@ -55,6 +55,24 @@ def test_workspace_size_and_shape_validation(K):
         K.clt_workspace_bytes(cfg)
 
 
+def test_automatic_mode_thresholds_and_workspace(K):
+    """The two density thresholds of the automatic mode are checked, and the workspace grows with the larger of them
+    (capped lists, their transpose and the room for the partial sums of the fused dz)."""
+    base = dict(L=4, d=64, F=256, B=128, decode_mode=K.DECODE_AUTO)
+    for bad in (dict(gather_density_threshold=-0.1), dict(gather_density_threshold=1.5),
+                dict(list_backward_density_threshold=-0.1), dict(list_backward_density_threshold=2.0)):
+        with pytest.raises(K.CLTError) as e:
+            K.clt_workspace_bytes(K.make_config(**base, **bad))
+        assert e.value.code == -1, bad
+    dense = K.clt_workspace_bytes(K.make_config(4, 64, 256, 128))
+    small = K.clt_workspace_bytes(K.make_config(**base, gather_density_threshold=0.004))
+    same = K.clt_workspace_bytes(K.make_config(**base, gather_density_threshold=0.004,
+                                               list_backward_density_threshold=0.004))
+    large = K.clt_workspace_bytes(K.make_config(**base, gather_density_threshold=0.004,
+                                                list_backward_density_threshold=0.1))
+    assert dense < small == same < large      # 0 for the second threshold means: the same as the first
+
+
 def test_init_rejects_bad_workspace_before_any_device_call(K):
     cfg = K.make_config(4, 64, 256, 128)
     h = ctypes.c_void_p()
