@@ -339,6 +339,9 @@ __global__ __launch_bounds__(256) void adam_kernel(size_t n4, T* __restrict__ p,
 // of the floats finds the k-th largest value in four 8-bit passes (LDS histograms); a last pass
 // writes z and the class bytes.  Entries equal to the k-th value are taken in index order until
 // k entries are selected; that ordered count runs only for rows that have such ties to break.
+#ifndef TOPK_HIST_COPIES
+#define TOPK_HIST_COPIES 4
+#endif
 __device__ __forceinline__ uint32_t order_key(float x) {
   const uint32_t u = __float_as_uint(x);
   return (u & 0x80000000u) ? ~u : (u | 0x80000000u);     // larger float <=> larger key (NaN sorts by its bits)
@@ -350,7 +353,9 @@ template <typename T, int NV4>
 __global__ __launch_bounds__(256) void topk_select_kernel(Dims D, const float* __restrict__ pre32, int k,
                                                           T* __restrict__ z, uint8_t* __restrict__ cls,
                                                           int32_t* __restrict__ l0) {
-  __shared__ int hist[256];
+  // (TOPK_HIST_COPIES histograms, one per lane residue: pre-activations share a few exponents, so most keys of the
+  //  first pass fall into a handful of bins and atomics on one LDS word serialise)
+  __shared__ int hist[TOPK_HIST_COPIES][256];
   __shared__ int sh_bin, sh_rem, scan[256], wtot[4];
   const int tid = threadIdx.x;
   const size_t row = blockIdx.x;
@@ -384,7 +389,8 @@ __global__ __launch_bounds__(256) void topk_select_kernel(Dims D, const float* _
   int remaining = k;            // entries still to take among those whose key matches the prefix so far
   if (k > 0 && k < D.F) {
     for (int shift = 24; shift >= 0; shift -= 8) {
-      hist[tid] = 0;
+#pragma unroll
+      for (int c = 0; c < TOPK_HIST_COPIES; ++c) hist[c][tid] = 0;
       __syncthreads();
       const uint32_t himask = shift == 24 ? 0u : (0xffffffffu << (shift + 8));
 #pragma unroll NV4 > 0 ? NV4 : 1
@@ -394,14 +400,17 @@ __global__ __launch_bounds__(256) void topk_select_kernel(Dims D, const float* _
         if (tid + 256 * j < F4) {
 #pragma unroll
           for (int i = 0; i < 4; ++i)
-            if ((key[i] & himask) == prefix) atomicAdd(&hist[(key[i] >> shift) & 255u], 1);
+            if ((key[i] & himask) == prefix) atomicAdd(&hist[tid & (TOPK_HIST_COPIES - 1)][(key[i] >> shift) & 255u], 1);
         }
       }
       __syncthreads();
       // the bin that holds the `remaining`-th largest entry: suffix sums over the 256 bins (lane = bin),
       // wave scans plus the totals of the higher waves
       {
-        const int h = hist[tid], lane = tid & 63, wv = tid >> 6;
+        int h = 0;
+#pragma unroll
+        for (int c = 0; c < TOPK_HIST_COPIES; ++c) h += hist[c][tid];
+        const int lane = tid & 63, wv = tid >> 6;
         int sfx = h;
 #pragma unroll
         for (int off = 1; off < 64; off <<= 1) {
