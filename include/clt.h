@@ -254,9 +254,12 @@ int clt_backward_adam_step(clt_handle* handle, void* stream,
  * which = 0 decoder norms [L,F] float; 1 d y_hat [L,B,d] T; 2 d pre [L,B,F] T
  * (with int8 inputs every row holds d pre times that row's x_scale: the form
  * the encoder-weight gradient contracts with the integer codes);
- * 3 sparsity column sums G [L,F] float; 4 decode switch, 4 int32: {gather allowed by
- * the measured density, longest active list, path taken by the last forward
- * (1 dense, 2 gather), unused}; written by clt_forward in the gather and auto decode modes only.
+ * 3 sparsity column sums G [L,F] float; 4 decode switch, 4 int32: {what the measured
+ * density allows: bit 0 the gather decode, bit 1 the list-driven backward through the
+ * decoder (the backward clears it again when the lists turn out too long for it);
+ * longest (layer, token) list, active and in-window features; path taken by the last
+ * forward (1 dense, 2 gather); longest per-layer total of the feature lists, written by
+ * the backward when it runs on the lists}; gather and auto decode modes only.
  * Valid after the call that writes them. */
 int clt_workspace_view(const clt_handle* handle, int which, void** ptr, size_t* bytes);
 
