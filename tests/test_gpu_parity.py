@@ -613,6 +613,19 @@ def test_dz_taken_inside_the_row_kernel_of_dw_dec(monkeypatch, dtype, d, rho):
     show(f"fused dz {dtype} d={d} rho={rho}", compare_step(w, a, o, TOL[dtype]))
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_dz_inside_the_row_kernel_long_feature_lists(dtype):
+    """Features listed by more than 64 tokens (about 90 of 300 here, up to about 120): the row kernel hands the
+    dz sums of a feature over 64 tokens at a time, the last group ragged.  Lists stay under 128 entries per token
+    (about 80), so dz is taken inside the row kernel."""
+    w = S.scaled(S.WORKLOADS["tiny"], dtype=dtype, L=3, d=256, F=264, B=300, seed=89)
+    theta = sparse_theta(w, 0.3)
+    g, o = run_both(w, theta=theta, decode_mode=GATHER, fused=True)
+    per_feature = (g.active | g.window).sum(axis=1)
+    assert per_feature.max() > 100 and int(g.decode_switch[3]) <= 128 * w.B
+    show(f"fused dz, long feature lists {dtype}", compare_step(w, g, o, TOL[dtype]))
+
+
 def test_sparse_backward_many_layers():
     """More than 8 targets per source: the row kernel walks them in two chunks."""
     w = S.scaled(S.WORKLOADS["tiny"], dtype="bf16", L=11, d=64, F=256, B=48, seed=82)
