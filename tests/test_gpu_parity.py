@@ -217,15 +217,20 @@ def test_decoder_norms_reused_from_the_fused_update():
     assert rel_l2(gg.norms, pg.norms) < 1e-6
     # automatic mode: whichever of the two kernels the device-side switch picked leaves the sums, and the norms
     # kernel reads the same switch to know their layout
-    for thr, picked in ((1.0, "sparse_dW_dec"), (0.0, "dW_dec_gemm")):
-        ga = GpuRun(w, params, x, y, fused=True, pre_steps=2, reuse_decoder_norms=True, decode_mode=AUTO,
-                    gather_density_threshold=thr)
+    # (sparse thresholds, so that the lists fit the room the automatic mode gives them; third case: dense decode,
+    #  list-driven backward -- the row kernel's layout although the forward was dense)
+    th = sparse_theta(w, 0.02)
+    for thr, thr_bwd, switch in ((0.1, 0.0, 3), (0.001, 0.0, 0), (0.001, 0.1, 2)):
+        ga = GpuRun(w, params, x, y, theta=th, fused=True, pre_steps=2, reuse_decoder_norms=True, decode_mode=AUTO,
+                    gather_density_threshold=thr, list_backward_density_threshold=thr_bwd)
         assert ga.kernel_launches.get("decoder_norms_from_update") == 1 and "decoder_norms" not in ga.kernel_launches
-        assert ga.kernel_launches.get(picked, 0) >= 1
-        pa = GpuRun(w, params, x, y, fused=True, pre_steps=2, decode_mode=AUTO, gather_density_threshold=thr)
-        assert rel_l2(ga.norms, pa.norms) < 1e-6, (thr, rel_l2(ga.norms, pa.norms))
+        assert ga.decode_switch[0] == switch and (ga.decode_switch[3] > 0) == (switch >= 2)
+        pa = GpuRun(w, params, x, y, theta=th, fused=True, pre_steps=2, decode_mode=AUTO, gather_density_threshold=thr,
+                    list_backward_density_threshold=thr_bwd)
+        assert rel_l2(ga.norms, pa.norms) < 1e-6, (thr, thr_bwd, rel_l2(ga.norms, pa.norms))
         oa = OracleRun(w, ga.start_params, x, y, t=3, m=ga.start_m, v=ga.start_v, gpu_active=ga.active, gpu_window=ga.window)
-        show(f"norms from the update, automatic mode, threshold {thr}", compare_step(w, ga, oa, TOL["bf16"], check_adam=False))
+        show(f"norms from the update, automatic mode, thresholds {thr} / {thr_bwd}",
+             compare_step(w, ga, oa, TOL["bf16"], check_adam=False))
     # an unfused update in between changes W_dec without new row sums: the next forward must read W_dec again
     from paper_2603_21014_amd import binding as K
     step, (gp, gm, gv, _) = g.step, g.device_state
@@ -645,11 +650,12 @@ def test_sparse_backward_with_dead_feature_term():
     show("sparse bwd + dead term", compare_step(w, g, o, TOL["bf16"]))
 
 
-def test_sparse_backward_int8_inputs():
-    w = S.scaled(S.WORKLOADS["llama1b_int8"], L=2, d=264, F=520, B=300, k_active=8)
+@pytest.mark.parametrize("d", [264, 256])      # whole-row kernel + separate gather dz / column slices with dz inside
+def test_sparse_backward_int8_inputs(d):
+    w = S.scaled(S.WORKLOADS["llama1b_int8"], L=2, d=d, F=520, B=300, k_active=8)
     theta = sparse_theta(w, 0.03)
     g, o = run_both(w, theta=theta, decode_mode=GATHER, fused=True)
-    show("sparse bwd int8", compare_step(w, g, o, TOL["bf16"]))
+    show(f"sparse bwd int8 d={d}", compare_step(w, g, o, TOL["bf16"]))
 
 
 def test_auto_switch_follows_measured_density():
