@@ -181,8 +181,9 @@ Plan make_plan(const clt_config* c) {
   const size_t gathers = p.kcap ? 1 : 0;
   p.fl_off = o;     o += align_up(gathers * L * F * 4);
   p.fl_cnt = o;     o += align_up(gathers * L * F * 4);
-  p.fl_tok = o;     o += align_up(L * B * (size_t)p.kcap * 4);
-  p.fl_val = o;     o += align_up(L * B * (size_t)p.kcap * 4);
+  // (+16: the row kernel of dW_dec reads list entries four at a time, up to three past a list's end)
+  p.fl_tok = o;     o += align_up(L * B * (size_t)p.kcap * 4 + (gathers ? 16 : 0));
+  p.fl_val = o;     o += align_up(L * B * (size_t)p.kcap * 4 + (gathers ? 16 : 0));
   p.fl_seg = o;     o += align_up(gathers * FL_SEGS * L * F * 4);
   // partial dot products of the fused dz: (pair, column slice, entry), entries per layer capped (longer lists take
   // the separate gather kernel)
