@@ -710,11 +710,12 @@ def test_auto_dense_decode_with_list_driven_backward(dtype, fused):
     assert lo.decode_switch[0] == 3 and lo.decode_switch[2] == 2
 
 
-def test_auto_hands_long_lists_back_to_the_dense_backward():
+@pytest.mark.parametrize("dtype,lambda1", [("bf16", 0.0), ("f32", 0.0), ("bf16", 3.0)])
+def test_auto_hands_long_lists_back_to_the_dense_backward(dtype, lambda1):
     """Automatic mode, mean density below the backward threshold, but one layer's lists are longer than the room for
     the partial sums of the fused dz (sized from that threshold): the scan of the feature lists clears the backward
     bit and dz / dW_dec run as dense GEMMs -- the separate gather dz kernel would be slower than those."""
-    w = S.scaled(S.WORKLOADS["tiny"], dtype="bf16", L=3, d=128, F=1024, B=256, seed=88)
+    w = S.scaled(S.WORKLOADS["tiny"], dtype=dtype, L=3, d=128, F=1024, B=256, seed=88, lambda1=lambda1)
     params = S.make_params(w)
     x, y = S.make_inputs(w)
     theta = sparse_theta(w, 0.01)
@@ -731,7 +732,9 @@ def test_auto_hands_long_lists_back_to_the_dense_backward():
     for k in O.PARAM_NAMES:
         assert rel_l2(g.new_params[k], dn.new_params[k]) < 1e-3, k
     o = OracleRun(w, params, x, y, gpu_active=g.active, gpu_window=g.window, theta=theta)
-    show("auto: long lists -> dense backward", compare_step(w, g, o, TOL["bf16"]))
+    if lambda1:
+        dead_term_matters(w, o, TOL[dtype])
+    show(f"auto: long lists -> dense backward {dtype} lambda1={lambda1}", compare_step(w, g, o, TOL[dtype]))
 
 
 def test_restored_state_reproduces_the_step_bitwise():
