@@ -341,6 +341,10 @@ def main():
     ap.add_argument("--list-backward-density-threshold", type=float, default=0.016,
                     help="auto mode: the backward through the decoder runs on the active-feature lists at or below "
                          "this mean active fraction (measured break-even: about 0.02)")
+    ap.add_argument("--density", type=float, default=None,
+                    help="force the activation density of a JumpReLU workload: per-layer thresholds at which this "
+                         "fraction of the pre-activations is active (the recipe of --density-sweep), learning rate 0 so "
+                         "that it stays put; the step does all of its work as usual")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-timing", action="store_true",
                     help="skip the per-kernel HIP-event brackets (roofline entry becomes null)")
@@ -378,7 +382,6 @@ def main():
     params32 = S.make_params(w, device=dev)
     params = {k: (v.to(T) if k in ("W_enc", "W_dec") else v) for k, v in params32.items()}
     master = {k: params32[k] for k in ("W_enc", "W_dec")} if w.master_weights else None
-    del params32
     x, y = S.make_inputs(w, device=dev)
     xs = ys = None
     if w.int8_inputs:
@@ -386,6 +389,14 @@ def main():
         y, ys = S.quantize_rows_int8(y)
     else:
         x, y = x.to(T), y.to(T)
+    lr = w.lr
+    if args.density is not None:
+        assert not w.topk and not w.log_threshold, "--density sets the thresholds of a JumpReLU workload"
+        xf = x.float() * xs[:, :, None] if w.int8_inputs else x.float()
+        params["theta"] = theta_for_density(xf, params32["W_enc"], params32["b_enc"], args.density)
+        lr = 0.0
+        del xf
+    del params32
     m = {k: torch.zeros(v.shape, dtype=torch.float32, device=dev) for k, v in params.items()}
     v_ = {k: torch.zeros(v.shape, dtype=torch.float32, device=dev) for k, v in params.items()}
     step = K.CLTStep(w.L, w.d, w.F, w.B, dtype="bf16", int8_inputs=w.int8_inputs, master_weights=w.master_weights,
@@ -400,7 +411,7 @@ def main():
         f"{torch.cuda.memory_allocated() / 2**30:.1f} GiB allocated")
 
     def one_step(t):
-        step.train_step(x, y, params, m, v_, t, w.lr, w.lambda0, master, xs, ys, lambda1=w.lambda1)
+        step.train_step(x, y, params, m, v_, t, lr, w.lambda0, master, xs, ys, lambda1=w.lambda1)
 
     t = 0
     for _ in range(args.warmup):
@@ -508,7 +519,8 @@ def main():
         "config": {"workload": w.name, "L": w.L, "d_model": w.d, "features_per_layer": w.F, "tokens": w.B,
                    "decoder_blocks": w.P, "int8_inputs": w.int8_inputs, "master_weights": w.master_weights,
                    "activation": f"topk{w.topk}" if w.topk else "jumprelu", "decode_mode": args.decode_mode,
-                   "fused_adam": True, "reuse_decoder_norms": True},
+                   "fused_adam": True, "reuse_decoder_norms": True, "forced_density": args.density,
+                   "active_per_token_layer": l0},
         "median_ms_per_step_profiled_pass": median_ms,
         "step_dense_tflops": flop / (ms_per_step * 1e-3) / 1e12,
         "step_frac_of_bf16_mfma_peak": flop / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,

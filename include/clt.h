@@ -104,8 +104,9 @@ typedef struct clt_config {
                              Whenever the sums are not there, clt_forward reads W_dec as with 0.      */
   float gather_density_threshold; /* AUTO: the forward decode gathers when the mean active
                              fraction of the batch is <= this and no (layer, token) row has
-                             more than about 8x the larger of the two thresholds in listed
-                             features (else the step decodes densely).  On an MI355X the
+                             more than about 32x the larger of the two thresholds in listed
+                             features (else the step decodes densely; the backward is not
+                             bound by that row limit where d is a multiple of 32).  On an MI355X the
                              gather decode breaks even with the dense one near 0.003-0.0045
                              (24-38 active of 8192 features; binding default 0.004).     */
   float list_backward_density_threshold; /* AUTO: the backward through the decoder (dz, dW_dec
@@ -256,7 +257,8 @@ int clt_backward_adam_step(clt_handle* handle, void* stream,
  * the encoder-weight gradient contracts with the integer codes);
  * 3 sparsity column sums G [L,F] float; 4 decode switch, 4 int32: {what the measured
  * density allows: bit 0 the gather decode, bit 1 the list-driven backward through the
- * decoder (the backward clears it again when the lists turn out too long for it);
+ * decoder (the backward clears it again when the lists turn out too long for it),
+ * bit 2 that this backward works without the per-(layer, token) lists;
  * longest (layer, token) list, active and in-window features; path taken by the last
  * forward (1 dense, 2 gather); longest per-layer total of the feature lists, written by
  * the backward when it runs on the lists}; gather and auto decode modes only.

@@ -168,7 +168,7 @@ Plan make_plan(const clt_config* c) {
   p.kcap = 0;
   if (c->decode_mode == CLT_DECODE_GATHER) p.kcap = c->F;
   if (c->decode_mode == CLT_DECODE_AUTO) {
-    size_t k = (size_t)(8.0 * std::max(c->gather_density_threshold, backward_threshold(c)) * F) + 64;
+    size_t k = (size_t)(32.0 * std::max(c->gather_density_threshold, backward_threshold(c)) * F) + 64;
     k = (k + 7) / 8 * 8;
     p.kcap = (int)(k < F ? k : F);
   }
@@ -530,8 +530,12 @@ int clt_forward(clt_handle* h, void* stream, const void* x, const float* x_scale
   }
   if (topk) RUN(h, s, K_TOPK, launch_topk_select(s, h->bf16, h->D, pre32, h->cfg.topk_k, z, act_class, l0));
   if (mode != CLT_DECODE_DENSE) {   // Sec. 3.2: density monitor, then the gather path where it pays
+    // (automatic mode with dz taken inside the row kernel of dW_dec: the backward works from the per-feature lists
+    //  alone, so a row longer than the per-token lists hold does not stop it)
     RUN(h, s, K_DECIDE, launch_decode_decide(s, h->D, l0, h->cfg.gather_density_threshold, backward_threshold(&h->cfg),
-                                             mode == CLT_DECODE_GATHER, flags));
+                                             mode == CLT_DECODE_GATHER,
+                                             mode == CLT_DECODE_AUTO && sparse_dwdec_takes_dz(h->D) && h->plan.ecap > 0,
+                                             flags));
     RUN(h, s, K_COMPACT, launch_compact_active(s, h->bf16, h->D, z, act_class, gl, flags));
     RUN(h, s, K_GATHER, launch_gather_decode(s, h->bf16, h->D, gl, W_dec, b_dec, y_hat, flags));
   }

@@ -274,7 +274,7 @@ hipError_t launch_diag_fill(hipStream_t s, void* buf, size_t bytes, int random_d
 // ---- active-feature gather paths (kernels_gather.hip) -------------------------
 // Device-side switch, 4 ints in the workspace:
 //   [0] bit 0: the measured density allows the gather decode (or it is forced); bit 1: it allows the list-driven
-//       backward through the decoder (or it is forced)
+//       backward through the decoder (or it is forced); bit 2: that backward does not need the row lists
 //   [1] longest per-(layer, token) list seen by the compaction (active + window-only entries)
 //   [2] path taken by the last forward: 1 dense, 2 gather
 //   [3] longest per-layer total of the feature lists (see fused_dz_selected)
@@ -285,8 +285,11 @@ __host__ __device__ inline bool gather_selected(const int32_t* flags, int kcap) 
 }
 // The backward through the decoder (dz, dW_dec) has a switch of its own, flags[0] bit 1: its list-driven kernels pay
 // up to a higher density than the gather decode does.
+// Bit 2 says that this backward does not touch the per-(layer, token) lists (dz is taken inside the row kernel of
+// dW_dec, which works from the per-feature lists; their capacity is checked when they are built): a token with more
+// listed features than a row holds then only sends the forward decode back to the dense kernel.
 __host__ __device__ inline bool lists_backward_selected(const int32_t* flags, int kcap) {
-  return (flags[0] & 2) != 0 && flags[1] <= kcap;
+  return (flags[0] & 2) != 0 && ((flags[0] & 4) != 0 || flags[1] <= kcap);
 }
 // Per (layer, token) row of kcap slots: the active features in ascending order from the front
 // (counts[row] of them, val = z), the inactive features inside the threshold window from the
@@ -296,7 +299,8 @@ struct GatherLists { int32_t* idx; float* val; int32_t* counts; int32_t* counts_
 __host__ __device__ inline int list_stride(int kcap) { return kcap + 32; }
 // flags[0] = (sum l0 <= threshold * L*B*F) or forced; flags[1] = 0
 hipError_t launch_decode_decide(hipStream_t s, Dims D, const int32_t* l0, float density_threshold,
-                                float backward_density_threshold, int forced, int32_t* flags);
+                                float backward_density_threshold, int forced, bool backward_without_row_lists,
+                                int32_t* flags);
 hipError_t launch_compact_active(hipStream_t s, bool bf16, Dims D, const void* z, const uint8_t* cls, GatherLists g,
                                  int32_t* flags);
 // y_hat[lp, b, :] = b_dec[lp] + sum_{l<=lp} sum_{active f} z[l,b,f] W_dec[p(l,lp)][f, :]; records the path in flags[2]

@@ -32,12 +32,13 @@ namespace clt {
 namespace {
 
 __global__ void decode_decide_kernel(Dims D, const int32_t* __restrict__ l0, float thr, float thr_bwd, int forced,
-                                     int32_t* __restrict__ flags) {
+                                     int rows_free, int32_t* __restrict__ flags) {
   if (threadIdx.x != 0 || blockIdx.x != 0) return;
   long long tot = 0;
   for (int l = 0; l < D.L; ++l) tot += l0[l];
   const double dens = (double)tot / ((double)D.L * D.B * D.F);
-  flags[0] = ((forced || dens <= (double)thr) ? 1 : 0) | ((forced || dens <= (double)thr_bwd) ? 2 : 0);
+  flags[0] = ((forced || dens <= (double)thr) ? 1 : 0) | ((forced || dens <= (double)thr_bwd) ? 2 : 0) |
+             (rows_free ? 4 : 0);
   flags[1] = 0;
   flags[2] = 1;
   flags[3] = 0;
@@ -61,7 +62,8 @@ template <typename T>
 __global__ __launch_bounds__(256) void compact_active_kernel(Dims D, const T* __restrict__ z,
                                                              const uint8_t* __restrict__ cls, GatherLists g,
                                                              int32_t* __restrict__ flags) {
-  if (flags[0] == 0) return;
+  // the row lists serve the gather decode, and the backward unless it works from the per-feature lists alone
+  if (!((flags[0] & 1) || ((flags[0] & 2) && !(flags[0] & 4)))) return;
   const int lane = threadIdx.x & 63;
   const long row = (long)blockIdx.x * 4 + (threadIdx.x >> 6);   // l * B + b
   if (row >= (long)D.L * D.B) return;
@@ -995,9 +997,10 @@ __global__ __launch_bounds__(256) void dz_from_partials_kernel(Dims D, FeatureLi
 }  // namespace
 
 hipError_t launch_decode_decide(hipStream_t s, Dims D, const int32_t* l0, float density_threshold,
-                                float backward_density_threshold, int forced, int32_t* flags) {
+                                float backward_density_threshold, int forced, bool backward_without_row_lists,
+                                int32_t* flags) {
   hipLaunchKernelGGL(decode_decide_kernel, dim3(1), dim3(64), 0, s, D, l0, density_threshold,
-                     backward_density_threshold, forced, flags);
+                     backward_density_threshold, forced, backward_without_row_lists ? 1 : 0, flags);
   return hipGetLastError();
 }
 
