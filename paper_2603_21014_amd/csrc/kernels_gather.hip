@@ -174,7 +174,7 @@ template <> struct Raw8<float> {
   }
 };
 
-// One workgroup per (token, target): 8 columns per lane (d is walked in passes of 2048 columns), the
+// One wavefront per (token, target, run of 512 columns): 8 columns per lane, the
 // sources l <= l' and their lists in order.  Feature ids and values are wave-uniform, so a decoder row
 // is a scalar base plus the lane's fixed column offset; eight rows (16 bytes per lane each) are in
 // flight for long lists, four for short ones.
@@ -193,35 +193,40 @@ __device__ __forceinline__ void gather_rows(float (&acc)[8], const T* __restrict
   for (int u = 0; u < U; ++u) Raw8<T>::axpy(acc, v[u], r[u]);
 }
 
+#ifndef GD_THREADS
+#define GD_THREADS 64
+#endif
 template <typename T>
-__global__ __launch_bounds__(256) void gather_decode_kernel(Dims D, GatherLists g, const T* __restrict__ W_dec,
-                                                            const float* __restrict__ b_dec,
-                                                            float* __restrict__ y_hat, int32_t* __restrict__ flags) {
+__global__ __launch_bounds__(GD_THREADS) void gather_decode_kernel(Dims D, GatherLists g, const T* __restrict__ W_dec,
+                                                                  const float* __restrict__ b_dec,
+                                                                  float* __restrict__ y_hat, int32_t* __restrict__ flags) {
   if (!gather_selected(flags, g.kcap)) return;
-  const int lp = D.L - 1 - (int)(blockIdx.x / D.B);   // heaviest targets first
-  const int b = (int)(blockIdx.x % D.B);
+  // one workgroup per (token, target, run of GD_THREADS * 8 columns), the column runs of a row next to each other
+  const int ncs = (D.d + GD_THREADS * 8 - 1) / (GD_THREADS * 8);
+  const int cs = (int)(blockIdx.x % ncs);
+  const size_t bt = blockIdx.x / ncs;
+  const int lp = D.L - 1 - (int)(bt / D.B);   // heaviest targets first
+  const int b = (int)(bt % D.B);
   if (blockIdx.x == 0 && threadIdx.x == 0) flags[2] = 2;
-  for (int c0 = 0; c0 < D.d; c0 += 2048) {
-    const int col = c0 + threadIdx.x * 8;
-    if (col >= D.d) continue;
-    float acc[8];
+  const int col = (cs * GD_THREADS + threadIdx.x) * 8;
+  if (col >= D.d) return;
+  float acc[8];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) acc[i] = b_dec[(size_t)lp * D.d + col + i];
-    for (int l = 0; l <= lp; ++l) {
-      const size_t row = (size_t)l * D.B + b;
-      const int cnt = g.counts[row];
-      const int32_t* ii = g.idx + row * g.stride;
-      const float* vv = g.val + row * g.stride;
-      const T* Wp = W_dec + (size_t)packed_index(l, lp, D.L) * D.F * D.d;
-      int j = 0;
-      for (; j + 8 <= cnt; j += 8) gather_rows<T, 8>(acc, Wp, D.d, (uint32_t)col, ii, vv, j);
-      if (j + 4 <= cnt) { gather_rows<T, 4>(acc, Wp, D.d, (uint32_t)col, ii, vv, j); j += 4; }
-      for (; j < cnt; ++j) gather_rows<T, 1>(acc, Wp, D.d, (uint32_t)col, ii, vv, j);
-    }
-    float* o = y_hat + ((size_t)lp * D.B + b) * D.d + col;
-    *reinterpret_cast<float4*>(o) = make_float4(acc[0], acc[1], acc[2], acc[3]);
-    *reinterpret_cast<float4*>(o + 4) = make_float4(acc[4], acc[5], acc[6], acc[7]);
+  for (int i = 0; i < 8; ++i) acc[i] = b_dec[(size_t)lp * D.d + col + i];
+  for (int l = 0; l <= lp; ++l) {
+    const size_t row = (size_t)l * D.B + b;
+    const int cnt = g.counts[row];
+    const int32_t* ii = g.idx + row * g.stride;
+    const float* vv = g.val + row * g.stride;
+    const T* Wp = W_dec + (size_t)packed_index(l, lp, D.L) * D.F * D.d;
+    int j = 0;
+    for (; j + 8 <= cnt; j += 8) gather_rows<T, 8>(acc, Wp, D.d, (uint32_t)col, ii, vv, j);
+    if (j + 4 <= cnt) { gather_rows<T, 4>(acc, Wp, D.d, (uint32_t)col, ii, vv, j); j += 4; }
+    for (; j < cnt; ++j) gather_rows<T, 1>(acc, Wp, D.d, (uint32_t)col, ii, vv, j);
   }
+  float* o = y_hat + ((size_t)lp * D.B + b) * D.d + col;
+  *reinterpret_cast<float4*>(o) = make_float4(acc[0], acc[1], acc[2], acc[3]);
+  *reinterpret_cast<float4*>(o + 4) = make_float4(acc[4], acc[5], acc[6], acc[7]);
 }
 
 // ---------------------------------------------------------------------------
@@ -1017,13 +1022,14 @@ hipError_t launch_compact_active(hipStream_t s, bool bf16, Dims D, const void* z
 
 hipError_t launch_gather_decode(hipStream_t s, bool bf16, Dims D, GatherLists g, const void* W_dec,
                                 const float* b_dec, float* y_hat, int32_t* flags) {
-  const dim3 grid((unsigned)((size_t)D.L * D.B));
+  const size_t ncs = ((size_t)D.d + GD_THREADS * 8 - 1) / (GD_THREADS * 8);
+  const dim3 grid((unsigned)((size_t)D.L * D.B * ncs));
   if (bf16)
-    hipLaunchKernelGGL((gather_decode_kernel<bf16_t>), grid, dim3(256), 0, s, D, g, (const bf16_t*)W_dec, b_dec, y_hat,
-                       flags);
+    hipLaunchKernelGGL((gather_decode_kernel<bf16_t>), grid, dim3(GD_THREADS), 0, s, D, g, (const bf16_t*)W_dec, b_dec,
+                       y_hat, flags);
   else
-    hipLaunchKernelGGL((gather_decode_kernel<float>), grid, dim3(256), 0, s, D, g, (const float*)W_dec, b_dec, y_hat,
-                       flags);
+    hipLaunchKernelGGL((gather_decode_kernel<float>), grid, dim3(GD_THREADS), 0, s, D, g, (const float*)W_dec, b_dec,
+                       y_hat, flags);
   return hipGetLastError();
 }
 
