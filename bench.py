@@ -335,9 +335,9 @@ def main():
                     help="skip the vendor-library GEMM reference measured after the timed region")
     ap.add_argument("--decode-mode", default="dense", choices=["dense", "gather", "auto"],
                     help="dense GEMMs (default), the list-driven kernels of the sparse regime, or the device-side switch")
-    ap.add_argument("--gather-density-threshold", type=float, default=0.004,
+    ap.add_argument("--gather-density-threshold", type=float, default=0.0045,
                     help="auto mode: the forward decode gathers at or below this mean active fraction (measured "
-                         "break-even on an MI355X: 0.003-0.0045)")
+                         "break-even on an MI355X: 0.0047-0.0052)")
     ap.add_argument("--list-backward-density-threshold", type=float, default=0.016,
                     help="auto mode: the backward through the decoder runs on the active-feature lists at or below "
                          "this mean active fraction (measured break-even: about 0.02)")

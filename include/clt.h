@@ -107,8 +107,8 @@ typedef struct clt_config {
                              more than about 32x the larger of the two thresholds in listed
                              features (else the step decodes densely; the backward is not
                              bound by that row limit where d is a multiple of 32).  On an MI355X the
-                             gather decode breaks even with the dense one near 0.003-0.0045
-                             (24-38 active of 8192 features; binding default 0.004).     */
+                             gather decode breaks even with the dense one near 0.005
+                             (38-44 active of 8192 features; binding default 0.0045).    */
   float list_backward_density_threshold; /* AUTO: the backward through the decoder (dz, dW_dec
                              and its Adam update) runs on the active-feature lists when the
                              mean active fraction is <= this (same row limit); 0 = the same

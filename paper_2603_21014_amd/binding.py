@@ -107,7 +107,7 @@ def _ptr(t, shape, dtype, name, optional=False):
 
 
 def make_config(L, d, F, B, dtype=DTYPE_BF16, input_format=INPUT_NATIVE, master_weights=False,
-                decode_mode=DECODE_DENSE, gather_density_threshold=0.004, C_=4.0, ste_bandwidth=0.05,
+                decode_mode=DECODE_DENSE, gather_density_threshold=0.0045, C_=4.0, ste_bandwidth=0.05,
                 beta1=0.9, beta2=0.999, adam_eps=1e-8, log_threshold=False, topk=None, reuse_decoder_norms=False,
                 list_backward_density_threshold=0.0):
     """topk: None for JumpReLU, else k of the TopK activation.  reuse_decoder_norms: see include/clt.h (the caller
@@ -324,7 +324,7 @@ class CLTStep:
 
     def __init__(self, L, d, F, B, dtype="bf16", int8_inputs=False, master_weights=False, C_=4.0,
                  ste_bandwidth=0.05, beta1=0.9, beta2=0.999, adam_eps=1e-8, device="cuda:0", keep_pre=True,
-                 decode_mode=DECODE_DENSE, gather_density_threshold=0.004, matrix_grads=True, log_threshold=False,
+                 decode_mode=DECODE_DENSE, gather_density_threshold=0.0045, matrix_grads=True, log_threshold=False,
                  topk=None, workspace=None, reuse_decoder_norms=False, list_backward_density_threshold=0.016):
         """workspace: a uint8 device tensor of at least clt_workspace_bytes(config) bytes that the caller
         owns (256-byte aligned); by default one is allocated here."""

@@ -147,14 +147,6 @@ template <> struct Raw8<bf16_t> {
     }
     return acc;
   }
-  static __device__ __forceinline__ void axpy(float (&acc)[8], float v, const type& a) {
-    const uint32_t x[4] = {a.x, a.y, a.z, a.w};
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      acc[2 * i] = fmaf(v, __uint_as_float(x[i] << 16), acc[2 * i]);
-      acc[2 * i + 1] = fmaf(v, __uint_as_float(x[i] & 0xffff0000u), acc[2 * i + 1]);
-    }
-  }
 };
 template <> struct Raw8<float> {
   struct type { float4 lo, hi; };
@@ -167,52 +159,52 @@ template <> struct Raw8<float> {
     acc = fmaf(a.hi.z, b.hi.z, acc); acc = fmaf(a.hi.w, b.hi.w, acc);
     return acc;
   }
-  static __device__ __forceinline__ void axpy(float (&acc)[8], float v, const type& a) {
-    acc[0] = fmaf(v, a.lo.x, acc[0]); acc[1] = fmaf(v, a.lo.y, acc[1]); acc[2] = fmaf(v, a.lo.z, acc[2]);
-    acc[3] = fmaf(v, a.lo.w, acc[3]); acc[4] = fmaf(v, a.hi.x, acc[4]); acc[5] = fmaf(v, a.hi.y, acc[5]);
-    acc[6] = fmaf(v, a.hi.z, acc[6]); acc[7] = fmaf(v, a.hi.w, acc[7]);
-  }
 };
 
-// One wavefront per (token, target, run of 512 columns): 8 columns per lane, the
-// sources l <= l' and their lists in order.  Feature ids and values are wave-uniform, so a decoder row
-// is a scalar base plus the lane's fixed column offset; eight rows (16 bytes per lane each) are in
-// flight for long lists, four for short ones.
+// One wavefront per (token, target, run of 256 columns): 4 columns per lane, the sources l <= l' and their lists in
+// order.  Feature ids and values are wave-uniform, so a decoder row is a scalar base plus the lane's fixed column
+// offset; eight rows are in flight for long lists, four for short ones.  The runs of a row are neighbours in the
+// grid, and workgroups go round-robin to the XCDs: with d = 2048 an XCD always gets the same eighth of the columns,
+// so the eight L2s hold disjoint parts of the decoder instead of eight copies of what is hot, and the long rows of
+// a heavy-tailed batch are spread over eight CUs instead of going through one.
 template <typename T, int U>
-__device__ __forceinline__ void gather_rows(float (&acc)[8], const T* __restrict__ Wp, int ld, uint32_t col,
+__device__ __forceinline__ void gather_rows(float (&acc)[4], const T* __restrict__ Wp, int ld, uint32_t col,
                                             const int32_t* __restrict__ ii, const float* __restrict__ vv, int j) {
-  typename Raw8<T>::type r[U];
+  typename Elem<T>::Raw4 r[U];
   float v[U];
 #pragma unroll
   for (int u = 0; u < U; ++u) {
     const int f = __builtin_amdgcn_readfirstlane(ii[j + u]);
     v[u] = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(vv[j + u])));
-    r[u] = Raw8<T>::load(lane_ptr(Wp + (size_t)f * ld, col));
+    r[u] = Elem<T>::load_raw4(lane_ptr(Wp + (size_t)f * ld, col));
   }
 #pragma unroll
-  for (int u = 0; u < U; ++u) Raw8<T>::axpy(acc, v[u], r[u]);
+  for (int u = 0; u < U; ++u) {
+    const float4 q = Elem<T>::widen4(r[u]);
+    acc[0] = fmaf(v[u], q.x, acc[0]);
+    acc[1] = fmaf(v[u], q.y, acc[1]);
+    acc[2] = fmaf(v[u], q.z, acc[2]);
+    acc[3] = fmaf(v[u], q.w, acc[3]);
+  }
 }
 
-#ifndef GD_THREADS
-#define GD_THREADS 64
-#endif
+constexpr int GD_COLS = 256;      // columns per wavefront
 template <typename T>
-__global__ __launch_bounds__(GD_THREADS) void gather_decode_kernel(Dims D, GatherLists g, const T* __restrict__ W_dec,
-                                                                  const float* __restrict__ b_dec,
-                                                                  float* __restrict__ y_hat, int32_t* __restrict__ flags) {
+__global__ __launch_bounds__(64) void gather_decode_kernel(Dims D, GatherLists g, const T* __restrict__ W_dec,
+                                                          const float* __restrict__ b_dec,
+                                                          float* __restrict__ y_hat, int32_t* __restrict__ flags) {
   if (!gather_selected(flags, g.kcap)) return;
-  // one workgroup per (token, target, run of GD_THREADS * 8 columns), the column runs of a row next to each other
-  const int ncs = (D.d + GD_THREADS * 8 - 1) / (GD_THREADS * 8);
+  const int ncs = (D.d + GD_COLS - 1) / GD_COLS;
   const int cs = (int)(blockIdx.x % ncs);
   const size_t bt = blockIdx.x / ncs;
   const int lp = D.L - 1 - (int)(bt / D.B);   // heaviest targets first
   const int b = (int)(bt % D.B);
   if (blockIdx.x == 0 && threadIdx.x == 0) flags[2] = 2;
-  const int col = (cs * GD_THREADS + threadIdx.x) * 8;
+  const int col = cs * GD_COLS + threadIdx.x * 4;
   if (col >= D.d) return;
-  float acc[8];
+  float acc[4];
 #pragma unroll
-  for (int i = 0; i < 8; ++i) acc[i] = b_dec[(size_t)lp * D.d + col + i];
+  for (int i = 0; i < 4; ++i) acc[i] = b_dec[(size_t)lp * D.d + col + i];
   for (int l = 0; l <= lp; ++l) {
     const size_t row = (size_t)l * D.B + b;
     const int cnt = g.counts[row];
@@ -224,9 +216,7 @@ __global__ __launch_bounds__(GD_THREADS) void gather_decode_kernel(Dims D, Gathe
     if (j + 4 <= cnt) { gather_rows<T, 4>(acc, Wp, D.d, (uint32_t)col, ii, vv, j); j += 4; }
     for (; j < cnt; ++j) gather_rows<T, 1>(acc, Wp, D.d, (uint32_t)col, ii, vv, j);
   }
-  float* o = y_hat + ((size_t)lp * D.B + b) * D.d + col;
-  *reinterpret_cast<float4*>(o) = make_float4(acc[0], acc[1], acc[2], acc[3]);
-  *reinterpret_cast<float4*>(o + 4) = make_float4(acc[4], acc[5], acc[6], acc[7]);
+  *reinterpret_cast<float4*>(y_hat + ((size_t)lp * D.B + b) * D.d + col) = make_float4(acc[0], acc[1], acc[2], acc[3]);
 }
 
 // ---------------------------------------------------------------------------
@@ -1022,14 +1012,14 @@ hipError_t launch_compact_active(hipStream_t s, bool bf16, Dims D, const void* z
 
 hipError_t launch_gather_decode(hipStream_t s, bool bf16, Dims D, GatherLists g, const void* W_dec,
                                 const float* b_dec, float* y_hat, int32_t* flags) {
-  const size_t ncs = ((size_t)D.d + GD_THREADS * 8 - 1) / (GD_THREADS * 8);
+  const size_t ncs = ((size_t)D.d + GD_COLS - 1) / GD_COLS;
   const dim3 grid((unsigned)((size_t)D.L * D.B * ncs));
   if (bf16)
-    hipLaunchKernelGGL((gather_decode_kernel<bf16_t>), grid, dim3(GD_THREADS), 0, s, D, g, (const bf16_t*)W_dec, b_dec,
-                       y_hat, flags);
+    hipLaunchKernelGGL((gather_decode_kernel<bf16_t>), grid, dim3(64), 0, s, D, g, (const bf16_t*)W_dec, b_dec, y_hat,
+                       flags);
   else
-    hipLaunchKernelGGL((gather_decode_kernel<float>), grid, dim3(GD_THREADS), 0, s, D, g, (const float*)W_dec, b_dec,
-                       y_hat, flags);
+    hipLaunchKernelGGL((gather_decode_kernel<float>), grid, dim3(64), 0, s, D, g, (const float*)W_dec, b_dec, y_hat,
+                       flags);
   return hipGetLastError();
 }
 
