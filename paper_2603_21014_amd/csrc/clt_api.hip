@@ -648,8 +648,11 @@ static int backward_impl(clt_handle* h, hipStream_t s, const void* x, const floa
     // updates W_dec in place when Adam is fused: nothing after it reads the decoder.)
     RUN(h, s, K_SP_FILL, launch_sparse_dpre_fill(s, h->bf16, D, act_class, norms, lam1_over_b, dpre, flags, kcap));
     RUN(h, s, K_FLISTS, launch_feature_lists(s, h->bf16, D, act_class, z, fl, flags, mode == CLT_DECODE_AUTO));
-    RUN(h, s, K_GATHER_DZ, launch_gather_dz(s, h->bf16, D, gl, d_yhat, W_dec, norms, lam_c_over_b, h->cfg.C, dpre,
-                                            flags, &fl));
+    // (automatic mode with dz taken inside the row kernel: lists too long for that send the backward to the dense
+    //  kernels, so the separate gather kernel would only ever stand down)
+    if (!(mode == CLT_DECODE_AUTO && fl.dz_part))
+      RUN(h, s, K_GATHER_DZ, launch_gather_dz(s, h->bf16, D, gl, d_yhat, W_dec, norms, lam_c_over_b, h->cfg.C, dpre,
+                                              flags, &fl));
     RUN(h, s, K_SP_DWDEC, launch_sparse_dwdec(s, h->bf16, D, fl, wa, flags));
     RUN(h, s, K_GATHER_DZ, launch_dz_from_partials(s, h->bf16, D, fl, norms, lam_c_over_b, h->cfg.C, dpre, flags));
   }
