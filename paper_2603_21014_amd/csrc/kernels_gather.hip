@@ -449,6 +449,7 @@ __global__ __launch_bounds__(256) void fl_count_kernel(Dims D, const uint8_t* __
   const int seg_len = (D.B + FL_SEGS - 1) / FL_SEGS;
   const int b0 = sgm * seg_len, b1 = min(D.B, b0 + seg_len);
   int c[4] = {0, 0, 0, 0};
+#pragma unroll 8
   for (int b = b0; b < b1; ++b) {
     const uint32_t a4 = *reinterpret_cast<const uint32_t*>(cls + ((size_t)l * D.B + b) * D.F + f);
     const uint32_t listed = (a4 | (a4 >> 1)) & 0x01010101u;      // active, or inside the threshold window
@@ -519,20 +520,26 @@ __global__ __launch_bounds__(256) void fl_fill_kernel(Dims D, const uint8_t* __r
   const int32_t* so = fl.seg + (size_t)sgm * D.L * D.F + (size_t)q * 4;
   int pos[4] = {so[0], so[1], so[2], so[3]};
   const size_t base = (size_t)l * D.B * fl.kcap;        // layer l's region of the lists
-  for (int b = b0; b < b1; ++b) {
-    const size_t o = ((size_t)l * D.B + b) * D.F + f;
-    const uint32_t c4 = *reinterpret_cast<const uint32_t*>(cls + o);
-    const uint32_t a4 = (c4 | (c4 >> 1)) & 0x01010101u;      // as counted: active or in the window (z = 0 there)
-    if (!a4) continue;
-    const float4 z4 = Elem<T>::load4(z + o);
-    const float zz[4] = {z4.x, z4.y, z4.z, z4.w};
+  for (int bb = b0; bb < b1; bb += 8) {      // the class words of eight tokens in flight, then the (few) listed entries
+    uint32_t c8[8];
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
-      if ((a4 >> (8 * i)) & 1u) {
-        fl.tok[base + pos[i]] = b;
-        fl.val[base + pos[i]] = zz[i];
-        ++pos[i];
-      }
+    for (int u = 0; u < 8; ++u)
+      c8[u] = bb + u < b1 ? *reinterpret_cast<const uint32_t*>(cls + ((size_t)l * D.B + bb + u) * D.F + f) : 0u;
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const uint32_t a4 = (c8[u] | (c8[u] >> 1)) & 0x01010101u;      // as counted: active or in the window (z = 0 there)
+      if (!a4) continue;
+      const int b = bb + u;
+      const float4 z4 = Elem<T>::load4(z + ((size_t)l * D.B + b) * D.F + f);
+      const float zz[4] = {z4.x, z4.y, z4.z, z4.w};
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        if ((a4 >> (8 * i)) & 1u) {
+          fl.tok[base + pos[i]] = b;
+          fl.val[base + pos[i]] = zz[i];
+          ++pos[i];
+        }
+    }
   }
 }
 
